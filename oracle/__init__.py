@@ -1,0 +1,176 @@
+"""CPU oracle for the E0M4 quantised matmul -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes loader around ``e0m4_oracle.c`` (plain C, fp64 except where the
+arithmetic decides an integer code).  Nothing here is part of the product:
+only ``tests/``, the smoke check and the benchmark's CPU-baseline leg may
+import this package, and this package imports nothing from the GPU library.
+
+All arrays are numpy; fp16 data travels as ``uint16`` bit patterns or as
+``float16`` arrays (viewed, never converted).  Layouts are the canonical ones:
+``codes [N,K]`` one code (0..15) per byte, ``scales``/``bias`` ``[N, K/G]``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "e0m4_oracle.c")
+_LIB = os.path.join(_HERE, "libe0m4_oracle.so")
+_CFLAGS = ["-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC"]
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no GPU toolchain involved)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", *_CFLAGS, _SRC, "-o", tmp, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    L = ctypes.CDLL(_LIB)
+    u16p = ctypes.POINTER(ctypes.c_uint16)
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    i64 = ctypes.c_int64
+    L.oracle_half_bits_to_double.restype = ctypes.c_double
+    L.oracle_half_bits_to_double.argtypes = [ctypes.c_uint16]
+    L.oracle_double_to_half_bits.restype = ctypes.c_uint16
+    L.oracle_double_to_half_bits.argtypes = [ctypes.c_double]
+    L.oracle_e0m4_w1_bits.restype = ctypes.c_uint16
+    L.oracle_e0m4_w1_bits.argtypes = [ctypes.c_int]
+    L.oracle_e0m4_decode_one.restype = ctypes.c_uint16
+    L.oracle_e0m4_decode_one.argtypes = [ctypes.c_int, ctypes.c_uint16, ctypes.c_uint16]
+    L.oracle_e0m4_encode_one.restype = ctypes.c_int
+    L.oracle_e0m4_encode_one.argtypes = [ctypes.c_uint16, ctypes.c_uint16, ctypes.c_uint16]
+    L.oracle_e0m4_forward_bits.restype = ctypes.c_uint16
+    L.oracle_e0m4_forward_bits.argtypes = [ctypes.c_uint16, ctypes.c_uint16, ctypes.c_uint16]
+    L.oracle_e0m4_fit_group.restype = None
+    L.oracle_e0m4_fit_group.argtypes = [u16p, i64, u16p, u16p]
+    L.oracle_e0m4_quantize.restype = None
+    L.oracle_e0m4_quantize.argtypes = [u16p, i64, i64, i64, u8p, u16p, u16p]
+    L.oracle_e0m4_encode.restype = None
+    L.oracle_e0m4_encode.argtypes = [u16p, i64, i64, i64, u16p, u16p, u8p]
+    L.oracle_e0m4_dequant.restype = None
+    L.oracle_e0m4_dequant.argtypes = [u8p, u16p, u16p, i64, i64, i64, u16p]
+    L.oracle_e0m4_matmul.restype = None
+    L.oracle_e0m4_matmul.argtypes = [u16p, i64, u16p, i64, i64, u16p, f64p]
+    L.oracle_num_threads.restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def _u16(a: np.ndarray) -> np.ndarray:
+    """View an fp16 / uint16 array as contiguous uint16 bit patterns."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def _p(a: np.ndarray, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+# ---- scalar helpers (used by the pin tests) ---------------------------------
+
+def half_bits_to_double(h: int) -> float:
+    return _load().oracle_half_bits_to_double(int(h))
+
+
+def double_to_half_bits(d: float) -> int:
+    return _load().oracle_double_to_half_bits(float(d))
+
+
+def w1_bits(c: int) -> int:
+    """Bit pattern of the binade value of code c (paper: dequantization formula)."""
+    return _load().oracle_e0m4_w1_bits(int(c))
+
+
+def decode_one(c: int, scale_bits: int, bias_bits: int) -> int:
+    return _load().oracle_e0m4_decode_one(int(c), int(scale_bits), int(bias_bits))
+
+
+def encode_one(w0_bits: int, scale_bits: int, bias_bits: int) -> int:
+    return _load().oracle_e0m4_encode_one(int(w0_bits), int(scale_bits), int(bias_bits))
+
+
+def forward_bits(w0_bits: int, scale_bits: int, bias_bits: int) -> int:
+    return _load().oracle_e0m4_forward_bits(int(w0_bits), int(scale_bits), int(bias_bits))
+
+
+def fit_group(w0: np.ndarray):
+    """(scale_bits, bias_bits) of one group (paper: quantization paragraph)."""
+    w0 = _u16(w0).ravel()
+    s = ctypes.c_uint16()
+    b = ctypes.c_uint16()
+    _load().oracle_e0m4_fit_group(_p(w0, ctypes.c_uint16), w0.size, ctypes.byref(s), ctypes.byref(b))
+    return s.value, b.value
+
+
+# ---- array entry points -----------------------------------------------------
+
+def quantize(W: np.ndarray, group: int):
+    """W [N,K] fp16 -> (codes u8 [N,K], scales f16 [N,K/G], bias f16 [N,K/G])."""
+    Wb = _u16(W)
+    N, K = Wb.shape
+    assert K % group == 0
+    codes = np.empty((N, K), np.uint8)
+    scales = np.empty((N, K // group), np.uint16)
+    bias = np.empty((N, K // group), np.uint16)
+    _load().oracle_e0m4_quantize(_p(Wb, ctypes.c_uint16), N, K, group, _p(codes, ctypes.c_uint8),
+                                 _p(scales, ctypes.c_uint16), _p(bias, ctypes.c_uint16))
+    return codes, scales.view(np.float16), bias.view(np.float16)
+
+
+def encode(W: np.ndarray, scales: np.ndarray, bias: np.ndarray, group: int) -> np.ndarray:
+    """Codes of W under caller-supplied per-group parameters."""
+    Wb, sb, bb = _u16(W), _u16(scales), _u16(bias)
+    N, K = Wb.shape
+    assert sb.shape == (N, K // group) and bb.shape == sb.shape
+    codes = np.empty((N, K), np.uint8)
+    _load().oracle_e0m4_encode(_p(Wb, ctypes.c_uint16), N, K, group, _p(sb, ctypes.c_uint16),
+                               _p(bb, ctypes.c_uint16), _p(codes, ctypes.c_uint8))
+    return codes
+
+
+def dequant(codes: np.ndarray, scales: np.ndarray, bias: np.ndarray, group: int) -> np.ndarray:
+    """codes u8 [N,K] + params [N,K/G] -> dequantised weights f16 [N,K]."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    sb, bb = _u16(scales), _u16(bias)
+    N, K = codes.shape
+    assert sb.shape == (N, K // group) and bb.shape == sb.shape
+    out = np.empty((N, K), np.uint16)
+    _load().oracle_e0m4_dequant(_p(codes, ctypes.c_uint8), _p(sb, ctypes.c_uint16), _p(bb, ctypes.c_uint16),
+                                N, K, group, _p(out, ctypes.c_uint16))
+    return out.view(np.float16)
+
+
+def matmul(X: np.ndarray, What: np.ndarray, want_absdot: bool = True):
+    """Y[m,n] = fp16(sum_k X[m,k] What[n,k]) in fp64; also sum_k |x w| per output."""
+    Xb, Wb = _u16(X), _u16(What)
+    M, K = Xb.shape
+    N, K2 = Wb.shape
+    assert K == K2
+    Y = np.empty((M, N), np.uint16)
+    absdot = np.empty((M, N), np.float64) if want_absdot else None
+    _load().oracle_e0m4_matmul(_p(Xb, ctypes.c_uint16), M, _p(Wb, ctypes.c_uint16), N, K,
+                               _p(Y, ctypes.c_uint16),
+                               _p(absdot, ctypes.c_double) if want_absdot else None)
+    return (Y.view(np.float16), absdot) if want_absdot else Y.view(np.float16)
+
+
+def num_threads() -> int:
+    return _load().oracle_num_threads()
