@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the E0M4 matmul hot path on one MI355X.
+
+A "step" is one pass over the decode workload: the 28 x 4 weight matrices of a
+ChatGLM2-6B-shaped layer stack (E0M4, group 128, distinct random weights per
+layer so that nothing is served from cache), each multiplied with an M=1 fp16
+activation vector through e0m4_matmul.  All inputs are resident in HBM before
+the timed region.  The 112 launches of a step are captured once into a HIP
+graph and replayed, so the Python binding is not in the timed path.
+
+Reported on one JSON line: decode HBM GB/s (value), its roofline object, the
+prefill GEMM figures for the same four shapes at M=1024, and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 matrix peak
+GROUP = 128
+PREFILL_M = 1024
+
+
+def algorithmic_bytes(M, N, K, G):
+    """codes + fp16 scale and bias per group + X once + Y once."""
+    return N * K // 2 + 4 * N * (K // G) + 2 * M * K + 2 * M * N
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug)")
+    ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a single-GPU kernel library; run with --gpus 1 "
+              "(no multi-GPU figure exists for it)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2403_20041_amd as e0m4
+    import synth_inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    e0m4.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    shapes = synth_inputs.CHATGLM2_6B
+    n_layers = args.layers or synth_inputs.CHATGLM2_LAYERS
+
+    # ---------------- set-up: quantise every layer's weights on the GPU (offline step, untimed)
+    layers = []
+    t_q = time.perf_counter()
+    q_bytes = 0
+    for layer in range(n_layers):
+        mats = []
+        for p, (name, N, K) in enumerate(shapes):
+            W = synth_inputs.weights_device(N, K, synth_inputs.layer_seed(layer, p), dev)
+            packed = e0m4.e0m4_quantize(W, GROUP)
+            q_bytes += W.numel() * 2
+            del W
+            mats.append((name, N, K) + packed)
+        layers.append(mats)
+    torch.cuda.synchronize()
+    t_q = time.perf_counter() - t_q
+
+    xs = {K: synth_inputs.activations_device(1, K, 99 + K, dev) for _, _, K in shapes}
+    ys = {(N, K): torch.empty((1, N), dtype=torch.float16, device=dev) for _, N, K in shapes}
+    ws_bytes = max(e0m4.e0m4_workspace_bytes(1, N, K, GROUP) for _, N, K in shapes)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    step_bytes = sum(algorithmic_bytes(1, N, K, GROUP) for _, N, K in shapes) * n_layers
+    launches = len(shapes) * n_layers
+
+    stream = torch.cuda.Stream(device=dev)
+
+    def decode_step():
+        for mats in layers:
+            for name, N, K, codes, scales, bias in mats:
+                e0m4.e0m4_matmul(xs[K], codes, scales, bias, N, K, GROUP, out=ys[(N, K)], workspace=ws, stream=stream)
+
+    graph = None
+    with torch.cuda.stream(stream):
+        decode_step()                       # eager once: loads code objects
+        stream.synchronize()
+        if not args.no_graph:
+            try:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    decode_step()
+                graph = g
+            except Exception as exc:        # noqa: BLE001
+                print("graph capture failed (%s); timing eager launches" % exc, file=sys.stderr)
+                graph = None
+
+    def run_step():
+        if graph is not None:
+            graph.replay()
+        else:
+            decode_step()
+
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            run_step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        for _ in range(args.steps):
+            run_step()
+        ev1.record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall * 1e3 / args.steps
+    decode_gbps = step_bytes / (wall / args.steps) / 1e9
+    # dominant kernel: the M=1 GEMV.  One launch moves step_bytes / launches algorithmic bytes on average;
+    # its average duration is the event time of the timed region divided by the number of launches.
+    avg_launch_us = ev_ms * 1e3 / (args.steps * launches)
+    achieved = (step_bytes / launches) / (avg_launch_us * 1e-6) / 1e9
+
+    # per-shape decode rate, rotating over the layers' distinct weights (cold in cache)
+    per_shape = {}
+    with torch.cuda.stream(stream):
+        for p, (name, N, K) in enumerate(shapes):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = max(1, 200 // n_layers)
+            for timed in (False, True):
+                if timed:
+                    e0.record(stream)
+                for _ in range(reps):
+                    for mats in layers:
+                        _, _, _, codes, scales, bias = mats[p]
+                        e0m4.e0m4_matmul(xs[K], codes, scales, bias, N, K, GROUP, out=ys[(N, K)], workspace=ws,
+                                         stream=stream)
+                if timed:
+                    e1.record(stream)
+                stream.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / (reps * n_layers)
+            b = algorithmic_bytes(1, N, K, GROUP)
+            per_shape[name] = {"N": N, "K": K, "us": round(us, 3), "GBps": round(b / us / 1e3, 1),
+                               "frac_hbm": round(b / us / 1e3 / HBM_PEAK_GBPS, 4)}
+
+    out = {
+        "metric": "E0M4 matmul: decode GEMV HBM GB/s (% peak); prefill GEMM TFLOP/s (% MFMA)",
+        "value": round(decode_gbps, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16 x e0m4 codes, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "ChatGLM2-6B-shaped decode layer stack, M=1, %d layers x 4 projections, E0M4 group %d"
+                               % (n_layers, GROUP),
+                   "launches_per_step": launches, "algorithmic_bytes_per_step": step_bytes,
+                   "launch_mode": "hip_graph" if graph is not None else "eager"},
+        "pct_of_hbm_peak": round(100.0 * decode_gbps / HBM_PEAK_GBPS, 2),
+        "roofline": {"bound": "hbm", "kernel": "gemv_kernel<128,1>", "achieved": round(achieved, 2),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "avg_launch_us": round(avg_launch_us, 3), "traffic": None},
+        "decode_per_shape": per_shape,
+        "quantize": {"GBps_fp16_in": round(q_bytes / t_q / 1e9, 1), "note": "offline step incl. weight generation"},
+    }
+
+    # ---------------- prefill: same four shapes at M=1024 (activation outliers, per-row weight scale)
+    if not args.no_prefill:
+        pre = {}
+        tot_flops, tot_ms = 0.0, 0.0
+        best = None
+        with torch.cuda.stream(stream):
+            for p, (name, N, K) in enumerate(shapes):
+                W = synth_inputs.weights_device(N, K, 5000 + p, dev, row_std_range=(0.5, 2.0))
+                codes, scales, bias = e0m4.e0m4_quantize(W, GROUP, stream=stream)
+                del W
+                X = synth_inputs.activations_device(PREFILL_M, K, 6000 + p, dev, outlier_frac=0.01)
+                Y = torch.empty((PREFILL_M, N), dtype=torch.float16, device=dev)
+                for _ in range(3):
+                    e0m4.e0m4_matmul(X, codes, scales, bias, N, K, GROUP, out=Y, stream=stream)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                reps = 20
+                e0.record(stream)
+                for _ in range(reps):
+                    e0m4.e0m4_matmul(X, codes, scales, bias, N, K, GROUP, out=Y, stream=stream)
+                e1.record(stream)
+                stream.synchronize()
+                ms = e0.elapsed_time(e1) / reps
+                flops = 2.0 * PREFILL_M * N * K
+                tf = flops / ms / 1e9
+                pre[name] = {"N": N, "K": K, "ms": round(ms, 4), "TFLOPs": round(tf, 1),
+                             "frac_mfma": round(tf / MFMA_F16_PEAK_TFLOPS, 4)}
+                tot_flops += flops
+                tot_ms += ms
+                if best is None or flops > best[0]:
+                    best = (flops, ms, name)
+                del codes, scales, bias, X, Y
+        layer_tf = tot_flops / tot_ms / 1e9
+        out["prefill"] = {"workload": "ChatGLM2-6B-shaped prefill layer, M=%d, 4 GEMMs" % PREFILL_M,
+                          "value": round(layer_tf, 1), "unit": "TFLOP/s", "ms_per_layer": round(tot_ms, 4),
+                          "pct_of_mfma_peak": round(100.0 * layer_tf / MFMA_F16_PEAK_TFLOPS, 2), "per_shape": pre}
+        dom_tf = best[0] / best[1] / 1e9
+        out["roofline_prefill"] = {"bound": "mfma", "kernel": "gemm_kernel<128> (%s)" % best[2],
+                                   "achieved": round(dom_tf, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": round(dom_tf / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None}
+
+    # ---------------- CPU oracle on a bounded sample of the decode workload (one layer, repeated)
+    if not args.no_cpu:
+        import numpy as np
+
+        import oracle
+
+        cpu_layers = 1
+        packed = []
+        for p, (name, N, K) in enumerate(shapes):
+            W = synth_inputs.weights(N, K, synth_inputs.layer_seed(0, p))
+            packed.append((N, K) + oracle.quantize(W, GROUP))
+            del W
+        xcpu = {K: synth_inputs.activations(1, K, 99 + K) for _, _, K in shapes}
+        reps, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and reps < 8:
+            t0 = time.perf_counter()
+            for N, K, codes, scales, bias in packed:
+                What = oracle.dequant(codes, scales, bias, GROUP)
+                oracle.matmul(xcpu[K], What, want_absdot=False)
+            t_cpu += time.perf_counter() - t0
+            reps += 1
+        cpu_bytes = sum(algorithmic_bytes(1, N, K, GROUP) for _, N, K in shapes) * cpu_layers * reps
+        out["cpu_baseline"] = {"value": round(cpu_bytes / t_cpu / 1e9, 3), "unit": "GB/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "%d x (dequant + fp64 matmul, M=1) over the 4 projections of one layer "
+                                         "(%.1f s of CPU time)" % (reps, t_cpu)}
+        del np
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

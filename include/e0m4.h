@@ -1,0 +1,123 @@
+/*
+ * libe0m4 -- E0M4 FP4 weight-only quantised matrix multiplication for AMD
+ * MI355X (gfx950), C ABI.
+ *
+ * E0M4 is the 4-bit weight format of the paper "Transformer-Lite" (section
+ * "E0M4 FP4 quantization"): each group of `group` consecutive weights along K
+ * is mapped by a per-group scale and bias into one fp16 binade, [2,4) here,
+ * and the four highest fraction bits of the mapped fp16 value are the code.
+ * Dequantisation is the paper's two bitwise operations,
+ *     w1 = as_half(0x4000 | (code << 6)),
+ * followed by the inverse of the group's map, w = (w1 - bias) * scale.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or synchronises; every call only enqueues kernels
+ *     on `stream` (a hipStream_t passed as void*, NULL = the default stream).
+ *   - fp16 is IEEE binary16.  W is [N,K] row-major (N = output features,
+ *     K = input features, K contiguous), X is [M,K] row-major, Y is [M,N]
+ *     row-major.
+ *   - `scales` and `bias` are [K/group, N] fp16, group-major: the parameters
+ *     of group g of row n are at index g*N + n.  `scale` is the dequantisation
+ *     multiplier, `bias` the binade image of zero (always 2 + z/8, z in 0..15).
+ *   - `codes` is an opaque device layout of e0m4_codes_bytes(N,K) bytes (rows
+ *     padded to a multiple of 64, tiled so that a wavefront reads 1 KiB
+ *     contiguous); use e0m4_unpack_codes / e0m4_dequant to look inside.
+ *   - Shape rules: N >= 0, M >= 0, K >= 0, K % 32 == 0, K % group == 0,
+ *     group in {32, 64, 128}.  Data pointers must be 16-byte aligned.
+ *   - Return value: 0 on success; a negative E0M4_ERR_* code otherwise, in
+ *     which case nothing was enqueued (except E0M4_ERR_HIP, where a launch
+ *     itself failed; see e0m4_last_hip_error).  Nothing throws.
+ *   - Empty problems (M, N or K equal to 0) succeed and enqueue nothing,
+ *     except that a matmul with K == 0 writes zeros to Y.
+ */
+#ifndef E0M4_H
+#define E0M4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define E0M4_ABI_VERSION 1
+
+#define E0M4_OK              0
+#define E0M4_ERR_NULL      (-1)   /* a required pointer is NULL */
+#define E0M4_ERR_SHAPE     (-2)   /* negative size, K not a multiple of 32 or of group */
+#define E0M4_ERR_GROUP     (-3)   /* unsupported group size */
+#define E0M4_ERR_ALIGN     (-4)   /* a data pointer is not 16-byte aligned */
+#define E0M4_ERR_WORKSPACE (-5)   /* workspace smaller than e0m4_workspace_bytes() */
+#define E0M4_ERR_HIP       (-6)   /* the HIP runtime refused a launch */
+
+int         e0m4_abi_version(void);
+const char* e0m4_strerror(int code);
+/* Text of the last HIP error seen by this thread's calls ("" if none). */
+const char* e0m4_last_hip_error(void);
+
+/* Size in bytes of the packed code buffer: ceil(N/64)*64 * K/2.  0 on invalid shape. */
+size_t e0m4_codes_bytes(int64_t N, int64_t K);
+/* Number of fp16 elements in `scales` (and in `bias`): (K/group) * N. */
+size_t e0m4_params_elems(int64_t N, int64_t K, int group);
+/* Scratch bytes e0m4_matmul needs for this shape (split-K partial sums of the
+ * small-M path); may be 0.  Depends only on the arguments. */
+size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
+
+/*
+ * Quantise (paper: quantization paragraph).  Per (row, group): fit scale and
+ * bias from the group's min/max (range extended to contain 0; top of the
+ * binade is 4 - 2^-9; bias keeps its four highest fraction bits), map every
+ * weight as w/scale + bias in fp32, clamp into the binade, round once to fp16
+ * and take code = min(y1 + y2, 15) from the four highest fraction bits y1 and
+ * the next bit y2.  Outputs: codes (packed layout), scales, bias.
+ */
+int e0m4_quantize(const void* W_f16, int64_t N, int64_t K, int group,
+                  void* codes, void* scales_f16, void* bias_f16, void* stream);
+
+/*
+ * Encode only: codes of W under caller-supplied scales/bias (same map, clamp
+ * and rounding as e0m4_quantize, no fitting).  This is the seam for weight
+ * quantisers that choose their own group parameters (the paper notes E0M4
+ * composes with GPTQ/AWQ-style methods).
+ */
+int e0m4_encode(const void* W_f16, int64_t N, int64_t K, int group,
+                const void* scales_f16, const void* bias_f16, void* codes, void* stream);
+
+/*
+ * Dequantise (paper: dequantization formula): W_out[n,k] =
+ * fp16((as_half(0x4000 | code << 6) - bias) * scale), one rounding.
+ * W_out is [N,K] row-major fp16.
+ */
+int e0m4_dequant(const void* codes, const void* scales_f16, const void* bias_f16,
+                 int64_t N, int64_t K, int group, void* W_f16_out, void* stream);
+
+/* Test hook: codes_u8_out[n,k] = code of weight (n,k), one byte each, [N,K] row-major. */
+int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, void* codes_u8_out, void* stream);
+
+/*
+ * Y = X * dequant(codes)^T  (paper: section "Operator and lagging
+ * optimizations", fp16 activation x 4-bit weight matmul; vector-matrix for
+ * decode, matrix-matrix for prefill).  Dequantisation is fused in registers;
+ * accumulation is fp32; Y is rounded once to fp16.
+ *   M <= 8 : HBM-bound split-K GEMV path (may use `workspace`).
+ *   M >= 9 : MFMA GEMM path.
+ * `workspace` may be NULL iff e0m4_workspace_bytes(M,N,K,group) == 0.
+ * Calls that share a workspace must be ordered on one stream.
+ */
+int e0m4_matmul(const void* X_f16, int64_t M,
+                const void* codes, const void* scales_f16, const void* bias_f16,
+                int64_t N, int64_t K, int group,
+                void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Diagnostics for tuning sweeps; not needed for normal use.  Sets an integer
+ * knob by name (e.g. "gemv_waves_per_cu"); unknown names return E0M4_ERR_SHAPE.
+ * A value of 0 restores the built-in heuristic.
+ */
+int e0m4_set_knob(const char* name, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* E0M4_H */

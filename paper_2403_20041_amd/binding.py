@@ -1,0 +1,169 @@
+"""ctypes binding of libe0m4: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see
+``include/e0m4.h``) and does nothing but turn torch tensors into device
+pointers and sizes; all arithmetic happens in the HIP kernels.  torch is used
+for device memory and streams.  There is no CPU fallback: if the shared
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libe0m4.so")
+
+_lib = None
+
+
+class E0M4Error(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().e0m4_strerror(code).decode()
+        if code == -6:
+            msg += ": " + lib().e0m4_last_hip_error().decode()
+        super().__init__("%s failed (%d): %s" % (where, code, msg))
+
+
+def lib() -> ctypes.CDLL:
+    """Load libe0m4.so (built in-tree by ``paper_2403_20041_amd.build``); fails loudly if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "libe0m4.so is not built: run `python -m paper_2403_20041_amd.build` (needs hipcc); "
+            "there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, ci, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    L.e0m4_abi_version.restype = ci
+    L.e0m4_abi_version.argtypes = []
+    L.e0m4_strerror.restype = ctypes.c_char_p
+    L.e0m4_strerror.argtypes = [ci]
+    L.e0m4_last_hip_error.restype = ctypes.c_char_p
+    L.e0m4_last_hip_error.argtypes = []
+    L.e0m4_codes_bytes.restype = sz
+    L.e0m4_codes_bytes.argtypes = [i64, i64]
+    L.e0m4_params_elems.restype = sz
+    L.e0m4_params_elems.argtypes = [i64, i64, ci]
+    L.e0m4_workspace_bytes.restype = sz
+    L.e0m4_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    L.e0m4_quantize.restype = ci
+    L.e0m4_quantize.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
+    L.e0m4_encode.restype = ci
+    L.e0m4_encode.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
+    L.e0m4_dequant.restype = ci
+    L.e0m4_dequant.argtypes = [vp, vp, vp, i64, i64, ci, vp, vp]
+    L.e0m4_unpack_codes.restype = ci
+    L.e0m4_unpack_codes.argtypes = [vp, i64, i64, vp, vp]
+    L.e0m4_matmul.restype = ci
+    L.e0m4_matmul.argtypes = [vp, i64, vp, vp, vp, i64, i64, ci, vp, vp, sz, vp]
+    L.e0m4_set_knob.restype = ci
+    L.e0m4_set_knob.argtypes = [ctypes.c_char_p, ci]
+    if L.e0m4_abi_version() != 1:
+        raise RuntimeError("libe0m4 ABI version mismatch")
+    _lib = L
+    return L
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise E0M4Error(rc, where)
+
+
+def _need(t: torch.Tensor, dtype, shape, name: str):
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError("%s must be a contiguous cuda %s tensor of shape %s, got %s %s on %s"
+                         % (name, dtype, tuple(shape), t.dtype, tuple(t.shape), t.device))
+
+
+def e0m4_codes_bytes(N: int, K: int) -> int:
+    return lib().e0m4_codes_bytes(N, K)
+
+
+def e0m4_params_elems(N: int, K: int, group: int) -> int:
+    return lib().e0m4_params_elems(N, K, group)
+
+
+def e0m4_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    return lib().e0m4_workspace_bytes(M, N, K, group)
+
+
+def e0m4_set_knob(name: str, value: int) -> None:
+    _check(lib().e0m4_set_knob(name.encode(), int(value)), "e0m4_set_knob")
+
+
+def alloc_packed(N: int, K: int, group: int, device):
+    """Uninitialised output buffers for e0m4_quantize: (codes u8, scales f16 [K/G,N], bias f16 [K/G,N])."""
+    codes = torch.empty(max(e0m4_codes_bytes(N, K), 1), dtype=torch.uint8, device=device)
+    scales = torch.empty((K // group, N), dtype=torch.float16, device=device)
+    bias = torch.empty((K // group, N), dtype=torch.float16, device=device)
+    return codes, scales, bias
+
+
+def e0m4_quantize(W: torch.Tensor, group: int, out=None, stream=None):
+    """W [N,K] fp16 -> (codes, scales, bias); see include/e0m4.h."""
+    N, K = W.shape
+    _need(W, torch.float16, (N, K), "W")
+    codes, scales, bias = out if out is not None else alloc_packed(N, K, group, W.device)
+    _check(lib().e0m4_quantize(_ptr(W), N, K, group, _ptr(codes), _ptr(scales), _ptr(bias), _stream(stream)),
+           "e0m4_quantize")
+    return codes, scales, bias
+
+
+def e0m4_encode(W: torch.Tensor, scales: torch.Tensor, bias: torch.Tensor, group: int, codes=None, stream=None):
+    N, K = W.shape
+    _need(W, torch.float16, (N, K), "W")
+    _need(scales, torch.float16, (K // group, N), "scales")
+    _need(bias, torch.float16, (K // group, N), "bias")
+    if codes is None:
+        codes = torch.empty(max(e0m4_codes_bytes(N, K), 1), dtype=torch.uint8, device=W.device)
+    _check(lib().e0m4_encode(_ptr(W), N, K, group, _ptr(scales), _ptr(bias), _ptr(codes), _stream(stream)),
+           "e0m4_encode")
+    return codes
+
+
+def e0m4_dequant(codes, scales, bias, N: int, K: int, group: int, out=None, stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.float16, device=codes.device)
+    _need(out, torch.float16, (N, K), "out")
+    _check(lib().e0m4_dequant(_ptr(codes), _ptr(scales), _ptr(bias), N, K, group, _ptr(out), _stream(stream)),
+           "e0m4_dequant")
+    return out
+
+
+def e0m4_unpack_codes(codes, N: int, K: int, out=None, stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.uint8, device=codes.device)
+    _need(out, torch.uint8, (N, K), "out")
+    _check(lib().e0m4_unpack_codes(_ptr(codes), N, K, _ptr(out), _stream(stream)), "e0m4_unpack_codes")
+    return out
+
+
+def e0m4_matmul(X, codes, scales, bias, N: int, K: int, group: int, out=None, workspace=None, stream=None):
+    """Y [M,N] fp16 = X [M,K] fp16 times the dequantised weights, transposed."""
+    M = X.shape[0]
+    _need(X, torch.float16, (M, K), "X")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    _need(out, torch.float16, (M, N), "out")
+    need = e0m4_workspace_bytes(M, N, K, group)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().e0m4_matmul(_ptr(X), M, _ptr(codes), _ptr(scales), _ptr(bias), N, K, group, _ptr(out),
+                             _ptr(workspace), ws_bytes, _stream(stream)), "e0m4_matmul")
+    return out

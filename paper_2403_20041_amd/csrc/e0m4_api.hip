@@ -1,0 +1,189 @@
+// C ABI of libe0m4: argument validation and dispatch.  Every check happens on
+// the host before anything is enqueued, so an error return means no kernel ran.
+#include <string.h>
+
+#include <atomic>
+
+#include "e0m4_device.h"
+#include "e0m4_host.h"
+
+namespace e0m4 {
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+struct Knob {
+    const char* name;
+    std::atomic<int> value;
+};
+Knob g_knobs[] = {
+    {"gemv_wgs_per_cu", {0}},          // target resident workgroups per compute unit when splitting K
+    {"gemv_min_groups_per_wg", {0}},   // lower bound on the K extent of one workgroup, in groups
+    {"gemv_splits", {0}},              // force the number of K splits
+    {"gemm_variant", {0}},             // select a GEMM kernel variant
+};
+
+__global__ void zero_fill_kernel(half_t* y, int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) y[i] = (half_t)0.f;
+}
+
+bool group_ok(int group) { return group == 32 || group == 64 || group == 128; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape rules shared by all entry points.
+int check_shape(int64_t N, int64_t K, int group)
+{
+    if (!group_ok(group)) return E0M4_ERR_GROUP;
+    if (N < 0 || K < 0 || (K % kCodesPerChunk) != 0 || (K % group) != 0) return E0M4_ERR_SHAPE;
+    if (N > (int64_t)1 << 31 || K > (int64_t)1 << 22) return E0M4_ERR_SHAPE;
+    return E0M4_OK;
+}
+
+}  // namespace
+
+int record_hip_error(hipError_t e)
+{
+    if (e == hipSuccess) return E0M4_OK;
+    strncpy(g_hip_error, hipGetErrorString(e), sizeof(g_hip_error) - 1);
+    g_hip_error[sizeof(g_hip_error) - 1] = 0;
+    return E0M4_ERR_HIP;
+}
+
+int check_launch() { return record_hip_error(hipGetLastError()); }
+
+int knob(const char* name)
+{
+    for (auto& k : g_knobs)
+        if (strcmp(k.name, name) == 0) return k.value.load(std::memory_order_relaxed);
+    return 0;
+}
+
+}  // namespace e0m4
+
+using namespace e0m4;
+
+extern "C" {
+
+int e0m4_abi_version(void) { return E0M4_ABI_VERSION; }
+
+const char* e0m4_strerror(int code)
+{
+    switch (code) {
+        case E0M4_OK: return "ok";
+        case E0M4_ERR_NULL: return "a required pointer is NULL";
+        case E0M4_ERR_SHAPE: return "bad shape: sizes must be >= 0, K a multiple of 32 and of the group size";
+        case E0M4_ERR_GROUP: return "unsupported group size (supported: 32, 64, 128)";
+        case E0M4_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
+        case E0M4_ERR_WORKSPACE: return "workspace is smaller than e0m4_workspace_bytes()";
+        case E0M4_ERR_HIP: return "HIP launch failed (see e0m4_last_hip_error)";
+        default: return "unknown error code";
+    }
+}
+
+const char* e0m4_last_hip_error(void) { return g_hip_error; }
+
+size_t e0m4_codes_bytes(int64_t N, int64_t K)
+{
+    if (N < 0 || K < 0 || (K % kCodesPerChunk) != 0) return 0;
+    return (size_t)padded_rows(N) * (size_t)K / 2;
+}
+
+size_t e0m4_params_elems(int64_t N, int64_t K, int group)
+{
+    if (check_shape(N, K, group) != E0M4_OK) return 0;
+    return (size_t)(K / group) * (size_t)N;
+}
+
+size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
+{
+    if (M < 0 || check_shape(N, K, group) != E0M4_OK) return 0;
+    if (M >= 1 && M <= kGemvMaxM) return gemv_workspace_bytes(M, N, K, group);
+    return 0;
+}
+
+int e0m4_set_knob(const char* name, int value)
+{
+    if (!name) return E0M4_ERR_NULL;
+    for (auto& k : g_knobs)
+        if (strcmp(k.name, name) == 0) {
+            k.value.store(value, std::memory_order_relaxed);
+            return E0M4_OK;
+        }
+    return E0M4_ERR_SHAPE;
+}
+
+int e0m4_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, void* scales, void* bias, void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!W || !codes || !scales || !bias) return E0M4_ERR_NULL;
+    if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
+    return launch_quantize(W, N, K, group, codes, scales, bias, nullptr, nullptr, true, (hipStream_t)stream);
+}
+
+int e0m4_encode(const void* W, int64_t N, int64_t K, int group, const void* scales, const void* bias, void* codes,
+                void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!W || !codes || !scales || !bias) return E0M4_ERR_NULL;
+    if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
+    return launch_quantize(W, N, K, group, codes, nullptr, nullptr, scales, bias, false, (hipStream_t)stream);
+}
+
+int e0m4_dequant(const void* codes, const void* scales, const void* bias, int64_t N, int64_t K, int group, void* W_out,
+                 void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!W_out || !codes || !scales || !bias) return E0M4_ERR_NULL;
+    if (!aligned16(W_out) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
+    return launch_dequant(codes, scales, bias, N, K, group, W_out, (hipStream_t)stream);
+}
+
+int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, void* out, void* stream)
+{
+    int rc = check_shape(N, K, 32);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!codes || !out) return E0M4_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(out)) return E0M4_ERR_ALIGN;
+    return launch_unpack(codes, N, K, out, (hipStream_t)stream);
+}
+
+int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales, const void* bias, int64_t N, int64_t K,
+                int group, void* Y, void* workspace, size_t workspace_bytes, void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (M < 0 || M > (int64_t)1 << 31) return E0M4_ERR_SHAPE;
+    if (M == 0 || N == 0) return E0M4_OK;
+    if (!Y) return E0M4_ERR_NULL;
+    if (!aligned16(Y)) return E0M4_ERR_ALIGN;
+    if (K == 0) {                                   // empty contraction: Y = 0
+        const int64_t total = M * N;
+        hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                           static_cast<half_t*>(Y), total);
+        return check_launch();
+    }
+    if (!X || !codes || !scales || !bias) return E0M4_ERR_NULL;
+    if (!aligned16(X) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
+    if (M <= kGemvMaxM) {
+        const size_t need = gemv_workspace_bytes(M, N, K, group);
+        if (need > 0) {
+            if (!workspace) return E0M4_ERR_NULL;
+            if (!aligned16(workspace)) return E0M4_ERR_ALIGN;
+            if (workspace_bytes < need) return E0M4_ERR_WORKSPACE;
+        }
+        return launch_gemv(X, M, codes, scales, bias, N, K, group, Y, workspace, (hipStream_t)stream);
+    }
+    return launch_gemm(X, M, codes, scales, bias, N, K, group, Y, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,36 @@
+// Host-side internals of libe0m4: launcher prototypes shared between the C-ABI
+// file and the kernel files.  Not installed; the public interface is e0m4.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "e0m4.h"
+
+namespace e0m4 {
+
+// Records hipGetLastError(); returns E0M4_OK or E0M4_ERR_HIP.
+int check_launch();
+int record_hip_error(hipError_t e);
+
+// Tuning knobs (0 = use the heuristic).
+int knob(const char* name);
+
+int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, void* scales, void* bias,
+                    const void* scales_in, const void* bias_in, bool fit, hipStream_t stream);
+int launch_dequant(const void* codes, const void* scales, const void* bias, int64_t N, int64_t K, int group,
+                   void* W_out, hipStream_t stream);
+int launch_unpack(const void* codes, int64_t N, int64_t K, void* out, hipStream_t stream);
+
+// Small-M path (M <= kGemvMaxM).
+constexpr int kGemvMaxM = 8;
+size_t gemv_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
+int launch_gemv(const void* X, int64_t M, const void* codes, const void* scales, const void* bias, int64_t N,
+                int64_t K, int group, void* Y, void* workspace, hipStream_t stream);
+
+// MFMA path.
+int launch_gemm(const void* X, int64_t M, const void* codes, const void* scales, const void* bias, int64_t N,
+                int64_t K, int group, void* Y, hipStream_t stream);
+
+}  // namespace e0m4

@@ -1,0 +1,64 @@
+"""Parity at the full sizes of the benchmark workloads, in the launch
+configuration the benchmark times (default knobs): linear layers shaped like
+ChatGLM2-6B, Gemma-2B and a 14B decoder.  Codes/scales/bias/dequantised weights
+are compared in full (bit-exact).  The decode output (M=1) is compared in full;
+the prefill output on sampled rows (all N) and sampled columns (all M), which
+the oracle can compute one by one."""
+import numpy as np
+import pytest
+
+import synth_inputs
+from test_gpu_parity import DEV, assert_quantize_exact, bits, check_matmul, e0m4, to_dev, torch  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # (name, N, K, G, prefill M or None)
+    ("cfg1_square", 4096, 4096, 128, None),
+    ("chatglm2_qkv", 4608, 4096, 128, 1024),
+    ("chatglm2_attn_out", 4096, 4096, 128, 1024),
+    ("chatglm2_gate_up", 27392, 4096, 128, 1024),
+    ("chatglm2_down", 4096, 13696, 128, 1024),
+    ("gemma_qkv", 2560, 2048, 128, 512),
+    ("gemma_attn_out", 2048, 2048, 128, 512),
+    ("gemma_gate_up", 32768, 2048, 128, 512),
+    ("gemma_down", 2048, 16384, 128, 512),
+    ("gemma_lm_head", 256000, 2048, 128, None),
+    ("d14b_qkv_g64", 15360, 5120, 64, 2048),
+    ("d14b_attn_out_g128", 5120, 5120, 128, 2048),
+    ("d14b_gate_up_g128", 27392, 5120, 128, None),
+    ("d14b_down_g64", 5120, 13696, 64, 2048),
+]
+
+
+def sample_indices(count, total, tile, rng):
+    fixed = {0, total - 1, tile - 1, tile, total // 2, max(total - tile, 0), max(total - tile - 1, 0)}
+    fixed = {i for i in fixed if 0 <= i < total}
+    extra = set(int(i) for i in rng.integers(0, total, max(count - len(fixed), 0)))
+    return np.array(sorted(fixed | extra), dtype=np.int64)
+
+
+@pytest.mark.parametrize("name,N,K,G,Mp", CASES, ids=[c[0] for c in CASES])
+def test_full_size_layer(e0m4, oracle, name, N, K, G, Mp):
+    seed = abs(hash((N, K, G))) % 10007
+    prefill = Mp is not None
+    W = synth_inputs.weights(N, K, seed=seed, row_std_range=(0.5, 2.0) if prefill else None)
+    (codes, scales, bias), What = assert_quantize_exact(e0m4, oracle, W, G)
+    del W
+    # decode: whole output
+    X1 = synth_inputs.activations(1, K, seed=seed)
+    Y1 = e0m4.e0m4_matmul(to_dev(X1), codes, scales, bias, N, K, G)
+    Yref, absdot = oracle.matmul(X1, What)
+    check_matmul(Y1, Yref, absdot, name + " decode")
+    if not prefill:
+        return
+    # prefill: sampled rows over all N, sampled columns over all M
+    X = synth_inputs.activations(Mp, K, seed=seed + 1, outlier_frac=0.01)
+    Y = e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G).cpu().numpy()
+    rng = np.random.default_rng(seed)
+    ms = sample_indices(16, Mp, 128, rng)
+    Yr, ad = oracle.matmul(X[ms], What)
+    check_matmul(torch.from_numpy(Y[ms]), Yr, ad, name + " prefill rows")
+    ns = sample_indices(64, N, 128, rng)
+    Yc, adc = oracle.matmul(X, What[ns])
+    check_matmul(torch.from_numpy(np.ascontiguousarray(Y[:, ns])), Yc, adc, name + " prefill cols")

@@ -1,0 +1,274 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the
+C ABI (ctypes binding).  Codes, scales, bias and dequantised weights must be
+bit-exact; matmul outputs must satisfy
+    |y_gpu - y_ref| <= 1e-2 * max(1, sum_k |x_k * w_k|)
+per element (fp32 accumulation on the GPU, fp64 in the oracle)."""
+import numpy as np
+import pytest
+
+import synth_inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def e0m4():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run with -m 'not gpu' elsewhere)")
+    import paper_2403_20041_amd as pkg
+
+    pkg.lib()                                   # raises if the HIP library is not built
+    for k in ("gemv_splits", "gemv_wgs_per_cu", "gemv_min_groups_per_wg", "gemm_variant"):
+        pkg.e0m4_set_knob(k, 0)
+    return pkg
+
+
+DEV = "cuda:0"
+
+
+def to_dev(a: np.ndarray):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def bits(t) -> np.ndarray:
+    a = t.detach().cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.float16 else a
+
+
+def gpu_quantize(e0m4, W: np.ndarray, G: int):
+    N, K = W.shape
+    codes, scales, bias = e0m4.e0m4_quantize(to_dev(W), G)
+    return codes, scales, bias
+
+
+def assert_quantize_exact(e0m4, oracle, W: np.ndarray, G: int):
+    N, K = W.shape
+    codes, scales, bias = gpu_quantize(e0m4, W, G)
+    oc, os_, ob = oracle.quantize(W, G)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(scales), os_.view(np.uint16).T), "scales differ"
+    assert np.array_equal(bits(bias), ob.view(np.uint16).T), "bias differ"
+    got_codes = bits(e0m4.e0m4_unpack_codes(codes, N, K))
+    assert np.array_equal(got_codes, oc), "codes differ"
+    got_w = bits(e0m4.e0m4_dequant(codes, scales, bias, N, K, G))
+    want_w = oracle.dequant(oc, os_, ob, G)
+    assert np.array_equal(got_w, want_w.view(np.uint16)), "dequantised weights differ"
+    return (codes, scales, bias), want_w
+
+
+def check_matmul(y_gpu, y_ref: np.ndarray, absdot: np.ndarray, what=""):
+    got = y_gpu.detach().cpu().numpy().astype(np.float64)
+    ref = y_ref.astype(np.float64)
+    err = np.abs(got - ref)
+    tol = 1e-2 * np.maximum(1.0, absdot)
+    worst = np.unravel_index(np.argmax(err / tol), err.shape)
+    assert (err <= tol).all(), "%s: worst at %s err %g tol %g" % (what, worst, err[worst], tol[worst])
+    # quality bound well inside the acceptance bar: fp16 rounding of y and of the weights, fp32 accumulation
+    tight = 2.0 ** -9 * absdot + 2.0 ** -10 * np.abs(ref) + 1e-7
+    assert (err <= tight).all(), "%s: quality bound: %g" % (what, (err / tight).max())
+
+
+# ------------------------------------------------------------------ quantise / dequant / unpack
+
+SMALL_SHAPES = [
+    (64, 128), (200, 384), (1, 128), (63, 256), (65, 256), (130, 1024), (256, 4096),
+]
+
+
+@pytest.mark.parametrize("G", [32, 64, 128])
+@pytest.mark.parametrize("N,K", SMALL_SHAPES)
+def test_quantize_dequant_bit_exact(e0m4, oracle, N, K, G):
+    W = synth_inputs.weights(N, K, seed=1000 + N + K + G)
+    assert_quantize_exact(e0m4, oracle, W, G)
+
+
+def test_quantize_ragged_k_tile(e0m4, oracle):
+    # K = 416 = 13 chunks: the last 128-wide tile holds one chunk only
+    assert_quantize_exact(e0m4, oracle, synth_inputs.weights(70, 416, seed=3), 32)
+    assert_quantize_exact(e0m4, oracle, synth_inputs.weights(70, 448, seed=4), 64)
+
+
+@pytest.mark.parametrize("G", [32, 64, 128])
+def test_quantize_value_distributions(e0m4, oracle, G):
+    rng = np.random.default_rng(7 + G)
+    N, K = 192, 512
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    W[0:8] = 0.0                                              # all-zero groups
+    W[8:16] = np.float16(0.5)                                 # constant groups
+    W[16:24] = np.abs(W[16:24])                               # one-signed groups
+    W[24:32] = -np.abs(W[24:32])
+    W[32:40] = (rng.standard_normal((8, K)) * 3e-6).astype(np.float16)      # subnormal weights, floor on the scale
+    W[40:48] = (rng.standard_normal((8, K)) * 2e4).astype(np.float16)       # large weights
+    W[48, ::2] = np.float16(65504.0)
+    W[48, 1::2] = np.float16(-65504.0)                        # scale saturates
+    W[49:56] = (rng.standard_normal((7, K)) * 1e-4).astype(np.float16)
+    W[56:64, ::7] = 0.0
+    W[64:72, ::5] = np.float16(-0.0)
+    W[72:80] *= np.float16(50.0)
+    W[80:88] = rng.integers(-3, 4, (8, K)).astype(np.float16) * np.float16(2.0 ** -14)
+    with np.errstate(over="ignore"):
+        assert_quantize_exact(e0m4, oracle, W, G)
+
+
+def test_quantize_exhaustive_fp16_values(e0m4, oracle):
+    # every finite fp16 value appears; groups of mixed magnitudes
+    vals = np.arange(65536, dtype=np.uint32).astype(np.uint16).view(np.float16)
+    vals = vals[np.isfinite(vals)]
+    rng = np.random.default_rng(11)
+    W = rng.permutation(np.resize(vals, 64 * 1024)).reshape(64, 1024)
+    with np.errstate(over="ignore"):
+        assert_quantize_exact(e0m4, oracle, W, 32)
+    Ws = np.sort(np.resize(vals, 64 * 1024)).reshape(64, 1024)    # neighbours in value share a group
+    with np.errstate(over="ignore"):
+        assert_quantize_exact(e0m4, oracle, Ws, 128)
+
+
+@pytest.mark.parametrize("G", [32, 128])
+def test_encode_with_given_parameters(e0m4, oracle, G):
+    rng = np.random.default_rng(21 + G)
+    N, K = 130, 512
+    W = synth_inputs.weights(N, K, seed=22)
+    sc = (np.abs(rng.standard_normal((N, K // G))) * 0.02 + 1e-3).astype(np.float16)
+    z = rng.integers(0, 16, (N, K // G)).astype(np.uint16)
+    bi = (0x4000 | (z << 6)).astype(np.uint16).view(np.float16)
+    want = oracle.encode(W, sc, bi, G)
+    codes = e0m4.e0m4_encode(to_dev(W), to_dev(sc.T), to_dev(bi.T), G)
+    got = bits(e0m4.e0m4_unpack_codes(codes, N, K))
+    assert np.array_equal(got, want)
+    got_w = bits(e0m4.e0m4_dequant(codes, to_dev(sc.T), to_dev(bi.T), N, K, G))
+    assert np.array_equal(got_w, oracle.dequant(want, sc, bi, G).view(np.uint16))
+
+
+def test_dequant_all_codes_all_biases_many_scales(e0m4, oracle):
+    """Drive e0m4_dequant over every (code, bias) pair for a sweep of scales, including
+    scales whose products are subnormal or overflow."""
+    G, K = 32, 32
+    sb = np.concatenate([np.arange(0x0400, 0x7C00, 13, dtype=np.uint16), np.array([0x0400, 0x7BFF], np.uint16)])
+    N = sb.size * 16
+    scales = np.repeat(sb, 16)[:, None]
+    zz = np.tile(np.arange(16, dtype=np.uint16), sb.size)
+    bias = (0x4000 | (zz << 6)).astype(np.uint16)[:, None]
+    codes_np = np.tile(np.concatenate([np.arange(16), np.arange(15, -1, -1)]).astype(np.uint8), (N, 1))
+    # build W whose codes under these parameters are exactly codes_np (fixed-parameter round trip)
+    with np.errstate(over="ignore"):
+        W = oracle.dequant(codes_np, scales, bias, G)
+    ok_rows = np.isfinite(W).all(axis=1)
+    W, scales, bias, codes_np = W[ok_rows], scales[ok_rows], bias[ok_rows], codes_np[ok_rows]
+    N = W.shape[0]
+    sd, bd = to_dev(scales.view(np.float16).T), to_dev(bias.view(np.float16).T)
+    codes = e0m4.e0m4_encode(to_dev(W), sd, bd, G)
+    assert np.array_equal(bits(e0m4.e0m4_unpack_codes(codes, N, K)), codes_np)
+    assert np.array_equal(bits(e0m4.e0m4_dequant(codes, sd, bd, N, K, G)), W.view(np.uint16))
+
+
+# ------------------------------------------------------------------ matmul, small-M path
+
+def run_matmul_case(e0m4, oracle, M, N, K, G, seed, outliers=False, row_std=None):
+    W = synth_inputs.weights(N, K, seed=seed, row_std_range=row_std)
+    X = synth_inputs.activations(M, K, seed=seed, outlier_frac=0.01 if outliers else 0.0)
+    (codes, scales, bias), What = assert_quantize_exact(e0m4, oracle, W, G)
+    Y = e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G)
+    Yref, absdot = oracle.matmul(X, What)
+    torch.cuda.synchronize()
+    check_matmul(Y, Yref, absdot, "M=%d N=%d K=%d G=%d" % (M, N, K, G))
+    return Y
+
+
+@pytest.mark.parametrize("G", [32, 64, 128])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_gemv_small(e0m4, oracle, M, G):
+    run_matmul_case(e0m4, oracle, M, 200, 1152, G, seed=30 + M)
+
+
+@pytest.mark.parametrize("N,K,G", [(64, 128, 128), (1, 32, 32), (4096, 4096, 128), (1000, 13696, 128),
+                                    (5120, 5120, 64), (8192, 2048, 32), (130, 13696, 64)])
+def test_gemv_shapes_m1(e0m4, oracle, N, K, G):
+    run_matmul_case(e0m4, oracle, 1, N, K, G, seed=N + K)
+
+
+@pytest.mark.parametrize("splits", [1, 2, 3, 7, 9])
+def test_gemv_forced_split_k(e0m4, oracle, splits):
+    e0m4.e0m4_set_knob("gemv_splits", splits)
+    try:
+        run_matmul_case(e0m4, oracle, 1, 300, 1152, 128, seed=50)      # 9 groups
+        run_matmul_case(e0m4, oracle, 3, 300, 1152, 64, seed=51)
+    finally:
+        e0m4.e0m4_set_knob("gemv_splits", 0)
+
+
+# ------------------------------------------------------------------ matmul, MFMA path
+
+@pytest.mark.parametrize("M,N,K,G", [
+    (9, 64, 128, 128), (128, 128, 128, 128), (200, 328, 384, 128), (257, 200, 448, 64), (130, 70, 416, 32),
+    (512, 512, 1024, 128), (300, 1000, 2048, 64), (1024, 256, 4096, 128),
+])
+def test_gemm_small(e0m4, oracle, M, N, K, G):
+    run_matmul_case(e0m4, oracle, M, N, K, G, seed=M + N + K, outliers=True, row_std=(0.5, 2.0))
+
+
+# ------------------------------------------------------------------ special inputs through both paths
+
+@pytest.mark.parametrize("M", [4, 160])
+def test_one_hot_activations_reproduce_weights_bit_exactly(e0m4, oracle, M):
+    N, K, G = 200, 512, 128
+    W = synth_inputs.weights(N, K, seed=60)
+    (codes, scales, bias), What = assert_quantize_exact(e0m4, oracle, W, G)
+    ks = np.random.default_rng(61).integers(0, K, M)
+    ks[0], ks[-1] = 0, K - 1
+    X = np.zeros((M, K), dtype=np.float16)
+    X[np.arange(M), ks] = 1.0
+    Y = bits(e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G))
+    assert np.array_equal(Y, What.view(np.uint16)[:, ks].T)
+
+
+@pytest.mark.parametrize("M", [1, 64])
+def test_all_ones_activations_give_row_sums(e0m4, oracle, M):
+    N, K, G = 192, 1024, 64
+    W = synth_inputs.weights(N, K, seed=62)
+    (codes, scales, bias), What = assert_quantize_exact(e0m4, oracle, W, G)
+    X = np.ones((M, K), dtype=np.float16)
+    Y = e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G)
+    sums = What.astype(np.float64).sum(axis=1)
+    absdot = np.abs(What.astype(np.float64)).sum(axis=1)
+    check_matmul(Y, np.tile(sums.astype(np.float16), (M, 1)), np.tile(absdot, (M, 1)))
+
+
+@pytest.mark.parametrize("M", [1, 5, 200])
+def test_matmul_is_deterministic(e0m4, M):
+    N, K, G = 4096, 4096, 128
+    W = synth_inputs.weights(N, K, seed=63)
+    X = to_dev(synth_inputs.activations(M, K, seed=63))
+    codes, scales, bias = e0m4.e0m4_quantize(to_dev(W), G)
+    y1 = bits(e0m4.e0m4_matmul(X, codes, scales, bias, N, K, G))
+    y2 = bits(e0m4.e0m4_matmul(X, codes, scales, bias, N, K, G))
+    assert np.array_equal(y1, y2)
+
+
+def test_empty_problems(e0m4):
+    X = torch.zeros((0, 128), dtype=torch.float16, device=DEV)
+    codes, scales, bias = e0m4.alloc_packed(64, 128, 128, DEV)
+    assert e0m4.e0m4_matmul(X, codes, scales, bias, 64, 128, 128).shape == (0, 64)
+    # K = 0: the empty sum is zero
+    X0 = torch.zeros((3, 0), dtype=torch.float16, device=DEV)
+    c0, s0, b0 = e0m4.alloc_packed(70, 0, 128, DEV)
+    Y = torch.full((3, 70), 7.0, dtype=torch.float16, device=DEV)
+    e0m4.e0m4_matmul(X0, c0, s0, b0, 70, 0, 128, out=Y)
+    assert not Y.cpu().numpy().any()
+    # N = 0
+    W0 = torch.zeros((0, 128), dtype=torch.float16, device=DEV)
+    e0m4.e0m4_quantize(W0, 128)
+    torch.cuda.synchronize()
+
+
+def test_workspace_too_small_is_rejected(e0m4):
+    N, K, G = 4096, 4096, 128
+    need = e0m4.e0m4_workspace_bytes(1, N, K, G)
+    assert need > 0
+    codes, scales, bias = e0m4.alloc_packed(N, K, G, DEV)
+    X = torch.zeros((1, K), dtype=torch.float16, device=DEV)
+    ws = torch.empty(need - 16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(e0m4.E0M4Error) as ei:
+        e0m4.e0m4_matmul(X, codes, scales, bias, N, K, G, workspace=ws)
+    assert ei.value.code == -5

@@ -1,0 +1,108 @@
+"""Host-side checks of libe0m4 that need no GPU: the library loads, exports every
+symbol the public header declares, sizes are what the header says, and every
+argument error is caught before anything could be launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "e0m4.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2403_20041_amd import binding, build
+
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_library(verbose=False)
+    return binding.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(e0m4_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(L):
+    names = declared_symbols()
+    assert {"e0m4_quantize", "e0m4_dequant", "e0m4_matmul", "e0m4_unpack_codes", "e0m4_encode",
+            "e0m4_codes_bytes", "e0m4_params_elems", "e0m4_workspace_bytes", "e0m4_abi_version",
+            "e0m4_strerror", "e0m4_last_hip_error", "e0m4_set_knob"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+    assert L.e0m4_abi_version() == 1
+
+
+def test_size_functions(L):
+    assert L.e0m4_codes_bytes(4096, 4096) == 4096 * 4096 // 2
+    assert L.e0m4_codes_bytes(1, 32) == 64 * 16            # rows padded to a block of 64
+    assert L.e0m4_codes_bytes(65, 64) == 128 * 32
+    assert L.e0m4_codes_bytes(0, 4096) == 0
+    assert L.e0m4_codes_bytes(64, 48) == 0                 # K not a multiple of 32
+    assert L.e0m4_params_elems(4096, 4096, 128) == 32 * 4096
+    assert L.e0m4_params_elems(100, 256, 64) == 400
+    assert L.e0m4_params_elems(100, 256, 48) == 0
+    # the M=1 path over a small N needs split-K scratch; the MFMA path needs none
+    assert L.e0m4_workspace_bytes(1, 4096, 4096, 128) > 0
+    assert L.e0m4_workspace_bytes(1, 4096, 4096, 128) % (4 * 4096) == 0
+    assert L.e0m4_workspace_bytes(1024, 4096, 4096, 128) == 0
+    assert L.e0m4_workspace_bytes(1, 256000, 2048, 128) == 0
+
+
+def test_error_codes_before_any_launch(L):
+    p = ctypes.c_void_p(0x1000)         # aligned, never dereferenced: every call below fails validation first
+    odd = ctypes.c_void_p(0x1008)
+    null = ctypes.c_void_p(0)
+    ERR_NULL, ERR_SHAPE, ERR_GROUP, ERR_ALIGN, ERR_WS = -1, -2, -3, -4, -5
+    assert L.e0m4_quantize(p, 64, 100, 128, p, p, p, null) == ERR_SHAPE      # K % 32
+    assert L.e0m4_quantize(p, 64, 192, 128, p, p, p, null) == ERR_SHAPE      # K % group
+    assert L.e0m4_quantize(p, -1, 128, 128, p, p, p, null) == ERR_SHAPE
+    assert L.e0m4_quantize(p, 64, 128, 16, p, p, p, null) == ERR_GROUP
+    assert L.e0m4_quantize(p, 64, 128, 256, p, p, p, null) == ERR_GROUP
+    assert L.e0m4_quantize(null, 64, 128, 128, p, p, p, null) == ERR_NULL
+    assert L.e0m4_quantize(p, 64, 128, 128, p, null, p, null) == ERR_NULL
+    assert L.e0m4_quantize(odd, 64, 128, 128, p, p, p, null) == ERR_ALIGN
+    assert L.e0m4_encode(p, 64, 128, 128, null, p, p, null) == ERR_NULL
+    assert L.e0m4_dequant(p, p, p, 64, 128, 128, null, null) == ERR_NULL
+    assert L.e0m4_dequant(p, p, p, 64, 128, 128, odd, null) == ERR_ALIGN
+    assert L.e0m4_unpack_codes(p, 64, 130, p, null) == ERR_SHAPE
+    assert L.e0m4_matmul(p, 1, p, p, p, 64, 100, 128, p, null, 0, null) == ERR_SHAPE
+    assert L.e0m4_matmul(p, -1, p, p, p, 64, 128, 128, p, null, 0, null) == ERR_SHAPE
+    assert L.e0m4_matmul(null, 1, p, p, p, 64, 128, 128, p, null, 0, null) == ERR_NULL
+    assert L.e0m4_matmul(p, 1, p, p, p, 64, 128, 128, odd, null, 0, null) == ERR_ALIGN
+    need = L.e0m4_workspace_bytes(1, 4096, 4096, 128)
+    assert L.e0m4_matmul(p, 1, p, p, p, 4096, 4096, 128, p, null, 0, null) == ERR_NULL       # workspace required
+    assert L.e0m4_matmul(p, 1, p, p, p, 4096, 4096, 128, p, p, need - 1, null) == ERR_WS
+    # empty problems succeed without touching anything
+    assert L.e0m4_quantize(null, 0, 128, 128, null, null, null, null) == 0
+    assert L.e0m4_matmul(null, 0, null, null, null, 64, 128, 128, null, null, 0, null) == 0
+    assert L.e0m4_matmul(null, 4, null, null, null, 0, 128, 128, null, null, 0, null) == 0
+    for code in (0, -1, -2, -3, -4, -5, -6, -99):
+        assert L.e0m4_strerror(code)
+    assert L.e0m4_set_knob(b"no_such_knob", 1) == ERR_SHAPE
+    assert L.e0m4_set_knob(b"gemv_splits", 0) == 0
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    from paper_2403_20041_amd import binding
+
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libe0m4.so"))
+    with pytest.raises(RuntimeError, match="not built"):
+        binding.lib()
+
+
+def test_product_does_not_import_oracle():
+    pkg = os.path.join(ROOT, "paper_2403_20041_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".hpp", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2403_20041_amd" not in text and "libe0m4.so" not in text
