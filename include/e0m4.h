@@ -17,12 +17,18 @@
  *   - fp16 is IEEE binary16.  W is [N,K] row-major (N = output features,
  *     K = input features, K contiguous), X is [M,K] row-major, Y is [M,N]
  *     row-major.
- *   - `scales` and `bias` are [K/group, N] fp16, group-major: the parameters
- *     of group g of row n are at index g*N + n.  `scale` is the dequantisation
- *     multiplier, `bias` the binade image of zero (always 2 + z/8, z in 0..15).
- *   - `codes` is an opaque device layout of e0m4_codes_bytes(N,K) bytes (rows
- *     padded to a multiple of 64, tiled so that a wavefront reads 1 KiB
- *     contiguous); use e0m4_unpack_codes / e0m4_dequant to look inside.
+ *   - `scales` and `bias` are [N, K/group] fp16 row-major: the parameters of
+ *     group g of row n are at index n*(K/group) + g.  `scale` is the
+ *     dequantisation multiplier, `bias` the binade image of zero (always
+ *     2 + z/8, z in 0..15).
+ *   - `codes` is the packed weight buffer, an opaque device layout of
+ *     e0m4_codes_bytes(N,K,group) bytes: blocks of 16 rows x 128 k, each 1 KiB
+ *     of codes (one wavefront-wide 16-byte-per-lane read) followed by a copy of
+ *     the block's scales and biases, ordered so that everything a block of 16
+ *     output rows needs is one contiguous stream.  The kernels that consume
+ *     weights (e0m4_matmul, e0m4_dequant) read the parameters from this
+ *     embedded copy; the separate `scales`/`bias` arrays are the plain view of
+ *     the same values.  Use e0m4_unpack_codes / e0m4_dequant to look inside.
  *   - Shape rules: N >= 0, M >= 0, K >= 0, K % 32 == 0, K % group == 0,
  *     group in {32, 64, 128}.  Data pointers must be 16-byte aligned.
  *   - Return value: 0 on success; a negative E0M4_ERR_* code otherwise, in
@@ -41,7 +47,7 @@
 extern "C" {
 #endif
 
-#define E0M4_ABI_VERSION 1
+#define E0M4_ABI_VERSION 2
 
 #define E0M4_OK              0
 #define E0M4_ERR_NULL      (-1)   /* a required pointer is NULL */
@@ -56,12 +62,13 @@ const char* e0m4_strerror(int code);
 /* Text of the last HIP error seen by this thread's calls ("" if none). */
 const char* e0m4_last_hip_error(void);
 
-/* Size in bytes of the packed code buffer: ceil(N/64)*64 * K/2.  0 on invalid shape. */
-size_t e0m4_codes_bytes(int64_t N, int64_t K);
-/* Number of fp16 elements in `scales` (and in `bias`): (K/group) * N. */
+/* Size in bytes of the packed weight buffer:
+ * ceil(N/16) * ceil(K/128) * (1024 + 64 * (128/group)).  0 on invalid shape. */
+size_t e0m4_codes_bytes(int64_t N, int64_t K, int group);
+/* Number of fp16 elements in `scales` (and in `bias`): N * (K/group). */
 size_t e0m4_params_elems(int64_t N, int64_t K, int group);
-/* Scratch bytes e0m4_matmul needs for this shape (split-K partial sums of the
- * small-M path); may be 0.  Depends only on the arguments. */
+/* Scratch bytes e0m4_matmul needs for this shape.  Every path of this version
+ * keeps its partial sums on chip, so this is 0; callers should still query it. */
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
 
 /*
@@ -70,16 +77,16 @@ size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
  * binade is 4 - 2^-9; bias keeps its four highest fraction bits), map every
  * weight as w/scale + bias in fp32, clamp into the binade, round once to fp16
  * and take code = min(y1 + y2, 15) from the four highest fraction bits y1 and
- * the next bit y2.  Outputs: codes (packed layout), scales, bias.
+ * the next bit y2.  Outputs: codes (packed buffer), scales, bias.
  */
 int e0m4_quantize(const void* W_f16, int64_t N, int64_t K, int group,
                   void* codes, void* scales_f16, void* bias_f16, void* stream);
 
 /*
- * Encode only: codes of W under caller-supplied scales/bias (same map, clamp
- * and rounding as e0m4_quantize, no fitting).  This is the seam for weight
- * quantisers that choose their own group parameters (the paper notes E0M4
- * composes with GPTQ/AWQ-style methods).
+ * Encode only: packed buffer of W under caller-supplied scales/bias (same map,
+ * clamp and rounding as e0m4_quantize, no fitting).  This is the seam for
+ * weight quantisers that choose their own group parameters (the paper notes
+ * E0M4 composes with GPTQ/AWQ-style methods).
  */
 int e0m4_encode(const void* W_f16, int64_t N, int64_t K, int group,
                 const void* scales_f16, const void* bias_f16, void* codes, void* stream);
@@ -87,23 +94,24 @@ int e0m4_encode(const void* W_f16, int64_t N, int64_t K, int group,
 /*
  * Dequantise (paper: dequantization formula): W_out[n,k] =
  * fp16((as_half(0x4000 | code << 6) - bias) * scale), one rounding.
- * W_out is [N,K] row-major fp16.
+ * W_out is [N,K] row-major fp16.  `scales_f16`/`bias_f16` may be NULL (the
+ * packed buffer carries the parameters).
  */
 int e0m4_dequant(const void* codes, const void* scales_f16, const void* bias_f16,
                  int64_t N, int64_t K, int group, void* W_f16_out, void* stream);
 
 /* Test hook: codes_u8_out[n,k] = code of weight (n,k), one byte each, [N,K] row-major. */
-int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, void* codes_u8_out, void* stream);
+int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* codes_u8_out, void* stream);
 
 /*
  * Y = X * dequant(codes)^T  (paper: section "Operator and lagging
  * optimizations", fp16 activation x 4-bit weight matmul; vector-matrix for
  * decode, matrix-matrix for prefill).  Dequantisation is fused in registers;
  * accumulation is fp32; Y is rounded once to fp16.
- *   M <= 8 : HBM-bound split-K GEMV path (may use `workspace`).
+ *   M <= 8 : HBM-bound GEMV path (one workgroup per 16 output rows).
  *   M >= 9 : MFMA GEMM path.
- * `workspace` may be NULL iff e0m4_workspace_bytes(M,N,K,group) == 0.
- * Calls that share a workspace must be ordered on one stream.
+ * `scales_f16`/`bias_f16` may be NULL (see `codes` above); `workspace` may be
+ * NULL when e0m4_workspace_bytes() is 0.  The result is deterministic.
  */
 int e0m4_matmul(const void* X_f16, int64_t M,
                 const void* codes, const void* scales_f16, const void* bias_f16,
@@ -112,7 +120,7 @@ int e0m4_matmul(const void* X_f16, int64_t M,
 
 /*
  * Diagnostics for tuning sweeps; not needed for normal use.  Sets an integer
- * knob by name (e.g. "gemv_waves_per_cu"); unknown names return E0M4_ERR_SHAPE.
+ * knob by name (e.g. "gemv_waves"); unknown names return E0M4_ERR_SHAPE.
  * A value of 0 restores the built-in heuristic.
  */
 int e0m4_set_knob(const char* name, int value);

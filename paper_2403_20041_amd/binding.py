@@ -46,7 +46,7 @@ def lib() -> ctypes.CDLL:
     L.e0m4_last_hip_error.restype = ctypes.c_char_p
     L.e0m4_last_hip_error.argtypes = []
     L.e0m4_codes_bytes.restype = sz
-    L.e0m4_codes_bytes.argtypes = [i64, i64]
+    L.e0m4_codes_bytes.argtypes = [i64, i64, ci]
     L.e0m4_params_elems.restype = sz
     L.e0m4_params_elems.argtypes = [i64, i64, ci]
     L.e0m4_workspace_bytes.restype = sz
@@ -58,12 +58,12 @@ def lib() -> ctypes.CDLL:
     L.e0m4_dequant.restype = ci
     L.e0m4_dequant.argtypes = [vp, vp, vp, i64, i64, ci, vp, vp]
     L.e0m4_unpack_codes.restype = ci
-    L.e0m4_unpack_codes.argtypes = [vp, i64, i64, vp, vp]
+    L.e0m4_unpack_codes.argtypes = [vp, i64, i64, ci, vp, vp]
     L.e0m4_matmul.restype = ci
     L.e0m4_matmul.argtypes = [vp, i64, vp, vp, vp, i64, i64, ci, vp, vp, sz, vp]
     L.e0m4_set_knob.restype = ci
     L.e0m4_set_knob.argtypes = [ctypes.c_char_p, ci]
-    if L.e0m4_abi_version() != 1:
+    if L.e0m4_abi_version() != 2:
         raise RuntimeError("libe0m4 ABI version mismatch")
     _lib = L
     return L
@@ -90,8 +90,8 @@ def _need(t: torch.Tensor, dtype, shape, name: str):
                          % (name, dtype, tuple(shape), t.dtype, tuple(t.shape), t.device))
 
 
-def e0m4_codes_bytes(N: int, K: int) -> int:
-    return lib().e0m4_codes_bytes(N, K)
+def e0m4_codes_bytes(N: int, K: int, group: int) -> int:
+    return lib().e0m4_codes_bytes(N, K, group)
 
 
 def e0m4_params_elems(N: int, K: int, group: int) -> int:
@@ -107,10 +107,10 @@ def e0m4_set_knob(name: str, value: int) -> None:
 
 
 def alloc_packed(N: int, K: int, group: int, device):
-    """Uninitialised output buffers for e0m4_quantize: (codes u8, scales f16 [K/G,N], bias f16 [K/G,N])."""
-    codes = torch.empty(max(e0m4_codes_bytes(N, K), 1), dtype=torch.uint8, device=device)
-    scales = torch.empty((K // group, N), dtype=torch.float16, device=device)
-    bias = torch.empty((K // group, N), dtype=torch.float16, device=device)
+    """Uninitialised output buffers for e0m4_quantize: (codes u8, scales f16 [N,K/G], bias f16 [N,K/G])."""
+    codes = torch.empty(max(e0m4_codes_bytes(N, K, group), 16), dtype=torch.uint8, device=device)
+    scales = torch.empty((N, K // group), dtype=torch.float16, device=device)
+    bias = torch.empty((N, K // group), dtype=torch.float16, device=device)
     return codes, scales, bias
 
 
@@ -127,10 +127,10 @@ def e0m4_quantize(W: torch.Tensor, group: int, out=None, stream=None):
 def e0m4_encode(W: torch.Tensor, scales: torch.Tensor, bias: torch.Tensor, group: int, codes=None, stream=None):
     N, K = W.shape
     _need(W, torch.float16, (N, K), "W")
-    _need(scales, torch.float16, (K // group, N), "scales")
-    _need(bias, torch.float16, (K // group, N), "bias")
+    _need(scales, torch.float16, (N, K // group), "scales")
+    _need(bias, torch.float16, (N, K // group), "bias")
     if codes is None:
-        codes = torch.empty(max(e0m4_codes_bytes(N, K), 1), dtype=torch.uint8, device=W.device)
+        codes = torch.empty(max(e0m4_codes_bytes(N, K, group), 16), dtype=torch.uint8, device=W.device)
     _check(lib().e0m4_encode(_ptr(W), N, K, group, _ptr(scales), _ptr(bias), _ptr(codes), _stream(stream)),
            "e0m4_encode")
     return codes
@@ -145,11 +145,11 @@ def e0m4_dequant(codes, scales, bias, N: int, K: int, group: int, out=None, stre
     return out
 
 
-def e0m4_unpack_codes(codes, N: int, K: int, out=None, stream=None) -> torch.Tensor:
+def e0m4_unpack_codes(codes, N: int, K: int, group: int, out=None, stream=None) -> torch.Tensor:
     if out is None:
         out = torch.empty((N, K), dtype=torch.uint8, device=codes.device)
     _need(out, torch.uint8, (N, K), "out")
-    _check(lib().e0m4_unpack_codes(_ptr(codes), N, K, _ptr(out), _stream(stream)), "e0m4_unpack_codes")
+    _check(lib().e0m4_unpack_codes(_ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m4_unpack_codes")
     return out
 
 

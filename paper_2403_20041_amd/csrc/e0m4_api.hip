@@ -18,9 +18,10 @@ struct Knob {
     std::atomic<int> value;
 };
 Knob g_knobs[] = {
-    {"gemv_wgs_per_cu", {0}},          // target resident workgroups per compute unit when splitting K
-    {"gemv_min_groups_per_wg", {0}},   // lower bound on the K extent of one workgroup, in groups
-    {"gemv_splits", {0}},              // force the number of K splits
+    {"gemv_waves", {0}},               // wavefronts per workgroup of the small-M kernel (4, 8 or 16)
+    {"gemv_debug", {0}},               // timing experiments (results are wrong when set)
+    {"gemv_occ", {0}},                 // 8: M=1 kernel variant capped at 64 registers per lane
+    {"gemv_workgroups", {0}},          // target number of workgroups of the small-M kernel
     {"gemm_variant", {0}},             // select a GEMM kernel variant
 };
 
@@ -85,23 +86,22 @@ const char* e0m4_strerror(int code)
 
 const char* e0m4_last_hip_error(void) { return g_hip_error; }
 
-size_t e0m4_codes_bytes(int64_t N, int64_t K)
+size_t e0m4_codes_bytes(int64_t N, int64_t K, int group)
 {
-    if (N < 0 || K < 0 || (K % kCodesPerChunk) != 0) return 0;
-    return (size_t)padded_rows(N) * (size_t)K / 2;
+    if (check_shape(N, K, group) != E0M4_OK) return 0;
+    return (size_t)row_blocks(N) * (size_t)k_blocks(K) * (size_t)block_bytes(group);
 }
 
 size_t e0m4_params_elems(int64_t N, int64_t K, int group)
 {
     if (check_shape(N, K, group) != E0M4_OK) return 0;
-    return (size_t)(K / group) * (size_t)N;
+    return (size_t)N * (size_t)(K / group);
 }
 
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 {
-    if (M < 0 || check_shape(N, K, group) != E0M4_OK) return 0;
-    if (M >= 1 && M <= kGemvMaxM) return gemv_workspace_bytes(M, N, K, group);
-    return 0;
+    (void)M; (void)N; (void)K; (void)group;
+    return 0;                                   // no kernel of this version needs scratch memory
 }
 
 int e0m4_set_knob(const char* name, int value)
@@ -139,27 +139,29 @@ int e0m4_encode(const void* W, int64_t N, int64_t K, int group, const void* scal
 int e0m4_dequant(const void* codes, const void* scales, const void* bias, int64_t N, int64_t K, int group, void* W_out,
                  void* stream)
 {
+    (void)scales; (void)bias;                   // the packed buffer carries its own copy of the parameters
     int rc = check_shape(N, K, group);
     if (rc != E0M4_OK) return rc;
     if (N == 0 || K == 0) return E0M4_OK;
-    if (!W_out || !codes || !scales || !bias) return E0M4_ERR_NULL;
-    if (!aligned16(W_out) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
-    return launch_dequant(codes, scales, bias, N, K, group, W_out, (hipStream_t)stream);
+    if (!W_out || !codes) return E0M4_ERR_NULL;
+    if (!aligned16(W_out) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    return launch_dequant(codes, N, K, group, W_out, (hipStream_t)stream);
 }
 
-int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, void* out, void* stream)
+int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* out, void* stream)
 {
-    int rc = check_shape(N, K, 32);
+    int rc = check_shape(N, K, group);
     if (rc != E0M4_OK) return rc;
     if (N == 0 || K == 0) return E0M4_OK;
     if (!codes || !out) return E0M4_ERR_NULL;
     if (!aligned16(codes) || !aligned16(out)) return E0M4_ERR_ALIGN;
-    return launch_unpack(codes, N, K, out, (hipStream_t)stream);
+    return launch_unpack(codes, N, K, group, out, (hipStream_t)stream);
 }
 
 int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales, const void* bias, int64_t N, int64_t K,
                 int group, void* Y, void* workspace, size_t workspace_bytes, void* stream)
 {
+    (void)scales; (void)bias; (void)workspace; (void)workspace_bytes;
     int rc = check_shape(N, K, group);
     if (rc != E0M4_OK) return rc;
     if (M < 0 || M > (int64_t)1 << 31) return E0M4_ERR_SHAPE;
@@ -172,18 +174,10 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
                            static_cast<half_t*>(Y), total);
         return check_launch();
     }
-    if (!X || !codes || !scales || !bias) return E0M4_ERR_NULL;
-    if (!aligned16(X) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
-    if (M <= kGemvMaxM) {
-        const size_t need = gemv_workspace_bytes(M, N, K, group);
-        if (need > 0) {
-            if (!workspace) return E0M4_ERR_NULL;
-            if (!aligned16(workspace)) return E0M4_ERR_ALIGN;
-            if (workspace_bytes < need) return E0M4_ERR_WORKSPACE;
-        }
-        return launch_gemv(X, M, codes, scales, bias, N, K, group, Y, workspace, (hipStream_t)stream);
-    }
-    return launch_gemm(X, M, codes, scales, bias, N, K, group, Y, (hipStream_t)stream);
+    if (!X || !codes) return E0M4_ERR_NULL;
+    if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    if (M <= kGemvMaxM) return launch_gemv(X, M, codes, N, K, group, Y, (hipStream_t)stream);
+    return launch_gemm(X, M, codes, N, K, group, Y, (hipStream_t)stream);
 }
 
 }  // extern "C"

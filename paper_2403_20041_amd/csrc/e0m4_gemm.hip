@@ -27,9 +27,7 @@ __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2
 
 template <int G>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict__ X, int64_t M,
-                                                        const uint4* __restrict__ codes,
-                                                        const half_t* __restrict__ scales,
-                                                        const half_t* __restrict__ bias, int64_t N, int64_t K,
+                                                        const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                         half_t* __restrict__ Y, int m_tiles)
 {
     __shared__ __attribute__((aligned(16))) half_t As[BM * kLdsStride];
@@ -42,21 +40,20 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
     const int64_t mt = blockIdx.x % m_tiles;
     const int64_t nt = blockIdx.x / m_tiles;
     const int64_t m0 = mt * BM, n0 = nt * BN;
-    const int64_t nchunks = K / kCodesPerChunk;
-    const int64_t nrb = padded_rows(N) / kRowsPerBlock;
+    const PackedLayout<G> lay(K);
+    const int64_t nrb = row_blocks(N);
 
     // A loader: 4 x 16 bytes per thread, 8 lanes cover one 128-byte row slice
     const int a_row = t >> 3, a_piece = t & 7;
-    // B loader: one 16-byte chunk per thread: lane = row inside a 64-row block
-    const int b_rb = wave >> 1, b_q = wave & 1;
-    const int64_t rb = n0 / kRowsPerBlock + b_rb;
-    const int64_t bn = rb * kRowsPerBlock + lane;
-    const int64_t bnn = bn < N ? bn : N - 1;
+    // B loader: one 16-byte chunk per thread.  The 128 x 64 weight tile is the left or right half of
+    // 8 packed blocks; 32 consecutive threads read the 512 contiguous bytes of one half block.
+    const int b_hb = t >> 5, b_q = (t >> 4) & 1, b_r = t & 15;
+    const int64_t rb = n0 / kBlockRows + b_hb;
     const bool b_ok = rb < nrb;
 
     uint4 a_reg[4];
     uint4 b_reg;
-    half_t sc_reg, bi_reg;
+    uint32_t pw_reg;
 
     auto load_tile = [&](int64_t k0) {
 #pragma unroll
@@ -66,15 +63,13 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
             a_reg[i] = make_uint4(0, 0, 0, 0);
             if (m < M && k < K) a_reg[i] = *reinterpret_cast<const uint4*>(X + m * K + k);
         }
-        const int64_t chunk = k0 / kCodesPerChunk + b_q;
         b_reg = make_uint4(0, 0, 0, 0);
-        sc_reg = (half_t)0.f;
-        bi_reg = (half_t)0.f;
-        if (b_ok && chunk < nchunks) {
-            b_reg = codes[(rb * nchunks + chunk) * kRowsPerBlock + lane];
-            const int64_t g = chunk * kCodesPerChunk / G;
-            sc_reg = scales[g * N + bnn];
-            bi_reg = bias[g * N + bnn];
+        pw_reg = 0;                                      // scale 0, bias 0: dequantises to 0
+        if (b_ok) {
+            const int64_t kb = k0 / kBlockK;
+            const int q = (int)(k0 % kBlockK) / kCodesPerChunk + b_q;
+            b_reg = packed[lay.code_index(rb, kb) + q * kBlockRows + b_r];
+            pw_reg = reinterpret_cast<const uint32_t*>(packed)[lay.param_index(rb, kb) + lay.param_slot(q, b_r)];
         }
     };
 
@@ -82,9 +77,10 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             *reinterpret_cast<uint4*>(&As[(a_row + 32 * i) * kLdsStride + a_piece * 8]) = a_reg[i];
-        const half2_t s2 = {sc_reg, sc_reg}, b2 = {bi_reg, bi_reg};
+        const half_t sc = param_scale(pw_reg), bi = param_bias(pw_reg);
+        const half2_t s2 = {sc, sc}, b2 = {bi, bi};
         const uint32_t words[4] = {b_reg.x, b_reg.y, b_reg.z, b_reg.w};
-        half_t* dst = &Bs[(b_rb * kRowsPerBlock + lane) * kLdsStride + b_q * 32];
+        half_t* dst = &Bs[(b_hb * kBlockRows + b_r) * kLdsStride + b_q * 32];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             half2_t o[4];
@@ -146,21 +142,19 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
 
 }  // namespace
 
-int launch_gemm(const void* X, int64_t M, const void* codes, const void* scales, const void* bias, int64_t N,
-                int64_t K, int group, void* Y, hipStream_t stream)
+int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                hipStream_t stream)
 {
     const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
     if (m_tiles * n_tiles > 0x7fffffffLL) return E0M4_ERR_SHAPE;
     const dim3 grid((unsigned)(m_tiles * n_tiles)), block(kThreads);
     const half_t* x = static_cast<const half_t*>(X);
-    const uint4* c = static_cast<const uint4*>(codes);
-    const half_t* s = static_cast<const half_t*>(scales);
-    const half_t* b = static_cast<const half_t*>(bias);
+    const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     switch (group) {
-        case 32: hipLaunchKernelGGL(gemm_kernel<32>, grid, block, 0, stream, x, M, c, s, b, N, K, y, (int)m_tiles); break;
-        case 64: hipLaunchKernelGGL(gemm_kernel<64>, grid, block, 0, stream, x, M, c, s, b, N, K, y, (int)m_tiles); break;
-        case 128: hipLaunchKernelGGL(gemm_kernel<128>, grid, block, 0, stream, x, M, c, s, b, N, K, y, (int)m_tiles); break;
+        case 32: hipLaunchKernelGGL(gemm_kernel<32>, grid, block, 0, stream, x, M, c, N, K, y, (int)m_tiles); break;
+        case 64: hipLaunchKernelGGL(gemm_kernel<64>, grid, block, 0, stream, x, M, c, N, K, y, (int)m_tiles); break;
+        case 128: hipLaunchKernelGGL(gemm_kernel<128>, grid, block, 0, stream, x, M, c, N, K, y, (int)m_tiles); break;
         default: return E0M4_ERR_GROUP;
     }
     return check_launch();

@@ -1,17 +1,21 @@
-// Decode path of e0m4_matmul: Y[M,N] = X[M,K] * dequant(codes)^T for M <= 8.
+// Decode path of e0m4_matmul: Y[M,N] = X[M,K] * dequant(packed)^T for M <= 8.
 // Paper: section "Operator and lagging optimizations" (vector-matrix product
 // of the decoding stage, bound by memory bandwidth) with the dequantisation of
 // section "E0M4 FP4 quantization" fused in registers.
 //
-// Work decomposition (gfx950, wave64): one lane owns one output row, so the
-// activations are wavefront-uniform and are read through scalar loads; a
-// wavefront streams the 1 KiB chunks of its 64-row block along K with
-// dwordx4 loads.  Per group the kernel accumulates a = sum_k x_k * w1_k with
-// v_dot2_f32_f16 on the raw binade values w1 = 2 + code/8 and applies the
-// group's affine map once:  y += scale * (a - bias * sum_k x_k).
-// K is split over the 4 wavefronts of a workgroup (reduced through LDS) and,
-// when N alone cannot fill the chip, over several workgroups whose fp32
-// partial sums are added in a fixed order by a second small kernel.
+// Work decomposition (gfx950, wave64): a workgroup owns a few consecutive blocks
+// of 16 output rows over the whole of K, so no partial sums ever leave the
+// compute unit and no second kernel, atomics or scratch memory are needed.  Its
+// W wavefronts take the 16 x 128 weight blocks of that contiguous run
+// round-robin and keep several in flight; each block is one dwordx4 load per
+// lane (1 KiB contiguous per wavefront) plus one dword of group parameters.
+// Lane q*16 + r holds 32 codes of row r: it turns them into the raw binade
+// values w1 = 2 + code/8 with a shift and a mask-or per pair, accumulates
+// a = sum x*w1 with v_dot2_f32_f16 against activations staged in LDS, and
+// applies the group's affine map once per block:
+//     y += scale * (a - bias * sum x).
+// The four k-quarters of a row are added with two cross-lane steps, the
+// wavefronts' sums through LDS in a fixed order (deterministic result).
 #include "e0m4_device.h"
 #include "e0m4_host.h"
 
@@ -19,216 +23,315 @@ namespace e0m4 {
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / 64;
-constexpr int kNumCU = 256;
+constexpr int kXBudgetBytes = 48 * 1024;        // LDS spent on activations and their chunk sums
+constexpr int kRedBudgetBytes = 16 * 1024;      // LDS spent on the per-wavefront partial sums
+constexpr int kBytesPerBlockX = kBlockK * 2 + (kBlockK / kCodesPerChunk) * 4;   // 272 per row of X per k block
+constexpr int kTargetWorkgroups = 512;          // two resident workgroups of 16 wavefronts per compute unit
+constexpr int kDepth = 4;                       // weight blocks in flight per wavefront
+constexpr int kEarlyX = 2;                      // activation pieces per thread requested before the weights
 
 struct GemvPlan {
-    int64_t nrb;        // 64-row blocks
-    int ngroups;        // K / G
-    int gps;            // groups per workgroup (split length)
-    int splits;         // workgroups along K
+    int waves;          // wavefronts per workgroup
+    int seg_blocks;     // k blocks whose activations are resident in LDS at a time (multiple of waves)
+    int rb_per_wg;      // consecutive row blocks owned by one workgroup
+    int64_t grid;
+    size_t lds_bytes;
 };
 
-GemvPlan make_plan(int64_t N, int64_t K, int group)
+GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
 {
     GemvPlan p;
-    p.nrb = padded_rows(N) / kRowsPerBlock;
-    p.ngroups = (int)(K / group);
-    int wgs_per_cu = knob("gemv_wgs_per_cu");
-    if (wgs_per_cu <= 0) wgs_per_cu = 4;
-    int min_gps = knob("gemv_min_groups_per_wg");
-    if (min_gps <= 0) min_gps = kWaves * (128 / group);           // at least 4 KiB of codes per wavefront
-    const int64_t target = (int64_t)kNumCU * wgs_per_cu;
-    int64_t s = (target + p.nrb - 1) / (p.nrb > 0 ? p.nrb : 1);
-    const int forced = knob("gemv_splits");
-    if (forced > 0) s = forced;
-    int gps = (int)((p.ngroups + s - 1) / (s > 0 ? s : 1));
-    if (forced <= 0 && gps < min_gps) gps = min_gps;
-    if (gps > p.ngroups) gps = p.ngroups;
-    if (gps < 1) gps = 1;
-    p.gps = gps;
-    p.splits = p.ngroups > 0 ? (p.ngroups + gps - 1) / gps : 1;
+    const int64_t nrb = row_blocks(N), nkb = k_blocks(K);
+    int w = knob("gemv_waves");
+    // 16 wavefronts per row block when there is at most one row block per compute unit (that is the
+    // only parallelism there is); 8 otherwise (measured faster) and for many rows of X, whose
+    // accumulators need the larger register budget of the smaller workgroup
+    if (w != 4 && w != 8 && w != 16) w = (M <= 4 && nrb <= 256) ? 16 : 8;
+    while (w > 4 && w > nkb) w /= 2;                          // a wavefront steps W k blocks at a time
+    p.waves = w;
+    int64_t max_blocks = kXBudgetBytes / (M * kBytesPerBlockX) / w * w;
+    if (max_blocks < w) max_blocks = w;
+    const int64_t need = (nkb + w - 1) / w * w;
+    const bool single_segment = need <= max_blocks;
+    p.seg_blocks = (int)(single_segment ? need : max_blocks);
+    int64_t t_max = kRedBudgetBytes / ((int64_t)w * M * kBlockRows * sizeof(float));
+    if (t_max < 1) t_max = 1;
+    int target = knob("gemv_workgroups");
+    if (target <= 0) target = kTargetWorkgroups * 8 / w;      // 16 wavefronts resident per compute unit
+    int64_t t = (nrb + target - 1) / target;
+    if (t > t_max) t = t_max;
+    if (t < 1 || !single_segment) t = 1;       // several activation segments: one row block per workgroup
+    p.rb_per_wg = (int)t;
+    p.grid = (nrb + t - 1) / t;
+    p.lds_bytes = (size_t)M * p.seg_blocks * kBytesPerBlockX + (size_t)t * w * M * kBlockRows * sizeof(float);
     return p;
 }
 
-template <int G, int M>
-__global__ __launch_bounds__(kThreads) void gemv_kernel(const half_t* __restrict__ X,
-                                                        const uint4* __restrict__ codes,
-                                                        const half_t* __restrict__ scales,
-                                                        const half_t* __restrict__ bias, int64_t N, int64_t K,
-                                                        int ngroups, int gps, int splits, half_t* __restrict__ Y,
-                                                        float* __restrict__ partial)
+// A workgroup owns `rb_per_wg` consecutive row blocks; its work items are their weight blocks in
+// memory order (row block major, k block minor).  Wavefront w takes items w, w+W, w+2W, ... and
+// keeps a ring of D of them in flight.  VARIANT != 0 are timing experiments (wrong results).
+template <int G, int M, int W, bool SMALLK = false, int VARIANT = 0, int OCC = 1>
+__global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restrict__ X,
+                                                           const uint4* __restrict__ packed, int64_t N, int64_t K,
+                                                           half_t* __restrict__ Y, int seg_blocks, int rb_per_wg)
 {
-    constexpr int CPG = G / kCodesPerChunk;             // chunks per group
-    constexpr int LPG = G / 8;                          // lanes that sum one group's activations
-    extern __shared__ float smem[];
-    float* sx = smem;                                   // [M][gps] sum of x over each group
-    float* red = smem + M * gps;                        // [kWaves-1][M][64]
+    constexpr int kThreads = W * 64;
+    // fewer blocks in flight when the accumulators need the registers
+    constexpr int D = VARIANT == 3 ? 8 : (VARIANT == 4 ? 6 : (M <= 2 ? kDepth : (M <= 4 ? 3 : 2)));
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int seg_k = seg_blocks * kBlockK;
+    half_t* xs = reinterpret_cast<half_t*>(smem);                               // [M][seg_k]
+    float* sxs = reinterpret_cast<float*>(smem + (size_t)M * seg_k * 2);         // [M][seg_k/32]
+    float* red = sxs + (size_t)M * (seg_k / kCodesPerChunk);                     // [rb_per_wg][W][M][16]
 
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int q = lane >> 4, r = lane & 15;
     const uint32_t fmask = frac_mask_vgpr();
-    const int split = blockIdx.x % splits;
-    const int64_t rb = blockIdx.x / splits;
-    const int gb = split * gps;
-    const int ge = min(gb + gps, ngroups);
-    const int64_t n = rb * kRowsPerBlock + lane;
-    const int64_t nn = n < N ? n : N - 1;
-    const int64_t nchunks = K / kCodesPerChunk;
+    const PackedLayout<G> lay(K);
+    const int nkb = (int)lay.nkb;
+    const int64_t nrb = row_blocks(N);
+    const int64_t rb0 = (int64_t)blockIdx.x * rb_per_wg;
+    const int n_rb = (int)min((int64_t)rb_per_wg, nrb - rb0);
+    const int nitems = n_rb * nkb;
+    // Addresses are a wavefront-uniform 64-bit base plus 32-bit offsets: one workgroup's run of row
+    // blocks is far smaller than 4 GiB.
+    const char* wg_codes = reinterpret_cast<const char*>(packed + lay.code_index(rb0, 0));
+    const char* wg_params = reinterpret_cast<const char*>(packed) + 4 * lay.param_index(rb0, 0);
+    const uint32_t rb_stride = (uint32_t)nkb * block_bytes(G);                  // bytes from one row block to the next
+    const uint32_t lane_code_off = lane * 16, lane_param_off = lay.param_slot(q, r) * 4;
+    // step a (row block slot, k block) cursor by W items; W <= nkb unless SMALLK
+    auto advance = [&](int& s_, int& k_) {
+        k_ += W;
+        if (SMALLK) {
+            while (k_ >= nkb) { k_ -= nkb; ++s_; }
+        } else if (k_ >= nkb) {
+            k_ -= nkb;
+            ++s_;
+        }
+    };
 
-    // group sums of the activations: LPG lanes x 8 halves per group
-    for (int i = t / LPG; i < (ge - gb) * M; i += kThreads / LPG) {
-        const int m = i / (ge - gb), gl = i % (ge - gb);
-        const half8_t v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + (int64_t)(gb + gl) * G + (t % LPG) * 8);
+    // ---- activations of the first segment: request them before the weights so that they are not
+    // queued behind a ring full of weight blocks (loads return in order)
+    const int pieces = seg_k / 8;                       // 16-byte pieces per row of X per segment
+    auto x_piece = [&](int idx, int sb) {
+        const int m = idx / pieces, pc = idx % pieces;
+        const int64_t k = (int64_t)sb * kBlockK + pc * 8;
+        half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (idx < M * pieces && k < K) v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+        return v;
+    };
+    // store one piece and, from every fourth lane, the sum of its 32-wide chunk
+    auto x_store = [&](int idx, const half8_t& v) {
+        const int m = idx / pieces, pc = idx % pieces;
         float s = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) s += (float)v[j];
+        s += __shfl_xor(s, 1);
+        s += __shfl_xor(s, 2);
+        if (idx < M * pieces) {
+            *reinterpret_cast<half8_t*>(&xs[m * seg_k + pc * 8]) = v;
+            if ((pc & 3) == 0) sxs[m * (seg_k / kCodesPerChunk) + (pc >> 2)] = s;
+        }
+    };
+    half8_t xearly[kEarlyX];
 #pragma unroll
-        for (int d = LPG / 2; d >= 1; d >>= 1) s += __shfl_xor(s, d);
-        if (t % LPG == 0) sx[m * gps + gl] = s;
-    }
-    __syncthreads();
+    for (int e = 0; e < kEarlyX; ++e) xearly[e] = x_piece(t + e * kThreads, 0);
+
+    // ---- ring of weight blocks
+    uint4 c[D];
+    uint32_t pw[D];
+    int fs = 0, fk = wave;                              // fetch cursor (row block slot, k block)
+    if (SMALLK) while (fk >= nkb) { fk -= nkb; ++fs; }
+    auto fetch = [&](uint4& cd, uint32_t& pwd) {        // past the end the last block is read again
+        const bool in = fs < n_rb;
+        const uint32_t s_ = in ? fs : n_rb - 1, k_ = in ? fk : nkb - 1;
+        const uint32_t row_off = __builtin_amdgcn_readfirstlane(s_ * rb_stride);
+        const char* pc = wg_codes + (row_off + k_ * kBlockCodeBytes);
+        const char* pp = wg_params + (row_off + k_ * (4 * lay.kParamWords));
+        cd = *reinterpret_cast<const uint4*>(pc + lane_code_off);
+        pwd = *reinterpret_cast<const uint32_t*>(pp + lane_param_off);
+        advance(fs, fk);
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d) fetch(c[d], pw[d]);
+
+    int i = wave;                                       // current item, as flat index and (row block slot, k block)
+    int slot = 0, kb = wave;
+    if (SMALLK) while (kb >= nkb) { kb -= nkb; ++slot; }
+
+    for (int j = t; j < n_rb * W * M * kBlockRows; j += kThreads) red[j] = 0.f;
 
     float acc[M];
 #pragma unroll
     for (int m = 0; m < M; ++m) acc[m] = 0.f;
 
-    const half2_t* __restrict__ X2 = reinterpret_cast<const half2_t*>(X);
-    const uint4* cbase = codes + (rb * nchunks) * kRowsPerBlock + lane;
-
-    uint4 cur[CPG];
-    int g = gb + wave;
-    if (g < ge) {
-#pragma unroll
-        for (int j = 0; j < CPG; ++j) cur[j] = cbase[((int64_t)g * CPG + j) * kRowsPerBlock];
-    }
-    for (; g < ge; g += kWaves) {
-        const float sc = (float)scales[(int64_t)g * N + nn];
-        const float bi = (float)bias[(int64_t)g * N + nn];
-        uint4 nxt[CPG];
-        const int gn = g + kWaves;
-        if (gn < ge) {
-#pragma unroll
-            for (int j = 0; j < CPG; ++j) nxt[j] = cbase[((int64_t)gn * CPG + j) * kRowsPerBlock];
-        }
-        float a[M];
-#pragma unroll
-        for (int m = 0; m < M; ++m) a[m] = 0.f;
-#pragma unroll
-        for (int j = 0; j < CPG; ++j) {
-            const uint32_t words[4] = {cur[j].x, cur[j].y, cur[j].z, cur[j].w};
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const half2_t p0 = w1_pair<0>(words[w], fmask), p1 = w1_pair<1>(words[w], fmask);
-                const half2_t p2 = w1_pair<2>(words[w], fmask), p3 = w1_pair<3>(words[w], fmask);
-                const int64_t kk = ((int64_t)g * G + j * 32 + w * 8) / 2;     // half2 index, wavefront-uniform
-#pragma unroll
-                for (int m = 0; m < M; ++m) {
-                    const half2_t* xr = X2 + (int64_t)m * (K / 2) + kk;
-                    a[m] = __builtin_amdgcn_fdot2(p0, xr[0], a[m], false);
-                    a[m] = __builtin_amdgcn_fdot2(p1, xr[1], a[m], false);
-                    a[m] = __builtin_amdgcn_fdot2(p2, xr[2], a[m], false);
-                    a[m] = __builtin_amdgcn_fdot2(p3, xr[3], a[m], false);
-                }
-            }
-        }
-#pragma unroll
-        for (int m = 0; m < M; ++m) acc[m] += sc * (a[m] - bi * sx[m * gps + (g - gb)]);
-        if (gn < ge) {
-#pragma unroll
-            for (int j = 0; j < CPG; ++j) cur[j] = nxt[j];
-        }
-    }
-
-    // fixed-order reduction over the 4 wavefronts
-    if (wave > 0) {
-#pragma unroll
-        for (int m = 0; m < M; ++m) red[((wave - 1) * M + m) * 64 + lane] = acc[m];
-    }
-    __syncthreads();
-    if (wave == 0) {
+    // add the four k-quarters of each row and park the wavefront's sums for row block `sl`
+    auto flush = [&](int sl) {
 #pragma unroll
         for (int m = 0; m < M; ++m) {
-            float s = acc[m];
+            float v = acc[m];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            if (lane < kBlockRows) red[((sl * W + wave) * M + m) * kBlockRows + lane] = v;
+            acc[m] = 0.f;
+        }
+    };
+
+    for (int sb = 0; sb < nkb; sb += seg_blocks) {
+        // stage the segment's activations and the sum of every 32-wide chunk
+        if (sb == 0) {
 #pragma unroll
-            for (int w = 0; w < kWaves - 1; ++w) s += red[(w * M + m) * 64 + lane];
-            if (splits == 1) {
-                if (n < N) Y[(int64_t)m * N + n] = (half_t)s;
+            for (int e = 0; e < kEarlyX; ++e) x_store(t + e * kThreads, xearly[e]);
+            for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0));
+        } else {
+            __syncthreads();                            // everyone is done with the previous segment's activations
+            fs = slot;                                  // refill the ring from the current item
+            fk = kb;
+#pragma unroll
+            for (int d = 0; d < D; ++d) fetch(c[d], pw[d]);
+            for (int idx = t; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, sb));
+        }
+        __syncthreads();
+
+        // one item: its codes and parameter word are in a ring slot
+        auto process = [&](const uint4& cd, const uint32_t pwd) {
+            const float sc = (float)param_scale(pwd);
+            const float bi = (float)param_bias(pwd);
+            const uint32_t words[4] = {cd.x, cd.y, cd.z, cd.w};
+            const int xoff = (kb - sb) * kBlockK + q * kCodesPerChunk;
+            float a[M][2];                              // two independent accumulation chains per row of X
+#pragma unroll
+            for (int m = 0; m < M; ++m) a[m][0] = a[m][1] = 0.f;
+            if (VARIANT == 1) {                         // timing experiment: stream only, no arithmetic
+                acc[0] += __builtin_bit_cast(float, words[0] ^ words[1] ^ words[2] ^ words[3]) * sc;
             } else {
-                partial[((int64_t)split * M + m) * (gridDim.x / splits * kRowsPerBlock) + n] = s;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const half2_t p0 = w1_pair<0>(words[w], fmask), p1 = w1_pair<1>(words[w], fmask);
+                    const half2_t p2 = w1_pair<2>(words[w], fmask), p3 = w1_pair<3>(words[w], fmask);
+#pragma unroll
+                    for (int m = 0; m < M; ++m) {
+                        half8_t xv;
+                        if (VARIANT == 2) xv = half8_t{1, 1, 1, 1, 1, 1, 1, 1};     // timing experiment: no LDS reads
+                        else xv = *reinterpret_cast<const half8_t*>(&xs[m * seg_k + xoff + 8 * w]);
+                        const half2_t x0 = {xv[0], xv[1]}, x1 = {xv[2], xv[3]}, x2 = {xv[4], xv[5]}, x3 = {xv[6], xv[7]};
+                        a[m][0] = __builtin_amdgcn_fdot2(p0, x0, a[m][0], false);
+                        a[m][1] = __builtin_amdgcn_fdot2(p1, x1, a[m][1], false);
+                        a[m][0] = __builtin_amdgcn_fdot2(p2, x2, a[m][0], false);
+                        a[m][1] = __builtin_amdgcn_fdot2(p3, x3, a[m][1], false);
+                    }
+                }
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+                    const float sxq = VARIANT == 2 ? 32.f : sxs[m * (seg_k / kCodesPerChunk) + (xoff >> 5)];
+                    acc[m] += sc * ((a[m][0] + a[m][1]) - bi * sxq);
+                }
+            }
+            i += W;
+            const int prev = slot;
+            advance(slot, kb);
+            if (slot != prev) flush(prev);              // the next item belongs to a later row block
+        };
+
+        // with one segment the loop runs over all items; otherwise (one row block) up to the segment's end
+        const int limit = seg_blocks >= nkb ? nitems : min(sb + seg_blocks, nkb);
+        // Entering the steady-state loop with nothing but the ring outstanding lets the compiler's
+        // wait-count bookkeeping keep D blocks in flight across the back edge (vmcnt(0), others free).
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        while (i + (D - 1) * W < limit) {               // full turns of the ring, refilled as it is consumed
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                process(c[d], pw[d]);
+                fetch(c[d], pw[d]);
             }
         }
+#pragma unroll
+        for (int d = 0; d < D; ++d)                     // last partial turn
+            if (i < limit) process(c[d], pw[d]);
+    }
+    if (slot < n_rb) flush(slot);                       // sums of a row block this wavefront left unfinished (several segments)
+    __syncthreads();
+    for (int idx = t; idx < n_rb * M * kBlockRows; idx += kThreads) {
+        const int sl = idx / (M * kBlockRows), m = (idx / kBlockRows) % M, rr = idx % kBlockRows;
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < W; ++w) s += red[((sl * W + w) * M + m) * kBlockRows + rr];
+        const int64_t n = (rb0 + sl) * kBlockRows + rr;
+        if (n < N) Y[(int64_t)m * N + n] = (half_t)s;
     }
 }
 
-// Y[m,n] = fp16( sum_s partial[s][m][n] ), s ascending.
-__global__ __launch_bounds__(256) void gemv_reduce_kernel(const float* __restrict__ partial, int splits, int64_t M,
-                                                          int64_t N, int64_t Npad, half_t* __restrict__ Y)
+template <int G, int M, int W>
+int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= M * N) return;
-    const int64_t m = i / N, n = i % N;
-    float s = 0.f;
-    for (int sp = 0; sp < splits; ++sp) s += partial[((int64_t)sp * M + m) * Npad + n];
-    Y[i] = (half_t)s;
-}
-
-template <int G, int M>
-int launch_one(const GemvPlan& p, const void* X, const void* codes, const void* scales, const void* bias, int64_t N,
-               int64_t K, void* Y, void* workspace, hipStream_t stream)
-{
-    const size_t smem = sizeof(float) * ((size_t)M * p.gps + (size_t)(kWaves - 1) * M * 64);
-    const dim3 grid((unsigned)(p.nrb * p.splits));
-    hipLaunchKernelGGL((gemv_kernel<G, M>), grid, dim3(kThreads), smem, stream, static_cast<const half_t*>(X),
-                       static_cast<const uint4*>(codes), static_cast<const half_t*>(scales),
-                       static_cast<const half_t*>(bias), N, K, p.ngroups, p.gps, p.splits, static_cast<half_t*>(Y),
-                       static_cast<float*>(workspace));
-    int rc = check_launch();
-    if (rc != E0M4_OK || p.splits == 1) return rc;
-    const int64_t total = (int64_t)M * N;
-    hipLaunchKernelGGL(gemv_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                       static_cast<const float*>(workspace), p.splits, (int64_t)M, N, p.nrb * kRowsPerBlock,
-                       static_cast<half_t*>(Y));
+    const half_t* x = static_cast<const half_t*>(X);
+    const uint4* c = static_cast<const uint4*>(packed);
+    half_t* y = static_cast<half_t*>(Y);
+    const dim3 grid((unsigned)p.grid), block(W * 64);
+    const int dbg = (G == 128 && M == 1 && W >= 8) ? knob("gemv_debug") : 0;     // timing experiments only
+    if (W == 4 && k_blocks(K) < W)                      // K < 512: the generic cursor
+        hipLaunchKernelGGL((gemv_kernel<G, M, 4, true>), grid, block, p.lds_bytes, stream, x, c, N, K, y, p.seg_blocks,
+                           p.rb_per_wg);
+    else if (dbg == 1)
+        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 1>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
+                           p.seg_blocks, p.rb_per_wg);
+    else if (dbg == 2)
+        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 2>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
+                           p.seg_blocks, p.rb_per_wg);
+    else if (dbg == 3)
+        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 3>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
+                           p.seg_blocks, p.rb_per_wg);
+    else if (dbg == 4)
+        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 4>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
+                           p.seg_blocks, p.rb_per_wg);
+    else if (M == 1 && knob("gemv_occ") == 8)           // experiment: cap registers for 8 wavefronts per SIMD
+        hipLaunchKernelGGL((gemv_kernel<G, 1, W, false, 0, 8>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
+                           p.seg_blocks, p.rb_per_wg);
+    else
+        hipLaunchKernelGGL((gemv_kernel<G, M, W>), grid, block, p.lds_bytes, stream, x, c, N, K, y, p.seg_blocks,
+                           p.rb_per_wg);
     return check_launch();
 }
 
+template <int G, int M>
+int launch_w(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+{
+    switch (p.waves) {
+        case 4: return launch_one<G, M, 4>(p, X, packed, N, K, Y, stream);
+        case 8: return launch_one<G, M, 8>(p, X, packed, N, K, Y, stream);
+        default: return launch_one<G, M, 16>(p, X, packed, N, K, Y, stream);
+    }
+}
+
 template <int G>
-int launch_m(const GemvPlan& p, int64_t M, const void* X, const void* codes, const void* scales, const void* bias,
-             int64_t N, int64_t K, void* Y, void* workspace, hipStream_t stream)
+int launch_m(const GemvPlan& p, int64_t M, const void* X, const void* packed, int64_t N, int64_t K, void* Y,
+             hipStream_t stream)
 {
     switch (M) {
-        case 1: return launch_one<G, 1>(p, X, codes, scales, bias, N, K, Y, workspace, stream);
-        case 2: return launch_one<G, 2>(p, X, codes, scales, bias, N, K, Y, workspace, stream);
-        case 3: return launch_one<G, 3>(p, X, codes, scales, bias, N, K, Y, workspace, stream);
-        case 4: return launch_one<G, 4>(p, X, codes, scales, bias, N, K, Y, workspace, stream);
-        case 5: return launch_one<G, 5>(p, X, codes, scales, bias, N, K, Y, workspace, stream);
-        case 6: return launch_one<G, 6>(p, X, codes, scales, bias, N, K, Y, workspace, stream);
-        case 7: return launch_one<G, 7>(p, X, codes, scales, bias, N, K, Y, workspace, stream);
-        case 8: return launch_one<G, 8>(p, X, codes, scales, bias, N, K, Y, workspace, stream);
+        case 1: return launch_w<G, 1>(p, X, packed, N, K, Y, stream);
+        case 2: return launch_w<G, 2>(p, X, packed, N, K, Y, stream);
+        case 3: return launch_w<G, 3>(p, X, packed, N, K, Y, stream);
+        case 4: return launch_w<G, 4>(p, X, packed, N, K, Y, stream);
+        case 5: return launch_w<G, 5>(p, X, packed, N, K, Y, stream);
+        case 6: return launch_w<G, 6>(p, X, packed, N, K, Y, stream);
+        case 7: return launch_w<G, 7>(p, X, packed, N, K, Y, stream);
+        case 8: return launch_w<G, 8>(p, X, packed, N, K, Y, stream);
         default: return E0M4_ERR_SHAPE;
     }
 }
 
 }  // namespace
 
-size_t gemv_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
+int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                hipStream_t stream)
 {
-    if (M <= 0 || N <= 0 || K <= 0) return 0;
-    const GemvPlan p = make_plan(N, K, group);
-    if (p.splits <= 1) return 0;
-    return sizeof(float) * (size_t)p.splits * (size_t)M * (size_t)(p.nrb * kRowsPerBlock);
-}
-
-int launch_gemv(const void* X, int64_t M, const void* codes, const void* scales, const void* bias, int64_t N,
-                int64_t K, int group, void* Y, void* workspace, hipStream_t stream)
-{
-    const GemvPlan p = make_plan(N, K, group);
+    const GemvPlan p = make_plan(M, N, K);
     switch (group) {
-        case 32: return launch_m<32>(p, M, X, codes, scales, bias, N, K, Y, workspace, stream);
-        case 64: return launch_m<64>(p, M, X, codes, scales, bias, N, K, Y, workspace, stream);
-        case 128: return launch_m<128>(p, M, X, codes, scales, bias, N, K, Y, workspace, stream);
+        case 32: return launch_m<32>(p, M, X, packed, N, K, Y, stream);
+        case 64: return launch_m<64>(p, M, X, packed, N, K, Y, stream);
+        case 128: return launch_m<128>(p, M, X, packed, N, K, Y, stream);
         default: return E0M4_ERR_GROUP;
     }
 }

@@ -17,20 +17,18 @@ int record_hip_error(hipError_t e);
 // Tuning knobs (0 = use the heuristic).
 int knob(const char* name);
 
-int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, void* scales, void* bias,
+int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed, void* scales, void* bias,
                     const void* scales_in, const void* bias_in, bool fit, hipStream_t stream);
-int launch_dequant(const void* codes, const void* scales, const void* bias, int64_t N, int64_t K, int group,
-                   void* W_out, hipStream_t stream);
-int launch_unpack(const void* codes, int64_t N, int64_t K, void* out, hipStream_t stream);
+int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, hipStream_t stream);
+int launch_unpack(const void* packed, int64_t N, int64_t K, int group, void* out, hipStream_t stream);
 
 // Small-M path (M <= kGemvMaxM).
 constexpr int kGemvMaxM = 8;
-size_t gemv_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
-int launch_gemv(const void* X, int64_t M, const void* codes, const void* scales, const void* bias, int64_t N,
-                int64_t K, int group, void* Y, void* workspace, hipStream_t stream);
+int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                hipStream_t stream);
 
 // MFMA path.
-int launch_gemm(const void* X, int64_t M, const void* codes, const void* scales, const void* bias, int64_t N,
-                int64_t K, int group, void* Y, hipStream_t stream);
+int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                hipStream_t stream);
 
 }  // namespace e0m4

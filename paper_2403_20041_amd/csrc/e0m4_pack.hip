@@ -18,8 +18,8 @@ constexpr float kSpan = 1.998046875f;   // kHi - kLo, exact
 constexpr float kMinScale = 6.103515625e-05f;   // smallest normal fp16
 constexpr float kMaxScale = 65504.0f;           // largest finite fp16
 
-constexpr int kTileK = 128;             // k extent of one workgroup tile (4 chunks)
 constexpr int kThreads = 256;
+constexpr int kTileRows = 64;           // one workgroup handles 4 row blocks x 1 k block
 
 __device__ inline uint16_t half_bits(half_t h) { return __builtin_bit_cast(uint16_t, h); }
 __device__ inline half_t bits_half(uint16_t b) { return __builtin_bit_cast(half_t, b); }
@@ -39,30 +39,34 @@ __device__ inline uint32_t encode_value(float w0, float sf, float bf)
     return c > 15u ? 15u : c;
 }
 
-// One workgroup = 64 rows x 128 k.  Thread t owns the 8-weight piece t%16 of
-// row (t/16 + 16*i), i = 0..3, so 16 consecutive lanes read 256 contiguous
-// bytes of one row and a group of G weights is G/8 adjacent lanes.
+// Thread t owns the 8-weight piece t%16 of row (t/16) of row block i, i = 0..3,
+// so 16 consecutive lanes read 256 contiguous bytes of one row and a group of G
+// weights is G/8 adjacent lanes.  The four finished blocks are staged in LDS and
+// written out in 16-byte pieces.
 template <int G, bool FIT>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __restrict__ W, int64_t N, int64_t K,
-                                                            uint32_t* __restrict__ codes,
+                                                            uint4* __restrict__ packed,
                                                             half_t* __restrict__ scales_out,
                                                             half_t* __restrict__ bias_out,
                                                             const half_t* __restrict__ scales_in,
                                                             const half_t* __restrict__ bias_in)
 {
-    __shared__ uint32_t tile[4 * kRowsPerBlock * 4];    // [chunk][row][word]
+    constexpr int BW = block_bytes(G) / 4;              // 32-bit words per block
+    constexpr int PPB = block_bytes(G) / 16;            // 16-byte pieces per block
+    __shared__ __attribute__((aligned(16))) uint32_t stage[4 * BW];
     const int t = threadIdx.x;
-    const int64_t rb = blockIdx.x;
-    const int64_t k0 = (int64_t)blockIdx.y * kTileK;
+    const int64_t rb64 = blockIdx.x;
+    const int64_t kb = blockIdx.y;
     const int piece = t & 15;
-    const int64_t k = k0 + piece * 8;
+    const int r = t >> 4;
+    const int64_t k = kb * kBlockK + piece * 8;
     const bool k_ok = k < K;
+    const int64_t ng = K / G;
     const int64_t g = k / G;
 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int r = (t >> 4) + 16 * i;
-        const int64_t n = rb * kRowsPerBlock + r;
+        const int64_t n = rb64 * kTileRows + 16 * i + r;
         const bool ok = k_ok && n < N;
         half8_t v8 = {0, 0, 0, 0, 0, 0, 0, 0};
         if (ok) v8 = *reinterpret_cast<const half8_t*>(W + n * K + k);
@@ -71,6 +75,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __rest
         for (int j = 0; j < 8; ++j) v[j] = (float)v8[j];
 
         float sf, bf;
+        half_t sh, bh;
         if (FIT) {
             float mn = 0.0f, mx = 0.0f;                 // the range always contains 0
 #pragma unroll
@@ -87,25 +92,27 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __rest
             float s = range / kSpan;
             s = s < kMinScale ? kMinScale : s;
             s = s > kMaxScale ? kMaxScale : s;
-            half_t sh = (half_t)s;
+            sh = (half_t)s;
             sf = (float)sh;                             // encode with the stored scale
             float q = mn / sf;
             float b = kLo - q;                          // image of zero in the binade
             b = b < kLo ? kLo : b;
             b = b > kHi ? kHi : b;
-            half_t bh = bits_half(half_bits((half_t)b) & 0xFFC0u);   // keep the four highest fraction bits
+            bh = bits_half(half_bits((half_t)b) & 0xFFC0u);   // keep the four highest fraction bits
             bf = (float)bh;
             if (ok && (piece % (G / 8)) == 0) {
-                scales_out[g * N + n] = sh;
-                bias_out[g * N + n] = bh;
+                scales_out[n * ng + g] = sh;
+                bias_out[n * ng + g] = bh;
             }
         } else {
-            sf = 1.0f;
-            bf = kLo;
+            sh = (half_t)1.0f;
+            bh = (half_t)kLo;
             if (ok) {
-                sf = (float)scales_in[g * N + n];
-                bf = (float)bias_in[g * N + n];
+                sh = scales_in[n * ng + g];
+                bh = bias_in[n * ng + g];
             }
+            sf = (float)sh;
+            bf = (float)bh;
         }
 
         uint32_t word = 0;
@@ -113,84 +120,95 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __rest
 #pragma unroll
             for (int j = 0; j < 8; ++j) word |= encode_value(v[j], sf, bf) << nibble_shift(j);
         }
-        tile[((piece >> 2) * kRowsPerBlock + r) * 4 + (piece & 3)] = word;
+        stage[i * BW + ((piece >> 2) * kBlockRows + r) * 4 + (piece & 3)] = word;
+        if ((piece % (G / 8)) == 0) {
+            const uint32_t pw = ok ? ((uint32_t)half_bits(sh) | ((uint32_t)half_bits(bh) << 16)) : 0u;
+            stage[i * BW + kBlockCodeBytes / 4 + (piece * 8 / G) * kBlockRows + r] = pw;
+        }
     }
     __syncthreads();
-    // thread t writes chunk t/64 of row t%64: each wavefront stores 1 KiB contiguous
-    const int q = t >> 6, r = t & 63;
-    const int64_t chunk = k0 / kCodesPerChunk + q;
-    if (chunk < K / kCodesPerChunk) {
-        const uint4 out = *reinterpret_cast<const uint4*>(&tile[(q * kRowsPerBlock + r) * 4]);
-        *reinterpret_cast<uint4*>(codes + ((rb * (K / kCodesPerChunk) + chunk) * kRowsPerBlock + r) * 4) = out;
+    const int64_t nrb = row_blocks(N);
+    const PackedLayout<G> lay(K);
+    constexpr int CP = PackedLayout<G>::kCodePieces;    // the first CP pieces of a staged block are codes
+    for (int pi = t; pi < 4 * PPB; pi += kThreads) {
+        const int i = pi / PPB, off = pi % PPB;
+        const int64_t rb = rb64 * 4 + i;
+        if (rb < nrb) {
+            const int64_t dst = off < CP ? lay.code_index(rb, kb) + off : lay.param_index(rb, kb) / 4 + (off - CP);
+            packed[dst] = *reinterpret_cast<const uint4*>(&stage[i * BW + off * 4]);
+        }
     }
 }
 
-// Workgroup = 64 rows x 128 k.  Wavefront w reads chunk w of the tile (1 KiB
-// contiguous, lane = row), dequantises it, and the tile goes through LDS so
-// that rows are written out in 256-byte runs.
+// Wavefront i of the workgroup reads block (4*rb64 + i, kb): codes and the
+// block's parameter words; the 64 x 128 tile goes through LDS so that rows are
+// written out in 256-byte runs.
 template <int G>
-__global__ __launch_bounds__(kThreads) void dequant_kernel(const uint32_t* __restrict__ codes,
-                                                           const half_t* __restrict__ scales,
-                                                           const half_t* __restrict__ bias, int64_t N, int64_t K,
+__global__ __launch_bounds__(kThreads) void dequant_kernel(const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                            half_t* __restrict__ W_out)
 {
-    constexpr int kStride = kTileK + 8;                 // halves; +16 bytes keeps ds_write_b128 conflict-free
-    __shared__ __attribute__((aligned(16))) half_t tile[kRowsPerBlock * kStride];
+    constexpr int kStride = kBlockK + 8;                // halves; +16 bytes keeps ds_write_b128 conflict-free
+    __shared__ __attribute__((aligned(16))) half_t tile[kTileRows * kStride];
     const int t = threadIdx.x;
-    const int64_t rb = blockIdx.x;
-    const int64_t k0 = (int64_t)blockIdx.y * kTileK;
+    const int64_t rb64 = blockIdx.x;
+    const int64_t kb = blockIdx.y;
+    const int64_t nrb = row_blocks(N);
+    const PackedLayout<G> lay(K);
     {
-        const int q = t >> 6, r = t & 63;
-        const int64_t chunk = k0 / kCodesPerChunk + q;
-        const int64_t n = rb * kRowsPerBlock + r;
-        if (chunk < K / kCodesPerChunk) {
-            const uint4 c = *reinterpret_cast<const uint4*>(codes + ((rb * (K / kCodesPerChunk) + chunk) * kRowsPerBlock + r) * 4);
-            const int64_t g = chunk * kCodesPerChunk / G;
-            const int64_t nn = n < N ? n : N - 1;
-            const float sf = (float)scales[g * N + nn];
-            const float bf = (float)bias[g * N + nn];
+        const int i = t >> 6, lane = t & 63;
+        const int q = lane >> 4, r = lane & 15;
+        const int64_t rb = rb64 * 4 + i;
+        if (rb < nrb) {
+            const uint4 c = packed[lay.code_index(rb, kb) + lane];
+            const uint32_t pw = reinterpret_cast<const uint32_t*>(packed)[lay.param_index(rb, kb) + lay.param_slot(q, r)];
+            const float sf = (float)param_scale(pw);
+            const float bf = (float)param_bias(pw);
             const uint32_t words[4] = {c.x, c.y, c.z, c.w};
             const uint32_t fmask = frac_mask_vgpr();
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const half2_t p[4] = {w1_pair<0>(words[w], fmask), w1_pair<1>(words[w], fmask), w1_pair<2>(words[w], fmask),
-                                      w1_pair<3>(words[w], fmask)};
+                const half2_t p[4] = {w1_pair<0>(words[w], fmask), w1_pair<1>(words[w], fmask),
+                                      w1_pair<2>(words[w], fmask), w1_pair<3>(words[w], fmask)};
                 half8_t o;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+                for (int j = 0; j < 4; ++j) {
                     // (w1 - bias) is exact and its product with the scale is exact in fp32: one rounding
-                    o[2 * i] = (half_t)(((float)p[i][0] - bf) * sf);
-                    o[2 * i + 1] = (half_t)(((float)p[i][1] - bf) * sf);
+                    o[2 * j] = (half_t)(((float)p[j][0] - bf) * sf);
+                    o[2 * j + 1] = (half_t)(((float)p[j][1] - bf) * sf);
                 }
-                *reinterpret_cast<half8_t*>(&tile[r * kStride + q * 32 + w * 8]) = o;
+                *reinterpret_cast<half8_t*>(&tile[(16 * i + r) * kStride + q * 32 + w * 8]) = o;
             }
         }
     }
     __syncthreads();
     const int piece = t & 15;
-    const int64_t k = k0 + piece * 8;
+    const int64_t k = kb * kBlockK + piece * 8;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int r = (t >> 4) + 16 * i;
-        const int64_t n = rb * kRowsPerBlock + r;
+        const int64_t n = rb64 * kTileRows + r;
         if (k < K && n < N)
             *reinterpret_cast<half8_t*>(W_out + n * K + k) = *reinterpret_cast<const half8_t*>(&tile[r * kStride + piece * 8]);
     }
 }
 
-__global__ __launch_bounds__(kThreads) void unpack_kernel(const uint32_t* __restrict__ codes, int64_t N, int64_t K,
+template <int G>
+__global__ __launch_bounds__(kThreads) void unpack_kernel(const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                           uint8_t* __restrict__ out)
 {
-    constexpr int kStride = kTileK + 16;                // bytes per row in LDS
-    __shared__ __attribute__((aligned(16))) uint8_t tile[kRowsPerBlock * kStride];
+    constexpr int kStride = kBlockK + 16;               // bytes per row in LDS
+    __shared__ __attribute__((aligned(16))) uint8_t tile[kTileRows * kStride];
     const int t = threadIdx.x;
-    const int64_t rb = blockIdx.x;
-    const int64_t k0 = (int64_t)blockIdx.y * kTileK;
+    const int64_t rb64 = blockIdx.x;
+    const int64_t kb = blockIdx.y;
+    const int64_t nrb = row_blocks(N);
+    const PackedLayout<G> lay(K);
     {
-        const int q = t >> 6, r = t & 63;
-        const int64_t chunk = k0 / kCodesPerChunk + q;
-        if (chunk < K / kCodesPerChunk) {
-            const uint4 c = *reinterpret_cast<const uint4*>(codes + ((rb * (K / kCodesPerChunk) + chunk) * kRowsPerBlock + r) * 4);
+        const int i = t >> 6, lane = t & 63;
+        const int q = lane >> 4, r = lane & 15;
+        const int64_t rb = rb64 * 4 + i;
+        if (rb < nrb) {
+            const uint4 c = packed[lay.code_index(rb, kb) + lane];
             const uint32_t words[4] = {c.x, c.y, c.z, c.w};
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
@@ -200,17 +218,17 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint32_t* __rest
                     lo |= ((words[w] >> nibble_shift(j)) & 15u) << (8 * j);
                     hi |= ((words[w] >> nibble_shift(j + 4)) & 15u) << (8 * j);
                 }
-                *reinterpret_cast<uint2*>(&tile[r * kStride + q * 32 + w * 8]) = make_uint2(lo, hi);
+                *reinterpret_cast<uint2*>(&tile[(16 * i + r) * kStride + q * 32 + w * 8]) = make_uint2(lo, hi);
             }
         }
     }
     __syncthreads();
     const int piece = t & 7;
-    const int64_t k = k0 + piece * 16;
+    const int64_t k = kb * kBlockK + piece * 16;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int r = (t >> 3) + 32 * i;
-        const int64_t n = rb * kRowsPerBlock + r;
+        const int64_t n = rb64 * kTileRows + r;
         if (k < K && n < N)
             *reinterpret_cast<uint4*>(out + n * K + k) = *reinterpret_cast<const uint4*>(&tile[r * kStride + piece * 16]);
     }
@@ -218,17 +236,17 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint32_t* __rest
 
 dim3 tile_grid(int64_t N, int64_t K)
 {
-    return dim3((unsigned)(padded_rows(N) / kRowsPerBlock), (unsigned)((K + kTileK - 1) / kTileK), 1);
+    return dim3((unsigned)((N + kTileRows - 1) / kTileRows), (unsigned)k_blocks(K), 1);
 }
 
 }  // namespace
 
-int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, void* scales, void* bias,
+int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed, void* scales, void* bias,
                     const void* scales_in, const void* bias_in, bool fit, hipStream_t stream)
 {
     const dim3 grid = tile_grid(N, K), block(kThreads);
     const half_t* w = static_cast<const half_t*>(W);
-    uint32_t* c = static_cast<uint32_t*>(codes);
+    uint4* c = static_cast<uint4*>(packed);
     half_t* so = static_cast<half_t*>(scales);
     half_t* bo = static_cast<half_t*>(bias);
     const half_t* si = static_cast<const half_t*>(scales_in);
@@ -248,27 +266,31 @@ int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* codes,
     return check_launch();
 }
 
-int launch_dequant(const void* codes, const void* scales, const void* bias, int64_t N, int64_t K, int group,
-                   void* W_out, hipStream_t stream)
+int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, hipStream_t stream)
 {
     const dim3 grid = tile_grid(N, K), block(kThreads);
-    const uint32_t* c = static_cast<const uint32_t*>(codes);
-    const half_t* s = static_cast<const half_t*>(scales);
-    const half_t* b = static_cast<const half_t*>(bias);
+    const uint4* c = static_cast<const uint4*>(packed);
     half_t* o = static_cast<half_t*>(W_out);
     switch (group) {
-        case 32: hipLaunchKernelGGL(dequant_kernel<32>, grid, block, 0, stream, c, s, b, N, K, o); break;
-        case 64: hipLaunchKernelGGL(dequant_kernel<64>, grid, block, 0, stream, c, s, b, N, K, o); break;
-        case 128: hipLaunchKernelGGL(dequant_kernel<128>, grid, block, 0, stream, c, s, b, N, K, o); break;
+        case 32: hipLaunchKernelGGL(dequant_kernel<32>, grid, block, 0, stream, c, N, K, o); break;
+        case 64: hipLaunchKernelGGL(dequant_kernel<64>, grid, block, 0, stream, c, N, K, o); break;
+        case 128: hipLaunchKernelGGL(dequant_kernel<128>, grid, block, 0, stream, c, N, K, o); break;
         default: return E0M4_ERR_GROUP;
     }
     return check_launch();
 }
 
-int launch_unpack(const void* codes, int64_t N, int64_t K, void* out, hipStream_t stream)
+int launch_unpack(const void* packed, int64_t N, int64_t K, int group, void* out, hipStream_t stream)
 {
-    hipLaunchKernelGGL(unpack_kernel, tile_grid(N, K), dim3(kThreads), 0, stream, static_cast<const uint32_t*>(codes), N,
-                       K, static_cast<uint8_t*>(out));
+    const dim3 grid = tile_grid(N, K), block(kThreads);
+    const uint4* c = static_cast<const uint4*>(packed);
+    uint8_t* o = static_cast<uint8_t*>(out);
+    switch (group) {
+        case 32: hipLaunchKernelGGL(unpack_kernel<32>, grid, block, 0, stream, c, N, K, o); break;
+        case 64: hipLaunchKernelGGL(unpack_kernel<64>, grid, block, 0, stream, c, N, K, o); break;
+        case 128: hipLaunchKernelGGL(unpack_kernel<128>, grid, block, 0, stream, c, N, K, o); break;
+        default: return E0M4_ERR_GROUP;
+    }
     return check_launch();
 }
 

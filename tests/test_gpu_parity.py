@@ -20,7 +20,7 @@ def e0m4():
     import paper_2403_20041_amd as pkg
 
     pkg.lib()                                   # raises if the HIP library is not built
-    for k in ("gemv_splits", "gemv_wgs_per_cu", "gemv_min_groups_per_wg", "gemm_variant"):
+    for k in ("gemv_waves", "gemm_variant"):
         pkg.e0m4_set_knob(k, 0)
     return pkg
 
@@ -48,9 +48,9 @@ def assert_quantize_exact(e0m4, oracle, W: np.ndarray, G: int):
     codes, scales, bias = gpu_quantize(e0m4, W, G)
     oc, os_, ob = oracle.quantize(W, G)
     torch.cuda.synchronize()
-    assert np.array_equal(bits(scales), os_.view(np.uint16).T), "scales differ"
-    assert np.array_equal(bits(bias), ob.view(np.uint16).T), "bias differ"
-    got_codes = bits(e0m4.e0m4_unpack_codes(codes, N, K))
+    assert np.array_equal(bits(scales), os_.view(np.uint16)), "scales differ"
+    assert np.array_equal(bits(bias), ob.view(np.uint16)), "bias differ"
+    got_codes = bits(e0m4.e0m4_unpack_codes(codes, N, K, G))
     assert np.array_equal(got_codes, oc), "codes differ"
     got_w = bits(e0m4.e0m4_dequant(codes, scales, bias, N, K, G))
     want_w = oracle.dequant(oc, os_, ob, G)
@@ -100,7 +100,7 @@ def test_quantize_value_distributions(e0m4, oracle, G):
     W[16:24] = np.abs(W[16:24])                               # one-signed groups
     W[24:32] = -np.abs(W[24:32])
     W[32:40] = (rng.standard_normal((8, K)) * 3e-6).astype(np.float16)      # subnormal weights, floor on the scale
-    W[40:48] = (rng.standard_normal((8, K)) * 2e4).astype(np.float16)       # large weights
+    W[40:48] = np.clip(rng.standard_normal((8, K)) * 2e4, -6e4, 6e4).astype(np.float16)   # large weights
     W[48, ::2] = np.float16(65504.0)
     W[48, 1::2] = np.float16(-65504.0)                        # scale saturates
     W[49:56] = (rng.standard_normal((7, K)) * 1e-4).astype(np.float16)
@@ -134,10 +134,10 @@ def test_encode_with_given_parameters(e0m4, oracle, G):
     z = rng.integers(0, 16, (N, K // G)).astype(np.uint16)
     bi = (0x4000 | (z << 6)).astype(np.uint16).view(np.float16)
     want = oracle.encode(W, sc, bi, G)
-    codes = e0m4.e0m4_encode(to_dev(W), to_dev(sc.T), to_dev(bi.T), G)
-    got = bits(e0m4.e0m4_unpack_codes(codes, N, K))
+    codes = e0m4.e0m4_encode(to_dev(W), to_dev(sc), to_dev(bi), G)
+    got = bits(e0m4.e0m4_unpack_codes(codes, N, K, G))
     assert np.array_equal(got, want)
-    got_w = bits(e0m4.e0m4_dequant(codes, to_dev(sc.T), to_dev(bi.T), N, K, G))
+    got_w = bits(e0m4.e0m4_dequant(codes, to_dev(sc), to_dev(bi), N, K, G))
     assert np.array_equal(got_w, oracle.dequant(want, sc, bi, G).view(np.uint16))
 
 
@@ -157,9 +157,9 @@ def test_dequant_all_codes_all_biases_many_scales(e0m4, oracle):
     ok_rows = np.isfinite(W).all(axis=1)
     W, scales, bias, codes_np = W[ok_rows], scales[ok_rows], bias[ok_rows], codes_np[ok_rows]
     N = W.shape[0]
-    sd, bd = to_dev(scales.view(np.float16).T), to_dev(bias.view(np.float16).T)
+    sd, bd = to_dev(scales.view(np.float16)), to_dev(bias.view(np.float16))
     codes = e0m4.e0m4_encode(to_dev(W), sd, bd, G)
-    assert np.array_equal(bits(e0m4.e0m4_unpack_codes(codes, N, K)), codes_np)
+    assert np.array_equal(bits(e0m4.e0m4_unpack_codes(codes, N, K, G)), codes_np)
     assert np.array_equal(bits(e0m4.e0m4_dequant(codes, sd, bd, N, K, G)), W.view(np.uint16))
 
 
@@ -188,14 +188,15 @@ def test_gemv_shapes_m1(e0m4, oracle, N, K, G):
     run_matmul_case(e0m4, oracle, 1, N, K, G, seed=N + K)
 
 
-@pytest.mark.parametrize("splits", [1, 2, 3, 7, 9])
-def test_gemv_forced_split_k(e0m4, oracle, splits):
-    e0m4.e0m4_set_knob("gemv_splits", splits)
+@pytest.mark.parametrize("waves", [4, 8, 16])
+def test_gemv_forced_waves_per_workgroup(e0m4, oracle, waves):
+    e0m4.e0m4_set_knob("gemv_waves", waves)
     try:
-        run_matmul_case(e0m4, oracle, 1, 300, 1152, 128, seed=50)      # 9 groups
+        run_matmul_case(e0m4, oracle, 1, 300, 1152, 128, seed=50)      # 9 k blocks
         run_matmul_case(e0m4, oracle, 3, 300, 1152, 64, seed=51)
+        run_matmul_case(e0m4, oracle, 8, 40, 16384, 128, seed=52)      # activations staged in several segments
     finally:
-        e0m4.e0m4_set_knob("gemv_splits", 0)
+        e0m4.e0m4_set_knob("gemv_waves", 0)
 
 
 # ------------------------------------------------------------------ matmul, MFMA path
@@ -260,15 +261,3 @@ def test_empty_problems(e0m4):
     W0 = torch.zeros((0, 128), dtype=torch.float16, device=DEV)
     e0m4.e0m4_quantize(W0, 128)
     torch.cuda.synchronize()
-
-
-def test_workspace_too_small_is_rejected(e0m4):
-    N, K, G = 4096, 4096, 128
-    need = e0m4.e0m4_workspace_bytes(1, N, K, G)
-    assert need > 0
-    codes, scales, bias = e0m4.alloc_packed(N, K, G, DEV)
-    X = torch.zeros((1, K), dtype=torch.float16, device=DEV)
-    ws = torch.empty(need - 16, dtype=torch.uint8, device=DEV)
-    with pytest.raises(e0m4.E0M4Error) as ei:
-        e0m4.e0m4_matmul(X, codes, scales, bias, N, K, G, workspace=ws)
-    assert ei.value.code == -5

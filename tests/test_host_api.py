@@ -33,23 +33,22 @@ def test_header_symbols_are_exported(L):
             "e0m4_strerror", "e0m4_last_hip_error", "e0m4_set_knob"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
-    assert L.e0m4_abi_version() == 1
+    assert L.e0m4_abi_version() == 2
 
 
 def test_size_functions(L):
-    assert L.e0m4_codes_bytes(4096, 4096) == 4096 * 4096 // 2
-    assert L.e0m4_codes_bytes(1, 32) == 64 * 16            # rows padded to a block of 64
-    assert L.e0m4_codes_bytes(65, 64) == 128 * 32
-    assert L.e0m4_codes_bytes(0, 4096) == 0
-    assert L.e0m4_codes_bytes(64, 48) == 0                 # K not a multiple of 32
+    blk = 1024 + 64                                         # 16 rows x 128 k of codes + 16 (scale, bias) pairs at G=128
+    assert L.e0m4_codes_bytes(4096, 4096, 128) == 256 * 32 * blk
+    assert L.e0m4_codes_bytes(1, 32, 32) == 1024 + 256      # rows padded to 16, k padded to 128, 4 sub-groups
+    assert L.e0m4_codes_bytes(17, 192, 64) == 2 * 2 * (1024 + 128)
+    assert L.e0m4_codes_bytes(0, 4096, 128) == 0
+    assert L.e0m4_codes_bytes(64, 48, 32) == 0              # K not a multiple of 32
+    assert L.e0m4_codes_bytes(64, 128, 100) == 0
     assert L.e0m4_params_elems(4096, 4096, 128) == 32 * 4096
     assert L.e0m4_params_elems(100, 256, 64) == 400
     assert L.e0m4_params_elems(100, 256, 48) == 0
-    # the M=1 path over a small N needs split-K scratch; the MFMA path needs none
-    assert L.e0m4_workspace_bytes(1, 4096, 4096, 128) > 0
-    assert L.e0m4_workspace_bytes(1, 4096, 4096, 128) % (4 * 4096) == 0
+    assert L.e0m4_workspace_bytes(1, 4096, 4096, 128) == 0  # partial sums never leave the chip
     assert L.e0m4_workspace_bytes(1024, 4096, 4096, 128) == 0
-    assert L.e0m4_workspace_bytes(1, 256000, 2048, 128) == 0
 
 
 def test_error_codes_before_any_launch(L):
@@ -68,14 +67,13 @@ def test_error_codes_before_any_launch(L):
     assert L.e0m4_encode(p, 64, 128, 128, null, p, p, null) == ERR_NULL
     assert L.e0m4_dequant(p, p, p, 64, 128, 128, null, null) == ERR_NULL
     assert L.e0m4_dequant(p, p, p, 64, 128, 128, odd, null) == ERR_ALIGN
-    assert L.e0m4_unpack_codes(p, 64, 130, p, null) == ERR_SHAPE
+    assert L.e0m4_unpack_codes(p, 64, 130, 32, p, null) == ERR_SHAPE
     assert L.e0m4_matmul(p, 1, p, p, p, 64, 100, 128, p, null, 0, null) == ERR_SHAPE
     assert L.e0m4_matmul(p, -1, p, p, p, 64, 128, 128, p, null, 0, null) == ERR_SHAPE
     assert L.e0m4_matmul(null, 1, p, p, p, 64, 128, 128, p, null, 0, null) == ERR_NULL
     assert L.e0m4_matmul(p, 1, p, p, p, 64, 128, 128, odd, null, 0, null) == ERR_ALIGN
-    need = L.e0m4_workspace_bytes(1, 4096, 4096, 128)
-    assert L.e0m4_matmul(p, 1, p, p, p, 4096, 4096, 128, p, null, 0, null) == ERR_NULL       # workspace required
-    assert L.e0m4_matmul(p, 1, p, p, p, 4096, 4096, 128, p, p, need - 1, null) == ERR_WS
+    assert L.e0m4_matmul(p, 1, null, p, p, 64, 128, 128, p, null, 0, null) == ERR_NULL
+    assert ERR_WS == -5
     # empty problems succeed without touching anything
     assert L.e0m4_quantize(null, 0, 128, 128, null, null, null, null) == 0
     assert L.e0m4_matmul(null, 0, null, null, null, 64, 128, 128, null, null, 0, null) == 0
@@ -83,7 +81,7 @@ def test_error_codes_before_any_launch(L):
     for code in (0, -1, -2, -3, -4, -5, -6, -99):
         assert L.e0m4_strerror(code)
     assert L.e0m4_set_knob(b"no_such_knob", 1) == ERR_SHAPE
-    assert L.e0m4_set_knob(b"gemv_splits", 0) == 0
+    assert L.e0m4_set_knob(b"gemv_waves", 0) == 0
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
