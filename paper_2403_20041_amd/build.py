@@ -13,7 +13,7 @@ INCLUDE = os.path.join(ROOT, "include")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libe0m4.so")
 
-SOURCES = ["e0m4_api.hip", "e0m4_pack.hip", "e0m4_gemv.hip", "e0m4_gemm.hip"]
+SOURCES = ["e0m4_api.hip", "e0m4_pack.hip", "e0m4_gemv.hip", "e0m4_gemm.hip", "e0m4_gemm_pipe.hip"]
 # the quantiser's fp32 steps must stay single IEEE operations
 EXTRA_FLAGS = {"e0m4_pack.hip": ["-ffp-contract=off"]}
 
@@ -47,7 +47,7 @@ def _compile(src: str, extra=()) -> str:
 
 def build_library(extra_flags=(), verbose: bool = True) -> str:
     os.makedirs(BUILD_DIR, exist_ok=True)
-    with concurrent.futures.ThreadPoolExecutor(max_workers=4) as ex:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra_flags), SOURCES))
     tmp = LIB_PATH + ".tmp.%d" % os.getpid()
     subprocess.check_call([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp])

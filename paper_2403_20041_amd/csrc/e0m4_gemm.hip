@@ -1,14 +1,21 @@
-// Prefill path of e0m4_matmul: Y[M,N] = X[M,K] * dequant(codes)^T on the matrix
+// Prefill path of e0m4_matmul: Y[M,N] = X[M,K] * dequant(packed)^T on the matrix
 // cores.  Paper: section "Operator and lagging optimizations" (matrix-matrix
 // product of the prefill stage, bound by compute) with the dequantisation of
 // section "E0M4 FP4 quantization" fused into the tile loader.
 //
-// A workgroup owns a BM x BN tile of Y.  Per BK slice the activations go
-// global -> registers -> LDS unchanged, the weight codes go global ->
-// registers -> (shift, mask|exponent, minus bias, times scale; packed fp16,
-// one rounding, bit-identical to e0m4_dequant) -> LDS, and the wavefronts run
-// v_mfma_f32_32x32x16_f16 on 16-byte K-contiguous fragments of both tiles with
-// fp32 accumulators.
+// A workgroup (4 wavefronts, 2 x 2) owns a BM x BN tile of Y and walks K in
+// slices of 64.  Per slice the activations go global -> registers -> LDS
+// unchanged; the weight codes go global -> registers -> (shift, mask-or with
+// the exponent, minus bias, times scale: packed fp16, one rounding, the same
+// bits e0m4_dequant produces) -> LDS.  Both tiles are K-contiguous, so every
+// MFMA operand is one 16-byte LDS read per lane; rows are 128 bytes and the
+// eight 16-byte pieces of a row are XOR-swizzled with the row number, which
+// keeps those reads (32 rows at one k offset) and the loader's writes free of
+// bank conflicts without padding.  Two LDS stages: the next slice is loaded
+// into registers while the current one feeds v_mfma_f32_32x32x16_f16, written
+// to the other stage, and one barrier per slice separates the two.
+// Workgroups are numbered so that each XCD (own L2) works on a contiguous run of
+// tiles that share weight rows.
 #include "e0m4_device.h"
 #include "e0m4_host.h"
 
@@ -16,128 +23,395 @@ namespace e0m4 {
 
 namespace {
 
-constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int BK = 64;
 constexpr int kThreads = 256;
-constexpr int kLdsStride = BK + 8;      // halves; 144-byte rows make the 16-byte fragment reads conflict-free
+constexpr int kRowBytes = BK * 2;                       // one tile row in LDS
+constexpr int kNumXcd = 8;
 
 __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2)
 {
-    return (w1 - bias2) * scale2;       // difference exact, product rounded once
+    return (w1 - bias2) * scale2;                       // difference exact, product rounded once
 }
 
-template <int G>
+// byte offset of 16-byte piece `piece` (0..7) of row `row` inside a swizzled tile
+__device__ inline int tile_off(int row, int piece) { return row * kRowBytes + ((piece ^ (row & 7)) << 4); }
+
+template <int G, int BM, int BN>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict__ X, int64_t M,
                                                         const uint4* __restrict__ packed, int64_t N, int64_t K,
-                                                        half_t* __restrict__ Y, int m_tiles)
+                                                        half_t* __restrict__ Y, int m_tiles, int n_tiles)
 {
-    __shared__ __attribute__((aligned(16))) half_t As[BM * kLdsStride];
-    __shared__ __attribute__((aligned(16))) half_t Bs[BN * kLdsStride];
+    constexpr int TM = BM / 64, TN = BN / 64;           // 32x32 MFMA blocks per wavefront along m and n
+    constexpr int PA = BM / 32, PB = BN / 128;          // loader passes
+    constexpr int A_BYTES = BM * kRowBytes, B_BYTES = BN * kRowBytes, STAGE = A_BYTES + B_BYTES;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    // XCD-aware numbering: workgroup w runs on XCD w % 8; give each XCD a contiguous run of tiles
+    const int total = m_tiles * n_tiles;
+    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    const int tile = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
+    if (tile >= total) return;
+    const int64_t m0 = (int64_t)(tile % m_tiles) * BM, n0 = (int64_t)(tile / m_tiles) * BN;
 
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = t >> 6;
     const uint32_t fmask = frac_mask_vgpr();
-    const int64_t mt = blockIdx.x % m_tiles;
-    const int64_t nt = blockIdx.x / m_tiles;
-    const int64_t m0 = mt * BM, n0 = nt * BN;
     const PackedLayout<G> lay(K);
     const int64_t nrb = row_blocks(N);
 
-    // A loader: 4 x 16 bytes per thread, 8 lanes cover one 128-byte row slice
+    // A loader: 8 lanes cover one 128-byte row slice; pass p handles rows 32p + t/8
     const int a_row = t >> 3, a_piece = t & 7;
-    // B loader: one 16-byte chunk per thread.  The 128 x 64 weight tile is the left or right half of
-    // 8 packed blocks; 32 consecutive threads read the 512 contiguous bytes of one half block.
+    // B loader: 32 consecutive threads read the 512 contiguous bytes of one half block (16 rows x 64 k)
     const int b_hb = t >> 5, b_q = (t >> 4) & 1, b_r = t & 15;
-    const int64_t rb = n0 / kBlockRows + b_hb;
-    const bool b_ok = rb < nrb;
 
-    uint4 a_reg[4];
-    uint4 b_reg;
-    uint32_t pw_reg;
+    uint4 a_reg[PA];
+    uint4 b_reg[PB];
+    uint32_t pw_reg[PB];
 
-    auto load_tile = [&](int64_t k0) {
+    // Per-thread base addresses, computed once; inside the K loop only uniform offsets are added.
+    // Rows outside M and row blocks outside N are clamped to the last valid one (their products
+    // are never stored), so the loads need no per-element predicate.
+    const int64_t a_m = min(m0 + a_row, M - 1);
+    const char* a_base = reinterpret_cast<const char*>(X + a_m * K + a_piece * 8);
+    uint32_t a_pass_off[PA];                            // byte offset of pass p's row from pass 0's row
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int64_t m = m0 + a_row + 32 * i;
-            const int64_t k = k0 + a_piece * 8;
-            a_reg[i] = make_uint4(0, 0, 0, 0);
-            if (m < M && k < K) a_reg[i] = *reinterpret_cast<const uint4*>(X + m * K + k);
+    for (int p = 0; p < PA; ++p)
+        a_pass_off[p] = (uint32_t)((min(m0 + a_row + 32 * p, M - 1) - a_m) * K * 2);
+    const int64_t rb_first = n0 / kBlockRows + b_hb;
+    const int64_t rb_c = min(rb_first, nrb - 1);
+    const char* b_code_base = reinterpret_cast<const char*>(packed + lay.code_index(rb_c, 0) + b_q * kBlockRows + b_r);
+    const char* b_param_base = reinterpret_cast<const char*>(packed) + 4 * (lay.param_index(rb_c, 0) + b_r) +
+                               (G == 32 ? b_q * 64 : 0);
+    uint32_t b_pass_off[PB];
+#pragma unroll
+    for (int p = 0; p < PB; ++p)
+        b_pass_off[p] = (uint32_t)((min(rb_first + 8 * p, nrb - 1) - rb_c) * lay.nkb * block_bytes(G));
+    const bool k_tail = (K % BK) != 0;                  // only then can a 16-byte piece of X lie beyond K
+
+    auto load_global = [&](int kt) {
+        const uint32_t k0 = (uint32_t)kt * BK;
+        const bool a_ok = !k_tail || (int64_t)k0 + a_piece * 8 < K;
+#pragma unroll
+        for (int p = 0; p < PA; ++p) {
+            a_reg[p] = make_uint4(0, 0, 0, 0);
+            if (a_ok) a_reg[p] = *reinterpret_cast<const uint4*>(a_base + (a_pass_off[p] + k0 * 2));
         }
-        b_reg = make_uint4(0, 0, 0, 0);
-        pw_reg = 0;                                      // scale 0, bias 0: dequantises to 0
-        if (b_ok) {
-            const int64_t kb = k0 / kBlockK;
-            const int q = (int)(k0 % kBlockK) / kCodesPerChunk + b_q;
-            b_reg = packed[lay.code_index(rb, kb) + q * kBlockRows + b_r];
-            pw_reg = reinterpret_cast<const uint32_t*>(packed)[lay.param_index(rb, kb) + lay.param_slot(q, b_r)];
+        // chunk q of k block kb starts (k0/32) * 256 bytes into the row block's codes; the parameter
+        // words of (kb, sub-group) follow the same order
+        const uint32_t code_off = (k0 / kCodesPerChunk) * (kBlockRows * 16);
+        const uint32_t param_off = (k0 / G) * (kBlockRows * 4);
+#pragma unroll
+        for (int p = 0; p < PB; ++p) {
+            b_reg[p] = *reinterpret_cast<const uint4*>(b_code_base + (b_pass_off[p] + code_off));
+            pw_reg[p] = *reinterpret_cast<const uint32_t*>(b_param_base + (b_pass_off[p] + param_off));
         }
     };
 
-    auto store_tile = [&]() {
+    auto store_lds = [&](unsigned char* stage) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<uint4*>(&As[(a_row + 32 * i) * kLdsStride + a_piece * 8]) = a_reg[i];
-        const half_t sc = param_scale(pw_reg), bi = param_bias(pw_reg);
-        const half2_t s2 = {sc, sc}, b2 = {bi, bi};
-        const uint32_t words[4] = {b_reg.x, b_reg.y, b_reg.z, b_reg.w};
-        half_t* dst = &Bs[(b_hb * kBlockRows + b_r) * kLdsStride + b_q * 32];
+        for (int p = 0; p < PA; ++p)
+            *reinterpret_cast<uint4*>(stage + tile_off(a_row + 32 * p, a_piece)) = a_reg[p];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            half2_t o[4];
-            o[0] = dequant_pair(w1_pair<0>(words[w], fmask), b2, s2);
-            o[1] = dequant_pair(w1_pair<1>(words[w], fmask), b2, s2);
-            o[2] = dequant_pair(w1_pair<2>(words[w], fmask), b2, s2);
-            o[3] = dequant_pair(w1_pair<3>(words[w], fmask), b2, s2);
-            *reinterpret_cast<uint4*>(dst + w * 8) = *reinterpret_cast<const uint4*>(o);
+        for (int p = 0; p < PB; ++p) {
+            const half_t sc = param_scale(pw_reg[p]), bi = param_bias(pw_reg[p]);
+            const half2_t s2 = {sc, sc}, b2 = {bi, bi};
+            const uint32_t words[4] = {b_reg[p].x, b_reg[p].y, b_reg[p].z, b_reg[p].w};
+            const int row = (b_hb + 8 * p) * kBlockRows + b_r;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                half2_t o[4];
+                o[0] = dequant_pair(w1_pair<0>(words[w], fmask), b2, s2);
+                o[1] = dequant_pair(w1_pair<1>(words[w], fmask), b2, s2);
+                o[2] = dequant_pair(w1_pair<2>(words[w], fmask), b2, s2);
+                o[3] = dequant_pair(w1_pair<3>(words[w], fmask), b2, s2);
+                *reinterpret_cast<uint4*>(stage + A_BYTES + tile_off(row, b_q * 4 + w)) = *reinterpret_cast<const uint4*>(o);
+            }
         }
     };
 
-    floatx16 acc[2][2];
+    floatx16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;     // wavefront tile origin inside the block tile
-    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    // wavefront tile origin inside the block tile, and this lane's fragment row / k piece
+    const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
+    const int frag_row = lane & 31, frag_piece = lane >> 5;
 
-    load_tile(0);
-    for (int64_t k0 = 0; k0 < K; k0 += BK) {
-        __syncthreads();
-        store_tile();
-        __syncthreads();
-        if (k0 + BK < K) load_tile(k0 + BK);
+    auto compute = [&](const unsigned char* stage) {
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            half8_t a[2], b[2];
+        for (int s = 0; s < BK / 16; ++s) {
+            half8_t a[TM], b[TN];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                a[i] = *reinterpret_cast<const half8_t*>(&As[(wm + 32 * i + frag_row) * kLdsStride + kk + frag_k]);
+            for (int i = 0; i < TM; ++i)
+                a[i] = *reinterpret_cast<const half8_t*>(stage + tile_off(wm + 32 * i + frag_row, 2 * s + frag_piece));
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                b[j] = *reinterpret_cast<const half8_t*>(&Bs[(wn + 32 * j + frag_row) * kLdsStride + kk + frag_k]);
+            for (int j = 0; j < TN; ++j)
+                b[j] = *reinterpret_cast<const half8_t*>(stage + A_BYTES + tile_off(wn + 32 * j + frag_row, 2 * s + frag_piece));
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
+    };
+
+    const int KT = (int)((K + BK - 1) / BK);
+    load_global(0);
+    store_lds(smem);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        unsigned char* cur = smem + (kt & 1) * STAGE;
+        unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+        if (kt + 1 < KT) load_global(kt + 1);
+        compute(cur);
+        if (kt + 1 < KT) store_lds(nxt);
+        __syncthreads();
     }
 
-    // accumulator layout of the 32x32 block: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
+    // accumulator layout of a 32x32 block: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
+    // (tile-local offsets fit 32 bits: at most 256 rows of N elements)
+    half_t* __restrict__ Yt = Y + m0 * N + n0;
+    const uint32_t n32 = (uint32_t)N;
+    const int rows_left = (int)min((int64_t)BM, M - m0), cols_left = (int)min((int64_t)BN, N - n0);
+    const int row0 = wm + 4 * (lane >> 5), col0 = wn + (lane & 31);
+    const uint32_t off0 = (uint32_t)row0 * n32 + (uint32_t)col0;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < TN; ++j) {
+        if (col0 + 32 * j < cols_left) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t n = n0 + wn + 32 * j + (lane & 31);
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t m = m0 + wm + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (m < M && n < N) Y[m * N + n] = (half_t)acc[i][j][r];
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 32 * i + 8 * (r >> 2) + (r & 3);       // compile-time row step
+                    if (row0 + dr < rows_left) Yt[off0 + (uint32_t)dr * n32 + 32 * j] = (half_t)acc[i][j][r];
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Variant with the weights kept out of LDS.  Only the activations are staged (swizzled, two
+// stages).  A wavefront reads the codes of its own 32-row x 64-k operand blocks straight from the
+// packed buffer: lane (n = l%32, h = l/32) takes the 16-byte chunk of row n that holds
+// k = 32h .. 32h+31 of the slice, so word s of every lane is exactly the lane's 8 K-values of MFMA
+// number s, whose K set is {8s..8s+7} u {32+8s..32+8s+7}; the activation fragment of the same MFMA
+// is then piece 4h+s of the row.  Each word is dequantised in registers (16 VALU operations) right
+// before it is consumed, in the shadow of the previous MFMAs.  LDS traffic drops to the activations
+// alone, at the price of dequantising each weight once per pair of wavefronts that share it.
+template <int G, int BM, int BN>
+__global__ __launch_bounds__(kThreads) void gemm_direct_kernel(const half_t* __restrict__ X, int64_t M,
+                                                               const uint4* __restrict__ packed, int64_t N, int64_t K,
+                                                               half_t* __restrict__ Y, int m_tiles, int n_tiles)
+{
+    constexpr int TM = BM / 64, TN = BN / 64;
+    constexpr int PA = BM / 32;
+    constexpr int A_BYTES = BM * kRowBytes;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int total = m_tiles * n_tiles;
+    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    const int tile = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
+    if (tile >= total) return;
+    const int64_t m0 = (int64_t)(tile % m_tiles) * BM, n0 = (int64_t)(tile / m_tiles) * BN;
+
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = t >> 6;
+    const uint32_t fmask = frac_mask_vgpr();
+    const PackedLayout<G> lay(K);
+    const int64_t nrb = row_blocks(N);
+    const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
+
+    // A loader (as in gemm_kernel)
+    const int a_row = t >> 3, a_piece = t & 7;
+    const int64_t a_m = min(m0 + a_row, M - 1);
+    const char* a_base = reinterpret_cast<const char*>(X + a_m * K + a_piece * 8);
+    uint32_t a_pass_off[PA];
+#pragma unroll
+    for (int p = 0; p < PA; ++p)
+        a_pass_off[p] = (uint32_t)((min(m0 + a_row + 32 * p, M - 1) - a_m) * K * 2);
+    const bool k_tail = (K % BK) != 0;
+
+    // B loader: operand block j of this wavefront covers rows n0 + wn + 32j .. +31 = two row blocks
+    const int b_h = lane >> 5, b_r = lane & 15;
+    const int64_t rb_first = (n0 + wn) / kBlockRows + ((lane >> 4) & 1);
+    const int64_t rb_c = min(rb_first, nrb - 1);
+    const char* b_code_base = reinterpret_cast<const char*>(packed + lay.code_index(rb_c, 0) + b_h * kBlockRows + b_r);
+    const char* b_param_base = reinterpret_cast<const char*>(packed) + 4 * (lay.param_index(rb_c, 0) + b_r) +
+                               (G == 32 ? b_h * 64 : 0);
+    uint32_t b_blk_off[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+        b_blk_off[j] = (uint32_t)((min(rb_first + 2 * j, nrb - 1) - rb_c) * lay.nkb * block_bytes(G));
+
+    uint4 a_reg[PA];
+    uint4 b_cur[TN], b_nxt[TN];
+    uint32_t pw_cur[TN], pw_nxt[TN];
+
+    auto load_a = [&](int kt) {
+        const uint32_t k0 = (uint32_t)kt * BK;
+        const bool a_ok = !k_tail || (int64_t)k0 + a_piece * 8 < K;
+#pragma unroll
+        for (int p = 0; p < PA; ++p) {
+            a_reg[p] = make_uint4(0, 0, 0, 0);
+            if (a_ok) a_reg[p] = *reinterpret_cast<const uint4*>(a_base + (a_pass_off[p] + k0 * 2));
+        }
+    };
+    auto load_b = [&](int kt, uint4 (&b)[TN], uint32_t (&pw)[TN]) {
+        const uint32_t k0 = (uint32_t)kt * BK;
+        const uint32_t code_off = (k0 / kCodesPerChunk) * (kBlockRows * 16);
+        const uint32_t param_off = (k0 / G) * (kBlockRows * 4);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            b[j] = *reinterpret_cast<const uint4*>(b_code_base + (b_blk_off[j] + code_off));
+            pw[j] = *reinterpret_cast<const uint32_t*>(b_param_base + (b_blk_off[j] + param_off));
+        }
+    };
+    auto store_a = [&](unsigned char* stage) {
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            *reinterpret_cast<uint4*>(stage + tile_off(a_row + 32 * p, a_piece)) = a_reg[p];
+    };
+    auto dequant_word = [&](uint32_t word, uint32_t pw) {
+        const half_t sc = param_scale(pw), bi = param_bias(pw);
+        const half2_t s2 = {sc, sc}, b2 = {bi, bi};
+        half2_t o[4];
+        o[0] = dequant_pair(w1_pair<0>(word, fmask), b2, s2);
+        o[1] = dequant_pair(w1_pair<1>(word, fmask), b2, s2);
+        o[2] = dequant_pair(w1_pair<2>(word, fmask), b2, s2);
+        o[3] = dequant_pair(w1_pair<3>(word, fmask), b2, s2);
+        return *reinterpret_cast<const half8_t*>(o);
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int frag_row = lane & 31;
+    auto compute = [&](const unsigned char* stage) {
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            half8_t a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                a[i] = *reinterpret_cast<const half8_t*>(stage + tile_off(wm + 32 * i + frag_row, 4 * b_h + s));
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const uint32_t word = s == 0 ? b_cur[j].x : (s == 1 ? b_cur[j].y : (s == 2 ? b_cur[j].z : b_cur[j].w));
+                b[j] = dequant_word(word, pw_cur[j]);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    const int KT = (int)((K + BK - 1) / BK);
+    load_a(0);
+    load_b(0, b_cur, pw_cur);
+    store_a(smem);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        unsigned char* cur = smem + (kt & 1) * A_BYTES;
+        unsigned char* nxt = smem + ((kt + 1) & 1) * A_BYTES;
+        const bool more = kt + 1 < KT;
+        if (more) {
+            load_a(kt + 1);
+            load_b(kt + 1, b_nxt, pw_nxt);
+        }
+        compute(cur);
+        if (more) {
+            store_a(nxt);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                b_cur[j] = b_nxt[j];
+                pw_cur[j] = pw_nxt[j];
             }
         }
+        __syncthreads();
+    }
+
+    half_t* __restrict__ Yt = Y + m0 * N + n0;
+    const uint32_t n32 = (uint32_t)N;
+    const int rows_left = (int)min((int64_t)BM, M - m0), cols_left = (int)min((int64_t)BN, N - n0);
+    const int row0 = wm + 4 * (lane >> 5), col0 = wn + (lane & 31);
+    const uint32_t off0 = (uint32_t)row0 * n32 + (uint32_t)col0;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        if (col0 + 32 * j < cols_left) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
+                    if (row0 + dr < rows_left) Yt[off0 + (uint32_t)dr * n32 + 32 * j] = (half_t)acc[i][j][r];
+                }
+        }
+    }
+}
+
+template <int G, int BM, int BN>
+int launch_direct(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
+{
+    const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
+    if (m_tiles * n_tiles > 0x3fffffffLL) return E0M4_ERR_SHAPE;
+    const int total = (int)(m_tiles * n_tiles);
+    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    constexpr size_t lds = 2 * (size_t)BM * kRowBytes;
+    hipLaunchKernelGGL((gemm_direct_kernel<G, BM, BN>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(kThreads), lds,
+                       stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles);
+    return check_launch();
+}
+
+template <int G, int BM, int BN>
+int launch_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
+{
+    const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
+    if (m_tiles * n_tiles > 0x3fffffffLL) return E0M4_ERR_SHAPE;
+    const int total = (int)(m_tiles * n_tiles);
+    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    constexpr size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
+    static bool attr_set = false;                       // LDS above the default 64 KiB limit must be requested once
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<G, BM, BN>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return record_hip_error(e);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemm_kernel<G, BM, BN>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(kThreads), lds, stream, x,
+                       M, c, N, K, y, (int)m_tiles, (int)n_tiles);
+    return check_launch();
+}
+
+template <int G>
+int launch_g(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
+{
+    // Tile choice: the largest tile that still gives every compute unit work.
+    int variant = knob("gemm_variant");
+    if (variant <= 0) {
+        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+        const int64_t t2x1 = ((M + 255) / 256) * ((N + 127) / 128);
+        variant = t256 >= 256 ? 1 : (t2x1 >= 256 ? 2 : 3);
+    }
+    switch (variant) {
+        case 1: return launch_tile<G, 256, 256>(x, M, c, N, K, y, stream);
+        case 2: return launch_tile<G, 256, 128>(x, M, c, N, K, y, stream);
+        case 4: return launch_direct<G, 256, 256>(x, M, c, N, K, y, stream);
+        case 5: return launch_direct<G, 256, 128>(x, M, c, N, K, y, stream);
+        case 6: return launch_direct<G, 128, 128>(x, M, c, N, K, y, stream);
+        default: return launch_tile<G, 128, 128>(x, M, c, N, K, y, stream);
+    }
 }
 
 }  // namespace
@@ -145,19 +419,18 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                 hipStream_t stream)
 {
-    const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
-    if (m_tiles * n_tiles > 0x7fffffffLL) return E0M4_ERR_SHAPE;
-    const dim3 grid((unsigned)(m_tiles * n_tiles)), block(kThreads);
     const half_t* x = static_cast<const half_t*>(X);
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
+    const int v = knob("gemm_variant");
+    if ((v == 7 || v == 8) && gemm_pipe_supported(K))
+        return launch_gemm_pipe(X, M, packed, N, K, group, v == 8 ? 8 : 4, Y, stream);
     switch (group) {
-        case 32: hipLaunchKernelGGL(gemm_kernel<32>, grid, block, 0, stream, x, M, c, N, K, y, (int)m_tiles); break;
-        case 64: hipLaunchKernelGGL(gemm_kernel<64>, grid, block, 0, stream, x, M, c, N, K, y, (int)m_tiles); break;
-        case 128: hipLaunchKernelGGL(gemm_kernel<128>, grid, block, 0, stream, x, M, c, N, K, y, (int)m_tiles); break;
+        case 32: return launch_g<32>(x, M, c, N, K, y, stream);
+        case 64: return launch_g<64>(x, M, c, N, K, y, stream);
+        case 128: return launch_g<128>(x, M, c, N, K, y, stream);
         default: return E0M4_ERR_GROUP;
     }
-    return check_launch();
 }
 
 }  // namespace e0m4

@@ -1,0 +1,298 @@
+// Software-pipelined 256 x 256 tile of the prefill GEMM (paper: section "Operator and lagging
+// optimizations", matrix-matrix product; dequantisation of section "E0M4 FP4 quantization" fused
+// in registers).
+//
+// One wavefront per SIMD owns a 128 x 128 quarter of the tile (256 fp32 accumulator registers per
+// lane), so nothing but its own instruction stream can hide latency.  The stream is therefore laid
+// out by hand, per K slice of 64 (= 4 MFMA sub-steps of 16):
+//   - activations: global -> registers (issued two slices ahead) -> LDS ring of three stages ->
+//     16-byte fragments, read one sub-step ahead of their use;
+//   - weights: never touch LDS.  Lane (n = l%32, h = l/32) reads the 16-byte chunk of row n with
+//     k = 32h..32h+31 of the slice (two slices ahead), and word s of that chunk is dequantised
+//     (shift, mask-or exponent, minus bias, times scale; packed fp16, bit-identical to
+//     e0m4_dequant) one sub-step ahead of MFMA number s, whose K set is {8s..8s+7} u
+//     {32+8s..32+8s+7}; the activation fragment of the same MFMA is piece 4h+s of the row.
+//   - one barrier per slice, placed after sub-step 1, separates the LDS write of slice kt+1 from
+//     the fragment reads that start in sub-step 3.
+// The LDS tile is 128-byte rows whose eight 16-byte pieces are XOR-swizzled with the row number.
+#include "e0m4_device.h"
+#include "e0m4_host.h"
+
+namespace e0m4 {
+
+namespace {
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kRowBytes = BK * 2;
+constexpr int kStageBytes = BM * kRowBytes;             // 32 KiB
+constexpr int kStages = 3;
+constexpr int kNumXcd = 8;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// Buffer resource over [p, p + 2 GiB): raw (stride 0), 32-bit data format word of gfx9-class targets.
+// p must be wavefront-uniform; passing its halves through readfirstlane pins the resource to scalar
+// registers (otherwise every buffer load is wrapped in a per-lane "waterfall" loop).
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p)
+{
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    void* q = reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
+    return __builtin_amdgcn_make_buffer_rsrc(q, 0, 0x7fffffff, 0x00020000);
+}
+
+__device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2)
+{
+    return (w1 - bias2) * scale2;                       // difference exact, product rounded once
+}
+
+// WGM x WGN wavefronts share the tile: 2 x 2 (one per SIMD, 128 x 128 each) or 2 x 4 (two per SIMD,
+// 128 x 64 each, which doubles the instruction issue capacity and lets one wavefront's waits hide
+// behind the other's MFMAs, for twice the activation fragment traffic).
+template <int G, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
+                                                             const uint4* __restrict__ packed, int64_t N, int64_t K,
+                                                             half_t* __restrict__ Y, int m_tiles, int n_tiles)
+{
+    constexpr int kThreads = 64 * WGM * WGN;
+    constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);      // 32x32 MFMA blocks per wavefront
+    constexpr int RP = kThreads / 8;                    // rows covered by one activation loader pass
+    constexpr int PA = BM / RP;                         // activation loader passes
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int total = m_tiles * n_tiles;
+    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    const int tile = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
+    if (tile >= total) return;
+    // (the quotient and remainder are computed on the vector unit; move them to scalar registers)
+    const int64_t m0 = (int64_t)__builtin_amdgcn_readfirstlane(tile % m_tiles) * BM;
+    const int64_t n0 = (int64_t)__builtin_amdgcn_readfirstlane(tile / m_tiles) * BN;
+
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = t >> 6;
+    const uint32_t fmask = frac_mask_vgpr();
+    const PackedLayout<G> lay(K);
+    const int64_t nrb = row_blocks(N);
+    const int wm = (wave / WGN) * (BM / WGM), wn = (wave % WGN) * (BN / WGN);
+    const int KT = (int)(K / BK);                       // K % 64 == 0 is required by the launcher
+
+    // ---- activation loader: 8 lanes cover one 128-byte row slice; pass p handles row RP*p + t/8.
+    // Rows beyond M are clamped (their products are never stored).
+    // Global reads are buffer loads: a wavefront-uniform resource (base of this tile's data, in
+    // scalar registers), a scalar offset that advances with the K slice, and a 32-bit per-lane
+    // offset that never changes -- no vector address arithmetic inside the K loop.
+    const int a_row = t >> 3, a_piece = t & 7;
+    const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(X + m0 * K);
+    uint32_t a_pass_off[PA];
+#pragma unroll
+    for (int p = 0; p < PA; ++p)
+        a_pass_off[p] = (uint32_t)((min((int64_t)(a_row + RP * p), M - 1 - m0) * K + a_piece * 8) * 2);
+    // LDS write position of this thread's piece (pass p adds RP rows)
+    const uint32_t a_lds_off = (uint32_t)(a_row * kRowBytes + ((a_piece ^ (a_row & 7)) << 4));
+
+    // ---- weight loader: operand block j of this wavefront covers rows n0 + wn + 32j .. +31
+    const int b_h = lane >> 5, b_r = lane & 15;
+    const int64_t rb_tile = n0 / kBlockRows;            // first row block of the tile (exists: n0 < N)
+    const __amdgpu_buffer_rsrc_t b_code_rsrc = make_rsrc(packed + lay.code_index(rb_tile, 0));
+    const __amdgpu_buffer_rsrc_t b_param_rsrc =
+        make_rsrc(reinterpret_cast<const uint32_t*>(packed) + lay.param_index(rb_tile, 0));
+    const uint32_t rb_stride = (uint32_t)lay.nkb * block_bytes(G);
+    uint32_t b_code_off[TN], b_param_off[TN];           // row blocks beyond N are clamped (never stored)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int64_t rb = min(rb_tile + wn / kBlockRows + 2 * j + ((lane >> 4) & 1), nrb - 1) - rb_tile;
+        b_code_off[j] = (uint32_t)rb * rb_stride + (uint32_t)(b_h * kBlockRows + b_r) * 16;
+        b_param_off[j] = (uint32_t)rb * rb_stride + (uint32_t)b_r * 4 + (G == 32 ? b_h * 64 : 0);
+    }
+
+    // ---- fragment read position: row wm + 32i + l%32 (32i rows = immediate 4096 i), piece 4h + s
+    uint32_t frag_off[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+        frag_off[s] = (uint32_t)((wm + (lane & 31)) * kRowBytes + (((4 * b_h + s) ^ (lane & 7)) << 4));
+
+    u32x4 a_reg[PA];
+    u32x4 bset[2][TN];
+    uint32_t pwset[2][TN];
+    half8_t fa[2][TM], fb[2][TN];
+
+    auto load_a = [&](int kt) {
+        const uint32_t k0 = (uint32_t)min(kt, KT - 1) * BK;
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            a_reg[p] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_pass_off[p], (int)(k0 * 2), 0);
+    };
+    auto load_b = [&](int kt, int set) {
+        const uint32_t k0 = (uint32_t)min(kt, KT - 1) * BK;
+        // chunk (k0/32) of the row block's codes starts (k0/32)*256 bytes in; the parameter words of
+        // group k0/G start (k0/G)*64 bytes into the row block's parameters
+        const int code_soff = (int)((k0 / kCodesPerChunk) * (kBlockRows * 16));
+        const int param_soff = (int)((k0 / G) * (kBlockRows * 4));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            bset[set][j] = __builtin_amdgcn_raw_buffer_load_b128(b_code_rsrc, (int)b_code_off[j], code_soff, 0);
+            pwset[set][j] = __builtin_amdgcn_raw_buffer_load_b32(b_param_rsrc, (int)b_param_off[j], param_soff, 0);
+        }
+    };
+    auto store_a = [&](uint32_t stage_off) {
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            *reinterpret_cast<u32x4*>(smem + stage_off + a_lds_off + p * RP * kRowBytes) = a_reg[p];
+    };
+    auto read_frags = [&](uint32_t stage_off, int s, half8_t (&dst)[TM]) {
+        const unsigned char* base = smem + stage_off + frag_off[s];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) dst[i] = *reinterpret_cast<const half8_t*>(base + i * 32 * kRowBytes);
+    };
+    auto dequant_frags = [&](int set, int s, half8_t (&dst)[TN]) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const uint32_t word = bset[set][j][s];
+            const half_t sc = param_scale(pwset[set][j]), bi = param_bias(pwset[set][j]);
+            const half2_t s2 = {sc, sc}, b2 = {bi, bi};
+            half2_t o[4];
+            o[0] = dequant_pair(w1_pair<0>(word, fmask), b2, s2);
+            o[1] = dequant_pair(w1_pair<1>(word, fmask), b2, s2);
+            o[2] = dequant_pair(w1_pair<2>(word, fmask), b2, s2);
+            o[3] = dequant_pair(w1_pair<3>(word, fmask), b2, s2);
+            dst[j] = *reinterpret_cast<const half8_t*>(o);
+        }
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    auto mfma_block = [&](const half8_t (&a)[TM], const half8_t (&b)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+
+    // One K slice.  On entry: stage `cur` holds slice kt; fa[0], fb[0] hold its sub-step 0 operands;
+    // bset[set] holds its codes; bset[set^1] and a_reg are in flight for slice kt+1.
+    auto step = [&](int kt, int set, uint32_t cur, uint32_t nxt) {
+        // sub-step 0: operands of sub-step 1; publish slice kt+1's activations and, the staging
+        // registers being free again, request those of slice kt+2 at once
+        read_frags(cur, 1, fa[1]);
+        dequant_frags(set, 1, fb[1]);
+        store_a(nxt);
+        load_a(kt + 2);
+        mfma_block(fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        // sub-step 1: operands of sub-step 2
+        read_frags(cur, 2, fa[0]);
+        dequant_frags(set, 2, fb[0]);
+        mfma_block(fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();                                // slice kt+1 is complete in stage `nxt`
+        __builtin_amdgcn_sched_barrier(0);
+        // sub-step 2: operands of sub-step 3 (last use of this slice's codes, so the codes of
+        // slice kt+2 can be requested into the same registers)
+        read_frags(cur, 3, fa[1]);
+        dequant_frags(set, 3, fb[1]);
+        load_b(kt + 2, set);
+        mfma_block(fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        // sub-step 3: operands of the next slice's sub-step 0
+        read_frags(nxt, 0, fa[0]);
+        dequant_frags(set ^ 1, 0, fb[0]);
+        mfma_block(fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // ---- prologue
+    load_a(0);
+    load_b(0, 0);
+    load_b(1, 1);
+    store_a(0);
+    load_a(1);
+    __syncthreads();
+    read_frags(0, 0, fa[0]);
+    dequant_frags(0, 0, fb[0]);
+
+    uint32_t s0 = 0, s1 = kStageBytes, s2 = 2 * kStageBytes;      // ring: current, next, the one after
+    for (int kt = 0; kt < KT; kt += 2) {                // KT is even: K is a multiple of 128
+        step(kt, 0, s0, s1);
+        step(kt + 1, 1, s1, s2);
+        const uint32_t tmp = s0;                        // advance the ring by two slices
+        s0 = s2;
+        s2 = s1;
+        s1 = tmp;
+    }
+
+    // accumulator layout of a 32x32 block: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
+    half_t* __restrict__ Yt = Y + m0 * N + n0;
+    const uint32_t n32 = (uint32_t)N;
+    const int rows_left = (int)min((int64_t)BM, M - m0), cols_left = (int)min((int64_t)BN, N - n0);
+    const int row0 = wm + 4 * (lane >> 5), col0 = wn + (lane & 31);
+    const uint32_t off0 = (uint32_t)row0 * n32 + (uint32_t)col0;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        if (col0 + 32 * j < cols_left) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
+                    if (row0 + dr < rows_left) Yt[off0 + (uint32_t)dr * n32 + 32 * j] = (half_t)acc[i][j][r];
+                }
+        }
+    }
+}
+
+template <int G, int WGM, int WGN>
+int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
+{
+    const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
+    if (m_tiles * n_tiles > 0x3fffffffLL) return E0M4_ERR_SHAPE;
+    const int total = (int)(m_tiles * n_tiles);
+    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    constexpr size_t lds = (size_t)kStages * kStageBytes;          // 96 KiB: above the default limit
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_pipe_kernel<G, WGM, WGN>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return record_hip_error(e);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(64 * WGM * WGN), lds,
+                       stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles);
+    return check_launch();
+}
+
+template <int G>
+int launch_pipe_g(int waves, const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y,
+                  hipStream_t stream)
+{
+    if (waves == 8) return launch_pipe<G, 2, 4>(x, M, c, N, K, y, stream);
+    return launch_pipe<G, 2, 2>(x, M, c, N, K, y, stream);
+}
+
+}  // namespace
+
+bool gemm_pipe_supported(int64_t K) { return K >= 128 && (K % (2 * BK)) == 0; }
+
+int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, int waves,
+                     void* Y, hipStream_t stream)
+{
+    const half_t* x = static_cast<const half_t*>(X);
+    const uint4* c = static_cast<const uint4*>(packed);
+    half_t* y = static_cast<half_t*>(Y);
+    switch (group) {
+        case 32: return launch_pipe_g<32>(waves, x, M, c, N, K, y, stream);
+        case 64: return launch_pipe_g<64>(waves, x, M, c, N, K, y, stream);
+        case 128: return launch_pipe_g<128>(waves, x, M, c, N, K, y, stream);
+        default: return E0M4_ERR_GROUP;
+    }
+}
+
+}  // namespace e0m4

@@ -30,5 +30,9 @@ int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t
 // MFMA path.
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                 hipStream_t stream);
+// Software-pipelined 256 x 256 tile kernel (needs K % 64 == 0 and K >= 128).
+bool gemm_pipe_supported(int64_t K);
+int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, int waves,
+                     void* Y, hipStream_t stream);
 
 }  // namespace e0m4
