@@ -23,6 +23,7 @@ Knob g_knobs[] = {
     {"gemv_occ", {0}},                 // 8: M=1 kernel variant capped at 64 registers per lane
     {"gemv_workgroups", {0}},          // target number of workgroups of the small-M kernel
     {"gemm_variant", {0}},             // select a GEMM kernel variant
+    {"gemm_splits", {0}},              // force the number of K splits of the pipelined GEMM kernel
 };
 
 __global__ void zero_fill_kernel(half_t* y, int64_t count)
@@ -100,8 +101,8 @@ size_t e0m4_params_elems(int64_t N, int64_t K, int group)
 
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 {
-    (void)M; (void)N; (void)K; (void)group;
-    return 0;                                   // no kernel of this version needs scratch memory
+    if (check_shape(N, K, group) != E0M4_OK || M <= kGemvMaxM || K == 0) return 0;   // the small-M kernel needs none
+    return gemm_workspace_bytes(M, N, K);       // partial tiles of the split-K GEMM, if it splits
 }
 
 int e0m4_set_knob(const char* name, int value)
@@ -161,7 +162,7 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
 int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales, const void* bias, int64_t N, int64_t K,
                 int group, void* Y, void* workspace, size_t workspace_bytes, void* stream)
 {
-    (void)scales; (void)bias; (void)workspace; (void)workspace_bytes;
+    (void)scales; (void)bias;
     int rc = check_shape(N, K, group);
     if (rc != E0M4_OK) return rc;
     if (M < 0 || M > (int64_t)1 << 31) return E0M4_ERR_SHAPE;
@@ -177,7 +178,8 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
     if (!X || !codes) return E0M4_ERR_NULL;
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
     if (M <= kGemvMaxM) return launch_gemv(X, M, codes, N, K, group, Y, (hipStream_t)stream);
-    return launch_gemm(X, M, codes, N, K, group, Y, (hipStream_t)stream);
+    if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
+    return launch_gemm(X, M, codes, N, K, group, Y, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
 }  // extern "C"

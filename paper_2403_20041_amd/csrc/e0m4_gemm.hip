@@ -414,17 +414,34 @@ int launch_g(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, h
     }
 }
 
+// The pipelined 256 x 256 kernel runs whenever its work items (tiles x K splits) can occupy a good
+// part of the chip; small problems (and K not a multiple of 128) take the 128 x 128 tile of this
+// file.  Returns the wavefront count of the pipelined kernel to use, or 0 for the kernels here.
+int pipe_waves(int64_t M, int64_t N, int64_t K)
+{
+    if (!gemm_pipe_supported(K)) return 0;
+    const int v = knob("gemm_variant");
+    if (v == 7) return 4;
+    if (v == 8) return 8;
+    if (v > 0) return 0;
+    return gemm_pipe_work_items(M, N, K) >= 96 ? 8 : 0;
+}
+
 }  // namespace
 
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    return pipe_waves(M, N, K) ? gemm_pipe_workspace_bytes(M, N, K) : 0;
+}
+
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
-                hipStream_t stream)
+                void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
     const half_t* x = static_cast<const half_t*>(X);
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
-    const int v = knob("gemm_variant");
-    if ((v == 7 || v == 8) && gemm_pipe_supported(K))
-        return launch_gemm_pipe(X, M, packed, N, K, group, v == 8 ? 8 : 4, Y, stream);
+    if (const int waves = pipe_waves(M, N, K))
+        return launch_gemm_pipe(X, M, packed, N, K, group, waves, Y, workspace, workspace_bytes, stream);
     switch (group) {
         case 32: return launch_g<32>(x, M, c, N, K, y, stream);
         case 64: return launch_g<64>(x, M, c, N, K, y, stream);

@@ -18,6 +18,9 @@
 #include "e0m4_device.h"
 #include "e0m4_host.h"
 
+#include <algorithm>
+#include <type_traits>
+
 namespace e0m4 {
 
 namespace {
@@ -53,7 +56,8 @@ __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2
 template <int G, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
                                                              const uint4* __restrict__ packed, int64_t N, int64_t K,
-                                                             half_t* __restrict__ Y, int m_tiles, int n_tiles)
+                                                             half_t* __restrict__ Y, int m_tiles, int n_tiles,
+                                                             int splits, float* __restrict__ partial)
 {
     constexpr int kThreads = 64 * WGM * WGN;
     constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);      // 32x32 MFMA blocks per wavefront
@@ -61,10 +65,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     constexpr int PA = BM / RP;                         // activation loader passes
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-    const int total = m_tiles * n_tiles;
+    // Work items are (tile, K split) pairs, the splits of a tile adjacent; each XCD takes a contiguous run.
+    const int total = m_tiles * n_tiles * splits;
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
-    const int tile = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
-    if (tile >= total) return;
+    const int item = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
+    if (item >= total) return;
+    const int tile = item / splits, split = item % splits;
     // (the quotient and remainder are computed on the vector unit; move them to scalar registers)
     const int64_t m0 = (int64_t)__builtin_amdgcn_readfirstlane(tile % m_tiles) * BM;
     const int64_t n0 = (int64_t)__builtin_amdgcn_readfirstlane(tile / m_tiles) * BN;
@@ -76,7 +82,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     const PackedLayout<G> lay(K);
     const int64_t nrb = row_blocks(N);
     const int wm = (wave / WGN) * (BM / WGM), wn = (wave % WGN) * (BN / WGN);
-    const int KT = (int)(K / BK);                       // K % 64 == 0 is required by the launcher
+    const int KT = (int)(K / BK);                       // K % 128 == 0 is required by the launcher: KT is even
+    // this work item's K slices [kt_begin, kt_end): whole pairs of slices, spread evenly over the splits
+    const int pairs = KT / 2;
+    const int kt_begin = 2 * (int)((int64_t)pairs * split / splits);
+    const int kt_end = 2 * (int)((int64_t)pairs * (split + 1) / splits);
 
     // ---- activation loader: 8 lanes cover one 128-byte row slice; pass p handles row RP*p + t/8.
     // Rows beyond M are clamped (their products are never stored).
@@ -210,17 +220,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     };
 
     // ---- prologue
-    load_a(0);
-    load_b(0, 0);
-    load_b(1, 1);
+    load_a(kt_begin);
+    load_b(kt_begin, 0);
+    load_b(kt_begin + 1, 1);
     store_a(0);
-    load_a(1);
+    load_a(kt_begin + 1);
     __syncthreads();
     read_frags(0, 0, fa[0]);
     dequant_frags(0, 0, fb[0]);
 
     uint32_t s0 = 0, s1 = kStageBytes, s2 = 2 * kStageBytes;      // ring: current, next, the one after
-    for (int kt = 0; kt < KT; kt += 2) {                // KT is even: K is a multiple of 128
+    for (int kt = kt_begin; kt < kt_end; kt += 2) {
         step(kt, 0, s0, s1);
         step(kt + 1, 1, s1, s2);
         const uint32_t tmp = s0;                        // advance the ring by two slices
@@ -230,32 +240,82 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     }
 
     // accumulator layout of a 32x32 block: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
-    half_t* __restrict__ Yt = Y + m0 * N + n0;
     const uint32_t n32 = (uint32_t)N;
     const int rows_left = (int)min((int64_t)BM, M - m0), cols_left = (int)min((int64_t)BN, N - n0);
     const int row0 = wm + 4 * (lane >> 5), col0 = wn + (lane & 31);
     const uint32_t off0 = (uint32_t)row0 * n32 + (uint32_t)col0;
+    auto store_tile = [&](auto* __restrict__ dst) {     // dst: element (m0, n0) of a row-major [M, N] array
+        using out_t = std::remove_reference_t<decltype(*dst)>;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        if (col0 + 32 * j < cols_left) {
+        for (int j = 0; j < TN; ++j) {
+            if (col0 + 32 * j < cols_left) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
-                    if (row0 + dr < rows_left) Yt[off0 + (uint32_t)dr * n32 + 32 * j] = (half_t)acc[i][j][r];
-                }
+                    for (int r = 0; r < 16; ++r) {
+                        const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
+                        if (row0 + dr < rows_left) dst[off0 + (uint32_t)dr * n32 + 32 * j] = (out_t)acc[i][j][r];
+                    }
+            }
         }
-    }
+    };
+    // Split K: this work item's fp32 partial sums go to slab `split` of the workspace (row-major
+    // [splits][M][N]); a second kernel adds the slabs in split order and rounds to fp16.  (Adding them
+    // here, in the last work item to arrive, needs device-scope fences, which cost far more than the
+    // second launch on a chip whose eight L2 caches are not coherent with each other.)
+    if (splits > 1)
+        store_tile(partial + ((size_t)split * (size_t)M + (size_t)m0) * (size_t)N + (size_t)n0);
+    else
+        store_tile(Y + m0 * N + n0);
 }
 
+// Y[i] = fp16(sum over splits, in split order, of partial[s][i]); V elements per thread.
+template <int V>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int64_t count,
+                                                            half_t* __restrict__ Y)
+{
+    typedef float fvec __attribute__((ext_vector_type(V)));
+    typedef _Float16 hvec __attribute__((ext_vector_type(V)));
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * V;
+    if (i >= count) return;
+    fvec sum = *reinterpret_cast<const fvec*>(partial + i);
+    for (int s = 1; s < splits; ++s) sum += *reinterpret_cast<const fvec*>(partial + (size_t)s * count + i);
+    *reinterpret_cast<hvec*>(Y + i) = __builtin_convertvector(sum, hvec);
+}
+
+// Number of K splits for a problem: 1 when the tiles alone give every compute unit work, else as
+// many as fit the chip, each split keeping at least kMinPairsPerSplit pairs of K slices.
+constexpr int kComputeUnits = 256;
+constexpr int kMinPairsPerSplit = 4;
+constexpr int kMaxSplits = 8;
+
+int choose_splits(int64_t tiles, int64_t K)
+{
+    const int forced = knob("gemm_splits");
+    const int64_t pairs = K / (2 * BK);
+    int64_t s = forced > 0 ? std::min<int64_t>(forced, pairs)                   // tests: down to one pair per split
+                           : std::min<int64_t>(kComputeUnits / tiles, pairs / kMinPairsPerSplit);
+    s = std::min<int64_t>(s, kMaxSplits);
+    return (int)std::max<int64_t>(s, 1);
+}
+
+size_t partial_bytes(int splits, int64_t M, int64_t N) { return (size_t)splits * (size_t)M * (size_t)N * sizeof(float); }
+
 template <int G, int WGM, int WGN>
-int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
+int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, void* workspace,
+                size_t workspace_bytes, hipStream_t stream)
 {
     const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
-    if (m_tiles * n_tiles > 0x3fffffffLL) return E0M4_ERR_SHAPE;
-    const int total = (int)(m_tiles * n_tiles);
+    const int64_t tiles = m_tiles * n_tiles;
+    const int splits = choose_splits(tiles, K);
+    if (tiles * splits > 0x3fffffffLL) return E0M4_ERR_SHAPE;
+    const int total = (int)(tiles * splits);
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    float* partial = nullptr;
+    if (splits > 1) {
+        if (workspace == nullptr || workspace_bytes < partial_bytes(splits, M, N)) return E0M4_ERR_WORKSPACE;
+        partial = static_cast<float*>(workspace);
+    }
     constexpr size_t lds = (size_t)kStages * kStageBytes;          // 96 KiB: above the default limit
     static bool attr_set = false;
     if (!attr_set) {
@@ -265,32 +325,58 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
         attr_set = true;
     }
     hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(64 * WGM * WGN), lds,
-                       stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles);
+                       stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial);
+    int rc = check_launch();
+    if (rc != E0M4_OK || splits == 1) return rc;
+    const int64_t count = M * N;
+    if (count % 4 == 0)                                 // slabs stay 16-byte aligned
+        hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, stream,
+                           partial, splits, count, y);
+    else
+        hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream,
+                           partial, splits, count, y);
     return check_launch();
 }
 
 template <int G>
 int launch_pipe_g(int waves, const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y,
-                  hipStream_t stream)
+                  void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
-    if (waves == 8) return launch_pipe<G, 2, 4>(x, M, c, N, K, y, stream);
-    return launch_pipe<G, 2, 2>(x, M, c, N, K, y, stream);
+    // Only the 2 x 4 arrangement is built: with one wavefront per SIMD (2 x 2) the kernel is bound by
+    // instruction issue and, with the split-K epilogue, no longer fits the register file.
+    (void)waves;
+    return launch_pipe<G, 2, 4>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
 }
 
 }  // namespace
 
 bool gemm_pipe_supported(int64_t K) { return K >= 128 && (K % (2 * BK)) == 0; }
 
+size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    if (tiles == 0 || !gemm_pipe_supported(K)) return 0;
+    const int splits = choose_splits(tiles, K);
+    return splits > 1 ? partial_bytes(splits, M, N) : 0;
+}
+
+int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K)
+{
+    const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    if (tiles == 0 || !gemm_pipe_supported(K)) return 0;
+    return tiles * choose_splits(tiles, K);
+}
+
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, int waves,
-                     void* Y, hipStream_t stream)
+                     void* Y, void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
     const half_t* x = static_cast<const half_t*>(X);
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     switch (group) {
-        case 32: return launch_pipe_g<32>(waves, x, M, c, N, K, y, stream);
-        case 64: return launch_pipe_g<64>(waves, x, M, c, N, K, y, stream);
-        case 128: return launch_pipe_g<128>(waves, x, M, c, N, K, y, stream);
+        case 32: return launch_pipe_g<32>(waves, x, M, c, N, K, y, workspace, workspace_bytes, stream);
+        case 64: return launch_pipe_g<64>(waves, x, M, c, N, K, y, workspace, workspace_bytes, stream);
+        case 128: return launch_pipe_g<128>(waves, x, M, c, N, K, y, workspace, workspace_bytes, stream);
         default: return E0M4_ERR_GROUP;
     }
 }

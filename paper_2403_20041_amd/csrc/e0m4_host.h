@@ -29,10 +29,15 @@ int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t
 
 // MFMA path.
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
-                hipStream_t stream);
-// Software-pipelined 256 x 256 tile kernel (needs K % 64 == 0 and K >= 128).
+                void* workspace, size_t workspace_bytes, hipStream_t stream);
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+// Software-pipelined 256 x 256 tile kernel (needs K % 128 == 0).  Problems with too few tiles to
+// fill the chip are split along K; the fp32 partial sums ([splits][M][N]) live in the caller's
+// workspace of gemm_pipe_workspace_bytes() bytes and a second kernel adds them.
 bool gemm_pipe_supported(int64_t K);
+size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K);      // tiles x K splits
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, int waves,
-                     void* Y, hipStream_t stream);
+                     void* Y, void* workspace, size_t workspace_bytes, hipStream_t stream);
 
 }  // namespace e0m4

@@ -20,7 +20,7 @@ def e0m4():
     import paper_2403_20041_amd as pkg
 
     pkg.lib()                                   # raises if the HIP library is not built
-    for k in ("gemv_waves", "gemm_variant"):
+    for k in ("gemv_waves", "gemm_variant", "gemm_splits"):
         pkg.e0m4_set_knob(k, 0)
     return pkg
 
@@ -222,6 +222,46 @@ def test_gemm_every_tile_shape(e0m4, oracle, variant, M, N, K, G):
         run_matmul_case(e0m4, oracle, M, N, K, G, seed=variant + M + N, outliers=True, row_std=(0.5, 2.0))
     finally:
         e0m4.e0m4_set_knob("gemm_variant", 0)
+
+
+@pytest.mark.parametrize("splits", [2, 3, 8])
+@pytest.mark.parametrize("M,N,K,G", [
+    (300, 600, 1024, 128),      # 6 tiles, 8 slice pairs: 3 splits get 2, 3 and 3 pairs; 8 splits one each
+    (513, 272, 384, 32),        # 3 slice pairs: fewer pairs than the 8 splits asked for
+    (256, 256, 128, 64),        # one tile, one slice pair: cannot split
+    (1024, 1040, 2048, 128),    # 20 tiles, ragged last column of tiles
+])
+def test_gemm_split_k(e0m4, oracle, splits, M, N, K, G):
+    e0m4.e0m4_set_knob("gemm_variant", 8)
+    e0m4.e0m4_set_knob("gemm_splits", splits)
+    try:
+        run_matmul_case(e0m4, oracle, M, N, K, G, seed=splits + M + N, outliers=True, row_std=(0.5, 2.0))
+    finally:
+        e0m4.e0m4_set_knob("gemm_variant", 0)
+        e0m4.e0m4_set_knob("gemm_splits", 0)
+
+
+def test_gemm_split_k_default_choice_and_reused_workspace(e0m4, oracle):
+    # 1024 x 2304 outputs = 36 tiles of 256 x 256: the heuristic splits K; two calls share one
+    # workspace, the second with other activations
+    M, N, K, G = 1024, 2304, 2048, 128
+    need = e0m4.e0m4_workspace_bytes(M, N, K, G)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    W = synth_inputs.weights(N, K, seed=70)
+    codes, scales, bias = e0m4.e0m4_quantize(to_dev(W), G)
+    What = oracle.dequant(*oracle.quantize(W, G), G)
+    rows = np.array([0, 1, 255, 256, 511, 777, 1023])
+    for seed in (71, 72):
+        X = synth_inputs.activations(M, K, seed=seed)
+        Xd = to_dev(X)
+        Y = e0m4.e0m4_matmul(Xd, codes, scales, bias, N, K, G, workspace=ws)
+        y_ref, absdot = oracle.matmul(X[rows], What)
+        check_matmul(Y[torch.from_numpy(rows).to(DEV)], y_ref, absdot, "seed %d" % seed)
+    # a workspace that is too small is refused before anything is launched
+    rc = e0m4.lib().e0m4_matmul(Xd.data_ptr(), M, codes.data_ptr(), None, None, N, K, G, Y.data_ptr(), ws.data_ptr(),
+                               need - 256, None)
+    assert rc == -5
 
 
 # ------------------------------------------------------------------ special inputs through both paths

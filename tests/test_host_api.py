@@ -47,8 +47,12 @@ def test_size_functions(L):
     assert L.e0m4_params_elems(4096, 4096, 128) == 32 * 4096
     assert L.e0m4_params_elems(100, 256, 64) == 400
     assert L.e0m4_params_elems(100, 256, 48) == 0
-    assert L.e0m4_workspace_bytes(1, 4096, 4096, 128) == 0  # partial sums never leave the chip
-    assert L.e0m4_workspace_bytes(1024, 4096, 4096, 128) == 0
+    assert L.e0m4_workspace_bytes(1, 4096, 4096, 128) == 0  # small M: partial sums never leave the chip
+    assert L.e0m4_workspace_bytes(8, 151936, 4096, 128) == 0
+    # 64 tiles of 256 x 256 on 256 compute units: 4 K splits, one fp32 [M, N] slab each
+    assert L.e0m4_workspace_bytes(1024, 4096, 4096, 128) == 4 * 1024 * 4096 * 4
+    assert L.e0m4_workspace_bytes(2048, 27392, 5120, 128) == 0          # enough tiles: no split
+    assert L.e0m4_workspace_bytes(1024, 4096, 4160, 64) == 0            # K not a multiple of 128: other kernel
 
 
 def test_error_codes_before_any_launch(L):
