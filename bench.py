@@ -28,6 +28,12 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 matrix peak
 GROUP = 128
 PREFILL_M = 1024
+# HBM bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE in separate runs of
+# this script, each scaled by the same counter's reading for a plain 1 GiB copy: x2.000 and x1.000); the
+# figures and the commands are in profiles/gemv_gemm_chatglm2_6b_hbm_traffic.txt.  They cannot be collected
+# inside a timed run, so they are constants here and apply to the default workload only.
+MEASURED_TRAFFIC_DECODE_LAUNCH = 27.35e6      # average GEMV launch of the 28 x 4 stack (algorithmic: 27.12e6)
+MEASURED_TRAFFIC_PREFILL_GATE_UP = 272.1e6    # M=1024 FFN gate+up GEMM (algorithmic: 124.1e6)
 
 
 def algorithmic_bytes(M, N, K, G):
@@ -44,6 +50,8 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="first run three plain device copies of 1 GiB (calibration of HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU kernel library; run with --gpus 1 "
@@ -61,6 +69,15 @@ def main():
     torch.cuda.set_device(dev)
     shapes = synth_inputs.CHATGLM2_6B
     n_layers = args.layers or synth_inputs.CHATGLM2_LAYERS
+
+    if args.copy_probe:
+        # a plain copy of known size: reads 2^30 bytes and writes 2^30 bytes per launch
+        src = torch.ones(1 << 29, dtype=torch.float16, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------- set-up: quantise every layer's weights on the GPU (offline step, untimed)
     layers = []
@@ -189,7 +206,9 @@ def main():
         "pct_of_hbm_peak": round(100.0 * decode_gbps / HBM_PEAK_GBPS, 2),
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel<G=128,M=1>", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "avg_launch_us": round(avg_launch_us, 3), "traffic": None},
+                     "avg_launch_us": round(avg_launch_us, 3),
+                     "algorithmic_bytes_per_launch": round(step_bytes / launches),
+                     "traffic": MEASURED_TRAFFIC_DECODE_LAUNCH if args.layers is None else None},
         "decode_per_shape": per_shape,
         "quantize": {"GBps_fp16_in": round(q_bytes / t_q / 1e9, 1), "note": "offline step incl. weight generation"},
     }
@@ -206,33 +225,36 @@ def main():
                 del W
                 X = synth_inputs.activations_device(PREFILL_M, K, 6000 + p, dev, outlier_frac=0.01)
                 Y = torch.empty((PREFILL_M, N), dtype=torch.float16, device=dev)
+                pws_bytes = e0m4.e0m4_workspace_bytes(PREFILL_M, N, K, GROUP)    # split-K partial sums, if any
+                pws = torch.empty(max(pws_bytes, 16), dtype=torch.uint8, device=dev)
                 for _ in range(3):
-                    e0m4.e0m4_matmul(X, codes, scales, bias, N, K, GROUP, out=Y, stream=stream)
+                    e0m4.e0m4_matmul(X, codes, scales, bias, N, K, GROUP, out=Y, workspace=pws, stream=stream)
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 reps = 20
                 e0.record(stream)
                 for _ in range(reps):
-                    e0m4.e0m4_matmul(X, codes, scales, bias, N, K, GROUP, out=Y, stream=stream)
+                    e0m4.e0m4_matmul(X, codes, scales, bias, N, K, GROUP, out=Y, workspace=pws, stream=stream)
                 e1.record(stream)
                 stream.synchronize()
                 ms = e0.elapsed_time(e1) / reps
                 flops = 2.0 * PREFILL_M * N * K
                 tf = flops / ms / 1e9
                 pre[name] = {"N": N, "K": K, "ms": round(ms, 4), "TFLOPs": round(tf, 1),
-                             "frac_mfma": round(tf / MFMA_F16_PEAK_TFLOPS, 4)}
+                             "frac_mfma": round(tf / MFMA_F16_PEAK_TFLOPS, 4), "workspace_bytes": pws_bytes}
                 tot_flops += flops
                 tot_ms += ms
                 if best is None or flops > best[0]:
                     best = (flops, ms, name)
-                del codes, scales, bias, X, Y
+                del codes, scales, bias, X, Y, pws
         layer_tf = tot_flops / tot_ms / 1e9
         out["prefill"] = {"workload": "ChatGLM2-6B-shaped prefill layer, M=%d, 4 GEMMs" % PREFILL_M,
                           "value": round(layer_tf, 1), "unit": "TFLOP/s", "ms_per_layer": round(tot_ms, 4),
                           "pct_of_mfma_peak": round(100.0 * layer_tf / MFMA_F16_PEAK_TFLOPS, 2), "per_shape": pre}
         dom_tf = best[0] / best[1] / 1e9
-        out["roofline_prefill"] = {"bound": "mfma", "kernel": "gemm_kernel<128> (%s)" % best[2],
+        out["roofline_prefill"] = {"bound": "mfma", "kernel": "gemm_pipe_kernel<G=128> (%s)" % best[2],
                                    "achieved": round(dom_tf, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                   "frac": round(dom_tf / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None}
+                                   "frac": round(dom_tf / MFMA_F16_PEAK_TFLOPS, 4),
+                                   "traffic": MEASURED_TRAFFIC_PREFILL_GATE_UP}
 
     # ---------------- CPU oracle on a bounded sample of the decode workload (one layer, repeated)
     if not args.no_cpu:
