@@ -67,8 +67,10 @@ const char* e0m4_last_hip_error(void);
 size_t e0m4_codes_bytes(int64_t N, int64_t K, int group);
 /* Number of fp16 elements in `scales` (and in `bias`): N * (K/group). */
 size_t e0m4_params_elems(int64_t N, int64_t K, int group);
-/* Scratch bytes e0m4_matmul needs for this shape.  Every path of this version
- * keeps its partial sums on chip, so this is 0; callers should still query it. */
+/* Scratch bytes e0m4_matmul needs for this shape: 0 for M <= 8 (partial sums
+ * stay on chip) and for GEMM shapes with enough output tiles to fill the GPU;
+ * otherwise splits * M * N * 4 bytes of fp32 partial sums for the GEMM's split
+ * along K.  Depends on the tuning knobs in force; query after setting them. */
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
 
 /*
@@ -111,7 +113,11 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  *   M <= 8 : HBM-bound GEMV path (one workgroup per 16 output rows).
  *   M >= 9 : MFMA GEMM path.
  * `scales_f16`/`bias_f16` may be NULL (see `codes` above); `workspace` may be
- * NULL when e0m4_workspace_bytes() is 0.  The result is deterministic.
+ * NULL when e0m4_workspace_bytes() is 0, else it is device memory of at least
+ * that many bytes, 16-byte aligned, owned by the caller, overwritten by the
+ * call and free for reuse once the call's work on `stream` has completed
+ * (E0M4_ERR_WORKSPACE if too small).  The result is deterministic: every
+ * reduction, the split along K included, has a fixed order.
  */
 int e0m4_matmul(const void* X_f16, int64_t M,
                 const void* codes, const void* scales_f16, const void* bias_f16,
