@@ -28,10 +28,15 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // never shares a cache line with another workgroup.
 //
 // Inside a chunk, 32-bit word w holds the codes of k = 8w .. 8w+7 (of the
-// chunk); inside a word the nibbles are interleaved so that nibble i (bits
-// 4i..4i+3) is code 2i and nibble 4+i is code 2i+1: a shift by 6-4i and one
-// mask-or then leave two codes sitting in the four highest fraction bits of the
-// two fp16 halves of a register.
+// chunk) as four pairs (2i, 2i+1).  The two codes of a pair sit 16 bits apart,
+// so that after at most one shift or rotate they occupy fraction bits of the
+// two fp16 halves of a register.  Bit position of the low bit of each code:
+//     pair 0: 6 and 22    pair 1: 2 and 18    pair 2: 10 and 26
+//     pair 3: 14 and 30 (the second code wraps around: bits 30, 31, 0, 1)
+// Pair 0 already lies in the four highest fraction bits (9..6 and 25..22);
+// pair 1 lies in fraction bits 5..2.  Rotating the word right by 8 brings
+// pair 3 to 9..6 and pair 2 to 5..2.  A code in bits 9..6 of a half with the
+// exponent of [2,4) reads 2 + code/8; in bits 5..2 it reads 2 + code/128.
 //
 // Rows beyond N and k beyond K inside the last blocks are stored as zero codes
 // with zero parameters (they dequantise to 0).
@@ -66,10 +71,20 @@ struct PackedLayout {
     __host__ __device__ static constexpr int param_slot(int q, int r) { return (q * kCodesPerChunk / G) * kBlockRows + r; }
 };
 
-// bit position of code j (0..7) inside its 32-bit word
-__host__ __device__ inline int nibble_shift(int j) { return 4 * ((j >> 1) + ((j & 1) << 2)); }
+// bit position of the low bit of code j (0..7) inside its 32-bit word; code 7 wraps (see above)
+__host__ __device__ inline int nibble_shift(int j)
+{
+    const int pair_pos[4] = {6, 2, 10, 14};
+    return pair_pos[j >> 1] + ((j & 1) << 4);
+}
+__host__ __device__ inline uint32_t rotl32(uint32_t v, int n) { return n ? (v << n) | (v >> (32 - n)) : v; }
+__host__ __device__ inline uint32_t rotr32(uint32_t v, int n) { return n ? (v >> n) | (v << (32 - n)) : v; }
+// a word with code c at position j, and the code at position j of a word
+__host__ __device__ inline uint32_t place_code(uint32_t c, int j) { return rotl32(c & 15u, nibble_shift(j)); }
+__host__ __device__ inline uint32_t extract_code(uint32_t word, int j) { return rotr32(word, nibble_shift(j)) & 15u; }
 
 constexpr uint32_t kFracMask2 = 0x03C003C0u;   // four highest fraction bits of both halves
+constexpr uint32_t kFracMaskLow2 = 0x003C003Cu;    // fraction bits 5..2 of both halves
 constexpr uint32_t kExpBits2 = 0x40004000u;    // sign 0, exponent of the binade [2,4), both halves
 
 // The paper's two bitwise operations, applied to two codes at once: pair i of
@@ -82,10 +97,10 @@ __device__ inline uint32_t w1_pair_bits(uint32_t word, uint32_t mask)
 {
     static_assert(I >= 0 && I < 4, "pair index");
     uint32_t s;
-    if (I == 0) s = word << 6;
-    else if (I == 1) s = word << 2;
-    else if (I == 2) s = word >> 2;
-    else s = word >> 6;
+    if (I == 0) s = word;
+    else if (I == 1) s = word << 4;
+    else if (I == 2) s = word >> 4;
+    else s = __builtin_amdgcn_alignbit(word, word, 8);      // rotate right by 8
     return (s & mask) | kExpBits2;
 }
 
@@ -95,12 +110,44 @@ __device__ inline half2_t w1_pair(uint32_t word, uint32_t mask)
     return __builtin_bit_cast(half2_t, w1_pair_bits<I>(word, mask));
 }
 
+// All four pairs of a word with one rotate: p[0] and p[3] read 2 + code/8, p[1] and p[2] read
+// 2 + code/128 (see the layout above).  mask_hi holds kFracMask2, mask_lo kFracMaskLow2, both in
+// vector registers.  For dot products: sum x*(2 + c/8) over the codes of pairs 1 and 2 equals
+// 16 * sum x*(2 + c/128) - 30 * sum x.
+__device__ inline void w1_pairs_mixed(uint32_t word, uint32_t mask_hi, uint32_t mask_lo, half2_t (&p)[4])
+{
+    const uint32_t t = __builtin_amdgcn_alignbit(word, word, 8);
+    p[0] = __builtin_bit_cast(half2_t, (word & mask_hi) | kExpBits2);
+    p[1] = __builtin_bit_cast(half2_t, (word & mask_lo) | kExpBits2);
+    p[2] = __builtin_bit_cast(half2_t, (t & mask_lo) | kExpBits2);
+    p[3] = __builtin_bit_cast(half2_t, (t & mask_hi) | kExpBits2);
+}
+
 // kFracMask2 in a vector register the optimiser cannot fold back into a literal.
 __device__ inline uint32_t frac_mask_vgpr()
 {
     uint32_t m = kFracMask2;
     asm volatile("" : "+v"(m));
     return m;
+}
+
+__device__ inline uint32_t frac_mask_low_vgpr()
+{
+    uint32_t m = kFracMaskLow2;
+    asm volatile("" : "+v"(m));
+    return m;
+}
+
+// Buffer resource over [p, p + 2 GiB): raw (stride 0), 32-bit data format word of gfx9-class targets.
+// p must be wavefront-uniform; passing its halves through readfirstlane pins the resource to scalar
+// registers (otherwise every buffer load is wrapped in a per-lane "waterfall" loop).
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p)
+{
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    void* q = reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
+    return __builtin_amdgcn_make_buffer_rsrc(q, 0, 0x7fffffff, 0x00020000);
 }
 
 __device__ inline half_t param_scale(uint32_t word) { return __builtin_bit_cast(half_t, (uint16_t)(word & 0xFFFFu)); }

@@ -33,18 +33,6 @@ constexpr int kNumXcd = 8;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-// Buffer resource over [p, p + 2 GiB): raw (stride 0), 32-bit data format word of gfx9-class targets.
-// p must be wavefront-uniform; passing its halves through readfirstlane pins the resource to scalar
-// registers (otherwise every buffer load is wrapped in a per-lane "waterfall" loop).
-__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p)
-{
-    const uint64_t a = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
-    void* q = reinterpret_cast<void*>(((uint64_t)hi << 32) | lo);
-    return __builtin_amdgcn_make_buffer_rsrc(q, 0, 0x7fffffff, 0x00020000);
-}
-
 __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2)
 {
     return (w1 - bias2) * scale2;                       // difference exact, product rounded once

@@ -23,9 +23,11 @@ namespace e0m4 {
 
 namespace {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kXBudgetBytes = 48 * 1024;        // LDS spent on activations and their chunk sums
 constexpr int kRedBudgetBytes = 16 * 1024;      // LDS spent on the per-wavefront partial sums
-constexpr int kBytesPerBlockX = kBlockK * 2 + (kBlockK / kCodesPerChunk) * 4;   // 272 per row of X per k block
+constexpr int kBytesPerBlockX = kBlockK * 2 + (kBlockK / kCodesPerChunk) * 8;   // 288 per row of X per k block
 constexpr int kTargetWorkgroups = 512;          // two resident workgroups of 16 wavefronts per compute unit
 constexpr int kDepth = 4;                       // weight blocks in flight per wavefront
 constexpr int kEarlyX = 2;                      // activation pieces per thread requested before the weights
@@ -61,8 +63,12 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
     int64_t t = (nrb + target - 1) / target;
     if (t > t_max) t = t_max;
     if (t < 1 || !single_segment) t = 1;       // several activation segments: one row block per workgroup
-    p.rb_per_wg = (int)t;
+    p.rb_per_wg = (int)t;                       // the most row blocks any workgroup owns
+    // Row blocks are dealt out evenly: workgroup b owns [b * nrb / grid, (b + 1) * nrb / grid).  When
+    // the target number of workgroups can be reached with at most t row blocks each, use exactly the
+    // target (every compute unit then holds the same number of workgroups); else the fewest that do.
     p.grid = (nrb + t - 1) / t;
+    if (t > 1 && p.grid < target && (int64_t)target * t >= nrb) p.grid = target;
     p.lds_bytes = (size_t)M * p.seg_blocks * kBytesPerBlockX + (size_t)t * w * M * kBlockRows * sizeof(float);
     return p;
 }
@@ -81,24 +87,25 @@ __global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restr
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int seg_k = seg_blocks * kBlockK;
     half_t* xs = reinterpret_cast<half_t*>(smem);                               // [M][seg_k]
-    float* sxs = reinterpret_cast<float*>(smem + (size_t)M * seg_k * 2);         // [M][seg_k/32]
-    float* red = sxs + (size_t)M * (seg_k / kCodesPerChunk);                     // [rb_per_wg][W][M][16]
+    // per 32-wide chunk of X: (sum of the chunk, 30 x sum of its elements with k % 8 in 2..5)
+    float2* sxs = reinterpret_cast<float2*>(smem + (size_t)M * seg_k * 2);      // [M][seg_k/32]
+    float* red = reinterpret_cast<float*>(sxs + (size_t)M * (seg_k / kCodesPerChunk));   // [rb_per_wg][W][M][16]
 
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int q = lane >> 4, r = lane & 15;
-    const uint32_t fmask = frac_mask_vgpr();
+    const uint32_t fmask = frac_mask_vgpr(), fmask_low = frac_mask_low_vgpr();
     const PackedLayout<G> lay(K);
     const int nkb = (int)lay.nkb;
     const int64_t nrb = row_blocks(N);
-    const int64_t rb0 = (int64_t)blockIdx.x * rb_per_wg;
-    const int n_rb = (int)min((int64_t)rb_per_wg, nrb - rb0);
+    const int64_t rb0 = (int64_t)blockIdx.x * nrb / gridDim.x;      // even deal of row blocks (<= rb_per_wg each)
+    const int n_rb = (int)((int64_t)(blockIdx.x + 1) * nrb / gridDim.x - rb0);
     const int nitems = n_rb * nkb;
-    // Addresses are a wavefront-uniform 64-bit base plus 32-bit offsets: one workgroup's run of row
-    // blocks is far smaller than 4 GiB.
-    const char* wg_codes = reinterpret_cast<const char*>(packed + lay.code_index(rb0, 0));
-    const char* wg_params = reinterpret_cast<const char*>(packed) + 4 * lay.param_index(rb0, 0);
+    // Weights are read with buffer loads: a wavefront-uniform resource (base of this workgroup's run
+    // of row blocks, far smaller than 2 GiB), a scalar offset per block and a constant lane offset.
+    const __amdgpu_buffer_rsrc_t wg_codes = make_rsrc(packed + lay.code_index(rb0, 0));
+    const __amdgpu_buffer_rsrc_t wg_params = make_rsrc(reinterpret_cast<const char*>(packed) + 4 * lay.param_index(rb0, 0));
     const uint32_t rb_stride = (uint32_t)nkb * block_bytes(G);                  // bytes from one row block to the next
     const uint32_t lane_code_off = lane * 16, lane_param_off = lay.param_slot(q, r) * 4;
     // step a (row block slot, k block) cursor by W items; W <= nkb unless SMALLK
@@ -119,20 +126,26 @@ __global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restr
         const int m = idx / pieces, pc = idx % pieces;
         const int64_t k = (int64_t)sb * kBlockK + pc * 8;
         half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (idx < M * pieces && k < K) v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+        if (VARIANT < 5 && idx < M * pieces && k < K) v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
         return v;
     };
-    // store one piece and, from every fourth lane, the sum of its 32-wide chunk
+    // store one piece and, from every fourth lane, the two sums of its 32-wide chunk (a piece is the
+    // k range of one code word: elements 2..5 meet the code pairs that are read at 1/128 scale)
     auto x_store = [&](int idx, const half8_t& v) {
         const int m = idx / pieces, pc = idx % pieces;
-        float s = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) s += (float)v[j];
+        const half2_t ones = {(half_t)1.f, (half_t)1.f};
+        const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
+        float sl = __builtin_amdgcn_fdot2(x1, ones, 0.f, false);
+        sl = __builtin_amdgcn_fdot2(x2, ones, sl, false);
+        float s = __builtin_amdgcn_fdot2(x0, ones, sl, false);
+        s = __builtin_amdgcn_fdot2(x3, ones, s, false);
         s += __shfl_xor(s, 1);
+        sl += __shfl_xor(sl, 1);
         s += __shfl_xor(s, 2);
-        if (idx < M * pieces) {
+        sl += __shfl_xor(sl, 2);
+        if (VARIANT < 5 && idx < M * pieces) {
             *reinterpret_cast<half8_t*>(&xs[m * seg_k + pc * 8]) = v;
-            if ((pc & 3) == 0) sxs[m * (seg_k / kCodesPerChunk) + (pc >> 2)] = s;
+            if ((pc & 3) == 0) sxs[m * (seg_k / kCodesPerChunk) + (pc >> 2)] = make_float2(s, 30.f * sl);
         }
     };
     half8_t xearly[kEarlyX];
@@ -148,10 +161,13 @@ __global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restr
         const bool in = fs < n_rb;
         const uint32_t s_ = in ? fs : n_rb - 1, k_ = in ? fk : nkb - 1;
         const uint32_t row_off = __builtin_amdgcn_readfirstlane(s_ * rb_stride);
-        const char* pc = wg_codes + (row_off + k_ * kBlockCodeBytes);
-        const char* pp = wg_params + (row_off + k_ * (4 * lay.kParamWords));
-        cd = *reinterpret_cast<const uint4*>(pc + lane_code_off);
-        pwd = *reinterpret_cast<const uint32_t*>(pp + lane_param_off);
+        const u32x4 cv = __builtin_amdgcn_raw_buffer_load_b128(wg_codes, (int)lane_code_off,
+                                                               (int)(row_off + k_ * kBlockCodeBytes), 0);
+        cd = make_uint4(cv.x, cv.y, cv.z, cv.w);
+        if (VARIANT >= 6) pwd = 0x3c003c00u;
+        else
+            pwd = __builtin_amdgcn_raw_buffer_load_b32(wg_params, (int)lane_param_off,
+                                                       (int)(row_off + k_ * (4 * lay.kParamWords)), 0);
         advance(fs, fk);
     };
 #pragma unroll
@@ -184,7 +200,8 @@ __global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restr
         if (sb == 0) {
 #pragma unroll
             for (int e = 0; e < kEarlyX; ++e) x_store(t + e * kThreads, xearly[e]);
-            for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0));
+            if (VARIANT < 5)
+                for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0));
         } else {
             __syncthreads();                            // everyone is done with the previous segment's activations
             fs = slot;                                  // refill the ring from the current item
@@ -193,7 +210,7 @@ __global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restr
             for (int d = 0; d < D; ++d) fetch(c[d], pw[d]);
             for (int idx = t; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, sb));
         }
-        __syncthreads();
+        if (VARIANT < 5) __syncthreads();
 
         // one item: its codes and parameter word are in a ring slot
         auto process = [&](const uint4& cd, const uint32_t pwd) {
@@ -201,38 +218,39 @@ __global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restr
             const float bi = (float)param_bias(pwd);
             const uint32_t words[4] = {cd.x, cd.y, cd.z, cd.w};
             const int xoff = (kb - sb) * kBlockK + q * kCodesPerChunk;
-            float a[M][2];                              // two independent accumulation chains per row of X
+            float a[M][2];          // per row of X: sum x*(2 + c/8) over code pairs 0 and 3, sum x*(2 + c/128) over 1 and 2
 #pragma unroll
             for (int m = 0; m < M; ++m) a[m][0] = a[m][1] = 0.f;
-            if (VARIANT == 1) {                         // timing experiment: stream only, no arithmetic
+            if (VARIANT == 1 || VARIANT >= 5) {         // timing experiment: stream only, no arithmetic
                 acc[0] += __builtin_bit_cast(float, words[0] ^ words[1] ^ words[2] ^ words[3]) * sc;
             } else {
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
-                    const half2_t p0 = w1_pair<0>(words[w], fmask), p1 = w1_pair<1>(words[w], fmask);
-                    const half2_t p2 = w1_pair<2>(words[w], fmask), p3 = w1_pair<3>(words[w], fmask);
+                    half2_t p[4];
+                    w1_pairs_mixed(words[w], fmask, fmask_low, p);
 #pragma unroll
                     for (int m = 0; m < M; ++m) {
                         half8_t xv;
                         if (VARIANT == 2) xv = half8_t{1, 1, 1, 1, 1, 1, 1, 1};     // timing experiment: no LDS reads
                         else xv = *reinterpret_cast<const half8_t*>(&xs[m * seg_k + xoff + 8 * w]);
                         const half2_t x0 = {xv[0], xv[1]}, x1 = {xv[2], xv[3]}, x2 = {xv[4], xv[5]}, x3 = {xv[6], xv[7]};
-                        a[m][0] = __builtin_amdgcn_fdot2(p0, x0, a[m][0], false);
-                        a[m][1] = __builtin_amdgcn_fdot2(p1, x1, a[m][1], false);
-                        a[m][0] = __builtin_amdgcn_fdot2(p2, x2, a[m][0], false);
-                        a[m][1] = __builtin_amdgcn_fdot2(p3, x3, a[m][1], false);
+                        a[m][0] = __builtin_amdgcn_fdot2(p[0], x0, a[m][0], false);
+                        a[m][1] = __builtin_amdgcn_fdot2(p[1], x1, a[m][1], false);
+                        a[m][1] = __builtin_amdgcn_fdot2(p[2], x2, a[m][1], false);
+                        a[m][0] = __builtin_amdgcn_fdot2(p[3], x3, a[m][0], false);
                     }
                 }
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
-                    const float sxq = VARIANT == 2 ? 32.f : sxs[m * (seg_k / kCodesPerChunk) + (xoff >> 5)];
-                    acc[m] += sc * ((a[m][0] + a[m][1]) - bi * sxq);
+                    // sum x*w1 = a0 + 16*a1 - 30*(sum of x over pairs 1 and 2); then the group's affine map
+                    const float2 sx = VARIANT == 2 ? make_float2(32.f, 480.f) : sxs[m * (seg_k / kCodesPerChunk) + (xoff >> 5)];
+                    acc[m] += sc * ((a[m][0] + 16.f * a[m][1] - sx.y) - bi * sx.x);
                 }
             }
             i += W;
             const int prev = slot;
             advance(slot, kb);
-            if (slot != prev) flush(prev);              // the next item belongs to a later row block
+            if (VARIANT < 7 && slot != prev) flush(prev);       // the next item belongs to a later row block
         };
 
         // with one segment the loop runs over all items; otherwise (one row block) up to the segment's end
@@ -250,6 +268,10 @@ __global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restr
 #pragma unroll
         for (int d = 0; d < D; ++d)                     // last partial turn
             if (i < limit) process(c[d], pw[d]);
+    }
+    if (VARIANT >= 7) {
+        if (acc[0] == 1.2345f) Y[t] = (half_t)acc[0];
+        return;
     }
     if (slot < n_rb) flush(slot);                       // sums of a row block this wavefront left unfinished (several segments)
     __syncthreads();
@@ -285,6 +307,15 @@ int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, 
                            p.seg_blocks, p.rb_per_wg);
     else if (dbg == 4)
         hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 4>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
+                           p.seg_blocks, p.rb_per_wg);
+    else if (dbg == 5)
+        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 5>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
+                           p.seg_blocks, p.rb_per_wg);
+    else if (dbg == 6)
+        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 6>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
+                           p.seg_blocks, p.rb_per_wg);
+    else if (dbg == 7)
+        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 7>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
                            p.seg_blocks, p.rb_per_wg);
     else if (M == 1 && knob("gemv_occ") == 8)           // experiment: cap registers for 8 wavefronts per SIMD
         hipLaunchKernelGGL((gemv_kernel<G, 1, W, false, 0, 8>), grid, block, p.lds_bytes, stream, x, c, N, K, y,

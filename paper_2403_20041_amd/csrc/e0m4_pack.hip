@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __rest
         uint32_t word = 0;
         if (ok) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) word |= encode_value(v[j], sf, bf) << nibble_shift(j);
+            for (int j = 0; j < 8; ++j) word |= place_code(encode_value(v[j], sf, bf), j);
         }
         stage[i * BW + ((piece >> 2) * kBlockRows + r) * 4 + (piece & 3)] = word;
         if ((piece % (G / 8)) == 0) {
@@ -215,8 +215,8 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint4* __restric
                 uint32_t lo = 0, hi = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    lo |= ((words[w] >> nibble_shift(j)) & 15u) << (8 * j);
-                    hi |= ((words[w] >> nibble_shift(j + 4)) & 15u) << (8 * j);
+                    lo |= extract_code(words[w], j) << (8 * j);
+                    hi |= extract_code(words[w], j + 4) << (8 * j);
                 }
                 *reinterpret_cast<uint2*>(&tile[(16 * i + r) * kStride + q * 32 + w * 8]) = make_uint2(lo, hi);
             }
