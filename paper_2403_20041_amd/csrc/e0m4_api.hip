@@ -19,8 +19,6 @@ struct Knob {
 };
 Knob g_knobs[] = {
     {"gemv_waves", {0}},               // wavefronts per workgroup of the small-M kernel (4, 8 or 16)
-    {"gemv_debug", {0}},               // timing experiments (results are wrong when set)
-    {"gemv_occ", {0}},                 // 8: M=1 kernel variant capped at 64 registers per lane
     {"gemv_workgroups", {0}},          // target number of workgroups of the small-M kernel
     {"gemm_variant", {0}},             // select a GEMM kernel variant
     {"gemm_splits", {0}},              // force the number of K splits of the pipelined GEMM kernel

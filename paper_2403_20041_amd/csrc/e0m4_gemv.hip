@@ -5,19 +5,24 @@
 //
 // Work decomposition (gfx950, wave64): a workgroup owns a few consecutive blocks
 // of 16 output rows over the whole of K, so no partial sums ever leave the
-// compute unit and no second kernel, atomics or scratch memory are needed.  Its
-// W wavefronts take the 16 x 128 weight blocks of that contiguous run
-// round-robin and keep several in flight; each block is one dwordx4 load per
-// lane (1 KiB contiguous per wavefront) plus one dword of group parameters.
-// Lane q*16 + r holds 32 codes of row r: it turns them into the raw binade
-// values w1 = 2 + code/8 with a shift and a mask-or per pair, accumulates
-// a = sum x*w1 with v_dot2_f32_f16 against activations staged in LDS, and
-// applies the group's affine map once per block:
-//     y += scale * (a - bias * sum x).
-// The four k-quarters of a row are added with two cross-lane steps, the
-// wavefronts' sums through LDS in a fixed order (deterministic result).
+// compute unit and no second kernel, atomics or scratch memory are needed.  A
+// work item is four consecutive 16 x 128 weight blocks of one row block (4 KiB
+// of codes, contiguous, plus their group parameters); the W wavefronts take the
+// work items of the workgroup's contiguous run round-robin and keep one item
+// (four dwordx4 loads per lane) in flight while they process the previous one.
+// Lane q*16 + r holds 32 codes of row r per block: it turns them into the raw
+// binade values with one rotate and four mask-or per eight codes, accumulates
+// a = sum x*w1 with v_dot2_f32_f16, and applies the group's affine map once per
+// block:  y += scale * (a - bias * sum x).
+// Activations come from LDS (staged once per workgroup, with the sums of every
+// 32-wide chunk).  The four k-quarters of a row are added with two cross-lane
+// steps, the wavefronts' sums through LDS in a fixed order (deterministic
+// result).  (Keeping the activations in registers instead was measured slower:
+// a wavefront handles too few blocks to repay loading them.)
 #include "e0m4_device.h"
 #include "e0m4_host.h"
+
+#include <algorithm>
 
 namespace e0m4 {
 
@@ -25,17 +30,20 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+constexpr int kSuper = 4;                       // weight blocks (of 128 k) per work item
 constexpr int kXBudgetBytes = 48 * 1024;        // LDS spent on activations and their chunk sums
-constexpr int kRedBudgetBytes = 16 * 1024;      // LDS spent on the per-wavefront partial sums
+constexpr int kRedBudgetBytes = 32 * 1024;      // LDS spent on the per-wavefront partial sums, at most
+constexpr int kLdsLimitBytes = 64 * 1024;       // dynamic LDS a kernel may ask for without opting in to more
 constexpr int kBytesPerBlockX = kBlockK * 2 + (kBlockK / kCodesPerChunk) * 8;   // 288 per row of X per k block
-constexpr int kTargetWorkgroups = 512;          // two resident workgroups of 16 wavefronts per compute unit
-constexpr int kDepth = 4;                       // weight blocks in flight per wavefront
+constexpr int kTargetWorkgroups = 256;          // one workgroup per compute unit (measured best: activations are staged once per workgroup)
 constexpr int kEarlyX = 2;                      // activation pieces per thread requested before the weights
 
 struct GemvPlan {
     int waves;          // wavefronts per workgroup
-    int seg_blocks;     // k blocks whose activations are resident in LDS at a time (multiple of waves)
-    int rb_per_wg;      // consecutive row blocks owned by one workgroup
+    int seg_items;      // work items (per row block) whose activations are resident in LDS at a time
+    int rb_per_wg;      // the most consecutive row blocks one workgroup owns
+    int step_slots;     // a wavefront's next work item: this many row blocks further ...
+    int step_item;      // ... and this many items further (with carry), i.e. W items ahead
     int64_t grid;
     size_t lds_bytes;
 };
@@ -44,48 +52,58 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
 {
     GemvPlan p;
     const int64_t nrb = row_blocks(N), nkb = k_blocks(K);
+    const int64_t nsi = (nkb + kSuper - 1) / kSuper;           // work items per row block
     int w = knob("gemv_waves");
-    // 16 wavefronts per row block when there is at most one row block per compute unit (that is the
-    // only parallelism there is); 8 otherwise (measured faster) and for many rows of X, whose
-    // accumulators need the larger register budget of the smaller workgroup
-    if (w != 4 && w != 8 && w != 16) w = (M <= 4 && nrb <= 256) ? 16 : 8;
-    while (w > 4 && w > nkb) w /= 2;                          // a wavefront steps W k blocks at a time
+    if (w == 16 && M > 4) w = 8;                // 16 wavefronts leave too few registers for that many accumulators
+    const bool forced = w == 4 || w == 8 || w == 16;
+    // 16 wavefronts when K is long, or when a workgroup has many work items of a medium K; 8 otherwise
+    // (measured on the layer shapes of 2B to 14B models)
+    const int64_t t_guess = (nrb + kTargetWorkgroups - 1) / kTargetWorkgroups;
+    if (!forced) w = (M <= 4 && (nsi >= 16 || (nsi >= 8 && nsi * t_guess >= 32))) ? 16 : 8;
+    int64_t t = 1;
+    bool single_segment = true;
+    for (;;) {
+        const int64_t cap = kXBudgetBytes / (M * kSuper * kBytesPerBlockX);    // work items whose X fits (>= 5)
+        single_segment = nsi <= cap;
+        p.seg_items = (int)(single_segment ? nsi : (cap >= w ? cap / w * w : cap));   // a multiple of W if possible
+        const int64_t x_bytes = M * p.seg_items * kSuper * kBytesPerBlockX;
+        const int64_t red_budget = std::min<int64_t>(kRedBudgetBytes, kLdsLimitBytes - x_bytes);
+        int64_t t_max = red_budget / ((int64_t)w * M * kBlockRows * sizeof(float));
+        if (t_max < 1) t_max = 1;
+        int target = knob("gemv_workgroups");
+        if (target <= 0) target = kTargetWorkgroups;
+        t = (nrb + target - 1) / target;
+        if (t > t_max) t = t_max;
+        if (t < 1 || !single_segment) t = 1;   // several activation segments: one row block per workgroup
+        // Row blocks are dealt out evenly: workgroup b owns [b * nrb / grid, (b + 1) * nrb / grid).  When
+        // the target number of workgroups can be reached with at most t row blocks each, use exactly the
+        // target (every compute unit then holds the same number of workgroups); else the fewest that do.
+        p.grid = (nrb + t - 1) / t;
+        if (t > 1 && p.grid < target && (int64_t)target * t >= nrb) p.grid = target;
+        // fewer wavefronts when a workgroup has fewer work items than wavefronts
+        if (!forced && w > 4 && nsi * t < w) { w /= 2; continue; }
+        break;
+    }
     p.waves = w;
-    int64_t max_blocks = kXBudgetBytes / (M * kBytesPerBlockX) / w * w;
-    if (max_blocks < w) max_blocks = w;
-    const int64_t need = (nkb + w - 1) / w * w;
-    const bool single_segment = need <= max_blocks;
-    p.seg_blocks = (int)(single_segment ? need : max_blocks);
-    int64_t t_max = kRedBudgetBytes / ((int64_t)w * M * kBlockRows * sizeof(float));
-    if (t_max < 1) t_max = 1;
-    int target = knob("gemv_workgroups");
-    if (target <= 0) target = kTargetWorkgroups * 8 / w;      // 16 wavefronts resident per compute unit
-    int64_t t = (nrb + target - 1) / target;
-    if (t > t_max) t = t_max;
-    if (t < 1 || !single_segment) t = 1;       // several activation segments: one row block per workgroup
-    p.rb_per_wg = (int)t;                       // the most row blocks any workgroup owns
-    // Row blocks are dealt out evenly: workgroup b owns [b * nrb / grid, (b + 1) * nrb / grid).  When
-    // the target number of workgroups can be reached with at most t row blocks each, use exactly the
-    // target (every compute unit then holds the same number of workgroups); else the fewest that do.
-    p.grid = (nrb + t - 1) / t;
-    if (t > 1 && p.grid < target && (int64_t)target * t >= nrb) p.grid = target;
-    p.lds_bytes = (size_t)M * p.seg_blocks * kBytesPerBlockX + (size_t)t * w * M * kBlockRows * sizeof(float);
+    p.rb_per_wg = (int)t;
+    p.step_slots = (int)(w / nsi);
+    p.step_item = (int)(w % nsi);
+    p.lds_bytes = (size_t)M * p.seg_items * kSuper * kBytesPerBlockX + (size_t)t * w * M * kBlockRows * sizeof(float);
     return p;
 }
 
-// A workgroup owns `rb_per_wg` consecutive row blocks; its work items are their weight blocks in
-// memory order (row block major, k block minor).  Wavefront w takes items w, w+W, w+2W, ... and
-// keeps a ring of D of them in flight.  VARIANT != 0 are timing experiments (wrong results).
-template <int G, int M, int W, bool SMALLK = false, int VARIANT = 0, int OCC = 1>
-__global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restrict__ X,
-                                                           const uint4* __restrict__ packed, int64_t N, int64_t K,
-                                                           half_t* __restrict__ Y, int seg_blocks, int rb_per_wg)
+// A workgroup owns up to `rb_per_wg` consecutive row blocks; its work items are (row block, group of
+// four k blocks) in memory order.  Wavefront w takes items w, w+W, w+2W, ...
+template <int G, int M, int W>
+__global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__ X, const uint4* __restrict__ packed,
+                                                      int64_t N, int64_t K, half_t* __restrict__ Y, int seg_items,
+                                                      int step_slots, int step_item)
 {
     constexpr int kThreads = W * 64;
-    // fewer blocks in flight when the accumulators need the registers
-    constexpr int D = VARIANT == 3 ? 8 : (VARIANT == 4 ? 6 : (M <= 2 ? kDepth : (M <= 4 ? 3 : 2)));
+    constexpr int PW = block_param_words(G);            // parameter words per k block: 16, 32 or 64
+    constexpr int NPL = kSuper * PW / 64;               // dword loads per lane that fetch a work item's parameters
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int seg_k = seg_blocks * kBlockK;
+    const int seg_k = seg_items * kSuper * kBlockK;
     half_t* xs = reinterpret_cast<half_t*>(smem);                               // [M][seg_k]
     // per 32-wide chunk of X: (sum of the chunk, 30 x sum of its elements with k % 8 in 2..5)
     float2* sxs = reinterpret_cast<float2*>(smem + (size_t)M * seg_k * 2);      // [M][seg_k/32]
@@ -98,86 +116,108 @@ __global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restr
     const uint32_t fmask = frac_mask_vgpr(), fmask_low = frac_mask_low_vgpr();
     const PackedLayout<G> lay(K);
     const int nkb = (int)lay.nkb;
+    const int nsi = (nkb + kSuper - 1) / kSuper;
     const int64_t nrb = row_blocks(N);
-    const int64_t rb0 = (int64_t)blockIdx.x * nrb / gridDim.x;      // even deal of row blocks (<= rb_per_wg each)
+    const int64_t rb0 = (int64_t)blockIdx.x * nrb / gridDim.x;      // even deal of row blocks
     const int n_rb = (int)((int64_t)(blockIdx.x + 1) * nrb / gridDim.x - rb0);
-    const int nitems = n_rb * nkb;
     // Weights are read with buffer loads: a wavefront-uniform resource (base of this workgroup's run
     // of row blocks, far smaller than 2 GiB), a scalar offset per block and a constant lane offset.
+    // Every address is clamped into the run by hand; nothing relies on the resource's range check.
     const __amdgpu_buffer_rsrc_t wg_codes = make_rsrc(packed + lay.code_index(rb0, 0));
     const __amdgpu_buffer_rsrc_t wg_params = make_rsrc(reinterpret_cast<const char*>(packed) + 4 * lay.param_index(rb0, 0));
     const uint32_t rb_stride = (uint32_t)nkb * block_bytes(G);                  // bytes from one row block to the next
-    const uint32_t lane_code_off = lane * 16, lane_param_off = lay.param_slot(q, r) * 4;
-    // step a (row block slot, k block) cursor by W items; W <= nkb unless SMALLK
-    auto advance = [&](int& s_, int& k_) {
-        k_ += W;
-        if (SMALLK) {
-            while (k_ >= nkb) { k_ -= nkb; ++s_; }
-        } else if (k_ >= nkb) {
-            k_ -= nkb;
+    const uint32_t lane_code_off = lane * 16;
+    // Parameters of a work item: its 4*PW words are contiguous; load n gives lane l word 64n + l, and
+    // block j of lane (q, r) needs word j*PW + slot(q, r), i.e. load (j*PW)/64, lane (j*PW)%64 + slot.
+    const int pslot = lay.param_slot(q, r);
+    const int param_words_rb = nkb * PW;                // parameter words of one row block
+
+    auto advance = [&](int& s_, int& i_) {              // W work items ahead
+        s_ += step_slots;
+        i_ += step_item;
+        if (i_ >= nsi) {
+            i_ -= nsi;
             ++s_;
         }
     };
+    int slot = 0, si = wave;                            // current work item: row block slot, item inside the row block
+    while (si >= nsi) {
+        si -= nsi;
+        ++slot;
+    }
+    int nslot = slot, nitem = si;                       // the one after
+    advance(nslot, nitem);
 
-    // ---- activations of the first segment: request them before the weights so that they are not
-    // queued behind a ring full of weight blocks (loads return in order)
+    // ---- activations
     const int pieces = seg_k / 8;                       // 16-byte pieces per row of X per segment
-    auto x_piece = [&](int idx, int sb) {
+    auto x_piece = [&](int idx, int kb_first) {
         const int m = idx / pieces, pc = idx % pieces;
-        const int64_t k = (int64_t)sb * kBlockK + pc * 8;
+        const int64_t k = (int64_t)kb_first * kBlockK + pc * 8;
         half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (VARIANT < 5 && idx < M * pieces && k < K) v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+        if (idx < M * pieces && k < K) v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
         return v;
     };
-    // store one piece and, from every fourth lane, the two sums of its 32-wide chunk (a piece is the
-    // k range of one code word: elements 2..5 meet the code pairs that are read at 1/128 scale)
-    auto x_store = [&](int idx, const half8_t& v) {
-        const int m = idx / pieces, pc = idx % pieces;
+    // the two sums of one piece (a piece is the k range of one code word: elements 2..5 meet the code
+    // pairs that are read at 1/128 scale)
+    auto piece_sums = [&](const half8_t& v, float& s, float& sl) {
         const half2_t ones = {(half_t)1.f, (half_t)1.f};
         const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
-        float sl = __builtin_amdgcn_fdot2(x1, ones, 0.f, false);
+        sl = __builtin_amdgcn_fdot2(x1, ones, sl, false);
         sl = __builtin_amdgcn_fdot2(x2, ones, sl, false);
-        float s = __builtin_amdgcn_fdot2(x0, ones, sl, false);
+        s = __builtin_amdgcn_fdot2(x0, ones, s, false);
         s = __builtin_amdgcn_fdot2(x3, ones, s, false);
+    };
+    // store one piece and, from every fourth lane, the two sums of its 32-wide chunk
+    auto x_store = [&](int idx, const half8_t& v) {
+        const int m = idx / pieces, pc = idx % pieces;
+        float s = 0.f, sl = 0.f;
+        piece_sums(v, s, sl);
+        s += sl;
         s += __shfl_xor(s, 1);
         sl += __shfl_xor(sl, 1);
         s += __shfl_xor(s, 2);
         sl += __shfl_xor(sl, 2);
-        if (VARIANT < 5 && idx < M * pieces) {
+        if (idx < M * pieces) {
             *reinterpret_cast<half8_t*>(&xs[m * seg_k + pc * 8]) = v;
             if ((pc & 3) == 0) sxs[m * (seg_k / kCodesPerChunk) + (pc >> 2)] = make_float2(s, 30.f * sl);
         }
     };
+    // requested before the weights so that they are not queued behind them (loads return in order);
+    // what two pieces per thread do not cover (large M * K) is staged right away
     half8_t xearly[kEarlyX];
 #pragma unroll
     for (int e = 0; e < kEarlyX; ++e) xearly[e] = x_piece(t + e * kThreads, 0);
+    for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0));
 
-    // ---- ring of weight blocks
-    uint4 c[D];
-    uint32_t pw[D];
-    int fs = 0, fk = wave;                              // fetch cursor (row block slot, k block)
-    if (SMALLK) while (fk >= nkb) { fk -= nkb; ++fs; }
-    auto fetch = [&](uint4& cd, uint32_t& pwd) {        // past the end the last block is read again
+    // ---- the work item in flight: four code blocks and the parameter words
+    uint4 c[kSuper];
+    uint32_t pwraw[NPL];
+    auto fetch_params = [&](int fs, int fi) {           // past the end the last item is read again
         const bool in = fs < n_rb;
-        const uint32_t s_ = in ? fs : n_rb - 1, k_ = in ? fk : nkb - 1;
-        const uint32_t row_off = __builtin_amdgcn_readfirstlane(s_ * rb_stride);
-        const u32x4 cv = __builtin_amdgcn_raw_buffer_load_b128(wg_codes, (int)lane_code_off,
-                                                               (int)(row_off + k_ * kBlockCodeBytes), 0);
-        cd = make_uint4(cv.x, cv.y, cv.z, cv.w);
-        if (VARIANT >= 6) pwd = 0x3c003c00u;
-        else
-            pwd = __builtin_amdgcn_raw_buffer_load_b32(wg_params, (int)lane_param_off,
-                                                       (int)(row_off + k_ * (4 * lay.kParamWords)), 0);
-        advance(fs, fk);
-    };
+        const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(s_ * rb_stride + i_ * (kSuper * PW * 4));
+        const int last = param_words_rb - 1 - (int)i_ * (kSuper * PW);       // words left in this row block
 #pragma unroll
-    for (int d = 0; d < D; ++d) fetch(c[d], pw[d]);
+        for (int n = 0; n < NPL; ++n)
+            pwraw[n] = __builtin_amdgcn_raw_buffer_load_b32(wg_params, min(n * 64 + lane, last) * 4, (int)soff, 0);
+    };
+    auto fetch_code = [&](int j, int fs, int fi) {      // k blocks beyond K: the last block again (their X is zero)
+        const bool in = fs < n_rb;
+        const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
+        const uint32_t kb = min(i_ * kSuper + j, (uint32_t)nkb - 1);
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(s_ * rb_stride + kb * kBlockCodeBytes);
+        const u32x4 cv = __builtin_amdgcn_raw_buffer_load_b128(wg_codes, (int)lane_code_off, (int)soff, 0);
+        c[j] = make_uint4(cv.x, cv.y, cv.z, cv.w);
+    };
+    fetch_params(slot, si);
+#pragma unroll
+    for (int j = 0; j < kSuper; ++j) fetch_code(j, slot, si);
 
-    int i = wave;                                       // current item, as flat index and (row block slot, k block)
-    int slot = 0, kb = wave;
-    if (SMALLK) while (kb >= nkb) { kb -= nkb; ++slot; }
-
-    for (int j = t; j < n_rb * W * M * kBlockRows; j += kThreads) red[j] = 0.f;
+    // every wavefront clears its own partial sums (it may not visit every row block)
+    if (lane < kBlockRows)
+        for (int sl = 0; sl < n_rb; ++sl)
+#pragma unroll
+            for (int m = 0; m < M; ++m) red[((sl * W + wave) * M + m) * kBlockRows + lane] = 0.f;
 
     float acc[M];
 #pragma unroll
@@ -195,44 +235,42 @@ __global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restr
         }
     };
 
-    for (int sb = 0; sb < nkb; sb += seg_blocks) {
-        // stage the segment's activations and the sum of every 32-wide chunk
-        if (sb == 0) {
+    for (int seg0 = 0; seg0 < nsi; seg0 += seg_items) {
+        // stage the segment's activations and the sums of every 32-wide chunk
+        if (seg0 == 0) {
 #pragma unroll
             for (int e = 0; e < kEarlyX; ++e) x_store(t + e * kThreads, xearly[e]);
-            if (VARIANT < 5)
-                for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0));
         } else {
             __syncthreads();                            // everyone is done with the previous segment's activations
-            fs = slot;                                  // refill the ring from the current item
-            fk = kb;
-#pragma unroll
-            for (int d = 0; d < D; ++d) fetch(c[d], pw[d]);
-            for (int idx = t; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, sb));
+            for (int idx = t; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, seg0 * kSuper));
         }
-        if (VARIANT < 5) __syncthreads();
-
-        // one item: its codes and parameter word are in a ring slot
-        auto process = [&](const uint4& cd, const uint32_t pwd) {
-            const float sc = (float)param_scale(pwd);
-            const float bi = (float)param_bias(pwd);
-            const uint32_t words[4] = {cd.x, cd.y, cd.z, cd.w};
-            const int xoff = (kb - sb) * kBlockK + q * kCodesPerChunk;
-            float a[M][2];          // per row of X: sum x*(2 + c/8) over code pairs 0 and 3, sum x*(2 + c/128) over 1 and 2
+        __syncthreads();
+        const int seg_end = seg0 + seg_items;
+        while (slot < n_rb && si < seg_end) {
+            // the item's parameter words, then request the next item's
+            uint32_t pwj[kSuper];
 #pragma unroll
-            for (int m = 0; m < M; ++m) a[m][0] = a[m][1] = 0.f;
-            if (VARIANT == 1 || VARIANT >= 5) {         // timing experiment: stream only, no arithmetic
-                acc[0] += __builtin_bit_cast(float, words[0] ^ words[1] ^ words[2] ^ words[3]) * sc;
-            } else {
+            for (int j = 0; j < kSuper; ++j) {
+                if (G == 32) pwj[j] = pwraw[j];
+                else pwj[j] = (uint32_t)__builtin_amdgcn_ds_bpermute((((j * PW) % 64) + pslot) * 4, (int)pwraw[(j * PW) / 64]);
+            }
+            fetch_params(nslot, nitem);
+#pragma unroll
+            for (int j = 0; j < kSuper; ++j) {
+                const float sc = (float)param_scale(pwj[j]);
+                const float bi = (float)param_bias(pwj[j]);
+                const uint32_t words[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
+                const int xoff = ((si - seg0) * kSuper + j) * kBlockK + q * kCodesPerChunk;
+                float a[M][2];      // per row of X: sum x*(2 + c/8) over code pairs 0 and 3, sum x*(2 + c/128) over 1 and 2
+#pragma unroll
+                for (int m = 0; m < M; ++m) a[m][0] = a[m][1] = 0.f;
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     half2_t p[4];
                     w1_pairs_mixed(words[w], fmask, fmask_low, p);
 #pragma unroll
                     for (int m = 0; m < M; ++m) {
-                        half8_t xv;
-                        if (VARIANT == 2) xv = half8_t{1, 1, 1, 1, 1, 1, 1, 1};     // timing experiment: no LDS reads
-                        else xv = *reinterpret_cast<const half8_t*>(&xs[m * seg_k + xoff + 8 * w]);
+                        const half8_t xv = *reinterpret_cast<const half8_t*>(&xs[m * seg_k + xoff + 8 * w]);
                         const half2_t x0 = {xv[0], xv[1]}, x1 = {xv[2], xv[3]}, x2 = {xv[4], xv[5]}, x3 = {xv[6], xv[7]};
                         a[m][0] = __builtin_amdgcn_fdot2(p[0], x0, a[m][0], false);
                         a[m][1] = __builtin_amdgcn_fdot2(p[1], x1, a[m][1], false);
@@ -240,38 +278,20 @@ __global__ __launch_bounds__(W * 64, OCC) void gemv_kernel(const half_t* __restr
                         a[m][0] = __builtin_amdgcn_fdot2(p[3], x3, a[m][0], false);
                     }
                 }
+                fetch_code(j, nslot, nitem);            // the block's registers are free: request the next item's
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
                     // sum x*w1 = a0 + 16*a1 - 30*(sum of x over pairs 1 and 2); then the group's affine map
-                    const float2 sx = VARIANT == 2 ? make_float2(32.f, 480.f) : sxs[m * (seg_k / kCodesPerChunk) + (xoff >> 5)];
+                    const float2 sx = sxs[m * (seg_k / kCodesPerChunk) + (xoff >> 5)];
                     acc[m] += sc * ((a[m][0] + 16.f * a[m][1] - sx.y) - bi * sx.x);
                 }
             }
-            i += W;
             const int prev = slot;
-            advance(slot, kb);
-            if (VARIANT < 7 && slot != prev) flush(prev);       // the next item belongs to a later row block
-        };
-
-        // with one segment the loop runs over all items; otherwise (one row block) up to the segment's end
-        const int limit = seg_blocks >= nkb ? nitems : min(sb + seg_blocks, nkb);
-        // Entering the steady-state loop with nothing but the ring outstanding lets the compiler's
-        // wait-count bookkeeping keep D blocks in flight across the back edge (vmcnt(0), others free).
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        while (i + (D - 1) * W < limit) {               // full turns of the ring, refilled as it is consumed
-#pragma unroll
-            for (int d = 0; d < D; ++d) {
-                process(c[d], pw[d]);
-                fetch(c[d], pw[d]);
-            }
+            slot = nslot;
+            si = nitem;
+            advance(nslot, nitem);
+            if (slot != prev) flush(prev);              // the next item belongs to a later row block
         }
-#pragma unroll
-        for (int d = 0; d < D; ++d)                     // last partial turn
-            if (i < limit) process(c[d], pw[d]);
-    }
-    if (VARIANT >= 7) {
-        if (acc[0] == 1.2345f) Y[t] = (half_t)acc[0];
-        return;
     }
     if (slot < n_rb) flush(slot);                       // sums of a row block this wavefront left unfinished (several segments)
     __syncthreads();
@@ -292,37 +312,8 @@ int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, 
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     const dim3 grid((unsigned)p.grid), block(W * 64);
-    const int dbg = (G == 128 && M == 1 && W >= 8) ? knob("gemv_debug") : 0;     // timing experiments only
-    if (W == 4 && k_blocks(K) < W)                      // K < 512: the generic cursor
-        hipLaunchKernelGGL((gemv_kernel<G, M, 4, true>), grid, block, p.lds_bytes, stream, x, c, N, K, y, p.seg_blocks,
-                           p.rb_per_wg);
-    else if (dbg == 1)
-        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 1>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
-                           p.seg_blocks, p.rb_per_wg);
-    else if (dbg == 2)
-        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 2>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
-                           p.seg_blocks, p.rb_per_wg);
-    else if (dbg == 3)
-        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 3>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
-                           p.seg_blocks, p.rb_per_wg);
-    else if (dbg == 4)
-        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 4>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
-                           p.seg_blocks, p.rb_per_wg);
-    else if (dbg == 5)
-        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 5>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
-                           p.seg_blocks, p.rb_per_wg);
-    else if (dbg == 6)
-        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 6>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
-                           p.seg_blocks, p.rb_per_wg);
-    else if (dbg == 7)
-        hipLaunchKernelGGL((gemv_kernel<128, 1, W, false, 7>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
-                           p.seg_blocks, p.rb_per_wg);
-    else if (M == 1 && knob("gemv_occ") == 8)           // experiment: cap registers for 8 wavefronts per SIMD
-        hipLaunchKernelGGL((gemv_kernel<G, 1, W, false, 0, 8>), grid, block, p.lds_bytes, stream, x, c, N, K, y,
-                           p.seg_blocks, p.rb_per_wg);
-    else
-        hipLaunchKernelGGL((gemv_kernel<G, M, W>), grid, block, p.lds_bytes, stream, x, c, N, K, y, p.seg_blocks,
-                           p.rb_per_wg);
+    hipLaunchKernelGGL((gemv_kernel<G, M, W>), grid, block, p.lds_bytes, stream, x, c, N, K, y, p.seg_items,
+                       p.step_slots, p.step_item);
     return check_launch();
 }
 
@@ -332,7 +323,9 @@ int launch_w(const GemvPlan& p, const void* X, const void* packed, int64_t N, in
     switch (p.waves) {
         case 4: return launch_one<G, M, 4>(p, X, packed, N, K, Y, stream);
         case 8: return launch_one<G, M, 8>(p, X, packed, N, K, Y, stream);
-        default: return launch_one<G, M, 16>(p, X, packed, N, K, Y, stream);
+        default:
+            if constexpr (M <= 4) return launch_one<G, M, 16>(p, X, packed, N, K, Y, stream);
+            else return E0M4_ERR_SHAPE;                 // make_plan never asks for this
     }
 }
 

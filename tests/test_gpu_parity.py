@@ -20,7 +20,7 @@ def e0m4():
     import paper_2403_20041_amd as pkg
 
     pkg.lib()                                   # raises if the HIP library is not built
-    for k in ("gemv_waves", "gemm_variant", "gemm_splits"):
+    for k in ("gemv_waves", "gemv_workgroups", "gemm_variant", "gemm_splits"):
         pkg.e0m4_set_knob(k, 0)
     return pkg
 
@@ -197,6 +197,25 @@ def test_gemv_forced_waves_per_workgroup(e0m4, oracle, waves):
         run_matmul_case(e0m4, oracle, 8, 40, 16384, 128, seed=52)      # activations staged in several segments
     finally:
         e0m4.e0m4_set_knob("gemv_waves", 0)
+
+
+@pytest.mark.parametrize("N,K,G", [(4096, 4096, 128), (8192, 2048, 64), (333, 1024, 32), (48, 512, 128),
+                                    (700, 3968, 128)])
+def test_gemv_forced_workgroup_counts(e0m4, oracle, N, K, G):
+    # few workgroups: many row blocks each, dealt unevenly; many: one row block each
+    for target in (0, 7, 100000):
+        e0m4.e0m4_set_knob("gemv_workgroups", target)
+        try:
+            run_matmul_case(e0m4, oracle, 1, N, K, G, seed=N + K + 1)
+        finally:
+            e0m4.e0m4_set_knob("gemv_workgroups", 0)
+
+
+@pytest.mark.parametrize("M", [1, 2, 5, 8])
+def test_gemv_ragged_last_work_item(e0m4, oracle, M):
+    # K = 13 and 14 blocks of 128: the last group of four k blocks holds one or two; N ends inside a row block
+    run_matmul_case(e0m4, oracle, M, 203, 1664, 128, seed=80 + M)
+    run_matmul_case(e0m4, oracle, M, 77, 1760, 32, seed=90 + M)     # K = 13.75 blocks: ragged inside the last block
 
 
 # ------------------------------------------------------------------ matmul, MFMA path
