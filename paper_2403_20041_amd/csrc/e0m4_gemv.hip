@@ -45,6 +45,7 @@ struct GemvPlan {
     int step_slots;     // a wavefront's next work item: this many row blocks further ...
     int step_item;      // ... and this many items further (with carry), i.e. W items ahead
     int64_t grid;
+    int rb_base, rb_rem;  // even deal of row blocks: workgroup b owns rb_base (+1 if b < rb_rem) consecutive row blocks
     size_t lds_bytes;
 };
 
@@ -75,7 +76,7 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
         t = (nrb + target - 1) / target;
         if (t > t_max) t = t_max;
         if (t < 1 || !single_segment) t = 1;   // several activation segments: one row block per workgroup
-        // Row blocks are dealt out evenly: workgroup b owns [b * nrb / grid, (b + 1) * nrb / grid).  When
+        // Row blocks are dealt out evenly (the first nrb % grid workgroups own one more).  When
         // the target number of workgroups can be reached with at most t row blocks each, use exactly the
         // target (every compute unit then holds the same number of workgroups); else the fewest that do.
         p.grid = (nrb + t - 1) / t;
@@ -88,6 +89,8 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
     p.rb_per_wg = (int)t;
     p.step_slots = (int)(w / nsi);
     p.step_item = (int)(w % nsi);
+    p.rb_base = (int)(nrb / p.grid);
+    p.rb_rem = (int)(nrb % p.grid);
     p.lds_bytes = (size_t)M * p.seg_items * kSuper * kBytesPerBlockX + (size_t)t * w * M * kBlockRows * sizeof(float);
     return p;
 }
@@ -97,7 +100,7 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
 template <int G, int M, int W>
 __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__ X, const uint4* __restrict__ packed,
                                                       int64_t N, int64_t K, half_t* __restrict__ Y, int seg_items,
-                                                      int step_slots, int step_item)
+                                                      int step_slots, int step_item, int rb_base, int rb_rem)
 {
     constexpr int kThreads = W * 64;
     constexpr int PW = block_param_words(G);            // parameter words per k block: 16, 32 or 64
@@ -117,9 +120,8 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     const PackedLayout<G> lay(K);
     const int nkb = (int)lay.nkb;
     const int nsi = (nkb + kSuper - 1) / kSuper;
-    const int64_t nrb = row_blocks(N);
-    const int64_t rb0 = (int64_t)blockIdx.x * nrb / gridDim.x;      // even deal of row blocks
-    const int n_rb = (int)((int64_t)(blockIdx.x + 1) * nrb / gridDim.x - rb0);
+    const int64_t rb0 = (int64_t)blockIdx.x * rb_base + min((int)blockIdx.x, rb_rem);    // even deal of row blocks
+    const int n_rb = rb_base + ((int)blockIdx.x < rb_rem ? 1 : 0);
     // Weights are read with buffer loads: a wavefront-uniform resource (base of this workgroup's run
     // of row blocks, far smaller than 2 GiB), a scalar offset per block and a constant lane offset.
     // Every address is clamped into the run by hand; nothing relies on the resource's range check.
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     // ---- activations
     const int pieces = seg_k / 8;                       // 16-byte pieces per row of X per segment
     auto x_piece = [&](int idx, int kb_first) {
-        const int m = idx / pieces, pc = idx % pieces;
+        const int m = M == 1 ? 0 : idx / pieces, pc = M == 1 ? idx : idx % pieces;
         const int64_t k = (int64_t)kb_first * kBlockK + pc * 8;
         half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
         if (idx < M * pieces && k < K) v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     };
     // store one piece and, from every fourth lane, the two sums of its 32-wide chunk
     auto x_store = [&](int idx, const half8_t& v) {
-        const int m = idx / pieces, pc = idx % pieces;
+        const int m = M == 1 ? 0 : idx / pieces, pc = M == 1 ? idx : idx % pieces;
         float s = 0.f, sl = 0.f;
         piece_sums(v, s, sl);
         s += sl;
@@ -182,8 +184,9 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
             if ((pc & 3) == 0) sxs[m * (seg_k / kCodesPerChunk) + (pc >> 2)] = make_float2(s, 30.f * sl);
         }
     };
-    // requested before the weights so that they are not queued behind them (loads return in order);
-    // what two pieces per thread do not cover (large M * K) is staged right away
+    // Two pieces of X per thread are requested before the weights, so that they are not queued behind
+    // them (loads return in order; requesting the weights first was measured slower).  What two pieces
+    // per thread do not cover (large M * K) is staged right away.
     half8_t xearly[kEarlyX];
 #pragma unroll
     for (int e = 0; e < kEarlyX; ++e) xearly[e] = x_piece(t + e * kThreads, 0);
@@ -313,7 +316,7 @@ int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, 
     half_t* y = static_cast<half_t*>(Y);
     const dim3 grid((unsigned)p.grid), block(W * 64);
     hipLaunchKernelGGL((gemv_kernel<G, M, W>), grid, block, p.lds_bytes, stream, x, c, N, K, y, p.seg_items,
-                       p.step_slots, p.step_item);
+                       p.step_slots, p.step_item, p.rb_base, p.rb_rem);
     return check_launch();
 }
 
