@@ -14,7 +14,10 @@
 //     {32+8s..32+8s+7}; the activation fragment of the same MFMA is piece 4h+s of the row.
 //   - one barrier per slice, placed after sub-step 1, separates the LDS write of slice kt+1 from
 //     the fragment reads that start in sub-step 3.
-// The LDS tile is 128-byte rows whose eight 16-byte pieces are XOR-swizzled with the row number.
+// The LDS tile is 128-byte rows whose eight 16-byte pieces are XOR-swizzled with (row / 2) % 8: the
+// LDS of gfx950 serves a 16-byte-per-lane read 16 lanes (256 bytes, two rows of the tile) at a time,
+// so 16 consecutive rows have to land in 16 different 16-byte bank groups (swizzling with row % 8, the
+// right choice for 128-byte-wide LDS, costs 40 % more LDS cycles here, all of them bank conflicts).
 #include "e0m4_device.h"
 #include "e0m4_host.h"
 
@@ -41,11 +44,11 @@ __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2
 // WGM x WGN wavefronts share the tile: 2 x 2 (one per SIMD, 128 x 128 each) or 2 x 4 (two per SIMD,
 // 128 x 64 each, which doubles the instruction issue capacity and lets one wavefront's waits hide
 // behind the other's MFMAs, for twice the activation fragment traffic).
-template <int G, int WGM, int WGN>
+template <int G, int WGM, int WGN, int DBG = 0>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
                                                              const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                              half_t* __restrict__ Y, int m_tiles, int n_tiles,
-                                                             int splits, float* __restrict__ partial)
+                                                             int splits, float* __restrict__ partial, int dbg)
 {
     constexpr int kThreads = 64 * WGM * WGN;
     constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);      // 32x32 MFMA blocks per wavefront
@@ -58,8 +61,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
     const int item = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
     if (item >= total) return;
-    const int tile = item / splits, split = item % splits;
-    // (the quotient and remainder are computed on the vector unit; move them to scalar registers)
+    // (quotients and remainders are computed on the vector unit; move them to scalar registers, or
+    // everything derived from them, the K loop counter included, is treated as divergent and every
+    // buffer load below turns into a per-lane loop)
+    const int tile = __builtin_amdgcn_readfirstlane(item / splits);
+    const int split = __builtin_amdgcn_readfirstlane(item % splits);
     const int64_t m0 = (int64_t)__builtin_amdgcn_readfirstlane(tile % m_tiles) * BM;
     const int64_t n0 = (int64_t)__builtin_amdgcn_readfirstlane(tile / m_tiles) * BN;
 
@@ -73,8 +79,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     const int KT = (int)(K / BK);                       // K % 128 == 0 is required by the launcher: KT is even
     // this work item's K slices [kt_begin, kt_end): whole pairs of slices, spread evenly over the splits
     const int pairs = KT / 2;
-    const int kt_begin = 2 * (int)((int64_t)pairs * split / splits);
-    const int kt_end = 2 * (int)((int64_t)pairs * (split + 1) / splits);
+    const int kt_begin = __builtin_amdgcn_readfirstlane(2 * (int)((int64_t)pairs * split / splits));
+    const int kt_end = __builtin_amdgcn_readfirstlane(2 * (int)((int64_t)pairs * (split + 1) / splits));
 
     // ---- activation loader: 8 lanes cover one 128-byte row slice; pass p handles row RP*p + t/8.
     // Rows beyond M are clamped (their products are never stored).
@@ -88,7 +94,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     for (int p = 0; p < PA; ++p)
         a_pass_off[p] = (uint32_t)((min((int64_t)(a_row + RP * p), M - 1 - m0) * K + a_piece * 8) * 2);
     // LDS write position of this thread's piece (pass p adds RP rows)
-    const uint32_t a_lds_off = (uint32_t)(a_row * kRowBytes + ((a_piece ^ (a_row & 7)) << 4));
+    const uint32_t a_lds_off = (uint32_t)(a_row * kRowBytes + ((a_piece ^ ((a_row >> 1) & 7)) << 4));
 
     // ---- weight loader: operand block j of this wavefront covers rows n0 + wn + 32j .. +31
     const int b_h = lane >> 5, b_r = lane & 15;
@@ -109,7 +115,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     uint32_t frag_off[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s)
-        frag_off[s] = (uint32_t)((wm + (lane & 31)) * kRowBytes + (((4 * b_h + s) ^ (lane & 7)) << 4));
+        frag_off[s] = (uint32_t)((wm + (lane & 31)) * kRowBytes + (((4 * b_h + s) ^ ((lane >> 1) & 7)) << 4));
 
     u32x4 a_reg[PA];
     u32x4 bset[2][TN];
@@ -117,13 +123,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     half8_t fa[2][TM], fb[2][TN];
 
     auto load_a = [&](int kt) {
-        const uint32_t k0 = (uint32_t)min(kt, KT - 1) * BK;
+        const uint32_t k0 = (dbg & 1) ? 0u : (uint32_t)min(kt, KT - 1) * BK;
 #pragma unroll
         for (int p = 0; p < PA; ++p)
             a_reg[p] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_pass_off[p], (int)(k0 * 2), 0);
     };
     auto load_b = [&](int kt, int set) {
-        const uint32_t k0 = (uint32_t)min(kt, KT - 1) * BK;
+        const uint32_t k0 = (dbg & 2) ? 0u : (uint32_t)min(kt, KT - 1) * BK;
         // chunk (k0/32) of the row block's codes starts (k0/32)*256 bytes in; the parameter words of
         // group k0/G start (k0/G)*64 bytes into the row block's parameters
         const int code_soff = (int)((k0 / kCodesPerChunk) * (kBlockRows * 16));
@@ -141,6 +147,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     };
     auto read_frags = [&](uint32_t stage_off, int s, half8_t (&dst)[TM]) {
         const unsigned char* base = smem + stage_off + frag_off[s];
+        if (DBG & 16) return;
 #pragma unroll
         for (int i = 0; i < TM; ++i) dst[i] = *reinterpret_cast<const half8_t*>(base + i * 32 * kRowBytes);
     };
@@ -148,6 +155,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const uint32_t word = bset[set][j][s];
+            if (DBG & 8) {
+                const uint32_t o4[4] = {word, word ^ pwset[set][j], word, word};
+                dst[j] = *reinterpret_cast<const half8_t*>(o4);
+                continue;
+            }
             const half_t sc = param_scale(pwset[set][j]), bi = param_bias(pwset[set][j]);
             const half2_t s2 = {sc, sc}, b2 = {bi, bi};
             half2_t o[4];
@@ -175,6 +187,24 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
     };
 
+    // Instruction order inside one sub-step: after every MFMA a few of the vector instructions that
+    // prepare the next sub-step's operands, so that a single wavefront keeps the matrix pipe busy
+    // (an MFMA of this shape occupies it for 32 cycles, its issue only for 4).
+    auto interleave = [&](auto dsw, auto vmem) {
+        constexpr int kMfma = TM * TN;
+#pragma unroll
+        for (int i = 0; i < kMfma; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // one MFMA
+            if (i < TM) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // one LDS fragment read
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);          // vector ALU
+            if (i < decltype(dsw)::value) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);    // LDS write
+            if (i < decltype(vmem)::value) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // global load
+        }
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using IPA = std::integral_constant<int, PA>;
+    using ITN2 = std::integral_constant<int, 2 * TN>;
+
     // One K slice.  On entry: stage `cur` holds slice kt; fa[0], fb[0] hold its sub-step 0 operands;
     // bset[set] holds its codes; bset[set^1] and a_reg are in flight for slice kt+1.
     auto step = [&](int kt, int set, uint32_t cur, uint32_t nxt) {
@@ -185,13 +215,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
         store_a(nxt);
         load_a(kt + 2);
         mfma_block(fa[0], fb[0]);
+        interleave(IPA{}, IPA{});
         __builtin_amdgcn_sched_barrier(0);
         // sub-step 1: operands of sub-step 2
         read_frags(cur, 2, fa[0]);
         dequant_frags(set, 2, fb[0]);
         mfma_block(fa[1], fb[1]);
+        interleave(I0{}, I0{});
         __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();                                // slice kt+1 is complete in stage `nxt`
+        if (!(DBG & 4)) __syncthreads();                // slice kt+1 is complete in stage `nxt`
         __builtin_amdgcn_sched_barrier(0);
         // sub-step 2: operands of sub-step 3 (last use of this slice's codes, so the codes of
         // slice kt+2 can be requested into the same registers)
@@ -199,11 +231,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
         dequant_frags(set, 3, fb[1]);
         load_b(kt + 2, set);
         mfma_block(fa[0], fb[0]);
+        interleave(I0{}, ITN2{});
         __builtin_amdgcn_sched_barrier(0);
         // sub-step 3: operands of the next slice's sub-step 0
         read_frags(nxt, 0, fa[0]);
         dequant_frags(set ^ 1, 0, fb[0]);
         mfma_block(fa[1], fb[1]);
+        interleave(I0{}, I0{});
         __builtin_amdgcn_sched_barrier(0);
     };
 
@@ -312,8 +346,23 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
         if (e != hipSuccess) return record_hip_error(e);
         attr_set = true;
     }
+    const int dbg = knob("gemm_debug");
+    if (G == 128 && (dbg & 28)) {
+        static bool attr2 = false;
+        auto launch_dbg = [&](auto kern) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * kNumXcd)), dim3(64 * WGM * WGN), lds, stream, x, M, c, N, K, y,
+                               (int)m_tiles, (int)n_tiles, splits, partial, dbg);
+        };
+        (void)attr2;
+        if ((dbg & 28) == 4) launch_dbg(&gemm_pipe_kernel<128, WGM, WGN, 4>);
+        else if ((dbg & 28) == 8) launch_dbg(&gemm_pipe_kernel<128, WGM, WGN, 8>);
+        else if ((dbg & 28) == 16) launch_dbg(&gemm_pipe_kernel<128, WGM, WGN, 16>);
+        else launch_dbg(&gemm_pipe_kernel<128, WGM, WGN, 28>);
+        return check_launch();
+    }
     hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(64 * WGM * WGN), lds,
-                       stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial);
+                       stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial, dbg);
     int rc = check_launch();
     if (rc != E0M4_OK || splits == 1) return rc;
     const int64_t count = M * N;
