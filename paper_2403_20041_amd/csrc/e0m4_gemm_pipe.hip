@@ -225,19 +225,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
         __builtin_amdgcn_sched_barrier(0);
         if (!(DBG & 4)) __syncthreads();                // slice kt+1 is complete in stage `nxt`
         __builtin_amdgcn_sched_barrier(0);
-        // sub-step 2: operands of sub-step 3 (last use of this slice's codes, so the codes of
-        // slice kt+2 can be requested into the same registers)
+        // sub-step 2: operands of sub-step 3 (last use of this slice's codes)
         read_frags(cur, 3, fa[1]);
         dequant_frags(set, 3, fb[1]);
-        load_b(kt + 2, set);
         mfma_block(fa[0], fb[0]);
-        interleave(I0{}, ITN2{});
+        interleave(I0{}, I0{});
         __builtin_amdgcn_sched_barrier(0);
-        // sub-step 3: operands of the next slice's sub-step 0
+        // sub-step 3: operands of the next slice's sub-step 0; this slice's code registers are free,
+        // so the codes of slice kt+2 are requested into them
+        load_b(kt + 2, set);
         read_frags(nxt, 0, fa[0]);
         dequant_frags(set ^ 1, 0, fb[0]);
         mfma_block(fa[1], fb[1]);
-        interleave(I0{}, I0{});
+        interleave(I0{}, ITN2{});
         __builtin_amdgcn_sched_barrier(0);
     };
 
