@@ -20,7 +20,6 @@ struct Knob {
 Knob g_knobs[] = {
     {"gemv_waves", {0}},               // wavefronts per workgroup of the small-M kernel (4, 8 or 16)
     {"gemv_workgroups", {0}},          // target number of workgroups of the small-M kernel
-    {"gemm_debug", {0}},               // timing experiments (wrong results)
     {"gemm_variant", {0}},             // select a GEMM kernel variant
     {"gemm_splits", {0}},              // force the number of K splits of the pipelined GEMM kernel
 };

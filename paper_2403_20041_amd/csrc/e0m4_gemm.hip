@@ -3,15 +3,20 @@
 // product of the prefill stage, bound by compute) with the dequantisation of
 // section "E0M4 FP4 quantization" fused into the tile loader.
 //
+// This file holds the dispatch between the two GEMM kernels and the small-tile
+// kernel, used for problems too small to fill the chip with 256 x 256 tiles and
+// for K that is not a multiple of 128 (the pipelined kernel is in
+// e0m4_gemm_pipe.hip).
+//
 // A workgroup (4 wavefronts, 2 x 2) owns a BM x BN tile of Y and walks K in
 // slices of 64.  Per slice the activations go global -> registers -> LDS
 // unchanged; the weight codes go global -> registers -> (shift, mask-or with
 // the exponent, minus bias, times scale: packed fp16, one rounding, the same
 // bits e0m4_dequant produces) -> LDS.  Both tiles are K-contiguous, so every
 // MFMA operand is one 16-byte LDS read per lane; rows are 128 bytes and the
-// eight 16-byte pieces of a row are XOR-swizzled with the row number, which
-// keeps those reads (32 rows at one k offset) and the loader's writes free of
-// bank conflicts without padding.  Two LDS stages: the next slice is loaded
+// eight 16-byte pieces of a row are XOR-swizzled with half the row number,
+// which keeps those reads (32 rows at one k offset) and the loader's writes
+// free of bank conflicts without padding.  Two LDS stages: the next slice is loaded
 // into registers while the current one feeds v_mfma_f32_32x32x16_f16, written
 // to the other stage, and one barrier per slice separates the two.
 // Workgroups are numbered so that each XCD (own L2) works on a contiguous run of
@@ -34,7 +39,9 @@ __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2
 }
 
 // byte offset of 16-byte piece `piece` (0..7) of row `row` inside a swizzled tile
-__device__ inline int tile_off(int row, int piece) { return row * kRowBytes + ((piece ^ (row & 7)) << 4); }
+// (swizzled with (row / 2) % 8: the LDS of gfx950 serves 16-byte reads 16 lanes, i.e. 256 bytes or two
+// tile rows, at a time, so 16 consecutive rows must fall into 16 different 16-byte bank groups)
+__device__ inline int tile_off(int row, int piece) { return row * kRowBytes + ((piece ^ ((row >> 1) & 7)) << 4); }
 
 template <int G, int BM, int BN>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict__ X, int64_t M,
@@ -194,186 +201,6 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Variant with the weights kept out of LDS.  Only the activations are staged (swizzled, two
-// stages).  A wavefront reads the codes of its own 32-row x 64-k operand blocks straight from the
-// packed buffer: lane (n = l%32, h = l/32) takes the 16-byte chunk of row n that holds
-// k = 32h .. 32h+31 of the slice, so word s of every lane is exactly the lane's 8 K-values of MFMA
-// number s, whose K set is {8s..8s+7} u {32+8s..32+8s+7}; the activation fragment of the same MFMA
-// is then piece 4h+s of the row.  Each word is dequantised in registers (16 VALU operations) right
-// before it is consumed, in the shadow of the previous MFMAs.  LDS traffic drops to the activations
-// alone, at the price of dequantising each weight once per pair of wavefronts that share it.
-template <int G, int BM, int BN>
-__global__ __launch_bounds__(kThreads) void gemm_direct_kernel(const half_t* __restrict__ X, int64_t M,
-                                                               const uint4* __restrict__ packed, int64_t N, int64_t K,
-                                                               half_t* __restrict__ Y, int m_tiles, int n_tiles)
-{
-    constexpr int TM = BM / 64, TN = BN / 64;
-    constexpr int PA = BM / 32;
-    constexpr int A_BYTES = BM * kRowBytes;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-    const int total = m_tiles * n_tiles;
-    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
-    const int tile = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
-    if (tile >= total) return;
-    const int64_t m0 = (int64_t)(tile % m_tiles) * BM, n0 = (int64_t)(tile / m_tiles) * BN;
-
-    const int t = threadIdx.x;
-    const int lane = t & 63;
-    const int wave = t >> 6;
-    const uint32_t fmask = frac_mask_vgpr();
-    const PackedLayout<G> lay(K);
-    const int64_t nrb = row_blocks(N);
-    const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
-
-    // A loader (as in gemm_kernel)
-    const int a_row = t >> 3, a_piece = t & 7;
-    const int64_t a_m = min(m0 + a_row, M - 1);
-    const char* a_base = reinterpret_cast<const char*>(X + a_m * K + a_piece * 8);
-    uint32_t a_pass_off[PA];
-#pragma unroll
-    for (int p = 0; p < PA; ++p)
-        a_pass_off[p] = (uint32_t)((min(m0 + a_row + 32 * p, M - 1) - a_m) * K * 2);
-    const bool k_tail = (K % BK) != 0;
-
-    // B loader: operand block j of this wavefront covers rows n0 + wn + 32j .. +31 = two row blocks
-    const int b_h = lane >> 5, b_r = lane & 15;
-    const int64_t rb_first = (n0 + wn) / kBlockRows + ((lane >> 4) & 1);
-    const int64_t rb_c = min(rb_first, nrb - 1);
-    const char* b_code_base = reinterpret_cast<const char*>(packed + lay.code_index(rb_c, 0) + b_h * kBlockRows + b_r);
-    const char* b_param_base = reinterpret_cast<const char*>(packed) + 4 * (lay.param_index(rb_c, 0) + b_r) +
-                               (G == 32 ? b_h * 64 : 0);
-    uint32_t b_blk_off[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-        b_blk_off[j] = (uint32_t)((min(rb_first + 2 * j, nrb - 1) - rb_c) * lay.nkb * block_bytes(G));
-
-    uint4 a_reg[PA];
-    uint4 b_cur[TN], b_nxt[TN];
-    uint32_t pw_cur[TN], pw_nxt[TN];
-
-    auto load_a = [&](int kt) {
-        const uint32_t k0 = (uint32_t)kt * BK;
-        const bool a_ok = !k_tail || (int64_t)k0 + a_piece * 8 < K;
-#pragma unroll
-        for (int p = 0; p < PA; ++p) {
-            a_reg[p] = make_uint4(0, 0, 0, 0);
-            if (a_ok) a_reg[p] = *reinterpret_cast<const uint4*>(a_base + (a_pass_off[p] + k0 * 2));
-        }
-    };
-    auto load_b = [&](int kt, uint4 (&b)[TN], uint32_t (&pw)[TN]) {
-        const uint32_t k0 = (uint32_t)kt * BK;
-        const uint32_t code_off = (k0 / kCodesPerChunk) * (kBlockRows * 16);
-        const uint32_t param_off = (k0 / G) * (kBlockRows * 4);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            b[j] = *reinterpret_cast<const uint4*>(b_code_base + (b_blk_off[j] + code_off));
-            pw[j] = *reinterpret_cast<const uint32_t*>(b_param_base + (b_blk_off[j] + param_off));
-        }
-    };
-    auto store_a = [&](unsigned char* stage) {
-#pragma unroll
-        for (int p = 0; p < PA; ++p)
-            *reinterpret_cast<uint4*>(stage + tile_off(a_row + 32 * p, a_piece)) = a_reg[p];
-    };
-    auto dequant_word = [&](uint32_t word, uint32_t pw) {
-        const half_t sc = param_scale(pw), bi = param_bias(pw);
-        const half2_t s2 = {sc, sc}, b2 = {bi, bi};
-        half2_t o[4];
-        o[0] = dequant_pair(w1_pair<0>(word, fmask), b2, s2);
-        o[1] = dequant_pair(w1_pair<1>(word, fmask), b2, s2);
-        o[2] = dequant_pair(w1_pair<2>(word, fmask), b2, s2);
-        o[3] = dequant_pair(w1_pair<3>(word, fmask), b2, s2);
-        return *reinterpret_cast<const half8_t*>(o);
-    };
-
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    const int frag_row = lane & 31;
-    auto compute = [&](const unsigned char* stage) {
-#pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
-            half8_t a[TM], b[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                a[i] = *reinterpret_cast<const half8_t*>(stage + tile_off(wm + 32 * i + frag_row, 4 * b_h + s));
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const uint32_t word = s == 0 ? b_cur[j].x : (s == 1 ? b_cur[j].y : (s == 2 ? b_cur[j].z : b_cur[j].w));
-                b[j] = dequant_word(word, pw_cur[j]);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-    };
-
-    const int KT = (int)((K + BK - 1) / BK);
-    load_a(0);
-    load_b(0, b_cur, pw_cur);
-    store_a(smem);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        unsigned char* cur = smem + (kt & 1) * A_BYTES;
-        unsigned char* nxt = smem + ((kt + 1) & 1) * A_BYTES;
-        const bool more = kt + 1 < KT;
-        if (more) {
-            load_a(kt + 1);
-            load_b(kt + 1, b_nxt, pw_nxt);
-        }
-        compute(cur);
-        if (more) {
-            store_a(nxt);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                b_cur[j] = b_nxt[j];
-                pw_cur[j] = pw_nxt[j];
-            }
-        }
-        __syncthreads();
-    }
-
-    half_t* __restrict__ Yt = Y + m0 * N + n0;
-    const uint32_t n32 = (uint32_t)N;
-    const int rows_left = (int)min((int64_t)BM, M - m0), cols_left = (int)min((int64_t)BN, N - n0);
-    const int row0 = wm + 4 * (lane >> 5), col0 = wn + (lane & 31);
-    const uint32_t off0 = (uint32_t)row0 * n32 + (uint32_t)col0;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        if (col0 + 32 * j < cols_left) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
-                    if (row0 + dr < rows_left) Yt[off0 + (uint32_t)dr * n32 + 32 * j] = (half_t)acc[i][j][r];
-                }
-        }
-    }
-}
-
-template <int G, int BM, int BN>
-int launch_direct(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
-{
-    const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
-    if (m_tiles * n_tiles > 0x3fffffffLL) return E0M4_ERR_SHAPE;
-    const int total = (int)(m_tiles * n_tiles);
-    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
-    constexpr size_t lds = 2 * (size_t)BM * kRowBytes;
-    hipLaunchKernelGGL((gemm_direct_kernel<G, BM, BN>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(kThreads), lds,
-                       stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles);
-    return check_launch();
-}
-
 template <int G, int BM, int BN>
 int launch_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
 {
@@ -397,21 +224,7 @@ int launch_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
 template <int G>
 int launch_g(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
 {
-    // Tile choice: the largest tile that still gives every compute unit work.
-    int variant = knob("gemm_variant");
-    if (variant <= 0) {
-        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-        const int64_t t2x1 = ((M + 255) / 256) * ((N + 127) / 128);
-        variant = t256 >= 256 ? 1 : (t2x1 >= 256 ? 2 : 3);
-    }
-    switch (variant) {
-        case 1: return launch_tile<G, 256, 256>(x, M, c, N, K, y, stream);
-        case 2: return launch_tile<G, 256, 128>(x, M, c, N, K, y, stream);
-        case 4: return launch_direct<G, 256, 256>(x, M, c, N, K, y, stream);
-        case 5: return launch_direct<G, 256, 128>(x, M, c, N, K, y, stream);
-        case 6: return launch_direct<G, 128, 128>(x, M, c, N, K, y, stream);
-        default: return launch_tile<G, 128, 128>(x, M, c, N, K, y, stream);
-    }
+    return launch_tile<G, 128, 128>(x, M, c, N, K, y, stream);
 }
 
 // The pipelined 256 x 256 kernel runs whenever its work items (tiles x K splits) can occupy a good
@@ -420,10 +233,9 @@ int launch_g(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, h
 int pipe_waves(int64_t M, int64_t N, int64_t K)
 {
     if (!gemm_pipe_supported(K)) return 0;
-    const int v = knob("gemm_variant");
-    if (v == 7) return 4;
-    if (v == 8) return 8;
-    if (v > 0) return 0;
+    const int v = knob("gemm_variant");             // 1: always the small tile of this file, 2: always the pipelined kernel
+    if (v == 2) return 8;
+    if (v == 1) return 0;
     return gemm_pipe_work_items(M, N, K) >= 96 ? 8 : 0;
 }
 

@@ -44,11 +44,11 @@ __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2
 // WGM x WGN wavefronts share the tile: 2 x 2 (one per SIMD, 128 x 128 each) or 2 x 4 (two per SIMD,
 // 128 x 64 each, which doubles the instruction issue capacity and lets one wavefront's waits hide
 // behind the other's MFMAs, for twice the activation fragment traffic).
-template <int G, int WGM, int WGN, int DBG = 0>
+template <int G, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
                                                              const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                              half_t* __restrict__ Y, int m_tiles, int n_tiles,
-                                                             int splits, float* __restrict__ partial, int dbg)
+                                                             int splits, float* __restrict__ partial)
 {
     constexpr int kThreads = 64 * WGM * WGN;
     constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);      // 32x32 MFMA blocks per wavefront
@@ -123,13 +123,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     half8_t fa[2][TM], fb[2][TN];
 
     auto load_a = [&](int kt) {
-        const uint32_t k0 = (dbg & 1) ? 0u : (uint32_t)min(kt, KT - 1) * BK;
+        const uint32_t k0 = (uint32_t)min(kt, KT - 1) * BK;
 #pragma unroll
         for (int p = 0; p < PA; ++p)
             a_reg[p] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_pass_off[p], (int)(k0 * 2), 0);
     };
     auto load_b = [&](int kt, int set) {
-        const uint32_t k0 = (dbg & 2) ? 0u : (uint32_t)min(kt, KT - 1) * BK;
+        const uint32_t k0 = (uint32_t)min(kt, KT - 1) * BK;
         // chunk (k0/32) of the row block's codes starts (k0/32)*256 bytes in; the parameter words of
         // group k0/G start (k0/G)*64 bytes into the row block's parameters
         const int code_soff = (int)((k0 / kCodesPerChunk) * (kBlockRows * 16));
@@ -147,7 +147,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     };
     auto read_frags = [&](uint32_t stage_off, int s, half8_t (&dst)[TM]) {
         const unsigned char* base = smem + stage_off + frag_off[s];
-        if (DBG & 16) return;
 #pragma unroll
         for (int i = 0; i < TM; ++i) dst[i] = *reinterpret_cast<const half8_t*>(base + i * 32 * kRowBytes);
     };
@@ -155,11 +154,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const uint32_t word = bset[set][j][s];
-            if (DBG & 8) {
-                const uint32_t o4[4] = {word, word ^ pwset[set][j], word, word};
-                dst[j] = *reinterpret_cast<const half8_t*>(o4);
-                continue;
-            }
             const half_t sc = param_scale(pwset[set][j]), bi = param_bias(pwset[set][j]);
             const half2_t s2 = {sc, sc}, b2 = {bi, bi};
             half2_t o[4];
@@ -223,7 +217,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
         mfma_block(fa[1], fb[1]);
         interleave(I0{}, I0{});
         __builtin_amdgcn_sched_barrier(0);
-        if (!(DBG & 4)) __syncthreads();                // slice kt+1 is complete in stage `nxt`
+        __syncthreads();                // slice kt+1 is complete in stage `nxt`
         __builtin_amdgcn_sched_barrier(0);
         // sub-step 2: operands of sub-step 3 (last use of this slice's codes)
         read_frags(cur, 3, fa[1]);
@@ -346,23 +340,8 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
         if (e != hipSuccess) return record_hip_error(e);
         attr_set = true;
     }
-    const int dbg = knob("gemm_debug");
-    if (G == 128 && (dbg & 28)) {
-        static bool attr2 = false;
-        auto launch_dbg = [&](auto kern) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * kNumXcd)), dim3(64 * WGM * WGN), lds, stream, x, M, c, N, K, y,
-                               (int)m_tiles, (int)n_tiles, splits, partial, dbg);
-        };
-        (void)attr2;
-        if ((dbg & 28) == 4) launch_dbg(&gemm_pipe_kernel<128, WGM, WGN, 4>);
-        else if ((dbg & 28) == 8) launch_dbg(&gemm_pipe_kernel<128, WGM, WGN, 8>);
-        else if ((dbg & 28) == 16) launch_dbg(&gemm_pipe_kernel<128, WGM, WGN, 16>);
-        else launch_dbg(&gemm_pipe_kernel<128, WGM, WGN, 28>);
-        return check_launch();
-    }
     hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(64 * WGM * WGN), lds,
-                       stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial, dbg);
+                       stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial);
     int rc = check_launch();
     if (rc != E0M4_OK || splits == 1) return rc;
     const int64_t count = M * N;

@@ -228,14 +228,14 @@ def test_gemm_small(e0m4, oracle, M, N, K, G):
     run_matmul_case(e0m4, oracle, M, N, K, G, seed=M + N + K, outliers=True, row_std=(0.5, 2.0))
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("variant", [1, 2])       # 1: small-tile kernel, 2: pipelined 256 x 256 kernel
 @pytest.mark.parametrize("M,N,K,G", [
     (300, 600, 1024, 128),      # ragged in M and N against every tile size, several tiles each way
     (513, 272, 416, 32),        # ragged K slice (416 = 6.5 x 64), N ends inside a 16-row block run
     (256, 256, 192, 64),        # exactly one large tile
     (40, 1040, 2048, 128),      # fewer rows than any tile
 ])
-def test_gemm_every_tile_shape(e0m4, oracle, variant, M, N, K, G):
+def test_gemm_both_kernels(e0m4, oracle, variant, M, N, K, G):
     e0m4.e0m4_set_knob("gemm_variant", variant)
     try:
         run_matmul_case(e0m4, oracle, M, N, K, G, seed=variant + M + N, outliers=True, row_std=(0.5, 2.0))
@@ -251,7 +251,7 @@ def test_gemm_every_tile_shape(e0m4, oracle, variant, M, N, K, G):
     (1024, 1040, 2048, 128),    # 20 tiles, ragged last column of tiles
 ])
 def test_gemm_split_k(e0m4, oracle, splits, M, N, K, G):
-    e0m4.e0m4_set_knob("gemm_variant", 8)
+    e0m4.e0m4_set_knob("gemm_variant", 2)
     e0m4.e0m4_set_knob("gemm_splits", splits)
     try:
         run_matmul_case(e0m4, oracle, M, N, K, G, seed=splits + M + N, outliers=True, row_std=(0.5, 2.0))
