@@ -31,9 +31,10 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kSuper = 4;                       // weight blocks (of 128 k) per work item
-constexpr int kXBudgetBytes = 48 * 1024;        // LDS spent on activations and their chunk sums
+constexpr int kXBudgetBytes = 112 * 1024;       // LDS spent on activations and their chunk sums, at most
 constexpr int kRedBudgetBytes = 32 * 1024;      // LDS spent on the per-wavefront partial sums, at most
-constexpr int kLdsLimitBytes = 64 * 1024;       // dynamic LDS a kernel may ask for without opting in to more
+constexpr int kLdsLimitBytes = 144 * 1024;      // of the 160 KiB of a compute unit (one workgroup per unit)
+constexpr int kLdsDefaultBytes = 64 * 1024;     // dynamic LDS a kernel may ask for without opting in to more
 constexpr int kBytesPerBlockX = kBlockK * 2 + (kBlockK / kCodesPerChunk) * 8;   // 288 per row of X per k block
 constexpr int kTargetWorkgroups = 256;          // one workgroup per compute unit (measured best: activations are staged once per workgroup)
 constexpr int kEarlyX = 2;                      // activation pieces per thread requested before the weights
@@ -315,6 +316,15 @@ int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, 
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     const dim3 grid((unsigned)p.grid), block(W * 64);
+    if (p.lds_bytes > (size_t)kLdsDefaultBytes) {
+        static bool attr_set = false;                   // per instantiation
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<G, M, W>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimitBytes);
+            if (e != hipSuccess) return record_hip_error(e);
+            attr_set = true;
+        }
+    }
     hipLaunchKernelGGL((gemv_kernel<G, M, W>), grid, block, p.lds_bytes, stream, x, c, N, K, y, p.seg_items,
                        p.step_slots, p.step_item, p.rb_base, p.rb_rem);
     return check_launch();
