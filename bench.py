@@ -270,7 +270,7 @@ def main():
             del W
         xcpu = {K: synth_inputs.activations(1, K, 99 + K) for _, _, K in shapes}
         reps, t_cpu = 0, 0.0
-        while t_cpu < 10.0 and reps < 8:
+        while t_cpu < 12.0 and reps < 64:
             t0 = time.perf_counter()
             for N, K, codes, scales, bias in packed:
                 What = oracle.dequant(codes, scales, bias, GROUP)

@@ -62,3 +62,38 @@ def test_full_size_layer(e0m4, oracle, name, N, K, G, Mp):
     ns = sample_indices(64, N, 128, rng)
     Yc, adc = oracle.matmul(X, What[ns])
     check_matmul(torch.from_numpy(np.ascontiguousarray(Y[:, ns])), Yc, adc, name + " prefill cols")
+
+
+def test_decode_layer_in_a_hip_graph_matches_eager(e0m4):
+    """The benchmark replays a captured HIP graph of e0m4_matmul launches: several replays, with eager
+    work and synchronisation in between, must reproduce the eager results bit for bit."""
+    G = 128
+    stream = torch.cuda.Stream()
+    mats = []
+    for p, (name, N, K) in enumerate(synth_inputs.CHATGLM2_6B):
+        W = synth_inputs.weights_device(N, K, 7000 + p, DEV)
+        codes, scales, bias = e0m4.e0m4_quantize(W, G)
+        del W
+        x = synth_inputs.activations_device(1, K, 7100 + p, DEV)
+        y = torch.empty((1, N), dtype=torch.float16, device=DEV)
+        mats.append((N, K, codes, scales, bias, x, y))
+    torch.cuda.synchronize()
+    eager = [e0m4.e0m4_matmul(x, codes, scales, bias, N, K, G).clone() for N, K, codes, scales, bias, x, y in mats]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        for N, K, codes, scales, bias, x, y in mats:           # loads the code objects before capture
+            e0m4.e0m4_matmul(x, codes, scales, bias, N, K, G, out=y, stream=stream)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for N, K, codes, scales, bias, x, y in mats:
+                e0m4.e0m4_matmul(x, codes, scales, bias, N, K, G, out=y, stream=stream)
+    for replay in range(3):
+        for m in mats:
+            m[6].fill_(float("nan"))                           # eager work between replays
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            graph.replay()
+        stream.synchronize()
+        for want, m in zip(eager, mats):
+            assert np.array_equal(bits(m[6]), bits(want)), "replay %d" % replay
