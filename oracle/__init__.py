@@ -64,6 +64,14 @@ def _load():
     L.oracle_e0m4_encode.argtypes = [u16p, i64, i64, i64, u16p, u16p, u8p]
     L.oracle_e0m4_dequant.restype = None
     L.oracle_e0m4_dequant.argtypes = [u8p, u16p, u16p, i64, i64, i64, u16p]
+    L.oracle_int4_decode_one.restype = ctypes.c_uint16
+    L.oracle_int4_decode_one.argtypes = [ctypes.c_int, ctypes.c_uint16, ctypes.c_uint16]
+    L.oracle_int4_encode_one.restype = ctypes.c_int
+    L.oracle_int4_encode_one.argtypes = [ctypes.c_uint16, ctypes.c_uint16, ctypes.c_uint16]
+    L.oracle_int4_quantize.restype = None
+    L.oracle_int4_quantize.argtypes = [u16p, i64, i64, i64, u8p, u16p, u16p]
+    L.oracle_int4_dequant.restype = None
+    L.oracle_int4_dequant.argtypes = [u8p, u16p, u16p, i64, i64, i64, u16p]
     L.oracle_e0m4_matmul.restype = None
     L.oracle_e0m4_matmul.argtypes = [u16p, i64, u16p, i64, i64, u16p, f64p]
     L.oracle_num_threads.restype = ctypes.c_int
@@ -154,6 +162,40 @@ def dequant(codes: np.ndarray, scales: np.ndarray, bias: np.ndarray, group: int)
     assert sb.shape == (N, K // group) and bb.shape == sb.shape
     out = np.empty((N, K), np.uint16)
     _load().oracle_e0m4_dequant(_p(codes, ctypes.c_uint8), _p(sb, ctypes.c_uint16), _p(bb, ctypes.c_uint16),
+                                N, K, group, _p(out, ctypes.c_uint16))
+    return out.view(np.float16)
+
+
+# ---- INT4 comparison format (paper: section "Evaluation of FP4 quantization") ----
+
+def int4_decode_one(q: int, scale_bits: int, zero_bits: int) -> int:
+    return _load().oracle_int4_decode_one(q, scale_bits, zero_bits)
+
+
+def int4_encode_one(w0_bits: int, scale_bits: int, zero_bits: int) -> int:
+    return _load().oracle_int4_encode_one(w0_bits, scale_bits, zero_bits)
+
+
+def int4_quantize(W: np.ndarray, group: int):
+    """W [N,K] fp16 -> (codes u8 [N,K], scales f16 [N,K/G], zeros f16 [N,K/G], integer-valued 0..15)."""
+    Wb = _u16(W)
+    N, K = Wb.shape
+    assert K % group == 0
+    codes = np.empty((N, K), np.uint8)
+    scales = np.empty((N, K // group), np.uint16)
+    zeros = np.empty((N, K // group), np.uint16)
+    _load().oracle_int4_quantize(_p(Wb, ctypes.c_uint16), N, K, group, _p(codes, ctypes.c_uint8),
+                                 _p(scales, ctypes.c_uint16), _p(zeros, ctypes.c_uint16))
+    return codes, scales.view(np.float16), zeros.view(np.float16)
+
+
+def int4_dequant(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, group: int) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    sb, zb = _u16(scales), _u16(zeros)
+    N, K = codes.shape
+    assert sb.shape == (N, K // group) and zb.shape == sb.shape
+    out = np.empty((N, K), np.uint16)
+    _load().oracle_int4_dequant(_p(codes, ctypes.c_uint8), _p(sb, ctypes.c_uint16), _p(zb, ctypes.c_uint16),
                                 N, K, group, _p(out, ctypes.c_uint16))
     return out.view(np.float16)
 

@@ -34,6 +34,12 @@
  *   - rounding of the code: add the fifth fraction bit to the four kept bits
  *     and saturate at 15, exactly as the paper writes it.
  *
+ * The file also holds the INT4 format the paper compares E0M4 with in its
+ * section "Evaluation of FP4 quantization" (Tables 1 and 2).  The paper does not
+ * define that quantiser; the reading taken is written above the functions, and
+ * its pins tie it to that stated definition, to the E0M4 decoder (of which an
+ * integer-zero-point INT4 group is a special case) and to Table 2's ratio.
+ *
  * Build: gcc -O2 -fopenmp -ffp-contract=off -fno-fast-math -shared -fPIC
  */
 #include <math.h>
@@ -217,6 +223,90 @@ void oracle_e0m4_dequant(const uint8_t* codes, const uint16_t* scales, const uin
         for (int64_t k = 0; k < K; ++k)
             W_out[n * K + k] = oracle_e0m4_decode_one(codes[n * K + k], scales[n * ng + k / G],
                                                       bias[n * ng + k / G]);
+}
+
+/* ------------------------------------------------------------------ */
+/* INT4 comparison format (paper: section "Evaluation of FP4           */
+/* quantization", Tables 1 and 2).                                     */
+/* ------------------------------------------------------------------ */
+/* The paper compares E0M4 with "INT4 quantization" but does not define the
+ * INT4 quantiser.  Reading taken (stated in the design document): group-wise
+ * asymmetric min/max quantisation with 15 steps, an integer zero point and
+ * round-to-nearest,
+ *     scale = fp16((max - min) / 15), range extended to contain 0,
+ *     zero  = clamp(rne(-min / scale), 0, 15),
+ *     q     = clamp(rne(w / scale) + zero, 0, 15),
+ *     w^    = fp16((q - zero) * scale),
+ * fp32 arithmetic, one IEEE operation per step, rne = round half to even.
+ * The scale is floored at the smallest normal fp16 and capped at the largest
+ * finite one, like the E0M4 scale.  zero is stored as the fp16 number 0..15. */
+
+void oracle_int4_fit_group(const uint16_t* w0, int64_t G, uint16_t* scale_bits, uint16_t* zero_bits)
+{
+    float mn = 0.0f, mx = 0.0f;
+    for (int64_t k = 0; k < G; ++k) {
+        float v = h2f(w0[k]);
+        if (v < mn) mn = v;
+        if (v > mx) mx = v;
+    }
+    float range = mx - mn;
+    float s = range / 15.0f;
+    if (s < 6.103515625e-05f) s = 6.103515625e-05f;
+    if (s > 65504.0f) s = 65504.0f;
+    uint16_t sb = f2h(s);
+    float sf = h2f(sb);
+    float q = mn / sf;
+    float z = rintf(-q);                      /* default rounding mode: half to even */
+    if (z < 0.0f) z = 0.0f;
+    if (z > 15.0f) z = 15.0f;
+    *scale_bits = sb;
+    *zero_bits = f2h(z);                      /* exact */
+}
+
+int oracle_int4_encode_one(uint16_t w0_bits, uint16_t scale_bits, uint16_t zero_bits)
+{
+    float q = h2f(w0_bits) / h2f(scale_bits);
+    float t = rintf(q) + h2f(zero_bits);
+    if (t < 0.0f) t = 0.0f;
+    if (t > 15.0f) t = 15.0f;
+    return (int)t;
+}
+
+/* w^ = (q - zero) * scale: the difference is an exact small integer, the
+ * product is rounded once to fp16. */
+uint16_t oracle_int4_decode_one(int q, uint16_t scale_bits, uint16_t zero_bits)
+{
+    double d = (double)q - oracle_half_bits_to_double(zero_bits);
+    return oracle_double_to_half_bits(d * oracle_half_bits_to_double(scale_bits));
+}
+
+void oracle_int4_quantize(const uint16_t* W, int64_t N, int64_t K, int64_t G,
+                          uint8_t* codes, uint16_t* scales, uint16_t* zeros)
+{
+    const int64_t ng = K / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t g = 0; g < ng; ++g) {
+            const uint16_t* w0 = W + n * K + g * G;
+            uint16_t sb, zb;
+            oracle_int4_fit_group(w0, G, &sb, &zb);
+            scales[n * ng + g] = sb;
+            zeros[n * ng + g] = zb;
+            for (int64_t k = 0; k < G; ++k)
+                codes[n * K + g * G + k] = (uint8_t)oracle_int4_encode_one(w0[k], sb, zb);
+        }
+    }
+}
+
+void oracle_int4_dequant(const uint8_t* codes, const uint16_t* scales, const uint16_t* zeros,
+                         int64_t N, int64_t K, int64_t G, uint16_t* W_out)
+{
+    const int64_t ng = K / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k)
+            W_out[n * K + k] = oracle_int4_decode_one(codes[n * K + k], scales[n * ng + k / G],
+                                                      zeros[n * ng + k / G]);
 }
 
 /* ------------------------------------------------------------------ */
