@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (debug)")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-table1", action="store_true", help="skip the E0M4 / INT4 latency comparison")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--copy-probe", action="store_true",
                     help="first run three plain device copies of 1 GiB (calibration of HBM traffic counters)")
@@ -212,6 +213,59 @@ def main():
         "decode_per_shape": per_shape,
         "quantize": {"GBps_fp16_in": round(q_bytes / t_q / 1e9, 1), "note": "offline step incl. weight generation"},
     }
+
+    # ---------------- the paper's Table 1: E0M4 against the INT4 twin, M = 1, weight [K, N]
+    # (same layout, launch shape and accumulation; the twin extracts integers and converts them to fp16).
+    # Each shape rotates over distinct weight copies (cold in cache), replayed from a HIP graph.
+    if not args.no_table1:
+        t1 = {}
+        with torch.cuda.stream(stream):
+            for K, N in synth_inputs.TABLE1_SHAPES:
+                W = synth_inputs.weights_device(N, K, 8000 + K + N, dev)
+                ec, _, _ = e0m4.e0m4_quantize(W, GROUP, stream=stream)
+                ic, _, _ = e0m4.e0m4_int4_quantize(W, GROUP, stream=stream)
+                del W
+                copies = max(2, min(24, int(1.5e9 // ec.numel())))
+                ecs = [ec] + [ec.clone() for _ in range(copies - 1)]
+                ics = [ic] + [ic.clone() for _ in range(copies - 1)]
+                x = synth_inputs.activations_device(1, K, 8100 + K, dev)
+                y = torch.empty((1, N), dtype=torch.float16, device=dev)
+                us = {}
+                for fmt, bufs in (("e0m4", ecs), ("int4", ics)):
+                    def one_pass():
+                        for c in bufs:
+                            if fmt == "e0m4":
+                                e0m4.e0m4_matmul(x, c, None, None, N, K, GROUP, out=y, stream=stream)
+                            else:
+                                e0m4.e0m4_int4_gemv(x, c, N, K, GROUP, out=y, stream=stream)
+                    one_pass()
+                    stream.synchronize()
+                    run = one_pass
+                    if graph is not None:
+                        gt = torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(gt, stream=stream):
+                            one_pass()
+                        run = gt.replay
+                    best = None
+                    for _ in range(5):
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record(stream)
+                        for _ in range(4):
+                            run()
+                        e1.record(stream)
+                        stream.synchronize()
+                        t = e0.elapsed_time(e1) * 1e3 / (4 * copies)
+                        best = t if best is None else min(best, t)
+                    us[fmt] = best
+                b = algorithmic_bytes(1, N, K, GROUP)
+                t1["K%d_N%d" % (K, N)] = {"e0m4_us": round(us["e0m4"], 3), "int4_us": round(us["int4"], 3),
+                                           "int4_over_e0m4": round(us["int4"] / us["e0m4"], 3),
+                                           "e0m4_GBps": round(b / us["e0m4"] / 1e3, 1),
+                                           "int4_GBps": round(b / us["int4"] / 1e3, 1)}
+                del ecs, ics, ec, ic, x, y
+        out["table1_e0m4_vs_int4"] = {"workload": "M=1, weight [K,N] of the paper's Table 1, group %d; latency per launch, "
+                                                  "cold weights; ratio as the table's 'acceleration'" % GROUP,
+                                      "shapes": t1}
 
     # ---------------- prefill: same four shapes at M=1024 (activation outliers, per-row weight scale)
     if not args.no_prefill:

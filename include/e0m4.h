@@ -125,6 +125,34 @@ int e0m4_matmul(const void* X_f16, int64_t M,
                 void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * INT4 twin (paper: section "Evaluation of FP4 quantization", Table 1 and
+ * Table 2, which compare E0M4 with "INT4 quantization").  The paper does not
+ * define that quantiser; this library's reading is group-wise asymmetric
+ * min/max quantisation with 15 steps and an integer zero point:
+ *     scale = fp16((max - min) / 15)   (range extended to contain 0),
+ *     zero  = clamp(rne(-min / scale), 0, 15),
+ *     q     = clamp(rne(w / scale) + zero, 0, 15),
+ *     w^    = fp16((q - zero) * scale).
+ * The packed buffer has the E0M4 layout (same e0m4_codes_bytes, readable with
+ * e0m4_unpack_codes); its embedded parameter words hold (scale, zero).
+ * `scales_f16` and `zeros_f16` are [N, K/group] fp16, zero being the integer
+ * 0..15 as an fp16 number.  Same pointer, alignment, stream and error rules as
+ * the E0M4 entry points.
+ *
+ * e0m4_int4_gemv computes Y[1,N] = X[1,K] * dequant(codes)^T like e0m4_matmul
+ * at M = 1, with the same data layout, launch shape and accumulation, but it
+ * turns every code into a number with an integer extraction and an integer-to-
+ * float conversion instruction instead of E0M4's bit operations: the pair of
+ * kernels re-runs the paper's latency comparison.  (An INT4 group with an
+ * integer zero point is also a valid E0M4 group with scale' = 8 * scale and
+ * bias' = 2 + zero / 8, so INT4 data can take the E0M4 path unchanged.)
+ */
+int e0m4_int4_quantize(const void* W_f16, int64_t N, int64_t K, int group,
+                       void* codes, void* scales_f16, void* zeros_f16, void* stream);
+int e0m4_int4_dequant(const void* codes, int64_t N, int64_t K, int group, void* W_f16_out, void* stream);
+int e0m4_int4_gemv(const void* X_f16, const void* codes, int64_t N, int64_t K, int group, void* Y_f16, void* stream);
+
+/*
  * Diagnostics for tuning sweeps; not needed for normal use.  Sets an integer
  * knob by name (e.g. "gemv_waves"); unknown names return E0M4_ERR_SHAPE.
  * A value of 0 restores the built-in heuristic.

@@ -9,6 +9,9 @@ from .binding import (  # noqa: F401
     e0m4_codes_bytes,
     e0m4_dequant,
     e0m4_encode,
+    e0m4_int4_dequant,
+    e0m4_int4_gemv,
+    e0m4_int4_quantize,
     e0m4_matmul,
     e0m4_params_elems,
     e0m4_quantize,

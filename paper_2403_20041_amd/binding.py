@@ -61,6 +61,12 @@ def lib() -> ctypes.CDLL:
     L.e0m4_unpack_codes.argtypes = [vp, i64, i64, ci, vp, vp]
     L.e0m4_matmul.restype = ci
     L.e0m4_matmul.argtypes = [vp, i64, vp, vp, vp, i64, i64, ci, vp, vp, sz, vp]
+    L.e0m4_int4_quantize.restype = ci
+    L.e0m4_int4_quantize.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
+    L.e0m4_int4_dequant.restype = ci
+    L.e0m4_int4_dequant.argtypes = [vp, i64, i64, ci, vp, vp]
+    L.e0m4_int4_gemv.restype = ci
+    L.e0m4_int4_gemv.argtypes = [vp, vp, i64, i64, ci, vp, vp]
     L.e0m4_set_knob.restype = ci
     L.e0m4_set_knob.argtypes = [ctypes.c_char_p, ci]
     if L.e0m4_abi_version() != 2:
@@ -166,4 +172,34 @@ def e0m4_matmul(X, codes, scales, bias, N: int, K: int, group: int, out=None, wo
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().e0m4_matmul(_ptr(X), M, _ptr(codes), _ptr(scales), _ptr(bias), N, K, group, _ptr(out),
                              _ptr(workspace), ws_bytes, _stream(stream)), "e0m4_matmul")
+    return out
+
+
+# ---- INT4 twin (see include/e0m4.h) ------------------------------------------------------------
+
+def e0m4_int4_quantize(W: torch.Tensor, group: int, out=None, stream=None):
+    """W [N,K] fp16 -> (codes, scales, zeros) in the INT4 comparison format."""
+    N, K = W.shape
+    _need(W, torch.float16, (N, K), "W")
+    codes, scales, zeros = out if out is not None else alloc_packed(N, K, group, W.device)
+    _check(lib().e0m4_int4_quantize(_ptr(W), N, K, group, _ptr(codes), _ptr(scales), _ptr(zeros), _stream(stream)),
+           "e0m4_int4_quantize")
+    return codes, scales, zeros
+
+
+def e0m4_int4_dequant(codes, N: int, K: int, group: int, out=None, stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.float16, device=codes.device)
+    _need(out, torch.float16, (N, K), "out")
+    _check(lib().e0m4_int4_dequant(_ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m4_int4_dequant")
+    return out
+
+
+def e0m4_int4_gemv(X, codes, N: int, K: int, group: int, out=None, stream=None) -> torch.Tensor:
+    """Y [1,N] fp16 = X [1,K] fp16 times the dequantised INT4 weights, transposed."""
+    _need(X, torch.float16, (1, K), "X")
+    if out is None:
+        out = torch.empty((1, N), dtype=torch.float16, device=X.device)
+    _need(out, torch.float16, (1, N), "out")
+    _check(lib().e0m4_int4_gemv(_ptr(X), _ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m4_int4_gemv")
     return out

@@ -121,7 +121,7 @@ int e0m4_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, v
     if (N == 0 || K == 0) return E0M4_OK;
     if (!W || !codes || !scales || !bias) return E0M4_ERR_NULL;
     if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
-    return launch_quantize(W, N, K, group, codes, scales, bias, nullptr, nullptr, true, (hipStream_t)stream);
+    return launch_quantize(W, N, K, group, codes, scales, bias, nullptr, nullptr, true, false, (hipStream_t)stream);
 }
 
 int e0m4_encode(const void* W, int64_t N, int64_t K, int group, const void* scales, const void* bias, void* codes,
@@ -132,7 +132,7 @@ int e0m4_encode(const void* W, int64_t N, int64_t K, int group, const void* scal
     if (N == 0 || K == 0) return E0M4_OK;
     if (!W || !codes || !scales || !bias) return E0M4_ERR_NULL;
     if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
-    return launch_quantize(W, N, K, group, codes, nullptr, nullptr, scales, bias, false, (hipStream_t)stream);
+    return launch_quantize(W, N, K, group, codes, nullptr, nullptr, scales, bias, false, false, (hipStream_t)stream);
 }
 
 int e0m4_dequant(const void* codes, const void* scales, const void* bias, int64_t N, int64_t K, int group, void* W_out,
@@ -144,7 +144,45 @@ int e0m4_dequant(const void* codes, const void* scales, const void* bias, int64_
     if (N == 0 || K == 0) return E0M4_OK;
     if (!W_out || !codes) return E0M4_ERR_NULL;
     if (!aligned16(W_out) || !aligned16(codes)) return E0M4_ERR_ALIGN;
-    return launch_dequant(codes, N, K, group, W_out, (hipStream_t)stream);
+    return launch_dequant(codes, N, K, group, W_out, false, (hipStream_t)stream);
+}
+
+int e0m4_int4_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, void* scales, void* zeros,
+                       void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!W || !codes || !scales || !zeros) return E0M4_ERR_NULL;
+    if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(zeros)) return E0M4_ERR_ALIGN;
+    return launch_quantize(W, N, K, group, codes, scales, zeros, nullptr, nullptr, true, true, (hipStream_t)stream);
+}
+
+int e0m4_int4_dequant(const void* codes, int64_t N, int64_t K, int group, void* W_out, void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!W_out || !codes) return E0M4_ERR_NULL;
+    if (!aligned16(W_out) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    return launch_dequant(codes, N, K, group, W_out, true, (hipStream_t)stream);
+}
+
+int e0m4_int4_gemv(const void* X, const void* codes, int64_t N, int64_t K, int group, void* Y, void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0) return E0M4_OK;
+    if (!Y) return E0M4_ERR_NULL;
+    if (!aligned16(Y)) return E0M4_ERR_ALIGN;
+    if (K == 0) {                                   // empty contraction: Y = 0
+        hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                           static_cast<half_t*>(Y), N);
+        return check_launch();
+    }
+    if (!X || !codes) return E0M4_ERR_NULL;
+    if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    return launch_gemv_int4(X, codes, N, K, group, Y, (hipStream_t)stream);
 }
 
 int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* out, void* stream)

@@ -98,7 +98,13 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
 
 // A workgroup owns up to `rb_per_wg` consecutive row blocks; its work items are (row block, group of
 // four k blocks) in memory order.  Wavefront w takes items w, w+W, w+2W, ...
-template <int G, int M, int W>
+// DEQ selects how a 4-bit code becomes a number: kDeqE0M4 is the product path (bit operations only);
+// kDeqInt4Convert is the INT4 twin of the paper's section "Evaluation of FP4 quantization" (Table 1):
+// same data layout and work decomposition, but every code is extracted as an integer and turned into
+// fp16 with a conversion instruction, and the parameter word holds (scale, integer zero point).
+enum { kDeqE0M4 = 0, kDeqInt4Convert = 1 };
+
+template <int G, int M, int W, int DEQ = kDeqE0M4>
 __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__ X, const uint4* __restrict__ packed,
                                                       int64_t N, int64_t K, half_t* __restrict__ Y, int seg_items,
                                                       int step_slots, int step_item, int rb_base, int rb_rem)
@@ -271,7 +277,14 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     half2_t p[4];
-                    w1_pairs_mixed(words[w], fmask, fmask_low, p);
+                    if (DEQ == kDeqInt4Convert) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)     // integer code -> fp16 by conversion
+                            p[i] = half2_t{(half_t)(uint16_t)extract_code(words[w], 2 * i),
+                                           (half_t)(uint16_t)extract_code(words[w], 2 * i + 1)};
+                    } else {
+                        w1_pairs_mixed(words[w], fmask, fmask_low, p);
+                    }
 #pragma unroll
                     for (int m = 0; m < M; ++m) {
                         const half8_t xv = *reinterpret_cast<const half8_t*>(&xs[m * seg_k + xoff + 8 * w]);
@@ -285,9 +298,11 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
                 fetch_code(j, nslot, nitem);            // the block's registers are free: request the next item's
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
-                    // sum x*w1 = a0 + 16*a1 - 30*(sum of x over pairs 1 and 2); then the group's affine map
                     const float2 sx = sxs[m * (seg_k / kCodesPerChunk) + (xoff >> 5)];
-                    acc[m] += sc * ((a[m][0] + 16.f * a[m][1] - sx.y) - bi * sx.x);
+                    if (DEQ == kDeqInt4Convert)         // y += scale * (sum x*q - zero * sum x)
+                        acc[m] += sc * ((a[m][0] + a[m][1]) - bi * sx.x);
+                    else    // sum x*w1 = a0 + 16*a1 - 30*(sum of x over pairs 1 and 2); then the group's affine map
+                        acc[m] += sc * ((a[m][0] + 16.f * a[m][1] - sx.y) - bi * sx.x);
                 }
             }
             const int prev = slot;
@@ -309,7 +324,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     }
 }
 
-template <int G, int M, int W>
+template <int G, int M, int W, int DEQ = kDeqE0M4>
 int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
 {
     const half_t* x = static_cast<const half_t*>(X);
@@ -319,15 +334,26 @@ int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, 
     if (p.lds_bytes > (size_t)kLdsDefaultBytes) {
         static bool attr_set = false;                   // per instantiation
         if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<G, M, W>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<G, M, W, DEQ>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimitBytes);
             if (e != hipSuccess) return record_hip_error(e);
             attr_set = true;
         }
     }
-    hipLaunchKernelGGL((gemv_kernel<G, M, W>), grid, block, p.lds_bytes, stream, x, c, N, K, y, p.seg_items,
+    hipLaunchKernelGGL((gemv_kernel<G, M, W, DEQ>), grid, block, p.lds_bytes, stream, x, c, N, K, y, p.seg_items,
                        p.step_slots, p.step_item, p.rb_base, p.rb_rem);
     return check_launch();
+}
+
+// INT4 twin, M = 1: the same plan and launch shape as the product kernel.
+template <int G>
+int launch_int4_w(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+{
+    switch (p.waves) {
+        case 4: return launch_one<G, 1, 4, kDeqInt4Convert>(p, X, packed, N, K, Y, stream);
+        case 8: return launch_one<G, 1, 8, kDeqInt4Convert>(p, X, packed, N, K, Y, stream);
+        default: return launch_one<G, 1, 16, kDeqInt4Convert>(p, X, packed, N, K, Y, stream);
+    }
 }
 
 template <int G, int M>
@@ -369,6 +395,17 @@ int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t
         case 32: return launch_m<32>(p, M, X, packed, N, K, Y, stream);
         case 64: return launch_m<64>(p, M, X, packed, N, K, Y, stream);
         case 128: return launch_m<128>(p, M, X, packed, N, K, Y, stream);
+        default: return E0M4_ERR_GROUP;
+    }
+}
+
+int launch_gemv_int4(const void* X, const void* packed, int64_t N, int64_t K, int group, void* Y, hipStream_t stream)
+{
+    const GemvPlan p = make_plan(1, N, K);
+    switch (group) {
+        case 32: return launch_int4_w<32>(p, X, packed, N, K, Y, stream);
+        case 64: return launch_int4_w<64>(p, X, packed, N, K, Y, stream);
+        case 128: return launch_int4_w<128>(p, X, packed, N, K, Y, stream);
         default: return E0M4_ERR_GROUP;
     }
 }

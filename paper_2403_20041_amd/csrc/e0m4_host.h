@@ -18,14 +18,17 @@ int record_hip_error(hipError_t e);
 int knob(const char* name);
 
 int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed, void* scales, void* bias,
-                    const void* scales_in, const void* bias_in, bool fit, hipStream_t stream);
-int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, hipStream_t stream);
+                    const void* scales_in, const void* bias_in, bool fit, bool int4, hipStream_t stream);
+int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, bool int4, hipStream_t stream);
 int launch_unpack(const void* packed, int64_t N, int64_t K, int group, void* out, hipStream_t stream);
 
 // Small-M path (M <= kGemvMaxM).
 constexpr int kGemvMaxM = 8;
 int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                 hipStream_t stream);
+// INT4 twin of the M = 1 kernel: same layout and work decomposition, codes turned into numbers with
+// integer-to-float conversion instructions.
+int launch_gemv_int4(const void* X, const void* packed, int64_t N, int64_t K, int group, void* Y, hipStream_t stream);
 
 // MFMA path.
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,

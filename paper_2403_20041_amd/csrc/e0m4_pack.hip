@@ -39,11 +39,24 @@ __device__ inline uint32_t encode_value(float w0, float sf, float bf)
     return c > 15u ? 15u : c;
 }
 
+// INT4 comparison format (paper: section "Evaluation of FP4 quantization"): q = clamp(rne(w / scale)
+// + zero, 0, 15) with an integer zero point kept as an fp16 number.
+__device__ inline uint32_t encode_value_int4(float w0, float sf, float zf)
+{
+    float q = w0 / sf;
+    float t = rintf(q) + zf;
+    t = t < 0.0f ? 0.0f : t;
+    t = t > 15.0f ? 15.0f : t;
+    return (uint32_t)t;
+}
+
+enum Format { kE0M4 = 0, kInt4 = 1 };
+
 // Thread t owns the 8-weight piece t%16 of row (t/16) of row block i, i = 0..3,
 // so 16 consecutive lanes read 256 contiguous bytes of one row and a group of G
 // weights is G/8 adjacent lanes.  The four finished blocks are staged in LDS and
 // written out in 16-byte pieces.
-template <int G, bool FIT>
+template <int G, bool FIT, int FMT = kE0M4>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __restrict__ W, int64_t N, int64_t K,
                                                             uint4* __restrict__ packed,
                                                             half_t* __restrict__ scales_out,
@@ -89,16 +102,23 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __rest
                 mx = fmaxf(mx, __shfl_xor(mx, d));
             }
             float range = mx - mn;
-            float s = range / kSpan;
+            float s = range / (FMT == kInt4 ? 15.0f : kSpan);
             s = s < kMinScale ? kMinScale : s;
             s = s > kMaxScale ? kMaxScale : s;
             sh = (half_t)s;
             sf = (float)sh;                             // encode with the stored scale
             float q = mn / sf;
-            float b = kLo - q;                          // image of zero in the binade
-            b = b < kLo ? kLo : b;
-            b = b > kHi ? kHi : b;
-            bh = bits_half(half_bits((half_t)b) & 0xFFC0u);   // keep the four highest fraction bits
+            if (FMT == kInt4) {
+                float z = rintf(-q);                    // integer zero point, round half to even
+                z = z < 0.0f ? 0.0f : z;
+                z = z > 15.0f ? 15.0f : z;
+                bh = (half_t)z;                         // exact
+            } else {
+                float b = kLo - q;                      // image of zero in the binade
+                b = b < kLo ? kLo : b;
+                b = b > kHi ? kHi : b;
+                bh = bits_half(half_bits((half_t)b) & 0xFFC0u);   // keep the four highest fraction bits
+            }
             bf = (float)bh;
             if (ok && (piece % (G / 8)) == 0) {
                 scales_out[n * ng + g] = sh;
@@ -118,7 +138,8 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __rest
         uint32_t word = 0;
         if (ok) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) word |= place_code(encode_value(v[j], sf, bf), j);
+            for (int j = 0; j < 8; ++j)
+                word |= place_code(FMT == kInt4 ? encode_value_int4(v[j], sf, bf) : encode_value(v[j], sf, bf), j);
         }
         stage[i * BW + ((piece >> 2) * kBlockRows + r) * 4 + (piece & 3)] = word;
         if ((piece % (G / 8)) == 0) {
@@ -143,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __rest
 // Wavefront i of the workgroup reads block (4*rb64 + i, kb): codes and the
 // block's parameter words; the 64 x 128 tile goes through LDS so that rows are
 // written out in 256-byte runs.
-template <int G>
+template <int G, int FMT = kE0M4>
 __global__ __launch_bounds__(kThreads) void dequant_kernel(const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                            half_t* __restrict__ W_out)
 {
@@ -172,9 +193,15 @@ __global__ __launch_bounds__(kThreads) void dequant_kernel(const uint4* __restri
                 half8_t o;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    // (w1 - bias) is exact and its product with the scale is exact in fp32: one rounding
-                    o[2 * j] = (half_t)(((float)p[j][0] - bf) * sf);
-                    o[2 * j + 1] = (half_t)(((float)p[j][1] - bf) * sf);
+                    if (FMT == kInt4) {
+                        // (q - zero) is an exact small integer, its product with the scale exact in fp32
+                        o[2 * j] = (half_t)(((float)extract_code(words[w], 2 * j) - bf) * sf);
+                        o[2 * j + 1] = (half_t)(((float)extract_code(words[w], 2 * j + 1) - bf) * sf);
+                    } else {
+                        // (w1 - bias) is exact and its product with the scale is exact in fp32: one rounding
+                        o[2 * j] = (half_t)(((float)p[j][0] - bf) * sf);
+                        o[2 * j + 1] = (half_t)(((float)p[j][1] - bf) * sf);
+                    }
                 }
                 *reinterpret_cast<half8_t*>(&tile[(16 * i + r) * kStride + q * 32 + w * 8]) = o;
             }
@@ -242,7 +269,7 @@ dim3 tile_grid(int64_t N, int64_t K)
 }  // namespace
 
 int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed, void* scales, void* bias,
-                    const void* scales_in, const void* bias_in, bool fit, hipStream_t stream)
+                    const void* scales_in, const void* bias_in, bool fit, bool int4, hipStream_t stream)
 {
     const dim3 grid = tile_grid(N, K), block(kThreads);
     const half_t* w = static_cast<const half_t*>(W);
@@ -253,7 +280,8 @@ int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed
     const half_t* bi = static_cast<const half_t*>(bias_in);
 #define E0M4_LAUNCH_Q(G)                                                                              \
     do {                                                                                              \
-        if (fit) hipLaunchKernelGGL((quantize_kernel<G, true>), grid, block, 0, stream, w, N, K, c, so, bo, si, bi); \
+        if (int4) hipLaunchKernelGGL((quantize_kernel<G, true, kInt4>), grid, block, 0, stream, w, N, K, c, so, bo, si, bi); \
+        else if (fit) hipLaunchKernelGGL((quantize_kernel<G, true>), grid, block, 0, stream, w, N, K, c, so, bo, si, bi); \
         else hipLaunchKernelGGL((quantize_kernel<G, false>), grid, block, 0, stream, w, N, K, c, so, bo, si, bi);    \
     } while (0)
     switch (group) {
@@ -266,11 +294,20 @@ int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed
     return check_launch();
 }
 
-int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, hipStream_t stream)
+int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, bool int4, hipStream_t stream)
 {
     const dim3 grid = tile_grid(N, K), block(kThreads);
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* o = static_cast<half_t*>(W_out);
+    if (int4) {
+        switch (group) {
+            case 32: hipLaunchKernelGGL((dequant_kernel<32, kInt4>), grid, block, 0, stream, c, N, K, o); break;
+            case 64: hipLaunchKernelGGL((dequant_kernel<64, kInt4>), grid, block, 0, stream, c, N, K, o); break;
+            case 128: hipLaunchKernelGGL((dequant_kernel<128, kInt4>), grid, block, 0, stream, c, N, K, o); break;
+            default: return E0M4_ERR_GROUP;
+        }
+        return check_launch();
+    }
     switch (group) {
         case 32: hipLaunchKernelGGL(dequant_kernel<32>, grid, block, 0, stream, c, N, K, o); break;
         case 64: hipLaunchKernelGGL(dequant_kernel<64>, grid, block, 0, stream, c, N, K, o); break;

@@ -19,6 +19,8 @@ CHATGLM2_6B = [("qkv", 4608, 4096), ("attn_out", 4096, 4096), ("ffn_gate_up", 27
 GEMMA_2B = [("qkv", 2560, 2048), ("attn_out", 2048, 2048), ("ffn_gate_up", 32768, 2048), ("ffn_down", 2048, 16384)]
 GEMMA_2B_LM_HEAD = ("lm_head", 256000, 2048)
 DENSE_14B = [("qkv", 15360, 5120), ("attn_out", 5120, 5120), ("ffn_gate_up", 27392, 5120), ("ffn_down", 5120, 13696)]
+# weight shapes [K, N] of the latency comparison between E0M4 and INT4 (paper: Table 1), M = 1
+TABLE1_SHAPES = [(4096, 4096), (4096, 11008), (11008, 4096)]
 CHATGLM2_LAYERS = 28
 DENSE_14B_LAYERS = 40
 GEMMA_2B_LAYERS = 18
