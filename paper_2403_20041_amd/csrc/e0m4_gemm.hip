@@ -221,29 +221,22 @@ int launch_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     return check_launch();
 }
 
-template <int G>
-int launch_g(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
-{
-    return launch_tile<G, 128, 128>(x, M, c, N, K, y, stream);
-}
-
 // The pipelined 256 x 256 kernel runs whenever its work items (tiles x K splits) can occupy a good
-// part of the chip; small problems (and K not a multiple of 128) take the 128 x 128 tile of this
-// file.  Returns the wavefront count of the pipelined kernel to use, or 0 for the kernels here.
-int pipe_waves(int64_t M, int64_t N, int64_t K)
+// part of the chip; small problems (and K not a multiple of 128) take the 128 x 128 tile of this file.
+bool use_pipe(int64_t M, int64_t N, int64_t K)
 {
-    if (!gemm_pipe_supported(K)) return 0;
+    if (!gemm_pipe_supported(K)) return false;
     const int v = knob("gemm_variant");             // 1: always the small tile of this file, 2: always the pipelined kernel
-    if (v == 2) return 8;
-    if (v == 1) return 0;
-    return gemm_pipe_work_items(M, N, K) >= 96 ? 8 : 0;
+    if (v == 2) return true;
+    if (v == 1) return false;
+    return gemm_pipe_work_items(M, N, K) >= 96;
 }
 
 }  // namespace
 
 size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    return pipe_waves(M, N, K) ? gemm_pipe_workspace_bytes(M, N, K) : 0;
+    return use_pipe(M, N, K) ? gemm_pipe_workspace_bytes(M, N, K) : 0;
 }
 
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
@@ -252,12 +245,11 @@ int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t
     const half_t* x = static_cast<const half_t*>(X);
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
-    if (const int waves = pipe_waves(M, N, K))
-        return launch_gemm_pipe(X, M, packed, N, K, group, waves, Y, workspace, workspace_bytes, stream);
+    if (use_pipe(M, N, K)) return launch_gemm_pipe(X, M, packed, N, K, group, Y, workspace, workspace_bytes, stream);
     switch (group) {
-        case 32: return launch_g<32>(x, M, c, N, K, y, stream);
-        case 64: return launch_g<64>(x, M, c, N, K, y, stream);
-        case 128: return launch_g<128>(x, M, c, N, K, y, stream);
+        case 32: return launch_tile<32, 128, 128>(x, M, c, N, K, y, stream);
+        case 64: return launch_tile<64, 128, 128>(x, M, c, N, K, y, stream);
+        case 128: return launch_tile<128, 128, 128>(x, M, c, N, K, y, stream);
         default: return E0M4_ERR_GROUP;
     }
 }

@@ -2,9 +2,10 @@
 // optimizations", matrix-matrix product; dequantisation of section "E0M4 FP4 quantization" fused
 // in registers).
 //
-// One wavefront per SIMD owns a 128 x 128 quarter of the tile (256 fp32 accumulator registers per
-// lane), so nothing but its own instruction stream can hide latency.  The stream is therefore laid
-// out by hand, per K slice of 64 (= 4 MFMA sub-steps of 16):
+// Eight wavefronts (2 x 4, two per SIMD) share the tile, 128 x 64 outputs and 128 fp32 accumulator
+// registers per lane each, which leaves two wavefronts per SIMD at most: little but a wavefront's own
+// instruction stream can hide latency.  The stream is therefore laid out by hand, per K slice of 64
+// (= 4 MFMA sub-steps of 16):
 //   - activations: global -> registers (issued two slices ahead) -> LDS ring of three stages ->
 //     16-byte fragments, read one sub-step ahead of their use;
 //   - weights: never touch LDS.  Lane (n = l%32, h = l/32) reads the 16-byte chunk of row n with
@@ -41,9 +42,10 @@ __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2
     return (w1 - bias2) * scale2;                       // difference exact, product rounded once
 }
 
-// WGM x WGN wavefronts share the tile: 2 x 2 (one per SIMD, 128 x 128 each) or 2 x 4 (two per SIMD,
-// 128 x 64 each, which doubles the instruction issue capacity and lets one wavefront's waits hide
-// behind the other's MFMAs, for twice the activation fragment traffic).
+// WGM x WGN wavefronts share the tile.  Built as 2 x 4 (two per SIMD, 128 x 64 each): against 2 x 2
+// (one per SIMD, 128 x 128 each) that doubles the instruction issue capacity and lets one wavefront's
+// waits hide behind the other's MFMAs, for twice the activation fragment traffic; 2 x 2 was measured
+// slower and does not fit the register file once the split-K epilogue is compiled in.
 template <int G, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
                                                              const uint4* __restrict__ packed, int64_t N, int64_t K,
@@ -354,16 +356,6 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     return check_launch();
 }
 
-template <int G>
-int launch_pipe_g(int waves, const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y,
-                  void* workspace, size_t workspace_bytes, hipStream_t stream)
-{
-    // Only the 2 x 4 arrangement is built: with one wavefront per SIMD (2 x 2) the kernel is bound by
-    // instruction issue and, with the split-K epilogue, no longer fits the register file.
-    (void)waves;
-    return launch_pipe<G, 2, 4>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
-}
-
 }  // namespace
 
 bool gemm_pipe_supported(int64_t K) { return K >= 128 && (K % (2 * BK)) == 0; }
@@ -383,16 +375,16 @@ int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K)
     return tiles * choose_splits(tiles, K);
 }
 
-int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, int waves,
-                     void* Y, void* workspace, size_t workspace_bytes, hipStream_t stream)
+int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                     void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
     const half_t* x = static_cast<const half_t*>(X);
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     switch (group) {
-        case 32: return launch_pipe_g<32>(waves, x, M, c, N, K, y, workspace, workspace_bytes, stream);
-        case 64: return launch_pipe_g<64>(waves, x, M, c, N, K, y, workspace, workspace_bytes, stream);
-        case 128: return launch_pipe_g<128>(waves, x, M, c, N, K, y, workspace, workspace_bytes, stream);
+        case 32: return launch_pipe<32, 2, 4>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
+        case 64: return launch_pipe<64, 2, 4>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
+        case 128: return launch_pipe<128, 2, 4>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
         default: return E0M4_ERR_GROUP;
     }
 }

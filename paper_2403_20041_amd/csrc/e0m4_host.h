@@ -40,7 +40,7 @@ size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 bool gemm_pipe_supported(int64_t K);
 size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K);      // tiles x K splits
-int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, int waves,
-                     void* Y, void* workspace, size_t workspace_bytes, hipStream_t stream);
+int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                     void* workspace, size_t workspace_bytes, hipStream_t stream);
 
 }  // namespace e0m4
