@@ -29,8 +29,11 @@
  *     weights (e0m4_matmul, e0m4_dequant) read the parameters from this
  *     embedded copy; the separate `scales`/`bias` arrays are the plain view of
  *     the same values.  Use e0m4_unpack_codes / e0m4_dequant to look inside.
- *   - Shape rules: N >= 0, M >= 0, K >= 0, K % 32 == 0, K % group == 0,
- *     group in {32, 64, 128}.  Data pointers must be 16-byte aligned.
+ *   - Shape rules: 0 <= N <= 2^31, 0 <= M <= 2^31, 0 <= K <= 2^20,
+ *     K % 32 == 0, K % group == 0, group in {32, 64, 128}.  (The K limit keeps
+ *     every 32-bit offset the kernels form inside one workgroup's share of the
+ *     packed buffer, or inside one tile's rows of X, below 2 GiB.)  Data
+ *     pointers must be 16-byte aligned.
  *   - Return value: 0 on success; a negative E0M4_ERR_* code otherwise, in
  *     which case nothing was enqueued (except E0M4_ERR_HIP, where a launch
  *     itself failed; see e0m4_last_hip_error).  Nothing throws.
@@ -51,7 +54,7 @@ extern "C" {
 
 #define E0M4_OK              0
 #define E0M4_ERR_NULL      (-1)   /* a required pointer is NULL */
-#define E0M4_ERR_SHAPE     (-2)   /* negative size, K not a multiple of 32 or of group */
+#define E0M4_ERR_SHAPE     (-2)   /* size negative or above its limit, K not a multiple of 32 or of group */
 #define E0M4_ERR_GROUP     (-3)   /* unsupported group size */
 #define E0M4_ERR_ALIGN     (-4)   /* a data pointer is not 16-byte aligned */
 #define E0M4_ERR_WORKSPACE (-5)   /* workspace smaller than e0m4_workspace_bytes() */
@@ -110,7 +113,8 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  * optimizations", fp16 activation x 4-bit weight matmul; vector-matrix for
  * decode, matrix-matrix for prefill).  Dequantisation is fused in registers;
  * accumulation is fp32; Y is rounded once to fp16.
- *   M <= 8 : HBM-bound GEMV path (one workgroup per 16 output rows).
+ *   M <= 8 : HBM-bound GEMV path (a workgroup owns whole blocks of 16 output
+ *            rows over all of K; no partial sums leave the compute unit).
  *   M >= 9 : MFMA GEMM path.
  * `scales_f16`/`bias_f16` may be NULL (see `codes` above); `workspace` may be
  * NULL when e0m4_workspace_bytes() is 0, else it is device memory of at least

@@ -38,7 +38,7 @@ int check_shape(int64_t N, int64_t K, int group)
 {
     if (!group_ok(group)) return E0M4_ERR_GROUP;
     if (N < 0 || K < 0 || (K % kCodesPerChunk) != 0 || (K % group) != 0) return E0M4_ERR_SHAPE;
-    if (N > (int64_t)1 << 31 || K > (int64_t)1 << 22) return E0M4_ERR_SHAPE;
+    if (N > (int64_t)1 << 31 || K > (int64_t)1 << 20) return E0M4_ERR_SHAPE;   // 32-bit offsets in the kernels
     return E0M4_OK;
 }
 
@@ -74,7 +74,7 @@ const char* e0m4_strerror(int code)
     switch (code) {
         case E0M4_OK: return "ok";
         case E0M4_ERR_NULL: return "a required pointer is NULL";
-        case E0M4_ERR_SHAPE: return "bad shape: sizes must be >= 0, K a multiple of 32 and of the group size";
+        case E0M4_ERR_SHAPE: return "bad shape: sizes must be >= 0 and within their limits, K a multiple of 32 and of the group size";
         case E0M4_ERR_GROUP: return "unsupported group size (supported: 32, 64, 128)";
         case E0M4_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
         case E0M4_ERR_WORKSPACE: return "workspace is smaller than e0m4_workspace_bytes()";

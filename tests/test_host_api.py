@@ -74,6 +74,8 @@ def test_error_codes_before_any_launch(L):
     assert L.e0m4_unpack_codes(p, 64, 130, 32, p, null) == ERR_SHAPE
     assert L.e0m4_matmul(p, 1, p, p, p, 64, 100, 128, p, null, 0, null) == ERR_SHAPE
     assert L.e0m4_matmul(p, -1, p, p, p, 64, 128, 128, p, null, 0, null) == ERR_SHAPE
+    assert L.e0m4_matmul(p, 1, p, p, p, 64, (1 << 20) + 128, 128, p, null, 0, null) == ERR_SHAPE     # K above its limit
+    assert L.e0m4_quantize(p, (1 << 31) + 1, 128, 128, p, p, p, null) == ERR_SHAPE
     assert L.e0m4_matmul(null, 1, p, p, p, 64, 128, 128, p, null, 0, null) == ERR_NULL
     assert L.e0m4_matmul(p, 1, p, p, p, 64, 128, 128, odd, null, 0, null) == ERR_ALIGN
     assert L.e0m4_matmul(p, 1, null, p, p, 64, 128, 128, p, null, 0, null) == ERR_NULL
