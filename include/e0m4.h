@@ -30,7 +30,8 @@
  *     embedded copy; the separate `scales`/`bias` arrays are the plain view of
  *     the same values.  Use e0m4_unpack_codes / e0m4_dequant to look inside.
  *   - Shape rules: 0 <= N <= 2^31, 0 <= M <= 2^31, 0 <= K <= 2^20,
- *     K % 32 == 0, K % group == 0, group in {32, 64, 128}.  (The K limit keeps
+ *     K % 32 == 0, K % group == 0, group in {32, 64, 128}; e0m4_matmul with
+ *     M > 8 also needs N <= 2^24.  (The K limit keeps
  *     every 32-bit offset the kernels form inside one workgroup's share of the
  *     packed buffer, or inside one tile's rows of X, below 2 GiB.)  Data
  *     pointers must be 16-byte aligned.

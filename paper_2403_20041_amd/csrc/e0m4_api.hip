@@ -214,6 +214,7 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
     if (!X || !codes) return E0M4_ERR_NULL;
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
     if (M <= kGemvMaxM) return launch_gemv(X, M, codes, N, K, group, Y, (hipStream_t)stream);
+    if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // the GEMM epilogue forms 32-bit offsets of up to 256 rows of Y
     if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
     return launch_gemm(X, M, codes, N, K, group, Y, workspace, workspace_bytes, (hipStream_t)stream);
 }
