@@ -71,8 +71,8 @@ const char* e0m4_last_hip_error(void);
 size_t e0m4_codes_bytes(int64_t N, int64_t K, int group);
 /* Number of fp16 elements in `scales` (and in `bias`): N * (K/group). */
 size_t e0m4_params_elems(int64_t N, int64_t K, int group);
-/* Scratch bytes e0m4_matmul needs for this shape: 0 for M <= 8 (partial sums
- * stay on chip) and for GEMM shapes with enough output tiles to fill the GPU;
+/* Scratch bytes e0m4_matmul needs for this shape: 0 for the small-M paths
+ * (partial sums stay on chip) and for GEMM shapes with enough output tiles to fill the GPU;
  * otherwise splits * M * N * 4 bytes of fp32 partial sums for the GEMM's split
  * along K.  Depends on the tuning knobs in force; query after setting them. */
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
@@ -116,7 +116,11 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  * accumulation is fp32; Y is rounded once to fp16.
  *   M <= 8 : HBM-bound GEMV path (a workgroup owns whole blocks of 16 output
  *            rows over all of K; no partial sums leave the compute unit).
- *   M >= 9 : MFMA GEMM path.
+ *   3 <= M <= 16, group 128, M rows of X fit the LDS of a compute unit
+ *            (about M * K * 2 <= 140 KiB): same decomposition, the dot
+ *            products run on the matrix cores so the cost stays near the
+ *            weight stream for every such M.
+ *   M >= 9 otherwise : MFMA GEMM path.
  * `scales_f16`/`bias_f16` may be NULL (see `codes` above); `workspace` may be
  * NULL when e0m4_workspace_bytes() is 0, else it is device memory of at least
  * that many bytes, 16-byte aligned, owned by the caller, overwritten by the

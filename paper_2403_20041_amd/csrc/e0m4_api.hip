@@ -20,6 +20,7 @@ struct Knob {
 Knob g_knobs[] = {
     {"gemv_waves", {0}},               // wavefronts per workgroup of the small-M kernel (4, 8 or 16)
     {"gemv_workgroups", {0}},          // target number of workgroups of the small-M kernel
+    {"gemv_mfma", {0}},                // 1: never use the matrix-core small-batch kernel (3 <= M <= 16)
     {"gemm_variant", {0}},             // select a GEMM kernel variant
     {"gemm_splits", {0}},              // force the number of K splits of the pipelined GEMM kernel
 };
@@ -31,6 +32,10 @@ __global__ void zero_fill_kernel(half_t* y, int64_t count)
 }
 
 bool group_ok(int group) { return group == 32 || group == 64 || group == 128; }
+bool use_gemv_mfma(int64_t M, int64_t N, int64_t K, int group)
+{
+    return knob("gemv_mfma") != 1 && gemv_mfma_supported(M, N, K, group);
+}
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Shape rules shared by all entry points.
@@ -99,7 +104,8 @@ size_t e0m4_params_elems(int64_t N, int64_t K, int group)
 
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 {
-    if (check_shape(N, K, group) != E0M4_OK || M <= kGemvMaxM || K == 0) return 0;   // the small-M kernel needs none
+    if (check_shape(N, K, group) != E0M4_OK || M <= kGemvMaxM || K == 0) return 0;   // the small-M kernels need none
+    if (use_gemv_mfma(M, N, K, group)) return 0;
     return gemm_workspace_bytes(M, N, K);       // partial tiles of the split-K GEMM, if it splits
 }
 
@@ -213,6 +219,7 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
     }
     if (!X || !codes) return E0M4_ERR_NULL;
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    if (use_gemv_mfma(M, N, K, group)) return launch_gemv_mfma(X, M, codes, N, K, Y, (hipStream_t)stream);
     if (M <= kGemvMaxM) return launch_gemv(X, M, codes, N, K, group, Y, (hipStream_t)stream);
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // the GEMM epilogue forms 32-bit offsets of up to 256 rows of Y
     if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;

@@ -1,0 +1,287 @@
+// Small-batch decode path of e0m4_matmul: Y[M,N] = X[M,K] * dequant(packed)^T for 3 <= M <= 16 and
+// group size 128.  Paper: section "Operator and lagging optimizations" (vector-matrix product of the
+// decoding stage, bound by memory bandwidth) with the dequantisation of section "E0M4 FP4
+// quantization" fused in registers.
+//
+// Same work decomposition as the M = 1 kernel (a workgroup owns whole 16-row blocks over all of K, a
+// work item is four consecutive 16 x 128 weight blocks, the next item is in flight while the current
+// one is processed), but the dot products run on the matrix cores: per weight block four
+// v_mfma_f32_16x16x32_f16 compute the 16 (rows of X, padded) x 16 (weight rows) products over the
+// block's 128 k, so the vector work per block (bit operations on the codes, the group's affine map)
+// no longer grows with M and the kernel stays close to the memory stream for every M up to 16.
+//
+// Operands.  The weight operand of an MFMA is taken straight from the lane's 16-byte chunk: lane
+// (n = l%16, q = l/16) owns the 32 codes of weight row n, k = 32q..32q+31, and supplies 8 of them per
+// MFMA, which is exactly the k-group layout of the instruction (lane l supplies k-group l/16).  The
+// code pairs that read 2 + c/8 after the mask-or (pairs 0 and 3 of a word) and those that read
+// 2 + c/128 (pairs 1 and 2) go to separate MFMAs and accumulators, and are folded back with
+//     sum x*(2 + c/8) = 16 * sum x*(2 + c/128) - 30 * sum x       (over the k of pairs 1 and 2).
+// The activation operand comes from LDS, where X is staged once per workgroup in the order the
+// MFMAs consume it (one 16-byte unit per MFMA and lane), with the two sums per (row of X, block).
+// One group of 128 k is one block, so the group's affine map  y += scale * (a - bias * sum x)  is
+// applied once per block on the MFMA result; that is why this kernel needs group size 128.
+#include "e0m4_device.h"
+#include "e0m4_host.h"
+
+#include <algorithm>
+
+namespace e0m4 {
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kSuper = 4;                       // weight blocks (of 128 k) per work item
+constexpr int kG = 128;                         // group size: one group per block
+constexpr int kMinM = 3;                         // below, the vector kernel is as fast or faster
+constexpr int kMaxM = 16;
+constexpr int kPW = block_param_words(kG);      // 16 parameter words per block
+constexpr int kXBlockBytes = kBlockK * 2;       // one row of X, one block: 256 bytes
+constexpr int kRowPadBytes = 16;                // keeps the 16 rows of X in different LDS bank groups
+constexpr int kSumBytesPerBlock = 2 * kMaxM * 4;        // (sum x, 30 * sum of x over pairs 1 and 2) per row of X
+constexpr int kLdsLimitBytes = 156 * 1024;      // of the 160 KiB of a compute unit
+constexpr int kTargetWorkgroups = 256;          // one workgroup per compute unit
+
+struct MfmaPlan {
+    int waves;
+    int step_slots, step_item;                  // a wavefront's next work item: W items ahead, as (row blocks, items) with carry
+    int rb_base, rb_rem;                        // even deal of row blocks
+    int64_t grid;
+    size_t lds_bytes;
+};
+
+size_t lds_need(int64_t M, int64_t nkb, int waves)
+{
+    return (size_t)M * (nkb * kXBlockBytes + kRowPadBytes) + (size_t)nkb * kSumBytesPerBlock +
+           2 * (size_t)waves * kMaxM * kBlockRows * sizeof(float);
+}
+
+// Byte offset, inside one block of one row of X, of the 8-byte half-unit that holds the elements of
+// word w (k = 8w..8w+7 of chunk q) for the MFMA of pair set hl (0: elements 0,1,6,7; 1: elements 2..5).
+__device__ inline int x_unit_off(int q, int w, int hl) { return ((q * 4 + (w >> 1) * 2 + hl) << 4) + ((w & 1) << 3); }
+
+template <int W>
+__global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restrict__ X, int M,
+                                                           const uint4* __restrict__ packed, int64_t N, int64_t K,
+                                                           half_t* __restrict__ Y, int step_slots, int step_item,
+                                                           int rb_base, int rb_rem)
+{
+    constexpr int kThreads = W * 64;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const PackedLayout<kG> lay(K);
+    const int nkb = (int)lay.nkb;
+    const int nsi = (nkb + kSuper - 1) / kSuper;
+    const int row_stride = nkb * kXBlockBytes + kRowPadBytes;
+    unsigned char* xs = smem;                                                   // [M] rows of X in MFMA order
+    float* sums = reinterpret_cast<float*>(smem + (size_t)M * row_stride);      // [nkb][2][16]
+    float* red = sums + (size_t)nkb * 2 * kMaxM;                                // [2][W][16 m][16 n]
+
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int n_l = lane & 15, g_l = lane >> 4;         // weight row / k-group of this lane; also (row of X, k-group)
+    const uint32_t fmask = frac_mask_vgpr(), fmask_low = frac_mask_low_vgpr();
+    const int64_t rb0 = (int64_t)blockIdx.x * rb_base + min((int)blockIdx.x, rb_rem);
+    const int n_rb = rb_base + ((int)blockIdx.x < rb_rem ? 1 : 0);
+    const __amdgpu_buffer_rsrc_t wg_codes = make_rsrc(packed + lay.code_index(rb0, 0));
+    const __amdgpu_buffer_rsrc_t wg_params = make_rsrc(reinterpret_cast<const char*>(packed) + 4 * lay.param_index(rb0, 0));
+    const uint32_t rb_stride = (uint32_t)nkb * block_bytes(kG);
+    const uint32_t lane_code_off = lane * 16;
+    const int param_words_rb = nkb * kPW;
+
+    auto advance = [&](int& s_, int& i_) {              // W work items ahead
+        s_ += step_slots;
+        i_ += step_item;
+        if (i_ >= nsi) {
+            i_ -= nsi;
+            ++s_;
+        }
+    };
+    int slot = 0, si = wave;                            // current work item: row block slot, item inside the row block
+    while (si >= nsi) {
+        si -= nsi;
+        ++slot;
+    }
+    int nslot = slot, nitem = si;
+    advance(nslot, nitem);
+
+    // ---- the work item in flight: four code blocks and their 64 parameter words (one per lane)
+    uint4 c[kSuper];
+    uint32_t pwraw;
+    auto fetch_params = [&](int fs, int fi) {           // past the end the last item is read again
+        const bool in = fs < n_rb;
+        const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(s_ * rb_stride + i_ * (kSuper * kPW * 4));
+        const int last = param_words_rb - 1 - (int)i_ * (kSuper * kPW);
+        pwraw = __builtin_amdgcn_raw_buffer_load_b32(wg_params, min(lane, last) * 4, (int)soff, 0);
+    };
+    auto fetch_code = [&](int j, int fs, int fi) {      // k blocks beyond K: the last block again (their X is zero)
+        const bool in = fs < n_rb;
+        const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
+        const uint32_t kb = min(i_ * kSuper + j, (uint32_t)nkb - 1);
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(s_ * rb_stride + kb * kBlockCodeBytes);
+        const u32x4 cv = __builtin_amdgcn_raw_buffer_load_b128(wg_codes, (int)lane_code_off, (int)soff, 0);
+        c[j] = make_uint4(cv.x, cv.y, cv.z, cv.w);
+    };
+    fetch_params(slot, si);
+#pragma unroll
+    for (int j = 0; j < kSuper; ++j) fetch_code(j, slot, si);
+
+    // ---- stage X: thread idx handles the 8 elements k = 8*pc..8*pc+7 of row m; 16 consecutive threads
+    // cover one block of one row and add up its two sums
+    const int pieces = nkb * (kBlockK / 8);
+    for (int base = 0; base < M * pieces; base += kThreads) {
+        const int idx = base + t;
+        const int m = idx / pieces, pc = idx - m * pieces;
+        const int64_t k = (int64_t)pc * 8;
+        half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (idx < M * pieces && k < K) v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+        const half2_t ones = {(half_t)1.f, (half_t)1.f};
+        const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
+        float sl = __builtin_amdgcn_fdot2(x1, ones, 0.f, false);
+        sl = __builtin_amdgcn_fdot2(x2, ones, sl, false);
+        float s = __builtin_amdgcn_fdot2(x0, ones, sl, false);
+        s = __builtin_amdgcn_fdot2(x3, ones, s, false);
+#pragma unroll
+        for (int d = 1; d < 16; d <<= 1) {
+            s += __shfl_xor(s, d);
+            sl += __shfl_xor(sl, d);
+        }
+        if (idx < M * pieces) {
+            const int kb = pc >> 4, q = (pc >> 2) & 3, w = pc & 3;
+            unsigned char* blk = xs + (size_t)m * row_stride + kb * kXBlockBytes;
+            const half4_t hpart = {v[0], v[1], v[6], v[7]}, lpart = {v[2], v[3], v[4], v[5]};
+            *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 0)) = hpart;
+            *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 1)) = lpart;
+            if ((pc & 15) == 0) {
+                sums[(kb * 2 + 0) * kMaxM + m] = s;
+                sums[(kb * 2 + 1) * kMaxM + m] = 30.f * sl;
+            }
+        }
+    }
+    __syncthreads();
+
+    // X operand address of this lane: row min(l%16, M-1) (rows beyond M repeat the last one; their
+    // results are never stored), k-group l/16
+    const unsigned char* x_lane = xs + (size_t)min(n_l, M - 1) * row_stride + g_l * 64;
+
+    const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    for (int s_rb = 0; s_rb < n_rb; ++s_rb) {
+        floatx4 ysum = zero4;                           // this wavefront's share of Y[4*g_l .. 4*g_l+3][row n_l] of row block s_rb
+        while (slot == s_rb) {
+            // parameter word of (block j, weight row n_l): lane 16 j + n_l of the item's 64 words
+            uint32_t pwj[kSuper];
+#pragma unroll
+            for (int j = 0; j < kSuper; ++j) pwj[j] = (uint32_t)__builtin_amdgcn_ds_bpermute((j * kPW + n_l) * 4, (int)pwraw);
+            fetch_params(nslot, nitem);
+#pragma unroll
+            for (int j = 0; j < kSuper; ++j) {
+                const int kb = si * kSuper + j;         // may lie beyond K in the last item: X and sums are zero there
+                const float sc = (float)param_scale(pwj[j]);
+                const float bi = (float)param_bias(pwj[j]);
+                const uint32_t words[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
+                half2_t p[4][4];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) w1_pairs_mixed(words[w], fmask, fmask_low, p[w]);
+                fetch_code(j, nslot, nitem);            // the block's registers are free: request the next item's
+                floatx4 acc_h = zero4, acc_l = zero4;
+                const unsigned char* xb = x_lane + (size_t)min(kb, nkb - 1) * kXBlockBytes;
+#pragma unroll
+                for (int wp = 0; wp < 2; ++wp) {
+                    const half8_t xh = *reinterpret_cast<const half8_t*>(xb + wp * 32);
+                    const half8_t xl = *reinterpret_cast<const half8_t*>(xb + wp * 32 + 16);
+                    const half2_t* w0 = p[2 * wp];
+                    const half2_t* w1 = p[2 * wp + 1];
+                    const half8_t wh = {w0[0][0], w0[0][1], w0[3][0], w0[3][1], w1[0][0], w1[0][1], w1[3][0], w1[3][1]};
+                    const half8_t wl = {w0[1][0], w0[1][1], w0[2][0], w0[2][1], w1[1][0], w1[1][1], w1[2][0], w1[2][1]};
+                    acc_h = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh, wh, acc_h, 0, 0, 0);
+                    acc_l = __builtin_amdgcn_mfma_f32_16x16x32_f16(xl, wl, acc_l, 0, 0, 0);
+                }
+                if (kb < nkb) {
+                    const floatx4 sx = *reinterpret_cast<const floatx4*>(&sums[(kb * 2 + 0) * kMaxM + 4 * g_l]);
+                    const floatx4 sx30 = *reinterpret_cast<const floatx4*>(&sums[(kb * 2 + 1) * kMaxM + 4 * g_l]);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        ysum[r] += sc * ((acc_h[r] + 16.f * acc_l[r] - sx30[r]) - bi * sx[r]);
+                }
+            }
+            slot = nslot;
+            si = nitem;
+            advance(nslot, nitem);
+        }
+        // the wavefronts' shares of row block s_rb are added in wavefront order
+        float* mine = red + (((s_rb & 1) * W + wave) * kMaxM + 4 * g_l) * kBlockRows + n_l;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mine[r * kBlockRows] = ysum[r];
+        __syncthreads();
+        if (t < kMaxM * kBlockRows) {
+            const int m = t >> 4, n = t & 15;
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < W; ++w) s += red[(((s_rb & 1) * W + w) * kMaxM + m) * kBlockRows + n];
+            const int64_t row = (rb0 + s_rb) * kBlockRows + n;
+            if (m < M && row < N) Y[(int64_t)m * N + row] = (half_t)s;
+        }
+        // no second barrier: row block s_rb + 1 uses the other half of `red`, and nobody writes this
+        // half again before passing the barrier of s_rb + 1, which the readers above reach after reading
+    }
+}
+
+bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p)
+{
+    const int64_t nrb = row_blocks(N), nkb = k_blocks(K);
+    const int64_t nsi = (nkb + kSuper - 1) / kSuper;
+    int w = knob("gemv_waves");
+    if (w != 4 && w != 8 && w != 16) w = nsi >= 16 ? 16 : 8;
+    while (w > 4 && lds_need(M, nkb, w) > (size_t)kLdsLimitBytes) w /= 2;
+    if (lds_need(M, nkb, w) > (size_t)kLdsLimitBytes) return false;
+    int target = knob("gemv_workgroups");
+    if (target <= 0) target = kTargetWorkgroups;
+    p.grid = std::min<int64_t>(nrb, target);
+    p.waves = w;
+    p.step_slots = (int)(w / nsi);
+    p.step_item = (int)(w % nsi);
+    p.rb_base = (int)(nrb / p.grid);
+    p.rb_rem = (int)(nrb % p.grid);
+    p.lds_bytes = lds_need(M, nkb, w);
+    return true;
+}
+
+template <int W>
+int launch_mfma(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                hipStream_t stream)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_mfma_kernel<W>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimitBytes);
+        if (e != hipSuccess) return record_hip_error(e);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gemv_mfma_kernel<W>, dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
+                       static_cast<const half_t*>(X), (int)M, static_cast<const uint4*>(packed), N, K,
+                       static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem);
+    return check_launch();
+}
+
+}  // namespace
+
+bool gemv_mfma_supported(int64_t M, int64_t N, int64_t K, int group)
+{
+    if (group != kG || M < kMinM || M > kMaxM || N <= 0 || K <= 0) return false;
+    MfmaPlan p;
+    return make_mfma_plan(M, N, K, p);
+}
+
+int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+{
+    MfmaPlan p;
+    if (!make_mfma_plan(M, N, K, p)) return E0M4_ERR_SHAPE;
+    switch (p.waves) {
+        case 4: return launch_mfma<4>(p, X, M, packed, N, K, Y, stream);
+        case 8: return launch_mfma<8>(p, X, M, packed, N, K, Y, stream);
+        default: return launch_mfma<16>(p, X, M, packed, N, K, Y, stream);
+    }
+}
+
+}  // namespace e0m4

@@ -26,6 +26,9 @@ int launch_unpack(const void* packed, int64_t N, int64_t K, int group, void* out
 constexpr int kGemvMaxM = 8;
 int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                 hipStream_t stream);
+// Small-batch path on the matrix cores: 3 <= M <= 16, group 128, X must fit the LDS of one compute unit.
+bool gemv_mfma_supported(int64_t M, int64_t N, int64_t K, int group);
+int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream);
 // INT4 twin of the M = 1 kernel: same layout and work decomposition, codes turned into numbers with
 // integer-to-float conversion instructions.
 int launch_gemv_int4(const void* X, const void* packed, int64_t N, int64_t K, int group, void* Y, hipStream_t stream);

@@ -20,7 +20,7 @@ def e0m4():
     import paper_2403_20041_amd as pkg
 
     pkg.lib()                                   # raises if the HIP library is not built
-    for k in ("gemv_waves", "gemv_workgroups", "gemm_variant", "gemm_splits"):
+    for k in ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemm_variant", "gemm_splits"):
         pkg.e0m4_set_knob(k, 0)
     return pkg
 
@@ -216,6 +216,46 @@ def test_gemv_ragged_last_work_item(e0m4, oracle, M):
     # K = 13 and 14 blocks of 128: the last group of four k blocks holds one or two; N ends inside a row block
     run_matmul_case(e0m4, oracle, M, 203, 1664, 128, seed=80 + M)
     run_matmul_case(e0m4, oracle, M, 77, 1760, 32, seed=90 + M)     # K = 13.75 blocks: ragged inside the last block
+
+
+# ------------------------------------------------------------------ matmul, small batch on the matrix cores
+
+@pytest.mark.parametrize("M", [2, 3, 4, 5, 7, 8, 9, 12, 15, 16])
+def test_small_batch_matrix_core_kernel(e0m4, oracle, M):
+    # group 128 and 3 <= M <= 16: the MFMA small-batch kernel (M = 2 stays on the vector kernel)
+    run_matmul_case(e0m4, oracle, M, 200, 1152, 128, seed=130 + M)              # 9 k blocks: ragged last work item
+    run_matmul_case(e0m4, oracle, M, 333, 4096, 128, seed=140 + M, outliers=True)
+    run_matmul_case(e0m4, oracle, M, 40, 128, 128, seed=150 + M)                # a single block
+    run_matmul_case(e0m4, oracle, M, 1000, 1664, 128, seed=160 + M, row_std=(0.5, 2.0))   # 13 k blocks, N ends inside a row block
+
+
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("target", [0, 3])
+def test_small_batch_matrix_core_kernel_forced_shapes(e0m4, oracle, waves, target):
+    e0m4.e0m4_set_knob("gemv_waves", waves)
+    e0m4.e0m4_set_knob("gemv_workgroups", target)       # 3 workgroups: many row blocks each
+    try:
+        run_matmul_case(e0m4, oracle, 6, 300, 2304, 128, seed=170 + waves)
+        run_matmul_case(e0m4, oracle, 16, 130, 4096, 128, seed=171 + waves)
+    finally:
+        e0m4.e0m4_set_knob("gemv_waves", 0)
+        e0m4.e0m4_set_knob("gemv_workgroups", 0)
+
+
+@pytest.mark.parametrize("M", [2, 5, 8])
+def test_small_batch_vector_kernel_when_the_matrix_core_kernel_is_off(e0m4, oracle, M):
+    e0m4.e0m4_set_knob("gemv_mfma", 1)
+    try:
+        run_matmul_case(e0m4, oracle, M, 200, 1152, 128, seed=180 + M)
+        run_matmul_case(e0m4, oracle, M, 333, 4096, 128, seed=190 + M, outliers=True)
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+
+
+def test_small_batch_falls_back_when_x_does_not_fit_lds(e0m4, oracle):
+    # 16 rows of K = 16384 need 512 KiB of LDS: the GEMM takes over; with 8 rows, the vector kernel
+    run_matmul_case(e0m4, oracle, 16, 130, 16384, 128, seed=200)
+    run_matmul_case(e0m4, oracle, 8, 130, 16384, 128, seed=201)
 
 
 # ------------------------------------------------------------------ matmul, MFMA path
