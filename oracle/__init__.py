@@ -216,3 +216,67 @@ def matmul(X: np.ndarray, What: np.ndarray, want_absdot: bool = True):
 
 def num_threads() -> int:
     return _load().oracle_num_threads()
+
+
+# --------------------------------------------------------------------------------------------------
+# Operators fused around the matmul (paper: section "Operator and lagging optimizations": the small
+# operators of rms-norm are fused into one, element-wise operators are fused into their neighbours).
+# The paper names the operators and gives no formulas; they are the textbook ones, written out in
+# fp64 with numpy:
+#   rms-norm   x'[k] = x[k] * gamma[k] / sqrt(mean_k(x^2) + eps)
+#   SiLU       silu(g) = g / (1 + exp(-g))
+#   gated unit y[j] = silu(a[j]) * a[N/2 + j]     (first half of the rows: gate, second half: up)
+#   residual   y = a + r
+# --------------------------------------------------------------------------------------------------
+
+def silu(g: np.ndarray) -> np.ndarray:
+    """g * sigmoid(g) in fp64, written so that exp never overflows."""
+    g = np.asarray(g, np.float64)
+    e = np.exp(-np.abs(g))                      # in (0, 1]
+    sig = np.where(g >= 0, 1.0 / (1.0 + e), e / (1.0 + e))
+    return g * sig
+
+
+def rmsnorm(X: np.ndarray, gamma: np.ndarray, eps: float) -> np.ndarray:
+    """Row-wise rms-norm of X [M,K] with weight gamma [K]; fp64 result (not rounded)."""
+    x = np.asarray(X).astype(np.float64)
+    g = np.asarray(gamma).astype(np.float64)
+    ms = np.mean(x * x, axis=1, keepdims=True)
+    return x * g[None, :] / np.sqrt(ms + float(eps))
+
+
+def matmul_fused(X: np.ndarray, What: np.ndarray, gamma=None, eps: float = 0.0, swiglu: bool = False,
+                 residual=None):
+    """The matmul with its neighbours folded in, each step the plain definition in fp64:
+
+    1. if gamma is given, X is replaced by fp16(rmsnorm(X, gamma, eps)) (the normalised activation is an
+       fp16 tensor, as it is when the operator runs on its own);
+    2. a[m,n] = sum_k X[m,k] * What[n,k];
+    3. if swiglu, y[m,j] = silu(a[m,j]) * a[m, N/2 + j] for j < N/2, else y = a;
+    4. if residual is given, y += residual;
+    5. one rounding to fp16.
+
+    Returns (Y fp16, info) where info holds what the acceptance tolerance is stated in: 'a' (fp64 sums of
+    step 2), 'absdot' (sum_k |x w| per entry of a) and 'y' (the fp64 result before step 5).
+    """
+    Xh = np.asarray(X)
+    assert Xh.dtype == np.float16 and np.asarray(What).dtype == np.float16
+    if gamma is not None:
+        Xh = rmsnorm(Xh, gamma, eps).astype(np.float16)
+    xd = Xh.astype(np.float64)
+    wd = np.asarray(What).astype(np.float64)
+    a = xd @ wd.T
+    absdot = np.abs(xd) @ np.abs(wd).T
+    if swiglu:
+        N = wd.shape[0]
+        assert N % 2 == 0
+        y = silu(a[:, : N // 2]) * a[:, N // 2:]
+    else:
+        y = a
+    if residual is not None:
+        r = np.asarray(residual)
+        assert r.dtype == np.float16 and r.shape == y.shape
+        y = y + r.astype(np.float64)
+    with np.errstate(over="ignore"):
+        Y = y.astype(np.float16)
+    return Y, {"a": a, "absdot": absdot, "y": y}

@@ -460,3 +460,101 @@ def test_table2_mae_ratio_with_the_oracle_int4(oracle):
     q, s4, z4 = oracle.int4_quantize(W, 128)
     mae_int4 = np.abs(w - oracle.int4_dequant(q, s4, z4, 128).astype(np.float64)).mean()
     assert abs(mae_e0m4 / mae_int4 - 0.955) <= 0.004
+
+
+# ---------------------------------------------------------------------------------------------------
+# Operators fused around the matmul (paper: section "Operator and lagging optimizations").  The oracle
+# writes the textbook formulas in numpy; the pins tie them to closed forms and to torch's own CPU
+# routines (an independent implementation), and the fused function to the composition of those.
+# ---------------------------------------------------------------------------------------------------
+
+def test_silu_closed_forms_and_library(oracle):
+    import torch
+    g = np.concatenate([np.linspace(-30, 30, 2001), [-800.0, 800.0, 0.0, -0.0]])
+    s = oracle.silu(g)
+    assert np.all(np.isfinite(s))
+    assert s[-2] == 0.0 and s[-1] == 0.0
+    np.testing.assert_allclose(s - oracle.silu(-g), g, rtol=0, atol=1e-12)         # silu(g) - silu(-g) = g
+    assert s[-4] == 0.0 and s[-3] == 800.0                                          # tails: 0 and the identity
+    # the one minimum of g*sigmoid(g): the derivative vanishes where g0 = -(1 + exp(g0)) = -1.2784645...,
+    # and the value there is g0 + 1 = -exp(g0)
+    fine = np.linspace(-1.3, -1.25, 200001)
+    i = np.argmin(oracle.silu(fine))
+    assert abs(fine[i] - (-1.2784645)) < 1e-5 and abs(oracle.silu(fine)[i] - (-0.2784645)) < 1e-7
+    g0 = -1.0
+    for _ in range(60):
+        g0 = -(1.0 + np.exp(g0))
+    assert abs(oracle.silu(np.array([g0]))[0] - (g0 + 1.0)) < 1e-15
+    ref = torch.nn.functional.silu(torch.from_numpy(g)).numpy()
+    np.testing.assert_allclose(s, ref, rtol=1e-14, atol=1e-300)
+
+
+def test_rmsnorm_invariants_and_library(oracle):
+    import torch
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((7, 96)).astype(np.float16)
+    gamma = (1.0 + 0.2 * rng.standard_normal(96)).astype(np.float16)
+    y = oracle.rmsnorm(X, gamma, 0.0)
+    # with eps = 0 the normalised rows have mean square 1 before gamma, and scaling a row changes nothing
+    np.testing.assert_allclose(np.mean((y / gamma.astype(np.float64)) ** 2, axis=1), 1.0, rtol=1e-13)
+    np.testing.assert_allclose(oracle.rmsnorm((X * np.float16(4)).astype(np.float16), gamma, 0.0), y, rtol=1e-13)
+    # eps sits inside the square root, next to the mean (not the sum) of squares
+    x1 = np.full((1, 4), 2.0, np.float16)
+    np.testing.assert_allclose(oracle.rmsnorm(x1, np.ones(4, np.float16), 5.0), np.full((1, 4), 2.0 / 3.0), rtol=1e-15)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(X.astype(np.float64)), (96,),
+                                       torch.from_numpy(gamma.astype(np.float64)), 1e-5).numpy()
+    np.testing.assert_allclose(oracle.rmsnorm(X, gamma, 1e-5), ref, rtol=1e-13)
+
+
+def test_matmul_fused_reduces_to_the_plain_matmul(oracle):
+    rng = np.random.default_rng(6)
+    X = rng.standard_normal((3, 64)).astype(np.float16)
+    W = rng.standard_normal((10, 64)).astype(np.float16)
+    Y, info = oracle.matmul_fused(X, W)
+    Yp, absdot = oracle.matmul(X, W)
+    assert np.array_equal(Y.view(np.uint16), Yp.view(np.uint16))
+    np.testing.assert_allclose(info["absdot"], absdot, rtol=1e-13)
+
+
+def test_matmul_fused_is_the_composition_of_library_operators(oracle):
+    import torch
+    rng = np.random.default_rng(7)
+    M, N, K = 5, 24, 128
+    X = (3.0 * rng.standard_normal((M, K))).astype(np.float16)
+    W = (0.1 * rng.standard_normal((N, K))).astype(np.float16)
+    gamma = (1.0 + 0.3 * rng.standard_normal(K)).astype(np.float16)
+    R = rng.standard_normal((M, N // 2)).astype(np.float16)
+    Y, info = oracle.matmul_fused(X, W, gamma=gamma, eps=1e-5, swiglu=True, residual=R)
+    t = lambda a: torch.from_numpy(np.asarray(a).astype(np.float64))
+    xn = torch.nn.functional.rms_norm(t(X), (K,), t(gamma), 1e-5).to(torch.float16).to(torch.float64)
+    a = torch.nn.functional.linear(xn, t(W))
+    gate, up = torch.chunk(a, 2, dim=-1)                    # first half of the rows is the gate
+    y = torch.nn.functional.silu(gate) * up + t(R)
+    np.testing.assert_allclose(info["y"], y.numpy(), rtol=1e-12, atol=1e-13)
+    assert np.array_equal(Y.view(np.uint16), y.to(torch.float16).numpy().view(np.uint16))
+    # the two halves are not interchangeable, and the residual is added after the product
+    W_swapped = np.concatenate([W[N // 2:], W[: N // 2]])
+    Ys, _ = oracle.matmul_fused(X, W_swapped, gamma=gamma, eps=1e-5, swiglu=True, residual=R)
+    assert not np.array_equal(Ys, Y)
+
+
+def test_matmul_fused_special_cases(oracle):
+    rng = np.random.default_rng(8)
+    M, Nh, K = 2, 6, 32
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    Wg = rng.standard_normal((Nh, K)).astype(np.float16)
+    # up rows that make a[m, Nh + j] = sum of x: one-hot-free check that gate and up meet at the same j
+    Wu = np.ones((Nh, K), np.float16)
+    Y, info = oracle.matmul_fused(X, np.concatenate([Wg, Wu]), swiglu=True)
+    sx = X.astype(np.float64).sum(axis=1, keepdims=True)
+    g = X.astype(np.float64) @ Wg.astype(np.float64).T
+    np.testing.assert_allclose(info["y"], oracle.silu(g) * sx, rtol=1e-13)
+    # residual only: one rounding of the exact sum
+    R = rng.standard_normal((M, 2 * Nh)).astype(np.float16)
+    Yr, info_r = oracle.matmul_fused(X, np.concatenate([Wg, Wu]), residual=R)
+    np.testing.assert_allclose(info_r["y"], info_r["a"] + R.astype(np.float64), rtol=0, atol=0)
+    assert np.array_equal(Yr, (info_r["a"] + R.astype(np.float64)).astype(np.float16))
+    # gamma = 1, eps = 0 on rows of equal magnitude: the norm divides by that magnitude
+    Xc = np.where(rng.random((M, K)) < 0.5, -3.0, 3.0).astype(np.float16)
+    Yn, info_n = oracle.matmul_fused(Xc, Wg, gamma=np.ones(K, np.float16), eps=0.0)
+    np.testing.assert_allclose(info_n["a"], (Xc.astype(np.float64) / 3.0) @ Wg.astype(np.float64).T, rtol=1e-13)
