@@ -51,7 +51,7 @@
 extern "C" {
 #endif
 
-#define E0M4_ABI_VERSION 2
+#define E0M4_ABI_VERSION 3
 
 #define E0M4_OK              0
 #define E0M4_ERR_NULL      (-1)   /* a required pointer is NULL */
@@ -132,6 +132,37 @@ int e0m4_matmul(const void* X_f16, int64_t M,
                 const void* codes, const void* scales_f16, const void* bias_f16,
                 int64_t N, int64_t K, int group,
                 void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The matmul with its neighbouring operators folded in (paper: section
+ * "Operator and lagging optimizations": the small operators of rms-norm are
+ * fused into one, element-wise operators are fused into the operator next to
+ * them; the paper names the operators and gives no formulas, these are the
+ * textbook ones):
+ *   1. rms-norm of the rows of X, if `rms_gamma_f16` ([K] fp16) is not NULL:
+ *        x'[m,k] = fp16(x[m,k] * gamma[k] / sqrt(mean_k x[m,k]^2 + rms_eps));
+ *   2. a[m,n] = sum_k x'[m,k] * dequant(codes)[n,k], fp32 accumulation;
+ *   3. epilogue E0M4_EPILOGUE_SWIGLU: the first N/2 weight rows are the gate and
+ *      the last N/2 the up projection, y[m,j] = silu(a[m,j]) * a[m,N/2+j] with
+ *      silu(g) = g / (1 + exp(-g)), and N_out = N/2 (N must be a multiple of
+ *      64); E0M4_EPILOGUE_NONE: y = a, N_out = N;
+ *   4. y += residual[m,j], if `residual_f16` ([M, N_out] fp16) is not NULL; it
+ *      may be the same buffer as Y (in-place residual stream);
+ *   5. Y[m,j] = fp16(y), the only rounding after step 1.  Y is [M, N_out].
+ * For M <= 8 everything happens inside the one decode kernel; for larger M the
+ * epilogue runs inside the GEMM kernels (or the kernel that adds the K splits)
+ * and the rms-norm is a launch of its own that writes x' to the workspace.
+ * Workspace: e0m4_fused_workspace_bytes() bytes, same rules as e0m4_matmul.
+ * With no operator selected the result equals e0m4_matmul's.  K == 0 is
+ * rejected (E0M4_ERR_SHAPE); other shape, pointer and error rules as above.
+ */
+#define E0M4_EPILOGUE_NONE   0
+#define E0M4_EPILOGUE_SWIGLU 1
+size_t e0m4_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int group, int with_rmsnorm, int epilogue);
+int e0m4_matmul_fused(const void* X_f16, int64_t M, const void* rms_gamma_f16, float rms_eps,
+                      const void* codes, int64_t N, int64_t K, int group,
+                      int epilogue, const void* residual_f16,
+                      void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * INT4 twin (paper: section "Evaluation of FP4 quantization", Table 1 and

@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
     L.e0m4_unpack_codes.argtypes = [vp, i64, i64, ci, vp, vp]
     L.e0m4_matmul.restype = ci
     L.e0m4_matmul.argtypes = [vp, i64, vp, vp, vp, i64, i64, ci, vp, vp, sz, vp]
+    L.e0m4_fused_workspace_bytes.restype = sz
+    L.e0m4_fused_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci]
+    L.e0m4_matmul_fused.restype = ci
+    L.e0m4_matmul_fused.argtypes = [vp, i64, vp, ctypes.c_float, vp, i64, i64, ci, ci, vp, vp, vp, sz, vp]
     L.e0m4_int4_quantize.restype = ci
     L.e0m4_int4_quantize.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
     L.e0m4_int4_dequant.restype = ci
@@ -69,7 +73,7 @@ def lib() -> ctypes.CDLL:
     L.e0m4_int4_gemv.argtypes = [vp, vp, i64, i64, ci, vp, vp]
     L.e0m4_set_knob.restype = ci
     L.e0m4_set_knob.argtypes = [ctypes.c_char_p, ci]
-    if L.e0m4_abi_version() != 2:
+    if L.e0m4_abi_version() != 3:
         raise RuntimeError("libe0m4 ABI version mismatch")
     _lib = L
     return L
@@ -172,6 +176,38 @@ def e0m4_matmul(X, codes, scales, bias, N: int, K: int, group: int, out=None, wo
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().e0m4_matmul(_ptr(X), M, _ptr(codes), _ptr(scales), _ptr(bias), N, K, group, _ptr(out),
                              _ptr(workspace), ws_bytes, _stream(stream)), "e0m4_matmul")
+    return out
+
+
+E0M4_EPILOGUE_NONE = 0
+E0M4_EPILOGUE_SWIGLU = 1
+
+
+def e0m4_fused_workspace_bytes(M: int, N: int, K: int, group: int, with_rmsnorm: bool, epilogue: int) -> int:
+    return lib().e0m4_fused_workspace_bytes(M, N, K, group, 1 if with_rmsnorm else 0, epilogue)
+
+
+def e0m4_matmul_fused(X, codes, N: int, K: int, group: int, rms_gamma=None, rms_eps: float = 0.0,
+                      epilogue: int = E0M4_EPILOGUE_NONE, residual=None, out=None, workspace=None, stream=None):
+    """The matmul with rms-norm on X, the SiLU-gated product of the two output halves and a residual add
+    folded in (each optional; see include/e0m4.h).  Y is [M, N/2] with the gated epilogue, else [M, N]."""
+    M = X.shape[0]
+    _need(X, torch.float16, (M, K), "X")
+    n_out = N // 2 if epilogue == E0M4_EPILOGUE_SWIGLU else N
+    if rms_gamma is not None:
+        _need(rms_gamma, torch.float16, (K,), "rms_gamma")
+    if residual is not None:
+        _need(residual, torch.float16, (M, n_out), "residual")
+    if out is None:
+        out = torch.empty((M, n_out), dtype=torch.float16, device=X.device)
+    _need(out, torch.float16, (M, n_out), "out")
+    need = e0m4_fused_workspace_bytes(M, N, K, group, rms_gamma is not None, epilogue)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().e0m4_matmul_fused(_ptr(X), M, _ptr(rms_gamma), float(rms_eps), _ptr(codes), N, K, group, epilogue,
+                                   _ptr(residual), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream)),
+           "e0m4_matmul_fused")
     return out
 
 

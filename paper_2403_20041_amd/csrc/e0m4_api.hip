@@ -109,6 +109,27 @@ size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
     return gemm_workspace_bytes(M, N, K);       // partial tiles of the split-K GEMM, if it splits
 }
 
+// Fused matmul: the normalised copy of X (GEMM path with rms-norm) comes first in the workspace,
+// rounded up to 256 bytes, then the partial sums of the split along K.
+static size_t norm_bytes(int64_t M, int64_t K) { return ((size_t)M * (size_t)K * 2 + 255) & ~(size_t)255; }
+
+// Which kernel family serves a fused matmul: 0 the decode kernel (everything in one launch),
+// 1 the GEMM kernels (rms-norm, if any, as a launch of its own before them).
+static int fused_path(const Fusion& f, int64_t M, int64_t N, int64_t K)
+{
+    return (M <= kGemvMaxM && gemv_fused_supported(f, M, N, K)) ? 0 : 1;
+}
+
+size_t e0m4_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int group, int with_rmsnorm, int epilogue)
+{
+    if (check_shape(N, K, group) != E0M4_OK || M <= 0 || N == 0 || K == 0) return 0;
+    if (epilogue != E0M4_EPILOGUE_NONE && epilogue != E0M4_EPILOGUE_SWIGLU) return 0;
+    Fusion f;
+    f.swiglu = epilogue == E0M4_EPILOGUE_SWIGLU;
+    if (fused_path(f, M, N, K) == 0) return 0;
+    return (with_rmsnorm ? norm_bytes(M, K) : 0) + gemm_workspace_bytes(M, N, K, f.swiglu);
+}
+
 int e0m4_set_knob(const char* name, int value)
 {
     if (!name) return E0M4_ERR_NULL;
@@ -224,6 +245,48 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // the GEMM epilogue forms 32-bit offsets of up to 256 rows of Y
     if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
     return launch_gemm(X, M, codes, N, K, group, Y, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int e0m4_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms_eps, const void* codes, int64_t N,
+                      int64_t K, int group, int epilogue, const void* residual, void* Y, void* workspace,
+                      size_t workspace_bytes, void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (M < 0 || M > (int64_t)1 << 31) return E0M4_ERR_SHAPE;
+    if (epilogue != E0M4_EPILOGUE_NONE && epilogue != E0M4_EPILOGUE_SWIGLU) return E0M4_ERR_SHAPE;
+    Fusion f;
+    f.gamma = rms_gamma;
+    f.eps = rms_eps;
+    f.residual = residual;
+    f.swiglu = epilogue == E0M4_EPILOGUE_SWIGLU;
+    // the gated epilogue pairs weight row j with row N/2 + j: the halves must be whole pairs of 16-row blocks
+    if (f.swiglu && (N % (4 * kBlockRows)) != 0) return E0M4_ERR_SHAPE;
+    if (M == 0 || N == 0) return E0M4_OK;
+    if (K == 0) return E0M4_ERR_SHAPE;                  // nothing to normalise or to gate
+    if (!X || !codes || !Y) return E0M4_ERR_NULL;
+    if (!aligned16(X) || !aligned16(codes) || !aligned16(Y) || (rms_gamma && !aligned16(rms_gamma)) ||
+        (residual && !aligned16(residual)))
+        return E0M4_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    if (fused_path(f, M, N, K) == 0) return launch_gemv_fused(f, X, M, codes, N, K, group, Y, st);
+    if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // 32-bit offsets in the GEMM epilogue
+    const size_t nb = rms_gamma ? norm_bytes(M, K) : 0;
+    const size_t need = nb + gemm_workspace_bytes(M, N, K, f.swiglu);
+    if (need > 0) {
+        if (!workspace) return E0M4_ERR_NULL;
+        if (!aligned16(workspace)) return E0M4_ERR_ALIGN;
+        if (workspace_bytes < need) return E0M4_ERR_WORKSPACE;
+    }
+    const void* x = X;
+    if (rms_gamma) {
+        rc = launch_rmsnorm(X, M, K, rms_gamma, rms_eps, workspace, st);
+        if (rc != E0M4_OK) return rc;
+        x = workspace;
+        f.gamma = nullptr;
+    }
+    return launch_gemm_fused(f, x, M, codes, N, K, group, Y, static_cast<char*>(workspace) + nb,
+                             workspace_bytes - nb, st);
 }
 
 }  // extern "C"

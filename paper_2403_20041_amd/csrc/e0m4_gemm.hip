@@ -43,10 +43,21 @@ __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2
 // tile rows, at a time, so 16 consecutive rows must fall into 16 different 16-byte bank groups)
 __device__ inline int tile_off(int row, int piece) { return row * kRowBytes + ((piece ^ ((row >> 1) & 7)) << 4); }
 
-template <int G, int BM, int BN>
+// Epilogue operators of e0m4_matmul_fused (FUSED).  Gated: the tile covers BN/2 output columns; of the
+// two 32-row operand blocks of a wavefront the first holds gate rows o .. o+31 and the second the up rows
+// N/2 + o .. N/2 + o+31, and the lane that holds both values of an output element writes silu(gate) * up.
+struct TileFusion {
+    const half_t* residual;
+    int swiglu;
+    int64_t n_half;                                     // N / 2 (gated epilogue)
+};
+
+__device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
+
+template <int G, int BM, int BN, bool FUSED>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict__ X, int64_t M,
                                                         const uint4* __restrict__ packed, int64_t N, int64_t K,
-                                                        half_t* __restrict__ Y, int m_tiles, int n_tiles)
+                                                        half_t* __restrict__ Y, int m_tiles, int n_tiles, TileFusion fu)
 {
     constexpr int TM = BM / 64, TN = BN / 64;           // 32x32 MFMA blocks per wavefront along m and n
     constexpr int PA = BM / 32, PB = BN / 128;          // loader passes
@@ -58,7 +69,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
     const int tile = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
     if (tile >= total) return;
-    const int64_t m0 = (int64_t)(tile % m_tiles) * BM, n0 = (int64_t)(tile / m_tiles) * BN;
+    const bool gated = FUSED && fu.swiglu;
+    // n0: first weight row of the tile, or first output column (= gate row) when gated
+    const int64_t m0 = (int64_t)(tile % m_tiles) * BM, n0 = (int64_t)(tile / m_tiles) * (gated ? BN / 2 : BN);
 
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -86,14 +99,21 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
     for (int p = 0; p < PA; ++p)
         a_pass_off[p] = (uint32_t)((min(m0 + a_row + 32 * p, M - 1) - a_m) * K * 2);
     const int64_t rb_first = n0 / kBlockRows + b_hb;
-    const int64_t rb_c = min(rb_first, nrb - 1);
+    int64_t rb_c = min(rb_first, nrb - 1);
+    if (gated) {
+        // tile row block b_hb belongs to wavefront column b_hb / 4, operand block (b_hb / 2) % 2 (0: gate,
+        // 1: up), and is row block b_hb % 2 of that operand block's 32 rows
+        static_assert(!FUSED || (BN == 128 && PB == 1), "gated epilogue: one loader pass, two wavefront columns");
+        const int64_t nrbh = fu.n_half / kBlockRows;
+        rb_c = ((b_hb >> 1) & 1) * nrbh + min(n0 / kBlockRows + 2 * (b_hb >> 2) + (b_hb & 1), nrbh - 1);
+    }
     const char* b_code_base = reinterpret_cast<const char*>(packed + lay.code_index(rb_c, 0) + b_q * kBlockRows + b_r);
     const char* b_param_base = reinterpret_cast<const char*>(packed) + 4 * (lay.param_index(rb_c, 0) + b_r) +
                                (G == 32 ? b_q * 64 : 0);
     uint32_t b_pass_off[PB];
 #pragma unroll
     for (int p = 0; p < PB; ++p)
-        b_pass_off[p] = (uint32_t)((min(rb_first + 8 * p, nrb - 1) - rb_c) * lay.nkb * block_bytes(G));
+        b_pass_off[p] = gated ? 0u : (uint32_t)((min(rb_first + 8 * p, nrb - 1) - rb_c) * lay.nkb * block_bytes(G));
     const bool k_tail = (K % BK) != 0;                  // only then can a 16-byte piece of X lie beyond K
 
     auto load_global = [&](int kt) {
@@ -187,6 +207,47 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
     const int rows_left = (int)min((int64_t)BM, M - m0), cols_left = (int)min((int64_t)BN, N - n0);
     const int row0 = wm + 4 * (lane >> 5), col0 = wn + (lane & 31);
     const uint32_t off0 = (uint32_t)row0 * n32 + (uint32_t)col0;
+    if (FUSED) {
+        if (gated) {
+            const int ocols_left = (int)min((int64_t)(BN / 2), fu.n_half - n0);
+            const int ocol = (wave & 1) * 32 + (lane & 31);
+            const uint32_t nh32 = (uint32_t)fu.n_half;
+            half_t* __restrict__ yt = Y + m0 * fu.n_half + n0;
+            const half_t* __restrict__ rt = fu.residual ? fu.residual + m0 * fu.n_half + n0 : nullptr;
+            const uint32_t o0 = (uint32_t)row0 * nh32 + (uint32_t)ocol;
+            if (ocol < ocols_left) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
+                        if (row0 + dr < rows_left) {
+                            float v = silu_f32(acc[i][0][r]) * acc[i][TN - 1][r];
+                            if (rt) v += (float)rt[o0 + (uint32_t)dr * nh32];
+                            yt[o0 + (uint32_t)dr * nh32] = (half_t)v;
+                        }
+                    }
+            }
+            return;
+        }
+        if (fu.residual) {
+            const half_t* __restrict__ rt = fu.residual + m0 * N + n0;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (col0 + 32 * j < cols_left) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
+                            const uint32_t o = off0 + (uint32_t)dr * n32 + 32 * j;
+                            if (row0 + dr < rows_left) Yt[o] = (half_t)(acc[i][j][r] + (float)rt[o]);
+                        }
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         if (col0 + 32 * j < cols_left) {
@@ -201,42 +262,48 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
     }
 }
 
-template <int G, int BM, int BN>
-int launch_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
+template <int G, int BM, int BN, bool FUSED>
+int launch_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream,
+                const Fusion& f = Fusion{})
 {
-    const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
+    TileFusion fu;
+    fu.residual = static_cast<const half_t*>(f.residual);
+    fu.swiglu = f.swiglu ? 1 : 0;
+    fu.n_half = N / 2;
+    const int64_t m_tiles = (M + BM - 1) / BM;
+    const int64_t n_tiles = f.swiglu ? (N / 2 + BN / 2 - 1) / (BN / 2) : (N + BN - 1) / BN;
     if (m_tiles * n_tiles > 0x3fffffffLL) return E0M4_ERR_SHAPE;
     const int total = (int)(m_tiles * n_tiles);
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
     constexpr size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
     static bool attr_set = false;                       // LDS above the default 64 KiB limit must be requested once
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<G, BM, BN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<G, BM, BN, FUSED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return record_hip_error(e);
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_kernel<G, BM, BN>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(kThreads), lds, stream, x,
-                       M, c, N, K, y, (int)m_tiles, (int)n_tiles);
+    hipLaunchKernelGGL((gemm_kernel<G, BM, BN, FUSED>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(kThreads), lds, stream,
+                       x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, fu);
     return check_launch();
 }
 
 // The pipelined 256 x 256 kernel runs whenever its work items (tiles x K splits) can occupy a good
 // part of the chip; small problems (and K not a multiple of 128) take the 128 x 128 tile of this file.
-bool use_pipe(int64_t M, int64_t N, int64_t K)
+bool use_pipe(int64_t M, int64_t N, int64_t K, bool swiglu = false)
 {
     if (!gemm_pipe_supported(K)) return false;
     const int v = knob("gemm_variant");             // 1: always the small tile of this file, 2: always the pipelined kernel
     if (v == 2) return true;
     if (v == 1) return false;
-    return gemm_pipe_work_items(M, N, K) >= 96;
+    return gemm_pipe_work_items(M, N, K, swiglu) >= 96;
 }
 
 }  // namespace
 
-size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu)
 {
-    return use_pipe(M, N, K) ? gemm_pipe_workspace_bytes(M, N, K) : 0;
+    return use_pipe(M, N, K, swiglu) ? gemm_pipe_workspace_bytes(M, N, K, swiglu) : 0;
 }
 
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
@@ -247,9 +314,30 @@ int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t
     half_t* y = static_cast<half_t*>(Y);
     if (use_pipe(M, N, K)) return launch_gemm_pipe(X, M, packed, N, K, group, Y, workspace, workspace_bytes, stream);
     switch (group) {
-        case 32: return launch_tile<32, 128, 128>(x, M, c, N, K, y, stream);
-        case 64: return launch_tile<64, 128, 128>(x, M, c, N, K, y, stream);
-        case 128: return launch_tile<128, 128, 128>(x, M, c, N, K, y, stream);
+        case 32: return launch_tile<32, 128, 128, false>(x, M, c, N, K, y, stream);
+        case 64: return launch_tile<64, 128, 128, false>(x, M, c, N, K, y, stream);
+        case 128: return launch_tile<128, 128, 128, false>(x, M, c, N, K, y, stream);
+        default: return E0M4_ERR_GROUP;
+    }
+}
+
+// With the epilogue operators of e0m4_matmul_fused; X is already normalised if rms-norm was asked for.
+int launch_gemm_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group,
+                      void* Y, void* workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    const half_t* x = static_cast<const half_t*>(X);
+    const uint4* c = static_cast<const uint4*>(packed);
+    half_t* y = static_cast<half_t*>(Y);
+    if (f.swiglu) {
+        const int64_t half_bytes = (N / 2 / kBlockRows) * k_blocks(K) * (int64_t)block_bytes(group);
+        if (N % (2 * kBlockRows) != 0 || half_bytes >= ((int64_t)1 << 31)) return E0M4_ERR_SHAPE;
+    }
+    if (use_pipe(M, N, K, f.swiglu))
+        return launch_gemm_pipe_fused(f, X, M, packed, N, K, group, Y, workspace, workspace_bytes, stream);
+    switch (group) {
+        case 32: return launch_tile<32, 128, 128, true>(x, M, c, N, K, y, stream, f);
+        case 64: return launch_tile<64, 128, 128, true>(x, M, c, N, K, y, stream, f);
+        case 128: return launch_tile<128, 128, 128, true>(x, M, c, N, K, y, stream, f);
         default: return E0M4_ERR_GROUP;
     }
 }

@@ -46,11 +46,26 @@ __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2
 // (one per SIMD, 128 x 128 each) that doubles the instruction issue capacity and lets one wavefront's
 // waits hide behind the other's MFMAs, for twice the activation fragment traffic; 2 x 2 was measured
 // slower and does not fit the register file once the split-K epilogue is compiled in.
-template <int G, int WGM, int WGN>
+//
+// FUSED adds the operators of e0m4_matmul_fused that belong to the epilogue (paper: section "Operator and
+// lagging optimizations", element-wise operators fused into their neighbours).  With the gated
+// epilogue a tile covers 128 output columns: the first operand block of a wavefront holds 32 gate rows
+// o .. o+31 and its second the up rows N/2 + o .. N/2 + o+31, so that a lane finds the gate and the up
+// value of an output element in the same register of its two accumulator blocks and writes
+// silu(gate) * up.  The residual is added before the one rounding.
+struct PipeFusion {
+    const half_t* residual;
+    int swiglu;
+    int64_t n_half;                                     // N / 2 (gated epilogue)
+};
+
+__device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
+
+template <int G, int WGM, int WGN, bool FUSED>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
                                                              const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                              half_t* __restrict__ Y, int m_tiles, int n_tiles,
-                                                             int splits, float* __restrict__ partial)
+                                                             int splits, float* __restrict__ partial, PipeFusion fu)
 {
     constexpr int kThreads = 64 * WGM * WGN;
     constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);      // 32x32 MFMA blocks per wavefront
@@ -69,7 +84,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     const int tile = __builtin_amdgcn_readfirstlane(item / splits);
     const int split = __builtin_amdgcn_readfirstlane(item % splits);
     const int64_t m0 = (int64_t)__builtin_amdgcn_readfirstlane(tile % m_tiles) * BM;
-    const int64_t n0 = (int64_t)__builtin_amdgcn_readfirstlane(tile / m_tiles) * BN;
+    const bool gated = FUSED && fu.swiglu;
+    // first column of the tile: of the weight rows, or of the output (= of the gate rows) when gated
+    const int64_t n0 = (int64_t)__builtin_amdgcn_readfirstlane(tile / m_tiles) * (gated ? BN / 2 : BN);
 
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -108,7 +125,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     uint32_t b_code_off[TN], b_param_off[TN];           // row blocks beyond N are clamped (never stored)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int64_t rb = min(rb_tile + wn / kBlockRows + 2 * j + ((lane >> 4) & 1), nrb - 1) - rb_tile;
+        int64_t rb = min(rb_tile + wn / kBlockRows + 2 * j + ((lane >> 4) & 1), nrb - 1) - rb_tile;
+        if (gated) {                                    // block 0: gate rows, block 1: the up rows, N/2 further
+            const int64_t nrbh = fu.n_half / kBlockRows;
+            rb = min(rb_tile + (wave % WGN) * 2 + ((lane >> 4) & 1), nrbh - 1) - rb_tile + j * nrbh;
+        }
         b_code_off[j] = (uint32_t)rb * rb_stride + (uint32_t)(b_h * kBlockRows + b_r) * 16;
         b_param_off[j] = (uint32_t)rb * rb_stride + (uint32_t)b_r * 4 + (G == 32 ? b_h * 64 : 0);
     }
@@ -281,10 +302,91 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
     // [splits][M][N]); a second kernel adds the slabs in split order and rounds to fp16.  (Adding them
     // here, in the last work item to arrive, needs device-scope fences, which cost far more than the
     // second launch on a chip whose eight L2 caches are not coherent with each other.)
+    if (FUSED) {
+        static_assert(!FUSED || TN == 2, "the gated epilogue pairs the two operand blocks of a wavefront");
+        if (gated) {
+            const int ocols_left = (int)min((int64_t)(BN / 2), fu.n_half - n0);
+            const int ocol = (wave % WGN) * 32 + (lane & 31);
+            if (ocol < ocols_left) {
+                if (splits > 1) {                       // partial sums keep the [M, N] layout of the weight rows
+                    float* __restrict__ pg = partial + ((size_t)split * (size_t)M + (size_t)m0) * (size_t)N + (size_t)n0;
+                    float* __restrict__ pu = pg + fu.n_half;
+                    const uint32_t o0 = (uint32_t)row0 * n32 + (uint32_t)ocol;
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
+                            if (row0 + dr < rows_left) {
+                                pg[o0 + (uint32_t)dr * n32] = acc[i][0][r];
+                                pu[o0 + (uint32_t)dr * n32] = acc[i][1][r];
+                            }
+                        }
+                } else {
+                    const uint32_t nh32 = (uint32_t)fu.n_half;
+                    half_t* __restrict__ yt = Y + m0 * fu.n_half + n0;
+                    const half_t* __restrict__ rt = fu.residual ? fu.residual + m0 * fu.n_half + n0 : nullptr;
+                    const uint32_t o0 = (uint32_t)row0 * nh32 + (uint32_t)ocol;
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
+                            if (row0 + dr < rows_left) {
+                                float v = silu_f32(acc[i][0][r]) * acc[i][1][r];
+                                if (rt) v += (float)rt[o0 + (uint32_t)dr * nh32];
+                                yt[o0 + (uint32_t)dr * nh32] = (half_t)v;
+                            }
+                        }
+                }
+            }
+            return;
+        }
+        if (splits == 1 && fu.residual) {
+            const half_t* __restrict__ rt = fu.residual + m0 * N + n0;
+            half_t* __restrict__ yt = Y + m0 * N + n0;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (col0 + 32 * j < cols_left) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
+                            const uint32_t o = off0 + (uint32_t)dr * n32 + 32 * j;
+                            if (row0 + dr < rows_left) yt[o] = (half_t)(acc[i][j][r] + (float)rt[o]);
+                        }
+                }
+            }
+            return;
+        }
+    }
     if (splits > 1)
         store_tile(partial + ((size_t)split * (size_t)M + (size_t)m0) * (size_t)N + (size_t)n0);
     else
         store_tile(Y + m0 * N + n0);
+}
+
+// The same with the fused epilogue: element i of the output is (m, j) with j < n_out; its sums are at
+// [m, j] of the slabs (and, gated, [m, n_half + j]), whose rows are N long.
+__global__ __launch_bounds__(256) void splitk_reduce_fused_kernel(const float* __restrict__ partial, int splits,
+                                                                  int64_t M, int64_t N, int64_t n_out,
+                                                                  half_t* __restrict__ Y, PipeFusion fu)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= M * n_out) return;
+    const int64_t m = i / n_out, j = i - m * n_out;
+    const size_t slab = (size_t)M * (size_t)N;
+    const float* __restrict__ src = partial + (size_t)m * (size_t)N + (size_t)j;
+    float v = src[0];
+    for (int s = 1; s < splits; ++s) v += src[(size_t)s * slab];
+    if (fu.swiglu) {
+        float up = src[fu.n_half];
+        for (int s = 1; s < splits; ++s) up += src[(size_t)s * slab + fu.n_half];
+        v = silu_f32(v) * up;
+    }
+    if (fu.residual) v += (float)fu.residual[i];
+    Y[i] = (half_t)v;
 }
 
 // Y[i] = fp16(sum over splits, in split order, of partial[s][i]); V elements per thread.
@@ -319,11 +421,17 @@ int choose_splits(int64_t tiles, int64_t K)
 
 size_t partial_bytes(int splits, int64_t M, int64_t N) { return (size_t)splits * (size_t)M * (size_t)N * sizeof(float); }
 
-template <int G, int WGM, int WGN>
+int64_t pipe_n_tiles(int64_t N, bool swiglu) { return swiglu ? (N / 2 + BN / 2 - 1) / (BN / 2) : (N + BN - 1) / BN; }
+
+template <int G, int WGM, int WGN, bool FUSED>
 int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, void* workspace,
-                size_t workspace_bytes, hipStream_t stream)
+                size_t workspace_bytes, hipStream_t stream, const Fusion& f = Fusion{})
 {
-    const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
+    PipeFusion fu;
+    fu.residual = static_cast<const half_t*>(f.residual);
+    fu.swiglu = f.swiglu ? 1 : 0;
+    fu.n_half = N / 2;
+    const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = pipe_n_tiles(N, f.swiglu);
     const int64_t tiles = m_tiles * n_tiles;
     const int splits = choose_splits(tiles, K);
     if (tiles * splits > 0x3fffffffLL) return E0M4_ERR_SHAPE;
@@ -337,15 +445,21 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     constexpr size_t lds = (size_t)kStages * kStageBytes;          // 96 KiB: above the default limit
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_pipe_kernel<G, WGM, WGN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_pipe_kernel<G, WGM, WGN, FUSED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return record_hip_error(e);
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(64 * WGM * WGN), lds,
-                       stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial);
+    hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN, FUSED>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(64 * WGM * WGN),
+                       lds, stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial, fu);
     int rc = check_launch();
     if (rc != E0M4_OK || splits == 1) return rc;
+    if (FUSED) {
+        const int64_t n_out = f.swiglu ? N / 2 : N;
+        hipLaunchKernelGGL(splitk_reduce_fused_kernel, dim3((unsigned)((M * n_out + 255) / 256)), dim3(256), 0, stream,
+                           partial, splits, M, N, n_out, y, fu);
+        return check_launch();
+    }
     const int64_t count = M * N;
     if (count % 4 == 0)                                 // slabs stay 16-byte aligned
         hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3((unsigned)((count / 4 + 255) / 256)), dim3(256), 0, stream,
@@ -360,17 +474,17 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
 
 bool gemm_pipe_supported(int64_t K) { return K >= 128 && (K % (2 * BK)) == 0; }
 
-size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K)
+size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu)
 {
-    const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    const int64_t tiles = ((M + BM - 1) / BM) * pipe_n_tiles(N, swiglu);
     if (tiles == 0 || !gemm_pipe_supported(K)) return 0;
     const int splits = choose_splits(tiles, K);
     return splits > 1 ? partial_bytes(splits, M, N) : 0;
 }
 
-int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K)
+int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K, bool swiglu)
 {
-    const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    const int64_t tiles = ((M + BM - 1) / BM) * pipe_n_tiles(N, swiglu);
     if (tiles == 0 || !gemm_pipe_supported(K)) return 0;
     return tiles * choose_splits(tiles, K);
 }
@@ -382,9 +496,29 @@ int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, in
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     switch (group) {
-        case 32: return launch_pipe<32, 2, 4>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
-        case 64: return launch_pipe<64, 2, 4>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
-        case 128: return launch_pipe<128, 2, 4>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
+        case 32: return launch_pipe<32, 2, 4, false>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
+        case 64: return launch_pipe<64, 2, 4, false>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
+        case 128: return launch_pipe<128, 2, 4, false>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
+        default: return E0M4_ERR_GROUP;
+    }
+}
+
+// With the epilogue operators of e0m4_matmul_fused (rms-norm is applied to X before this call).  The
+// gated epilogue needs N/2 to be whole pairs of row blocks and the halves less than 2 GiB apart.
+int launch_gemm_pipe_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group,
+                           void* Y, void* workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    const half_t* x = static_cast<const half_t*>(X);
+    const uint4* c = static_cast<const uint4*>(packed);
+    half_t* y = static_cast<half_t*>(Y);
+    if (f.swiglu) {
+        const int64_t half_bytes = (N / 2 / kBlockRows) * k_blocks(K) * (int64_t)block_bytes(group);
+        if (N % (2 * kBlockRows) != 0 || half_bytes >= ((int64_t)1 << 31)) return E0M4_ERR_SHAPE;
+    }
+    switch (group) {
+        case 32: return launch_pipe<32, 2, 4, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+        case 64: return launch_pipe<64, 2, 4, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+        case 128: return launch_pipe<128, 2, 4, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
         default: return E0M4_ERR_GROUP;
     }
 }

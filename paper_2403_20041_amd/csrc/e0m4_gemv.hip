@@ -50,10 +50,13 @@ struct GemvPlan {
     size_t lds_bytes;
 };
 
-GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
+// `unit`: row blocks are dealt to workgroups in units of this many (2 for the gated epilogue, whose
+// workgroups own pairs of a gate and an up row block; the plan then counts units where it says row blocks,
+// except rb_per_wg, which counts row blocks).  `single_segment` tells whether all of X fits the LDS.
+GemvPlan make_plan(int64_t M, int64_t N, int64_t K, int unit = 1, bool* single_segment_out = nullptr)
 {
     GemvPlan p;
-    const int64_t nrb = row_blocks(N), nkb = k_blocks(K);
+    const int64_t nrb = row_blocks(N) / unit, nkb = k_blocks(K);
     const int64_t nsi = (nkb + kSuper - 1) / kSuper;           // work items per row block
     int w = knob("gemv_waves");
     if (w == 16 && M > 4) w = 8;                // 16 wavefronts leave too few registers for that many accumulators
@@ -61,7 +64,7 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
     // 16 wavefronts when K is long, or when a workgroup has many work items of a medium K; 8 otherwise
     // (measured on the layer shapes of 2B to 14B models)
     const int64_t t_guess = (nrb + kTargetWorkgroups - 1) / kTargetWorkgroups;
-    if (!forced) w = (M <= 4 && (nsi >= 16 || (nsi >= 8 && nsi * t_guess >= 32))) ? 16 : 8;
+    if (!forced) w = (M <= 4 && (nsi >= 16 || (nsi >= 8 && nsi * unit * t_guess >= 32))) ? 16 : 8;
     int64_t t = 1;
     bool single_segment = true;
     for (;;) {
@@ -70,7 +73,7 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
         p.seg_items = (int)(single_segment ? nsi : (cap >= w ? cap / w * w : cap));   // a multiple of W if possible
         const int64_t x_bytes = M * p.seg_items * kSuper * kBytesPerBlockX;
         const int64_t red_budget = std::min<int64_t>(kRedBudgetBytes, kLdsLimitBytes - x_bytes);
-        int64_t t_max = red_budget / ((int64_t)w * M * kBlockRows * sizeof(float));
+        int64_t t_max = red_budget / ((int64_t)unit * w * M * kBlockRows * sizeof(float));
         if (t_max < 1) t_max = 1;
         int target = knob("gemv_workgroups");
         if (target <= 0) target = kTargetWorkgroups;
@@ -83,16 +86,17 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
         p.grid = (nrb + t - 1) / t;
         if (t > 1 && p.grid < target && (int64_t)target * t >= nrb) p.grid = target;
         // fewer wavefronts when a workgroup has fewer work items than wavefronts
-        if (!forced && w > 4 && nsi * t < w) { w /= 2; continue; }
+        if (!forced && w > 4 && nsi * unit * t < w) { w /= 2; continue; }
         break;
     }
+    if (single_segment_out) *single_segment_out = single_segment;
     p.waves = w;
-    p.rb_per_wg = (int)t;
+    p.rb_per_wg = (int)(unit * t);
     p.step_slots = (int)(w / nsi);
     p.step_item = (int)(w % nsi);
     p.rb_base = (int)(nrb / p.grid);
     p.rb_rem = (int)(nrb % p.grid);
-    p.lds_bytes = (size_t)M * p.seg_items * kSuper * kBytesPerBlockX + (size_t)t * w * M * kBlockRows * sizeof(float);
+    p.lds_bytes = (size_t)M * p.seg_items * kSuper * kBytesPerBlockX + (size_t)unit * t * w * M * kBlockRows * sizeof(float);
     return p;
 }
 
@@ -104,10 +108,30 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K)
 // fp16 with a conversion instruction, and the parameter word holds (scale, integer zero point).
 enum { kDeqE0M4 = 0, kDeqInt4Convert = 1 };
 
-template <int G, int M, int W, int DEQ = kDeqE0M4>
+// Operators folded into the kernel when FUSED (paper: section "Operator and lagging optimizations",
+// fusion of rms-norm and of element-wise operators into their neighbours):
+//   gamma    : the rows of X are rms-normalised while they are staged (x * rsqrt(mean x^2 + eps) * gamma,
+//              rounded to fp16 as the stand-alone operator's output would be);
+//   swiglu   : weight row j (gate) is paired with row N/2 + j (up) and Y[m, j] = silu(gate) * up; a
+//              workgroup then owns pairs of row blocks, slot 2p the gate block and slot 2p + 1 the up block
+//              of pair p, `half_bytes` apart in the packed buffer;
+//   residual : added to the result before its one rounding.
+struct GemvFusion {
+    const half_t* gamma;
+    const half_t* residual;
+    float eps;
+    int swiglu;
+    uint32_t half_bytes;
+    int64_t n_out;                                      // row length of Y and of the residual
+};
+
+__device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
+
+template <int G, int M, int W, int DEQ = kDeqE0M4, bool FUSED = false>
 __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__ X, const uint4* __restrict__ packed,
                                                       int64_t N, int64_t K, half_t* __restrict__ Y, int seg_items,
-                                                      int step_slots, int step_item, int rb_base, int rb_rem)
+                                                      int step_slots, int step_item, int rb_base, int rb_rem,
+                                                      GemvFusion fu)
 {
     constexpr int kThreads = W * 64;
     constexpr int PW = block_param_words(G);            // parameter words per k block: 16, 32 or 64
@@ -117,7 +141,8 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     half_t* xs = reinterpret_cast<half_t*>(smem);                               // [M][seg_k]
     // per 32-wide chunk of X: (sum of the chunk, 30 x sum of its elements with k % 8 in 2..5)
     float2* sxs = reinterpret_cast<float2*>(smem + (size_t)M * seg_k * 2);      // [M][seg_k/32]
-    float* red = reinterpret_cast<float*>(sxs + (size_t)M * (seg_k / kCodesPerChunk));   // [rb_per_wg][W][M][16]
+    float* part = reinterpret_cast<float*>(sxs + (size_t)M * (seg_k / kCodesPerChunk));  // [W][M] sums of squares (FUSED only)
+    float* red = part + (FUSED ? W * M : 0);                                    // [rb_per_wg][W][M][16]
 
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -127,8 +152,11 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     const PackedLayout<G> lay(K);
     const int nkb = (int)lay.nkb;
     const int nsi = (nkb + kSuper - 1) / kSuper;
-    const int64_t rb0 = (int64_t)blockIdx.x * rb_base + min((int)blockIdx.x, rb_rem);    // even deal of row blocks
-    const int n_rb = rb_base + ((int)blockIdx.x < rb_rem ? 1 : 0);
+    // even deal of row blocks (of pairs of row blocks with the gated epilogue: rb0 is then the first pair,
+    // which is also the number of its gate row block)
+    const bool gated = FUSED && fu.swiglu;
+    const int64_t rb0 = (int64_t)blockIdx.x * rb_base + min((int)blockIdx.x, rb_rem);
+    const int n_rb = (rb_base + ((int)blockIdx.x < rb_rem ? 1 : 0)) * (gated ? 2 : 1);
     // Weights are read with buffer loads: a wavefront-uniform resource (base of this workgroup's run
     // of row blocks, far smaller than 2 GiB), a scalar offset per block and a constant lane offset.
     // Every address is clamped into the run by hand; nothing relies on the resource's range check.
@@ -136,6 +164,11 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     const __amdgpu_buffer_rsrc_t wg_params = make_rsrc(reinterpret_cast<const char*>(packed) + 4 * lay.param_index(rb0, 0));
     const uint32_t rb_stride = (uint32_t)nkb * block_bytes(G);                  // bytes from one row block to the next
     const uint32_t lane_code_off = lane * 16;
+    // byte offset of row block slot s from the workgroup's first row block
+    auto slot_off = [&](uint32_t s_) -> uint32_t {
+        if (FUSED && fu.swiglu) return (s_ >> 1) * rb_stride + (s_ & 1) * fu.half_bytes;
+        return s_ * rb_stride;
+    };
     // Parameters of a work item: its 4*PW words are contiguous; load n gives lane l word 64n + l, and
     // block j of lane (q, r) needs word j*PW + slot(q, r), i.e. load (j*PW)/64, lane (j*PW)%64 + slot.
     const int pslot = lay.param_slot(q, r);
@@ -176,9 +209,24 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
         s = __builtin_amdgcn_fdot2(x0, ones, s, false);
         s = __builtin_amdgcn_fdot2(x3, ones, s, false);
     };
+    // rms-norm (FUSED with gamma): 1 / sqrt(mean of squares + eps) of every row of X, set below
+    float rs[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) rs[m] = 1.f;
     // store one piece and, from every fourth lane, the two sums of its 32-wide chunk
-    auto x_store = [&](int idx, const half8_t& v) {
+    auto x_store = [&](int idx, const half8_t& vin, int kb_first) {
         const int m = M == 1 ? 0 : idx / pieces, pc = M == 1 ? idx : idx % pieces;
+        half8_t v = vin;
+        if (FUSED && fu.gamma) {                        // normalise on the way in: (x * rs[m]) * gamma[k], one rounding
+            const int64_t k = (int64_t)kb_first * kBlockK + pc * 8;
+            half8_t gv = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (idx < M * pieces && k < K) gv = *reinterpret_cast<const half8_t*>(fu.gamma + k);
+            float r = rs[0];
+#pragma unroll
+            for (int mm = 1; mm < M; ++mm) r = mm == m ? rs[mm] : r;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = (half_t)(((float)vin[i] * r) * (float)gv[i]);
+        }
         float s = 0.f, sl = 0.f;
         piece_sums(v, s, sl);
         s += sl;
@@ -197,7 +245,9 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     half8_t xearly[kEarlyX];
 #pragma unroll
     for (int e = 0; e < kEarlyX; ++e) xearly[e] = x_piece(t + e * kThreads, 0);
-    for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0));
+    const bool normed = FUSED && fu.gamma != nullptr;   // then staging waits for the row scales (below)
+    if (!normed)
+        for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0), 0);
 
     // ---- the work item in flight: four code blocks and the parameter words
     uint4 c[kSuper];
@@ -205,7 +255,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     auto fetch_params = [&](int fs, int fi) {           // past the end the last item is read again
         const bool in = fs < n_rb;
         const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
-        const uint32_t soff = __builtin_amdgcn_readfirstlane(s_ * rb_stride + i_ * (kSuper * PW * 4));
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(slot_off(s_) + i_ * (kSuper * PW * 4));
         const int last = param_words_rb - 1 - (int)i_ * (kSuper * PW);       // words left in this row block
 #pragma unroll
         for (int n = 0; n < NPL; ++n)
@@ -215,7 +265,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
         const bool in = fs < n_rb;
         const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
         const uint32_t kb = min(i_ * kSuper + j, (uint32_t)nkb - 1);
-        const uint32_t soff = __builtin_amdgcn_readfirstlane(s_ * rb_stride + kb * kBlockCodeBytes);
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(slot_off(s_) + kb * kBlockCodeBytes);
         const u32x4 cv = __builtin_amdgcn_raw_buffer_load_b128(wg_codes, (int)lane_code_off, (int)soff, 0);
         c[j] = make_uint4(cv.x, cv.y, cv.z, cv.w);
     };
@@ -228,6 +278,54 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
         for (int sl = 0; sl < n_rb; ++sl)
 #pragma unroll
             for (int m = 0; m < M; ++m) red[((sl * W + wave) * M + m) * kBlockRows + lane] = 0.f;
+
+    if (normed) {
+        // Sum of squares of every row of X over the whole of K: from the pieces already in registers when
+        // one segment holds whole rows, else (and for what the registers do not cover) from memory.
+        float ss[M];
+#pragma unroll
+        for (int m = 0; m < M; ++m) ss[m] = 0.f;
+        auto add_squares = [&](int m, const half8_t& v) {
+            const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
+            float d = __builtin_amdgcn_fdot2(x0, x0, 0.f, false);
+            d = __builtin_amdgcn_fdot2(x1, x1, d, false);
+            d = __builtin_amdgcn_fdot2(x2, x2, d, false);
+            d = __builtin_amdgcn_fdot2(x3, x3, d, false);
+#pragma unroll
+            for (int mm = 0; mm < M; ++mm) ss[mm] += mm == m ? d : 0.f;
+        };
+        if (seg_items >= nsi) {                         // segment 0 is all of K (pieces beyond K are zero)
+#pragma unroll
+            for (int e = 0; e < kEarlyX; ++e) {
+                const int idx = t + e * kThreads;
+                add_squares(M == 1 ? 0 : idx / pieces, xearly[e]);
+            }
+            for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads)
+                add_squares(M == 1 ? 0 : idx / pieces, x_piece(idx, 0));
+        } else {
+            const int row_pieces = (int)(K / 8);
+            for (int idx = t; idx < M * row_pieces; idx += kThreads) {
+                const int m = M == 1 ? 0 : idx / row_pieces, pc = M == 1 ? idx : idx % row_pieces;
+                add_squares(m, *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + (int64_t)pc * 8));
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            float v = ss[m];
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) v += __shfl_xor(v, d);
+            if (lane == 0) part[wave * M + m] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < W; ++w) v += part[w * M + m];
+            rs[m] = 1.f / sqrtf(v / (float)K + fu.eps);
+        }
+        for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0), 0);
+    }
 
     float acc[M];
 #pragma unroll
@@ -249,10 +347,10 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
         // stage the segment's activations and the sums of every 32-wide chunk
         if (seg0 == 0) {
 #pragma unroll
-            for (int e = 0; e < kEarlyX; ++e) x_store(t + e * kThreads, xearly[e]);
+            for (int e = 0; e < kEarlyX; ++e) x_store(t + e * kThreads, xearly[e], 0);
         } else {
             __syncthreads();                            // everyone is done with the previous segment's activations
-            for (int idx = t; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, seg0 * kSuper));
+            for (int idx = t; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, seg0 * kSuper), seg0 * kSuper);
         }
         __syncthreads();
         const int seg_end = seg0 + seg_items;
@@ -314,6 +412,29 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     }
     if (slot < n_rb) flush(slot);                       // sums of a row block this wavefront left unfinished (several segments)
     __syncthreads();
+    if (FUSED) {
+        // one result per (row block or pair of row blocks, row of X, row of the block)
+        const int units = gated ? n_rb / 2 : n_rb;
+        for (int idx = t; idx < units * M * kBlockRows; idx += kThreads) {
+            const int u = idx / (M * kBlockRows), m = (idx / kBlockRows) % M, rr = idx % kBlockRows;
+            const int sl = gated ? 2 * u : u;
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < W; ++w) s += red[((sl * W + w) * M + m) * kBlockRows + rr];
+            if (gated) {
+                float up = 0.f;
+#pragma unroll
+                for (int w = 0; w < W; ++w) up += red[(((sl + 1) * W + w) * M + m) * kBlockRows + rr];
+                s = silu_f32(s) * up;
+            }
+            const int64_t n = (rb0 + u) * kBlockRows + rr;
+            if (n < fu.n_out) {
+                if (fu.residual) s += (float)fu.residual[(int64_t)m * fu.n_out + n];
+                Y[(int64_t)m * fu.n_out + n] = (half_t)s;
+            }
+        }
+        return;
+    }
     for (int idx = t; idx < n_rb * M * kBlockRows; idx += kThreads) {
         const int sl = idx / (M * kBlockRows), m = (idx / kBlockRows) % M, rr = idx % kBlockRows;
         float s = 0.f;
@@ -324,24 +445,26 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     }
 }
 
-template <int G, int M, int W, int DEQ = kDeqE0M4>
-int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+template <int G, int M, int W, int DEQ = kDeqE0M4, bool FUSED = false>
+int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
+               const GemvFusion& fu = GemvFusion{})
 {
     const half_t* x = static_cast<const half_t*>(X);
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     const dim3 grid((unsigned)p.grid), block(W * 64);
-    if (p.lds_bytes > (size_t)kLdsDefaultBytes) {
+    const size_t lds_bytes = p.lds_bytes + (FUSED ? (size_t)W * M * sizeof(float) : 0);
+    if (lds_bytes > (size_t)kLdsDefaultBytes) {
         static bool attr_set = false;                   // per instantiation
         if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<G, M, W, DEQ>),
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<G, M, W, DEQ, FUSED>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimitBytes);
             if (e != hipSuccess) return record_hip_error(e);
             attr_set = true;
         }
     }
-    hipLaunchKernelGGL((gemv_kernel<G, M, W, DEQ>), grid, block, p.lds_bytes, stream, x, c, N, K, y, p.seg_items,
-                       p.step_slots, p.step_item, p.rb_base, p.rb_rem);
+    hipLaunchKernelGGL((gemv_kernel<G, M, W, DEQ, FUSED>), grid, block, lds_bytes, stream, x, c, N, K, y, p.seg_items,
+                       p.step_slots, p.step_item, p.rb_base, p.rb_rem, fu);
     return check_launch();
 }
 
@@ -356,31 +479,32 @@ int launch_int4_w(const GemvPlan& p, const void* X, const void* packed, int64_t 
     }
 }
 
-template <int G, int M>
-int launch_w(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+template <int G, int M, bool FUSED>
+int launch_w(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
+             const GemvFusion& fu)
 {
     switch (p.waves) {
-        case 4: return launch_one<G, M, 4>(p, X, packed, N, K, Y, stream);
-        case 8: return launch_one<G, M, 8>(p, X, packed, N, K, Y, stream);
+        case 4: return launch_one<G, M, 4, kDeqE0M4, FUSED>(p, X, packed, N, K, Y, stream, fu);
+        case 8: return launch_one<G, M, 8, kDeqE0M4, FUSED>(p, X, packed, N, K, Y, stream, fu);
         default:
-            if constexpr (M <= 4) return launch_one<G, M, 16>(p, X, packed, N, K, Y, stream);
+            if constexpr (M <= 4) return launch_one<G, M, 16, kDeqE0M4, FUSED>(p, X, packed, N, K, Y, stream, fu);
             else return E0M4_ERR_SHAPE;                 // make_plan never asks for this
     }
 }
 
-template <int G>
+template <int G, bool FUSED>
 int launch_m(const GemvPlan& p, int64_t M, const void* X, const void* packed, int64_t N, int64_t K, void* Y,
-             hipStream_t stream)
+             hipStream_t stream, const GemvFusion& fu = GemvFusion{})
 {
     switch (M) {
-        case 1: return launch_w<G, 1>(p, X, packed, N, K, Y, stream);
-        case 2: return launch_w<G, 2>(p, X, packed, N, K, Y, stream);
-        case 3: return launch_w<G, 3>(p, X, packed, N, K, Y, stream);
-        case 4: return launch_w<G, 4>(p, X, packed, N, K, Y, stream);
-        case 5: return launch_w<G, 5>(p, X, packed, N, K, Y, stream);
-        case 6: return launch_w<G, 6>(p, X, packed, N, K, Y, stream);
-        case 7: return launch_w<G, 7>(p, X, packed, N, K, Y, stream);
-        case 8: return launch_w<G, 8>(p, X, packed, N, K, Y, stream);
+        case 1: return launch_w<G, 1, FUSED>(p, X, packed, N, K, Y, stream, fu);
+        case 2: return launch_w<G, 2, FUSED>(p, X, packed, N, K, Y, stream, fu);
+        case 3: return launch_w<G, 3, FUSED>(p, X, packed, N, K, Y, stream, fu);
+        case 4: return launch_w<G, 4, FUSED>(p, X, packed, N, K, Y, stream, fu);
+        case 5: return launch_w<G, 5, FUSED>(p, X, packed, N, K, Y, stream, fu);
+        case 6: return launch_w<G, 6, FUSED>(p, X, packed, N, K, Y, stream, fu);
+        case 7: return launch_w<G, 7, FUSED>(p, X, packed, N, K, Y, stream, fu);
+        case 8: return launch_w<G, 8, FUSED>(p, X, packed, N, K, Y, stream, fu);
         default: return E0M4_ERR_SHAPE;
     }
 }
@@ -392,9 +516,44 @@ int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t
 {
     const GemvPlan p = make_plan(M, N, K);
     switch (group) {
-        case 32: return launch_m<32>(p, M, X, packed, N, K, Y, stream);
-        case 64: return launch_m<64>(p, M, X, packed, N, K, Y, stream);
-        case 128: return launch_m<128>(p, M, X, packed, N, K, Y, stream);
+        case 32: return launch_m<32, false>(p, M, X, packed, N, K, Y, stream);
+        case 64: return launch_m<64, false>(p, M, X, packed, N, K, Y, stream);
+        case 128: return launch_m<128, false>(p, M, X, packed, N, K, Y, stream);
+        default: return E0M4_ERR_GROUP;
+    }
+}
+
+// The gated epilogue needs a workgroup to own a gate row block together with its up row block, which
+// the kernel cannot do when X has to be staged in several segments (it then owns one row block at a
+// time); N/2 must be whole row blocks and the two halves less than 2 GiB apart.
+bool gemv_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K)
+{
+    if (M < 1 || M > kGemvMaxM) return false;
+    if (!f.swiglu) return true;
+    if (N % (2 * kBlockRows) != 0) return false;
+    bool single = true;
+    make_plan(M, N, K, 2, &single);
+    return single;
+}
+
+int launch_gemv_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group,
+                      void* Y, hipStream_t stream)
+{
+    if (!gemv_fused_supported(f, M, N, K)) return E0M4_ERR_SHAPE;
+    const GemvPlan p = make_plan(M, N, K, f.swiglu ? 2 : 1);
+    GemvFusion fu;
+    fu.gamma = static_cast<const half_t*>(f.gamma);
+    fu.residual = static_cast<const half_t*>(f.residual);
+    fu.eps = f.eps;
+    fu.swiglu = f.swiglu ? 1 : 0;
+    fu.n_out = f.swiglu ? N / 2 : N;
+    const int64_t half_bytes = (N / 2 / kBlockRows) * k_blocks(K) * (int64_t)block_bytes(group);
+    if (f.swiglu && half_bytes >= ((int64_t)1 << 31)) return E0M4_ERR_SHAPE;
+    fu.half_bytes = (uint32_t)half_bytes;
+    switch (group) {
+        case 32: return launch_m<32, true>(p, M, X, packed, N, K, Y, stream, fu);
+        case 64: return launch_m<64, true>(p, M, X, packed, N, K, Y, stream, fu);
+        case 128: return launch_m<128, true>(p, M, X, packed, N, K, Y, stream, fu);
         default: return E0M4_ERR_GROUP;
     }
 }

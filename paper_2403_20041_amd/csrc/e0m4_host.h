@@ -17,6 +17,15 @@ int record_hip_error(hipError_t e);
 // Tuning knobs (0 = use the heuristic).
 int knob(const char* name);
 
+// Operators folded into a matmul (e0m4_matmul_fused).  All-zero is the plain matmul.
+struct Fusion {
+    const void* gamma = nullptr;        // [K] fp16 rms-norm weight applied to the rows of X, or null
+    float eps = 0.f;                    // rms-norm epsilon
+    const void* residual = nullptr;     // [M, N_out] fp16 added to the result, or null
+    bool swiglu = false;                // Y[m, j] = silu(a[m, j]) * a[m, N/2 + j], N_out = N/2
+    bool any() const { return gamma || residual || swiglu; }
+};
+
 int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed, void* scales, void* bias,
                     const void* scales_in, const void* bias_in, bool fit, bool int4, hipStream_t stream);
 int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, bool int4, hipStream_t stream);
@@ -26,6 +35,11 @@ int launch_unpack(const void* packed, int64_t N, int64_t K, int group, void* out
 constexpr int kGemvMaxM = 8;
 int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                 hipStream_t stream);
+// With fused operators.  gemv_fused_supported: false when the gated epilogue meets activations that do
+// not fit the LDS in one piece (the caller then takes the GEMM path).
+bool gemv_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K);
+int launch_gemv_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group,
+                      void* Y, hipStream_t stream);
 // Small-batch path on the matrix cores: 3 <= M <= 16, group 128, X must fit the LDS of one compute unit.
 bool gemv_mfma_supported(int64_t M, int64_t N, int64_t K, int group);
 int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream);
@@ -36,13 +50,21 @@ int launch_gemv_int4(const void* X, const void* packed, int64_t N, int64_t K, in
 // MFMA path.
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                 void* workspace, size_t workspace_bytes, hipStream_t stream);
-size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu = false);
+// The same with the epilogue operators of `f` (residual add, gated product of the two halves of N);
+// rms-norm is not applied here: X must already be normalised.
+int launch_gemm_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group,
+                      void* Y, void* workspace, size_t workspace_bytes, hipStream_t stream);
+int launch_gemm_pipe_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group,
+                           void* Y, void* workspace, size_t workspace_bytes, hipStream_t stream);
+// Row-wise rms-norm of X [M, K] into X_out (fp16): the prologue of e0m4_matmul_fused for the GEMM path.
+int launch_rmsnorm(const void* X, int64_t M, int64_t K, const void* gamma, float eps, void* X_out, hipStream_t stream);
 // Software-pipelined 256 x 256 tile kernel (needs K % 128 == 0).  Problems with too few tiles to
 // fill the chip are split along K; the fp32 partial sums ([splits][M][N]) live in the caller's
 // workspace of gemm_pipe_workspace_bytes() bytes and a second kernel adds them.
 bool gemm_pipe_supported(int64_t K);
-size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K);
-int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K);      // tiles x K splits
+size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu = false);
+int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K, bool swiglu = false);      // tiles x K splits
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                      void* workspace, size_t workspace_bytes, hipStream_t stream);
 

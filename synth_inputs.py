@@ -56,6 +56,16 @@ def activations(M: int, K: int, seed: int, outlier_frac: float = 0.0, outlier_sc
     return X.astype(np.float16)
 
 
+def norm_weight(K: int, seed: int) -> np.ndarray:
+    """rms-norm weight gamma [K] fp16 ~ 1 + 0.1 N(0,1) (trained norm weights sit around one)."""
+    return (1.0 + 0.1 * _rng(seed, 5).standard_normal(K, dtype=np.float32)).astype(np.float16)
+
+
+def residual(M: int, N: int, seed: int) -> np.ndarray:
+    """Residual-stream values [M,N] fp16 ~ N(0,1)."""
+    return _rng(seed, 6).standard_normal((M, N), dtype=np.float32).astype(np.float16)
+
+
 def layer_seed(layer: int, proj: int) -> int:
     return layer * 4 + proj
 

@@ -33,7 +33,7 @@ def test_header_symbols_are_exported(L):
             "e0m4_strerror", "e0m4_last_hip_error", "e0m4_set_knob"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
-    assert L.e0m4_abi_version() == 2
+    assert L.e0m4_abi_version() == 3
 
 
 def test_size_functions(L):
