@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-table1", action="store_true", help="skip the E0M4 / INT4 latency comparison")
+    ap.add_argument("--no-fusion", action="store_true", help="skip the fused / unfused layer comparison")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--copy-probe", action="store_true",
                     help="first run three plain device copies of 1 GiB (calibration of HBM traffic counters)")
@@ -309,6 +310,79 @@ def main():
                                    "achieved": round(dom_tf, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                    "frac": round(dom_tf / MFMA_F16_PEAK_TFLOPS, 4),
                                    "traffic": MEASURED_TRAFFIC_PREFILL_GATE_UP}
+
+    # ---------------- operator fusion: a layer's four matmuls with their neighbours (rms-norm before qkv and
+    # gate+up, SiLU-gated product after gate+up, residual add after attn-out and down), fused into
+    # e0m4_matmul_fused against e0m4_matmul followed by torch's own operators; HIP graphs on both sides
+    if not args.no_fusion:
+        import torch.nn.functional as F
+
+        fus = {}
+        for M, n_l, reps in ((1, n_layers, 10), (PREFILL_M, 1, 10)):
+            (qn, qN, qK), (an, aN, aK), (gn, gN, gK), (dn, dN, dK) = shapes
+            xh = synth_inputs.activations_device(M, qK, 7000, dev)          # hidden state
+            xa = synth_inputs.activations_device(M, aK, 7001, dev)          # attention output
+            xd = synth_inputs.activations_device(M, dK, 7002, dev)          # input of down (unfused: product below)
+            gamma = torch.ones(qK, dtype=torch.float16, device=dev)
+            resid = synth_inputs.activations_device(M, aN, 7003, dev)
+            y_qkv = torch.empty((M, qN), dtype=torch.float16, device=dev)
+            y_h = torch.empty((M, aN), dtype=torch.float16, device=dev)
+            y_gu = torch.empty((M, gN), dtype=torch.float16, device=dev)
+            y_act = torch.empty((M, gN // 2), dtype=torch.float16, device=dev)
+            fws_bytes = max([e0m4.e0m4_fused_workspace_bytes(M, N, K, GROUP, True, e0m4.E0M4_EPILOGUE_SWIGLU
+                                                             if N == gN else e0m4.E0M4_EPILOGUE_NONE)
+                             for _, N, K in shapes] + [e0m4.e0m4_workspace_bytes(M, N, K, GROUP) for _, N, K in shapes])
+            fws = torch.empty(max(fws_bytes, 16), dtype=torch.uint8, device=dev)
+
+            def fused_layer(mats):
+                (_, _, _, cq, _, _), (_, _, _, ca, _, _), (_, _, _, cg, _, _), (_, _, _, cd, _, _) = mats
+                e0m4.e0m4_matmul_fused(xh, cq, qN, qK, GROUP, rms_gamma=gamma, rms_eps=1e-5, out=y_qkv,
+                                       workspace=fws, stream=stream)
+                e0m4.e0m4_matmul_fused(xa, ca, aN, aK, GROUP, residual=resid, out=y_h, workspace=fws, stream=stream)
+                e0m4.e0m4_matmul_fused(xh, cg, gN, gK, GROUP, rms_gamma=gamma, rms_eps=1e-5,
+                                       epilogue=e0m4.E0M4_EPILOGUE_SWIGLU, out=y_act, workspace=fws, stream=stream)
+                e0m4.e0m4_matmul_fused(xd, cd, dN, dK, GROUP, residual=resid, out=y_h, workspace=fws, stream=stream)
+
+            def unfused_layer(mats):
+                (_, _, _, cq, _, _), (_, _, _, ca, _, _), (_, _, _, cg, _, _), (_, _, _, cd, _, _) = mats
+                xn = F.rms_norm(xh, (qK,), gamma, 1e-5)
+                e0m4.e0m4_matmul(xn, cq, None, None, qN, qK, GROUP, out=y_qkv, workspace=fws, stream=stream)
+                e0m4.e0m4_matmul(xa, ca, None, None, aN, aK, GROUP, out=y_h, workspace=fws, stream=stream)
+                torch.add(y_h, resid, out=y_h)
+                xn = F.rms_norm(xh, (gK,), gamma, 1e-5)
+                e0m4.e0m4_matmul(xn, cg, None, None, gN, gK, GROUP, out=y_gu, workspace=fws, stream=stream)
+                torch.mul(F.silu(y_gu[:, : gN // 2]), y_gu[:, gN // 2:], out=y_act)
+                e0m4.e0m4_matmul(xd, cd, None, None, dN, dK, GROUP, out=y_h, workspace=fws, stream=stream)
+                torch.add(y_h, resid, out=y_h)
+
+            res = {}
+            with torch.cuda.stream(stream):
+                for label, fn in (("fused", fused_layer), ("unfused", unfused_layer)):
+                    for mats in layers[:n_l]:
+                        fn(mats)
+                    stream.synchronize()
+                    gf = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(gf, stream=stream):
+                        for mats in layers[:n_l]:
+                            fn(mats)
+                    for _ in range(2):
+                        gf.replay()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    for _ in range(reps):
+                        gf.replay()
+                    e1.record(stream)
+                    stream.synchronize()
+                    res[label] = e0.elapsed_time(e1) * 1e3 / (reps * n_l)
+                    del gf
+            fus["M%d" % M] = {"layers_in_graph": n_l, "fused_us_per_layer": round(res["fused"], 2),
+                              "unfused_us_per_layer": round(res["unfused"], 2),
+                              "unfused_over_fused": round(res["unfused"] / res["fused"], 3)}
+            del xh, xa, xd, gamma, resid, y_qkv, y_h, y_gu, y_act, fws
+        out["fusion"] = {"workload": "ChatGLM2-6B-shaped layer: rms-norm + qkv, attn-out + residual, rms-norm + gate+up + "
+                                     "SiLU-gated product, down + residual; e0m4_matmul_fused against e0m4_matmul plus "
+                                     "torch operators, HIP graphs",
+                         "results": fus}
 
     # ---------------- CPU oracle on a bounded sample of the decode workload (one layer, repeated)
     if not args.no_cpu:

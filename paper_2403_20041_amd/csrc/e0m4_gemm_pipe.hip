@@ -369,24 +369,33 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
 
 // The same with the fused epilogue: element i of the output is (m, j) with j < n_out; its sums are at
 // [m, j] of the slabs (and, gated, [m, n_half + j]), whose rows are N long.
+// V consecutive elements per thread (V = 4 needs n_out, N and N/2 to be multiples of 4).
+template <int V>
 __global__ __launch_bounds__(256) void splitk_reduce_fused_kernel(const float* __restrict__ partial, int splits,
                                                                   int64_t M, int64_t N, int64_t n_out,
                                                                   half_t* __restrict__ Y, PipeFusion fu)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    typedef float fvec __attribute__((ext_vector_type(V)));
+    typedef _Float16 hvec __attribute__((ext_vector_type(V)));
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * V;
     if (i >= M * n_out) return;
     const int64_t m = i / n_out, j = i - m * n_out;
     const size_t slab = (size_t)M * (size_t)N;
     const float* __restrict__ src = partial + (size_t)m * (size_t)N + (size_t)j;
-    float v = src[0];
-    for (int s = 1; s < splits; ++s) v += src[(size_t)s * slab];
+    fvec v = *reinterpret_cast<const fvec*>(src);
+    for (int s = 1; s < splits; ++s) v += *reinterpret_cast<const fvec*>(src + (size_t)s * slab);
     if (fu.swiglu) {
-        float up = src[fu.n_half];
-        for (int s = 1; s < splits; ++s) up += src[(size_t)s * slab + fu.n_half];
-        v = silu_f32(v) * up;
+        fvec up = *reinterpret_cast<const fvec*>(src + fu.n_half);
+        for (int s = 1; s < splits; ++s) up += *reinterpret_cast<const fvec*>(src + (size_t)s * slab + fu.n_half);
+#pragma unroll
+        for (int e = 0; e < V; ++e) v[e] = silu_f32(v[e]) * up[e];
     }
-    if (fu.residual) v += (float)fu.residual[i];
-    Y[i] = (half_t)v;
+    if (fu.residual) {
+        const hvec r = *reinterpret_cast<const hvec*>(fu.residual + i);
+#pragma unroll
+        for (int e = 0; e < V; ++e) v[e] += (float)r[e];
+    }
+    *reinterpret_cast<hvec*>(Y + i) = __builtin_convertvector(v, hvec);
 }
 
 // Y[i] = fp16(sum over splits, in split order, of partial[s][i]); V elements per thread.
@@ -456,8 +465,12 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     if (rc != E0M4_OK || splits == 1) return rc;
     if (FUSED) {
         const int64_t n_out = f.swiglu ? N / 2 : N;
-        hipLaunchKernelGGL(splitk_reduce_fused_kernel, dim3((unsigned)((M * n_out + 255) / 256)), dim3(256), 0, stream,
-                           partial, splits, M, N, n_out, y, fu);
+        if (n_out % 4 == 0 && N % 8 == 0)
+            hipLaunchKernelGGL(splitk_reduce_fused_kernel<4>, dim3((unsigned)((M * n_out / 4 + 255) / 256)), dim3(256), 0,
+                               stream, partial, splits, M, N, n_out, y, fu);
+        else
+            hipLaunchKernelGGL(splitk_reduce_fused_kernel<1>, dim3((unsigned)((M * n_out + 255) / 256)), dim3(256), 0,
+                               stream, partial, splits, M, N, n_out, y, fu);
         return check_launch();
     }
     const int64_t count = M * N;

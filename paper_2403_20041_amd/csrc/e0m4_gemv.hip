@@ -214,13 +214,18 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
 #pragma unroll
     for (int m = 0; m < M; ++m) rs[m] = 1.f;
     // store one piece and, from every fourth lane, the two sums of its 32-wide chunk
-    auto x_store = [&](int idx, const half8_t& vin, int kb_first) {
+    // the rms-norm weights that go with piece idx (zero beyond K)
+    auto g_piece = [&](int idx, int kb_first) {
+        const int pc = M == 1 ? idx : idx % pieces;
+        const int64_t k = (int64_t)kb_first * kBlockK + pc * 8;
+        half8_t gv = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (FUSED && fu.gamma && idx < M * pieces && k < K) gv = *reinterpret_cast<const half8_t*>(fu.gamma + k);
+        return gv;
+    };
+    auto x_store = [&](int idx, const half8_t& vin, const half8_t& gv) {
         const int m = M == 1 ? 0 : idx / pieces, pc = M == 1 ? idx : idx % pieces;
         half8_t v = vin;
         if (FUSED && fu.gamma) {                        // normalise on the way in: (x * rs[m]) * gamma[k], one rounding
-            const int64_t k = (int64_t)kb_first * kBlockK + pc * 8;
-            half8_t gv = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (idx < M * pieces && k < K) gv = *reinterpret_cast<const half8_t*>(fu.gamma + k);
             float r = rs[0];
 #pragma unroll
             for (int mm = 1; mm < M; ++mm) r = mm == m ? rs[mm] : r;
@@ -246,8 +251,20 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
 #pragma unroll
     for (int e = 0; e < kEarlyX; ++e) xearly[e] = x_piece(t + e * kThreads, 0);
     const bool normed = FUSED && fu.gamma != nullptr;   // then staging waits for the row scales (below)
+    const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    half8_t gearly[kEarlyX];                            // norm weights of the early pieces, requested with them
+#pragma unroll
+    for (int e = 0; e < kEarlyX; ++e) gearly[e] = normed ? g_piece(t + e * kThreads, 0) : zero8;
+    // gated or not, result number t of the epilogue is this thread's first: request its residual value now
+    float res_early = 0.f;
+    if (FUSED && fu.residual) {
+        const int units = gated ? n_rb / 2 : n_rb;
+        const int u = t / (M * kBlockRows), m = (t / kBlockRows) % M, rr = t % kBlockRows;
+        const int64_t n = (rb0 + u) * kBlockRows + rr;
+        if (u < units && n < fu.n_out) res_early = (float)fu.residual[(int64_t)m * fu.n_out + n];
+    }
     if (!normed)
-        for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0), 0);
+        for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0), zero8);
 
     // ---- the work item in flight: four code blocks and the parameter words
     uint4 c[kSuper];
@@ -324,7 +341,8 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
             for (int w = 0; w < W; ++w) v += part[w * M + m];
             rs[m] = 1.f / sqrtf(v / (float)K + fu.eps);
         }
-        for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0), 0);
+        for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads)
+            x_store(idx, x_piece(idx, 0), g_piece(idx, 0));
     }
 
     float acc[M];
@@ -347,10 +365,11 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
         // stage the segment's activations and the sums of every 32-wide chunk
         if (seg0 == 0) {
 #pragma unroll
-            for (int e = 0; e < kEarlyX; ++e) x_store(t + e * kThreads, xearly[e], 0);
+            for (int e = 0; e < kEarlyX; ++e) x_store(t + e * kThreads, xearly[e], gearly[e]);
         } else {
             __syncthreads();                            // everyone is done with the previous segment's activations
-            for (int idx = t; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, seg0 * kSuper), seg0 * kSuper);
+            for (int idx = t; idx < M * pieces; idx += kThreads)
+                x_store(idx, x_piece(idx, seg0 * kSuper), g_piece(idx, seg0 * kSuper));
         }
         __syncthreads();
         const int seg_end = seg0 + seg_items;
@@ -429,7 +448,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
             }
             const int64_t n = (rb0 + u) * kBlockRows + rr;
             if (n < fu.n_out) {
-                if (fu.residual) s += (float)fu.residual[(int64_t)m * fu.n_out + n];
+                if (fu.residual) s += idx == t ? res_early : (float)fu.residual[(int64_t)m * fu.n_out + n];
                 Y[(int64_t)m * fu.n_out + n] = (half_t)s;
             }
         }

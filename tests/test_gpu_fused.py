@@ -199,3 +199,81 @@ def test_argument_errors(e0m4):
     with pytest.raises(e0m4.E0M4Error):                 # workspace too small for the normalised copy of X
         e0m4.e0m4_matmul_fused(big, codes, 96, 128, 128, rms_gamma=gamma,
                                workspace=torch.zeros(64, dtype=torch.uint8, device=DEV))
+
+
+# ------------------------------------------------------------------ the benchmark's layer, full size
+
+def sample_indices(count, total, tile, rng):
+    fixed = {0, total - 1, tile - 1, tile, total // 2, max(total - tile, 0), max(total - tile - 1, 0)}
+    fixed = {i for i in fixed if 0 <= i < total}
+    extra = set(int(i) for i in rng.integers(0, total, max(count - len(fixed), 0)))
+    return np.array(sorted(fixed | extra), dtype=np.int64)
+
+
+FULL = [
+    # name, N, K, norm, swiglu, res  (the four fused calls of a ChatGLM2-6B-shaped layer, as the benchmark issues them)
+    ("qkv", 4608, 4096, True, False, False),
+    ("attn_out", 4096, 4096, False, False, True),
+    ("gate_up", 27392, 4096, True, True, False),
+    ("down", 4096, 13696, False, False, True),
+]
+
+
+@pytest.mark.parametrize("name,N,K,norm,swiglu,res", FULL, ids=[c[0] for c in FULL])
+def test_full_size_layer(e0m4, oracle, name, N, K, norm, swiglu, res):
+    G, Mp = 128, 1024
+    seed = 400 + N % 97 + K % 89
+    # decode: the whole output
+    run_fused(e0m4, oracle, 1, N, K, G, seed=seed, norm=norm, swiglu=swiglu, res=res)
+    # prefill: sampled rows over all outputs, sampled output columns over all rows
+    codes, What = quantized(e0m4, oracle, N, K, G, seed + 1, row_std=(0.5, 2.0))
+    X = synth_inputs.activations(Mp, K, seed=seed + 1, outlier_frac=0.01)
+    gamma = synth_inputs.norm_weight(K, seed + 1) if norm else None
+    n_out = N // 2 if swiglu else N
+    R = synth_inputs.residual(Mp, n_out, seed + 1) if res else None
+    Y = e0m4.e0m4_matmul_fused(to_dev(X), codes, N, K, G, rms_gamma=to_dev(gamma), rms_eps=1e-5,
+                               epilogue=e0m4.E0M4_EPILOGUE_SWIGLU if swiglu else e0m4.E0M4_EPILOGUE_NONE,
+                               residual=to_dev(R)).cpu().numpy()
+    rng = np.random.default_rng(seed)
+    ms = sample_indices(12, Mp, 128, rng)
+    Yr, info = oracle.matmul_fused(X[ms], What, gamma=gamma, eps=1e-5, swiglu=swiglu,
+                                   residual=None if R is None else R[ms])
+    check_fused(torch.from_numpy(Y[ms]), Yr, info, swiglu, norm, name + " prefill rows")
+    js = sample_indices(48, n_out, 128, rng)
+    rows = np.concatenate([js, js + N // 2]) if swiglu else js
+    Yc, info_c = oracle.matmul_fused(X, What[rows], gamma=gamma, eps=1e-5, swiglu=swiglu,
+                                     residual=None if R is None else np.ascontiguousarray(R[:, js]))
+    check_fused(torch.from_numpy(np.ascontiguousarray(Y[:, js])), Yc, info_c, swiglu, norm, name + " prefill cols")
+
+
+def test_fused_layer_in_a_hip_graph_matches_eager(e0m4):
+    """Graph replays of the fused decode calls reproduce the eager results bit for bit."""
+    G, N, K = 128, 27392, 4096
+    stream = torch.cuda.Stream()
+    W = synth_inputs.weights_device(N, K, 7300, DEV)
+    codes, _, _ = e0m4.e0m4_quantize(W, G)
+    del W
+    x = synth_inputs.activations_device(1, K, 7301, DEV)
+    gamma = to_dev(synth_inputs.norm_weight(K, 7302))
+    r = to_dev(synth_inputs.residual(1, N // 2, 7303))
+    y = torch.empty((1, N // 2), dtype=torch.float16, device=DEV)
+
+    def call(out, st=None):
+        return e0m4.e0m4_matmul_fused(x, codes, N, K, G, rms_gamma=gamma, rms_eps=1e-5,
+                                      epilogue=e0m4.E0M4_EPILOGUE_SWIGLU, residual=r, out=out, stream=st)
+
+    want = call(None).clone()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        call(y, stream)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            call(y, stream)
+    for replay in range(3):
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            graph.replay()
+        stream.synchronize()
+        assert torch.equal(y, want), "replay %d" % replay

@@ -110,3 +110,37 @@ def test_product_does_not_import_oracle():
         if f.endswith((".py", ".c", ".h")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2403_20041_amd" not in text and "libe0m4.so" not in text
+
+
+def test_fused_matmul_validation_and_workspace(L):
+    L.e0m4_matmul_fused.restype = ctypes.c_int
+    L.e0m4_matmul_fused.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
+                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.e0m4_fused_workspace_bytes.restype = ctypes.c_size_t
+    L.e0m4_fused_workspace_bytes.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 3
+    p, odd, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008), ctypes.c_void_p(0)
+    ERR_NULL, ERR_SHAPE, ERR_GROUP, ERR_ALIGN, ERR_WS = -1, -2, -3, -4, -5
+    NONE, SWIGLU = 0, 1
+    f = L.e0m4_matmul_fused
+    assert f(p, 1, null, 0.0, p, 128, 100, 128, NONE, null, p, null, 0, null) == ERR_SHAPE       # K % 32
+    assert f(p, 1, null, 0.0, p, 128, 128, 48, NONE, null, p, null, 0, null) == ERR_GROUP
+    assert f(p, 1, null, 0.0, p, 128, 128, 128, 2, null, p, null, 0, null) == ERR_SHAPE          # unknown epilogue
+    assert f(p, 1, null, 0.0, p, 96, 128, 128, SWIGLU, null, p, null, 0, null) == ERR_SHAPE      # N not a multiple of 64
+    assert f(p, 1, null, 0.0, p, 128, 0, 128, NONE, null, p, null, 0, null) == ERR_SHAPE         # nothing to contract
+    assert f(null, 1, null, 0.0, p, 128, 128, 128, NONE, null, p, null, 0, null) == ERR_NULL
+    assert f(p, 1, null, 0.0, p, 128, 128, 128, NONE, null, null, null, 0, null) == ERR_NULL
+    assert f(p, 1, odd, 0.0, p, 128, 128, 128, NONE, null, p, null, 0, null) == ERR_ALIGN        # gamma
+    assert f(p, 1, null, 0.0, p, 128, 128, 128, NONE, odd, p, null, 0, null) == ERR_ALIGN        # residual
+    assert f(p, 300, p, 0.0, p, 128, 128, 128, NONE, null, p, null, 0, null) == ERR_NULL         # GEMM path needs a workspace
+    assert f(p, 300, p, 0.0, p, 128, 128, 128, NONE, null, p, p, 64, null) == ERR_WS
+    assert f(null, 0, null, 0.0, null, 128, 128, 128, SWIGLU, null, null, null, 0, null) == 0    # empty problem
+    w = L.e0m4_fused_workspace_bytes
+    assert w(1, 27392, 4096, 128, 1, SWIGLU) == 0               # decode: everything stays in the one kernel
+    assert w(8, 4096, 4096, 128, 1, NONE) == 0
+    assert w(8, 4096, 16384, 128, 1, SWIGLU) > 0                # X does not fit the LDS in one piece: GEMM path
+    assert w(1024, 27392, 4096, 128, 1, SWIGLU) == 1024 * 4096 * 2         # normalised X; enough tiles, no K split
+    assert w(1024, 27392, 4096, 128, 0, SWIGLU) == 0
+    assert w(1024, 4096, 4096, 128, 0, NONE) == L.e0m4_workspace_bytes(1024, 4096, 4096, 128)
+    assert w(1024, 4096, 4096, 128, 1, NONE) == 1024 * 4096 * 2 + L.e0m4_workspace_bytes(1024, 4096, 4096, 128)
+    assert w(1024, 4096, 4096, 128, 1, 5) == 0
