@@ -149,9 +149,10 @@ int e0m4_matmul(const void* X_f16, int64_t M,
  *   4. y += residual[m,j], if `residual_f16` ([M, N_out] fp16) is not NULL; it
  *      may be the same buffer as Y (in-place residual stream);
  *   5. Y[m,j] = fp16(y), the only rounding after step 1.  Y is [M, N_out].
- * For M <= 8 everything happens inside the one decode kernel; for larger M the
- * epilogue runs inside the GEMM kernels (or the kernel that adds the K splits)
- * and the rms-norm is a launch of its own that writes x' to the workspace.
+ * On the decode paths (M <= 8, and the small-batch path of e0m4_matmul up to
+ * M = 16) everything happens inside the one kernel; for larger M the epilogue
+ * runs inside the GEMM kernels (or the kernel that adds the K splits) and the
+ * rms-norm is a launch of its own that writes x' to the workspace.
  * Workspace: e0m4_fused_workspace_bytes() bytes, same rules as e0m4_matmul.
  * With no operator selected the result equals e0m4_matmul's.  K == 0 is
  * rejected (E0M4_ERR_SHAPE); other shape, pointer and error rules as above.

@@ -113,10 +113,12 @@ size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 // rounded up to 256 bytes, then the partial sums of the split along K.
 static size_t norm_bytes(int64_t M, int64_t K) { return ((size_t)M * (size_t)K * 2 + 255) & ~(size_t)255; }
 
-// Which kernel family serves a fused matmul: 0 the decode kernel (everything in one launch),
-// 1 the GEMM kernels (rms-norm, if any, as a launch of its own before them).
-static int fused_path(const Fusion& f, int64_t M, int64_t N, int64_t K)
+// Which kernel family serves a fused matmul: 0 the decode kernel, 2 the small-batch kernel on the matrix
+// cores (both: everything in one launch), 1 the GEMM kernels (rms-norm, if any, as a launch of its own
+// before them).
+static int fused_path(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)
 {
+    if (knob("gemv_mfma") != 1 && gemv_mfma_fused_supported(f, M, N, K, group)) return 2;
     return (M <= kGemvMaxM && gemv_fused_supported(f, M, N, K)) ? 0 : 1;
 }
 
@@ -126,7 +128,7 @@ size_t e0m4_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int group, in
     if (epilogue != E0M4_EPILOGUE_NONE && epilogue != E0M4_EPILOGUE_SWIGLU) return 0;
     Fusion f;
     f.swiglu = epilogue == E0M4_EPILOGUE_SWIGLU;
-    if (fused_path(f, M, N, K) == 0) return 0;
+    if (fused_path(f, M, N, K, group) != 1) return 0;
     return (with_rmsnorm ? norm_bytes(M, K) : 0) + gemm_workspace_bytes(M, N, K, f.swiglu);
 }
 
@@ -269,7 +271,9 @@ int e0m4_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
         (residual && !aligned16(residual)))
         return E0M4_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    if (fused_path(f, M, N, K) == 0) return launch_gemv_fused(f, X, M, codes, N, K, group, Y, st);
+    const int path = fused_path(f, M, N, K, group);
+    if (path == 2) return launch_gemv_mfma_fused(f, X, M, codes, N, K, Y, st);
+    if (path == 0) return launch_gemv_fused(f, X, M, codes, N, K, group, Y, st);
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // 32-bit offsets in the GEMM epilogue
     const size_t nb = rms_gamma ? norm_bytes(M, K) : 0;
     const size_t need = nb + gemm_workspace_bytes(M, N, K, f.swiglu);

@@ -150,6 +150,33 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p)
     return __builtin_amdgcn_make_buffer_rsrc(q, 0, 0x7fffffff, 0x00020000);
 }
 
+// Operators folded into the decode kernels (e0m4_matmul_fused; paper: section "Operator and lagging
+// optimizations", fusion of rms-norm and of element-wise operators into their neighbours):
+//   gamma    : the rows of X are rms-normalised while they are staged (x * rsqrt(mean x^2 + eps) * gamma,
+//              rounded to fp16 as the stand-alone operator's output would be);
+//   swiglu   : weight row j (gate) is paired with row N/2 + j (up) and Y[m, j] = silu(gate) * up; a
+//              workgroup then owns pairs of row blocks, slot 2p the gate block and slot 2p + 1 the up block
+//              of pair p, `half_bytes` apart in the packed buffer;
+//   residual : added to the result before its one rounding.
+struct GemvFusion {
+    const half_t* gamma;
+    const half_t* residual;
+    float eps;
+    int swiglu;
+    uint32_t half_bytes;
+    int64_t n_out;                                      // row length of Y and of the residual
+};
+
+// Bytes between a gate row block and its up row block; the kernels add it to offsets inside a 2 GiB
+// buffer resource, so it may not exceed 1 GiB.
+constexpr int64_t kMaxHalfBytes = (int64_t)1 << 30;
+inline int64_t gated_half_bytes(int64_t N, int64_t K, int group)
+{
+    return (N / 2 / kBlockRows) * k_blocks(K) * (int64_t)block_bytes(group);
+}
+
+__device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
+
 __device__ inline half_t param_scale(uint32_t word) { return __builtin_bit_cast(half_t, (uint16_t)(word & 0xFFFFu)); }
 __device__ inline half_t param_bias(uint32_t word) { return __builtin_bit_cast(half_t, (uint16_t)(word >> 16)); }
 

@@ -52,8 +52,6 @@ struct TileFusion {
     int64_t n_half;                                     // N / 2 (gated epilogue)
 };
 
-__device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
-
 template <int G, int BM, int BN, bool FUSED>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict__ X, int64_t M,
                                                         const uint4* __restrict__ packed, int64_t N, int64_t K,
@@ -329,8 +327,7 @@ int launch_gemm_fused(const Fusion& f, const void* X, int64_t M, const void* pac
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     if (f.swiglu) {
-        const int64_t half_bytes = (N / 2 / kBlockRows) * k_blocks(K) * (int64_t)block_bytes(group);
-        if (N % (2 * kBlockRows) != 0 || half_bytes >= ((int64_t)1 << 31)) return E0M4_ERR_SHAPE;
+        if (N % (2 * kBlockRows) != 0 || gated_half_bytes(N, K, group) > kMaxHalfBytes) return E0M4_ERR_SHAPE;
     }
     if (use_pipe(M, N, K, f.swiglu))
         return launch_gemm_pipe_fused(f, X, M, packed, N, K, group, Y, workspace, workspace_bytes, stream);

@@ -108,25 +108,7 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K, int unit = 1, bool* single_s
 // fp16 with a conversion instruction, and the parameter word holds (scale, integer zero point).
 enum { kDeqE0M4 = 0, kDeqInt4Convert = 1 };
 
-// Operators folded into the kernel when FUSED (paper: section "Operator and lagging optimizations",
-// fusion of rms-norm and of element-wise operators into their neighbours):
-//   gamma    : the rows of X are rms-normalised while they are staged (x * rsqrt(mean x^2 + eps) * gamma,
-//              rounded to fp16 as the stand-alone operator's output would be);
-//   swiglu   : weight row j (gate) is paired with row N/2 + j (up) and Y[m, j] = silu(gate) * up; a
-//              workgroup then owns pairs of row blocks, slot 2p the gate block and slot 2p + 1 the up block
-//              of pair p, `half_bytes` apart in the packed buffer;
-//   residual : added to the result before its one rounding.
-struct GemvFusion {
-    const half_t* gamma;
-    const half_t* residual;
-    float eps;
-    int swiglu;
-    uint32_t half_bytes;
-    int64_t n_out;                                      // row length of Y and of the residual
-};
-
-__device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
-
+// FUSED adds the operators of GemvFusion (e0m4_device.h) to the kernel.
 template <int G, int M, int W, int DEQ = kDeqE0M4, bool FUSED = false>
 __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__ X, const uint4* __restrict__ packed,
                                                       int64_t N, int64_t K, half_t* __restrict__ Y, int seg_items,
@@ -542,6 +524,18 @@ int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t
     }
 }
 
+GemvFusion make_gemv_fusion(const Fusion& f, int64_t N, int64_t K, int group)
+{
+    GemvFusion fu;
+    fu.gamma = static_cast<const half_t*>(f.gamma);
+    fu.residual = static_cast<const half_t*>(f.residual);
+    fu.eps = f.eps;
+    fu.swiglu = f.swiglu ? 1 : 0;
+    fu.half_bytes = (uint32_t)gated_half_bytes(N, K, group);
+    fu.n_out = f.swiglu ? N / 2 : N;
+    return fu;
+}
+
 // The gated epilogue needs a workgroup to own a gate row block together with its up row block, which
 // the kernel cannot do when X has to be staged in several segments (it then owns one row block at a
 // time); N/2 must be whole row blocks and the two halves less than 2 GiB apart.
@@ -560,15 +554,9 @@ int launch_gemv_fused(const Fusion& f, const void* X, int64_t M, const void* pac
 {
     if (!gemv_fused_supported(f, M, N, K)) return E0M4_ERR_SHAPE;
     const GemvPlan p = make_plan(M, N, K, f.swiglu ? 2 : 1);
-    GemvFusion fu;
-    fu.gamma = static_cast<const half_t*>(f.gamma);
-    fu.residual = static_cast<const half_t*>(f.residual);
-    fu.eps = f.eps;
-    fu.swiglu = f.swiglu ? 1 : 0;
-    fu.n_out = f.swiglu ? N / 2 : N;
-    const int64_t half_bytes = (N / 2 / kBlockRows) * k_blocks(K) * (int64_t)block_bytes(group);
-    if (f.swiglu && half_bytes >= ((int64_t)1 << 31)) return E0M4_ERR_SHAPE;
-    fu.half_bytes = (uint32_t)half_bytes;
+    const int64_t half_bytes = gated_half_bytes(N, K, group);
+    if (f.swiglu && half_bytes > kMaxHalfBytes) return E0M4_ERR_SHAPE;
+    const GemvFusion fu = make_gemv_fusion(f, N, K, group);
     switch (group) {
         case 32: return launch_m<32, true>(p, M, X, packed, N, K, Y, stream, fu);
         case 64: return launch_m<64, true>(p, M, X, packed, N, K, Y, stream, fu);

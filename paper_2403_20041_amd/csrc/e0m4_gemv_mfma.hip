@@ -50,21 +50,25 @@ struct MfmaPlan {
     size_t lds_bytes;
 };
 
+constexpr int kNormBytes = (16 + 1) * kMaxM * 4;        // rms-norm: per-wavefront sums of squares and the row scales
+
 size_t lds_need(int64_t M, int64_t nkb, int waves)
 {
     return (size_t)M * (nkb * kXBlockBytes + kRowPadBytes) + (size_t)nkb * kSumBytesPerBlock +
-           2 * (size_t)waves * kMaxM * kBlockRows * sizeof(float);
+           2 * (size_t)waves * kMaxM * kBlockRows * sizeof(float) + kNormBytes;
 }
 
 // Byte offset, inside one block of one row of X, of the 8-byte half-unit that holds the elements of
 // word w (k = 8w..8w+7 of chunk q) for the MFMA of pair set hl (0: elements 0,1,6,7; 1: elements 2..5).
 __device__ inline int x_unit_off(int q, int w, int hl) { return ((q * 4 + (w >> 1) * 2 + hl) << 4) + ((w & 1) << 3); }
 
-template <int W>
+// FUSED adds the operators of GemvFusion (e0m4_device.h): rms-norm while X is staged, the gated epilogue
+// (the workgroup owns pairs of a gate and an up row block and writes silu(gate) * up), the residual add.
+template <int W, bool FUSED>
 __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restrict__ X, int M,
                                                            const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                            half_t* __restrict__ Y, int step_slots, int step_item,
-                                                           int rb_base, int rb_rem)
+                                                           int rb_base, int rb_rem, GemvFusion fu)
 {
     constexpr int kThreads = W * 64;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -75,19 +79,26 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     unsigned char* xs = smem;                                                   // [M] rows of X in MFMA order
     float* sums = reinterpret_cast<float*>(smem + (size_t)M * row_stride);      // [nkb][2][16]
     float* red = sums + (size_t)nkb * 2 * kMaxM;                                // [2][W][16 m][16 n]
+    float* norm_part = red + 2 * W * kMaxM * kBlockRows;                        // [W][16] sums of squares, then [16] row scales
 
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int n_l = lane & 15, g_l = lane >> 4;         // weight row / k-group of this lane; also (row of X, k-group)
     const uint32_t fmask = frac_mask_vgpr(), fmask_low = frac_mask_low_vgpr();
+    // even deal of row blocks; gated: of pairs of row blocks (rb0 is then the pair, i.e. its gate row block)
+    const bool gated = FUSED && fu.swiglu;
     const int64_t rb0 = (int64_t)blockIdx.x * rb_base + min((int)blockIdx.x, rb_rem);
-    const int n_rb = rb_base + ((int)blockIdx.x < rb_rem ? 1 : 0);
+    const int n_rb = (rb_base + ((int)blockIdx.x < rb_rem ? 1 : 0)) * (gated ? 2 : 1);
     const __amdgpu_buffer_rsrc_t wg_codes = make_rsrc(packed + lay.code_index(rb0, 0));
     const __amdgpu_buffer_rsrc_t wg_params = make_rsrc(reinterpret_cast<const char*>(packed) + 4 * lay.param_index(rb0, 0));
     const uint32_t rb_stride = (uint32_t)nkb * block_bytes(kG);
     const uint32_t lane_code_off = lane * 16;
     const int param_words_rb = nkb * kPW;
+    auto slot_off = [&](uint32_t s_) -> uint32_t {      // byte offset of row block slot s from the first row block
+        if (FUSED && fu.swiglu) return (s_ >> 1) * rb_stride + (s_ & 1) * fu.half_bytes;
+        return s_ * rb_stride;
+    };
 
     auto advance = [&](int& s_, int& i_) {              // W work items ahead
         s_ += step_slots;
@@ -111,7 +122,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     auto fetch_params = [&](int fs, int fi) {           // past the end the last item is read again
         const bool in = fs < n_rb;
         const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
-        const uint32_t soff = __builtin_amdgcn_readfirstlane(s_ * rb_stride + i_ * (kSuper * kPW * 4));
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(slot_off(s_) + i_ * (kSuper * kPW * 4));
         const int last = param_words_rb - 1 - (int)i_ * (kSuper * kPW);
         pwraw = __builtin_amdgcn_raw_buffer_load_b32(wg_params, min(lane, last) * 4, (int)soff, 0);
     };
@@ -119,7 +130,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
         const bool in = fs < n_rb;
         const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
         const uint32_t kb = min(i_ * kSuper + j, (uint32_t)nkb - 1);
-        const uint32_t soff = __builtin_amdgcn_readfirstlane(s_ * rb_stride + kb * kBlockCodeBytes);
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(slot_off(s_) + kb * kBlockCodeBytes);
         const u32x4 cv = __builtin_amdgcn_raw_buffer_load_b128(wg_codes, (int)lane_code_off, (int)soff, 0);
         c[j] = make_uint4(cv.x, cv.y, cv.z, cv.w);
     };
@@ -130,12 +141,60 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     // ---- stage X: thread idx handles the 8 elements k = 8*pc..8*pc+7 of row m; 16 consecutive threads
     // cover one block of one row and add up its two sums
     const int pieces = nkb * (kBlockK / 8);
+    const bool normed = FUSED && fu.gamma != nullptr;
+    if (normed) {
+        // rms-norm: sum of squares of every row (first pass over X; the staging pass below reads it again,
+        // from the cache), reduced in a fixed order: lanes, then wavefronts
+        float ss[kMaxM];
+#pragma unroll
+        for (int m = 0; m < kMaxM; ++m) ss[m] = 0.f;
+        for (int base = 0; base < M * pieces; base += kThreads) {
+            const int idx = base + t;
+            const int m = idx / pieces, pc = idx - m * pieces;
+            const int64_t k = (int64_t)pc * 8;
+            float d = 0.f;
+            if (idx < M * pieces && k < K) {
+                const half8_t v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+                const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
+                d = __builtin_amdgcn_fdot2(x0, x0, 0.f, false);
+                d = __builtin_amdgcn_fdot2(x1, x1, d, false);
+                d = __builtin_amdgcn_fdot2(x2, x2, d, false);
+                d = __builtin_amdgcn_fdot2(x3, x3, d, false);
+            }
+#pragma unroll
+            for (int mm = 0; mm < kMaxM; ++mm) ss[mm] += mm == m ? d : 0.f;
+        }
+#pragma unroll
+        for (int m = 0; m < kMaxM; ++m) {
+            float v = ss[m];
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) v += __shfl_xor(v, d);
+            if (lane == 0) norm_part[wave * kMaxM + m] = v;
+        }
+        __syncthreads();
+        float tot = 0.f;
+        if (t < kMaxM) {
+#pragma unroll
+            for (int w = 0; w < W; ++w) tot += norm_part[w * kMaxM + t];
+        }
+        __syncthreads();
+        if (t < kMaxM) norm_part[t] = 1.f / sqrtf(tot / (float)K + fu.eps);
+        __syncthreads();
+    }
     for (int base = 0; base < M * pieces; base += kThreads) {
         const int idx = base + t;
         const int m = idx / pieces, pc = idx - m * pieces;
         const int64_t k = (int64_t)pc * 8;
         half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (idx < M * pieces && k < K) v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+        if (idx < M * pieces && k < K) {
+            v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+            if (normed) {                               // (x * row scale) * gamma, one rounding
+                const half8_t gv = *reinterpret_cast<const half8_t*>(fu.gamma + k);
+                const float r = norm_part[m];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = (half_t)(((float)v[i] * r) * (float)gv[i]);
+            }
+        }
         const half2_t ones = {(half_t)1.f, (half_t)1.f};
         const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
         float sl = __builtin_amdgcn_fdot2(x1, ones, 0.f, false);
@@ -209,6 +268,32 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
             si = nitem;
             advance(nslot, nitem);
         }
+        if (gated) {
+            // slot 2p is the gate block and slot 2p + 1 the up block of pair p: park the gate sums in
+            // half 0 of `red`, the up sums in half 1, then combine
+            float* mine = red + (((s_rb & 1) * W + wave) * kMaxM + 4 * g_l) * kBlockRows + n_l;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mine[r * kBlockRows] = ysum[r];
+            if ((s_rb & 1) == 0) continue;
+            __syncthreads();
+            if (t < kMaxM * kBlockRows) {
+                const int m = t >> 4, n = t & 15;
+                float g = 0.f, u = 0.f;
+#pragma unroll
+                for (int w = 0; w < W; ++w) {
+                    g += red[((0 * W + w) * kMaxM + m) * kBlockRows + n];
+                    u += red[((1 * W + w) * kMaxM + m) * kBlockRows + n];
+                }
+                const int64_t col = (rb0 + (s_rb >> 1)) * kBlockRows + n;
+                if (m < M && col < fu.n_out) {
+                    float y = silu_f32(g) * u;
+                    if (fu.residual) y += (float)fu.residual[(int64_t)m * fu.n_out + col];
+                    Y[(int64_t)m * fu.n_out + col] = (half_t)y;
+                }
+            }
+            __syncthreads();                            // both halves of `red` are free again
+            continue;
+        }
         // the wavefronts' shares of row block s_rb are added in wavefront order
         float* mine = red + (((s_rb & 1) * W + wave) * kMaxM + 4 * g_l) * kBlockRows + n_l;
 #pragma unroll
@@ -220,6 +305,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 #pragma unroll
             for (int w = 0; w < W; ++w) s += red[(((s_rb & 1) * W + w) * kMaxM + m) * kBlockRows + n];
             const int64_t row = (rb0 + s_rb) * kBlockRows + n;
+            if (FUSED && fu.residual && m < M && row < N) s += (float)fu.residual[(int64_t)m * N + row];
             if (m < M && row < N) Y[(int64_t)m * N + row] = (half_t)s;
         }
         // no second barrier: row block s_rb + 1 uses the other half of `red`, and nobody writes this
@@ -227,9 +313,10 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     }
 }
 
-bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p)
+// `unit`: 2 when row blocks are dealt in (gate, up) pairs; rb_base and rb_rem then count pairs
+bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1)
 {
-    const int64_t nrb = row_blocks(N), nkb = k_blocks(K);
+    const int64_t nrb = row_blocks(N) / unit, nkb = k_blocks(K);
     const int64_t nsi = (nkb + kSuper - 1) / kSuper;
     int w = knob("gemv_waves");
     if (w != 4 && w != 8 && w != 16) w = nsi >= 16 ? 16 : 8;
@@ -247,20 +334,20 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p)
     return true;
 }
 
-template <int W>
+template <int W, bool FUSED>
 int launch_mfma(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
-                hipStream_t stream)
+                hipStream_t stream, const GemvFusion& fu = GemvFusion{})
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_mfma_kernel<W>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimitBytes);
         if (e != hipSuccess) return record_hip_error(e);
         attr_set = true;
     }
-    hipLaunchKernelGGL(gemv_mfma_kernel<W>, dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
+    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
                        static_cast<const half_t*>(X), (int)M, static_cast<const uint4*>(packed), N, K,
-                       static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem);
+                       static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, fu);
     return check_launch();
 }
 
@@ -278,9 +365,29 @@ int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, in
     MfmaPlan p;
     if (!make_mfma_plan(M, N, K, p)) return E0M4_ERR_SHAPE;
     switch (p.waves) {
-        case 4: return launch_mfma<4>(p, X, M, packed, N, K, Y, stream);
-        case 8: return launch_mfma<8>(p, X, M, packed, N, K, Y, stream);
-        default: return launch_mfma<16>(p, X, M, packed, N, K, Y, stream);
+        case 4: return launch_mfma<4, false>(p, X, M, packed, N, K, Y, stream);
+        case 8: return launch_mfma<8, false>(p, X, M, packed, N, K, Y, stream);
+        default: return launch_mfma<16, false>(p, X, M, packed, N, K, Y, stream);
+    }
+}
+
+bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)
+{
+    if (!gemv_mfma_supported(M, N, K, group)) return false;
+    if (!f.swiglu) return true;
+    return N % (2 * kBlockRows) == 0 && gated_half_bytes(N, K, group) <= kMaxHalfBytes;
+}
+
+int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                           hipStream_t stream)
+{
+    MfmaPlan p;
+    if (!gemv_mfma_fused_supported(f, M, N, K, kG) || !make_mfma_plan(M, N, K, p, f.swiglu ? 2 : 1)) return E0M4_ERR_SHAPE;
+    const GemvFusion fu = make_gemv_fusion(f, N, K, kG);
+    switch (p.waves) {
+        case 4: return launch_mfma<4, true>(p, X, M, packed, N, K, Y, stream, fu);
+        case 8: return launch_mfma<8, true>(p, X, M, packed, N, K, Y, stream, fu);
+        default: return launch_mfma<16, true>(p, X, M, packed, N, K, Y, stream, fu);
     }
 }
 

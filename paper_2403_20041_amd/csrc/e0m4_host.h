@@ -26,6 +26,10 @@ struct Fusion {
     bool any() const { return gamma || residual || swiglu; }
 };
 
+struct GemvFusion;
+// Device view of `f` for the decode kernels (defined in e0m4_gemv.hip).
+GemvFusion make_gemv_fusion(const Fusion& f, int64_t N, int64_t K, int group);
+
 int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed, void* scales, void* bias,
                     const void* scales_in, const void* bias_in, bool fit, bool int4, hipStream_t stream);
 int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, bool int4, hipStream_t stream);
@@ -43,6 +47,9 @@ int launch_gemv_fused(const Fusion& f, const void* X, int64_t M, const void* pac
 // Small-batch path on the matrix cores: 3 <= M <= 16, group 128, X must fit the LDS of one compute unit.
 bool gemv_mfma_supported(int64_t M, int64_t N, int64_t K, int group);
 int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream);
+bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K, int group);
+int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                           hipStream_t stream);
 // INT4 twin of the M = 1 kernel: same layout and work decomposition, codes turned into numbers with
 // integer-to-float conversion instructions.
 int launch_gemv_int4(const void* X, const void* packed, int64_t N, int64_t K, int group, void* Y, hipStream_t stream);

@@ -99,6 +99,37 @@ def test_decode_kernel(e0m4, oracle, M, norm, swiglu, res):
     run_fused(e0m4, oracle, M, 1088, 4096, 128, seed=310 + M, norm=norm, swiglu=swiglu, res=res, outliers=True)
 
 
+@pytest.mark.parametrize("norm,swiglu,res", COMBOS)
+@pytest.mark.parametrize("M", [2, 5, 8])
+def test_decode_vector_kernel_for_small_batches(e0m4, oracle, M, norm, swiglu, res):
+    e0m4.e0m4_set_knob("gemv_mfma", 1)                  # group 128 would take the matrix-core kernel for M >= 3
+    try:
+        run_fused(e0m4, oracle, M, 320, 1152, 128, seed=305 + M, norm=norm, swiglu=swiglu, res=res)
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+
+
+@pytest.mark.parametrize("norm,swiglu,res", COMBOS)
+@pytest.mark.parametrize("M", [3, 4, 8, 9, 13, 16])
+def test_small_batch_matrix_core_kernel(e0m4, oracle, M, norm, swiglu, res):
+    run_fused(e0m4, oracle, M, 320, 1152, 128, seed=500 + M, norm=norm, swiglu=swiglu, res=res)     # 9 k blocks, 10 pairs
+    run_fused(e0m4, oracle, M, 1088, 4096, 128, seed=510 + M, norm=norm, swiglu=swiglu, res=res, outliers=True)
+    run_fused(e0m4, oracle, M, 333 if not swiglu else 448, 1664, 128, seed=520 + M, norm=norm, swiglu=swiglu, res=res)
+
+
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("target", [0, 3])
+def test_small_batch_matrix_core_kernel_forced_shapes(e0m4, oracle, waves, target):
+    e0m4.e0m4_set_knob("gemv_waves", waves)
+    e0m4.e0m4_set_knob("gemv_workgroups", target)       # 3 workgroups: many pairs each, dealt unevenly
+    try:
+        run_fused(e0m4, oracle, 6, 2240, 2304, 128, seed=530 + waves, norm=True, swiglu=True, res=True)
+        run_fused(e0m4, oracle, 16, 130, 4096, 128, seed=531 + waves, norm=True, res=True)
+    finally:
+        e0m4.e0m4_set_knob("gemv_waves", 0)
+        e0m4.e0m4_set_knob("gemv_workgroups", 0)
+
+
 @pytest.mark.parametrize("G", [32, 64])
 def test_decode_kernel_other_groups(e0m4, oracle, G):
     run_fused(e0m4, oracle, 1, 448, 1760 if G == 32 else 1728, G, seed=320 + G, norm=True, swiglu=True, res=True)
@@ -133,14 +164,15 @@ def test_nothing_selected_equals_the_plain_matmul(e0m4, oracle):
         codes, What = quantized(e0m4, oracle, 200, 1152, 128, seed=350 + M)
         X = to_dev(synth_inputs.activations(M, 1152, seed=350 + M))
         y0 = e0m4.e0m4_matmul(X, codes, None, None, 200, 1152, 128)
-        e0m4.e0m4_set_knob("gemv_mfma", 1)              # the fused entry point uses the vector kernel for M <= 8
+        y1 = e0m4.e0m4_matmul_fused(X, codes, 200, 1152, 128)
+        e0m4.e0m4_set_knob("gemv_mfma", 1)              # small batches on the vector kernel
         try:
             y0v = e0m4.e0m4_matmul(X, codes, None, None, 200, 1152, 128)
+            y1v = e0m4.e0m4_matmul_fused(X, codes, 200, 1152, 128)
         finally:
             e0m4.e0m4_set_knob("gemv_mfma", 0)
-        y1 = e0m4.e0m4_matmul_fused(X, codes, 200, 1152, 128)
         torch.cuda.synchronize()
-        assert torch.equal(y1, y0v), M
+        assert torch.equal(y1, y0) and torch.equal(y1v, y0v), M
         Yref, absdot = oracle.matmul(X.cpu().numpy(), What)
         assert np.all(np.abs(y0.cpu().numpy().astype(np.float64) - Yref.astype(np.float64)) <= 1e-2 * np.maximum(1, absdot))
 
