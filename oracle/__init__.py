@@ -280,3 +280,21 @@ def matmul_fused(X: np.ndarray, What: np.ndarray, gamma=None, eps: float = 0.0, 
     with np.errstate(over="ignore"):
         Y = y.astype(np.float16)
     return Y, {"a": a, "absdot": absdot, "y": y}
+
+
+# --------------------------------------------------------------------------------------------------
+# KV-cache append (paper: section "KV cache copy optimization"): one tensor of the maximum sequence
+# length holds the cache, sequence position first; the rows produced for the new tokens are written in
+# place at the positions given by position_ids, which replaces concatenating old cache and new rows.
+# --------------------------------------------------------------------------------------------------
+
+def kv_append(cache: np.ndarray, new_rows: np.ndarray, position_ids: np.ndarray) -> np.ndarray:
+    """Returns the cache [max_seq, row] after writing new_rows[i] to row position_ids[i], one row at a
+    time in order (a position outside [0, max_seq) leaves the cache untouched for that row)."""
+    out = np.array(cache, copy=True)
+    for i in range(new_rows.shape[0]):
+        p = int(position_ids[i])
+        if 0 <= p < out.shape[0]:
+            for e in range(new_rows.shape[1]):
+                out[p, e] = new_rows[i, e]
+    return out

@@ -558,3 +558,34 @@ def test_matmul_fused_special_cases(oracle):
     Xc = np.where(rng.random((M, K)) < 0.5, -3.0, 3.0).astype(np.float16)
     Yn, info_n = oracle.matmul_fused(Xc, Wg, gamma=np.ones(K, np.float16), eps=0.0)
     np.testing.assert_allclose(info_n["a"], (Xc.astype(np.float64) / 3.0) @ Wg.astype(np.float64).T, rtol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------------------
+# KV-cache append (paper: section "KV cache copy optimization"): writing the new rows at consecutive
+# positions of the one big tensor must give what concatenating old cache and new rows gives.
+# ---------------------------------------------------------------------------------------------------
+
+def test_kv_append_equals_concatenation(oracle):
+    rng = np.random.default_rng(11)
+    max_seq, row, have, n_new = 40, 24, 17, 5
+    old = rng.standard_normal((have, row)).astype(np.float16)
+    new = rng.standard_normal((n_new, row)).astype(np.float16)
+    cache = np.full((max_seq, row), np.float16(-7.0))
+    cache[:have] = old
+    out = oracle.kv_append(cache, new, np.arange(have, have + n_new))
+    assert np.array_equal(out[: have + n_new], np.concatenate([old, new]))          # the operator it replaces
+    assert np.array_equal(out[have + n_new:], cache[have + n_new:])                  # the rest is untouched
+    assert np.array_equal(cache[have], np.full(row, np.float16(-7.0)))               # the input is not modified
+    # arbitrary positions: row i lands at position_ids[i] and nowhere else; out-of-range rows are dropped
+    pos = np.array([3, 39, 0, 40, -1])
+    out2 = oracle.kv_append(cache, new, pos)
+    for i, p in enumerate(pos):
+        if 0 <= p < max_seq:
+            assert np.array_equal(out2[p], new[i])
+    untouched = [p for p in range(max_seq) if p not in (3, 39, 0)]
+    assert np.array_equal(out2[untouched], cache[untouched])
+    # decode: one row at a time, step after step, builds the same cache as one prefill-sized append
+    step = cache
+    for i in range(n_new):
+        step = oracle.kv_append(step, new[i:i + 1], np.array([have + i]))
+    assert np.array_equal(step, out)
