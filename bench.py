@@ -384,6 +384,45 @@ def main():
                                      "torch operators, HIP graphs",
                          "results": fus}
 
+    # ---------------- KV-cache append in place against the concatenation it replaces (one layer's K and V rows
+    # of a ChatGLM2-6B-shaped model, 2 x 2 heads x 128, taken from the QKV output; cache of 2048 positions)
+    if not args.no_fusion:
+        kv = {}
+        max_seq, row = 2048, 512
+        for label, n_new in (("decode_1_token", 1), ("prefill_1024_tokens", 1024)):
+            have = max_seq - n_new
+            cache = torch.zeros((max_seq, row), dtype=torch.float16, device=dev)
+            qkv_out = synth_inputs.activations_device(n_new, 4608, 7200, dev)
+            pos = torch.arange(have, have + n_new, dtype=torch.int64, device=dev)
+            res = {}
+            with torch.cuda.stream(stream):
+                for what in ("append", "concat"):
+                    def op():
+                        if what == "append":
+                            e0m4.e0m4_kv_append(cache, qkv_out[:, 4096:], pos, stream=stream)
+                        else:
+                            torch.cat([cache[:have], qkv_out[:, 4096:]], dim=0)
+                    op()
+                    stream.synchronize()
+                    gk = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(gk, stream=stream):
+                        for _ in range(20):
+                            op()
+                    gk.replay()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    for _ in range(5):
+                        gk.replay()
+                    e1.record(stream)
+                    stream.synchronize()
+                    res[what] = e0.elapsed_time(e1) * 1e3 / 100
+                    del gk
+            kv[label] = {"append_us": round(res["append"], 2), "concat_us": round(res["concat"], 2),
+                         "bytes_moved_append": 2 * n_new * row * 2, "bytes_moved_concat": 2 * max_seq * row * 2}
+            del cache, qkv_out, pos
+        out["kv_append"] = {"workload": "cache [2048, 512] fp16, new rows = columns 4096..4607 of the QKV output; "
+                                        "20 back-to-back launches in a HIP graph", "results": kv}
+
     # ---------------- CPU oracle on a bounded sample of the decode workload (one layer, repeated)
     if not args.no_cpu:
         import numpy as np

@@ -166,6 +166,28 @@ int e0m4_matmul_fused(const void* X_f16, int64_t M, const void* rms_gamma_f16, f
                       void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * In-place KV-cache append (paper: section "KV cache copy optimization").  The
+ * cache of a layer is ONE tensor of the maximum sequence length with the
+ * sequence position as its first dimension, `cache_f16` = [max_seq, row_elems]
+ * fp16 row-major (e.g. row_elems = kv_heads * head_dim, or both K and V of a
+ * position side by side); the rows produced for the new tokens are written
+ * where they belong instead of being concatenated to a copy of the old cache:
+ *     cache[position_ids[i], e] = new_rows[i * new_ld + e],
+ *         0 <= i < n_new, 0 <= e < row_elems.
+ * `new_rows_f16` may be a column range of a wider matrix (the K/V columns of
+ * the QKV projection's output): new_ld is the distance between consecutive new
+ * rows in elements, new_ld >= row_elems.  `position_ids_i64` is a DEVICE array
+ * of n_new int64 positions.  A row whose position lies outside [0, max_seq) is
+ * skipped; positions must otherwise be distinct (two rows aimed at one position
+ * race).  row_elems and new_ld must be multiples of 8, cache and new_rows
+ * 16-byte aligned, position_ids 8-byte aligned.  Same stream and error rules as
+ * the other entry points; n_new == 0 succeeds and enqueues nothing.
+ */
+int e0m4_kv_append(void* cache_f16, int64_t max_seq, int64_t row_elems,
+                   const void* new_rows_f16, int64_t n_new, int64_t new_ld,
+                   const void* position_ids_i64, void* stream);
+
+/*
  * INT4 twin (paper: section "Evaluation of FP4 quantization", Table 1 and
  * Table 2, which compare E0M4 with "INT4 quantization").  The paper does not
  * define that quantiser; this library's reading is group-wise asymmetric

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     e0m4_int4_dequant,
     e0m4_int4_gemv,
     e0m4_int4_quantize,
+    e0m4_kv_append,
     e0m4_matmul,
     e0m4_matmul_fused,
     e0m4_params_elems,

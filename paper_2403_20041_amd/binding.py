@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
     L.e0m4_fused_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci]
     L.e0m4_matmul_fused.restype = ci
     L.e0m4_matmul_fused.argtypes = [vp, i64, vp, ctypes.c_float, vp, i64, i64, ci, ci, vp, vp, vp, sz, vp]
+    L.e0m4_kv_append.restype = ci
+    L.e0m4_kv_append.argtypes = [vp, i64, i64, vp, i64, i64, vp, vp]
     L.e0m4_int4_quantize.restype = ci
     L.e0m4_int4_quantize.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
     L.e0m4_int4_dequant.restype = ci
@@ -209,6 +211,21 @@ def e0m4_matmul_fused(X, codes, N: int, K: int, group: int, rms_gamma=None, rms_
                                    _ptr(residual), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream)),
            "e0m4_matmul_fused")
     return out
+
+
+def e0m4_kv_append(cache, new_rows, position_ids, stream=None):
+    """cache [max_seq, row] fp16 is updated in place: cache[position_ids[i]] = new_rows[i].  new_rows may be a
+    column slice of a wider matrix (last dimension contiguous); position_ids is an int64 device tensor."""
+    max_seq, row = cache.shape
+    n_new = new_rows.shape[0]
+    if cache.dtype != torch.float16 or new_rows.dtype != torch.float16 or position_ids.dtype != torch.int64:
+        raise TypeError("e0m4_kv_append: cache and new_rows must be float16, position_ids int64")
+    if not cache.is_contiguous() or new_rows.shape[1] != row or new_rows.stride(1) != 1 or \
+            not position_ids.is_contiguous() or position_ids.numel() != n_new:
+        raise ValueError("e0m4_kv_append: bad shapes or strides")
+    _check(lib().e0m4_kv_append(_ptr(cache), max_seq, row, _ptr(new_rows), n_new, new_rows.stride(0),
+                                _ptr(position_ids), _stream(stream)), "e0m4_kv_append")
+    return cache
 
 
 # ---- INT4 twin (see include/e0m4.h) ------------------------------------------------------------

@@ -293,4 +293,17 @@ int e0m4_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
                              workspace_bytes - nb, st);
 }
 
+int e0m4_kv_append(void* cache, int64_t max_seq, int64_t row_elems, const void* new_rows, int64_t n_new,
+                   int64_t new_ld, const void* position_ids, void* stream)
+{
+    if (max_seq < 0 || row_elems < 0 || n_new < 0 || (row_elems % 8) != 0 || (new_ld % 8) != 0 || new_ld < row_elems)
+        return E0M4_ERR_SHAPE;
+    if (row_elems > (int64_t)1 << 31 || max_seq > (int64_t)1 << 40 || n_new > (int64_t)1 << 31) return E0M4_ERR_SHAPE;
+    if (n_new == 0 || row_elems == 0 || max_seq == 0) return E0M4_OK;
+    if (!cache || !new_rows || !position_ids) return E0M4_ERR_NULL;
+    if (!aligned16(cache) || !aligned16(new_rows) || (reinterpret_cast<uintptr_t>(position_ids) & 7u) != 0)
+        return E0M4_ERR_ALIGN;
+    return launch_kv_append(cache, max_seq, row_elems, new_rows, n_new, new_ld, position_ids, (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -144,3 +144,21 @@ def test_fused_matmul_validation_and_workspace(L):
     assert w(1024, 4096, 4096, 128, 0, NONE) == L.e0m4_workspace_bytes(1024, 4096, 4096, 128)
     assert w(1024, 4096, 4096, 128, 1, NONE) == 1024 * 4096 * 2 + L.e0m4_workspace_bytes(1024, 4096, 4096, 128)
     assert w(1024, 4096, 4096, 128, 1, 5) == 0
+
+
+def test_kv_append_validation(L):
+    L.e0m4_kv_append.restype = ctypes.c_int
+    L.e0m4_kv_append.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                 ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+    p, odd, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004), ctypes.c_void_p(0)
+    ERR_NULL, ERR_SHAPE, ERR_ALIGN = -1, -2, -4
+    f = L.e0m4_kv_append
+    assert f(p, 16, 12, p, 1, 16, p, null) == ERR_SHAPE         # row not a multiple of 8
+    assert f(p, 16, 16, p, 1, 20, p, null) == ERR_SHAPE         # source stride not a multiple of 8
+    assert f(p, 16, 16, p, 1, 8, p, null) == ERR_SHAPE          # source stride shorter than a row
+    assert f(p, -1, 16, p, 1, 16, p, null) == ERR_SHAPE
+    assert f(null, 16, 16, p, 1, 16, p, null) == ERR_NULL
+    assert f(p, 16, 16, p, 1, 16, null, null) == ERR_NULL
+    assert f(p, 16, 16, ctypes.c_void_p(0x1008), 1, 16, p, null) == ERR_ALIGN
+    assert f(p, 16, 16, p, 1, 16, odd, null) == ERR_ALIGN       # position_ids are 8-byte integers
+    assert f(null, 16, 16, null, 0, 16, null, null) == 0        # nothing to append
