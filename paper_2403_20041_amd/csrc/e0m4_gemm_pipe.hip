@@ -1,6 +1,7 @@
-// Software-pipelined 256 x 256 tile of the prefill GEMM (paper: section "Operator and lagging
-// optimizations", matrix-matrix product; dequantisation of section "E0M4 FP4 quantization" fused
-// in registers).
+// Software-pipelined tile of the prefill GEMM (paper: section "Operator and lagging optimizations",
+// matrix-matrix product; dequantisation of section "E0M4 FP4 quantization" fused in registers), built
+// for 256 x 256 outputs (M above 384) and for 128 x 128 outputs (M up to 384, four wavefronts 2 x 2 of
+// 64 x 64 each, two or three workgroups per compute unit).  The description is that of the large tile.
 //
 // Eight wavefronts (2 x 4, two per SIMD) share the tile, 128 x 64 outputs and 128 fp32 accumulator
 // registers per lane each, which leaves two wavefronts per SIMD at most: little but a wavefront's own
@@ -29,9 +30,8 @@ namespace e0m4 {
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BK = 64;
 constexpr int kRowBytes = BK * 2;
-constexpr int kStageBytes = BM * kRowBytes;             // 32 KiB
 constexpr int kStages = 3;
 constexpr int kNumXcd = 8;
 
@@ -59,13 +59,18 @@ struct PipeFusion {
     int64_t n_half;                                     // N / 2 (gated epilogue)
 };
 
-template <int G, int WGM, int WGN, bool FUSED>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
+//
+// The tile is BM x BN: 256 x 256 with 2 x 4 wavefronts for large M; 128 x 128 with 2 x 2 wavefronts (two
+// workgroups per compute unit) for M up to a few hundred, where the large tile would compute rows that
+// do not exist and leave most compute units without a tile.
+template <int G, int WGM, int WGN, bool FUSED, int BM, int BN>
+__global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
                                                              const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                              half_t* __restrict__ Y, int m_tiles, int n_tiles,
                                                              int splits, float* __restrict__ partial, PipeFusion fu)
 {
     constexpr int kThreads = 64 * WGM * WGN;
+    constexpr int kStageBytes = BM * kRowBytes;
     constexpr int TM = BM / (32 * WGM), TN = BN / (32 * WGN);      // 32x32 MFMA blocks per wavefront
     constexpr int RP = kThreads / 8;                    // rows covered by one activation loader pass
     constexpr int PA = BM / RP;                         // activation loader passes
@@ -211,7 +216,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_pipe_kernel(const half_t*
         for (int i = 0; i < kMfma; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // one MFMA
             if (i < TM) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // one LDS fragment read
-            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);          // vector ALU
+            __builtin_amdgcn_sched_group_barrier(0x002, kMfma >= 8 ? 5 : 9, 0);     // vector ALU
             if (i < decltype(dsw)::value) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);    // LDS write
             if (i < decltype(vmem)::value) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // global load
         }
@@ -416,31 +421,54 @@ constexpr int kComputeUnits = 256;
 constexpr int kMinPairsPerSplit = 4;
 constexpr int kMaxSplits = 8;
 
-int choose_splits(int64_t tiles, int64_t K)
+// The tile a problem gets: 128 x 128 (two workgroups per compute unit) when M is at most kMidMaxM rows,
+// else 256 x 256.  (gemm_variant 2 forces the large tile, 3 the small one.)  Measured on the ChatGLM2-6B
+// shapes: at M = 128 the small tile takes 21-45 us where the large one takes 28-65, at M = 256 they are
+// within 10 %, at M = 512 the large tile is up to 1.3x faster; between 257 and 384 rows the large tile
+// would compute a quarter to a half of its rows for nothing.
+constexpr int kMidMaxM = 384;
+struct PipeTile {
+    int bm, bn;
+    int slots;                                          // work items wanted before K is split no further
+};
+
+PipeTile pipe_tile(int64_t M)
+{
+    const int v = knob("gemm_variant");
+    const bool mid = v == 3 || (v != 2 && M <= kMidMaxM);
+    return mid ? PipeTile{128, 128, kComputeUnits + kComputeUnits / 2} : PipeTile{256, 256, kComputeUnits};
+}
+
+int choose_splits(int64_t tiles, int64_t K, int slots)
 {
     const int forced = knob("gemm_splits");
     const int64_t pairs = K / (2 * BK);
     int64_t s = forced > 0 ? std::min<int64_t>(forced, pairs)                   // tests: down to one pair per split
-                           : std::min<int64_t>(kComputeUnits / tiles, pairs / kMinPairsPerSplit);
+                           : std::min<int64_t>(slots / tiles, pairs / kMinPairsPerSplit);
     s = std::min<int64_t>(s, kMaxSplits);
     return (int)std::max<int64_t>(s, 1);
 }
 
 size_t partial_bytes(int splits, int64_t M, int64_t N) { return (size_t)splits * (size_t)M * (size_t)N * sizeof(float); }
 
-int64_t pipe_n_tiles(int64_t N, bool swiglu) { return swiglu ? (N / 2 + BN / 2 - 1) / (BN / 2) : (N + BN - 1) / BN; }
+int64_t pipe_tiles(const PipeTile& t, int64_t M, int64_t N, bool swiglu)
+{
+    const int64_t n_tiles = swiglu ? (N / 2 + t.bn / 2 - 1) / (t.bn / 2) : (N + t.bn - 1) / t.bn;
+    return ((M + t.bm - 1) / t.bm) * n_tiles;
+}
 
-template <int G, int WGM, int WGN, bool FUSED>
+template <int G, int WGM, int WGN, bool FUSED, int BM, int BN>
 int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, void* workspace,
-                size_t workspace_bytes, hipStream_t stream, const Fusion& f = Fusion{})
+                size_t workspace_bytes, hipStream_t stream, const Fusion& f)
 {
     PipeFusion fu;
     fu.residual = static_cast<const half_t*>(f.residual);
     fu.swiglu = f.swiglu ? 1 : 0;
     fu.n_half = N / 2;
-    const int64_t m_tiles = (M + BM - 1) / BM, n_tiles = pipe_n_tiles(N, f.swiglu);
-    const int64_t tiles = m_tiles * n_tiles;
-    const int splits = choose_splits(tiles, K);
+    const PipeTile shape = pipe_tile(M);
+    const int64_t m_tiles = (M + BM - 1) / BM;
+    const int64_t tiles = pipe_tiles(shape, M, N, f.swiglu), n_tiles = tiles / m_tiles;
+    const int splits = choose_splits(tiles, K, shape.slots);
     if (tiles * splits > 0x3fffffffLL) return E0M4_ERR_SHAPE;
     const int total = (int)(tiles * splits);
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
@@ -449,16 +477,16 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
         if (workspace == nullptr || workspace_bytes < partial_bytes(splits, M, N)) return E0M4_ERR_WORKSPACE;
         partial = static_cast<float*>(workspace);
     }
-    constexpr size_t lds = (size_t)kStages * kStageBytes;          // 96 KiB: above the default limit
+    constexpr size_t lds = (size_t)kStages * BM * kRowBytes;       // 96 KiB for the large tile: above the default limit
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_pipe_kernel<G, WGM, WGN, FUSED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return record_hip_error(e);
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN, FUSED>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(64 * WGM * WGN),
-                       lds, stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial, fu);
+    hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN>), dim3((unsigned)(per_xcd * kNumXcd)),
+                       dim3(64 * WGM * WGN), lds, stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial, fu);
     int rc = check_launch();
     if (rc != E0M4_OK || splits == 1) return rc;
     if (FUSED) {
@@ -487,18 +515,33 @@ bool gemm_pipe_supported(int64_t K) { return K >= 128 && (K % (2 * BK)) == 0; }
 
 size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu)
 {
-    const int64_t tiles = ((M + BM - 1) / BM) * pipe_n_tiles(N, swiglu);
+    const PipeTile shape = pipe_tile(M);
+    const int64_t tiles = pipe_tiles(shape, M, N, swiglu);
     if (tiles == 0 || !gemm_pipe_supported(K)) return 0;
-    const int splits = choose_splits(tiles, K);
+    const int splits = choose_splits(tiles, K, shape.slots);
     return splits > 1 ? partial_bytes(splits, M, N) : 0;
 }
 
 int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K, bool swiglu)
 {
-    const int64_t tiles = ((M + BM - 1) / BM) * pipe_n_tiles(N, swiglu);
+    const PipeTile shape = pipe_tile(M);
+    const int64_t tiles = pipe_tiles(shape, M, N, swiglu);
     if (tiles == 0 || !gemm_pipe_supported(K)) return 0;
-    return tiles * choose_splits(tiles, K);
+    return tiles * choose_splits(tiles, K, shape.slots);
 }
+
+namespace {
+
+template <int G, bool FUSED>
+int launch_pipe_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, void* workspace,
+                     size_t workspace_bytes, hipStream_t stream, const Fusion& f)
+{
+    if (pipe_tile(M).bm == 128)
+        return launch_pipe<G, 2, 2, FUSED, 128, 128>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+    return launch_pipe<G, 2, 4, FUSED, 256, 256>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+}
+
+}  // namespace
 
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                      void* workspace, size_t workspace_bytes, hipStream_t stream)
@@ -507,9 +550,9 @@ int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, in
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     switch (group) {
-        case 32: return launch_pipe<32, 2, 4, false>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
-        case 64: return launch_pipe<64, 2, 4, false>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
-        case 128: return launch_pipe<128, 2, 4, false>(x, M, c, N, K, y, workspace, workspace_bytes, stream);
+        case 32: return launch_pipe_tile<32, false>(x, M, c, N, K, y, workspace, workspace_bytes, stream, Fusion{});
+        case 64: return launch_pipe_tile<64, false>(x, M, c, N, K, y, workspace, workspace_bytes, stream, Fusion{});
+        case 128: return launch_pipe_tile<128, false>(x, M, c, N, K, y, workspace, workspace_bytes, stream, Fusion{});
         default: return E0M4_ERR_GROUP;
     }
 }
@@ -526,9 +569,9 @@ int launch_gemm_pipe_fused(const Fusion& f, const void* X, int64_t M, const void
         if (N % (2 * kBlockRows) != 0 || gated_half_bytes(N, K, group) > kMaxHalfBytes) return E0M4_ERR_SHAPE;
     }
     switch (group) {
-        case 32: return launch_pipe<32, 2, 4, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
-        case 64: return launch_pipe<64, 2, 4, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
-        case 128: return launch_pipe<128, 2, 4, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+        case 32: return launch_pipe_tile<32, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+        case 64: return launch_pipe_tile<64, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+        case 128: return launch_pipe_tile<128, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
         default: return E0M4_ERR_GROUP;
     }
 }

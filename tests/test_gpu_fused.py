@@ -177,7 +177,8 @@ def test_nothing_selected_equals_the_plain_matmul(e0m4, oracle):
         assert np.all(np.abs(y0.cpu().numpy().astype(np.float64) - Yref.astype(np.float64)) <= 1e-2 * np.maximum(1, absdot))
 
 
-@pytest.mark.parametrize("variant", [1, 2])           # 1: small-tile kernel, 2: pipelined 256 x 256 kernel
+# 1: small-tile kernel, 2: pipelined kernel with 256 x 256 tiles, 3: pipelined kernel with 128 x 128 tiles
+@pytest.mark.parametrize("variant", [1, 2, 3])
 @pytest.mark.parametrize("norm,swiglu,res", COMBOS)
 def test_gemm_kernels(e0m4, oracle, variant, norm, swiglu, res):
     e0m4.e0m4_set_knob("gemm_variant", variant)
@@ -190,10 +191,11 @@ def test_gemm_kernels(e0m4, oracle, variant, norm, swiglu, res):
         e0m4.e0m4_set_knob("gemm_variant", 0)
 
 
+@pytest.mark.parametrize("variant", [2, 3])
 @pytest.mark.parametrize("splits", [2, 3, 8])
 @pytest.mark.parametrize("norm,swiglu,res", COMBOS)
-def test_gemm_split_along_k(e0m4, oracle, splits, norm, swiglu, res):
-    e0m4.e0m4_set_knob("gemm_variant", 2)
+def test_gemm_split_along_k(e0m4, oracle, variant, splits, norm, swiglu, res):
+    e0m4.e0m4_set_knob("gemm_variant", variant)
     e0m4.e0m4_set_knob("gemm_splits", splits)
     try:
         run_fused(e0m4, oracle, 257, 704, 1024, 128, seed=370 + splits, norm=norm, swiglu=swiglu, res=res)
