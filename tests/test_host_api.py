@@ -50,7 +50,10 @@ def test_size_functions(L):
     assert L.e0m4_workspace_bytes(1, 4096, 4096, 128) == 0  # small M: partial sums never leave the chip
     assert L.e0m4_workspace_bytes(8, 151936, 4096, 128) == 0
     # 64 tiles of 256 x 256 on 256 compute units: 4 K splits, one fp32 [M, N] slab each
+    assert L.e0m4_workspace_bytes(1024, 4096, 13696, 128) == 4 * 1024 * 4096 * 4
     assert L.e0m4_workspace_bytes(1024, 4096, 4096, 128) == 4 * 1024 * 4096 * 4
+    # 128 rows: 36 tiles of 128 x 128, 8 K splits
+    assert L.e0m4_workspace_bytes(128, 4608, 4096, 128) == 8 * 128 * 4608 * 4
     assert L.e0m4_workspace_bytes(2048, 27392, 5120, 128) == 0          # enough tiles: no split
     assert L.e0m4_workspace_bytes(1024, 4096, 4160, 64) == 0            # K not a multiple of 128: other kernel
 
@@ -141,8 +144,8 @@ def test_fused_matmul_validation_and_workspace(L):
     assert w(8, 4096, 16384, 128, 1, SWIGLU) > 0                # X does not fit the LDS in one piece: GEMM path
     assert w(1024, 27392, 4096, 128, 1, SWIGLU) == 1024 * 4096 * 2         # normalised X; enough tiles, no K split
     assert w(1024, 27392, 4096, 128, 0, SWIGLU) == 0
-    assert w(1024, 4096, 4096, 128, 0, NONE) == L.e0m4_workspace_bytes(1024, 4096, 4096, 128)
-    assert w(1024, 4096, 4096, 128, 1, NONE) == 1024 * 4096 * 2 + L.e0m4_workspace_bytes(1024, 4096, 4096, 128)
+    assert w(1024, 4096, 13696, 128, 0, NONE) == L.e0m4_workspace_bytes(1024, 4096, 13696, 128) > 0
+    assert w(1024, 4096, 13696, 128, 1, NONE) == 1024 * 13696 * 2 + L.e0m4_workspace_bytes(1024, 4096, 13696, 128)
     assert w(1024, 4096, 4096, 128, 1, 5) == 0
 
 
