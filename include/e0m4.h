@@ -116,7 +116,7 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  * accumulation is fp32; Y is rounded once to fp16.
  *   M <= 8 : HBM-bound GEMV path (a workgroup owns whole blocks of 16 output
  *            rows over all of K; no partial sums leave the compute unit).
- *   3 <= M <= 16, group 128, M rows of X fit the LDS of a compute unit
+ *   2 <= M <= 16, group 128, M rows of X fit the LDS of a compute unit
  *            (about M * K * 2 <= 140 KiB): same decomposition, the dot
  *            products run on the matrix cores so the cost stays near the
  *            weight stream for every such M.

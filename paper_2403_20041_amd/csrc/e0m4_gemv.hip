@@ -226,6 +226,20 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
             if ((pc & 3) == 0) sxs[m * (seg_k / kCodesPerChunk) + (pc >> 2)] = make_float2(s, 30.f * sl);
         }
     };
+    // stage pieces start, start + kThreads, ... : loads in batches of four, issued together and then
+    // consumed, so that their latencies overlap
+    auto stage_from = [&](int start, int kb_first) {
+        for (int base = start; base < M * pieces; base += 4 * kThreads) {
+            half8_t vb[4], gb[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                vb[u] = x_piece(base + u * kThreads, kb_first);
+                gb[u] = g_piece(base + u * kThreads, kb_first);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x_store(base + u * kThreads, vb[u], gb[u]);
+        }
+    };
     // Two pieces of X per thread are requested before the weights, so that they are not queued behind
     // them (loads return in order; requesting the weights first was measured slower).  What two pieces
     // per thread do not cover (large M * K) is staged right away.
@@ -245,8 +259,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
         const int64_t n = (rb0 + u) * kBlockRows + rr;
         if (u < units && n < fu.n_out) res_early = (float)fu.residual[(int64_t)m * fu.n_out + n];
     }
-    if (!normed)
-        for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads) x_store(idx, x_piece(idx, 0), zero8);
+    if (!normed) stage_from(t + kEarlyX * kThreads, 0);
 
     // ---- the work item in flight: four code blocks and the parameter words
     uint4 c[kSuper];
@@ -323,8 +336,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
             for (int w = 0; w < W; ++w) v += part[w * M + m];
             rs[m] = 1.f / sqrtf(v / (float)K + fu.eps);
         }
-        for (int idx = t + kEarlyX * kThreads; idx < M * pieces; idx += kThreads)
-            x_store(idx, x_piece(idx, 0), g_piece(idx, 0));
+        stage_from(t + kEarlyX * kThreads, 0);
     }
 
     float acc[M];
@@ -350,8 +362,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
             for (int e = 0; e < kEarlyX; ++e) x_store(t + e * kThreads, xearly[e], gearly[e]);
         } else {
             __syncthreads();                            // everyone is done with the previous segment's activations
-            for (int idx = t; idx < M * pieces; idx += kThreads)
-                x_store(idx, x_piece(idx, seg0 * kSuper), g_piece(idx, seg0 * kSuper));
+            stage_from(t, seg0 * kSuper);
         }
         __syncthreads();
         const int seg_end = seg0 + seg_items;

@@ -1,4 +1,4 @@
-// Small-batch decode path of e0m4_matmul: Y[M,N] = X[M,K] * dequant(packed)^T for 3 <= M <= 16 and
+// Small-batch decode path of e0m4_matmul: Y[M,N] = X[M,K] * dequant(packed)^T for 2 <= M <= 16 and
 // group size 128.  Paper: section "Operator and lagging optimizations" (vector-matrix product of the
 // decoding stage, bound by memory bandwidth) with the dequantisation of section "E0M4 FP4
 // quantization" fused in registers.
@@ -17,7 +17,8 @@
 // 2 + c/128 (pairs 1 and 2) go to separate MFMAs and accumulators, and are folded back with
 //     sum x*(2 + c/8) = 16 * sum x*(2 + c/128) - 30 * sum x       (over the k of pairs 1 and 2).
 // The activation operand comes from LDS, where X is staged once per workgroup in the order the
-// MFMAs consume it (one 16-byte unit per MFMA and lane), with the two sums per (row of X, block).
+// MFMAs consume it (one 16-byte unit per MFMA and lane); the two sums per (row of X, block) that the
+// factored form needs are MFMAs of the same operands with an all-ones weight operand.
 // One group of 128 k is one block, so the group's affine map  y += scale * (a - bias * sum x)  is
 // applied once per block on the MFMA result; that is why this kernel needs group size 128.
 #include "e0m4_device.h"
@@ -33,12 +34,11 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kSuper = 4;                       // weight blocks (of 128 k) per work item
 constexpr int kG = 128;                         // group size: one group per block
-constexpr int kMinM = 3;                         // below, the vector kernel is as fast or faster
+constexpr int kMinM = 2;                         // a single row is faster on the vector kernel
 constexpr int kMaxM = 16;
 constexpr int kPW = block_param_words(kG);      // 16 parameter words per block
 constexpr int kXBlockBytes = kBlockK * 2;       // one row of X, one block: 256 bytes
 constexpr int kRowPadBytes = 16;                // keeps the 16 rows of X in different LDS bank groups
-constexpr int kSumBytesPerBlock = 2 * kMaxM * 4;        // (sum x, 30 * sum of x over pairs 1 and 2) per row of X
 constexpr int kLdsLimitBytes = 156 * 1024;      // of the 160 KiB of a compute unit
 constexpr int kTargetWorkgroups = 256;          // one workgroup per compute unit
 
@@ -54,7 +54,7 @@ constexpr int kNormBytes = (16 + 1) * kMaxM * 4;        // rms-norm: per-wavefro
 
 size_t lds_need(int64_t M, int64_t nkb, int waves)
 {
-    return (size_t)M * (nkb * kXBlockBytes + kRowPadBytes) + (size_t)nkb * kSumBytesPerBlock +
+    return (size_t)M * (nkb * kXBlockBytes + kRowPadBytes) +
            2 * (size_t)waves * kMaxM * kBlockRows * sizeof(float) + kNormBytes;
 }
 
@@ -64,7 +64,10 @@ __device__ inline int x_unit_off(int q, int w, int hl) { return ((q * 4 + (w >> 
 
 // FUSED adds the operators of GemvFusion (e0m4_device.h): rms-norm while X is staged, the gated epilogue
 // (the workgroup owns pairs of a gate and an up row block and writes silu(gate) * up), the residual add.
-template <int W, bool FUSED>
+// XREG: the wavefront count is a multiple of the work items per row block, so a wavefront meets the same
+// four k blocks in every row block and keeps their activation operands in registers (64 per lane)
+// instead of reading them from LDS for every weight block.
+template <int W, bool FUSED, bool XREG>
 __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restrict__ X, int M,
                                                            const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                            half_t* __restrict__ Y, int step_slots, int step_item,
@@ -77,8 +80,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     const int nsi = (nkb + kSuper - 1) / kSuper;
     const int row_stride = nkb * kXBlockBytes + kRowPadBytes;
     unsigned char* xs = smem;                                                   // [M] rows of X in MFMA order
-    float* sums = reinterpret_cast<float*>(smem + (size_t)M * row_stride);      // [nkb][2][16]
-    float* red = sums + (size_t)nkb * 2 * kMaxM;                                // [2][W][16 m][16 n]
+    float* red = reinterpret_cast<float*>(smem + (size_t)M * row_stride);       // [2][W][16 m][16 n]
     float* norm_part = red + 2 * W * kMaxM * kBlockRows;                        // [W][16] sums of squares, then [16] row scales
 
     const int t = threadIdx.x;
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     for (int j = 0; j < kSuper; ++j) fetch_code(j, slot, si);
 
     // ---- stage X: thread idx handles the 8 elements k = 8*pc..8*pc+7 of row m; 16 consecutive threads
-    // cover one block of one row and add up its two sums
+    // cover one block of one row
     const int pieces = nkb * (kBlockK / 8);
     const bool normed = FUSED && fu.gamma != nullptr;
     if (normed) {
@@ -148,21 +150,29 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
         float ss[kMaxM];
 #pragma unroll
         for (int m = 0; m < kMaxM; ++m) ss[m] = 0.f;
-        for (int base = 0; base < M * pieces; base += kThreads) {
-            const int idx = base + t;
-            const int m = idx / pieces, pc = idx - m * pieces;
-            const int64_t k = (int64_t)pc * 8;
-            float d = 0.f;
-            if (idx < M * pieces && k < K) {
-                const half8_t v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+        for (int base = 0; base < M * pieces; base += 4 * kThreads) {
+            half8_t vb[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {               // four loads in flight
+                const int idx = base + u * kThreads + t;
+                const int m = idx / pieces, pc = idx - m * pieces;
+                const int64_t k = (int64_t)pc * 8;
+                const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+                vb[u] = zero8;
+                if (idx < M * pieces && k < K) vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int m = (base + u * kThreads + t) / pieces;      // beyond the last row: adds zeros
+                const half8_t v = vb[u];
                 const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
-                d = __builtin_amdgcn_fdot2(x0, x0, 0.f, false);
+                float d = __builtin_amdgcn_fdot2(x0, x0, 0.f, false);
                 d = __builtin_amdgcn_fdot2(x1, x1, d, false);
                 d = __builtin_amdgcn_fdot2(x2, x2, d, false);
                 d = __builtin_amdgcn_fdot2(x3, x3, d, false);
-            }
 #pragma unroll
-            for (int mm = 0; mm < kMaxM; ++mm) ss[mm] += mm == m ? d : 0.f;
+                for (int mm = 0; mm < kMaxM; ++mm) ss[mm] += mm == m ? d : 0.f;
+            }
         }
 #pragma unroll
         for (int m = 0; m < kMaxM; ++m) {
@@ -181,40 +191,39 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
         if (t < kMaxM) norm_part[t] = 1.f / sqrtf(tot / (float)K + fu.eps);
         __syncthreads();
     }
-    for (int base = 0; base < M * pieces; base += kThreads) {
-        const int idx = base + t;
-        const int m = idx / pieces, pc = idx - m * pieces;
-        const int64_t k = (int64_t)pc * 8;
-        half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (idx < M * pieces && k < K) {
-            v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
-            if (normed) {                               // (x * row scale) * gamma, one rounding
-                const half8_t gv = *reinterpret_cast<const half8_t*>(fu.gamma + k);
-                const float r = norm_part[m];
+    // (loads in batches of kStageBatch: issued together, then consumed, so that their latencies overlap)
+    constexpr int kStageBatch = 4;
+    for (int base = 0; base < M * pieces; base += kStageBatch * kThreads) {
+        half8_t vb[kStageBatch], gb[kStageBatch];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) v[i] = (half_t)(((float)v[i] * r) * (float)gv[i]);
+        for (int u = 0; u < kStageBatch; ++u) {
+            const int idx = base + u * kThreads + t;
+            const int m = idx / pieces, pc = idx - m * pieces;
+            const int64_t k = (int64_t)pc * 8;
+            const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+            vb[u] = zero8;
+            gb[u] = zero8;
+            if (idx < M * pieces && k < K) {
+                vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+                if (normed) gb[u] = *reinterpret_cast<const half8_t*>(fu.gamma + k);
             }
         }
-        const half2_t ones = {(half_t)1.f, (half_t)1.f};
-        const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
-        float sl = __builtin_amdgcn_fdot2(x1, ones, 0.f, false);
-        sl = __builtin_amdgcn_fdot2(x2, ones, sl, false);
-        float s = __builtin_amdgcn_fdot2(x0, ones, sl, false);
-        s = __builtin_amdgcn_fdot2(x3, ones, s, false);
 #pragma unroll
-        for (int d = 1; d < 16; d <<= 1) {
-            s += __shfl_xor(s, d);
-            sl += __shfl_xor(sl, d);
-        }
-        if (idx < M * pieces) {
-            const int kb = pc >> 4, q = (pc >> 2) & 3, w = pc & 3;
-            unsigned char* blk = xs + (size_t)m * row_stride + kb * kXBlockBytes;
-            const half4_t hpart = {v[0], v[1], v[6], v[7]}, lpart = {v[2], v[3], v[4], v[5]};
-            *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 0)) = hpart;
-            *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 1)) = lpart;
-            if ((pc & 15) == 0) {
-                sums[(kb * 2 + 0) * kMaxM + m] = s;
-                sums[(kb * 2 + 1) * kMaxM + m] = 30.f * sl;
+        for (int u = 0; u < kStageBatch; ++u) {
+            const int idx = base + u * kThreads + t;
+            const int m = idx / pieces, pc = idx - m * pieces;
+            half8_t v = vb[u];
+            if (normed && idx < M * pieces) {           // (x * row scale) * gamma, one rounding
+                const float r = norm_part[m];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = (half_t)(((float)v[i] * r) * (float)gb[u][i]);
+            }
+            if (idx < M * pieces) {
+                const int kb = pc >> 4, q = (pc >> 2) & 3, w = pc & 3;
+                unsigned char* blk = xs + (size_t)m * row_stride + kb * kXBlockBytes;
+                const half4_t hpart = {v[0], v[1], v[6], v[7]}, lpart = {v[2], v[3], v[4], v[5]};
+                *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 0)) = hpart;
+                *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 1)) = lpart;
             }
         }
     }
@@ -224,7 +233,39 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     // results are never stored), k-group l/16
     const unsigned char* x_lane = xs + (size_t)min(n_l, M - 1) * row_stride + g_l * 64;
 
+    half8_t xreg_h[XREG ? kSuper : 1][2], xreg_l[XREG ? kSuper : 1][2];
+    if (XREG) {
+#pragma unroll
+        for (int j = 0; j < kSuper; ++j) {
+            const unsigned char* xb = x_lane + (size_t)min(si * kSuper + j, nkb - 1) * kXBlockBytes;
+#pragma unroll
+            for (int wp = 0; wp < 2; ++wp) {
+                xreg_h[j][wp] = *reinterpret_cast<const half8_t*>(xb + wp * 32);
+                xreg_l[j][wp] = *reinterpret_cast<const half8_t*>(xb + wp * 32 + 16);
+            }
+        }
+    }
+
+    // The two sums of a block's activations per row of X (all of them, and those that meet the code pairs
+    // read at 1/128 scale) come from the matrix cores as well: products with an all-ones weight operand.
     const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    const half8_t ones8 = {(half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f};
+    auto block_sums = [&](const half8_t (&xh)[2], const half8_t (&xl)[2], floatx4& sx, floatx4& sx30) {
+        floatx4 sh = zero4, sl = zero4;
+#pragma unroll
+        for (int wp = 0; wp < 2; ++wp) {
+            sh = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh[wp], ones8, sh, 0, 0, 0);
+            sl = __builtin_amdgcn_mfma_f32_16x16x32_f16(xl[wp], ones8, sl, 0, 0, 0);
+        }
+        sx = sh + sl;
+        sx30 = 30.f * sl;
+    };
+    floatx4 sxr[XREG ? kSuper : 1], sx30r[XREG ? kSuper : 1];
+    if (XREG) {
+#pragma unroll
+        for (int j = 0; j < kSuper; ++j) block_sums(xreg_h[j], xreg_l[j], sxr[j], sx30r[j]);
+    }
+
     for (int s_rb = 0; s_rb < n_rb; ++s_rb) {
         floatx4 ysum = zero4;                           // this wavefront's share of Y[4*g_l .. 4*g_l+3][row n_l] of row block s_rb
         while (slot == s_rb) {
@@ -235,7 +276,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
             fetch_params(nslot, nitem);
 #pragma unroll
             for (int j = 0; j < kSuper; ++j) {
-                const int kb = si * kSuper + j;         // may lie beyond K in the last item: X and sums are zero there
+                const int kb = si * kSuper + j;         // may lie beyond K in the last item: such a block is left out below
                 const float sc = (float)param_scale(pwj[j]);
                 const float bi = (float)param_bias(pwj[j]);
                 const uint32_t words[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
@@ -245,10 +286,15 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
                 fetch_code(j, nslot, nitem);            // the block's registers are free: request the next item's
                 floatx4 acc_h = zero4, acc_l = zero4;
                 const unsigned char* xb = x_lane + (size_t)min(kb, nkb - 1) * kXBlockBytes;
+                half8_t xh2[2], xl2[2];
 #pragma unroll
                 for (int wp = 0; wp < 2; ++wp) {
-                    const half8_t xh = *reinterpret_cast<const half8_t*>(xb + wp * 32);
-                    const half8_t xl = *reinterpret_cast<const half8_t*>(xb + wp * 32 + 16);
+                    xh2[wp] = XREG ? xreg_h[XREG ? j : 0][wp] : *reinterpret_cast<const half8_t*>(xb + wp * 32);
+                    xl2[wp] = XREG ? xreg_l[XREG ? j : 0][wp] : *reinterpret_cast<const half8_t*>(xb + wp * 32 + 16);
+                }
+#pragma unroll
+                for (int wp = 0; wp < 2; ++wp) {
+                    const half8_t xh = xh2[wp], xl = xl2[wp];
                     const half2_t* w0 = p[2 * wp];
                     const half2_t* w1 = p[2 * wp + 1];
                     const half8_t wh = {w0[0][0], w0[0][1], w0[3][0], w0[3][1], w1[0][0], w1[0][1], w1[3][0], w1[3][1]};
@@ -257,8 +303,13 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
                     acc_l = __builtin_amdgcn_mfma_f32_16x16x32_f16(xl, wl, acc_l, 0, 0, 0);
                 }
                 if (kb < nkb) {
-                    const floatx4 sx = *reinterpret_cast<const floatx4*>(&sums[(kb * 2 + 0) * kMaxM + 4 * g_l]);
-                    const floatx4 sx30 = *reinterpret_cast<const floatx4*>(&sums[(kb * 2 + 1) * kMaxM + 4 * g_l]);
+                    floatx4 sx, sx30;
+                    if (XREG) {
+                        sx = sxr[XREG ? j : 0];
+                        sx30 = sx30r[XREG ? j : 0];
+                    } else {
+                        block_sums(xh2, xl2, sx, sx30);
+                    }
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
                         ysum[r] += sc * ((acc_h[r] + 16.f * acc_l[r] - sx30[r]) - bi * sx[r]);
@@ -334,21 +385,32 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1)
     return true;
 }
 
-template <int W, bool FUSED>
-int launch_mfma(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
-                hipStream_t stream, const GemvFusion& fu = GemvFusion{})
+template <int W, bool FUSED, bool XREG>
+int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                  hipStream_t stream, const GemvFusion& fu)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED, XREG>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimitBytes);
         if (e != hipSuccess) return record_hip_error(e);
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
+    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
                        static_cast<const half_t*>(X), (int)M, static_cast<const uint4*>(packed), N, K,
                        static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, fu);
     return check_launch();
+}
+
+// Activations in registers when a wavefront always meets the same k blocks (step_item == 0); the kernel
+// then needs about 125 registers per lane, which 16 wavefronts still allow.
+template <int W, bool FUSED>
+int launch_mfma(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                hipStream_t stream, const GemvFusion& fu = GemvFusion{})
+{
+    if (p.step_item == 0 && knob("gemv_mfma") != 2)
+        return launch_mfma_x<W, FUSED, true>(p, X, M, packed, N, K, Y, stream, fu);
+    return launch_mfma_x<W, FUSED, false>(p, X, M, packed, N, K, Y, stream, fu);
 }
 
 }  // namespace

@@ -44,7 +44,7 @@ int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t
 bool gemv_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K);
 int launch_gemv_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group,
                       void* Y, hipStream_t stream);
-// Small-batch path on the matrix cores: 3 <= M <= 16, group 128, X must fit the LDS of one compute unit.
+// Small-batch path on the matrix cores: 2 <= M <= 16, group 128, X must fit the LDS of one compute unit.
 bool gemv_mfma_supported(int64_t M, int64_t N, int64_t K, int group);
 int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream);
 bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K, int group);

@@ -102,7 +102,7 @@ def test_decode_kernel(e0m4, oracle, M, norm, swiglu, res):
 @pytest.mark.parametrize("norm,swiglu,res", COMBOS)
 @pytest.mark.parametrize("M", [2, 5, 8])
 def test_decode_vector_kernel_for_small_batches(e0m4, oracle, M, norm, swiglu, res):
-    e0m4.e0m4_set_knob("gemv_mfma", 1)                  # group 128 would take the matrix-core kernel for M >= 3
+    e0m4.e0m4_set_knob("gemv_mfma", 1)                  # group 128 would take the matrix-core kernel for M >= 2
     try:
         run_fused(e0m4, oracle, M, 320, 1152, 128, seed=305 + M, norm=norm, swiglu=swiglu, res=res)
     finally:

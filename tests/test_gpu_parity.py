@@ -222,7 +222,7 @@ def test_gemv_ragged_last_work_item(e0m4, oracle, M):
 
 @pytest.mark.parametrize("M", [2, 3, 4, 5, 7, 8, 9, 12, 15, 16])
 def test_small_batch_matrix_core_kernel(e0m4, oracle, M):
-    # group 128 and 3 <= M <= 16: the MFMA small-batch kernel (M = 2 stays on the vector kernel)
+    # group 128 and 2 <= M <= 16: the MFMA small-batch kernel
     run_matmul_case(e0m4, oracle, M, 200, 1152, 128, seed=130 + M)              # 9 k blocks: ragged last work item
     run_matmul_case(e0m4, oracle, M, 333, 4096, 128, seed=140 + M, outliers=True)
     run_matmul_case(e0m4, oracle, M, 40, 128, 128, seed=150 + M)                # a single block
@@ -240,6 +240,16 @@ def test_small_batch_matrix_core_kernel_forced_shapes(e0m4, oracle, waves, targe
     finally:
         e0m4.e0m4_set_knob("gemv_waves", 0)
         e0m4.e0m4_set_knob("gemv_workgroups", 0)
+
+
+@pytest.mark.parametrize("M", [3, 16])
+def test_small_batch_matrix_core_kernel_activations_from_lds(e0m4, oracle, M):
+    # K = 4096 with 8 wavefronts would keep the activations in registers; knob value 2 reads them from LDS
+    e0m4.e0m4_set_knob("gemv_mfma", 2)
+    try:
+        run_matmul_case(e0m4, oracle, M, 333, 4096, 128, seed=175 + M, outliers=True)
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
 
 
 @pytest.mark.parametrize("M", [2, 5, 8])
