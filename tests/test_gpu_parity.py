@@ -20,7 +20,7 @@ def e0m4():
     import paper_2403_20041_amd as pkg
 
     pkg.lib()                                   # raises if the HIP library is not built
-    for k in ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemm_variant", "gemm_splits"):
+    for k in ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits"):
         pkg.e0m4_set_knob(k, 0)
     return pkg
 
@@ -209,6 +209,21 @@ def test_gemv_forced_workgroup_counts(e0m4, oracle, N, K, G):
             run_matmul_case(e0m4, oracle, 1, N, K, G, seed=N + K + 1)
         finally:
             e0m4.e0m4_set_knob("gemv_workgroups", 0)
+
+
+@pytest.mark.parametrize("xreg", [1, 2])              # 1: activations in registers wherever possible, 2: never
+@pytest.mark.parametrize("waves", [0, 4, 8, 16])
+def test_gemv_activations_in_registers(e0m4, oracle, waves, xreg):
+    e0m4.e0m4_set_knob("gemv_waves", waves)
+    e0m4.e0m4_set_knob("gemv_xreg", xreg)
+    try:
+        run_matmul_case(e0m4, oracle, 1, 333, 4096, 128, seed=60 + waves, outliers=True)     # 8 work items per row block
+        run_matmul_case(e0m4, oracle, 1, 200, 2048, 64, seed=61 + waves)                     # 4
+        run_matmul_case(e0m4, oracle, 1, 100, 8192, 32, seed=62 + waves)                     # 16
+        run_matmul_case(e0m4, oracle, 1, 40, 512, 128, seed=63 + waves)                      # 1
+    finally:
+        e0m4.e0m4_set_knob("gemv_waves", 0)
+        e0m4.e0m4_set_knob("gemv_xreg", 0)
 
 
 @pytest.mark.parametrize("M", [1, 2, 5, 8])
