@@ -292,7 +292,7 @@ bool use_pipe(int64_t M, int64_t N, int64_t K, bool swiglu = false)
 {
     if (!gemm_pipe_supported(K)) return false;
     const int v = knob("gemm_variant");             // 1: always the small tile of this file, 2: always the pipelined kernel
-    if (v == 2 || v == 3) return true;
+    if (v == 2 || v == 3 || v == 4) return true;
     if (v == 1) return false;
     return gemm_pipe_work_items(M, N, K, swiglu) >= 96;
 }

@@ -62,7 +62,7 @@ struct PipeFusion {
 //
 // The tile is BM x BN: 256 x 256 with 2 x 4 wavefronts for large M; 128 x 128 with 2 x 2 wavefronts (two
 // workgroups per compute unit) for M up to a few hundred, where the large tile would compute rows that
-// do not exist and leave most compute units without a tile.
+// do not exist and leave most compute units without a tile; 64 x 256 with 1 x 4 wavefronts for M up to 64.
 template <int G, int WGM, int WGN, bool FUSED, int BM, int BN>
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
                                                              const uint4* __restrict__ packed, int64_t N, int64_t K,
@@ -427,6 +427,7 @@ constexpr int kMaxSplits = 8;
 // within 10 %, at M = 512 the large tile is up to 1.3x faster; between 257 and 384 rows the large tile
 // would compute a quarter to a half of its rows for nothing.
 constexpr int kMidMaxM = 384;
+constexpr int kFlatMaxM = 64;                           // 64 x 256 tile: no rows computed for nothing up to here
 struct PipeTile {
     int bm, bn;
     int slots;                                          // work items wanted before K is split no further
@@ -435,9 +436,12 @@ struct PipeTile {
 PipeTile pipe_tile(int64_t M, int64_t N, int64_t K)
 {
     const PipeTile mid{128, 128, kComputeUnits + kComputeUnits / 2}, big{256, 256, kComputeUnits};
+    const PipeTile flat{64, 256, 2 * kComputeUnits};                       // few rows: four wavefronts side by side
     const int v = knob("gemm_variant");
+    if (v == 4) return flat;
     if (v == 3) return mid;
     if (v == 2) return big;
+    if (M <= kFlatMaxM) return flat;
     if (M <= kMidMaxM) return mid;
     // (For larger M with few large tiles the small tile avoids the K split and measured 12 % faster on
     // 1024 x 4096 x 4096 alone, but not inside the benchmark's back-to-back stream: not used there.)
@@ -541,7 +545,9 @@ template <int G, bool FUSED>
 int launch_pipe_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, void* workspace,
                      size_t workspace_bytes, hipStream_t stream, const Fusion& f)
 {
-    if (pipe_tile(M, N, K).bm == 128)
+    const int bm = pipe_tile(M, N, K).bm;
+    if (bm == 64) return launch_pipe<G, 1, 4, FUSED, 64, 256>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+    if (bm == 128)
         return launch_pipe<G, 2, 2, FUSED, 128, 128>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
     return launch_pipe<G, 2, 4, FUSED, 256, 256>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
 }

@@ -177,8 +177,8 @@ def test_nothing_selected_equals_the_plain_matmul(e0m4, oracle):
         assert np.all(np.abs(y0.cpu().numpy().astype(np.float64) - Yref.astype(np.float64)) <= 1e-2 * np.maximum(1, absdot))
 
 
-# 1: small-tile kernel, 2: pipelined kernel with 256 x 256 tiles, 3: pipelined kernel with 128 x 128 tiles
-@pytest.mark.parametrize("variant", [1, 2, 3])
+# 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 @pytest.mark.parametrize("norm,swiglu,res", COMBOS)
 def test_gemm_kernels(e0m4, oracle, variant, norm, swiglu, res):
     e0m4.e0m4_set_knob("gemm_variant", variant)
@@ -191,7 +191,7 @@ def test_gemm_kernels(e0m4, oracle, variant, norm, swiglu, res):
         e0m4.e0m4_set_knob("gemm_variant", 0)
 
 
-@pytest.mark.parametrize("variant", [2, 3])
+@pytest.mark.parametrize("variant", [2, 3, 4])
 @pytest.mark.parametrize("splits", [2, 3, 8])
 @pytest.mark.parametrize("norm,swiglu,res", COMBOS)
 def test_gemm_split_along_k(e0m4, oracle, variant, splits, norm, swiglu, res):
