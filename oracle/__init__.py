@@ -72,6 +72,19 @@ def _load():
     L.oracle_int4_quantize.argtypes = [u16p, i64, i64, i64, u8p, u16p, u16p]
     L.oracle_int4_dequant.restype = None
     L.oracle_int4_dequant.argtypes = [u8p, u16p, u16p, i64, i64, i64, u16p]
+    ci = ctypes.c_int
+    L.oracle_e0mk_w1_bits.restype = ctypes.c_uint16
+    L.oracle_e0mk_w1_bits.argtypes = [ci, ci]
+    L.oracle_e0mk_decode_one.restype = ctypes.c_uint16
+    L.oracle_e0mk_decode_one.argtypes = [ci, ctypes.c_uint16, ctypes.c_uint16, ci]
+    L.oracle_e0mk_encode_one.restype = ci
+    L.oracle_e0mk_encode_one.argtypes = [ctypes.c_uint16, ctypes.c_uint16, ctypes.c_uint16, ci]
+    L.oracle_e0mk_fit_group.restype = None
+    L.oracle_e0mk_fit_group.argtypes = [u16p, i64, ci, u16p, u16p]
+    L.oracle_e0mk_quantize.restype = None
+    L.oracle_e0mk_quantize.argtypes = [u16p, i64, i64, i64, ci, u8p, u16p, u16p]
+    L.oracle_e0mk_dequant.restype = None
+    L.oracle_e0mk_dequant.argtypes = [u8p, u16p, u16p, i64, i64, i64, ci, u16p]
     L.oracle_e0m4_matmul.restype = None
     L.oracle_e0m4_matmul.argtypes = [u16p, i64, u16p, i64, i64, u16p, f64p]
     L.oracle_num_threads.restype = ctypes.c_int
@@ -298,3 +311,51 @@ def kv_append(cache: np.ndarray, new_rows: np.ndarray, position_ids: np.ndarray)
             for e in range(new_rows.shape[1]):
                 out[p, e] = new_rows[i, e]
     return out
+
+
+# --------------------------------------------------------------------------------------------------
+# Other code widths, E0Mk with 1 <= k <= 8 (paper: the closing remark of the section "E0M4 FP4
+# quantization").  Same definition with the k highest fraction bits in place of four.
+# --------------------------------------------------------------------------------------------------
+
+def w1_bits_k(c: int, bits: int) -> int:
+    return int(_load().oracle_e0mk_w1_bits(int(c), int(bits)))
+
+
+def decode_one_k(c: int, scale_bits: int, bias_bits: int, bits: int) -> int:
+    return int(_load().oracle_e0mk_decode_one(int(c), int(scale_bits), int(bias_bits), int(bits)))
+
+
+def encode_one_k(w0_bits: int, scale_bits: int, bias_bits: int, bits: int) -> int:
+    return int(_load().oracle_e0mk_encode_one(int(w0_bits), int(scale_bits), int(bias_bits), int(bits)))
+
+
+def fit_group_k(w0: np.ndarray, bits: int):
+    w0 = _u16(w0)
+    sb, bb = ctypes.c_uint16(0), ctypes.c_uint16(0)
+    _load().oracle_e0mk_fit_group(_p(w0, ctypes.c_uint16), w0.size, int(bits), ctypes.byref(sb), ctypes.byref(bb))
+    return int(sb.value), int(bb.value)
+
+
+def quantize_k(W: np.ndarray, group: int, bits: int):
+    """W [N,K] fp16 -> (codes [N,K] uint8 in 0..2^bits-1, scales, bias [N,K/group] fp16)."""
+    Wb = _u16(W)
+    N, K = Wb.shape
+    assert K % group == 0 and 1 <= bits <= 8
+    codes = np.empty((N, K), np.uint8)
+    scales = np.empty((N, K // group), np.uint16)
+    bias = np.empty((N, K // group), np.uint16)
+    _load().oracle_e0mk_quantize(_p(Wb, ctypes.c_uint16), N, K, group, int(bits), _p(codes, ctypes.c_uint8),
+                                 _p(scales, ctypes.c_uint16), _p(bias, ctypes.c_uint16))
+    return codes, scales.view(np.float16), bias.view(np.float16)
+
+
+def dequant_k(codes: np.ndarray, scales: np.ndarray, bias: np.ndarray, group: int, bits: int) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, np.uint8)
+    N, K = codes.shape
+    sb, bb = _u16(scales), _u16(bias)
+    assert sb.shape == (N, K // group) and bb.shape == sb.shape
+    out = np.empty((N, K), np.uint16)
+    _load().oracle_e0mk_dequant(_p(codes, ctypes.c_uint8), _p(sb, ctypes.c_uint16), _p(bb, ctypes.c_uint16),
+                                N, K, group, int(bits), _p(out, ctypes.c_uint16))
+    return out.view(np.float16)

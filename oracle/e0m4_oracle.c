@@ -226,6 +226,96 @@ void oracle_e0m4_dequant(const uint8_t* codes, const uint16_t* scales, const uin
 }
 
 /* ------------------------------------------------------------------ */
+/* Other code widths (paper: end of the section "E0M4 FP4              */
+/* quantization": the approach carries over to other bit widths).      */
+/* ------------------------------------------------------------------ */
+/* E0Mk keeps the k highest fraction bits of the mapped fp16 value, 1 <= k <= 8,
+ * and one more bit for rounding.  Everything is the E0M4 definition above with 4
+ * replaced by k: the code is shifted left by 10 - k, it saturates at 2^k - 1,
+ * the bias keeps its k highest fraction bits.  Written out again on purpose (not
+ * by calling the E0M4 functions), so that k = 4 can be pinned against them. */
+
+uint16_t oracle_e0mk_w1_bits(int c, int k)
+{
+    return (uint16_t)(E0M4_EXP_BITS | ((unsigned)(c & ((1 << k) - 1)) << (10 - k)));
+}
+
+uint16_t oracle_e0mk_decode_one(int c, uint16_t scale_bits, uint16_t bias_bits, int k)
+{
+    double w1 = oracle_half_bits_to_double(oracle_e0mk_w1_bits(c, k));
+    double b = oracle_half_bits_to_double(bias_bits);
+    double s = oracle_half_bits_to_double(scale_bits);
+    return oracle_double_to_half_bits((w1 - b) * s);
+}
+
+void oracle_e0mk_fit_group(const uint16_t* w0, int64_t G, int k, uint16_t* scale_bits, uint16_t* bias_bits)
+{
+    float mn = 0.0f, mx = 0.0f;
+    for (int64_t i = 0; i < G; ++i) {
+        float v = h2f(w0[i]);
+        if (v < mn) mn = v;
+        if (v > mx) mx = v;
+    }
+    const float span = HI - LO;
+    float range = mx - mn;
+    float s = range / span;
+    if (s < 6.103515625e-05f) s = 6.103515625e-05f;
+    if (s > 65504.0f) s = 65504.0f;
+    uint16_t sb = f2h(s);
+    float sf = h2f(sb);
+    float q = mn / sf;
+    float b = LO - q;
+    if (b < LO) b = LO;
+    if (b > HI) b = HI;
+    const uint16_t keep = (uint16_t)(0xFFFFu << (10 - k));     /* sign, exponent, k highest fraction bits */
+    *scale_bits = sb;
+    *bias_bits = (uint16_t)(f2h(b) & keep);
+}
+
+int oracle_e0mk_encode_one(uint16_t w0_bits, uint16_t scale_bits, uint16_t bias_bits, int k)
+{
+    float q = h2f(w0_bits) / h2f(scale_bits);
+    float t = q + h2f(bias_bits);
+    if (t < LO) t = LO;
+    if (t > HI) t = HI;
+    uint16_t bits = f2h(t);
+    const int top = (1 << k) - 1;
+    int y1 = (bits >> (10 - k)) & top;         /* the k highest fraction bits */
+    int y2 = (bits >> (9 - k)) & 1;            /* the next one */
+    int c = y1 + y2;
+    return c > top ? top : c;
+}
+
+void oracle_e0mk_quantize(const uint16_t* W, int64_t N, int64_t K, int64_t G, int k,
+                          uint8_t* codes, uint16_t* scales, uint16_t* bias)
+{
+    const int64_t ng = K / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t g = 0; g < ng; ++g) {
+            const uint16_t* w0 = W + n * K + g * G;
+            uint16_t sb, bb;
+            oracle_e0mk_fit_group(w0, G, k, &sb, &bb);
+            scales[n * ng + g] = sb;
+            bias[n * ng + g] = bb;
+            for (int64_t i = 0; i < G; ++i)
+                codes[n * K + g * G + i] = (uint8_t)oracle_e0mk_encode_one(w0[i], sb, bb, k);
+        }
+    }
+}
+
+void oracle_e0mk_dequant(const uint8_t* codes, const uint16_t* scales, const uint16_t* bias,
+                         int64_t N, int64_t K, int64_t G, int k, uint16_t* W_out)
+{
+    const int64_t ng = K / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t i = 0; i < K; ++i)
+            W_out[n * K + i] = oracle_e0mk_decode_one(codes[n * K + i], scales[n * ng + i / G],
+                                                      bias[n * ng + i / G], k);
+}
+
+/* ------------------------------------------------------------------ */
 /* INT4 comparison format (paper: section "Evaluation of FP4           */
 /* quantization", Tables 1 and 2).                                     */
 /* ------------------------------------------------------------------ */

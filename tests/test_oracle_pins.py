@@ -589,3 +589,96 @@ def test_kv_append_equals_concatenation(oracle):
     for i in range(n_new):
         step = oracle.kv_append(step, new[i:i + 1], np.array([have + i]))
     assert np.array_equal(step, out)
+
+
+# ---------------------------------------------------------------------------------------------------
+# Other code widths, E0Mk (paper: closing remark of the section "E0M4 FP4 quantization").  The generic
+# functions are written out separately in the oracle; at k = 4 they must be the E0M4 functions bit for
+# bit, and for every k the rounding rule, the levels, nearest-level choice and the error bound are
+# checked against their definitions.
+# ---------------------------------------------------------------------------------------------------
+
+def test_e0mk_at_four_bits_is_e0m4(oracle):
+    W = synth_inputs.weights(64, 512, seed=21)
+    W[0, :8] = [0.0, -0.0, 65504.0, -65504.0, 6e-8, -6e-8, 1.0, -1.0]
+    for G in (32, 128):
+        c4, s4, b4 = oracle.quantize(W, G)
+        ck, sk, bk = oracle.quantize_k(W, G, 4)
+        assert np.array_equal(c4, ck)
+        assert np.array_equal(s4.view(np.uint16), sk.view(np.uint16))
+        assert np.array_equal(b4.view(np.uint16), bk.view(np.uint16))
+        assert np.array_equal(oracle.dequant(c4, s4, b4, G).view(np.uint16),
+                              oracle.dequant_k(ck, sk, bk, G, 4).view(np.uint16))
+    for c in range(16):
+        assert oracle.w1_bits_k(c, 4) == oracle.w1_bits(c)
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 5, 8])
+def test_e0mk_levels_and_rounding_rule_exhaustive(oracle, bits):
+    top = (1 << bits) - 1
+    # the 2^k levels are 2 + c / 2^(k-1): uniform over the binade, the paper's shift-and-or with 10 - k
+    for c in range(top + 1):
+        assert oracle.w1_bits_k(c, bits) == (0x4000 | (c << (10 - bits)))
+        assert Fraction(bits_f16(oracle.w1_bits_k(c, bits))) == 2 + Fraction(c, 1 << (bits - 1))
+    # all 1024 fp16 values of [2,4) under scale 1, bias 2: round half up in units of the step, saturated
+    for b in range(0x4000, 0x4400):
+        v = bits_f16(b)
+        c = oracle.encode_one_k(f16_bits(v - 2.0), F16_ONE, F16_TWO, bits)
+        assert c == min(int(np.floor((v - 2.0) * (1 << (bits - 1)) + 0.5)), top), hex(b)
+        assert c == min(((b >> (10 - bits)) & top) + ((b >> (9 - bits)) & 1), top)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 8])
+def test_e0mk_nearest_level_and_error_bound(oracle, bits):
+    rng = np.random.default_rng(200 + bits)
+    G = 8
+    W = (rng.standard_normal((2000, G)) * 0.02).astype(np.float16)
+    codes, scales, bias = oracle.quantize_k(W, G, bits)
+    assert codes.max() <= (1 << bits) - 1
+    s = scales.astype(np.float64)
+    b = bias.astype(np.float64)
+    # the bias keeps exactly its k highest fraction bits, so a zero weight decodes to exactly zero
+    assert np.all((bias.view(np.uint16) & ((1 << (10 - bits)) - 1)) == 0)
+    Wz = W.copy()
+    Wz[:, 0] = 0
+    cz, sz, bz = oracle.quantize_k(Wz, G, bits)
+    assert np.all(oracle.dequant_k(cz, sz, bz, G, bits)[:, 0] == 0)
+    levels = (2.0 + np.arange(1 << bits) / float(1 << (bits - 1)))[None, None, :]
+    cand = (levels - b[:, :, None]) * s[:, :, None]
+    w = W.astype(np.float64)[:, :, None]
+    best = np.abs(w - cand).min(axis=2)
+    chosen = np.abs(w[:, :, 0] - np.take_along_axis(cand, codes[:, :, None].astype(np.int64), 2)[:, :, 0])
+    step = (s / float(1 << (bits - 1))).repeat(G, 1)
+    # double rounding (fp32 -> fp16 -> k bits) can pick the other neighbour only near a tie: within one
+    # fp16 ulp of the binade (2^-9) of it, i.e. 2^(k-10) of a step
+    slack = step * 2.0 ** (bits - 10) + 1e-12
+    assert (chosen <= best + slack).all()
+    assert (chosen <= best + 1e-15).mean() > (0.97 if bits < 8 else 0.7)
+    # decoded weights: fp16 values, within half a step (plus the rounding slop) unless clamped
+    What = oracle.dequant_k(codes, scales, bias, G, bits).astype(np.float64)
+    t = W.astype(np.float64) / s.repeat(G, 1) + b.repeat(G, 1)
+    inner = (t >= 2.0) & (t < 4.0 - step / s.repeat(G, 1))
+    err = np.abs(W.astype(np.float64) - What)
+    assert (err[inner] <= 0.5 * step[inner] * (1 + 2.0 ** (bits - 9)) + np.abs(What[inner]) * 2.0 ** -11 + 2.0 ** -24).all()
+
+
+def test_e0mk_monotone_and_round_trip(oracle):
+    for bits in (2, 8):
+        top = (1 << bits) - 1
+        sb, bb = f16_bits(0.0123), oracle.w1_bits_k(top // 3, bits)
+        vals = [bits_f16(oracle.decode_one_k(c, sb, bb, bits)) for c in range(top + 1)]
+        assert all(a < b for a, b in zip(vals, vals[1:]))
+        # dequant(quant(dequant(c))) == dequant(c) under fixed parameters
+        for c in range(top + 1):
+            w = oracle.decode_one_k(c, sb, bb, bits)
+            c2 = oracle.encode_one_k(w, sb, bb, bits)
+            assert oracle.decode_one_k(c2, sb, bb, bits) == w
+
+
+def test_e0m8_mean_error_is_a_sixteenth_of_e0m4(oracle):
+    W = synth_inputs.weights(128, 1024, seed=23)
+    e = {}
+    for bits in (4, 8):
+        c, s, b = oracle.quantize_k(W, 128, bits)
+        e[bits] = np.abs(W.astype(np.float64) - oracle.dequant_k(c, s, b, 128, bits).astype(np.float64)).mean()
+    assert 12.0 < e[4] / e[8] < 17.0        # sixteen times finer steps; fp16 rounding of the result takes a little back
