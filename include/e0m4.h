@@ -188,6 +188,34 @@ int e0m4_kv_append(void* cache_f16, int64_t max_seq, int64_t row_elems,
                    const void* position_ids_i64, void* stream);
 
 /*
+ * E0M8, the 8-bit member of the format family (paper: closing remark of the
+ * section "E0M4 FP4 quantization": the approach carries over to other bit
+ * widths).  The E0M4 definition with eight bits in place of four: the code is the
+ * eight highest fraction bits of the mapped fp16 value plus the next one for
+ * rounding, saturated at 255; w1 = as_half(0x4000 | code << 2); the bias keeps
+ * its eight highest fraction bits; w = fp16((w1 - bias) * scale).
+ *   - group is 64 or 128; K % 16 == 0, K % group == 0, K <= 2^19; N as above.
+ *   - `codes` is a packed buffer of e0m8_codes_bytes(N, K, group) bytes: the E0M4
+ *     block layout with two 4-bit slots per code, arranged so that one mask-or
+ *     turns two codes into two fp16 values (blocks of 16 rows x 64 weights, each
+ *     followed by a (scale, bias) word per row).  `scales`/`bias` are
+ *     [N, K/group] fp16.
+ *   - e0m8_unpack_codes writes one byte per weight, [N, K] row-major.
+ *   - e0m8_matmul: Y[M,N] = X[M,K] * dequant(codes)^T, fp32 accumulation, one
+ *     rounding, no workspace.  It runs the decode kernel on up to 8 rows of X at
+ *     a time (HBM-bound for small M; there is no 8-bit GEMM kernel, so large M
+ *     re-reads the weights M/8 times); M > 8 needs N % 8 == 0.
+ * Pointer, alignment, stream and error rules as for the E0M4 entry points.
+ */
+size_t e0m8_codes_bytes(int64_t N, int64_t K, int group);
+int e0m8_quantize(const void* W_f16, int64_t N, int64_t K, int group,
+                  void* codes, void* scales_f16, void* bias_f16, void* stream);
+int e0m8_dequant(const void* codes, int64_t N, int64_t K, int group, void* W_f16_out, void* stream);
+int e0m8_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* codes_u8_out, void* stream);
+int e0m8_matmul(const void* X_f16, int64_t M, const void* codes, int64_t N, int64_t K, int group,
+                void* Y_f16, void* stream);
+
+/*
  * INT4 twin (paper: section "Evaluation of FP4 quantization", Table 1 and
  * Table 2, which compare E0M4 with "INT4 quantization").  The paper does not
  * define that quantiser; this library's reading is group-wise asymmetric

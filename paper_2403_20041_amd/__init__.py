@@ -23,5 +23,10 @@ from .binding import (  # noqa: F401
     e0m4_set_knob,
     e0m4_unpack_codes,
     e0m4_workspace_bytes,
+    e0m8_codes_bytes,
+    e0m8_dequant,
+    e0m8_matmul,
+    e0m8_quantize,
+    e0m8_unpack_codes,
     lib,
 )

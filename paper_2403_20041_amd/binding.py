@@ -65,6 +65,16 @@ def lib() -> ctypes.CDLL:
     L.e0m4_fused_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci]
     L.e0m4_matmul_fused.restype = ci
     L.e0m4_matmul_fused.argtypes = [vp, i64, vp, ctypes.c_float, vp, i64, i64, ci, ci, vp, vp, vp, sz, vp]
+    L.e0m8_codes_bytes.restype = sz
+    L.e0m8_codes_bytes.argtypes = [i64, i64, ci]
+    L.e0m8_quantize.restype = ci
+    L.e0m8_quantize.argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
+    L.e0m8_dequant.restype = ci
+    L.e0m8_dequant.argtypes = [vp, i64, i64, ci, vp, vp]
+    L.e0m8_unpack_codes.restype = ci
+    L.e0m8_unpack_codes.argtypes = [vp, i64, i64, ci, vp, vp]
+    L.e0m8_matmul.restype = ci
+    L.e0m8_matmul.argtypes = [vp, i64, vp, i64, i64, ci, vp, vp]
     L.e0m4_kv_append.restype = ci
     L.e0m4_kv_append.argtypes = [vp, i64, i64, vp, i64, i64, vp, vp]
     L.e0m4_int4_quantize.restype = ci
@@ -226,6 +236,52 @@ def e0m4_kv_append(cache, new_rows, position_ids, stream=None):
     _check(lib().e0m4_kv_append(_ptr(cache), max_seq, row, _ptr(new_rows), n_new, new_rows.stride(0),
                                 _ptr(position_ids), _stream(stream)), "e0m4_kv_append")
     return cache
+
+
+# ---- E0M8, the 8-bit member of the family (see include/e0m4.h) ---------------------------------------
+
+def e0m8_codes_bytes(N: int, K: int, group: int) -> int:
+    return lib().e0m8_codes_bytes(N, K, group)
+
+
+def e0m8_quantize(W: torch.Tensor, group: int, stream=None):
+    """W [N,K] fp16 -> (codes packed uint8, scales [N,K/group] fp16, bias [N,K/group] fp16)."""
+    N, K = W.shape
+    _need(W, torch.float16, (N, K), "W")
+    nbytes = e0m8_codes_bytes(N, K, group)
+    if nbytes == 0 and N * K > 0:
+        raise ValueError("e0m8_quantize: unsupported shape or group")
+    codes = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=W.device)
+    scales = torch.empty((N, max(K // group, 1)), dtype=torch.float16, device=W.device)
+    bias = torch.empty_like(scales)
+    _check(lib().e0m8_quantize(_ptr(W), N, K, group, _ptr(codes), _ptr(scales), _ptr(bias), _stream(stream)),
+           "e0m8_quantize")
+    return codes, scales, bias
+
+
+def e0m8_dequant(codes, N: int, K: int, group: int, out=None, stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.float16, device=codes.device)
+    _need(out, torch.float16, (N, K), "out")
+    _check(lib().e0m8_dequant(_ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m8_dequant")
+    return out
+
+
+def e0m8_unpack_codes(codes, N: int, K: int, group: int, stream=None) -> torch.Tensor:
+    out = torch.empty((N, K), dtype=torch.uint8, device=codes.device)
+    _check(lib().e0m8_unpack_codes(_ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m8_unpack_codes")
+    return out
+
+
+def e0m8_matmul(X, codes, N: int, K: int, group: int, out=None, stream=None) -> torch.Tensor:
+    """Y [M,N] fp16 = X [M,K] fp16 times the dequantised 8-bit weights, transposed."""
+    M = X.shape[0]
+    _need(X, torch.float16, (M, K), "X")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+    _need(out, torch.float16, (M, N), "out")
+    _check(lib().e0m8_matmul(_ptr(X), M, _ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m8_matmul")
+    return out
 
 
 # ---- INT4 twin (see include/e0m4.h) ------------------------------------------------------------

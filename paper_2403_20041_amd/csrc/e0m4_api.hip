@@ -294,6 +294,78 @@ int e0m4_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
                              workspace_bytes - nb, st);
 }
 
+// ---- E0M8: the 8-bit member of the format family ------------------------------------------------------
+static int check_shape8(int64_t N, int64_t K, int group)
+{
+    if (group != 64 && group != 128) return E0M4_ERR_GROUP;
+    if (N < 0 || K < 0 || (K % 16) != 0 || (K % group) != 0) return E0M4_ERR_SHAPE;
+    if (N > (int64_t)1 << 31 || K > (int64_t)1 << 19) return E0M4_ERR_SHAPE;   // 2K 4-bit slots within the K limit
+    return E0M4_OK;
+}
+
+size_t e0m8_codes_bytes(int64_t N, int64_t K, int group)
+{
+    if (check_shape8(N, K, group) != E0M4_OK) return 0;
+    return (size_t)row_blocks(N) * (size_t)k_blocks(2 * K) * (size_t)block_bytes(128);
+}
+
+int e0m8_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, void* scales, void* bias, void* stream)
+{
+    int rc = check_shape8(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!W || !codes || !scales || !bias) return E0M4_ERR_NULL;
+    if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
+    return launch_quantize8(W, N, K, group, codes, scales, bias, (hipStream_t)stream);
+}
+
+int e0m8_dequant(const void* codes, int64_t N, int64_t K, int group, void* W_out, void* stream)
+{
+    int rc = check_shape8(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!codes || !W_out) return E0M4_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(W_out)) return E0M4_ERR_ALIGN;
+    return launch_dequant8(codes, N, K, W_out, nullptr, (hipStream_t)stream);
+}
+
+int e0m8_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* out, void* stream)
+{
+    int rc = check_shape8(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!codes || !out) return E0M4_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(out)) return E0M4_ERR_ALIGN;
+    return launch_dequant8(codes, N, K, nullptr, out, (hipStream_t)stream);
+}
+
+int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t K, int group, void* Y, void* stream)
+{
+    int rc = check_shape8(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (M < 0 || M > (int64_t)1 << 31) return E0M4_ERR_SHAPE;
+    if (M == 0 || N == 0) return E0M4_OK;
+    if (!Y) return E0M4_ERR_NULL;
+    if (!aligned16(Y)) return E0M4_ERR_ALIGN;
+    if (K == 0) {
+        const int64_t total = M * N;
+        hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                           static_cast<half_t*>(Y), total);
+        return check_launch();
+    }
+    if (!X || !codes) return E0M4_ERR_NULL;
+    if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    if (M > kGemvMaxM && ((N % 8) != 0)) return E0M4_ERR_SHAPE;    // row chunks of Y must stay 16-byte aligned
+    // up to 8 rows of X per launch of the decode kernel (there is no 8-bit GEMM kernel yet)
+    for (int64_t m0 = 0; m0 < M; m0 += kGemvMaxM) {
+        const int64_t rows = M - m0 < kGemvMaxM ? M - m0 : kGemvMaxM;
+        rc = launch_gemv8(static_cast<const half_t*>(X) + m0 * K, rows, codes, N, K, static_cast<half_t*>(Y) + m0 * N,
+                          (hipStream_t)stream);
+        if (rc != E0M4_OK) return rc;
+    }
+    return E0M4_OK;
+}
+
 int e0m4_kv_append(void* cache, int64_t max_seq, int64_t row_elems, const void* new_rows, int64_t n_new,
                    int64_t new_ld, const void* position_ids, void* stream)
 {

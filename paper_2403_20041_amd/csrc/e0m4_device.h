@@ -85,6 +85,7 @@ __host__ __device__ inline uint32_t extract_code(uint32_t word, int j) { return 
 
 constexpr uint32_t kFracMask2 = 0x03C003C0u;   // four highest fraction bits of both halves
 constexpr uint32_t kFracMaskLow2 = 0x003C003Cu;    // fraction bits 5..2 of both halves
+constexpr uint32_t kFrac8Mask2 = 0x03FC03FCu;  // eight highest fraction bits of both halves (8-bit format)
 constexpr uint32_t kExpBits2 = 0x40004000u;    // sign 0, exponent of the binade [2,4), both halves
 
 // The paper's two bitwise operations, applied to two codes at once: pair i of

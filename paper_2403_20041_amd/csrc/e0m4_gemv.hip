@@ -23,6 +23,7 @@
 #include "e0m4_host.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace e0m4 {
 
@@ -109,7 +110,10 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K, int unit = 1, bool* single_s
 // kDeqInt4Convert is the INT4 twin of the paper's section "Evaluation of FP4 quantization" (Table 1):
 // same data layout and work decomposition, but every code is extracted as an integer and turned into
 // fp16 with a conversion instruction, and the parameter word holds (scale, integer zero point).
-enum { kDeqE0M4 = 0, kDeqInt4Convert = 1 };
+// kDeqE0M8 is the 8-bit member of the format family (e0m8_pack.hip): a block holds 64 weights, a lane's
+// chunk 16, a 32-bit word four codes that one mask-or (and one more after a rotation) turns into two pairs
+// of binade values, so the dot product needs no folding of pair kinds.
+enum { kDeqE0M4 = 0, kDeqInt4Convert = 1, kDeqE0M8 = 2 };
 
 // FUSED adds the operators of GemvFusion (e0m4_device.h) to the kernel.
 // XREG (M = 1, one segment, wavefront count a multiple of the work items per row block): a wavefront meets
@@ -124,11 +128,13 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     constexpr int PW = block_param_words(G);            // parameter words per k block: 16, 32 or 64
     constexpr int NPL = kSuper * PW / 64;               // dword loads per lane that fetch a work item's parameters
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int seg_k = seg_items * kSuper * kBlockK;
+    constexpr int BLK_K = DEQ == kDeqE0M8 ? 64 : kBlockK;       // weights per block
+    constexpr int CHUNK = DEQ == kDeqE0M8 ? 16 : kCodesPerChunk; // weights per lane and block
+    const int seg_k = seg_items * kSuper * BLK_K;
     half_t* xs = reinterpret_cast<half_t*>(smem);                               // [M][seg_k]
     // per 32-wide chunk of X: (sum of the chunk, 30 x sum of its elements with k % 8 in 2..5)
     float2* sxs = reinterpret_cast<float2*>(smem + (size_t)M * seg_k * 2);      // [M][seg_k/32]
-    float* part = reinterpret_cast<float*>(sxs + (size_t)M * (seg_k / kCodesPerChunk));  // [W][M] sums of squares (FUSED only)
+    float* part = reinterpret_cast<float*>(sxs + (size_t)M * (seg_k / CHUNK));  // [W][M] sums of squares (FUSED only)
     float* red = part + (FUSED ? W * M : 0);                                    // [rb_per_wg][W][M][16]
 
     const int t = threadIdx.x;
@@ -136,7 +142,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int q = lane >> 4, r = lane & 15;
     const uint32_t fmask = frac_mask_vgpr(), fmask_low = frac_mask_low_vgpr();
-    const PackedLayout<G> lay(K);
+    const PackedLayout<G> lay(DEQ == kDeqE0M8 ? 2 * K : K);     // 8-bit codes: two 4-bit slots each
     const int nkb = (int)lay.nkb;
     const int nsi = (nkb + kSuper - 1) / kSuper;
     // even deal of row blocks (of pairs of row blocks with the gated epilogue: rb0 is then the first pair,
@@ -181,7 +187,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     const int pieces = seg_k / 8;                       // 16-byte pieces per row of X per segment
     auto x_piece = [&](int idx, int kb_first) {
         const int m = M == 1 ? 0 : idx / pieces, pc = M == 1 ? idx : idx % pieces;
-        const int64_t k = (int64_t)kb_first * kBlockK + pc * 8;
+        const int64_t k = (int64_t)kb_first * BLK_K + pc * 8;
         half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
         if (idx < M * pieces && k < K) v = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
         return v;
@@ -204,7 +210,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     // the rms-norm weights that go with piece idx (zero beyond K)
     auto g_piece = [&](int idx, int kb_first) {
         const int pc = M == 1 ? idx : idx % pieces;
-        const int64_t k = (int64_t)kb_first * kBlockK + pc * 8;
+        const int64_t k = (int64_t)kb_first * BLK_K + pc * 8;
         half8_t gv = {0, 0, 0, 0, 0, 0, 0, 0};
         if (FUSED && fu.gamma && idx < M * pieces && k < K) gv = *reinterpret_cast<const half8_t*>(fu.gamma + k);
         return gv;
@@ -224,11 +230,14 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
         s += sl;
         s += __shfl_xor(s, 1);
         sl += __shfl_xor(sl, 1);
-        s += __shfl_xor(s, 2);
-        sl += __shfl_xor(sl, 2);
+        if (CHUNK == 32) {                              // a chunk is four pieces (two for the 8-bit format)
+            s += __shfl_xor(s, 2);
+            sl += __shfl_xor(sl, 2);
+        }
         if (idx < M * pieces) {
+            constexpr int PPC = CHUNK / 8;              // pieces per chunk
             *reinterpret_cast<half8_t*>(&xs[m * seg_k + pc * 8]) = v;
-            if ((pc & 3) == 0) sxs[m * (seg_k / kCodesPerChunk) + (pc >> 2)] = make_float2(s, 30.f * sl);
+            if ((pc % PPC) == 0) sxs[m * (seg_k / CHUNK) + pc / PPC] = make_float2(s, 30.f * sl);
         }
     };
     // stage pieces start, start + kThreads, ... : loads in batches of four, issued together and then
@@ -375,10 +384,10 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
         if (XREG) {
 #pragma unroll
             for (int j = 0; j < kSuper; ++j) {
-                const int xoff = (si * kSuper + j) * kBlockK + q * kCodesPerChunk;
+                const int xoff = (si * kSuper + j) * BLK_K + q * CHUNK;
 #pragma unroll
                 for (int w = 0; w < 4; ++w) xr[j][w] = *reinterpret_cast<const half8_t*>(&xs[xoff + 8 * w]);
-                sxr[j] = sxs[xoff >> 5];
+                sxr[j] = sxs[xoff / CHUNK];
             }
         }
         const int seg_end = seg0 + seg_items;
@@ -396,12 +405,25 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
                 const float sc = (float)param_scale(pwj[j]);
                 const float bi = (float)param_bias(pwj[j]);
                 const uint32_t words[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
-                const int xoff = ((si - seg0) * kSuper + j) * kBlockK + q * kCodesPerChunk;
+                const int xoff = ((si - seg0) * kSuper + j) * BLK_K + q * CHUNK;
                 float a[M][2];      // per row of X: sum x*(2 + c/8) over code pairs 0 and 3, sum x*(2 + c/128) over 1 and 2
 #pragma unroll
                 for (int m = 0; m < M; ++m) a[m][0] = a[m][1] = 0.f;
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
+                    if (DEQ == kDeqE0M8) {              // four weights per word: two mask-or, two dot instructions
+                        const half2_t p01 = __builtin_bit_cast(half2_t, (words[w] & kFrac8Mask2) | kExpBits2);
+                        const half2_t p23 =
+                            __builtin_bit_cast(half2_t, (__builtin_amdgcn_alignbit(words[w], words[w], 8) & kFrac8Mask2) | kExpBits2);
+#pragma unroll
+                        for (int m = 0; m < M; ++m) {
+                            const half4_t xv = *reinterpret_cast<const half4_t*>(&xs[m * seg_k + xoff + 4 * w]);
+                            const half2_t x01 = {xv[0], xv[1]}, x23 = {xv[2], xv[3]};
+                            a[m][0] = __builtin_amdgcn_fdot2(p01, x01, a[m][0], false);
+                            a[m][0] = __builtin_amdgcn_fdot2(p23, x23, a[m][0], false);
+                        }
+                        continue;
+                    }
                     half2_t p[4];
                     if (DEQ == kDeqInt4Convert) {
 #pragma unroll
@@ -424,8 +446,10 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
                 fetch_code(j, nslot, nitem);            // the block's registers are free: request the next item's
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
-                    const float2 sx = XREG ? sxr[XREG ? j : 0] : sxs[m * (seg_k / kCodesPerChunk) + (xoff >> 5)];
-                    if (DEQ == kDeqInt4Convert)         // y += scale * (sum x*q - zero * sum x)
+                    const float2 sx = XREG ? sxr[XREG ? j : 0] : sxs[m * (seg_k / CHUNK) + xoff / CHUNK];
+                    if (DEQ == kDeqE0M8)                // y += scale * (sum x*w1 - bias * sum x)
+                        acc[m] += sc * (a[m][0] - bi * sx.x);
+                    else if (DEQ == kDeqInt4Convert)    // y += scale * (sum x*q - zero * sum x)
                         acc[m] += sc * ((a[m][0] + a[m][1]) - bi * sx.x);
                     else    // sum x*w1 = a0 + 16*a1 - 30*(sum of x over pairs 1 and 2); then the group's affine map
                         acc[m] += sc * ((a[m][0] + 16.f * a[m][1] - sx.y) - bi * sx.x);
@@ -477,7 +501,7 @@ template <int G, int M, int W, int DEQ = kDeqE0M4, bool FUSED = false, bool XREG
 int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
                const GemvFusion& fu = GemvFusion{})
 {
-    if constexpr (M == 1 && !XREG) {
+    if constexpr (M == 1 && !XREG && DEQ != kDeqE0M8) {
         // every wavefront stays on its own k blocks, all of X in one segment, and a work item that exists
         const int64_t nsi = (k_blocks(K) + kSuper - 1) / kSuper;
         const int xk = knob("gemv_xreg");               // 1: wherever possible, 2: never; else up to 8 wavefronts
@@ -597,6 +621,33 @@ int launch_gemv_fused(const Fusion& f, const void* X, int64_t M, const void* pac
         case 64: return launch_m<64, true>(p, M, X, packed, N, K, Y, stream, fu);
         case 128: return launch_m<128, true>(p, M, X, packed, N, K, Y, stream, fu);
         default: return E0M4_ERR_GROUP;
+    }
+}
+
+// 8-bit format, M <= 8: the packed buffer is a 4-bit layout of 2K codes with groups of 128.
+int launch_gemv8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+{
+    const GemvPlan p = make_plan(M, N, 2 * K);
+    auto go = [&](auto m_tag) -> int {
+        constexpr int MM = decltype(m_tag)::value;
+        switch (p.waves) {
+            case 4: return launch_one<128, MM, 4, kDeqE0M8>(p, X, packed, N, K, Y, stream);
+            case 8: return launch_one<128, MM, 8, kDeqE0M8>(p, X, packed, N, K, Y, stream);
+            default:
+                if constexpr (MM <= 4) return launch_one<128, MM, 16, kDeqE0M8>(p, X, packed, N, K, Y, stream);
+                else return E0M4_ERR_SHAPE;
+        }
+    };
+    switch (M) {
+        case 1: return go(std::integral_constant<int, 1>{});
+        case 2: return go(std::integral_constant<int, 2>{});
+        case 3: return go(std::integral_constant<int, 3>{});
+        case 4: return go(std::integral_constant<int, 4>{});
+        case 5: return go(std::integral_constant<int, 5>{});
+        case 6: return go(std::integral_constant<int, 6>{});
+        case 7: return go(std::integral_constant<int, 7>{});
+        case 8: return go(std::integral_constant<int, 8>{});
+        default: return E0M4_ERR_SHAPE;
     }
 }
 

@@ -75,6 +75,12 @@ int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K, bool swiglu = fals
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                      void* workspace, size_t workspace_bytes, hipStream_t stream);
 
+// 8-bit format (E0M8): offline side and decode kernel.
+int launch_quantize8(const void* W, int64_t N, int64_t K, int group, void* packed, void* scales, void* bias,
+                     hipStream_t stream);
+int launch_dequant8(const void* packed, int64_t N, int64_t K, void* W_out, void* codes_out, hipStream_t stream);
+int launch_gemv8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream);
+
 // In-place KV-cache append: cache[position_ids[i], :] = src[i, :row_elems], src rows src_ld elements apart.
 int launch_kv_append(void* cache, int64_t max_seq, int64_t row_elems, const void* src, int64_t n_new, int64_t src_ld,
                      const void* position_ids, hipStream_t stream);

@@ -1,0 +1,155 @@
+"""Parity of the 8-bit format E0M8 (paper: closing remark of the section "E0M4 FP4 quantization") with the
+CPU oracle, through the C ABI: codes, scales, bias and dequantised weights bit for bit; matmul outputs within
+    |y_gpu - y_ref| <= 1e-2 * max(1, sum_k |x_k * w_k|)
+and within the tighter quality bound of the other matmul tests."""
+import numpy as np
+import pytest
+
+import synth_inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+DEV = "cuda:0"
+KNOBS = ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits")
+
+
+@pytest.fixture(scope="module")
+def e0m4():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run with -m 'not gpu' elsewhere)")
+    import paper_2403_20041_amd as pkg
+
+    pkg.lib()                                   # raises if the HIP library is not built
+    for k in KNOBS:
+        pkg.e0m4_set_knob(k, 0)
+    return pkg
+
+
+def to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def bits(t):
+    a = t.detach().cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.float16 else a
+
+
+def assert_quantize_exact(e0m4, oracle, W, G):
+    N, K = W.shape
+    codes, scales, bias = e0m4.e0m8_quantize(to_dev(W), G)
+    oc, os_, ob = oracle.quantize_k(W, G, 8)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(scales), os_.view(np.uint16)), "scales differ"
+    assert np.array_equal(bits(bias), ob.view(np.uint16)), "bias differ"
+    assert np.array_equal(bits(e0m4.e0m8_unpack_codes(codes, N, K, G)), oc), "codes differ"
+    want = oracle.dequant_k(oc, os_, ob, G, 8)
+    assert np.array_equal(bits(e0m4.e0m8_dequant(codes, N, K, G)), want.view(np.uint16)), "dequantised weights differ"
+    return codes, want
+
+
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("N,K", [(64, 128), (200, 384), (1, 128), (63, 256), (65, 1152), (130, 1024), (256, 4096)])
+def test_quantize_dequant_bit_exact(e0m4, oracle, N, K, G):
+    assert_quantize_exact(e0m4, oracle, synth_inputs.weights(N, K, seed=2000 + N + K + G), G)
+
+
+def test_quantize_ragged_block_pair(e0m4, oracle):
+    # K = 17 and 3 blocks of 64: the last pair of blocks holds one block only
+    assert_quantize_exact(e0m4, oracle, synth_inputs.weights(70, 1088, seed=5), 64)
+    assert_quantize_exact(e0m4, oracle, synth_inputs.weights(33, 192, seed=6), 64)
+
+
+@pytest.mark.parametrize("G", [64, 128])
+def test_quantize_value_distributions(e0m4, oracle, G):
+    rng = np.random.default_rng(17 + G)
+    N, K = 96, 512
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    W[0:8] = 0.0
+    W[8:16] = np.float16(0.5)
+    W[16:24] = np.abs(W[16:24])
+    W[24:32] = -np.abs(W[24:32])
+    W[32:40] = (rng.standard_normal((8, K)) * 3e-6).astype(np.float16)          # floor on the scale
+    W[40:48] = np.clip(rng.standard_normal((8, K)) * 2e4, -6e4, 6e4).astype(np.float16)
+    W[48, ::2] = np.float16(65504.0)
+    W[48, 1::2] = np.float16(-65504.0)                                            # scale saturates
+    W[56:64, ::7] = 0.0
+    W[64:72, ::5] = np.float16(-0.0)
+    W[72:80] = rng.integers(-3, 4, (8, K)).astype(np.float16) * np.float16(2.0 ** -14)
+    assert_quantize_exact(e0m4, oracle, W, G)
+
+
+def check_matmul(y_gpu, y_ref, absdot, what):
+    got = y_gpu.detach().cpu().numpy().astype(np.float64)
+    ref = y_ref.astype(np.float64)
+    err = np.abs(got - ref)
+    tol = 1e-2 * np.maximum(1.0, absdot)
+    worst = np.unravel_index(np.argmax(err / tol), err.shape)
+    assert (err <= tol).all(), "%s: worst at %s err %g tol %g" % (what, worst, err[worst], tol[worst])
+    tight = 2.0 ** -9 * absdot + 2.0 ** -10 * np.abs(ref) + 1e-7
+    assert (err <= tight).all(), "%s: quality bound: %g" % (what, (err / tight).max())
+
+
+def run_matmul_case(e0m4, oracle, M, N, K, G, seed, outliers=False):
+    W = synth_inputs.weights(N, K, seed=seed)
+    X = synth_inputs.activations(M, K, seed=seed, outlier_frac=0.01 if outliers else 0.0)
+    codes, What = assert_quantize_exact(e0m4, oracle, W, G)
+    Y = e0m4.e0m8_matmul(to_dev(X), codes, N, K, G)
+    Yref, absdot = oracle.matmul(X, What)
+    torch.cuda.synchronize()
+    check_matmul(Y, Yref, absdot, "M=%d N=%d K=%d G=%d" % (M, N, K, G))
+
+
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_decode_small(e0m4, oracle, M, G):
+    run_matmul_case(e0m4, oracle, M, 200, 1152, G, seed=700 + M)
+
+
+@pytest.mark.parametrize("N,K,G", [(64, 128, 128), (1, 64, 64), (4096, 4096, 128), (1000, 6848, 64), (203, 832, 64),
+                                    (77, 1088, 64), (8192, 1024, 128)])
+def test_decode_shapes_m1(e0m4, oracle, N, K, G):
+    run_matmul_case(e0m4, oracle, 1, N, K, G, seed=N + K, outliers=True)
+
+
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("target", [0, 7, 100000])
+def test_decode_forced_shapes(e0m4, oracle, waves, target):
+    e0m4.e0m4_set_knob("gemv_waves", waves)
+    e0m4.e0m4_set_knob("gemv_workgroups", target)
+    try:
+        run_matmul_case(e0m4, oracle, 1, 300, 576, 64, seed=710 + waves)        # 9 blocks
+        run_matmul_case(e0m4, oracle, 3, 1000, 2048, 128, seed=711 + waves)
+    finally:
+        e0m4.e0m4_set_knob("gemv_waves", 0)
+        e0m4.e0m4_set_knob("gemv_workgroups", 0)
+
+
+def test_decode_long_rows_and_row_chunks(e0m4, oracle):
+    run_matmul_case(e0m4, oracle, 8, 40, 16384, 128, seed=720)      # activations staged in several segments
+    run_matmul_case(e0m4, oracle, 21, 136, 1152, 64, seed=721)      # three launches: 8 + 8 + 5 rows
+    run_matmul_case(e0m4, oracle, 16, 64, 256, 128, seed=722)
+
+
+def test_one_hot_activations_reproduce_weights_bit_exactly(e0m4, oracle):
+    N, K, G = 100, 256, 64
+    W = synth_inputs.weights(N, K, seed=730)
+    codes, What = assert_quantize_exact(e0m4, oracle, W, G)
+    for k in (0, 15, 16, 63, 64, 127, 200, 255):
+        X = np.zeros((1, K), np.float16)
+        X[0, k] = 1.0
+        Y = e0m4.e0m8_matmul(to_dev(X), codes, N, K, G).cpu().numpy()
+        assert np.array_equal(Y[0].view(np.uint16), What[:, k].view(np.uint16)), k
+
+
+def test_argument_errors(e0m4):
+    x = torch.zeros((1, 128), dtype=torch.float16, device=DEV)
+    w = torch.zeros((64, 128), dtype=torch.float16, device=DEV)
+    with pytest.raises(ValueError):
+        e0m4.e0m8_quantize(w, 32)                       # group 32 is not offered for the 8-bit format
+    codes, _, _ = e0m4.e0m8_quantize(w, 64)
+    with pytest.raises(e0m4.E0M4Error):
+        e0m4.e0m8_matmul(x, codes, 64, 128, 48)
+    assert e0m4.e0m8_codes_bytes(64, 128, 64) == 4 * 2 * (1024 + 64)
+    assert e0m4.e0m8_codes_bytes(64, 100, 64) == 0

@@ -23,7 +23,7 @@ def L():
 def declared_symbols():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(e0m4_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(e0m[48]_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported(L):
@@ -165,3 +165,31 @@ def test_kv_append_validation(L):
     assert f(p, 16, 16, ctypes.c_void_p(0x1008), 1, 16, p, null) == ERR_ALIGN
     assert f(p, 16, 16, p, 1, 16, odd, null) == ERR_ALIGN       # position_ids are 8-byte integers
     assert f(null, 16, 16, null, 0, 16, null, null) == 0        # nothing to append
+
+
+def test_e0m8_validation_and_sizes(L):
+    for name, res, args in (("e0m8_codes_bytes", ctypes.c_size_t, [ctypes.c_int64, ctypes.c_int64, ctypes.c_int]),
+                            ("e0m8_quantize", ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+                             + [ctypes.c_void_p] * 4),
+                            ("e0m8_dequant", ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                                            ctypes.c_void_p, ctypes.c_void_p]),
+                            ("e0m8_matmul", ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                                           ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p])):
+        getattr(L, name).restype = res
+        getattr(L, name).argtypes = args
+    p, odd, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008), ctypes.c_void_p(0)
+    ERR_NULL, ERR_SHAPE, ERR_GROUP, ERR_ALIGN = -1, -2, -3, -4
+    blk = 1024 + 64                                         # 16 rows x 64 weights + 16 (scale, bias) words
+    assert L.e0m8_codes_bytes(4096, 4096, 128) == 256 * 64 * blk      # twice the 4-bit size
+    assert L.e0m8_codes_bytes(17, 192, 64) == 2 * 3 * blk
+    assert L.e0m8_codes_bytes(64, 200, 64) == 0
+    assert L.e0m8_codes_bytes(64, 128, 32) == 0
+    assert L.e0m8_quantize(p, 64, 128, 32, p, p, p, null) == ERR_GROUP
+    assert L.e0m8_quantize(p, 64, 200, 64, p, p, p, null) == ERR_SHAPE
+    assert L.e0m8_quantize(p, 64, (1 << 19) + 128, 128, p, p, p, null) == ERR_SHAPE     # K above its limit
+    assert L.e0m8_quantize(null, 64, 128, 64, p, p, p, null) == ERR_NULL
+    assert L.e0m8_quantize(odd, 64, 128, 64, p, p, p, null) == ERR_ALIGN
+    assert L.e0m8_dequant(p, 64, 128, 64, null, null) == ERR_NULL
+    assert L.e0m8_matmul(p, 1, p, 64, 128, 64, odd, null) == ERR_ALIGN
+    assert L.e0m8_matmul(p, 9, p, 68, 128, 64, p, null) == ERR_SHAPE                    # several row chunks need N % 8 == 0
+    assert L.e0m8_matmul(null, 0, null, 64, 128, 64, null, null) == 0
