@@ -268,6 +268,48 @@ def main():
                                                   "cold weights; ratio as the table's 'acceleration'" % GROUP,
                                       "shapes": t1}
 
+    # ---------------- E0M8 (8-bit codes) decode: the ChatGLM2-6B shapes at M = 1, cold weights, HIP graph
+    if not args.no_table1:
+        e8 = {}
+        with torch.cuda.stream(stream):
+            for name, N, K in shapes:
+                W = synth_inputs.weights_device(N, K, 8500 + N + K, dev)
+                c8, _, _ = e0m4.e0m8_quantize(W, GROUP, stream=stream)
+                del W
+                copies = max(2, min(24, int(1.5e9 // c8.numel())))
+                bufs = [c8] + [c8.clone() for _ in range(copies - 1)]
+                x = synth_inputs.activations_device(1, K, 8600 + K, dev)
+                y = torch.empty((1, N), dtype=torch.float16, device=dev)
+
+                def one_pass():
+                    for c in bufs:
+                        e0m4.e0m8_matmul(x, c, N, K, GROUP, out=y, stream=stream)
+                one_pass()
+                stream.synchronize()
+                run = one_pass
+                if graph is not None:
+                    g8 = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g8, stream=stream):
+                        one_pass()
+                    run = g8.replay
+                best = None
+                for _ in range(5):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    for _ in range(4):
+                        run()
+                    e1.record(stream)
+                    stream.synchronize()
+                    t = e0.elapsed_time(e1) * 1e3 / (4 * copies)
+                    best = t if best is None else min(best, t)
+                b = N * K * (1.0 + 4.0 / 64) + 2 * K + 2 * N        # a byte per code, a (scale, bias) word per 64 weights
+                e8[name] = {"N": N, "K": K, "us": round(best, 3), "GBps": round(b / best / 1e3, 1),
+                            "frac_hbm": round(b / best / 1e3 / HBM_PEAK_GBPS, 4)}
+                del bufs, c8, x, y
+        out["e0m8_decode"] = {"workload": "E0M8 (8-bit codes, group %d), M=1, ChatGLM2-6B shapes; latency per launch, "
+                                          "cold weights; algorithmic bytes N*K*(1 + 4/64) + 2K + 2N" % GROUP,
+                              "per_shape": e8}
+
     # ---------------- prefill: same four shapes at M=1024 (activation outliers, per-row weight scale)
     if not args.no_prefill:
         pre = {}
