@@ -202,9 +202,10 @@ int e0m4_kv_append(void* cache_f16, int64_t max_seq, int64_t row_elems,
  *     [N, K/group] fp16.
  *   - e0m8_unpack_codes writes one byte per weight, [N, K] row-major.
  *   - e0m8_matmul: Y[M,N] = X[M,K] * dequant(codes)^T, fp32 accumulation, one
- *     rounding, no workspace.  It runs the decode kernel on up to 8 rows of X at
- *     a time (HBM-bound for small M; there is no 8-bit GEMM kernel, so large M
- *     re-reads the weights M/8 times); M > 8 needs N % 8 == 0.
+ *     rounding.  M <= 8: the HBM-bound decode kernel.  M > 8 with K % 128 == 0
+ *     (and N <= 2^24): the MFMA GEMM kernels, workspace of
+ *     e0m8_workspace_bytes() bytes under the rules of e0m4_matmul.  Other M > 8:
+ *     the decode kernel on 8 rows of X at a time (needs N % 8 == 0).
  * Pointer, alignment, stream and error rules as for the E0M4 entry points.
  */
 size_t e0m8_codes_bytes(int64_t N, int64_t K, int group);
@@ -212,8 +213,9 @@ int e0m8_quantize(const void* W_f16, int64_t N, int64_t K, int group,
                   void* codes, void* scales_f16, void* bias_f16, void* stream);
 int e0m8_dequant(const void* codes, int64_t N, int64_t K, int group, void* W_f16_out, void* stream);
 int e0m8_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* codes_u8_out, void* stream);
+size_t e0m8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
 int e0m8_matmul(const void* X_f16, int64_t M, const void* codes, int64_t N, int64_t K, int group,
-                void* Y_f16, void* stream);
+                void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * INT4 twin (paper: section "Evaluation of FP4 quantization", Table 1 and

@@ -28,5 +28,6 @@ from .binding import (  # noqa: F401
     e0m8_matmul,
     e0m8_quantize,
     e0m8_unpack_codes,
+    e0m8_workspace_bytes,
     lib,
 )

@@ -74,7 +74,9 @@ def lib() -> ctypes.CDLL:
     L.e0m8_unpack_codes.restype = ci
     L.e0m8_unpack_codes.argtypes = [vp, i64, i64, ci, vp, vp]
     L.e0m8_matmul.restype = ci
-    L.e0m8_matmul.argtypes = [vp, i64, vp, i64, i64, ci, vp, vp]
+    L.e0m8_matmul.argtypes = [vp, i64, vp, i64, i64, ci, vp, vp, sz, vp]
+    L.e0m8_workspace_bytes.restype = sz
+    L.e0m8_workspace_bytes.argtypes = [i64, i64, i64, ci]
     L.e0m4_kv_append.restype = ci
     L.e0m4_kv_append.argtypes = [vp, i64, i64, vp, i64, i64, vp, vp]
     L.e0m4_int4_quantize.restype = ci
@@ -273,14 +275,23 @@ def e0m8_unpack_codes(codes, N: int, K: int, group: int, stream=None) -> torch.T
     return out
 
 
-def e0m8_matmul(X, codes, N: int, K: int, group: int, out=None, stream=None) -> torch.Tensor:
+def e0m8_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    return lib().e0m8_workspace_bytes(M, N, K, group)
+
+
+def e0m8_matmul(X, codes, N: int, K: int, group: int, out=None, workspace=None, stream=None) -> torch.Tensor:
     """Y [M,N] fp16 = X [M,K] fp16 times the dequantised 8-bit weights, transposed."""
     M = X.shape[0]
     _need(X, torch.float16, (M, K), "X")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=X.device)
     _need(out, torch.float16, (M, N), "out")
-    _check(lib().e0m8_matmul(_ptr(X), M, _ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m8_matmul")
+    need = e0m8_workspace_bytes(M, N, K, group)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().e0m8_matmul(_ptr(X), M, _ptr(codes), N, K, group, _ptr(out), _ptr(workspace), ws_bytes,
+                             _stream(stream)), "e0m8_matmul")
     return out
 
 

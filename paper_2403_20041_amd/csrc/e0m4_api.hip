@@ -339,7 +339,20 @@ int e0m8_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
     return launch_dequant8(codes, N, K, nullptr, out, (hipStream_t)stream);
 }
 
-int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t K, int group, void* Y, void* stream)
+// The pipelined GEMM serves M > 8 when K is a multiple of 128 (its K slices come in pairs).
+static bool e0m8_use_gemm(int64_t M, int64_t N, int64_t K)
+{
+    return M > kGemvMaxM && gemm_pipe_supported(K) && N <= (int64_t)1 << 24;
+}
+
+size_t e0m8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
+{
+    if (check_shape8(N, K, group) != E0M4_OK || M <= 0 || N == 0 || K == 0) return 0;
+    return e0m8_use_gemm(M, N, K) ? gemm_pipe_workspace_bytes(M, N, K) : 0;
+}
+
+int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t K, int group, void* Y, void* workspace,
+                size_t workspace_bytes, void* stream)
 {
     int rc = check_shape8(N, K, group);
     if (rc != E0M4_OK) return rc;
@@ -355,8 +368,12 @@ int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t 
     }
     if (!X || !codes) return E0M4_ERR_NULL;
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    if (e0m8_use_gemm(M, N, K)) {
+        if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
+        return launch_gemm_pipe8(X, M, codes, N, K, Y, workspace, workspace_bytes, (hipStream_t)stream);
+    }
     if (M > kGemvMaxM && ((N % 8) != 0)) return E0M4_ERR_SHAPE;    // row chunks of Y must stay 16-byte aligned
-    // up to 8 rows of X per launch of the decode kernel (there is no 8-bit GEMM kernel yet)
+    // otherwise up to 8 rows of X per launch of the decode kernel
     for (int64_t m0 = 0; m0 < M; m0 += kGemvMaxM) {
         const int64_t rows = M - m0 < kGemvMaxM ? M - m0 : kGemvMaxM;
         rc = launch_gemv8(static_cast<const half_t*>(X) + m0 * K, rows, codes, N, K, static_cast<half_t*>(Y) + m0 * N,

@@ -63,7 +63,12 @@ struct PipeFusion {
 // The tile is BM x BN: 256 x 256 with 2 x 4 wavefronts for large M; 128 x 128 with 2 x 2 wavefronts (two
 // workgroups per compute unit) for M up to a few hundred, where the large tile would compute rows that
 // do not exist and leave most compute units without a tile; 64 x 256 with 1 x 4 wavefronts for M up to 64.
-template <int G, int WGM, int WGN, bool FUSED, int BM, int BN>
+//
+// E8 selects the 8-bit format E0M8 (e0m8_pack.hip; G is then 128, the group of its 4-bit slots): a K slice
+// of 64 is one block, a lane reads two 16-byte chunks of 16 weights per slice, and MFMA number s takes
+// words 2(s%2) and 2(s%2)+1 of chunk s/2, each of which one mask-or (and one more after a rotation) turns
+// into four binade values.
+template <int G, int WGM, int WGN, bool FUSED, int BM, int BN, bool E8 = false>
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
                                                              const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                              half_t* __restrict__ Y, int m_tiles, int n_tiles,
@@ -95,7 +100,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
     const int lane = t & 63;
     const int wave = t >> 6;
     const uint32_t fmask = frac_mask_vgpr();
-    const PackedLayout<G> lay(K);
+    const PackedLayout<G> lay(E8 ? 2 * K : K);
     const int64_t nrb = row_blocks(N);
     const int wm = (wave / WGN) * (BM / WGM), wn = (wave % WGN) * (BN / WGN);
     const int KT = (int)(K / BK);                       // K % 128 == 0 is required by the launcher: KT is even
@@ -133,7 +138,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
             const int64_t nrbh = fu.n_half / kBlockRows;
             rb = min(rb_tile + (wave % WGN) * 2 + ((lane >> 4) & 1), nrbh - 1) - rb_tile + j * nrbh;
         }
-        b_code_off[j] = (uint32_t)rb * rb_stride + (uint32_t)(b_h * kBlockRows + b_r) * 16;
+        // 4-bit: chunk b_h of the slice; 8-bit: chunks 2 b_h and 2 b_h + 1 of the block (the second 256 bytes on)
+        b_code_off[j] = (uint32_t)rb * rb_stride + (uint32_t)((E8 ? 2 * b_h : b_h) * kBlockRows + b_r) * 16;
         b_param_off[j] = (uint32_t)rb * rb_stride + (uint32_t)b_r * 4 + (G == 32 ? b_h * 64 : 0);
     }
 
@@ -144,7 +150,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
         frag_off[s] = (uint32_t)((wm + (lane & 31)) * kRowBytes + (((4 * b_h + s) ^ ((lane >> 1) & 7)) << 4));
 
     u32x4 a_reg[PA];
-    u32x4 bset[2][TN];
+    constexpr int NCH = E8 ? 2 : 1;                     // 16-byte chunks per lane, slice and operand block
+    u32x4 bset[2][TN][NCH];
     uint32_t pwset[2][TN];
     half8_t fa[2][TM], fb[2][TN];
 
@@ -158,11 +165,15 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
         const uint32_t k0 = (uint32_t)min(kt, KT - 1) * BK;
         // chunk (k0/32) of the row block's codes starts (k0/32)*256 bytes in; the parameter words of
         // group k0/G start (k0/G)*64 bytes into the row block's parameters
-        const int code_soff = (int)((k0 / kCodesPerChunk) * (kBlockRows * 16));
-        const int param_soff = (int)((k0 / G) * (kBlockRows * 4));
+        // (8-bit: the slice is block k0/64 of 1 KiB with 16 parameter words)
+        const int code_soff = E8 ? (int)((k0 / BK) * kBlockCodeBytes) : (int)((k0 / kCodesPerChunk) * (kBlockRows * 16));
+        const int param_soff = E8 ? (int)((k0 / BK) * (kBlockRows * 4)) : (int)((k0 / G) * (kBlockRows * 4));
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            bset[set][j] = __builtin_amdgcn_raw_buffer_load_b128(b_code_rsrc, (int)b_code_off[j], code_soff, 0);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c)
+                bset[set][j][c] = __builtin_amdgcn_raw_buffer_load_b128(b_code_rsrc, (int)b_code_off[j] + c * kBlockRows * 16,
+                                                                        code_soff, 0);
             pwset[set][j] = __builtin_amdgcn_raw_buffer_load_b32(b_param_rsrc, (int)b_param_off[j], param_soff, 0);
         }
     };
@@ -179,10 +190,23 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
     auto dequant_frags = [&](int set, int s, half8_t (&dst)[TN]) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const uint32_t word = bset[set][j][s];
             const half_t sc = param_scale(pwset[set][j]), bi = param_bias(pwset[set][j]);
             const half2_t s2 = {sc, sc}, b2 = {bi, bi};
             half2_t o[4];
+            if (E8) {
+                const uint32_t m8 = fmask | (fmask >> 4);       // 0x03FC03FC: eight fraction bits of both halves
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    const uint32_t w8 = bset[set][j][(s >> 1) * (NCH - 1)][2 * (s & 1) + h2];
+                    const uint32_t lo = (w8 & m8) | kExpBits2;
+                    const uint32_t hi = (__builtin_amdgcn_alignbit(w8, w8, 8) & m8) | kExpBits2;
+                    o[2 * h2] = dequant_pair(__builtin_bit_cast(half2_t, lo), b2, s2);
+                    o[2 * h2 + 1] = dequant_pair(__builtin_bit_cast(half2_t, hi), b2, s2);
+                }
+                dst[j] = *reinterpret_cast<const half8_t*>(o);
+                continue;
+            }
+            const uint32_t word = bset[set][j][0][s];
             o[0] = dequant_pair(w1_pair<0>(word, fmask), b2, s2);
             o[1] = dequant_pair(w1_pair<1>(word, fmask), b2, s2);
             o[2] = dequant_pair(w1_pair<2>(word, fmask), b2, s2);
@@ -223,7 +247,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
     };
     using I0 = std::integral_constant<int, 0>;
     using IPA = std::integral_constant<int, PA>;
-    using ITN2 = std::integral_constant<int, 2 * TN>;
+    using ITN2 = std::integral_constant<int, (1 + NCH) * TN>;      // loads issued by load_b
 
     // One K slice.  On entry: stage `cur` holds slice kt; fa[0], fb[0] hold its sub-step 0 operands;
     // bset[set] holds its codes; bset[set^1] and a_reg are in flight for slice kt+1.
@@ -466,7 +490,7 @@ int64_t pipe_tiles(const PipeTile& t, int64_t M, int64_t N, bool swiglu)
     return ((M + t.bm - 1) / t.bm) * n_tiles;
 }
 
-template <int G, int WGM, int WGN, bool FUSED, int BM, int BN>
+template <int G, int WGM, int WGN, bool FUSED, int BM, int BN, bool E8 = false>
 int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, void* workspace,
                 size_t workspace_bytes, hipStream_t stream, const Fusion& f)
 {
@@ -489,12 +513,12 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     constexpr size_t lds = (size_t)kStages * BM * kRowBytes;       // 96 KiB for the large tile: above the default limit
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN, E8>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return record_hip_error(e);
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN>), dim3((unsigned)(per_xcd * kNumXcd)),
+    hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN, E8>), dim3((unsigned)(per_xcd * kNumXcd)),
                        dim3(64 * WGM * WGN), lds, stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial, fu);
     int rc = check_launch();
     if (rc != E0M4_OK || splits == 1) return rc;
@@ -553,6 +577,21 @@ int launch_pipe_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int6
 }
 
 }  // namespace
+
+// 8-bit format: same tiles, K splits and workspace as the 4-bit problem of the same M, N, K.
+int launch_gemm_pipe8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, void* workspace,
+                      size_t workspace_bytes, hipStream_t stream)
+{
+    const half_t* x = static_cast<const half_t*>(X);
+    const uint4* c = static_cast<const uint4*>(packed);
+    half_t* y = static_cast<half_t*>(Y);
+    const Fusion f;
+    const int bm = pipe_tile(M, N, K).bm;
+    if (bm == 64) return launch_pipe<128, 1, 4, false, 64, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+    if (bm == 128)
+        return launch_pipe<128, 2, 2, false, 128, 128, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+    return launch_pipe<128, 2, 4, false, 256, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+}
 
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                      void* workspace, size_t workspace_bytes, hipStream_t stream)

@@ -126,9 +126,28 @@ def test_decode_forced_shapes(e0m4, oracle, waves, target):
         e0m4.e0m4_set_knob("gemv_workgroups", 0)
 
 
+@pytest.mark.parametrize("variant", [2, 3, 4])        # pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
+@pytest.mark.parametrize("splits", [0, 2, 3])
+def test_gemm_kernels(e0m4, oracle, variant, splits):
+    e0m4.e0m4_set_knob("gemm_variant", variant)
+    e0m4.e0m4_set_knob("gemm_splits", splits)
+    try:
+        run_matmul_case(e0m4, oracle, 300, 600, 1024, 128, seed=740 + variant, outliers=True)    # ragged in M and N
+        run_matmul_case(e0m4, oracle, 9, 200, 384, 64, seed=741 + variant)
+        run_matmul_case(e0m4, oracle, 257, 1040, 512, 64, seed=742 + variant)
+    finally:
+        e0m4.e0m4_set_knob("gemm_variant", 0)
+        e0m4.e0m4_set_knob("gemm_splits", 0)
+
+
+@pytest.mark.parametrize("M", [16, 64, 200, 1024])
+def test_gemm_default_choice(e0m4, oracle, M):
+    run_matmul_case(e0m4, oracle, M, 1152, 2048, 128, seed=750 + M, outliers=True)
+
+
 def test_decode_long_rows_and_row_chunks(e0m4, oracle):
     run_matmul_case(e0m4, oracle, 8, 40, 16384, 128, seed=720)      # activations staged in several segments
-    run_matmul_case(e0m4, oracle, 21, 136, 1152, 64, seed=721)      # three launches: 8 + 8 + 5 rows
+    run_matmul_case(e0m4, oracle, 21, 136, 1088, 64, seed=721)      # K = 8.5 x 128: three launches of 8 + 8 + 5 rows
     run_matmul_case(e0m4, oracle, 16, 64, 256, 128, seed=722)
 
 

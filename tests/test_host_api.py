@@ -174,7 +174,9 @@ def test_e0m8_validation_and_sizes(L):
                             ("e0m8_dequant", ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                                             ctypes.c_void_p, ctypes.c_void_p]),
                             ("e0m8_matmul", ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
-                                                           ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p])):
+                                                           ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                                           ctypes.c_size_t, ctypes.c_void_p]),
+                            ("e0m8_workspace_bytes", ctypes.c_size_t, [ctypes.c_int64] * 3 + [ctypes.c_int])):
         getattr(L, name).restype = res
         getattr(L, name).argtypes = args
     p, odd, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008), ctypes.c_void_p(0)
@@ -190,6 +192,10 @@ def test_e0m8_validation_and_sizes(L):
     assert L.e0m8_quantize(null, 64, 128, 64, p, p, p, null) == ERR_NULL
     assert L.e0m8_quantize(odd, 64, 128, 64, p, p, p, null) == ERR_ALIGN
     assert L.e0m8_dequant(p, 64, 128, 64, null, null) == ERR_NULL
-    assert L.e0m8_matmul(p, 1, p, 64, 128, 64, odd, null) == ERR_ALIGN
-    assert L.e0m8_matmul(p, 9, p, 68, 128, 64, p, null) == ERR_SHAPE                    # several row chunks need N % 8 == 0
-    assert L.e0m8_matmul(null, 0, null, 64, 128, 64, null, null) == 0
+    assert L.e0m8_matmul(p, 1, p, 64, 128, 64, odd, null, 0, null) == ERR_ALIGN
+    assert L.e0m8_matmul(p, 9, p, 68, 192, 64, p, null, 0, null) == ERR_SHAPE           # row chunks of Y need N % 8 == 0
+    assert L.e0m8_matmul(null, 0, null, 64, 128, 64, null, null, 0, null) == 0
+    assert L.e0m8_matmul(p, 1024, p, 4096, 13696, 128, p, null, 0, null) == -5          # split K: workspace needed
+    assert L.e0m8_workspace_bytes(8, 4096, 4096, 128) == 0
+    assert L.e0m8_workspace_bytes(1024, 4096, 13696, 128) == L.e0m4_workspace_bytes(1024, 4096, 13696, 128) > 0
+    assert L.e0m8_workspace_bytes(1024, 4096, 192, 64) == 0                             # K % 128 != 0: decode kernel, row chunks
