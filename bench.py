@@ -305,6 +305,22 @@ def main():
                 b = N * K * (1.0 + 4.0 / 64) + 2 * K + 2 * N        # a byte per code, a (scale, bias) word per 64 weights
                 e8[name] = {"N": N, "K": K, "us": round(best, 3), "GBps": round(b / best / 1e3, 1),
                             "frac_hbm": round(b / best / 1e3 / HBM_PEAK_GBPS, 4)}
+                if not args.no_prefill:                 # the same weights at M = 1024 on the MFMA kernels
+                    X = synth_inputs.activations_device(PREFILL_M, K, 8700 + K, dev, outlier_frac=0.01)
+                    Y = torch.empty((PREFILL_M, N), dtype=torch.float16, device=dev)
+                    ws8 = torch.empty(max(e0m4.e0m8_workspace_bytes(PREFILL_M, N, K, GROUP), 16), dtype=torch.uint8, device=dev)
+                    for _ in range(3):
+                        e0m4.e0m8_matmul(X, c8, N, K, GROUP, out=Y, workspace=ws8, stream=stream)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    for _ in range(20):
+                        e0m4.e0m8_matmul(X, c8, N, K, GROUP, out=Y, workspace=ws8, stream=stream)
+                    e1.record(stream)
+                    stream.synchronize()
+                    ms = e0.elapsed_time(e1) / 20
+                    e8[name]["prefill_M%d_ms" % PREFILL_M] = round(ms, 4)
+                    e8[name]["prefill_TFLOPs"] = round(2.0 * PREFILL_M * N * K / ms / 1e9, 1)
+                    del X, Y, ws8
                 del bufs, c8, x, y
         out["e0m8_decode"] = {"workload": "E0M8 (8-bit codes, group %d), M=1, ChatGLM2-6B shapes; latency per launch, "
                                           "cold weights; algorithmic bytes N*K*(1 + 4/64) + 2K + 2N" % GROUP,

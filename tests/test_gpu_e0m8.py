@@ -172,3 +172,22 @@ def test_argument_errors(e0m4):
         e0m4.e0m8_matmul(x, codes, 64, 128, 48)
     assert e0m4.e0m8_codes_bytes(64, 128, 64) == 4 * 2 * (1024 + 64)
     assert e0m4.e0m8_codes_bytes(64, 100, 64) == 0
+
+
+def test_full_size_layer_shapes(e0m4, oracle):
+    """The benchmark's configuration: ChatGLM2-6B shapes, decode output in full, prefill on sampled rows."""
+    for name, N, K in (("gate_up", 27392, 4096), ("down", 4096, 13696)):
+        W = synth_inputs.weights(N, K, seed=760 + N % 13, row_std_range=(0.5, 2.0))
+        codes, What = assert_quantize_exact(e0m4, oracle, W, 128)
+        del W
+        X1 = synth_inputs.activations(1, K, seed=761)
+        Yref, absdot = oracle.matmul(X1, What)
+        check_matmul(e0m4.e0m8_matmul(to_dev(X1), codes, N, K, 128), Yref, absdot, name + " decode")
+        X = synth_inputs.activations(1024, K, seed=762, outlier_frac=0.01)
+        Y = e0m4.e0m8_matmul(to_dev(X), codes, N, K, 128).cpu().numpy()
+        rows = np.array([0, 1, 127, 128, 255, 256, 511, 640, 1023])
+        Yr, ad = oracle.matmul(X[rows], What)
+        check_matmul(torch.from_numpy(Y[rows]), Yr, ad, name + " prefill rows")
+        cols = np.array([0, 15, 16, 255, 256, N // 2, N - 257, N - 1])
+        Yc, adc = oracle.matmul(X, What[cols])
+        check_matmul(torch.from_numpy(np.ascontiguousarray(Y[:, cols])), Yc, adc, name + " prefill cols")
