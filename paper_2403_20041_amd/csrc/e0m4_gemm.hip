@@ -4,9 +4,9 @@
 // section "E0M4 FP4 quantization" fused into the tile loader.
 //
 // This file holds the dispatch between the two GEMM kernels and the small-tile
-// kernel, used for problems too small to fill the chip with 256 x 256 tiles and
-// for K that is not a multiple of 128 (the pipelined kernel is in
-// e0m4_gemm_pipe.hip).
+// kernel, used for problems that give the pipelined kernel too few work items
+// and for K that is not a multiple of 128 (the pipelined kernel, with its three
+// tile shapes, is in e0m4_gemm_pipe.hip).
 //
 // A workgroup (4 wavefronts, 2 x 2) owns a BM x BN tile of Y and walks K in
 // slices of 64.  Per slice the activations go global -> registers -> LDS

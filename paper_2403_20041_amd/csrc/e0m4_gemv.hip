@@ -14,11 +14,14 @@
 // binade values with one rotate and four mask-or per eight codes, accumulates
 // a = sum x*w1 with v_dot2_f32_f16, and applies the group's affine map once per
 // block:  y += scale * (a - bias * sum x).
-// Activations come from LDS (staged once per workgroup, with the sums of every
-// 32-wide chunk).  The four k-quarters of a row are added with two cross-lane
-// steps, the wavefronts' sums through LDS in a fixed order (deterministic
-// result).  (Keeping the activations in registers instead was measured slower:
-// a wavefront handles too few blocks to repay loading them.)
+// Activations are staged once per workgroup in LDS, with the sums of every
+// 32-wide chunk; a wavefront that meets the same k blocks in every row block
+// (M = 1, see XREG below) copies them to registers once, otherwise they are read
+// from LDS block by block.  The four k-quarters of a row are added with two
+// cross-lane steps, the wavefronts' sums through LDS in a fixed order
+// (deterministic result).  The same kernel serves the INT4 comparison format and
+// the 8-bit format E0M8 (template argument DEQ) and, as FUSED, folds in the
+// operators of e0m4_matmul_fused.
 #include "e0m4_device.h"
 #include "e0m4_host.h"
 
