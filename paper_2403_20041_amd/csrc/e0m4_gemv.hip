@@ -121,6 +121,9 @@ enum { kDeqE0M4 = 0, kDeqInt4Convert = 1, kDeqE0M8 = 2 };
 // FUSED adds the operators of GemvFusion (e0m4_device.h) to the kernel.
 // XREG (M = 1, one segment, wavefront count a multiple of the work items per row block): a wavefront meets
 // the same four k blocks in every row block and keeps their activations and chunk sums in registers.
+// (They are copied from the staged LDS copy: letting every lane request its 4 x 64 bytes of X from memory
+// instead, without staging and its barrier, measured 3-6 % slower: sixteen more load instructions per
+// lane queue up ahead of the weights.)
 template <int G, int M, int W, int DEQ = kDeqE0M4, bool FUSED = false, bool XREG = false>
 __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__ X, const uint4* __restrict__ packed,
                                                       int64_t N, int64_t K, half_t* __restrict__ Y, int seg_items,
