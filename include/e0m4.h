@@ -203,7 +203,8 @@ int e0m4_kv_append(void* cache_f16, int64_t max_seq, int64_t row_elems,
  *     [N, K/group] fp16.
  *   - e0m8_unpack_codes writes one byte per weight, [N, K] row-major.
  *   - e0m8_matmul: Y[M,N] = X[M,K] * dequant(codes)^T, fp32 accumulation, one
- *     rounding.  M <= 8: the HBM-bound decode kernel.  M > 8 with K % 128 == 0
+ *     rounding.  M <= 8: the HBM-bound decode kernel (2 <= M <= 16 with X
+ *     fitting the LDS: its matrix-core variant).  M > 8 with K % 128 == 0
  *     (and N <= 2^24): the MFMA GEMM kernels, workspace of
  *     e0m8_workspace_bytes() bytes under the rules of e0m4_matmul.  Other M > 8:
  *     the decode kernel on 8 rows of X at a time (needs N % 8 == 0).

@@ -340,9 +340,14 @@ int e0m8_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
 }
 
 // The pipelined GEMM serves M > 8 when K is a multiple of 128 (its K slices come in pairs).
+static bool e0m8_use_mfma_decode(int64_t M, int64_t N, int64_t K)
+{
+    return knob("gemv_mfma") != 1 && gemv_mfma8_supported(M, N, K);
+}
+
 static bool e0m8_use_gemm(int64_t M, int64_t N, int64_t K)
 {
-    return M > kGemvMaxM && gemm_pipe_supported(K) && N <= (int64_t)1 << 24;
+    return !e0m8_use_mfma_decode(M, N, K) && M > kGemvMaxM && gemm_pipe_supported(K) && N <= (int64_t)1 << 24;
 }
 
 size_t e0m8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
@@ -368,6 +373,7 @@ int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t 
     }
     if (!X || !codes) return E0M4_ERR_NULL;
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    if (e0m8_use_mfma_decode(M, N, K)) return launch_gemv_mfma8(X, M, codes, N, K, Y, (hipStream_t)stream);
     if (e0m8_use_gemm(M, N, K)) {
         if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
         return launch_gemm_pipe8(X, M, codes, N, K, Y, workspace, workspace_bytes, (hipStream_t)stream);

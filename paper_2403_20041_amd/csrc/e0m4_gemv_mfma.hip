@@ -52,9 +52,10 @@ struct MfmaPlan {
 
 constexpr int kNormBytes = (16 + 1) * kMaxM * 4;        // rms-norm: per-wavefront sums of squares and the row scales
 
-size_t lds_need(int64_t M, int64_t nkb, int waves)
+// (nkb blocks of 128 4-bit codes or of 64 8-bit codes: 256 or 128 bytes of X per row and block)
+size_t lds_need(int64_t M, int64_t nkb, int waves, bool e8 = false)
 {
-    return (size_t)M * (nkb * kXBlockBytes + kRowPadBytes) +
+    return (size_t)M * (nkb * (e8 ? kXBlockBytes / 2 : kXBlockBytes) + kRowPadBytes) +
            2 * (size_t)waves * kMaxM * kBlockRows * sizeof(float) + kNormBytes;
 }
 
@@ -67,7 +68,10 @@ __device__ inline int x_unit_off(int q, int w, int hl) { return ((q * 4 + (w >> 
 // XREG: the wavefront count is a multiple of the work items per row block, so a wavefront meets the same
 // four k blocks in every row block and keeps their activation operands in registers (64 per lane)
 // instead of reading them from LDS for every weight block.
-template <int W, bool FUSED, bool XREG>
+// E8: the 8-bit format E0M8 (e0m8_pack.hip).  A block holds 64 weights, a lane's chunk 16, and one MFMA
+// takes the eight weights of two words per lane, each word turned into two pairs of binade values by a
+// mask-or and a rotation; there is only one kind of code slot, so one accumulator and the plain sum of X.
+template <int W, bool FUSED, bool XREG, bool E8 = false>
 __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restrict__ X, int M,
                                                            const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                            half_t* __restrict__ Y, int step_slots, int step_item,
@@ -75,10 +79,12 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 {
     constexpr int kThreads = W * 64;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const PackedLayout<kG> lay(K);
+    constexpr int XBB = E8 ? kXBlockBytes / 2 : kXBlockBytes;   // bytes of X per row and block
+    constexpr int UB = E8 ? 16 : 32;                            // bytes per (k-group, MFMA pair) unit of a block
+    const PackedLayout<kG> lay(E8 ? 2 * K : K);
     const int nkb = (int)lay.nkb;
     const int nsi = (nkb + kSuper - 1) / kSuper;
-    const int row_stride = nkb * kXBlockBytes + kRowPadBytes;
+    const int row_stride = nkb * XBB + kRowPadBytes;
     unsigned char* xs = smem;                                                   // [M] rows of X in MFMA order
     float* red = reinterpret_cast<float*>(smem + (size_t)M * row_stride);       // [2][W][16 m][16 n]
     float* norm_part = red + 2 * W * kMaxM * kBlockRows;                        // [W][16] sums of squares, then [16] row scales
@@ -142,7 +148,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 
     // ---- stage X: thread idx handles the 8 elements k = 8*pc..8*pc+7 of row m; 16 consecutive threads
     // cover one block of one row
-    const int pieces = nkb * (kBlockK / 8);
+    const int pieces = nkb * (XBB / 16);
     const bool normed = FUSED && fu.gamma != nullptr;
     if (normed) {
         // rms-norm: sum of squares of every row (first pass over X; the staging pass below reads it again,
@@ -219,11 +225,16 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
                 for (int i = 0; i < 8; ++i) v[i] = (half_t)(((float)v[i] * r) * (float)gb[u][i]);
             }
             if (idx < M * pieces) {
-                const int kb = pc >> 4, q = (pc >> 2) & 3, w = pc & 3;
-                unsigned char* blk = xs + (size_t)m * row_stride + kb * kXBlockBytes;
-                const half4_t hpart = {v[0], v[1], v[6], v[7]}, lpart = {v[2], v[3], v[4], v[5]};
-                *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 0)) = hpart;
-                *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 1)) = lpart;
+                if (E8) {                               // piece = the 8 weights of (k-group q, MFMA wp)
+                    const int kb = pc >> 3, q = (pc >> 1) & 3, wp = pc & 1;
+                    *reinterpret_cast<half8_t*>(xs + (size_t)m * row_stride + kb * XBB + q * 2 * UB + wp * UB) = v;
+                } else {
+                    const int kb = pc >> 4, q = (pc >> 2) & 3, w = pc & 3;
+                    unsigned char* blk = xs + (size_t)m * row_stride + kb * XBB;
+                    const half4_t hpart = {v[0], v[1], v[6], v[7]}, lpart = {v[2], v[3], v[4], v[5]};
+                    *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 0)) = hpart;
+                    *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 1)) = lpart;
+                }
             }
         }
     }
@@ -231,17 +242,17 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 
     // X operand address of this lane: row min(l%16, M-1) (rows beyond M repeat the last one; their
     // results are never stored), k-group l/16
-    const unsigned char* x_lane = xs + (size_t)min(n_l, M - 1) * row_stride + g_l * 64;
+    const unsigned char* x_lane = xs + (size_t)min(n_l, M - 1) * row_stride + g_l * 2 * UB;
 
     half8_t xreg_h[XREG ? kSuper : 1][2], xreg_l[XREG ? kSuper : 1][2];
     if (XREG) {
 #pragma unroll
         for (int j = 0; j < kSuper; ++j) {
-            const unsigned char* xb = x_lane + (size_t)min(si * kSuper + j, nkb - 1) * kXBlockBytes;
+            const unsigned char* xb = x_lane + (size_t)min(si * kSuper + j, nkb - 1) * XBB;
 #pragma unroll
             for (int wp = 0; wp < 2; ++wp) {
-                xreg_h[j][wp] = *reinterpret_cast<const half8_t*>(xb + wp * 32);
-                xreg_l[j][wp] = *reinterpret_cast<const half8_t*>(xb + wp * 32 + 16);
+                xreg_h[j][wp] = *reinterpret_cast<const half8_t*>(xb + wp * UB);
+                xreg_l[j][wp] = E8 ? xreg_h[j][wp] : *reinterpret_cast<const half8_t*>(xb + wp * UB + 16);
             }
         }
     }
@@ -255,7 +266,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 #pragma unroll
         for (int wp = 0; wp < 2; ++wp) {
             sh = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh[wp], ones8, sh, 0, 0, 0);
-            sl = __builtin_amdgcn_mfma_f32_16x16x32_f16(xl[wp], ones8, sl, 0, 0, 0);
+            if (!E8) sl = __builtin_amdgcn_mfma_f32_16x16x32_f16(xl[wp], ones8, sl, 0, 0, 0);
         }
         sx = sh + sl;
         sx30 = 30.f * sl;
@@ -282,18 +293,33 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
                 const uint32_t words[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
                 half2_t p[4][4];
 #pragma unroll
-                for (int w = 0; w < 4; ++w) w1_pairs_mixed(words[w], fmask, fmask_low, p[w]);
+                for (int w = 0; w < 4; ++w) {
+                    if (E8) {                           // (w1_0, w1_1) and, after the rotation, (w1_2, w1_3)
+                        const uint32_t m8 = fmask | fmask_low;
+                        p[w][0] = __builtin_bit_cast(half2_t, (words[w] & m8) | kExpBits2);
+                        p[w][1] = __builtin_bit_cast(half2_t, (__builtin_amdgcn_alignbit(words[w], words[w], 8) & m8) | kExpBits2);
+                    } else {
+                        w1_pairs_mixed(words[w], fmask, fmask_low, p[w]);
+                    }
+                }
                 fetch_code(j, nslot, nitem);            // the block's registers are free: request the next item's
                 floatx4 acc_h = zero4, acc_l = zero4;
-                const unsigned char* xb = x_lane + (size_t)min(kb, nkb - 1) * kXBlockBytes;
+                const unsigned char* xb = x_lane + (size_t)min(kb, nkb - 1) * XBB;
                 half8_t xh2[2], xl2[2];
 #pragma unroll
                 for (int wp = 0; wp < 2; ++wp) {
-                    xh2[wp] = XREG ? xreg_h[XREG ? j : 0][wp] : *reinterpret_cast<const half8_t*>(xb + wp * 32);
-                    xl2[wp] = XREG ? xreg_l[XREG ? j : 0][wp] : *reinterpret_cast<const half8_t*>(xb + wp * 32 + 16);
+                    xh2[wp] = XREG ? xreg_h[XREG ? j : 0][wp] : *reinterpret_cast<const half8_t*>(xb + wp * UB);
+                    xl2[wp] = E8 ? xh2[wp] : XREG ? xreg_l[XREG ? j : 0][wp] : *reinterpret_cast<const half8_t*>(xb + wp * UB + 16);
                 }
 #pragma unroll
                 for (int wp = 0; wp < 2; ++wp) {
+                    if (E8) {
+                        const half2_t* w0 = p[2 * wp];
+                        const half2_t* w1 = p[2 * wp + 1];
+                        const half8_t w8 = {w0[0][0], w0[0][1], w0[1][0], w0[1][1], w1[0][0], w1[0][1], w1[1][0], w1[1][1]};
+                        acc_h = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh2[wp], w8, acc_h, 0, 0, 0);
+                        continue;
+                    }
                     const half8_t xh = xh2[wp], xl = xl2[wp];
                     const half2_t* w0 = p[2 * wp];
                     const half2_t* w1 = p[2 * wp + 1];
@@ -365,14 +391,15 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 }
 
 // `unit`: 2 when row blocks are dealt in (gate, up) pairs; rb_base and rb_rem then count pairs
-bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1)
+// (e8: K counts 4-bit slots, two per weight, and a block of X is half as long)
+bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, bool e8 = false)
 {
     const int64_t nrb = row_blocks(N) / unit, nkb = k_blocks(K);
     const int64_t nsi = (nkb + kSuper - 1) / kSuper;
     int w = knob("gemv_waves");
     if (w != 4 && w != 8 && w != 16) w = nsi >= 16 ? 16 : 8;
-    while (w > 4 && lds_need(M, nkb, w) > (size_t)kLdsLimitBytes) w /= 2;
-    if (lds_need(M, nkb, w) > (size_t)kLdsLimitBytes) return false;
+    while (w > 4 && lds_need(M, nkb, w, e8) > (size_t)kLdsLimitBytes) w /= 2;
+    if (lds_need(M, nkb, w, e8) > (size_t)kLdsLimitBytes) return false;
     int target = knob("gemv_workgroups");
     if (target <= 0) target = kTargetWorkgroups;
     p.grid = std::min<int64_t>(nrb, target);
@@ -381,22 +408,22 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1)
     p.step_item = (int)(w % nsi);
     p.rb_base = (int)(nrb / p.grid);
     p.rb_rem = (int)(nrb % p.grid);
-    p.lds_bytes = lds_need(M, nkb, w);
+    p.lds_bytes = lds_need(M, nkb, w, e8);
     return true;
 }
 
-template <int W, bool FUSED, bool XREG>
+template <int W, bool FUSED, bool XREG, bool E8 = false>
 int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                   hipStream_t stream, const GemvFusion& fu)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED, XREG>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED, XREG, E8>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimitBytes);
         if (e != hipSuccess) return record_hip_error(e);
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
+    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
                        static_cast<const half_t*>(X), (int)M, static_cast<const uint4*>(packed), N, K,
                        static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, fu);
     return check_launch();
@@ -430,6 +457,33 @@ int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, in
         case 4: return launch_mfma<4, false>(p, X, M, packed, N, K, Y, stream);
         case 8: return launch_mfma<8, false>(p, X, M, packed, N, K, Y, stream);
         default: return launch_mfma<16, false>(p, X, M, packed, N, K, Y, stream);
+    }
+}
+
+// 8-bit format: K in weights; group 64 or 128 (the packed buffer carries one parameter word per block either way).
+bool gemv_mfma8_supported(int64_t M, int64_t N, int64_t K)
+{
+    if (M < kMinM || M > kMaxM || N <= 0 || K <= 0) return false;
+    MfmaPlan p;
+    return make_mfma_plan(M, N, 2 * K, p, 1, true);
+}
+
+int launch_gemv_mfma8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+{
+    MfmaPlan p;
+    if (!make_mfma_plan(M, N, 2 * K, p, 1, true)) return E0M4_ERR_SHAPE;
+    const GemvFusion fu{};
+    const bool xreg = p.step_item == 0 && knob("gemv_mfma") != 2;
+    switch (p.waves) {
+        case 4:
+            return xreg ? launch_mfma_x<4, false, true, true>(p, X, M, packed, N, K, Y, stream, fu)
+                        : launch_mfma_x<4, false, false, true>(p, X, M, packed, N, K, Y, stream, fu);
+        case 8:
+            return xreg ? launch_mfma_x<8, false, true, true>(p, X, M, packed, N, K, Y, stream, fu)
+                        : launch_mfma_x<8, false, false, true>(p, X, M, packed, N, K, Y, stream, fu);
+        default:
+            return xreg ? launch_mfma_x<16, false, true, true>(p, X, M, packed, N, K, Y, stream, fu)
+                        : launch_mfma_x<16, false, false, true>(p, X, M, packed, N, K, Y, stream, fu);
     }
 }
 

@@ -126,6 +126,39 @@ def test_decode_forced_shapes(e0m4, oracle, waves, target):
         e0m4.e0m4_set_knob("gemv_workgroups", 0)
 
 
+@pytest.mark.parametrize("M", [2, 3, 5, 8, 9, 13, 16])
+def test_small_batch_matrix_core_kernel(e0m4, oracle, M):
+    run_matmul_case(e0m4, oracle, M, 200, 1152, 64, seed=770 + M)                   # 18 blocks: ragged last work item
+    run_matmul_case(e0m4, oracle, M, 333, 4096, 128, seed=771 + M, outliers=True)   # 16 work items per row block
+    run_matmul_case(e0m4, oracle, M, 40, 64, 64, seed=772 + M)                      # a single block
+    run_matmul_case(e0m4, oracle, M, 1000, 2048, 128, seed=773 + M)                 # 8 work items: activations in registers
+
+
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("mode", [0, 2])                # 2: activations always from LDS
+def test_small_batch_matrix_core_kernel_forced_shapes(e0m4, oracle, waves, mode):
+    e0m4.e0m4_set_knob("gemv_waves", waves)
+    e0m4.e0m4_set_knob("gemv_workgroups", 3)
+    e0m4.e0m4_set_knob("gemv_mfma", mode)
+    try:
+        run_matmul_case(e0m4, oracle, 6, 300, 1024, 128, seed=780 + waves)
+        run_matmul_case(e0m4, oracle, 16, 130, 2048, 64, seed=781 + waves)
+    finally:
+        e0m4.e0m4_set_knob("gemv_waves", 0)
+        e0m4.e0m4_set_knob("gemv_workgroups", 0)
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+
+
+@pytest.mark.parametrize("M", [2, 8, 12])
+def test_small_batch_other_kernels_when_the_matrix_core_kernel_is_off(e0m4, oracle, M):
+    e0m4.e0m4_set_knob("gemv_mfma", 1)
+    try:
+        run_matmul_case(e0m4, oracle, M, 200, 1152, 64, seed=790 + M)
+        run_matmul_case(e0m4, oracle, M, 336, 4096, 128, seed=791 + M)
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+
+
 @pytest.mark.parametrize("variant", [2, 3, 4])        # pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
 @pytest.mark.parametrize("splits", [0, 2, 3])
 def test_gemm_kernels(e0m4, oracle, variant, splits):
