@@ -43,6 +43,7 @@ constexpr int kLdsLimitBytes = 156 * 1024;      // of the 160 KiB of a compute u
 constexpr int kTargetWorkgroups = 256;          // one workgroup per compute unit
 
 struct MfmaPlan {
+    int late;                                   // reduce the wavefront sums once at the end (they fit the LDS)
     int waves;
     int step_slots, step_item;                  // a wavefront's next work item: W items ahead, as (row blocks, items) with carry
     int rb_base, rb_rem;                        // even deal of row blocks
@@ -57,6 +58,12 @@ size_t lds_need(int64_t M, int64_t nkb, int waves, bool e8 = false)
 {
     return (size_t)M * (nkb * (e8 ? kXBlockBytes / 2 : kXBlockBytes) + kRowPadBytes) +
            2 * (size_t)waves * kMaxM * kBlockRows * sizeof(float) + kNormBytes;
+}
+
+// LDS for the wavefront sums of all `slots` row blocks of a workgroup at once
+size_t late_red_bytes(int64_t M, int slots, int waves)
+{
+    return (size_t)slots * waves * M * kBlockRows * sizeof(float);
 }
 
 // Byte offset, inside one block of one row of X, of the 8-byte half-unit that holds the elements of
@@ -75,7 +82,7 @@ template <int W, bool FUSED, bool XREG, bool E8 = false>
 __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restrict__ X, int M,
                                                            const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                            half_t* __restrict__ Y, int step_slots, int step_item,
-                                                           int rb_base, int rb_rem, GemvFusion fu)
+                                                           int rb_base, int rb_rem, int late, GemvFusion fu)
 {
     constexpr int kThreads = W * 64;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -86,8 +93,10 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     const int nsi = (nkb + kSuper - 1) / kSuper;
     const int row_stride = nkb * XBB + kRowPadBytes;
     unsigned char* xs = smem;                                                   // [M] rows of X in MFMA order
-    float* red = reinterpret_cast<float*>(smem + (size_t)M * row_stride);       // [2][W][16 m][16 n]
-    float* norm_part = red + 2 * W * kMaxM * kBlockRows;                        // [W][16] sums of squares, then [16] row scales
+    float* norm_part = reinterpret_cast<float*>(smem + (size_t)M * row_stride); // [W][16] sums of squares, then [16] row scales
+    // wavefront sums: [2][W][16 m][16 n], reduced row block by row block; or, when `late` (LDS permitting),
+    // [row blocks][W][M][16 n], reduced once at the end without a barrier per row block
+    float* red = norm_part + kNormBytes / 4;
 
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -345,6 +354,12 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
             si = nitem;
             advance(nslot, nitem);
         }
+        if (late) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (4 * g_l + r < M) red[((s_rb * W + wave) * M + 4 * g_l + r) * kBlockRows + n_l] = ysum[r];
+            continue;
+        }
         if (gated) {
             // slot 2p is the gate block and slot 2p + 1 the up block of pair p: park the gate sums in
             // half 0 of `red`, the up sums in half 1, then combine
@@ -388,6 +403,29 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
         // no second barrier: row block s_rb + 1 uses the other half of `red`, and nobody writes this
         // half again before passing the barrier of s_rb + 1, which the readers above reach after reading
     }
+    if (late) {
+        __syncthreads();
+        const int units = gated ? n_rb / 2 : n_rb;      // one result per (row block or pair, row of X, weight row)
+        for (int idx = t; idx < units * M * kBlockRows; idx += kThreads) {
+            const int u = idx / (M * kBlockRows), m = (idx / kBlockRows) % M, n = idx % kBlockRows;
+            const int sl = gated ? 2 * u : u;
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < W; ++w) v += red[((sl * W + w) * M + m) * kBlockRows + n];
+            if (gated) {
+                float up = 0.f;
+#pragma unroll
+                for (int w = 0; w < W; ++w) up += red[(((sl + 1) * W + w) * M + m) * kBlockRows + n];
+                v = silu_f32(v) * up;
+            }
+            const int64_t n_out = gated ? fu.n_out : N;
+            const int64_t col = (rb0 + u) * kBlockRows + n;
+            if (col < n_out) {
+                if (FUSED && fu.residual) v += (float)fu.residual[(int64_t)m * n_out + col];
+                Y[(int64_t)m * n_out + col] = (half_t)v;
+            }
+        }
+    }
 }
 
 // `unit`: 2 when row blocks are dealt in (gate, up) pairs; rb_base and rb_rem then count pairs
@@ -409,6 +447,10 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, 
     p.rb_base = (int)(nrb / p.grid);
     p.rb_rem = (int)(nrb % p.grid);
     p.lds_bytes = lds_need(M, nkb, w, e8);
+    const size_t per_rb = 2 * (size_t)w * kMaxM * kBlockRows * sizeof(float);
+    const size_t late_bytes = late_red_bytes(M, (p.rb_base + 1) * unit, w);
+    p.late = knob("gemv_mfma") != 3 && p.lds_bytes - per_rb + late_bytes <= (size_t)kLdsLimitBytes;
+    if (p.late) p.lds_bytes = p.lds_bytes - per_rb + std::max(late_bytes, (size_t)16);
     return true;
 }
 
@@ -425,7 +467,7 @@ int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packe
     }
     hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
                        static_cast<const half_t*>(X), (int)M, static_cast<const uint4*>(packed), N, K,
-                       static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, fu);
+                       static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.late, fu);
     return check_launch();
 }
 

@@ -117,6 +117,16 @@ def test_small_batch_matrix_core_kernel(e0m4, oracle, M, norm, swiglu, res):
     run_fused(e0m4, oracle, M, 333 if not swiglu else 448, 1664, 128, seed=520 + M, norm=norm, swiglu=swiglu, res=res)
 
 
+@pytest.mark.parametrize("M", [2, 6, 16])
+def test_small_batch_matrix_core_kernel_reduction_per_row_block(e0m4, oracle, M):
+    e0m4.e0m4_set_knob("gemv_mfma", 3)
+    try:
+        run_fused(e0m4, oracle, M, 1088, 2048, 128, seed=525 + M, norm=True, swiglu=True, res=True)
+        run_fused(e0m4, oracle, M, 333, 1664, 128, seed=526 + M, norm=True, res=True)
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+
+
 @pytest.mark.parametrize("waves", [4, 8, 16])
 @pytest.mark.parametrize("target", [0, 3])
 def test_small_batch_matrix_core_kernel_forced_shapes(e0m4, oracle, waves, target):

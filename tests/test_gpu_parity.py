@@ -257,6 +257,17 @@ def test_small_batch_matrix_core_kernel_forced_shapes(e0m4, oracle, waves, targe
         e0m4.e0m4_set_knob("gemv_workgroups", 0)
 
 
+@pytest.mark.parametrize("M", [2, 5, 16])
+def test_small_batch_matrix_core_kernel_reduction_per_row_block(e0m4, oracle, M):
+    # knob value 3: the wavefront sums are reduced after every row block even where all of them fit the LDS
+    e0m4.e0m4_set_knob("gemv_mfma", 3)
+    try:
+        run_matmul_case(e0m4, oracle, M, 1000, 2048, 128, seed=172 + M)
+        run_matmul_case(e0m4, oracle, M, 200, 1152, 128, seed=173 + M)
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+
+
 @pytest.mark.parametrize("M", [3, 16])
 def test_small_batch_matrix_core_kernel_activations_from_lds(e0m4, oracle, M):
     # K = 4096 with 8 wavefronts would keep the activations in registers; knob value 2 reads them from LDS
