@@ -216,6 +216,13 @@ int e0m8_quantize(const void* W_f16, int64_t N, int64_t K, int group,
 int e0m8_dequant(const void* codes, int64_t N, int64_t K, int group, void* W_f16_out, void* stream);
 int e0m8_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* codes_u8_out, void* stream);
 size_t e0m8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
+/* e0m4_matmul_fused on 8-bit codes: same operators, arguments and rules (N a multiple of 64 for the gated
+ * epilogue).  M > 16, or M > 8 when X does not fit the LDS, needs K % 128 == 0 (E0M4_ERR_SHAPE otherwise). */
+size_t e0m8_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int group, int with_rmsnorm, int epilogue);
+int e0m8_matmul_fused(const void* X_f16, int64_t M, const void* rms_gamma_f16, float rms_eps,
+                      const void* codes, int64_t N, int64_t K, int group,
+                      int epilogue, const void* residual_f16,
+                      void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
 int e0m8_matmul(const void* X_f16, int64_t M, const void* codes, int64_t N, int64_t K, int group,
                 void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
 

@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     e0m8_codes_bytes,
     e0m8_dequant,
     e0m8_matmul,
+    e0m8_matmul_fused,
     e0m8_quantize,
     e0m8_unpack_codes,
     e0m8_workspace_bytes,

@@ -75,6 +75,10 @@ def lib() -> ctypes.CDLL:
     L.e0m8_unpack_codes.argtypes = [vp, i64, i64, ci, vp, vp]
     L.e0m8_matmul.restype = ci
     L.e0m8_matmul.argtypes = [vp, i64, vp, i64, i64, ci, vp, vp, sz, vp]
+    L.e0m8_fused_workspace_bytes.restype = sz
+    L.e0m8_fused_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci]
+    L.e0m8_matmul_fused.restype = ci
+    L.e0m8_matmul_fused.argtypes = [vp, i64, vp, ctypes.c_float, vp, i64, i64, ci, ci, vp, vp, vp, sz, vp]
     L.e0m8_workspace_bytes.restype = sz
     L.e0m8_workspace_bytes.argtypes = [i64, i64, i64, ci]
     L.e0m4_kv_append.restype = ci
@@ -292,6 +296,29 @@ def e0m8_matmul(X, codes, N: int, K: int, group: int, out=None, workspace=None, 
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().e0m8_matmul(_ptr(X), M, _ptr(codes), N, K, group, _ptr(out), _ptr(workspace), ws_bytes,
                              _stream(stream)), "e0m8_matmul")
+    return out
+
+
+def e0m8_matmul_fused(X, codes, N: int, K: int, group: int, rms_gamma=None, rms_eps: float = 0.0,
+                      epilogue: int = E0M4_EPILOGUE_NONE, residual=None, out=None, workspace=None, stream=None):
+    """e0m4_matmul_fused on 8-bit codes."""
+    M = X.shape[0]
+    _need(X, torch.float16, (M, K), "X")
+    n_out = N // 2 if epilogue == E0M4_EPILOGUE_SWIGLU else N
+    if rms_gamma is not None:
+        _need(rms_gamma, torch.float16, (K,), "rms_gamma")
+    if residual is not None:
+        _need(residual, torch.float16, (M, n_out), "residual")
+    if out is None:
+        out = torch.empty((M, n_out), dtype=torch.float16, device=X.device)
+    _need(out, torch.float16, (M, n_out), "out")
+    need = lib().e0m8_fused_workspace_bytes(M, N, K, group, 1 if rms_gamma is not None else 0, epilogue)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().e0m8_matmul_fused(_ptr(X), M, _ptr(rms_gamma), float(rms_eps), _ptr(codes), N, K, group, epilogue,
+                                   _ptr(residual), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream)),
+           "e0m8_matmul_fused")
     return out
 
 

@@ -389,6 +389,66 @@ int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t 
     return E0M4_OK;
 }
 
+// Fused matmul on 8-bit codes: 2 the small-batch kernel, 0 the decode kernel, 1 the GEMM kernels (K % 128 == 0), -1 none.
+static int fused_path8(const Fusion& f, int64_t M, int64_t N, int64_t K)
+{
+    if (knob("gemv_mfma") != 1 && gemv_mfma8_fused_supported(f, M, N, K)) return 2;
+    if (M <= kGemvMaxM && gemv_fused_supported(f, M, N, 2 * K)) return 0;
+    return gemm_pipe_supported(K) && N <= (int64_t)1 << 24 ? 1 : -1;
+}
+
+size_t e0m8_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int group, int with_rmsnorm, int epilogue)
+{
+    if (check_shape8(N, K, group) != E0M4_OK || M <= 0 || N == 0 || K == 0) return 0;
+    if (epilogue != E0M4_EPILOGUE_NONE && epilogue != E0M4_EPILOGUE_SWIGLU) return 0;
+    Fusion f;
+    f.swiglu = epilogue == E0M4_EPILOGUE_SWIGLU;
+    if (fused_path8(f, M, N, K) != 1) return 0;
+    return (with_rmsnorm ? norm_bytes(M, K) : 0) + gemm_pipe_workspace_bytes(M, N, K, f.swiglu);
+}
+
+int e0m8_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms_eps, const void* codes, int64_t N,
+                      int64_t K, int group, int epilogue, const void* residual, void* Y, void* workspace,
+                      size_t workspace_bytes, void* stream)
+{
+    int rc = check_shape8(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (M < 0 || M > (int64_t)1 << 31) return E0M4_ERR_SHAPE;
+    if (epilogue != E0M4_EPILOGUE_NONE && epilogue != E0M4_EPILOGUE_SWIGLU) return E0M4_ERR_SHAPE;
+    Fusion f;
+    f.gamma = rms_gamma;
+    f.eps = rms_eps;
+    f.residual = residual;
+    f.swiglu = epilogue == E0M4_EPILOGUE_SWIGLU;
+    if (f.swiglu && (N % (4 * kBlockRows)) != 0) return E0M4_ERR_SHAPE;
+    if (M == 0 || N == 0) return E0M4_OK;
+    if (K == 0) return E0M4_ERR_SHAPE;
+    if (!X || !codes || !Y) return E0M4_ERR_NULL;
+    if (!aligned16(X) || !aligned16(codes) || !aligned16(Y) || (rms_gamma && !aligned16(rms_gamma)) ||
+        (residual && !aligned16(residual)))
+        return E0M4_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    const int path = fused_path8(f, M, N, K);
+    if (path == 2) return launch_gemv_mfma8_fused(f, X, M, codes, N, K, Y, st);
+    if (path == 0) return launch_gemv8_fused(f, X, M, codes, N, K, Y, st);
+    if (path != 1) return E0M4_ERR_SHAPE;               // larger M needs K % 128 == 0 (GEMM kernels)
+    const size_t nb = rms_gamma ? norm_bytes(M, K) : 0;
+    const size_t need = nb + gemm_pipe_workspace_bytes(M, N, K, f.swiglu);
+    if (need > 0) {
+        if (!workspace) return E0M4_ERR_NULL;
+        if (!aligned16(workspace)) return E0M4_ERR_ALIGN;
+        if (workspace_bytes < need) return E0M4_ERR_WORKSPACE;
+    }
+    const void* x = X;
+    if (rms_gamma) {
+        rc = launch_rmsnorm(X, M, K, rms_gamma, rms_eps, workspace, st);
+        if (rc != E0M4_OK) return rc;
+        x = workspace;
+        f.gamma = nullptr;
+    }
+    return launch_gemm_pipe8_fused(f, x, M, codes, N, K, Y, static_cast<char*>(workspace) + nb, workspace_bytes - nb, st);
+}
+
 int e0m4_kv_append(void* cache, int64_t max_seq, int64_t row_elems, const void* new_rows, int64_t n_new,
                    int64_t new_ld, const void* position_ids, void* stream)
 {

@@ -593,6 +593,20 @@ int launch_gemm_pipe8(const void* X, int64_t M, const void* packed, int64_t N, i
     return launch_pipe<128, 2, 4, false, 256, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
 }
 
+int launch_gemm_pipe8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                            void* workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    const half_t* x = static_cast<const half_t*>(X);
+    const uint4* c = static_cast<const uint4*>(packed);
+    half_t* y = static_cast<half_t*>(Y);
+    if (f.swiglu && (N % (2 * kBlockRows) != 0 || gated_half_bytes(N, 2 * K, 128) > kMaxHalfBytes)) return E0M4_ERR_SHAPE;
+    const int bm = pipe_tile(M, N, K).bm;
+    if (bm == 64) return launch_pipe<128, 1, 4, true, 64, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+    if (bm == 128)
+        return launch_pipe<128, 2, 2, true, 128, 128, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+    return launch_pipe<128, 2, 4, true, 256, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+}
+
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                      void* workspace, size_t workspace_bytes, hipStream_t stream)
 {

@@ -630,17 +630,20 @@ int launch_gemv_fused(const Fusion& f, const void* X, int64_t M, const void* pac
     }
 }
 
-// 8-bit format, M <= 8: the packed buffer is a 4-bit layout of 2K codes with groups of 128.
-int launch_gemv8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+// 8-bit format, M <= 8: the packed buffer is a 4-bit layout of 2K codes with groups of 128.  `f`: fused
+// operators, or null.
+namespace {
+template <bool FUSED>
+int launch_gemv8_m(const GemvPlan& p, const GemvFusion& fu, const void* X, int64_t M, const void* packed, int64_t N,
+                   int64_t K, void* Y, hipStream_t stream)
 {
-    const GemvPlan p = make_plan(M, N, 2 * K);
     auto go = [&](auto m_tag) -> int {
         constexpr int MM = decltype(m_tag)::value;
         switch (p.waves) {
-            case 4: return launch_one<128, MM, 4, kDeqE0M8>(p, X, packed, N, K, Y, stream);
-            case 8: return launch_one<128, MM, 8, kDeqE0M8>(p, X, packed, N, K, Y, stream);
+            case 4: return launch_one<128, MM, 4, kDeqE0M8, FUSED>(p, X, packed, N, K, Y, stream, fu);
+            case 8: return launch_one<128, MM, 8, kDeqE0M8, FUSED>(p, X, packed, N, K, Y, stream, fu);
             default:
-                if constexpr (MM <= 4) return launch_one<128, MM, 16, kDeqE0M8>(p, X, packed, N, K, Y, stream);
+                if constexpr (MM <= 4) return launch_one<128, MM, 16, kDeqE0M8, FUSED>(p, X, packed, N, K, Y, stream, fu);
                 else return E0M4_ERR_SHAPE;
         }
     };
@@ -655,6 +658,21 @@ int launch_gemv8(const void* X, int64_t M, const void* packed, int64_t N, int64_
         case 8: return go(std::integral_constant<int, 8>{});
         default: return E0M4_ERR_SHAPE;
     }
+}
+}  // namespace
+
+int launch_gemv8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+{
+    return launch_gemv8_m<false>(make_plan(M, N, 2 * K), GemvFusion{}, X, M, packed, N, K, Y, stream);
+}
+
+int launch_gemv8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                       hipStream_t stream)
+{
+    if (!gemv_fused_supported(f, M, N, 2 * K)) return E0M4_ERR_SHAPE;
+    if (f.swiglu && gated_half_bytes(N, 2 * K, 128) > kMaxHalfBytes) return E0M4_ERR_SHAPE;
+    return launch_gemv8_m<true>(make_plan(M, N, 2 * K, f.swiglu ? 2 : 1), make_gemv_fusion(f, N, 2 * K, 128), X, M, packed,
+                                N, K, Y, stream);
 }
 
 int launch_gemv_int4(const void* X, const void* packed, int64_t N, int64_t K, int group, void* Y, hipStream_t stream)

@@ -510,23 +510,48 @@ bool gemv_mfma8_supported(int64_t M, int64_t N, int64_t K)
     return make_mfma_plan(M, N, 2 * K, p, 1, true);
 }
 
+namespace {
+template <bool FUSED>
+int launch_mfma8(const MfmaPlan& p, const GemvFusion& fu, const void* X, int64_t M, const void* packed, int64_t N,
+                 int64_t K, void* Y, hipStream_t stream)
+{
+    const bool xreg = p.step_item == 0 && knob("gemv_mfma") != 2;
+    switch (p.waves) {
+        case 4:
+            return xreg ? launch_mfma_x<4, FUSED, true, true>(p, X, M, packed, N, K, Y, stream, fu)
+                        : launch_mfma_x<4, FUSED, false, true>(p, X, M, packed, N, K, Y, stream, fu);
+        case 8:
+            return xreg ? launch_mfma_x<8, FUSED, true, true>(p, X, M, packed, N, K, Y, stream, fu)
+                        : launch_mfma_x<8, FUSED, false, true>(p, X, M, packed, N, K, Y, stream, fu);
+        default:
+            return xreg ? launch_mfma_x<16, FUSED, true, true>(p, X, M, packed, N, K, Y, stream, fu)
+                        : launch_mfma_x<16, FUSED, false, true>(p, X, M, packed, N, K, Y, stream, fu);
+    }
+}
+}  // namespace
+
 int launch_gemv_mfma8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
 {
     MfmaPlan p;
     if (!make_mfma_plan(M, N, 2 * K, p, 1, true)) return E0M4_ERR_SHAPE;
-    const GemvFusion fu{};
-    const bool xreg = p.step_item == 0 && knob("gemv_mfma") != 2;
-    switch (p.waves) {
-        case 4:
-            return xreg ? launch_mfma_x<4, false, true, true>(p, X, M, packed, N, K, Y, stream, fu)
-                        : launch_mfma_x<4, false, false, true>(p, X, M, packed, N, K, Y, stream, fu);
-        case 8:
-            return xreg ? launch_mfma_x<8, false, true, true>(p, X, M, packed, N, K, Y, stream, fu)
-                        : launch_mfma_x<8, false, false, true>(p, X, M, packed, N, K, Y, stream, fu);
-        default:
-            return xreg ? launch_mfma_x<16, false, true, true>(p, X, M, packed, N, K, Y, stream, fu)
-                        : launch_mfma_x<16, false, false, true>(p, X, M, packed, N, K, Y, stream, fu);
-    }
+    return launch_mfma8<false>(p, GemvFusion{}, X, M, packed, N, K, Y, stream);
+}
+
+bool gemv_mfma8_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K)
+{
+    if (M < kMinM || M > kMaxM || N <= 0 || K <= 0) return false;
+    if (f.swiglu && (N % (2 * kBlockRows) != 0 || gated_half_bytes(N, 2 * K, kG) > kMaxHalfBytes)) return false;
+    MfmaPlan p;
+    return make_mfma_plan(M, N, 2 * K, p, f.swiglu ? 2 : 1, true);
+}
+
+int launch_gemv_mfma8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                            hipStream_t stream)
+{
+    MfmaPlan p;
+    if (!gemv_mfma8_fused_supported(f, M, N, K) || !make_mfma_plan(M, N, 2 * K, p, f.swiglu ? 2 : 1, true))
+        return E0M4_ERR_SHAPE;
+    return launch_mfma8<true>(p, make_gemv_fusion(f, N, 2 * K, kG), X, M, packed, N, K, Y, stream);
 }
 
 bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)

@@ -83,6 +83,13 @@ int launch_gemm_pipe8(const void* X, int64_t M, const void* packed, int64_t N, i
                       size_t workspace_bytes, hipStream_t stream);
 bool gemv_mfma8_supported(int64_t M, int64_t N, int64_t K);
 int launch_gemv_mfma8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream);
+int launch_gemv8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                       hipStream_t stream);
+bool gemv_mfma8_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K);
+int launch_gemv_mfma8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                            hipStream_t stream);
+int launch_gemm_pipe8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                            void* workspace, size_t workspace_bytes, hipStream_t stream);
 int launch_gemv8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream);
 
 // In-place KV-cache append: cache[position_ids[i], :] = src[i, :row_elems], src rows src_ld elements apart.

@@ -37,8 +37,12 @@ def to_dev(a):
     return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
-def quantized(e0m4, oracle, N, K, G, seed, row_std=None):
+def quantized(e0m4, oracle, N, K, G, seed, row_std=None, bits=4):
     W = synth_inputs.weights(N, K, seed=seed, row_std_range=row_std)
+    if bits == 8:
+        codes, _, _ = e0m4.e0m8_quantize(to_dev(W), G)
+        oc, os_, ob = oracle.quantize_k(W, G, 8)
+        return codes, oracle.dequant_k(oc, os_, ob, G, 8)
     codes, scales, bias = e0m4.e0m4_quantize(to_dev(W), G)
     oc, os_, ob = oracle.quantize(W, G)
     return codes, oracle.dequant(oc, os_, ob, G)
@@ -68,8 +72,8 @@ def check_fused(y_gpu, Yref, info, swiglu, normed, what):
 
 
 def run_fused(e0m4, oracle, M, N, K, G, seed, norm=False, swiglu=False, res=False, row_std=None, outliers=False,
-              in_place=False):
-    codes, What = quantized(e0m4, oracle, N, K, G, seed, row_std)
+              in_place=False, bits=4):
+    codes, What = quantized(e0m4, oracle, N, K, G, seed, row_std, bits)
     X = synth_inputs.activations(M, K, seed=seed, outlier_frac=0.01 if outliers else 0.0)
     gamma = synth_inputs.norm_weight(K, seed) if norm else None
     n_out = N // 2 if swiglu else N
@@ -79,12 +83,12 @@ def run_fused(e0m4, oracle, M, N, K, G, seed, norm=False, swiglu=False, res=Fals
     r_dev = to_dev(R)
     if in_place:
         out = r_dev                                     # the residual stream is updated in place
-    Y = e0m4.e0m4_matmul_fused(to_dev(X), codes, N, K, G, rms_gamma=to_dev(gamma), rms_eps=eps,
-                               epilogue=e0m4.E0M4_EPILOGUE_SWIGLU if swiglu else e0m4.E0M4_EPILOGUE_NONE,
-                               residual=r_dev, out=out)
+    fn = e0m4.e0m8_matmul_fused if bits == 8 else e0m4.e0m4_matmul_fused
+    Y = fn(to_dev(X), codes, N, K, G, rms_gamma=to_dev(gamma), rms_eps=eps,
+           epilogue=e0m4.E0M4_EPILOGUE_SWIGLU if swiglu else e0m4.E0M4_EPILOGUE_NONE, residual=r_dev, out=out)
     Yref, info = oracle.matmul_fused(X, What, gamma=gamma, eps=eps, swiglu=swiglu, residual=R)
     torch.cuda.synchronize()
-    what = "M=%d N=%d K=%d G=%d norm=%d swiglu=%d res=%d" % (M, N, K, G, norm, swiglu, res)
+    what = "bits=%d M=%d N=%d K=%d G=%d norm=%d swiglu=%d res=%d" % (bits, M, N, K, G, norm, swiglu, res)
     check_fused(Y, Yref, info, swiglu, norm, what)
     return Y
 
@@ -218,6 +222,77 @@ def test_gemm_small_kernel_ragged_k(e0m4, oracle):
     run_fused(e0m4, oracle, 70, 256, 416, 32, seed=380, norm=True, swiglu=True, res=True)      # K = 6.5 slices of 64
 
 
+# ---- the same operators on 8-bit codes (e0m8_matmul_fused)
+@pytest.mark.parametrize("norm,swiglu,res", COMBOS)
+@pytest.mark.parametrize("M", [1, 2, 5, 8])
+def test_8bit_decode_kernel(e0m4, oracle, M, norm, swiglu, res):
+    e0m4.e0m4_set_knob("gemv_mfma", 1)                  # M >= 2 would take the matrix-core kernel
+    try:
+        run_fused(e0m4, oracle, M, 320, 576, 64, seed=700 + M, norm=norm, swiglu=swiglu, res=res, bits=8)   # 9 blocks
+        run_fused(e0m4, oracle, M, 1088, 2048, 128, seed=710 + M, norm=norm, swiglu=swiglu, res=res, outliers=True, bits=8)
+        run_fused(e0m4, oracle, M, 192, 1088, 64, seed=720 + M, norm=norm, swiglu=swiglu, res=res, bits=8)  # 17 blocks
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+
+
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("target", [0, 3, 100000])
+def test_8bit_decode_kernel_forced_shapes(e0m4, oracle, waves, target):
+    e0m4.e0m4_set_knob("gemv_waves", waves)
+    e0m4.e0m4_set_knob("gemv_workgroups", target)
+    try:
+        for M in (1, 3):
+            run_fused(e0m4, oracle, M, 448, 1600, 64, seed=730 + waves, norm=True, swiglu=True, res=True, bits=8)
+    finally:
+        e0m4.e0m4_set_knob("gemv_waves", 0)
+        e0m4.e0m4_set_knob("gemv_workgroups", 0)
+
+
+@pytest.mark.parametrize("norm,swiglu,res", COMBOS)
+@pytest.mark.parametrize("M", [2, 3, 8, 9, 16])
+def test_8bit_small_batch_matrix_core_kernel(e0m4, oracle, M, norm, swiglu, res):
+    run_fused(e0m4, oracle, M, 320, 576, 64, seed=740 + M, norm=norm, swiglu=swiglu, res=res, bits=8)
+    run_fused(e0m4, oracle, M, 1088, 2048, 128, seed=750 + M, norm=norm, swiglu=swiglu, res=res, outliers=True, bits=8)
+    run_fused(e0m4, oracle, M, 333 if not swiglu else 448, 832, 64, seed=760 + M, norm=norm, swiglu=swiglu, res=res,
+              bits=8)
+
+
+@pytest.mark.parametrize("mode", [2, 3])
+@pytest.mark.parametrize("waves", [4, 8, 16])
+def test_8bit_small_batch_matrix_core_kernel_forced_shapes(e0m4, oracle, waves, mode):
+    e0m4.e0m4_set_knob("gemv_waves", waves)
+    e0m4.e0m4_set_knob("gemv_mfma", mode)               # 2: X from the LDS, 3: reduction per row block
+    try:
+        for M in (2, 11):
+            run_fused(e0m4, oracle, M, 448, 1600, 64, seed=770 + waves, norm=True, swiglu=True, res=True, bits=8)
+    finally:
+        e0m4.e0m4_set_knob("gemv_waves", 0)
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+
+
+@pytest.mark.parametrize("variant,splits", [(2, 0), (3, 0), (4, 0), (2, 3), (3, 2), (4, 8)])
+@pytest.mark.parametrize("norm,swiglu,res", COMBOS)
+def test_8bit_gemm_kernels(e0m4, oracle, variant, splits, norm, swiglu, res):
+    e0m4.e0m4_set_knob("gemm_variant", variant)
+    e0m4.e0m4_set_knob("gemm_splits", splits)
+    try:
+        run_fused(e0m4, oracle, 300, 640, 1024, 128, seed=780 + variant, norm=norm, swiglu=swiglu, res=res,
+                  row_std=(0.5, 2.0), outliers=True, bits=8)
+        run_fused(e0m4, oracle, 17, 192, 384, 64, seed=781 + variant, norm=norm, swiglu=swiglu, res=res, bits=8)
+    finally:
+        e0m4.e0m4_set_knob("gemm_variant", 0)
+        e0m4.e0m4_set_knob("gemm_splits", 0)
+
+
+def test_8bit_larger_batches_need_whole_k_slices(e0m4):
+    N, K, G = 128, 192, 64                              # K % 128 != 0: only the decode kernels take it
+    codes, _, _ = e0m4.e0m8_quantize(to_dev(synth_inputs.weights(N, K, seed=1)), G)
+    x = to_dev(synth_inputs.activations(40, K, seed=2))
+    assert e0m4.e0m8_matmul_fused(x[:8].contiguous(), codes, N, K, G, epilogue=e0m4.E0M4_EPILOGUE_SWIGLU).shape == (8, 64)
+    with pytest.raises(e0m4.E0M4Error, match="shape"):
+        e0m4.e0m8_matmul_fused(x, codes, N, K, G, epilogue=e0m4.E0M4_EPILOGUE_SWIGLU)
+
+
 def test_residual_in_place(e0m4, oracle):
     run_fused(e0m4, oracle, 1, 320, 1152, 128, seed=390, res=True, in_place=True)
     run_fused(e0m4, oracle, 5, 640, 1152, 128, seed=391, swiglu=True, res=True, in_place=True)
@@ -263,21 +338,22 @@ FULL = [
 ]
 
 
+@pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("name,N,K,norm,swiglu,res", FULL, ids=[c[0] for c in FULL])
-def test_full_size_layer(e0m4, oracle, name, N, K, norm, swiglu, res):
+def test_full_size_layer(e0m4, oracle, name, N, K, norm, swiglu, res, bits):
     G, Mp = 128, 1024
-    seed = 400 + N % 97 + K % 89
+    seed = 400 + N % 97 + K % 89 + (8 if bits == 8 else 0)
     # decode: the whole output
-    run_fused(e0m4, oracle, 1, N, K, G, seed=seed, norm=norm, swiglu=swiglu, res=res)
+    run_fused(e0m4, oracle, 1, N, K, G, seed=seed, norm=norm, swiglu=swiglu, res=res, bits=bits)
     # prefill: sampled rows over all outputs, sampled output columns over all rows
-    codes, What = quantized(e0m4, oracle, N, K, G, seed + 1, row_std=(0.5, 2.0))
+    codes, What = quantized(e0m4, oracle, N, K, G, seed + 1, row_std=(0.5, 2.0), bits=bits)
     X = synth_inputs.activations(Mp, K, seed=seed + 1, outlier_frac=0.01)
     gamma = synth_inputs.norm_weight(K, seed + 1) if norm else None
     n_out = N // 2 if swiglu else N
     R = synth_inputs.residual(Mp, n_out, seed + 1) if res else None
-    Y = e0m4.e0m4_matmul_fused(to_dev(X), codes, N, K, G, rms_gamma=to_dev(gamma), rms_eps=1e-5,
-                               epilogue=e0m4.E0M4_EPILOGUE_SWIGLU if swiglu else e0m4.E0M4_EPILOGUE_NONE,
-                               residual=to_dev(R)).cpu().numpy()
+    fn = e0m4.e0m8_matmul_fused if bits == 8 else e0m4.e0m4_matmul_fused
+    Y = fn(to_dev(X), codes, N, K, G, rms_gamma=to_dev(gamma), rms_eps=1e-5,
+           epilogue=e0m4.E0M4_EPILOGUE_SWIGLU if swiglu else e0m4.E0M4_EPILOGUE_NONE, residual=to_dev(R)).cpu().numpy()
     rng = np.random.default_rng(seed)
     ms = sample_indices(12, Mp, 128, rng)
     Yr, info = oracle.matmul_fused(X[ms], What, gamma=gamma, eps=1e-5, swiglu=swiglu,

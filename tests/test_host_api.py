@@ -199,3 +199,23 @@ def test_e0m8_validation_and_sizes(L):
     assert L.e0m8_workspace_bytes(8, 4096, 4096, 128) == 0
     assert L.e0m8_workspace_bytes(1024, 4096, 13696, 128) == L.e0m4_workspace_bytes(1024, 4096, 13696, 128) > 0
     assert L.e0m8_workspace_bytes(1024, 4096, 192, 64) == 0                             # K % 128 != 0: decode kernel, row chunks
+    # the fused matmul on 8-bit codes
+    L.e0m8_fused_workspace_bytes.restype = ctypes.c_size_t
+    L.e0m8_fused_workspace_bytes.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 3
+    L.e0m8_matmul_fused.restype = ctypes.c_int
+    L.e0m8_matmul_fused.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
+                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    assert L.e0m8_matmul_fused(p, 1, null, 0.0, p, 96, 128, 64, 1, null, p, null, 0, null) == ERR_SHAPE   # gated: N % 64
+    assert L.e0m8_matmul_fused(p, 1, null, 0.0, p, 128, 128, 64, 7, null, p, null, 0, null) == ERR_SHAPE  # epilogue
+    assert L.e0m8_matmul_fused(p, 1, null, 0.0, p, 128, 128, 32, 0, null, p, null, 0, null) == ERR_GROUP
+    assert L.e0m8_matmul_fused(p, 1, odd, 0.0, p, 128, 128, 64, 0, null, p, null, 0, null) == ERR_ALIGN
+    assert L.e0m8_matmul_fused(p, 1, null, 0.0, p, 128, 128, 64, 0, odd, p, null, 0, null) == ERR_ALIGN
+    assert L.e0m8_matmul_fused(null, 1, null, 0.0, p, 128, 128, 64, 0, null, p, null, 0, null) == ERR_NULL
+    assert L.e0m8_matmul_fused(null, 0, null, 0.0, null, 128, 128, 64, 0, null, null, null, 0, null) == 0
+    assert L.e0m8_matmul_fused(p, 40, null, 0.0, p, 128, 192, 64, 0, null, p, null, 0, null) == ERR_SHAPE  # M > 16: K % 128
+    assert L.e0m8_matmul_fused(p, 1024, p, 1e-5, p, 4096, 4096, 128, 0, null, p, null, 0, null) == ERR_NULL  # workspace
+    assert L.e0m8_fused_workspace_bytes(8, 27392, 4096, 128, 1, 1) == 0
+    assert (L.e0m8_fused_workspace_bytes(1024, 4096, 4096, 128, 1, 0) - L.e0m8_fused_workspace_bytes(1024, 4096, 4096, 128, 0, 0)
+            == 1024 * 4096 * 2)                                                         # the normalised copy of X
+    assert L.e0m8_fused_workspace_bytes(1024, 4096, 13696, 128, 0, 0) == L.e0m4_fused_workspace_bytes(1024, 4096, 13696, 128, 0, 0) > 0
