@@ -274,13 +274,9 @@ int launch_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     const int total = (int)(m_tiles * n_tiles);
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
     constexpr size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
-    static bool attr_set = false;                       // LDS above the default 64 KiB limit must be requested once
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<G, BM, BN, FUSED>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return record_hip_error(e);
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_allowed{0};        // LDS above the default 64 KiB limit must be requested
+    const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_kernel<G, BM, BN, FUSED>), (int)lds, lds_allowed);
+    if (arc != E0M4_OK) return arc;
     hipLaunchKernelGGL((gemm_kernel<G, BM, BN, FUSED>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(kThreads), lds, stream,
                        x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, fu);
     return check_launch();

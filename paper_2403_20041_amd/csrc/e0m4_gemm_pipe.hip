@@ -511,13 +511,10 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
         partial = static_cast<float*>(workspace);
     }
     constexpr size_t lds = (size_t)kStages * BM * kRowBytes;       // 96 KiB for the large tile: above the default limit
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN, E8>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return record_hip_error(e);
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_allowed{0};
+    const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN, E8>),
+                                      (int)lds, lds_allowed);
+    if (arc != E0M4_OK) return arc;
     hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN, E8>), dim3((unsigned)(per_xcd * kNumXcd)),
                        dim3(64 * WGM * WGN), lds, stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial, fu);
     int rc = check_launch();

@@ -521,13 +521,10 @@ int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, 
     const dim3 grid((unsigned)p.grid), block(W * 64);
     const size_t lds_bytes = p.lds_bytes + (FUSED ? (size_t)W * M * sizeof(float) : 0);
     if (lds_bytes > (size_t)kLdsDefaultBytes) {
-        static bool attr_set = false;                   // per instantiation
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<G, M, W, DEQ, FUSED, XREG>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimitBytes);
-            if (e != hipSuccess) return record_hip_error(e);
-            attr_set = true;
-        }
+        static std::atomic<uint64_t> lds_allowed{0};    // per instantiation
+        const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemv_kernel<G, M, W, DEQ, FUSED, XREG>),
+                                          kLdsLimitBytes, lds_allowed);
+        if (arc != E0M4_OK) return arc;
     }
     hipLaunchKernelGGL((gemv_kernel<G, M, W, DEQ, FUSED, XREG>), grid, block, lds_bytes, stream, x, c, N, K, y, p.seg_items,
                        p.step_slots, p.step_item, p.rb_base, p.rb_rem, fu);

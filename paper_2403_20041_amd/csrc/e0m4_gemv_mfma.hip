@@ -458,13 +458,10 @@ template <int W, bool FUSED, bool XREG, bool E8 = false>
 int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                   hipStream_t stream, const GemvFusion& fu)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED, XREG, E8>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimitBytes);
-        if (e != hipSuccess) return record_hip_error(e);
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_allowed{0};
+    const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED, XREG, E8>), kLdsLimitBytes,
+                                      lds_allowed);
+    if (arc != E0M4_OK) return arc;
     hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
                        static_cast<const half_t*>(X), (int)M, static_cast<const uint4*>(packed), N, K,
                        static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.late, fu);

@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "e0m4.h"
 
 namespace e0m4 {
@@ -13,6 +15,21 @@ namespace e0m4 {
 // Records hipGetLastError(); returns E0M4_OK or E0M4_ERR_HIP.
 int check_launch();
 int record_hip_error(hipError_t e);
+
+// Raises a kernel's dynamic LDS limit, once per device (it is an attribute of the function on the current
+// device).  `done` is the caller's own mask of devices that have it; safe to call from several threads.
+inline int allow_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return record_hip_error(e);
+    const uint64_t bit = dev < 64 ? (uint64_t)1 << dev : 0;        // devices beyond 64 are not remembered
+    if (done.load(std::memory_order_acquire) & bit) return E0M4_OK;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return record_hip_error(e);
+    done.fetch_or(bit, std::memory_order_release);
+    return E0M4_OK;
+}
 
 // Tuning knobs (0 = use the heuristic).
 int knob(const char* name);
