@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-table1", action="store_true", help="skip the E0M4 / INT4 latency comparison")
     ap.add_argument("--no-fusion", action="store_true", help="skip the fused / unfused layer comparison")
+    ap.add_argument("--no-library", action="store_true",
+                    help="skip the platform library's fp16 GEMM on the same prefill shapes (context figure)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--copy-probe", action="store_true",
                     help="first run three plain device copies of 1 GiB (calibration of HBM traffic counters)")
@@ -329,7 +331,7 @@ def main():
     # ---------------- prefill: same four shapes at M=1024 (activation outliers, per-row weight scale)
     if not args.no_prefill:
         pre = {}
-        tot_flops, tot_ms = 0.0, 0.0
+        tot_flops, tot_ms, lib_tot_ms = 0.0, 0.0, 0.0
         best = None
         with torch.cuda.stream(stream):
             for p, (name, N, K) in enumerate(shapes):
@@ -354,6 +356,33 @@ def main():
                 tf = flops / ms / 1e9
                 pre[name] = {"N": N, "K": K, "ms": round(ms, 4), "TFLOPs": round(tf, 1),
                              "frac_mfma": round(tf / MFMA_F16_PEAK_TFLOPS, 4), "workspace_bytes": pws_bytes}
+                if not args.no_library:
+                    # context only: the platform library's plain fp16 GEMM (torch.matmul) on the dequantised
+                    # weights, four times the weight bytes and no dequantisation in the kernel
+                    Wd = e0m4.e0m4_dequant(codes, scales, bias, N, K, GROUP, stream=stream)
+                    for _ in range(3):
+                        torch.matmul(X, Wd.t(), out=Y)
+                    e0.record(stream)
+                    for _ in range(reps):
+                        torch.matmul(X, Wd.t(), out=Y)
+                    e1.record(stream)
+                    stream.synchronize()
+                    lib_ms = e0.elapsed_time(e1) / reps
+                    pre[name]["library_fp16_gemm_TFLOPs"] = round(flops / lib_ms / 1e9, 1)
+                    lib_tot_ms += lib_ms
+                    # and its fp16 vector-matrix product at M = 1, three copies of the weights in turn (cold)
+                    wds = [Wd, Wd.clone(), Wd.clone()]
+                    x1, y1 = X[:1], Y[:1]
+                    for wd in wds:
+                        torch.matmul(x1, wd.t(), out=y1)
+                    e0.record(stream)
+                    for _ in range(4):
+                        for wd in wds:
+                            torch.matmul(x1, wd.t(), out=y1)
+                    e1.record(stream)
+                    stream.synchronize()
+                    pre[name]["library_fp16_gemv_us"] = round(e0.elapsed_time(e1) * 1e3 / 12, 2)
+                    del Wd, wds
                 tot_flops += flops
                 tot_ms += ms
                 if best is None or flops > best[0]:
@@ -363,6 +392,8 @@ def main():
         out["prefill"] = {"workload": "ChatGLM2-6B-shaped prefill layer, M=%d, 4 GEMMs" % PREFILL_M,
                           "value": round(layer_tf, 1), "unit": "TFLOP/s", "ms_per_layer": round(tot_ms, 4),
                           "pct_of_mfma_peak": round(100.0 * layer_tf / MFMA_F16_PEAK_TFLOPS, 2), "per_shape": pre}
+        if lib_tot_ms > 0:
+            out["prefill"]["library_fp16_gemm_layer_TFLOPs"] = round(tot_flops / lib_tot_ms / 1e9, 1)
         dom_tf = best[0] / best[1] / 1e9
         out["roofline_prefill"] = {"bound": "mfma", "kernel": "gemm_pipe_kernel<G=128> (%s)" % best[2],
                                    "achieved": round(dom_tf, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -44,8 +44,8 @@ __device__ inline half2_t dequant_pair(half2_t w1, half2_t bias2, half2_t scale2
 
 // WGM x WGN wavefronts share the tile.  Built as 2 x 4 (two per SIMD, 128 x 64 each): against 2 x 2
 // (one per SIMD, 128 x 128 each) that doubles the instruction issue capacity and lets one wavefront's
-// waits hide behind the other's MFMAs, for twice the activation fragment traffic; 2 x 2 was measured
-// slower and does not fit the register file once the split-K epilogue is compiled in.
+// waits hide behind the other's MFMAs, for twice the activation fragment traffic; 2 x 2 (accumulators in
+// the 256 AGPRs, one wavefront per SIMD, 17 registers spilled) was measured 3-9 % slower on every shape.
 //
 // FUSED adds the operators of e0m4_matmul_fused that belong to the epilogue (paper: section "Operator and
 // lagging optimizations", element-wise operators fused into their neighbours).  With the gated
