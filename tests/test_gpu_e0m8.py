@@ -184,6 +184,11 @@ def test_decode_long_rows_and_row_chunks(e0m4, oracle):
     run_matmul_case(e0m4, oracle, 16, 64, 256, 128, seed=722)
 
 
+@pytest.mark.parametrize("M", [1, 20])
+def test_longest_rows(e0m4, oracle, M):
+    run_matmul_case(e0m4, oracle, M, 24, 1 << 19, 128, seed=760 + M)   # K at its limit
+
+
 def test_one_hot_activations_reproduce_weights_bit_exactly(e0m4, oracle):
     N, K, G = 100, 256, 64
     W = synth_inputs.weights(N, K, seed=730)

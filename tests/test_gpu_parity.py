@@ -399,6 +399,12 @@ def test_matmul_is_deterministic(e0m4, M):
     assert np.array_equal(y1, y2)
 
 
+@pytest.mark.parametrize("M", [1, 3, 20])
+def test_longest_rows(e0m4, oracle, M):
+    # K at its limit of 2^20: the decode kernel stages X in many segments, the GEMM runs 16384 K slices in 8 splits
+    run_matmul_case(e0m4, oracle, M, 24, 1 << 20, 128, seed=600 + M)
+
+
 def test_empty_problems(e0m4):
     X = torch.zeros((0, 128), dtype=torch.float16, device=DEV)
     codes, scales, bias = e0m4.alloc_packed(64, 128, 128, DEV)
