@@ -263,10 +263,16 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     // Two pieces of X per thread are requested before the weights, so that they are not queued behind
     // them (loads return in order; requesting the weights first was measured slower).  What two pieces
     // per thread do not cover (large M * K) is staged right away.
+    // XREG without rms-norm: a wavefront needs nothing but the activations of its own four k blocks, so it
+    // stages exactly those (one piece per lane; wavefronts on the same k blocks write the same bytes) and
+    // waits for no other wavefront before it starts.
+    const bool normed = FUSED && fu.gamma != nullptr;   // then staging waits for the row scales (below)
+    const bool own_x = XREG && !normed;
+    constexpr int kItemPieces = kSuper * BLK_K / 8;     // pieces of one work item's activations: 64 (32 for 8-bit codes)
+    const int own_idx = lane < kItemPieces ? si * kItemPieces + lane : M * pieces;
     half8_t xearly[kEarlyX];
 #pragma unroll
-    for (int e = 0; e < kEarlyX; ++e) xearly[e] = x_piece(t + e * kThreads, 0);
-    const bool normed = FUSED && fu.gamma != nullptr;   // then staging waits for the row scales (below)
+    for (int e = 0; e < kEarlyX; ++e) xearly[e] = x_piece(own_x ? (e == 0 ? own_idx : M * pieces) : t + e * kThreads, 0);
     const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     half8_t gearly[kEarlyX];                            // norm weights of the early pieces, requested with them
 #pragma unroll
@@ -279,7 +285,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
         const int64_t n = (rb0 + u) * kBlockRows + rr;
         if (u < units && n < fu.n_out) res_early = (float)fu.residual[(int64_t)m * fu.n_out + n];
     }
-    if (!normed) stage_from(t + kEarlyX * kThreads, 0);
+    if (!normed && !own_x) stage_from(t + kEarlyX * kThreads, 0);
 
     // ---- the work item in flight: four code blocks and the parameter words
     uint4 c[kSuper];
@@ -377,14 +383,21 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
 
     for (int seg0 = 0; seg0 < nsi; seg0 += seg_items) {
         // stage the segment's activations and the sums of every 32-wide chunk
-        if (seg0 == 0) {
-#pragma unroll
-            for (int e = 0; e < kEarlyX; ++e) x_store(t + e * kThreads, xearly[e], gearly[e]);
+        if (own_x) {                                    // (single segment) the wavefront's own pieces, read back by itself
+            x_store(own_idx, xearly[0], zero8);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         } else {
-            __syncthreads();                            // everyone is done with the previous segment's activations
-            stage_from(t, seg0 * kSuper);
+            if (seg0 == 0) {
+#pragma unroll
+                for (int e = 0; e < kEarlyX; ++e) x_store(t + e * kThreads, xearly[e], gearly[e]);
+            } else {
+                __syncthreads();                        // everyone is done with the previous segment's activations
+                stage_from(t, seg0 * kSuper);
+            }
+            __syncthreads();
         }
-        __syncthreads();
         half8_t xr[XREG ? kSuper : 1][4];
         float2 sxr[XREG ? kSuper : 1];
         if (XREG) {
