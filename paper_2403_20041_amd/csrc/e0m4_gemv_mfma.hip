@@ -49,6 +49,7 @@ struct MfmaPlan {
     int rb_base, rb_rem;                        // even deal of row blocks
     int64_t grid;
     size_t lds_bytes;
+    uint32_t pieces_magic;                      // ceil(2^32 / pieces of 8 activations per row): row of a piece by multiplication
 };
 
 constexpr int kNormBytes = (16 + 1) * kMaxM * 4;        // rms-norm: per-wavefront sums of squares and the row scales
@@ -82,7 +83,8 @@ template <int W, bool FUSED, bool XREG, bool E8 = false>
 __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restrict__ X, int M,
                                                            const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                            half_t* __restrict__ Y, int step_slots, int step_item,
-                                                           int rb_base, int rb_rem, int late, GemvFusion fu)
+                                                           int rb_base, int rb_rem, int late, uint32_t pieces_magic,
+                                                           GemvFusion fu)
 {
     constexpr int kThreads = W * 64;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -155,99 +157,140 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 #pragma unroll
     for (int j = 0; j < kSuper; ++j) fetch_code(j, slot, si);
 
-    // ---- stage X: thread idx handles the 8 elements k = 8*pc..8*pc+7 of row m; 16 consecutive threads
-    // cover one block of one row
+    // ---- stage X in pieces of 8 elements (k = 8*pc .. 8*pc+7 of row m).  Pieces are visited row by row,
+    // kThreads at a time ("chunks"), so the row of a piece is uniform across the workgroup and no index needs
+    // a division; the loads of four chunks are in flight at a time.
     const int pieces = nkb * (XBB / 16);
     const bool normed = FUSED && fu.gamma != nullptr;
+    const int cpr = (pieces + kThreads - 1) / kThreads;        // chunks per row
+    const int n_chunks = M * cpr;
+    constexpr int kStageBatch = 4;
+    const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     if (normed) {
         // rms-norm: sum of squares of every row (first pass over X; the staging pass below reads it again,
         // from the cache), reduced in a fixed order: lanes, then wavefronts
-        float ss[kMaxM];
+        int m_it = 0, c_it = 0;                         // row and chunk of the next piece
+        int cur_m = 0;                                  // row whose squares `cur` holds
+        float cur = 0.f;
+        auto flush_row = [&]() {
+            float v = cur;
 #pragma unroll
-        for (int m = 0; m < kMaxM; ++m) ss[m] = 0.f;
-        for (int base = 0; base < M * pieces; base += 4 * kThreads) {
-            half8_t vb[4];
+            for (int d = 1; d < 64; d <<= 1) v += __shfl_xor(v, d);
+            if (lane == 0) norm_part[wave * kMaxM + cur_m] = v;
+        };
+        for (int j0 = 0; j0 < n_chunks; j0 += kStageBatch) {
+            half8_t vb[kStageBatch];
+            int mrow[kStageBatch];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {               // four loads in flight
-                const int idx = base + u * kThreads + t;
-                const int m = idx / pieces, pc = idx - m * pieces;
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int pc = c_it * kThreads + t;
                 const int64_t k = (int64_t)pc * 8;
-                const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+                mrow[u] = m_it;
                 vb[u] = zero8;
-                if (idx < M * pieces && k < K) vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+                if (j0 + u < n_chunks && pc < pieces && k < K) vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m_it * K + k);
+                if (++c_it == cpr) {
+                    c_it = 0;
+                    ++m_it;
+                }
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int m = (base + u * kThreads + t) / pieces;      // beyond the last row: adds zeros
+            for (int u = 0; u < kStageBatch; ++u) {
+                if (j0 + u >= n_chunks) break;
+                if (mrow[u] != cur_m) {                 // (uniform) the previous row is complete
+                    flush_row();
+                    cur = 0.f;
+                    cur_m = mrow[u];
+                }
                 const half8_t v = vb[u];
                 const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
                 float d = __builtin_amdgcn_fdot2(x0, x0, 0.f, false);
                 d = __builtin_amdgcn_fdot2(x1, x1, d, false);
                 d = __builtin_amdgcn_fdot2(x2, x2, d, false);
                 d = __builtin_amdgcn_fdot2(x3, x3, d, false);
-#pragma unroll
-                for (int mm = 0; mm < kMaxM; ++mm) ss[mm] += mm == m ? d : 0.f;
+                cur += d;
             }
         }
-#pragma unroll
-        for (int m = 0; m < kMaxM; ++m) {
-            float v = ss[m];
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) v += __shfl_xor(v, d);
-            if (lane == 0) norm_part[wave * kMaxM + m] = v;
-        }
+        flush_row();
         __syncthreads();
         float tot = 0.f;
-        if (t < kMaxM) {
+        if (t < M) {
 #pragma unroll
             for (int w = 0; w < W; ++w) tot += norm_part[w * kMaxM + t];
         }
         __syncthreads();
-        if (t < kMaxM) norm_part[t] = 1.f / sqrtf(tot / (float)K + fu.eps);
+        if (t < M) norm_part[t] = 1.f / sqrtf(tot / (float)K + fu.eps);
         __syncthreads();
     }
-    // (loads in batches of kStageBatch: issued together, then consumed, so that their latencies overlap)
-    constexpr int kStageBatch = 4;
-    for (int base = 0; base < M * pieces; base += kStageBatch * kThreads) {
-        half8_t vb[kStageBatch], gb[kStageBatch];
+    // one piece into the LDS image of X, in the order the MFMAs consume it
+    auto store_piece = [&](int m, int pc, bool ok, half8_t v, const half8_t& g) {
+        if (!ok) return;
+        if (normed) {                                   // (x * row scale) * gamma, one rounding
+            const float r = norm_part[m];
 #pragma unroll
-        for (int u = 0; u < kStageBatch; ++u) {
-            const int idx = base + u * kThreads + t;
-            const int m = idx / pieces, pc = idx - m * pieces;
-            const int64_t k = (int64_t)pc * 8;
-            const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-            vb[u] = zero8;
-            gb[u] = zero8;
-            if (idx < M * pieces && k < K) {
-                vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
-                if (normed) gb[u] = *reinterpret_cast<const half8_t*>(fu.gamma + k);
+            for (int i = 0; i < 8; ++i) v[i] = (half_t)(((float)v[i] * r) * (float)g[i]);
+        }
+        if (E8) {                                       // piece = the 8 weights of (k-group q, MFMA wp)
+            const int kb = pc >> 3, q = (pc >> 1) & 3, wp = pc & 1;
+            *reinterpret_cast<half8_t*>(xs + (size_t)m * row_stride + kb * XBB + q * 2 * UB + wp * UB) = v;
+        } else {
+            const int kb = pc >> 4, q = (pc >> 2) & 3, w = pc & 3;
+            unsigned char* blk = xs + (size_t)m * row_stride + kb * XBB;
+            const half4_t hpart = {v[0], v[1], v[6], v[7]}, lpart = {v[2], v[3], v[4], v[5]};
+            *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 0)) = hpart;
+            *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 1)) = lpart;
+        }
+    };
+    // XREG without rms-norm: a wavefront needs nothing but the activations of its own four k blocks, so it
+    // stages exactly those and waits for no other wavefront before it starts.  (Wavefronts on the same k
+    // blocks write the same bytes; not done when they would each load many rows twice.)
+    constexpr int kItemPieces = kSuper * XBB / 16;      // pieces of one row of X per work item: 64 (32 for 8-bit codes)
+    const bool own_x = XREG && !normed && (step_slots == 1 || M <= 4);
+    if (own_x) {
+        for (int i0 = 0; i0 < M * kItemPieces; i0 += kStageBatch * 64) {
+            half8_t vb[kStageBatch];
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int idx = i0 + u * 64 + lane;
+                const int m = idx / kItemPieces, pc = si * kItemPieces + idx % kItemPieces;
+                vb[u] = zero8;
+                if (m < M && pc < pieces && (int64_t)pc * 8 < K) vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + (int64_t)pc * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int idx = i0 + u * 64 + lane;
+                const int m = idx / kItemPieces, pc = si * kItemPieces + idx % kItemPieces;
+                store_piece(m, pc, m < M && pc < pieces, vb[u], zero8);     // (a last work item may reach beyond the row's blocks)
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // read back by the wavefront that wrote it
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+        // all M * pieces pieces, kThreads at a time; the row of piece idx is idx / pieces, taken as the high
+        // half of idx * ceil(2^32 / pieces) (exact while M * pieces^2 < 2^32, which the LDS limit implies)
+        for (int base = 0; base < M * pieces; base += kStageBatch * kThreads) {
+            half8_t vb[kStageBatch], gb[kStageBatch];
 #pragma unroll
-        for (int u = 0; u < kStageBatch; ++u) {
-            const int idx = base + u * kThreads + t;
-            const int m = idx / pieces, pc = idx - m * pieces;
-            half8_t v = vb[u];
-            if (normed && idx < M * pieces) {           // (x * row scale) * gamma, one rounding
-                const float r = norm_part[m];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[i] = (half_t)(((float)v[i] * r) * (float)gb[u][i]);
-            }
-            if (idx < M * pieces) {
-                if (E8) {                               // piece = the 8 weights of (k-group q, MFMA wp)
-                    const int kb = pc >> 3, q = (pc >> 1) & 3, wp = pc & 1;
-                    *reinterpret_cast<half8_t*>(xs + (size_t)m * row_stride + kb * XBB + q * 2 * UB + wp * UB) = v;
-                } else {
-                    const int kb = pc >> 4, q = (pc >> 2) & 3, w = pc & 3;
-                    unsigned char* blk = xs + (size_t)m * row_stride + kb * XBB;
-                    const half4_t hpart = {v[0], v[1], v[6], v[7]}, lpart = {v[2], v[3], v[4], v[5]};
-                    *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 0)) = hpart;
-                    *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 1)) = lpart;
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int idx = base + u * kThreads + t;
+                const int m = (int)__umulhi((uint32_t)idx, pieces_magic), pc = idx - m * pieces;
+                const int64_t k = (int64_t)pc * 8;
+                vb[u] = zero8;
+                gb[u] = zero8;
+                if (idx < M * pieces && k < K) {
+                    vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+                    if (normed) gb[u] = *reinterpret_cast<const half8_t*>(fu.gamma + k);
                 }
             }
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int idx = base + u * kThreads + t;
+                const int m = (int)__umulhi((uint32_t)idx, pieces_magic), pc = idx - m * pieces;
+                store_piece(m, pc, idx < M * pieces, vb[u], gb[u]);
+            }
         }
+        __syncthreads();
     }
-    __syncthreads();
 
     // X operand address of this lane: row min(l%16, M-1) (rows beyond M repeat the last one; their
     // results are never stored), k-group l/16
@@ -447,6 +490,9 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, 
     p.rb_base = (int)(nrb / p.grid);
     p.rb_rem = (int)(nrb % p.grid);
     p.lds_bytes = lds_need(M, nkb, w, e8);
+    const uint64_t row_pieces = (uint64_t)nkb * (e8 ? 8 : 16);
+    if ((uint64_t)M * row_pieces * row_pieces >= (1ull << 32)) return false;    // (never within the LDS limit)
+    p.pieces_magic = (uint32_t)(((1ull << 32) + row_pieces - 1) / row_pieces);
     const size_t per_rb = 2 * (size_t)w * kMaxM * kBlockRows * sizeof(float);
     const size_t late_bytes = late_red_bytes(M, (p.rb_base + 1) * unit, w);
     p.late = knob("gemv_mfma") != 3 && p.lds_bytes - per_rb + late_bytes <= (size_t)kLdsLimitBytes;
@@ -464,7 +510,7 @@ int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packe
     if (arc != E0M4_OK) return arc;
     hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
                        static_cast<const half_t*>(X), (int)M, static_cast<const uint4*>(packed), N, K,
-                       static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.late, fu);
+                       static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.late, p.pieces_magic, fu);
     return check_launch();
 }
 
