@@ -51,6 +51,7 @@ struct GemvPlan {
     int step_item;      // ... and this many items further (with carry), i.e. W items ahead
     int64_t grid;
     int rb_base, rb_rem;  // even deal of row blocks: workgroup b owns rb_base (+1 if b < rb_rem) consecutive row blocks
+    int own_items;        // M = 1, one row block per workgroup, few items per wavefront: each stages its own activations
     size_t lds_bytes;
 };
 
@@ -104,6 +105,7 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K, int unit = 1, bool* single_s
     p.rb_base = (int)(nrb / p.grid);
     p.rb_rem = (int)(nrb % p.grid);
     p.lds_bytes = (size_t)M * p.seg_items * kSuper * kBytesPerBlockX + (size_t)unit * t * w * M * kBlockRows * sizeof(float);
+    p.own_items = M == 1 && unit == 1 && single_segment && p.grid == nrb && nsi >= w && nsi <= (int64_t)kEarlyX * w;
     return p;
 }
 
@@ -127,7 +129,7 @@ enum { kDeqE0M4 = 0, kDeqInt4Convert = 1, kDeqE0M8 = 2 };
 template <int G, int M, int W, int DEQ = kDeqE0M4, bool FUSED = false, bool XREG = false>
 __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__ X, const uint4* __restrict__ packed,
                                                       int64_t N, int64_t K, half_t* __restrict__ Y, int seg_items,
-                                                      int step_slots, int step_item, int rb_base, int rb_rem,
+                                                      int step_slots, int step_item, int rb_base, int rb_rem, int own_items,
                                                       GemvFusion fu)
 {
     constexpr int kThreads = W * 64;
@@ -263,16 +265,20 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     // Two pieces of X per thread are requested before the weights, so that they are not queued behind
     // them (loads return in order; requesting the weights first was measured slower).  What two pieces
     // per thread do not cover (large M * K) is staged right away.
-    // XREG without rms-norm: a wavefront needs nothing but the activations of its own four k blocks, so it
-    // stages exactly those (one piece per lane; wavefronts on the same k blocks write the same bytes) and
-    // waits for no other wavefront before it starts.
+    // Without rms-norm, when a wavefront needs nothing but the activations of its own work items -- XREG
+    // (the same four k blocks in every row block), or `own_items` (M = 1, one row block per workgroup, at
+    // most kEarlyX items per wavefront) -- it stages exactly those (one piece per lane and item; wavefronts on
+    // the same k blocks write the same bytes) and waits for no other wavefront before it starts.
     const bool normed = FUSED && fu.gamma != nullptr;   // then staging waits for the row scales (below)
-    const bool own_x = XREG && !normed;
+    const bool own_x = !normed && (XREG || own_items != 0);
     constexpr int kItemPieces = kSuper * BLK_K / 8;     // pieces of one work item's activations: 64 (32 for 8-bit codes)
-    const int own_idx = lane < kItemPieces ? si * kItemPieces + lane : M * pieces;
+    auto own_idx = [&](int e) {                         // piece index of this lane for the wavefront's item number e
+        const int it = si + e * W;
+        return (lane < kItemPieces && it < nsi && (!XREG || e == 0)) ? it * kItemPieces + lane : M * pieces;
+    };
     half8_t xearly[kEarlyX];
 #pragma unroll
-    for (int e = 0; e < kEarlyX; ++e) xearly[e] = x_piece(own_x ? (e == 0 ? own_idx : M * pieces) : t + e * kThreads, 0);
+    for (int e = 0; e < kEarlyX; ++e) xearly[e] = x_piece(own_x ? own_idx(e) : t + e * kThreads, 0);
     const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     half8_t gearly[kEarlyX];                            // norm weights of the early pieces, requested with them
 #pragma unroll
@@ -384,7 +390,8 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     for (int seg0 = 0; seg0 < nsi; seg0 += seg_items) {
         // stage the segment's activations and the sums of every 32-wide chunk
         if (own_x) {                                    // (single segment) the wavefront's own pieces, read back by itself
-            x_store(own_idx, xearly[0], zero8);
+#pragma unroll
+            for (int e = 0; e < (XREG ? 1 : kEarlyX); ++e) x_store(own_idx(e), xearly[e], zero8);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -540,7 +547,7 @@ int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, 
         if (arc != E0M4_OK) return arc;
     }
     hipLaunchKernelGGL((gemv_kernel<G, M, W, DEQ, FUSED, XREG>), grid, block, lds_bytes, stream, x, c, N, K, y, p.seg_items,
-                       p.step_slots, p.step_item, p.rb_base, p.rb_rem, fu);
+                       p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.own_items, fu);
     return check_launch();
 }
 
