@@ -21,7 +21,7 @@ Knob g_knobs[] = {
     {"gemv_waves", {0}},               // wavefronts per workgroup of the small-M kernel (4, 8 or 16)
     {"gemv_workgroups", {0}},          // target number of workgroups of the small-M kernel
     {"gemv_mfma", {0}},                // 1: never use the matrix-core small-batch kernel (2 <= M <= 16); 2: use it, activations always from LDS; 3: use it, wavefront sums reduced per row block
-    {"gemv_xreg", {0}},                // M = 1 kernel, a wavefront's activations in registers: 1 wherever possible, 2 never
+    {"gemv_xreg", {0}},                // M = 1 kernel, a wavefront's activations in registers: 2 never
     {"gemm_variant", {0}},             // 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
     {"gemm_splits", {0}},              // force the number of K splits of the pipelined GEMM kernel
 };

@@ -530,8 +530,7 @@ int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, 
     if constexpr (M == 1 && !XREG && DEQ != kDeqE0M8) {
         // every wavefront stays on its own k blocks, all of X in one segment, and a work item that exists
         const int64_t nsi = (k_blocks(K) + kSuper - 1) / kSuper;
-        const int xk = knob("gemv_xreg");               // 1: wherever possible, 2: never; else up to 8 wavefronts
-        if ((xk == 1 || (xk != 2 && W <= 8)) && p.step_item == 0 && p.seg_items >= nsi && W >= nsi &&
+        if (knob("gemv_xreg") != 2 && p.step_item == 0 && p.seg_items >= nsi && W >= nsi &&       // (2: never)
             k_blocks(K) % kSuper == 0)
             return launch_one<G, M, W, DEQ, FUSED, true>(p, X, packed, N, K, Y, stream, fu);
     }

@@ -211,7 +211,7 @@ def test_gemv_forced_workgroup_counts(e0m4, oracle, N, K, G):
             e0m4.e0m4_set_knob("gemv_workgroups", 0)
 
 
-@pytest.mark.parametrize("xreg", [1, 2])              # 1: activations in registers wherever possible, 2: never
+@pytest.mark.parametrize("xreg", [0, 2])              # 0: activations in registers wherever possible, 2: never
 @pytest.mark.parametrize("waves", [0, 4, 8, 16])
 def test_gemv_activations_in_registers(e0m4, oracle, waves, xreg):
     e0m4.e0m4_set_knob("gemv_waves", waves)
