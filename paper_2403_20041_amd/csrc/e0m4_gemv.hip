@@ -412,7 +412,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
             for (int j = 0; j < kSuper; ++j) {
                 const int xoff = (si * kSuper + j) * BLK_K + q * CHUNK;
 #pragma unroll
-                for (int w = 0; w < 4; ++w) xr[j][w] = *reinterpret_cast<const half8_t*>(&xs[xoff + 8 * w]);
+                for (int w = 0; w < CHUNK / 8; ++w) xr[j][w] = *reinterpret_cast<const half8_t*>(&xs[xoff + 8 * w]);
                 sxr[j] = sxs[xoff / CHUNK];
             }
         }
@@ -443,7 +443,13 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
                             __builtin_bit_cast(half2_t, (__builtin_amdgcn_alignbit(words[w], words[w], 8) & kFrac8Mask2) | kExpBits2);
 #pragma unroll
                         for (int m = 0; m < M; ++m) {
-                            const half4_t xv = *reinterpret_cast<const half4_t*>(&xs[m * seg_k + xoff + 4 * w]);
+                            half4_t xv;
+                            if (XREG) {
+                                const half8_t x8 = xr[XREG ? j : 0][w >> 1];
+                                xv = (w & 1) ? half4_t{x8[4], x8[5], x8[6], x8[7]} : half4_t{x8[0], x8[1], x8[2], x8[3]};
+                            } else {
+                                xv = *reinterpret_cast<const half4_t*>(&xs[m * seg_k + xoff + 4 * w]);
+                            }
                             const half2_t x01 = {xv[0], xv[1]}, x23 = {xv[2], xv[3]};
                             a[m][0] = __builtin_amdgcn_fdot2(p01, x01, a[m][0], false);
                             a[m][0] = __builtin_amdgcn_fdot2(p23, x23, a[m][0], false);
@@ -527,11 +533,12 @@ template <int G, int M, int W, int DEQ = kDeqE0M4, bool FUSED = false, bool XREG
 int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
                const GemvFusion& fu = GemvFusion{})
 {
-    if constexpr (M == 1 && !XREG && DEQ != kDeqE0M8) {
+    if constexpr (M == 1 && !XREG) {
         // every wavefront stays on its own k blocks, all of X in one segment, and a work item that exists
-        const int64_t nsi = (k_blocks(K) + kSuper - 1) / kSuper;
+        const int64_t nkb = k_blocks(DEQ == kDeqE0M8 ? 2 * K : K);     // (8-bit codes: blocks of 64 weights)
+        const int64_t nsi = (nkb + kSuper - 1) / kSuper;
         if (knob("gemv_xreg") != 2 && p.step_item == 0 && p.seg_items >= nsi && W >= nsi &&       // (2: never)
-            k_blocks(K) % kSuper == 0)
+            nkb % kSuper == 0)
             return launch_one<G, M, W, DEQ, FUSED, true>(p, X, packed, N, K, Y, stream, fu);
     }
     const half_t* x = static_cast<const half_t*>(X);
