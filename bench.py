@@ -32,7 +32,7 @@ PREFILL_M = 1024
 # this script, each scaled by the same counter's reading for a plain 1 GiB copy: x2.000 and x1.000); the
 # figures and the commands are in profiles/gemv_gemm_chatglm2_6b_hbm_traffic.txt.  They cannot be collected
 # inside a timed run, so they are constants here and apply to the default workload only.
-MEASURED_TRAFFIC_DECODE_LAUNCH = 27.31e6      # average GEMV launch of the 28 x 4 stack (algorithmic: 27.12e6)
+MEASURED_TRAFFIC_DECODE_LAUNCH = 27.30e6      # average GEMV launch of the 28 x 4 stack (algorithmic: 27.12e6)
 MEASURED_TRAFFIC_PREFILL_GATE_UP = 272.2e6    # M=1024 FFN gate+up GEMM (algorithmic: 124.1e6)
 
 
