@@ -58,7 +58,9 @@ struct GemvPlan {
 // `unit`: row blocks are dealt to workgroups in units of this many (2 for the gated epilogue, whose
 // workgroups own pairs of a gate and an up row block; the plan then counts units where it says row blocks,
 // except rb_per_wg, which counts row blocks).  `single_segment` tells whether all of X fits the LDS.
-GemvPlan make_plan(int64_t M, int64_t N, int64_t K, int unit = 1, bool* single_segment_out = nullptr)
+// `more_waves`: the caller also has the kernels with 10, 12 and 14 wavefronts (E0M4 codes, M = 1).
+GemvPlan make_plan(int64_t M, int64_t N, int64_t K, int unit = 1, bool* single_segment_out = nullptr,
+                   bool more_waves = false)
 {
     GemvPlan p;
     const int64_t nrb = row_blocks(N) / unit, nkb = k_blocks(K);
@@ -72,7 +74,13 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K, int unit = 1, bool* single_s
     if (!forced) w = (M <= 4 && (nsi >= 16 || (nsi >= 8 && nsi * unit * t_guess >= 32))) ? 16 : 8;
     // M = 1 with 1, 2, 4 or 8 whole work items per row block: 8 wavefronts, each of which then stays on its
     // own k blocks and keeps their activations in registers (measured 2-4 % faster than 16 wavefronts)
-    if (!forced && M == 1 && nkb % kSuper == 0 && 8 % nsi == 0 && knob("gemv_xreg") != 2) w = 8;
+    // (K = 5120, 6144, 7168: 10, 12 or 14 work items per row block get as many wavefronts, for the same reason;
+    // 10 and 14 load the four SIMDs unevenly, which costs more than it gains when a workgroup has only one or
+    // two row blocks: 5120 x 5120 takes 6.1 us against 5.7)
+    if (!forced && M == 1 && nkb % kSuper == 0 && knob("gemv_xreg") != 2) {
+        if (8 % nsi == 0) w = 8;
+        else if (more_waves && (nsi == 12 || ((nsi == 10 || nsi == 14) && unit * t_guess >= 3))) w = (int)nsi;
+    }
     int64_t t = 1;
     bool single_segment = true;
     for (;;) {
@@ -572,6 +580,13 @@ template <int G, int M, bool FUSED>
 int launch_w(const GemvPlan& p, const void* X, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
              const GemvFusion& fu)
 {
+    if constexpr (M == 1) {                             // one wavefront per work item of a row block, activations in registers
+        const bool own = p.step_item == 0 && p.step_slots == 1 && p.seg_items == p.waves;
+        if (p.waves == 10 && own) return launch_one<G, 1, 10, kDeqE0M4, FUSED, true>(p, X, packed, N, K, Y, stream, fu);
+        if (p.waves == 12 && own) return launch_one<G, 1, 12, kDeqE0M4, FUSED, true>(p, X, packed, N, K, Y, stream, fu);
+        if (p.waves == 14 && own) return launch_one<G, 1, 14, kDeqE0M4, FUSED, true>(p, X, packed, N, K, Y, stream, fu);
+    }
+    if (p.waves != 4 && p.waves != 8 && p.waves != 16) return E0M4_ERR_SHAPE;      // make_plan never asks for this
     switch (p.waves) {
         case 4: return launch_one<G, M, 4, kDeqE0M4, FUSED>(p, X, packed, N, K, Y, stream, fu);
         case 8: return launch_one<G, M, 8, kDeqE0M4, FUSED>(p, X, packed, N, K, Y, stream, fu);
@@ -603,7 +618,7 @@ int launch_m(const GemvPlan& p, int64_t M, const void* X, const void* packed, in
 int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                 hipStream_t stream)
 {
-    const GemvPlan p = make_plan(M, N, K);
+    const GemvPlan p = make_plan(M, N, K, 1, nullptr, true);
     switch (group) {
         case 32: return launch_m<32, false>(p, M, X, packed, N, K, Y, stream);
         case 64: return launch_m<64, false>(p, M, X, packed, N, K, Y, stream);
@@ -641,7 +656,7 @@ int launch_gemv_fused(const Fusion& f, const void* X, int64_t M, const void* pac
                       void* Y, hipStream_t stream)
 {
     if (!gemv_fused_supported(f, M, N, K)) return E0M4_ERR_SHAPE;
-    const GemvPlan p = make_plan(M, N, K, f.swiglu ? 2 : 1);
+    const GemvPlan p = make_plan(M, N, K, f.swiglu ? 2 : 1, nullptr, true);
     const int64_t half_bytes = gated_half_bytes(N, K, group);
     if (f.swiglu && half_bytes > kMaxHalfBytes) return E0M4_ERR_SHAPE;
     const GemvFusion fu = make_gemv_fusion(f, N, K, group);

@@ -165,6 +165,12 @@ def test_decode_kernel_forced_shapes(e0m4, oracle, waves, target):
         e0m4.e0m4_set_knob("gemv_workgroups", 0)
 
 
+@pytest.mark.parametrize("norm,swiglu,res", COMBOS)
+def test_decode_kernel_one_wavefront_per_work_item(e0m4, oracle, norm, swiglu, res):
+    run_fused(e0m4, oracle, 1, 12352, 5120, 128, seed=330, norm=norm, swiglu=swiglu, res=res)   # 10 wavefronts
+    run_fused(e0m4, oracle, 1, 320, 6144, 64, seed=331, norm=norm, swiglu=swiglu, res=res)      # 12
+
+
 def test_decode_kernel_long_rows(e0m4, oracle):
     # 8 rows of K = 16384 are staged in several segments: the norm's row sums come from memory, and the
     # gated epilogue (which needs whole rows in LDS) is served by the GEMM kernels instead

@@ -226,6 +226,19 @@ def test_gemv_activations_in_registers(e0m4, oracle, waves, xreg):
         e0m4.e0m4_set_knob("gemv_xreg", 0)
 
 
+@pytest.mark.parametrize("K,G", [(5120, 128), (6144, 64), (7168, 32), (5120, 64)])
+def test_gemv_one_wavefront_per_work_item(e0m4, oracle, K, G):
+    # 10, 12 or 14 work items per row block: as many wavefronts, activations in registers; and the same shapes without
+    run_matmul_case(e0m4, oracle, 1, 333, K, G, seed=70 + K // 1024, outliers=True)
+    run_matmul_case(e0m4, oracle, 1, 12300, K, G, seed=71 + K // 1024)         # four row blocks per workgroup (10 and 14
+                                                                               # wavefronts are used from three on)
+    e0m4.e0m4_set_knob("gemv_xreg", 2)
+    try:
+        run_matmul_case(e0m4, oracle, 1, 333, K, G, seed=72 + K // 1024)
+    finally:
+        e0m4.e0m4_set_knob("gemv_xreg", 0)
+
+
 @pytest.mark.parametrize("M", [1, 2, 5, 8])
 def test_gemv_ragged_last_work_item(e0m4, oracle, M):
     # K = 13 and 14 blocks of 128: the last group of four k blocks holds one or two; N ends inside a row block
