@@ -469,6 +469,11 @@ PipeTile pipe_tile(int64_t M, int64_t N, int64_t K)
     if (M <= kMidMaxM) return mid;
     // (For larger M with few large tiles the small tile avoids the K split and measured 12 % faster on
     // 1024 x 4096 x 4096 alone, but not inside the benchmark's back-to-back stream: not used there.)
+    // Unless the large tiles, K splits included, would leave a quarter of the compute units without work:
+    // 512 x 2560 x 2048 takes 22 us with the small tile (80 tiles x 4 splits), 26 us with the large one (20 x 4).
+    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256), pairs = K / (2 * BK);
+    const int64_t big_splits = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kComputeUnits / big_tiles, pairs / kMinPairsPerSplit), kMaxSplits));
+    if (big_tiles * big_splits < kComputeUnits * 3 / 4) return mid;
     return big;
 }
 
