@@ -282,15 +282,13 @@ int launch_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     return check_launch();
 }
 
-// The pipelined 256 x 256 kernel runs whenever its work items (tiles x K splits) can occupy a good
-// part of the chip; small problems (and K not a multiple of 128) take the 128 x 128 tile of this file.
+// The pipelined kernel runs whenever it can (K a multiple of 128): with its three tiles and the K split it was
+// never slower than the kernel of this file on any measured shape, and up to 2.7x faster on small ones
+// (M = 17..96, 2048 x 2048: 12 us against 31).  gemm_variant 1 forces the kernel of this file.
 bool use_pipe(int64_t M, int64_t N, int64_t K, bool swiglu = false)
 {
-    if (!gemm_pipe_supported(K)) return false;
-    const int v = knob("gemm_variant");             // 1: always the small tile of this file, 2: always the pipelined kernel
-    if (v == 2 || v == 3 || v == 4) return true;
-    if (v == 1) return false;
-    return gemm_pipe_work_items(M, N, K, swiglu) >= 96;
+    (void)M; (void)N; (void)swiglu;
+    return gemm_pipe_supported(K) && knob("gemm_variant") != 1;
 }
 
 }  // namespace

@@ -445,13 +445,20 @@ constexpr int kComputeUnits = 256;
 constexpr int kMinPairsPerSplit = 4;
 constexpr int kMaxSplits = 8;
 
-// The tile a problem gets: 128 x 128 (two workgroups per compute unit) when M is at most kMidMaxM rows,
-// else 256 x 256.  (gemm_variant 2 forces the large tile, 3 the small one.)  Measured on the ChatGLM2-6B
-// shapes: at M = 128 the small tile takes 21-45 us where the large one takes 28-65, at M = 256 they are
-// within 10 %, at M = 512 the large tile is up to 1.3x faster; between 257 and 384 rows the large tile
-// would compute a quarter to a half of its rows for nothing.
-constexpr int kMidMaxM = 384;
-constexpr int kFlatMaxM = 64;                           // 64 x 256 tile: no rows computed for nothing up to here
+// The tile a problem gets (gemm_variant 2, 3, 4 force the 256 x 256, 128 x 128 and 64 x 256 tile).  Measured over
+// a grid of M = 17 .. 2048 and layer shapes of 2B to 14B models:
+//  - up to kFlatMaxM rows the 64 x 256 tile (four wavefronts side by side, every weight dequantised once per
+//    workgroup) is never slower than the 128 x 128 tile and up to 27 % faster (M = 160: three row tiles of 64
+//    instead of two of 128);
+//  - above, the 256 x 256 tile, unless it yields few tiles: under kFewBigTiles when M is at most kFlatAlsoMaxM
+//    (512 x 4096 x 4096: 31 us against 38), under kFewBigTilesShortK when the K splits that fill the chip would be
+//    very short (under kShortSplitPairs pairs of K slices each; 2048 x 2560 x 2048: 34 us against 43).  The
+//    prologue, epilogue and reduction of many short work items then cost more than the small tile's lower rate.
+constexpr int kFlatMaxM = 384;
+constexpr int kFlatAlsoMaxM = 640;
+constexpr int kFewBigTiles = 80;
+constexpr int kFewBigTilesShortK = 128;
+constexpr int kShortSplitPairs = 8;
 struct PipeTile {
     int bm, bn;
     int slots;                                          // work items wanted before K is split no further
@@ -460,20 +467,16 @@ struct PipeTile {
 PipeTile pipe_tile(int64_t M, int64_t N, int64_t K)
 {
     const PipeTile mid{128, 128, kComputeUnits + kComputeUnits / 2}, big{256, 256, kComputeUnits};
-    const PipeTile flat{64, 256, 2 * kComputeUnits};                       // few rows: four wavefronts side by side
+    const PipeTile flat{64, 256, 2 * kComputeUnits};
     const int v = knob("gemm_variant");
     if (v == 4) return flat;
     if (v == 3) return mid;
     if (v == 2) return big;
     if (M <= kFlatMaxM) return flat;
-    if (M <= kMidMaxM) return mid;
-    // (For larger M with few large tiles the small tile avoids the K split and measured 12 % faster on
-    // 1024 x 4096 x 4096 alone, but not inside the benchmark's back-to-back stream: not used there.)
-    // Unless the large tiles, K splits included, would leave a quarter of the compute units without work:
-    // 512 x 2560 x 2048 takes 22 us with the small tile (80 tiles x 4 splits), 26 us with the large one (20 x 4).
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256), pairs = K / (2 * BK);
     const int64_t big_splits = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kComputeUnits / big_tiles, pairs / kMinPairsPerSplit), kMaxSplits));
-    if (big_tiles * big_splits < kComputeUnits * 3 / 4) return mid;
+    if (big_tiles < kFewBigTiles && M <= kFlatAlsoMaxM) return flat;
+    if (big_tiles < kFewBigTilesShortK && pairs / big_splits < kShortSplitPairs) return flat;
     return big;
 }
 
