@@ -120,9 +120,11 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  *            (about M * K * 2 <= 140 KiB): same decomposition, the dot
  *            products run on the matrix cores so the cost stays near the
  *            weight stream for every such M.
- *   M >= 9 otherwise : MFMA GEMM path (tiles of 64 x 256 outputs up to
- *            M = 384 and for few large tiles, else 256 x 256; split along K
- *            when tiles are few).
+ *   M >= 9 otherwise, and 2 <= M <= 8 when M * N * K is about 3.8e8 or
+ *            more (the vector kernel's time grows with M): MFMA GEMM path
+ *            (tiles of 64 x 256 outputs up to M = 384 and for few large
+ *            tiles, else 256 x 256; split along K when tiles are few).
+ *            e0m4_workspace_bytes() tells when a workspace is needed.
  * `scales_f16`/`bias_f16` may be NULL (see `codes` above); `workspace` may be
  * NULL when e0m4_workspace_bytes() is 0, else it is device memory of at least
  * that many bytes, 16-byte aligned, owned by the caller, overwritten by the

@@ -37,6 +37,15 @@ bool use_gemv_mfma(int64_t M, int64_t N, int64_t K, int group)
 {
     return knob("gemv_mfma") != 1 && gemv_mfma_supported(M, N, K, group);
 }
+// M <= kGemvMaxM rows take the vector decode kernel, whose time grows with M, unless the matrix-core GEMM
+// (64 x 256 tile, time nearly independent of M) is faster: measured crossover at about M * N * K = 3.8e8
+// (27392 x 4096 from M = 4 on, 4096 x 13696 from M = 7 on, never for 4096 x 4096).
+bool small_m_on_vector(int64_t M, int64_t N, int64_t K)
+{
+    if (M > kGemvMaxM) return false;
+    if (M < 2 || !gemm_pipe_supported(K) || N > (int64_t)1 << 24) return true;
+    return (double)M * (double)N * (double)K < 3.8e8;
+}
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Shape rules shared by all entry points.
@@ -105,7 +114,7 @@ size_t e0m4_params_elems(int64_t N, int64_t K, int group)
 
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 {
-    if (check_shape(N, K, group) != E0M4_OK || M <= kGemvMaxM || K == 0) return 0;   // the small-M kernels need none
+    if (check_shape(N, K, group) != E0M4_OK || small_m_on_vector(M, N, K) || K == 0) return 0;   // the small-M kernels need none
     if (use_gemv_mfma(M, N, K, group)) return 0;
     return gemm_workspace_bytes(M, N, K);       // partial tiles of the split-K GEMM, if it splits
 }
@@ -120,7 +129,7 @@ static size_t norm_bytes(int64_t M, int64_t K) { return ((size_t)M * (size_t)K *
 static int fused_path(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)
 {
     if (knob("gemv_mfma") != 1 && gemv_mfma_fused_supported(f, M, N, K, group)) return 2;
-    return (M <= kGemvMaxM && gemv_fused_supported(f, M, N, K)) ? 0 : 1;
+    return (small_m_on_vector(M, N, K) && gemv_fused_supported(f, M, N, K)) ? 0 : 1;
 }
 
 size_t e0m4_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int group, int with_rmsnorm, int epilogue)
@@ -244,7 +253,7 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
     if (!X || !codes) return E0M4_ERR_NULL;
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
     if (use_gemv_mfma(M, N, K, group)) return launch_gemv_mfma(X, M, codes, N, K, Y, (hipStream_t)stream);
-    if (M <= kGemvMaxM) return launch_gemv(X, M, codes, N, K, group, Y, (hipStream_t)stream);
+    if (small_m_on_vector(M, N, K)) return launch_gemv(X, M, codes, N, K, group, Y, (hipStream_t)stream);
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // the GEMM epilogue forms 32-bit offsets of up to 256 rows of Y
     if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
     return launch_gemm(X, M, codes, N, K, group, Y, workspace, workspace_bytes, (hipStream_t)stream);

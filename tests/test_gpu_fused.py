@@ -171,6 +171,10 @@ def test_decode_kernel_one_wavefront_per_work_item(e0m4, oracle, norm, swiglu, r
     run_fused(e0m4, oracle, 1, 320, 6144, 64, seed=331, norm=norm, swiglu=swiglu, res=res)      # 12
 
 
+def test_few_rows_with_large_weights_take_the_gemm(e0m4, oracle):
+    run_fused(e0m4, oracle, 8, 12288, 4096, 64, seed=332, norm=True, swiglu=True, res=True)
+
+
 def test_decode_kernel_long_rows(e0m4, oracle):
     # 8 rows of K = 16384 are staged in several segments: the norm's row sums come from memory, and the
     # gated epilogue (which needs whole rows in LDS) is served by the GEMM kernels instead

@@ -412,6 +412,16 @@ def test_matmul_is_deterministic(e0m4, M):
     assert np.array_equal(y1, y2)
 
 
+@pytest.mark.parametrize("M,G", [(8, 64), (5, 32), (8, 128)])
+def test_few_rows_with_large_weights_take_the_gemm(e0m4, oracle, M, G):
+    # M * N * K above 3.8e8 and no small-batch matrix-core kernel (other groups; at G = 128, X beyond the LDS):
+    # the 64 x 256 GEMM tile instead of the vector kernel
+    if G == 128:
+        run_matmul_case(e0m4, oracle, M, 1600, 32768, G, seed=611)         # 8 rows of K = 32768 do not fit the LDS
+    else:
+        run_matmul_case(e0m4, oracle, M, 24000 if M == 5 else 12288, 4096, G, seed=610 + M, outliers=True)
+
+
 @pytest.mark.parametrize("M", [1, 3, 20])
 def test_longest_rows(e0m4, oracle, M):
     # K at its limit of 2^20: the decode kernel stages X in many segments, the GEMM runs 16384 K slices in 8 splits
