@@ -100,7 +100,10 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K, int unit = 1, bool* single_s
         // the target number of workgroups can be reached with at most t row blocks each, use exactly the
         // target (every compute unit then holds the same number of workgroups); else the fewest that do.
         p.grid = (nrb + t - 1) / t;
-        if (t > 1 && p.grid < target && (int64_t)target * t >= nrb) p.grid = target;
+        // (Not for pairs of row blocks, gated epilogue: their uneven deal leaves a few workgroups two row blocks
+        // more than the rest, and a compute unit on its own cannot draw the bandwidth to catch up; 856 pairs on
+        // 214 workgroups of four take 13.0 us, on 256 workgroups of three or four 13.9.)
+        if (unit == 1 && t > 1 && p.grid < target && (int64_t)target * t >= nrb) p.grid = target;
         // fewer wavefronts when a workgroup has fewer work items than wavefronts
         if (!forced && w > 4 && nsi * unit * t < w) { w /= 2; continue; }
         break;
