@@ -163,54 +163,47 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     const int pieces = nkb * (XBB / 16);
     const bool normed = FUSED && fu.gamma != nullptr;
     const int cpr = (pieces + kThreads - 1) / kThreads;        // chunks per row
-    const int n_chunks = M * cpr;
-    constexpr int kStageBatch = 4;
+    constexpr int kStageBatch = 8;                      // loads in flight per thread and staging step
     const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     if (normed) {
         // rms-norm: sum of squares of every row (first pass over X; the staging pass below reads it again,
-        // from the cache), reduced in a fixed order: lanes, then wavefronts
-        int m_it = 0, c_it = 0;                         // row and chunk of the next piece
-        int cur_m = 0;                                  // row whose squares `cur` holds
-        float cur = 0.f;
-        auto flush_row = [&]() {
-            float v = cur;
+        // from the cache), reduced in a fixed order: lanes, then wavefronts;
+        // kNormRows rows at a time: their loads are in flight together and their wavefront reductions (chains of
+        // cross-lane steps, each with the latency of an LDS access) overlap instead of running row after row
+        constexpr int kNormRows = 8;
+        for (int m0 = 0; m0 < M; m0 += kNormRows) {
+            float sq[kNormRows];
 #pragma unroll
-            for (int d = 1; d < 64; d <<= 1) v += __shfl_xor(v, d);
-            if (lane == 0) norm_part[wave * kMaxM + cur_m] = v;
-        };
-        for (int j0 = 0; j0 < n_chunks; j0 += kStageBatch) {
-            half8_t vb[kStageBatch];
-            int mrow[kStageBatch];
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int pc = c_it * kThreads + t;
+            for (int r = 0; r < kNormRows; ++r) sq[r] = 0.f;
+            for (int c0 = 0; c0 < cpr; ++c0) {
+                const int pc = c0 * kThreads + t;
                 const int64_t k = (int64_t)pc * 8;
-                mrow[u] = m_it;
-                vb[u] = zero8;
-                if (j0 + u < n_chunks && pc < pieces && k < K) vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m_it * K + k);
-                if (++c_it == cpr) {
-                    c_it = 0;
-                    ++m_it;
+                half8_t vb[kNormRows];
+#pragma unroll
+                for (int r = 0; r < kNormRows; ++r) {
+                    vb[r] = zero8;
+                    if (m0 + r < M && pc < pieces && k < K) vb[r] = *reinterpret_cast<const half8_t*>(X + (int64_t)(m0 + r) * K + k);
+                }
+#pragma unroll
+                for (int r = 0; r < kNormRows; ++r) {
+                    const half8_t v = vb[r];
+                    const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
+                    float d = __builtin_amdgcn_fdot2(x0, x0, sq[r], false);
+                    d = __builtin_amdgcn_fdot2(x1, x1, d, false);
+                    d = __builtin_amdgcn_fdot2(x2, x2, d, false);
+                    sq[r] = __builtin_amdgcn_fdot2(x3, x3, d, false);
                 }
             }
 #pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                if (j0 + u >= n_chunks) break;
-                if (mrow[u] != cur_m) {                 // (uniform) the previous row is complete
-                    flush_row();
-                    cur = 0.f;
-                    cur_m = mrow[u];
-                }
-                const half8_t v = vb[u];
-                const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
-                float d = __builtin_amdgcn_fdot2(x0, x0, 0.f, false);
-                d = __builtin_amdgcn_fdot2(x1, x1, d, false);
-                d = __builtin_amdgcn_fdot2(x2, x2, d, false);
-                d = __builtin_amdgcn_fdot2(x3, x3, d, false);
-                cur += d;
+            for (int d = 1; d < 64; d <<= 1)
+#pragma unroll
+                for (int r = 0; r < kNormRows; ++r) sq[r] += __shfl_xor(sq[r], d);
+            if (lane == 0) {
+#pragma unroll
+                for (int r = 0; r < kNormRows; ++r)
+                    if (m0 + r < M) norm_part[wave * kMaxM + m0 + r] = sq[r];
             }
         }
-        flush_row();
         __syncthreads();
         float tot = 0.f;
         if (t < M) {
