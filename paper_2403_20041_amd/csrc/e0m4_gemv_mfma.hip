@@ -157,9 +157,7 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 #pragma unroll
     for (int j = 0; j < kSuper; ++j) fetch_code(j, slot, si);
 
-    // ---- stage X in pieces of 8 elements (k = 8*pc .. 8*pc+7 of row m).  Pieces are visited row by row,
-    // kThreads at a time ("chunks"), so the row of a piece is uniform across the workgroup and no index needs
-    // a division; the loads of four chunks are in flight at a time.
+    // ---- stage X in pieces of 8 elements (k = 8*pc .. 8*pc+7 of row m); no piece index needs a division
     const int pieces = nkb * (XBB / 16);
     const bool normed = FUSED && fu.gamma != nullptr;
     const int cpr = (pieces + kThreads - 1) / kThreads;        // chunks per row
