@@ -281,7 +281,10 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     // most kEarlyX items per wavefront) -- it stages exactly those (one piece per lane and item; wavefronts on
     // the same k blocks write the same bytes) and waits for no other wavefront before it starts.
     const bool normed = FUSED && fu.gamma != nullptr;   // then staging waits for the row scales (below)
-    const bool own_x = !normed && (XREG || own_items != 0);
+    // With rms-norm the same holds for XREG when every k block belongs to exactly one wavefront (step_slots == 1):
+    // the wavefronts' sums of squares of their own pieces add up to the row's, and only that sum crosses wavefronts.
+    const bool own_norm = normed && XREG && M == 1 && step_slots == 1;
+    const bool own_x = (!normed && (XREG || own_items != 0)) || own_norm;
     constexpr int kItemPieces = kSuper * BLK_K / 8;     // pieces of one work item's activations: 64 (32 for 8-bit codes)
     auto own_idx = [&](int e) {                         // piece index of this lane for the wavefront's item number e
         const int it = si + e * W;
@@ -293,7 +296,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     half8_t gearly[kEarlyX];                            // norm weights of the early pieces, requested with them
 #pragma unroll
-    for (int e = 0; e < kEarlyX; ++e) gearly[e] = normed ? g_piece(t + e * kThreads, 0) : zero8;
+    for (int e = 0; e < kEarlyX; ++e) gearly[e] = normed ? g_piece(own_norm ? own_idx(e) : t + e * kThreads, 0) : zero8;
     // gated or not, result number t of the epilogue is this thread's first: request its residual value now
     float res_early = 0.f;
     if (FUSED && fu.residual) {
@@ -349,7 +352,9 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
 #pragma unroll
             for (int mm = 0; mm < M; ++mm) ss[mm] += mm == m ? d : 0.f;
         };
-        if (seg_items >= nsi) {                         // segment 0 is all of K (pieces beyond K are zero)
+        if (own_norm) {                                 // this wavefront's share: its own piece per lane
+            add_squares(0, xearly[0]);
+        } else if (seg_items >= nsi) {                  // segment 0 is all of K (pieces beyond K are zero)
 #pragma unroll
             for (int e = 0; e < kEarlyX; ++e) {
                 const int idx = t + e * kThreads;
@@ -379,7 +384,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
             for (int w = 0; w < W; ++w) v += part[w * M + m];
             rs[m] = 1.f / sqrtf(v / (float)K + fu.eps);
         }
-        stage_from(t + kEarlyX * kThreads, 0);
+        if (!own_norm) stage_from(t + kEarlyX * kThreads, 0);
     }
 
     float acc[M];
@@ -402,7 +407,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
         // stage the segment's activations and the sums of every 32-wide chunk
         if (own_x) {                                    // (single segment) the wavefront's own pieces, read back by itself
 #pragma unroll
-            for (int e = 0; e < (XREG ? 1 : kEarlyX); ++e) x_store(own_idx(e), xearly[e], zero8);
+            for (int e = 0; e < (XREG ? 1 : kEarlyX); ++e) x_store(own_idx(e), xearly[e], gearly[e]);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
