@@ -161,9 +161,50 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     const int pieces = nkb * (XBB / 16);
     const bool normed = FUSED && fu.gamma != nullptr;
     const int cpr = (pieces + kThreads - 1) / kThreads;        // chunks per row
-    constexpr int kStageBatch = 8;                      // loads in flight per thread and staging step
+    constexpr int kStageBatch = W >= 16 ? 4 : 8;        // loads in flight per thread and staging step (register budget)
     const half8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (normed) {
+    // XREG with every k block in exactly one wavefront (step_slots == 1): a wavefront needs only the pieces of its
+    // own four k blocks, also for the rms-norm, since the row's sum of squares is the sum of the wavefronts' own.
+    // The pieces (one per lane and row of X) stay in registers until the row scales are known.
+    constexpr int kItemPieces = kSuper * XBB / 16;      // pieces of one row of X per work item: 64 (32 for 8-bit codes)
+    // (not with sixteen wavefronts: 64 more registers do not fit their budget of 128)
+    const bool own_norm = W <= 8 && normed && XREG && step_slots == 1;
+    const int pc_own = si * kItemPieces + lane;
+    const bool own_ok = lane < kItemPieces && pc_own < pieces;      // (a last work item may reach beyond the row's blocks)
+    half8_t keep[kMaxM], g_own = zero8;
+    if (own_norm) {
+        const bool in_k = own_ok && (int64_t)pc_own * 8 < K;
+#pragma unroll
+        for (int m = 0; m < kMaxM; ++m) {
+            keep[m] = zero8;
+            if (m < M && in_k) keep[m] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + (int64_t)pc_own * 8);
+        }
+        if (in_k) g_own = *reinterpret_cast<const half8_t*>(fu.gamma + (int64_t)pc_own * 8);
+#pragma unroll
+        for (int m0 = 0; m0 < kMaxM; m0 += 8) {         // eight rows' reductions at a time (their latencies overlap)
+            if (m0 >= M) break;
+            float sq[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const half8_t v = keep[m0 + r];
+                const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
+                float d = __builtin_amdgcn_fdot2(x0, x0, 0.f, false);
+                d = __builtin_amdgcn_fdot2(x1, x1, d, false);
+                d = __builtin_amdgcn_fdot2(x2, x2, d, false);
+                sq[r] = __builtin_amdgcn_fdot2(x3, x3, d, false);
+            }
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1)
+#pragma unroll
+                for (int r = 0; r < 8; ++r) sq[r] += __shfl_xor(sq[r], d);
+            if (lane == 0) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    if (m0 + r < M) norm_part[wave * kMaxM + m0 + r] = sq[r];
+            }
+        }
+    }
+    if (normed && !own_norm) {
         // rms-norm: sum of squares of every row (first pass over X; the staging pass below reads it again,
         // from the cache), reduced in a fixed order: lanes, then wavefronts;
         // kNormRows rows at a time: their loads are in flight together and their wavefront reductions (chains of
@@ -202,6 +243,8 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
                     if (m0 + r < M) norm_part[wave * kMaxM + m0 + r] = sq[r];
             }
         }
+    }
+    if (normed) {                                       // the wavefronts' sums, in wavefront order, then the row scales
         __syncthreads();
         float tot = 0.f;
         if (t < M) {
@@ -234,9 +277,15 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     // XREG without rms-norm: a wavefront needs nothing but the activations of its own four k blocks, so it
     // stages exactly those and waits for no other wavefront before it starts.  (Wavefronts on the same k
     // blocks write the same bytes; not done when they would each load many rows twice.)
-    constexpr int kItemPieces = kSuper * XBB / 16;      // pieces of one row of X per work item: 64 (32 for 8-bit codes)
     const bool own_x = XREG && !normed && (step_slots == 1 || M <= 4);
-    if (own_x) {
+    if (own_norm) {
+#pragma unroll
+        for (int m = 0; m < kMaxM; ++m)
+            if (m < M) store_piece(m, pc_own, own_ok, keep[m], g_own);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // read back by the wavefront that wrote it
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else if (own_x) {
         for (int i0 = 0; i0 < M * kItemPieces; i0 += kStageBatch * 64) {
             half8_t vb[kStageBatch];
 #pragma unroll
