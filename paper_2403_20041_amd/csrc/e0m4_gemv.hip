@@ -96,14 +96,12 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K, int unit = 1, bool* single_s
         t = (nrb + target - 1) / target;
         if (t > t_max) t = t_max;
         if (t < 1 || !single_segment) t = 1;   // several activation segments: one row block per workgroup
-        // Row blocks are dealt out evenly (the first nrb % grid workgroups own one more).  When
-        // the target number of workgroups can be reached with at most t row blocks each, use exactly the
-        // target (every compute unit then holds the same number of workgroups); else the fewest that do.
+        // Row blocks (pairs of them with the gated epilogue) are dealt out evenly over the fewest workgroups that
+        // keep the largest share t: then nearly all of them end together.  With more workgroups a few would own
+        // one more than the rest, and a compute unit on its own cannot draw the bandwidth to catch up: 320 row
+        // blocks of K = 13696 take 10.6 us on 160 workgroups of two, 11.8 us on 256 of one or two; 856 pairs 13.0 us
+        // on 214 workgroups of four, 13.9 us on 256 of three or four.
         p.grid = (nrb + t - 1) / t;
-        // (Not for pairs of row blocks, gated epilogue: their uneven deal leaves a few workgroups two row blocks
-        // more than the rest, and a compute unit on its own cannot draw the bandwidth to catch up; 856 pairs on
-        // 214 workgroups of four take 13.0 us, on 256 workgroups of three or four 13.9.)
-        if (unit == 1 && t > 1 && p.grid < target && (int64_t)target * t >= nrb) p.grid = target;
         // fewer wavefronts when a workgroup has fewer work items than wavefronts
         if (!forced && w > 4 && nsi * unit * t < w) { w /= 2; continue; }
         break;

@@ -524,8 +524,8 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, 
     int target = knob("gemv_workgroups");
     if (target <= 0) target = kTargetWorkgroups;
     p.grid = std::min<int64_t>(nrb, target);
-    if (unit == 2 && nrb > target) {                    // pairs of row blocks: the fewest workgroups with the same
-        const int64_t most = (nrb + target - 1) / target;   // largest share, so that (nearly) all of them end together
+    if (nrb > target) {                                 // the fewest workgroups with the same largest share of row
+        const int64_t most = (nrb + target - 1) / target;   // blocks (or pairs), so that (nearly) all of them end together
         p.grid = (nrb + most - 1) / most;
     }
     p.waves = w;
