@@ -518,7 +518,8 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, 
     const int64_t nrb = row_blocks(N) / unit, nkb = k_blocks(K);
     const int64_t nsi = (nkb + kSuper - 1) / kSuper;
     int w = knob("gemv_waves");
-    if (w != 4 && w != 8 && w != 16) w = nsi >= 16 ? 16 : 8;
+    // (sixteen wavefronts beyond K = 8192; at K = 8192 eight are faster: 8192 x 8192 at M = 4 takes 10.5 us, 12.1 with 16)
+    if (w != 4 && w != 8 && w != 16) w = (e8 ? nsi >= 16 : nsi > 16) ? 16 : 8;
     while (w > 4 && lds_need(M, nkb, w, e8) > (size_t)kLdsLimitBytes) w /= 2;
     if (lds_need(M, nkb, w, e8) > (size_t)kLdsLimitBytes) return false;
     int target = knob("gemv_workgroups");
@@ -559,12 +560,13 @@ int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packe
 }
 
 // Activations in registers when a wavefront always meets the same k blocks (step_item == 0); the kernel
-// then needs about 125 registers per lane, which 16 wavefronts still allow.
+// then needs about 125 registers per lane -- more than sixteen wavefronts have without spilling (that form measured
+// twice as slow as reading X from LDS), so it is used with up to eight.
 template <int W, bool FUSED>
 int launch_mfma(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                 hipStream_t stream, const GemvFusion& fu = GemvFusion{})
 {
-    if (p.step_item == 0 && knob("gemv_mfma") != 2)
+    if (p.step_item == 0 && W <= 8 && knob("gemv_mfma") != 2)
         return launch_mfma_x<W, FUSED, true>(p, X, M, packed, N, K, Y, stream, fu);
     return launch_mfma_x<W, FUSED, false>(p, X, M, packed, N, K, Y, stream, fu);
 }
