@@ -356,7 +356,7 @@ static bool e0m8_use_mfma_decode(int64_t M, int64_t N, int64_t K)
 
 static bool e0m8_use_gemm(int64_t M, int64_t N, int64_t K)
 {
-    return !e0m8_use_mfma_decode(M, N, K) && M > kGemvMaxM && gemm_pipe_supported(K) && N <= (int64_t)1 << 24;
+    return !e0m8_use_mfma_decode(M, N, K) && !small_m_on_vector(M, N, K) && gemm_pipe_supported(K) && N <= (int64_t)1 << 24;
 }
 
 size_t e0m8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
@@ -402,7 +402,7 @@ int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t 
 static int fused_path8(const Fusion& f, int64_t M, int64_t N, int64_t K)
 {
     if (knob("gemv_mfma") != 1 && gemv_mfma8_fused_supported(f, M, N, K)) return 2;
-    if (M <= kGemvMaxM && gemv_fused_supported(f, M, N, 2 * K)) return 0;
+    if (small_m_on_vector(M, N, K) && gemv_fused_supported(f, M, N, 2 * K)) return 0;
     return gemm_pipe_supported(K) && N <= (int64_t)1 << 24 ? 1 : -1;
 }
 

@@ -518,8 +518,9 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, 
     const int64_t nrb = row_blocks(N) / unit, nkb = k_blocks(K);
     const int64_t nsi = (nkb + kSuper - 1) / kSuper;
     int w = knob("gemv_waves");
-    // (sixteen wavefronts beyond K = 8192; at K = 8192 eight are faster: 8192 x 8192 at M = 4 takes 10.5 us, 12.1 with 16)
-    if (w != 4 && w != 8 && w != 16) w = (e8 ? nsi >= 16 : nsi > 16) ? 16 : 8;
+    // (sixteen wavefronts for more than 16 work items per row block; with exactly 16 eight are faster: 8192 x 8192
+    // at M = 4 takes 10.5 us, 12.1 with sixteen; 8-bit 4096 x 4096 at M = 2 5.9 against 6.7)
+    if (w != 4 && w != 8 && w != 16) w = nsi > 16 ? 16 : 8;
     while (w > 4 && lds_need(M, nkb, w, e8) > (size_t)kLdsLimitBytes) w /= 2;
     if (lds_need(M, nkb, w, e8) > (size_t)kLdsLimitBytes) return false;
     int target = knob("gemv_workgroups");
