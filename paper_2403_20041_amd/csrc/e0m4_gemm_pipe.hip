@@ -452,7 +452,8 @@ constexpr int kMaxSplits = 8;
 //    instead of two of 128);
 //  - above, the 256 x 256 tile, unless it yields few tiles: under kFewBigTiles when M is at most kFlatAlsoMaxM
 //    (512 x 4096 x 4096: 31 us against 38), under kFewBigTilesShortK when the K splits that fill the chip would be
-//    very short (under kShortSplitPairs pairs of K slices each; 2048 x 2560 x 2048: 34 us against 43).  The
+//    short (at most kShortSplitPairs pairs of K slices each; 2048 x 2560 x 2048: 34 us against 43; 1024 x 4096 x
+//    4096: 50 us against 54).  The
 //    prologue, epilogue and reduction of many short work items then cost more than the small tile's lower rate.
 constexpr int kFlatMaxM = 384;
 constexpr int kFlatAlsoMaxM = 640;
@@ -476,7 +477,7 @@ PipeTile pipe_tile(int64_t M, int64_t N, int64_t K)
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256), pairs = K / (2 * BK);
     const int64_t big_splits = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kComputeUnits / big_tiles, pairs / kMinPairsPerSplit), kMaxSplits));
     if (big_tiles < kFewBigTiles && M <= kFlatAlsoMaxM) return flat;
-    if (big_tiles < kFewBigTilesShortK && pairs / big_splits < kShortSplitPairs) return flat;
+    if (big_tiles < kFewBigTilesShortK && pairs / big_splits <= kShortSplitPairs) return flat;
     return big;
 }
 
