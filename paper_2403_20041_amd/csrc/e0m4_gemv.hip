@@ -14,10 +14,11 @@
 // binade values with one rotate and four mask-or per eight codes, accumulates
 // a = sum x*w1 with v_dot2_f32_f16, and applies the group's affine map once per
 // block:  y += scale * (a - bias * sum x).
-// Activations are staged once per workgroup in LDS, with the sums of every
-// 32-wide chunk; a wavefront that meets the same k blocks in every row block
-// (M = 1, see XREG below) copies them to registers once, otherwise they are read
-// from LDS block by block.  The four k-quarters of a row are added with two
+// Activations are staged in LDS, with the sums of every 32-wide chunk: once per
+// workgroup, or, when a wavefront only ever needs the activations of its own work
+// items, by every wavefront for itself, without a workgroup barrier.  A wavefront
+// that meets the same k blocks in every row block (M = 1, see XREG below) copies
+// them to registers once, otherwise they are read from LDS block by block.  The four k-quarters of a row are added with two
 // cross-lane steps, the wavefronts' sums through LDS in a fixed order
 // (deterministic result).  The same kernel serves the INT4 comparison format and
 // the 8-bit format E0M8 (template argument DEQ) and, as FUSED, folds in the
