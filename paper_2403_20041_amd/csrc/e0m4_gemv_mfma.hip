@@ -50,6 +50,10 @@ struct MfmaPlan {
     int64_t grid;
     size_t lds_bytes;
     uint32_t pieces_magic;                      // ceil(2^32 / pieces of 8 activations per row): row of a piece by multiplication
+    // X longer than the LDS holds: K is walked in phases of kb_phase blocks (a multiple of kSuper; 0: one phase),
+    // each phase stages its part of X and visits all row blocks of the workgroup
+    int kb_phase;
+    uint32_t pieces_magic_last;                 // the same for the (shorter) last phase
 };
 
 constexpr int kNormBytes = (16 + 1) * kMaxM * 4;        // rms-norm: per-wavefront sums of squares and the row scales
@@ -79,27 +83,33 @@ __device__ inline int x_unit_off(int q, int w, int hl) { return ((q * 4 + (w >> 
 // E8: the 8-bit format E0M8 (e0m8_pack.hip).  A block holds 64 weights, a lane's chunk 16, and one MFMA
 // takes the eight weights of two words per lane, each word turned into two pairs of binade values by a
 // mask-or and a rotation; there is only one kind of code slot, so one accumulator and the plain sum of X.
-template <int W, bool FUSED, bool XREG, bool E8 = false>
+// PHASED: M rows of X do not fit the LDS.  K is walked in phases of kb_phase blocks: every phase stages its
+// part of X, visits all row blocks of the workgroup and adds to the wavefront sums, which stay in LDS
+// (`late`) until the last phase.  The weights are still read exactly once.
+template <int W, bool FUSED, bool XREG, bool E8 = false, bool PHASED = false>
 __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restrict__ X, int M,
                                                            const uint4* __restrict__ packed, int64_t N, int64_t K,
-                                                           half_t* __restrict__ Y, int step_slots, int step_item,
-                                                           int rb_base, int rb_rem, int late, uint32_t pieces_magic,
-                                                           GemvFusion fu)
+                                                           half_t* __restrict__ Y, int step_slots_arg, int step_item_arg,
+                                                           int rb_base, int rb_rem, int late, uint32_t pieces_magic_arg,
+                                                           int kb_phase, uint32_t pieces_magic_last, GemvFusion fu)
 {
+    static_assert(!(PHASED && XREG), "a wavefront meets other k blocks in every phase");
     constexpr int kThreads = W * 64;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int XBB = E8 ? kXBlockBytes / 2 : kXBlockBytes;   // bytes of X per row and block
     constexpr int UB = E8 ? 16 : 32;                            // bytes per (k-group, MFMA pair) unit of a block
     const PackedLayout<kG> lay(E8 ? 2 * K : K);
     const int nkb = (int)lay.nkb;
-    const int nsi = (nkb + kSuper - 1) / kSuper;
-    const int row_stride = nkb * XBB + kRowPadBytes;
+    const int nkb_lds = PHASED ? kb_phase : nkb;        // k blocks of X that the LDS holds at a time
+    const int n_ph = PHASED ? (nkb + kb_phase - 1) / kb_phase : 1;
+    const int row_stride = nkb_lds * XBB + kRowPadBytes;
     unsigned char* xs = smem;                                                   // [M] rows of X in MFMA order
     float* norm_part = reinterpret_cast<float*>(smem + (size_t)M * row_stride); // [W][16] sums of squares, then [16] row scales
     // wavefront sums: [2][W][16 m][16 n], reduced row block by row block; or, when `late` (LDS permitting),
     // [row blocks][W][M][16 n], reduced once at the end without a barrier per row block
     float* red = norm_part + kNormBytes / 4;
 
+    if (PHASED) late = 1;                               // the sums of a row block are complete after the last phase only
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -119,6 +129,9 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
         return s_ * rb_stride;
     };
 
+    // ---- per phase: the k blocks [kb_lo, kb_lo + nkb_ph) of every row block, as nsi work items per row block
+    int kb_lo = 0, nkb_ph = nkb, nsi = (nkb + kSuper - 1) / kSuper;
+    int step_slots = step_slots_arg, step_item = step_item_arg;
     auto advance = [&](int& s_, int& i_) {              // W work items ahead
         s_ += step_slots;
         i_ += step_item;
@@ -127,13 +140,8 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
             ++s_;
         }
     };
-    int slot = 0, si = wave;                            // current work item: row block slot, item inside the row block
-    while (si >= nsi) {
-        si -= nsi;
-        ++slot;
-    }
-    int nslot = slot, nitem = si;
-    advance(nslot, nitem);
+    int slot = 0, si = 0;                               // current work item: row block slot, item inside the row block
+    int nslot = 0, nitem = 0;                           // the one after it (in flight)
 
     // ---- the work item in flight: four code blocks and their 64 parameter words (one per lane)
     uint4 c[kSuper];
@@ -141,21 +149,40 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     auto fetch_params = [&](int fs, int fi) {           // past the end the last item is read again
         const bool in = fs < n_rb;
         const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
-        const uint32_t soff = __builtin_amdgcn_readfirstlane(slot_off(s_) + i_ * (kSuper * kPW * 4));
-        const int last = param_words_rb - 1 - (int)i_ * (kSuper * kPW);
+        const uint32_t first = (uint32_t)kb_lo * kPW + i_ * (kSuper * kPW);     // the item's first parameter word
+        const uint32_t soff = __builtin_amdgcn_readfirstlane(slot_off(s_) + first * 4);
+        const int last = param_words_rb - 1 - (int)first;
         pwraw = __builtin_amdgcn_raw_buffer_load_b32(wg_params, min(lane, last) * 4, (int)soff, 0);
     };
-    auto fetch_code = [&](int j, int fs, int fi) {      // k blocks beyond K: the last block again (their X is zero)
+    auto fetch_code = [&](int j, int fs, int fi) {      // k blocks beyond K: the last block again (left out of the sums)
         const bool in = fs < n_rb;
         const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
-        const uint32_t kb = min(i_ * kSuper + j, (uint32_t)nkb - 1);
+        const uint32_t kb = min((uint32_t)kb_lo + i_ * kSuper + j, (uint32_t)nkb - 1);
         const uint32_t soff = __builtin_amdgcn_readfirstlane(slot_off(s_) + kb * kBlockCodeBytes);
         const u32x4 cv = __builtin_amdgcn_raw_buffer_load_b128(wg_codes, (int)lane_code_off, (int)soff, 0);
         c[j] = make_uint4(cv.x, cv.y, cv.z, cv.w);
     };
-    fetch_params(slot, si);
+    auto first_item = [&]() {                           // of a phase: where this wavefront starts, and its first requests
+        slot = 0;
+        si = wave;
+        while (si >= nsi) {
+            si -= nsi;
+            ++slot;
+        }
+        nslot = slot;
+        nitem = si;
+        advance(nslot, nitem);
+        fetch_params(slot, si);
 #pragma unroll
-    for (int j = 0; j < kSuper; ++j) fetch_code(j, slot, si);
+        for (int j = 0; j < kSuper; ++j) fetch_code(j, slot, si);
+    };
+    if (PHASED) {
+        nkb_ph = min(kb_phase, nkb);
+        nsi = (nkb_ph + kSuper - 1) / kSuper;
+        step_slots = W / nsi;
+        step_item = W % nsi;
+    }
+    first_item();
 
     // ---- stage X in pieces of 8 elements (k = 8*pc .. 8*pc+7 of row m); no piece index needs a division
     const int pieces = nkb * (XBB / 16);
@@ -274,217 +301,234 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
             *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 1)) = lpart;
         }
     };
-    // XREG without rms-norm: a wavefront needs nothing but the activations of its own four k blocks, so it
-    // stages exactly those and waits for no other wavefront before it starts.  (Wavefronts on the same k
-    // blocks write the same bytes; not done when they would each load many rows twice.)
-    const bool own_x = XREG && !normed && (step_slots == 1 || M <= 4);
-    if (own_norm) {
-#pragma unroll
-        for (int m = 0; m < kMaxM; ++m)
-            if (m < M) store_piece(m, pc_own, own_ok, keep[m], g_own);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // read back by the wavefront that wrote it
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    } else if (own_x) {
-        for (int i0 = 0; i0 < M * kItemPieces; i0 += kStageBatch * 64) {
-            half8_t vb[kStageBatch];
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int idx = i0 + u * 64 + lane;
-                const int m = idx / kItemPieces, pc = si * kItemPieces + idx % kItemPieces;
-                vb[u] = zero8;
-                if (m < M && pc < pieces && (int64_t)pc * 8 < K) vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + (int64_t)pc * 8);
-            }
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int idx = i0 + u * 64 + lane;
-                const int m = idx / kItemPieces, pc = si * kItemPieces + idx % kItemPieces;
-                store_piece(m, pc, m < M && pc < pieces, vb[u], zero8);     // (a last work item may reach beyond the row's blocks)
-            }
+    for (int ph = 0; ph < n_ph; ++ph) {
+        if (PHASED && ph > 0) {
+            kb_lo = ph * kb_phase;
+            nkb_ph = min(kb_phase, nkb - kb_lo);
+            nsi = (nkb_ph + kSuper - 1) / kSuper;
+            step_slots = W / nsi;
+            step_item = W % nsi;
+            first_item();                               // its requests are in flight while X is staged
+            __syncthreads();                            // every wavefront has finished with the previous part of X
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // read back by the wavefront that wrote it
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    } else {
-        // all M * pieces pieces, kThreads at a time; the row of piece idx is idx / pieces, taken as the high
-        // half of idx * ceil(2^32 / pieces) (exact while M * pieces^2 < 2^32, which the LDS limit implies)
-        for (int base = 0; base < M * pieces; base += kStageBatch * kThreads) {
-            half8_t vb[kStageBatch], gb[kStageBatch];
+        // XREG without rms-norm: a wavefront needs nothing but the activations of its own four k blocks, so it
+        // stages exactly those and waits for no other wavefront before it starts.  (Wavefronts on the same k
+        // blocks write the same bytes; not done when they would each load many rows twice.)
+        const bool own_x = XREG && !normed && (step_slots == 1 || M <= 4);
+        if (own_norm) {
 #pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int idx = base + u * kThreads + t;
-                const int m = (int)__umulhi((uint32_t)idx, pieces_magic), pc = idx - m * pieces;
-                const int64_t k = (int64_t)pc * 8;
-                vb[u] = zero8;
-                gb[u] = zero8;
-                if (idx < M * pieces && k < K) {
-                    vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
-                    if (normed) gb[u] = *reinterpret_cast<const half8_t*>(fu.gamma + k);
+            for (int m = 0; m < kMaxM; ++m)
+                if (m < M) store_piece(m, pc_own, own_ok, keep[m], g_own);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // read back by the wavefront that wrote it
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else if (own_x) {
+            for (int i0 = 0; i0 < M * kItemPieces; i0 += kStageBatch * 64) {
+                half8_t vb[kStageBatch];
+#pragma unroll
+                for (int u = 0; u < kStageBatch; ++u) {
+                    const int idx = i0 + u * 64 + lane;
+                    const int m = idx / kItemPieces, pc = si * kItemPieces + idx % kItemPieces;
+                    vb[u] = zero8;
+                    if (m < M && pc < pieces && (int64_t)pc * 8 < K) vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + (int64_t)pc * 8);
+                }
+#pragma unroll
+                for (int u = 0; u < kStageBatch; ++u) {
+                    const int idx = i0 + u * 64 + lane;
+                    const int m = idx / kItemPieces, pc = si * kItemPieces + idx % kItemPieces;
+                    store_piece(m, pc, m < M && pc < pieces, vb[u], zero8);     // (a last work item may reach beyond the row's blocks)
                 }
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // read back by the wavefront that wrote it
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else {
+            // all M * ph_pieces pieces (of this phase: all of them unless PHASED), kThreads at a time; the row of
+            // piece idx is idx / ph_pieces, taken as the high half of idx * ceil(2^32 / ph_pieces) (exact while
+            // M * ph_pieces^2 < 2^32, which the LDS limit implies)
+            const int ph_pieces = PHASED ? nkb_ph * (XBB / 16) : pieces;
+            const int pc_lo = PHASED ? kb_lo * (XBB / 16) : 0;
+            const uint32_t pieces_magic = PHASED && ph == n_ph - 1 ? pieces_magic_last : pieces_magic_arg;
+            for (int base = 0; base < M * ph_pieces; base += kStageBatch * kThreads) {
+                half8_t vb[kStageBatch], gb[kStageBatch];
 #pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int idx = base + u * kThreads + t;
-                const int m = (int)__umulhi((uint32_t)idx, pieces_magic), pc = idx - m * pieces;
-                store_piece(m, pc, idx < M * pieces, vb[u], gb[u]);
+                for (int u = 0; u < kStageBatch; ++u) {
+                    const int idx = base + u * kThreads + t;
+                    const int m = (int)__umulhi((uint32_t)idx, pieces_magic), pc = idx - m * ph_pieces;
+                    const int64_t k = (int64_t)(pc_lo + pc) * 8;
+                    vb[u] = zero8;
+                    gb[u] = zero8;
+                    if (idx < M * ph_pieces && k < K) {
+                        vb[u] = *reinterpret_cast<const half8_t*>(X + (int64_t)m * K + k);
+                        if (normed) gb[u] = *reinterpret_cast<const half8_t*>(fu.gamma + k);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kStageBatch; ++u) {
+                    const int idx = base + u * kThreads + t;
+                    const int m = (int)__umulhi((uint32_t)idx, pieces_magic), pc = idx - m * ph_pieces;
+                    store_piece(m, pc, idx < M * ph_pieces, vb[u], gb[u]);     // (pc: inside the staged part of the row)
+                }
             }
+            __syncthreads();
         }
-        __syncthreads();
-    }
 
-    // X operand address of this lane: row min(l%16, M-1) (rows beyond M repeat the last one; their
-    // results are never stored), k-group l/16
-    const unsigned char* x_lane = xs + (size_t)min(n_l, M - 1) * row_stride + g_l * 2 * UB;
+        // X operand address of this lane: row min(l%16, M-1) (rows beyond M repeat the last one; their
+        // results are never stored), k-group l/16
+        const unsigned char* x_lane = xs + (size_t)min(n_l, M - 1) * row_stride + g_l * 2 * UB;
 
-    half8_t xreg_h[XREG ? kSuper : 1][2], xreg_l[XREG ? kSuper : 1][2];
-    if (XREG) {
-#pragma unroll
-        for (int j = 0; j < kSuper; ++j) {
-            const unsigned char* xb = x_lane + (size_t)min(si * kSuper + j, nkb - 1) * XBB;
-#pragma unroll
-            for (int wp = 0; wp < 2; ++wp) {
-                xreg_h[j][wp] = *reinterpret_cast<const half8_t*>(xb + wp * UB);
-                xreg_l[j][wp] = E8 ? xreg_h[j][wp] : *reinterpret_cast<const half8_t*>(xb + wp * UB + 16);
-            }
-        }
-    }
-
-    // The two sums of a block's activations per row of X (all of them, and those that meet the code pairs
-    // read at 1/128 scale) come from the matrix cores as well: products with an all-ones weight operand.
-    const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
-    const half8_t ones8 = {(half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f};
-    auto block_sums = [&](const half8_t (&xh)[2], const half8_t (&xl)[2], floatx4& sx, floatx4& sx30) {
-        floatx4 sh = zero4, sl = zero4;
-#pragma unroll
-        for (int wp = 0; wp < 2; ++wp) {
-            sh = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh[wp], ones8, sh, 0, 0, 0);
-            if (!E8) sl = __builtin_amdgcn_mfma_f32_16x16x32_f16(xl[wp], ones8, sl, 0, 0, 0);
-        }
-        sx = sh + sl;
-        sx30 = 30.f * sl;
-    };
-    floatx4 sxr[XREG ? kSuper : 1], sx30r[XREG ? kSuper : 1];
-    if (XREG) {
-#pragma unroll
-        for (int j = 0; j < kSuper; ++j) block_sums(xreg_h[j], xreg_l[j], sxr[j], sx30r[j]);
-    }
-
-    for (int s_rb = 0; s_rb < n_rb; ++s_rb) {
-        floatx4 ysum = zero4;                           // this wavefront's share of Y[4*g_l .. 4*g_l+3][row n_l] of row block s_rb
-        while (slot == s_rb) {
-            // parameter word of (block j, weight row n_l): lane 16 j + n_l of the item's 64 words
-            uint32_t pwj[kSuper];
-#pragma unroll
-            for (int j = 0; j < kSuper; ++j) pwj[j] = (uint32_t)__builtin_amdgcn_ds_bpermute((j * kPW + n_l) * 4, (int)pwraw);
-            fetch_params(nslot, nitem);
+        half8_t xreg_h[XREG ? kSuper : 1][2], xreg_l[XREG ? kSuper : 1][2];
+        if (XREG) {
 #pragma unroll
             for (int j = 0; j < kSuper; ++j) {
-                const int kb = si * kSuper + j;         // may lie beyond K in the last item: such a block is left out below
-                const float sc = (float)param_scale(pwj[j]);
-                const float bi = (float)param_bias(pwj[j]);
-                const uint32_t words[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
-                half2_t p[4][4];
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    if (E8) {                           // (w1_0, w1_1) and, after the rotation, (w1_2, w1_3)
-                        const uint32_t m8 = fmask | fmask_low;
-                        p[w][0] = __builtin_bit_cast(half2_t, (words[w] & m8) | kExpBits2);
-                        p[w][1] = __builtin_bit_cast(half2_t, (__builtin_amdgcn_alignbit(words[w], words[w], 8) & m8) | kExpBits2);
-                    } else {
-                        w1_pairs_mixed(words[w], fmask, fmask_low, p[w]);
-                    }
-                }
-                fetch_code(j, nslot, nitem);            // the block's registers are free: request the next item's
-                floatx4 acc_h = zero4, acc_l = zero4;
-                const unsigned char* xb = x_lane + (size_t)min(kb, nkb - 1) * XBB;
-                half8_t xh2[2], xl2[2];
+                const unsigned char* xb = x_lane + (size_t)min(si * kSuper + j, nkb_ph - 1) * XBB;
 #pragma unroll
                 for (int wp = 0; wp < 2; ++wp) {
-                    xh2[wp] = XREG ? xreg_h[XREG ? j : 0][wp] : *reinterpret_cast<const half8_t*>(xb + wp * UB);
-                    xl2[wp] = E8 ? xh2[wp] : XREG ? xreg_l[XREG ? j : 0][wp] : *reinterpret_cast<const half8_t*>(xb + wp * UB + 16);
-                }
-#pragma unroll
-                for (int wp = 0; wp < 2; ++wp) {
-                    if (E8) {
-                        const half2_t* w0 = p[2 * wp];
-                        const half2_t* w1 = p[2 * wp + 1];
-                        const half8_t w8 = {w0[0][0], w0[0][1], w0[1][0], w0[1][1], w1[0][0], w1[0][1], w1[1][0], w1[1][1]};
-                        acc_h = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh2[wp], w8, acc_h, 0, 0, 0);
-                        continue;
-                    }
-                    const half8_t xh = xh2[wp], xl = xl2[wp];
-                    const half2_t* w0 = p[2 * wp];
-                    const half2_t* w1 = p[2 * wp + 1];
-                    const half8_t wh = {w0[0][0], w0[0][1], w0[3][0], w0[3][1], w1[0][0], w1[0][1], w1[3][0], w1[3][1]};
-                    const half8_t wl = {w0[1][0], w0[1][1], w0[2][0], w0[2][1], w1[1][0], w1[1][1], w1[2][0], w1[2][1]};
-                    acc_h = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh, wh, acc_h, 0, 0, 0);
-                    acc_l = __builtin_amdgcn_mfma_f32_16x16x32_f16(xl, wl, acc_l, 0, 0, 0);
-                }
-                if (kb < nkb) {
-                    floatx4 sx, sx30;
-                    if (XREG) {
-                        sx = sxr[XREG ? j : 0];
-                        sx30 = sx30r[XREG ? j : 0];
-                    } else {
-                        block_sums(xh2, xl2, sx, sx30);
-                    }
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        ysum[r] += sc * ((acc_h[r] + 16.f * acc_l[r] - sx30[r]) - bi * sx[r]);
+                    xreg_h[j][wp] = *reinterpret_cast<const half8_t*>(xb + wp * UB);
+                    xreg_l[j][wp] = E8 ? xreg_h[j][wp] : *reinterpret_cast<const half8_t*>(xb + wp * UB + 16);
                 }
             }
-            slot = nslot;
-            si = nitem;
-            advance(nslot, nitem);
         }
-        if (late) {
+
+        // The two sums of a block's activations per row of X (all of them, and those that meet the code pairs
+        // read at 1/128 scale) come from the matrix cores as well: products with an all-ones weight operand.
+        const floatx4 zero4 = {0.f, 0.f, 0.f, 0.f};
+        const half8_t ones8 = {(half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f, (half_t)1.f};
+        auto block_sums = [&](const half8_t (&xh)[2], const half8_t (&xl)[2], floatx4& sx, floatx4& sx30) {
+            floatx4 sh = zero4, sl = zero4;
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (4 * g_l + r < M) red[((s_rb * W + wave) * M + 4 * g_l + r) * kBlockRows + n_l] = ysum[r];
-            continue;
+            for (int wp = 0; wp < 2; ++wp) {
+                sh = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh[wp], ones8, sh, 0, 0, 0);
+                if (!E8) sl = __builtin_amdgcn_mfma_f32_16x16x32_f16(xl[wp], ones8, sl, 0, 0, 0);
+            }
+            sx = sh + sl;
+            sx30 = 30.f * sl;
+        };
+        floatx4 sxr[XREG ? kSuper : 1], sx30r[XREG ? kSuper : 1];
+        if (XREG) {
+#pragma unroll
+            for (int j = 0; j < kSuper; ++j) block_sums(xreg_h[j], xreg_l[j], sxr[j], sx30r[j]);
         }
-        if (gated) {
-            // slot 2p is the gate block and slot 2p + 1 the up block of pair p: park the gate sums in
-            // half 0 of `red`, the up sums in half 1, then combine
+
+        for (int s_rb = 0; s_rb < n_rb; ++s_rb) {
+            floatx4 ysum = zero4;                           // this wavefront's share of Y[4*g_l .. 4*g_l+3][row n_l] of row block s_rb
+            while (slot == s_rb) {
+                // parameter word of (block j, weight row n_l): lane 16 j + n_l of the item's 64 words
+                uint32_t pwj[kSuper];
+#pragma unroll
+                for (int j = 0; j < kSuper; ++j) pwj[j] = (uint32_t)__builtin_amdgcn_ds_bpermute((j * kPW + n_l) * 4, (int)pwraw);
+                fetch_params(nslot, nitem);
+#pragma unroll
+                for (int j = 0; j < kSuper; ++j) {
+                    const int kb = si * kSuper + j;         // (inside the phase) may lie beyond K in the last item: such a block is left out below
+                    const float sc = (float)param_scale(pwj[j]);
+                    const float bi = (float)param_bias(pwj[j]);
+                    const uint32_t words[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
+                    half2_t p[4][4];
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        if (E8) {                           // (w1_0, w1_1) and, after the rotation, (w1_2, w1_3)
+                            const uint32_t m8 = fmask | fmask_low;
+                            p[w][0] = __builtin_bit_cast(half2_t, (words[w] & m8) | kExpBits2);
+                            p[w][1] = __builtin_bit_cast(half2_t, (__builtin_amdgcn_alignbit(words[w], words[w], 8) & m8) | kExpBits2);
+                        } else {
+                            w1_pairs_mixed(words[w], fmask, fmask_low, p[w]);
+                        }
+                    }
+                    fetch_code(j, nslot, nitem);            // the block's registers are free: request the next item's
+                    floatx4 acc_h = zero4, acc_l = zero4;
+                    const unsigned char* xb = x_lane + (size_t)min(kb, nkb_ph - 1) * XBB;
+                    half8_t xh2[2], xl2[2];
+#pragma unroll
+                    for (int wp = 0; wp < 2; ++wp) {
+                        xh2[wp] = XREG ? xreg_h[XREG ? j : 0][wp] : *reinterpret_cast<const half8_t*>(xb + wp * UB);
+                        xl2[wp] = E8 ? xh2[wp] : XREG ? xreg_l[XREG ? j : 0][wp] : *reinterpret_cast<const half8_t*>(xb + wp * UB + 16);
+                    }
+#pragma unroll
+                    for (int wp = 0; wp < 2; ++wp) {
+                        if (E8) {
+                            const half2_t* w0 = p[2 * wp];
+                            const half2_t* w1 = p[2 * wp + 1];
+                            const half8_t w8 = {w0[0][0], w0[0][1], w0[1][0], w0[1][1], w1[0][0], w1[0][1], w1[1][0], w1[1][1]};
+                            acc_h = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh2[wp], w8, acc_h, 0, 0, 0);
+                            continue;
+                        }
+                        const half8_t xh = xh2[wp], xl = xl2[wp];
+                        const half2_t* w0 = p[2 * wp];
+                        const half2_t* w1 = p[2 * wp + 1];
+                        const half8_t wh = {w0[0][0], w0[0][1], w0[3][0], w0[3][1], w1[0][0], w1[0][1], w1[3][0], w1[3][1]};
+                        const half8_t wl = {w0[1][0], w0[1][1], w0[2][0], w0[2][1], w1[1][0], w1[1][1], w1[2][0], w1[2][1]};
+                        acc_h = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh, wh, acc_h, 0, 0, 0);
+                        acc_l = __builtin_amdgcn_mfma_f32_16x16x32_f16(xl, wl, acc_l, 0, 0, 0);
+                    }
+                    if (kb < nkb_ph) {
+                        floatx4 sx, sx30;
+                        if (XREG) {
+                            sx = sxr[XREG ? j : 0];
+                            sx30 = sx30r[XREG ? j : 0];
+                        } else {
+                            block_sums(xh2, xl2, sx, sx30);
+                        }
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            ysum[r] += sc * ((acc_h[r] + 16.f * acc_l[r] - sx30[r]) - bi * sx[r]);
+                    }
+                }
+                slot = nslot;
+                si = nitem;
+                advance(nslot, nitem);
+            }
+            if (late) {                                 // (a cell belongs to one wavefront, which adds later phases to it)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float* cell = red + ((s_rb * W + wave) * M + 4 * g_l + r) * kBlockRows + n_l;
+                    if (4 * g_l + r < M) *cell = PHASED && ph > 0 ? *cell + ysum[r] : ysum[r];
+                }
+                continue;
+            }
+            if (gated) {
+                // slot 2p is the gate block and slot 2p + 1 the up block of pair p: park the gate sums in
+                // half 0 of `red`, the up sums in half 1, then combine
+                float* mine = red + (((s_rb & 1) * W + wave) * kMaxM + 4 * g_l) * kBlockRows + n_l;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) mine[r * kBlockRows] = ysum[r];
+                if ((s_rb & 1) == 0) continue;
+                __syncthreads();
+                if (t < kMaxM * kBlockRows) {
+                    const int m = t >> 4, n = t & 15;
+                    float g = 0.f, u = 0.f;
+#pragma unroll
+                    for (int w = 0; w < W; ++w) {
+                        g += red[((0 * W + w) * kMaxM + m) * kBlockRows + n];
+                        u += red[((1 * W + w) * kMaxM + m) * kBlockRows + n];
+                    }
+                    const int64_t col = (rb0 + (s_rb >> 1)) * kBlockRows + n;
+                    if (m < M && col < fu.n_out) {
+                        float y = silu_f32(g) * u;
+                        if (fu.residual) y += (float)fu.residual[(int64_t)m * fu.n_out + col];
+                        Y[(int64_t)m * fu.n_out + col] = (half_t)y;
+                    }
+                }
+                __syncthreads();                            // both halves of `red` are free again
+                continue;
+            }
+            // the wavefronts' shares of row block s_rb are added in wavefront order
             float* mine = red + (((s_rb & 1) * W + wave) * kMaxM + 4 * g_l) * kBlockRows + n_l;
 #pragma unroll
             for (int r = 0; r < 4; ++r) mine[r * kBlockRows] = ysum[r];
-            if ((s_rb & 1) == 0) continue;
             __syncthreads();
             if (t < kMaxM * kBlockRows) {
                 const int m = t >> 4, n = t & 15;
-                float g = 0.f, u = 0.f;
+                float s = 0.f;
 #pragma unroll
-                for (int w = 0; w < W; ++w) {
-                    g += red[((0 * W + w) * kMaxM + m) * kBlockRows + n];
-                    u += red[((1 * W + w) * kMaxM + m) * kBlockRows + n];
-                }
-                const int64_t col = (rb0 + (s_rb >> 1)) * kBlockRows + n;
-                if (m < M && col < fu.n_out) {
-                    float y = silu_f32(g) * u;
-                    if (fu.residual) y += (float)fu.residual[(int64_t)m * fu.n_out + col];
-                    Y[(int64_t)m * fu.n_out + col] = (half_t)y;
-                }
+                for (int w = 0; w < W; ++w) s += red[(((s_rb & 1) * W + w) * kMaxM + m) * kBlockRows + n];
+                const int64_t row = (rb0 + s_rb) * kBlockRows + n;
+                if (FUSED && fu.residual && m < M && row < N) s += (float)fu.residual[(int64_t)m * N + row];
+                if (m < M && row < N) Y[(int64_t)m * N + row] = (half_t)s;
             }
-            __syncthreads();                            // both halves of `red` are free again
-            continue;
+            // no second barrier: row block s_rb + 1 uses the other half of `red`, and nobody writes this
+            // half again before passing the barrier of s_rb + 1, which the readers above reach after reading
         }
-        // the wavefronts' shares of row block s_rb are added in wavefront order
-        float* mine = red + (((s_rb & 1) * W + wave) * kMaxM + 4 * g_l) * kBlockRows + n_l;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) mine[r * kBlockRows] = ysum[r];
-        __syncthreads();
-        if (t < kMaxM * kBlockRows) {
-            const int m = t >> 4, n = t & 15;
-            float s = 0.f;
-#pragma unroll
-            for (int w = 0; w < W; ++w) s += red[(((s_rb & 1) * W + w) * kMaxM + m) * kBlockRows + n];
-            const int64_t row = (rb0 + s_rb) * kBlockRows + n;
-            if (FUSED && fu.residual && m < M && row < N) s += (float)fu.residual[(int64_t)m * N + row];
-            if (m < M && row < N) Y[(int64_t)m * N + row] = (half_t)s;
-        }
-        // no second barrier: row block s_rb + 1 uses the other half of `red`, and nobody writes this
-        // half again before passing the barrier of s_rb + 1, which the readers above reach after reading
     }
     if (late) {
         __syncthreads();
@@ -511,6 +555,51 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     }
 }
 
+// M rows of X do not fit the LDS: K in phases.  The wavefront sums of all row blocks of a workgroup stay in LDS
+// through the phases, the rest holds one phase's X; the phases are of equal length up to the last one's
+// remainder.  One round of workgroups as long as that leaves room for kPhasedMinItems work items of X per
+// phase, more workgroups with fewer row blocks each otherwise.
+constexpr int kPhasedMinItems = 4;
+bool make_phased_plan(int64_t M, int64_t nrb, int64_t nkb, MfmaPlan& p, int unit, bool e8, int w_knob, int target)
+{
+    const int64_t nsi = (nkb + kSuper - 1) / kSuper;
+    const size_t xbb = e8 ? kXBlockBytes / 2 : kXBlockBytes;
+    auto plan = [&](int w) -> bool {
+        int64_t most = (nrb + std::min<int64_t>(nrb, target) - 1) / std::min<int64_t>(nrb, target);    // row blocks (or pairs) of a workgroup
+        const size_t per_item = (size_t)M * kSuper * xbb, other = kNormBytes + (size_t)M * kRowPadBytes;
+        const int64_t min_items = std::min<int64_t>(kPhasedMinItems, nsi);
+        while (most > 1 && late_red_bytes(M, (int)most * unit, w) + other + min_items * per_item > (size_t)kLdsLimitBytes) --most;
+        p.grid = (nrb + most - 1) / most;
+        const size_t fixed = late_red_bytes(M, (int)most * unit, w) + other;
+        if (fixed + per_item > (size_t)kLdsLimitBytes) return false;
+        const int64_t fit = (int64_t)(((size_t)kLdsLimitBytes - fixed) / per_item);     // work items of X at a time
+        const int64_t phases = (nsi + fit - 1) / fit;
+        const int64_t nsi_ph = (nsi + phases - 1) / phases;
+        p.waves = w;
+        p.kb_phase = (int)(nsi_ph * kSuper);
+        p.step_slots = (int)(w / nsi_ph);               // (the kernel derives them per phase)
+        p.step_item = (int)(w % nsi_ph);
+        p.rb_base = (int)(nrb / p.grid);
+        p.rb_rem = (int)(nrb % p.grid);
+        p.late = 1;
+        p.lds_bytes = fixed + (size_t)nsi_ph * per_item;
+        const uint64_t pieces = (uint64_t)p.kb_phase * (xbb / 16);
+        const uint64_t pieces_last = (uint64_t)(nkb - (nkb - 1) / p.kb_phase * p.kb_phase) * (xbb / 16);
+        p.pieces_magic = (uint32_t)(((1ull << 32) + pieces - 1) / pieces);      // (M * pieces^2 < 2^32: M * pieces * 16 bytes fit the LDS)
+        p.pieces_magic_last = (uint32_t)(((1ull << 32) + pieces_last - 1) / pieces_last);
+        return true;
+    };
+    if (w_knob >= 8) return plan(w_knob);
+    if (!plan(8)) return false;
+    // sixteen wavefronts for a single row block per workgroup (measured 7 - 14 % faster there: 4096 x 11008 and
+    // 2048 x 16384 from M = 8 on; slower or equal with more row blocks) and for very long phases
+    if (nrb <= target || p.kb_phase / kSuper > 16) {
+        const MfmaPlan with8 = p;
+        if (!plan(16)) p = with8;
+    }
+    return true;
+}
+
 // `unit`: 2 when row blocks are dealt in (gate, up) pairs; rb_base and rb_rem then count pairs
 // (e8: K counts 4-bit slots, two per weight, and a block of X is half as long)
 bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, bool e8 = false)
@@ -520,11 +609,19 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, 
     int w = knob("gemv_waves");
     // (sixteen wavefronts for more than 16 work items per row block; with exactly 16 eight are faster: 8192 x 8192
     // at M = 4 takes 10.5 us, 12.1 with sixteen; 8-bit 4096 x 4096 at M = 2 5.9 against 6.7)
-    if (w != 4 && w != 8 && w != 16) w = nsi > 16 ? 16 : 8;
-    while (w > 4 && lds_need(M, nkb, w, e8) > (size_t)kLdsLimitBytes) w /= 2;
-    if (lds_need(M, nkb, w, e8) > (size_t)kLdsLimitBytes) return false;
+    const int w_knob = (w == 4 || w == 8 || w == 16) ? w : 0;
+    if (!w_knob) w = nsi > 16 ? 16 : 8;
+    const int w_wanted = w;
+    while (w > 4 && lds_need(M, nkb, w, e8) > (size_t)kLdsLimitBytes) w /= 2;   // (smaller buffers for the wavefront sums)
     int target = knob("gemv_workgroups");
     if (target <= 0) target = kTargetWorkgroups;
+    p.kb_phase = 0;
+    p.pieces_magic_last = 0;
+    // X does not fit beside the sums of eight wavefronts: K in phases rather than all of X with four wavefronts
+    // (36864 x 7168 at M = 10: 33 us against 52)
+    if (w < 8 && w_wanted >= 8 && knob("gemv_mfma") != 3 && make_phased_plan(M, nrb, nkb, p, unit, e8, w_knob, target))
+        return true;
+    if (lds_need(M, nkb, w, e8) > (size_t)kLdsLimitBytes) return false;
     p.grid = std::min<int64_t>(nrb, target);
     if (nrb > target) {                                 // the fewest workgroups with the same largest share of row
         const int64_t most = (nrb + target - 1) / target;   // blocks (or pairs), so that (nearly) all of them end together
@@ -546,18 +643,31 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, 
     return true;
 }
 
-template <int W, bool FUSED, bool XREG, bool E8 = false>
+template <int W, bool FUSED, bool XREG, bool E8 = false, bool PHASED = false>
 int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                   hipStream_t stream, const GemvFusion& fu)
 {
+    if (PHASED != (p.kb_phase > 0) || (PHASED && !p.late) || p.lds_bytes > (size_t)kLdsLimitBytes) return E0M4_ERR_SHAPE;
     static std::atomic<uint64_t> lds_allowed{0};
-    const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED, XREG, E8>), kLdsLimitBytes,
-                                      lds_allowed);
+    const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED, XREG, E8, PHASED>),
+                                      kLdsLimitBytes, lds_allowed);
     if (arc != E0M4_OK) return arc;
-    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes, stream,
-                       static_cast<const half_t*>(X), (int)M, static_cast<const uint4*>(packed), N, K,
-                       static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.late, p.pieces_magic, fu);
+    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8, PHASED>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes,
+                       stream, static_cast<const half_t*>(X), (int)M, static_cast<const uint4*>(packed), N, K,
+                       static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.late, p.pieces_magic,
+                       p.kb_phase, p.pieces_magic_last, fu);
     return check_launch();
+}
+
+// K in phases (plans with kb_phase > 0; they have eight or sixteen wavefronts)
+template <int W, bool FUSED, bool E8>
+int launch_mfma_phased(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                       hipStream_t stream, const GemvFusion& fu)
+{
+    if constexpr (W >= 8)
+        return launch_mfma_x<W, FUSED, false, E8, true>(p, X, M, packed, N, K, Y, stream, fu);
+    else
+        return E0M4_ERR_SHAPE;
 }
 
 // Activations in registers when a wavefront always meets the same k blocks (step_item == 0); the kernel
@@ -567,6 +677,7 @@ template <int W, bool FUSED>
 int launch_mfma(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                 hipStream_t stream, const GemvFusion& fu = GemvFusion{})
 {
+    if (p.kb_phase > 0) return launch_mfma_phased<W, FUSED, false>(p, X, M, packed, N, K, Y, stream, fu);
     if (p.step_item == 0 && W <= 8 && knob("gemv_mfma") != 2)
         return launch_mfma_x<W, FUSED, true>(p, X, M, packed, N, K, Y, stream, fu);
     return launch_mfma_x<W, FUSED, false>(p, X, M, packed, N, K, Y, stream, fu);
@@ -605,6 +716,9 @@ template <bool FUSED>
 int launch_mfma8(const MfmaPlan& p, const GemvFusion& fu, const void* X, int64_t M, const void* packed, int64_t N,
                  int64_t K, void* Y, hipStream_t stream)
 {
+    if (p.kb_phase > 0)
+        return p.waves == 8 ? launch_mfma_phased<8, FUSED, true>(p, X, M, packed, N, K, Y, stream, fu)
+                            : launch_mfma_phased<16, FUSED, true>(p, X, M, packed, N, K, Y, stream, fu);
     const bool xreg = p.step_item == 0 && knob("gemv_mfma") != 2;
     switch (p.waves) {
         case 4:
@@ -648,7 +762,9 @@ bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K,
 {
     if (!gemv_mfma_supported(M, N, K, group)) return false;
     if (!f.swiglu) return true;
-    return N % (2 * kBlockRows) == 0 && gated_half_bytes(N, K, group) <= kMaxHalfBytes;
+    if (N % (2 * kBlockRows) != 0 || gated_half_bytes(N, K, group) > kMaxHalfBytes) return false;
+    MfmaPlan p;
+    return make_mfma_plan(M, N, K, p, 2);
 }
 
 int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,

@@ -121,6 +121,16 @@ def test_small_batch_matrix_core_kernel(e0m4, oracle, M, norm, swiglu, res):
     run_fused(e0m4, oracle, M, 333 if not swiglu else 448, 1664, 128, seed=520 + M, norm=norm, swiglu=swiglu, res=res)
 
 
+@pytest.mark.parametrize("norm,swiglu,res", COMBOS)
+@pytest.mark.parametrize("bits", [4, 8])
+def test_small_batch_rows_longer_than_the_lds(e0m4, oracle, bits, norm, swiglu, res):
+    # M rows of X do not fit the LDS: K in phases (the rms-norm sums run over all of K before the first phase)
+    run_fused(e0m4, oracle, 16, 448, 5248 if bits == 4 else 5184, 128 if bits == 4 else 64, seed=540 + bits, norm=norm,
+              swiglu=swiglu, res=res, bits=bits)
+    run_fused(e0m4, oracle, 7, 1088, 16384, 128, seed=541 + bits, norm=norm, swiglu=swiglu, res=res, outliers=True,
+              bits=bits)
+
+
 @pytest.mark.parametrize("M", [2, 6, 16])
 def test_small_batch_matrix_core_kernel_reduction_per_row_block(e0m4, oracle, M):
     e0m4.e0m4_set_knob("gemv_mfma", 3)

@@ -301,10 +301,34 @@ def test_small_batch_vector_kernel_when_the_matrix_core_kernel_is_off(e0m4, orac
         e0m4.e0m4_set_knob("gemv_mfma", 0)
 
 
-def test_small_batch_falls_back_when_x_does_not_fit_lds(e0m4, oracle):
-    # 16 rows of K = 16384 need 512 KiB of LDS: the GEMM takes over; with 8 rows, the vector kernel
-    run_matmul_case(e0m4, oracle, 16, 130, 16384, 128, seed=200)
-    run_matmul_case(e0m4, oracle, 8, 130, 16384, 128, seed=201)
+@pytest.mark.parametrize("M,N,K", [(16, 130, 16384), (8, 130, 16384), (16, 1000, 5248), (11, 333, 8192),
+                                   (6, 1100, 13696), (2, 40, 1 << 18)])
+def test_small_batch_rows_longer_than_the_lds(e0m4, oracle, M, N, K):
+    # M rows of X need more than the 160 KiB of LDS: the kernel walks K in phases (K = 5248: a last phase that is
+    # shorter and ends inside a work item)
+    run_matmul_case(e0m4, oracle, M, N, K, 128, seed=200 + M)
+
+
+@pytest.mark.parametrize("waves", [8, 16])
+@pytest.mark.parametrize("target", [0, 3])
+def test_small_batch_rows_longer_than_the_lds_forced_shapes(e0m4, oracle, waves, target):
+    e0m4.e0m4_set_knob("gemv_waves", waves)
+    e0m4.e0m4_set_knob("gemv_workgroups", target)       # 3 workgroups asked for: more are used, as many as the sums in LDS need
+    try:
+        run_matmul_case(e0m4, oracle, 16, 1000, 5248, 128, seed=210 + waves)
+        run_matmul_case(e0m4, oracle, 5, 300, 1 << 16, 128, seed=211 + waves)
+    finally:
+        e0m4.e0m4_set_knob("gemv_waves", 0)
+        e0m4.e0m4_set_knob("gemv_workgroups", 0)
+
+
+def test_small_batch_long_rows_without_the_late_reduction_take_another_kernel(e0m4, oracle):
+    # knob value 3 (reduction per row block) rules the phases out: the GEMM serves the case
+    e0m4.e0m4_set_knob("gemv_mfma", 3)
+    try:
+        run_matmul_case(e0m4, oracle, 16, 130, 16384, 128, seed=215)
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
 
 
 # ------------------------------------------------------------------ matmul, MFMA path

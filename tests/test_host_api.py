@@ -142,7 +142,8 @@ def test_fused_matmul_validation_and_workspace(L):
     w = L.e0m4_fused_workspace_bytes
     assert w(1, 27392, 4096, 128, 1, SWIGLU) == 0               # decode: everything stays in the one kernel
     assert w(8, 4096, 4096, 128, 1, NONE) == 0
-    assert w(8, 4096, 16384, 128, 1, SWIGLU) > 0                # X does not fit the LDS in one piece: GEMM path
+    assert w(16, 4096, 16384, 128, 1, SWIGLU) == 0              # X longer than the LDS: still one kernel (K in phases)
+    assert w(17, 4096, 16384, 128, 1, SWIGLU) > 0               # GEMM path: normalised copy of X
     assert w(1024, 27392, 4096, 128, 1, SWIGLU) == 1024 * 4096 * 2         # normalised X; enough tiles, no K split
     assert w(1024, 27392, 4096, 128, 0, SWIGLU) == 0
     assert w(1024, 4096, 13696, 128, 0, NONE) == L.e0m4_workspace_bytes(1024, 4096, 13696, 128) > 0
