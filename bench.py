@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-table1", action="store_true", help="skip the E0M4 / INT4 latency comparison")
+    ap.add_argument("--no-small-batch", action="store_true", help="skip the 2 <= M <= 16 latencies")
     ap.add_argument("--no-fusion", action="store_true", help="skip the fused / unfused layer comparison")
     ap.add_argument("--no-library", action="store_true",
                     help="skip the platform library's fp16 GEMM on the same prefill shapes (context figure)")
@@ -216,6 +217,48 @@ def main():
         "decode_per_shape": per_shape,
         "quantize": {"GBps_fp16_in": round(q_bytes / t_q / 1e9, 1), "note": "offline step incl. weight generation"},
     }
+
+    # ---------------- small batches (2 <= M <= 16) on the same weights: latency per launch, rotating over the
+    # layers' distinct weights (cold in cache); the weight stream is what a launch has to move
+    if not args.no_small_batch:
+        sb = {}
+        with torch.cuda.stream(stream):
+            for M in (2, 4, 8, 16):
+                row = {}
+                for p, (name, N, K) in enumerate(shapes):
+                    xm = synth_inputs.activations_device(M, K, 7000 + M + K, dev)
+                    ym = torch.empty((M, N), dtype=torch.float16, device=dev)
+                    wsm = torch.empty(max(e0m4.e0m4_workspace_bytes(M, N, K, GROUP), 16), dtype=torch.uint8, device=dev)
+
+                    def batch_pass():
+                        for mats in layers:
+                            _, _, _, codes, scales, bias = mats[p]
+                            e0m4.e0m4_matmul(xm, codes, scales, bias, N, K, GROUP, out=ym, workspace=wsm, stream=stream)
+
+                    batch_pass()
+                    stream.synchronize()
+                    run_pass = batch_pass
+                    if graph is not None:
+                        gm = torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(gm, stream=stream):
+                            batch_pass()
+                        run_pass = gm.replay
+                    reps = max(1, 100 // n_layers)
+                    best = None
+                    for _ in range(3):
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record(stream)
+                        for _ in range(reps):
+                            run_pass()
+                        e1.record(stream)
+                        stream.synchronize()
+                        t = e0.elapsed_time(e1) * 1e3 / (reps * n_layers)
+                        best = t if best is None else min(best, t)
+                    row[name] = {"us": round(best, 3), "GBps": round(algorithmic_bytes(M, N, K, GROUP) / best / 1e3, 1)}
+                    del xm, ym, wsm
+                sb["M=%d" % M] = row
+        out["small_batch"] = {"workload": "ChatGLM2-6B shapes, 2 <= M <= 16, group %d; latency per launch, cold weights"
+                                          % GROUP, "per_M": sb}
 
     # ---------------- the paper's Table 1: E0M4 against the INT4 twin, M = 1, weight [K, N]
     # (same layout, launch shape and accumulation; the twin extracts integers and converts them to fp16).

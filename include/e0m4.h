@@ -116,10 +116,11 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  * accumulation is fp32; Y is rounded once to fp16.
  *   M <= 8 : HBM-bound GEMV path (a workgroup owns whole blocks of 16 output
  *            rows over all of K; no partial sums leave the compute unit).
- *   2 <= M <= 16, group 128, M rows of X fit the LDS of a compute unit
- *            (about M * K * 2 <= 140 KiB): same decomposition, the dot
- *            products run on the matrix cores so the cost stays near the
- *            weight stream for every such M.
+ *   2 <= M <= 16, group 128: same decomposition, the dot products run on
+ *            the matrix cores so the cost stays near the weight stream for
+ *            every such M.  X is staged in the LDS of the compute unit, all
+ *            of it (about M * K * 2 <= 140 KiB) or one part of K after the
+ *            other; the weights are read once either way.
  *   M >= 9 otherwise, and 2 <= M <= 8 when M * N * K is about 3.8e8 or
  *            more (the vector kernel's time grows with M): MFMA GEMM path
  *            (tiles of 64 x 256 outputs up to M = 384 and for few large
@@ -206,10 +207,10 @@ int e0m4_kv_append(void* cache_f16, int64_t max_seq, int64_t row_elems,
  *     [N, K/group] fp16.
  *   - e0m8_unpack_codes writes one byte per weight, [N, K] row-major.
  *   - e0m8_matmul: Y[M,N] = X[M,K] * dequant(codes)^T, fp32 accumulation, one
- *     rounding.  M <= 8: the HBM-bound decode kernel (2 <= M <= 16 with X
- *     fitting the LDS: its matrix-core variant).  M > 8 with K % 128 == 0
+ *     rounding.  M <= 8: the HBM-bound decode kernel (2 <= M <= 16: its
+ *     matrix-core variant, any group).  M > 16 with K % 128 == 0
  *     (and N <= 2^24): the MFMA GEMM kernels, workspace of
- *     e0m8_workspace_bytes() bytes under the rules of e0m4_matmul.  Other M > 8:
+ *     e0m8_workspace_bytes() bytes under the rules of e0m4_matmul.  Other M > 16:
  *     the decode kernel on 8 rows of X at a time (needs N % 8 == 0).
  * Pointer, alignment, stream and error rules as for the E0M4 entry points.
  */
@@ -220,7 +221,7 @@ int e0m8_dequant(const void* codes, int64_t N, int64_t K, int group, void* W_f16
 int e0m8_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* codes_u8_out, void* stream);
 size_t e0m8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
 /* e0m4_matmul_fused on 8-bit codes: same operators, arguments and rules (N a multiple of 64 for the gated
- * epilogue).  M > 16, or M > 8 when X does not fit the LDS, needs K % 128 == 0 (E0M4_ERR_SHAPE otherwise). */
+ * epilogue).  M > 16 needs K % 128 == 0 (E0M4_ERR_SHAPE otherwise). */
 size_t e0m8_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int group, int with_rmsnorm, int epilogue);
 int e0m8_matmul_fused(const void* X_f16, int64_t M, const void* rms_gamma_f16, float rms_eps,
                       const void* codes, int64_t N, int64_t K, int group,

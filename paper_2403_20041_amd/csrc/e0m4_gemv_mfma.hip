@@ -21,6 +21,11 @@
 // factored form needs are MFMAs of the same operands with an all-ones weight operand.
 // One group of 128 k is one block, so the group's affine map  y += scale * (a - bias * sum x)  is
 // applied once per block on the MFMA result; that is why this kernel needs group size 128.
+//
+// Long rows.  When M rows of X exceed the LDS, K is walked in phases: a phase stages its part of X,
+// visits that part of every row block of the workgroup and adds to the wavefront sums, which stay in
+// LDS until the last phase.  The weight stream is the same, each byte once; what a phase costs is
+// the barrier before X is replaced and the restart of the wavefronts' prefetch.
 #include "e0m4_device.h"
 #include "e0m4_host.h"
 

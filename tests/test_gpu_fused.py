@@ -188,8 +188,10 @@ def test_few_rows_with_large_weights_take_the_gemm(e0m4, oracle):
 def test_decode_kernel_long_rows(e0m4, oracle):
     # 8 rows of K = 16384 are staged in several segments: the norm's row sums come from memory, and the
     # gated epilogue (which needs whole rows in LDS) is served by the GEMM kernels instead
-    run_fused(e0m4, oracle, 8, 130, 16384, 128, seed=340, norm=True, res=True)
-    run_fused(e0m4, oracle, 8, 128, 16384, 128, seed=341, norm=True, swiglu=True, res=True)
+    # (group 64: the vector kernel; group 128: the small-batch kernel with K in phases)
+    for G in (64, 128):
+        run_fused(e0m4, oracle, 8, 130, 16384, G, seed=340, norm=True, res=True)
+        run_fused(e0m4, oracle, 8, 128, 16384, G, seed=341, norm=True, swiglu=True, res=True)
     run_fused(e0m4, oracle, 1, 192, 32768, 128, seed=342, norm=True, swiglu=True)
 
 

@@ -438,10 +438,14 @@ def test_matmul_is_deterministic(e0m4, M):
 
 @pytest.mark.parametrize("M,G", [(8, 64), (5, 32), (8, 128)])
 def test_few_rows_with_large_weights_take_the_gemm(e0m4, oracle, M, G):
-    # M * N * K above 3.8e8 and no small-batch matrix-core kernel (other groups; at G = 128, X beyond the LDS):
-    # the 64 x 256 GEMM tile instead of the vector kernel
+    # M * N * K above 3.8e8 and no small-batch matrix-core kernel (other groups; at G = 128, that kernel switched
+    # off): the 64 x 256 GEMM tile instead of the vector kernel
     if G == 128:
-        run_matmul_case(e0m4, oracle, M, 1600, 32768, G, seed=611)         # 8 rows of K = 32768 do not fit the LDS
+        e0m4.e0m4_set_knob("gemv_mfma", 1)
+        try:
+            run_matmul_case(e0m4, oracle, M, 1600, 32768, G, seed=611)
+        finally:
+            e0m4.e0m4_set_knob("gemv_mfma", 0)
     else:
         run_matmul_case(e0m4, oracle, M, 24000 if M == 5 else 12288, 4096, G, seed=610 + M, outliers=True)
 
