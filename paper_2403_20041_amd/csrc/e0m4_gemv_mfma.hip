@@ -572,8 +572,9 @@ bool make_phased_plan(int64_t M, int64_t nrb, int64_t nkb, MfmaPlan& p, int unit
     auto plan = [&](int w) -> bool {
         int64_t most = (nrb + std::min<int64_t>(nrb, target) - 1) / std::min<int64_t>(nrb, target);    // row blocks (or pairs) of a workgroup
         const size_t per_item = (size_t)M * kSuper * xbb, other = kNormBytes + (size_t)M * kRowPadBytes;
-        const int64_t min_items = std::min<int64_t>(kPhasedMinItems, nsi);
-        while (most > 1 && late_red_bytes(M, (int)most * unit, w) + other + min_items * per_item > (size_t)kLdsLimitBytes) --most;
+        const size_t min_x = other + (size_t)std::min<int64_t>(kPhasedMinItems, nsi) * per_item;
+        const size_t room = (size_t)kLdsLimitBytes > min_x ? (size_t)kLdsLimitBytes - min_x : 0;    // for the sums
+        most = std::min<int64_t>(most, std::max<int64_t>(1, (int64_t)(room / late_red_bytes(M, unit, w))));
         p.grid = (nrb + most - 1) / most;
         const size_t fixed = late_red_bytes(M, (int)most * unit, w) + other;
         if (fixed + per_item > (size_t)kLdsLimitBytes) return false;
