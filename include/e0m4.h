@@ -121,6 +121,8 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  *            every such M.  X is staged in the LDS of the compute unit, all
  *            of it (about M * K * 2 <= 140 KiB) or one part of K after the
  *            other; the weights are read once either way.
+ *   17 <= M <= 32, group 128, N * K <= 7e7, 16 rows of X within the LDS:
+ *            that kernel twice, on 16 (M = 17: 8) rows and on the rest.
  *   M >= 9 otherwise, and 2 <= M <= 8 when M * N * K is about 3.8e8 or
  *            more (the vector kernel's time grows with M): MFMA GEMM path
  *            (tiles of 64 x 256 outputs up to M = 384 and for few large

@@ -46,6 +46,18 @@ bool small_m_on_vector(int64_t M, int64_t N, int64_t K)
     if (M < 2 || !gemm_pipe_supported(K) || N > (int64_t)1 << 24) return true;
     return (double)M * (double)N * (double)K < 3.8e8;
 }
+// 17 <= M <= 32 on small weights: two launches of the small-batch matrix-core kernel (16 rows, then the rest)
+// instead of the GEMM, whose 64 x 256 tile with its split along K costs 13 - 20 us whatever M is.  Measured
+// 5 - 23 % faster up to 11008 x 4096 and 32768 x 2048, equal at 27392 x 4096, slower beyond and when the 16 rows
+// need phases along K; slower from M = 33 on (three launches).
+constexpr int64_t kChunkRows = 16, kChunkedMaxM = 32;
+bool small_batch_in_chunks(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)
+{
+    return M > kChunkRows && M <= kChunkedMaxM && knob("gemv_mfma") != 1 && (double)N * (double)K <= 7e7 &&
+           gemv_mfma_whole_rows(f, kChunkRows, N, K, group);
+}
+// rows of the first launch: both launches get 2 to 16 rows, the second starts at a multiple of 8 rows
+int64_t first_chunk_rows(int64_t M) { return M - kChunkRows >= 2 ? kChunkRows : kChunkRows / 2; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Shape rules shared by all entry points.
@@ -115,7 +127,7 @@ size_t e0m4_params_elems(int64_t N, int64_t K, int group)
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 {
     if (check_shape(N, K, group) != E0M4_OK || small_m_on_vector(M, N, K) || K == 0) return 0;   // the small-M kernels need none
-    if (use_gemv_mfma(M, N, K, group)) return 0;
+    if (use_gemv_mfma(M, N, K, group) || small_batch_in_chunks(Fusion{}, M, N, K, group)) return 0;
     return gemm_workspace_bytes(M, N, K);       // partial tiles of the split-K GEMM, if it splits
 }
 
@@ -124,11 +136,12 @@ size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 static size_t norm_bytes(int64_t M, int64_t K) { return ((size_t)M * (size_t)K * 2 + 255) & ~(size_t)255; }
 
 // Which kernel family serves a fused matmul: 0 the decode kernel, 2 the small-batch kernel on the matrix
-// cores (both: everything in one launch), 1 the GEMM kernels (rms-norm, if any, as a launch of its own
-// before them).
+// cores (both: everything in one launch), 3 that kernel on two chunks of rows, 1 the GEMM kernels (rms-norm,
+// if any, as a launch of its own before them).
 static int fused_path(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)
 {
     if (knob("gemv_mfma") != 1 && gemv_mfma_fused_supported(f, M, N, K, group)) return 2;
+    if (small_batch_in_chunks(f, M, N, K, group)) return 3;
     return (small_m_on_vector(M, N, K) && gemv_fused_supported(f, M, N, K)) ? 0 : 1;
 }
 
@@ -254,6 +267,13 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
     if (use_gemv_mfma(M, N, K, group)) return launch_gemv_mfma(X, M, codes, N, K, Y, (hipStream_t)stream);
     if (small_m_on_vector(M, N, K)) return launch_gemv(X, M, codes, N, K, group, Y, (hipStream_t)stream);
+    if (small_batch_in_chunks(Fusion{}, M, N, K, group)) {
+        const int64_t m0 = first_chunk_rows(M);
+        rc = launch_gemv_mfma(X, m0, codes, N, K, Y, (hipStream_t)stream);
+        if (rc != E0M4_OK) return rc;
+        return launch_gemv_mfma(static_cast<const char*>(X) + m0 * K * 2, M - m0, codes, N, K,
+                                static_cast<char*>(Y) + m0 * N * 2, (hipStream_t)stream);
+    }
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // the GEMM epilogue forms 32-bit offsets of up to 256 rows of Y
     if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
     return launch_gemm(X, M, codes, N, K, group, Y, workspace, workspace_bytes, (hipStream_t)stream);
@@ -284,6 +304,15 @@ int e0m4_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
     const int path = fused_path(f, M, N, K, group);
     if (path == 2) return launch_gemv_mfma_fused(f, X, M, codes, N, K, Y, st);
     if (path == 0) return launch_gemv_fused(f, X, M, codes, N, K, group, Y, st);
+    if (path == 3) {                                    // rows are independent, the rms-norm included
+        const int64_t m0 = first_chunk_rows(M), n_out = f.swiglu ? N / 2 : N;
+        rc = launch_gemv_mfma_fused(f, X, m0, codes, N, K, Y, st);
+        if (rc != E0M4_OK) return rc;
+        Fusion rest = f;
+        if (f.residual) rest.residual = static_cast<const char*>(f.residual) + m0 * n_out * 2;
+        return launch_gemv_mfma_fused(rest, static_cast<const char*>(X) + m0 * K * 2, M - m0, codes, N, K,
+                                      static_cast<char*>(Y) + m0 * n_out * 2, st);
+    }
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // 32-bit offsets in the GEMM epilogue
     const size_t nb = rms_gamma ? norm_bytes(M, K) : 0;
     const size_t need = nb + gemm_workspace_bytes(M, N, K, f.swiglu);

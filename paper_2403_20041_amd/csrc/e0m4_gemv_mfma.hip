@@ -773,6 +773,12 @@ bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K,
     return make_mfma_plan(M, N, K, p, 2);
 }
 
+bool gemv_mfma_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)
+{
+    MfmaPlan p;
+    return gemv_mfma_fused_supported(f, M, N, K, group) && make_mfma_plan(M, N, K, p, f.swiglu ? 2 : 1) && p.kb_phase == 0;
+}
+
 int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                            hipStream_t stream)
 {

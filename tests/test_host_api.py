@@ -144,6 +144,10 @@ def test_fused_matmul_validation_and_workspace(L):
     assert w(8, 4096, 4096, 128, 1, NONE) == 0
     assert w(16, 4096, 16384, 128, 1, SWIGLU) == 0              # X longer than the LDS: still one kernel (K in phases)
     assert w(17, 4096, 16384, 128, 1, SWIGLU) > 0               # GEMM path: normalised copy of X
+    assert w(24, 4096, 4096, 128, 1, NONE) == 0                 # two chunks of rows on the small-batch kernel
+    assert w(33, 4096, 4096, 128, 1, NONE) > 0
+    assert L.e0m4_workspace_bytes(24, 4096, 4096, 128) == 0
+    assert L.e0m4_workspace_bytes(24, 27392, 4096, 128) > 0     # large weights: the GEMM, split along K
     assert w(1024, 27392, 4096, 128, 1, SWIGLU) == 1024 * 4096 * 2         # normalised X; enough tiles, no K split
     assert w(1024, 27392, 4096, 128, 0, SWIGLU) == 0
     assert w(1024, 4096, 13696, 128, 0, NONE) == L.e0m4_workspace_bytes(1024, 4096, 13696, 128) > 0
