@@ -212,7 +212,9 @@ int e0m4_kv_append(void* cache_f16, int64_t max_seq, int64_t row_elems,
  *     rounding.  M <= 8: the HBM-bound decode kernel (2 <= M <= 16: its
  *     matrix-core variant, any group).  M > 16 with K % 128 == 0
  *     (and N <= 2^24): the MFMA GEMM kernels, workspace of
- *     e0m8_workspace_bytes() bytes under the rules of e0m4_matmul.  Other M > 16:
+ *     e0m8_workspace_bytes() bytes under the rules of e0m4_matmul (17 <= M <=
+ *     32 with K <= 2048 and N * K <= 1e7: the matrix-core variant on two
+ *     chunks of rows instead).  Other M > 16:
  *     the decode kernel on 8 rows of X at a time (needs N % 8 == 0).
  * Pointer, alignment, stream and error rules as for the E0M4 entry points.
  */

@@ -383,9 +383,19 @@ static bool e0m8_use_mfma_decode(int64_t M, int64_t N, int64_t K)
     return knob("gemv_mfma") != 1 && gemv_mfma8_supported(M, N, K);
 }
 
+// The 8-bit form of small_batch_in_chunks.  Twice the weight bytes per launch: the two launches only win on
+// small weights with short rows (2048 x 2048: 9 against 11 us, 8192 x 1024: 10 against 10.7; 4096 x 4096 equal,
+// 512 x 4096 and larger weights 5 - 20 % slower).
+static bool small_batch8_in_chunks(const Fusion& f, int64_t M, int64_t N, int64_t K)
+{
+    return M > kChunkRows && M <= kChunkedMaxM && knob("gemv_mfma") != 1 && K <= 2048 && (double)N * (double)K <= 1e7 &&
+           gemv_mfma8_whole_rows(f, kChunkRows, N, K);
+}
+
 static bool e0m8_use_gemm(int64_t M, int64_t N, int64_t K)
 {
-    return !e0m8_use_mfma_decode(M, N, K) && !small_m_on_vector(M, N, K) && gemm_pipe_supported(K) && N <= (int64_t)1 << 24;
+    return !e0m8_use_mfma_decode(M, N, K) && !small_batch8_in_chunks(Fusion{}, M, N, K) && !small_m_on_vector(M, N, K) &&
+           gemm_pipe_supported(K) && N <= (int64_t)1 << 24;
 }
 
 size_t e0m8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
@@ -412,6 +422,13 @@ int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t 
     if (!X || !codes) return E0M4_ERR_NULL;
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
     if (e0m8_use_mfma_decode(M, N, K)) return launch_gemv_mfma8(X, M, codes, N, K, Y, (hipStream_t)stream);
+    if (small_batch8_in_chunks(Fusion{}, M, N, K)) {
+        const int64_t m0 = first_chunk_rows(M);
+        rc = launch_gemv_mfma8(X, m0, codes, N, K, Y, (hipStream_t)stream);
+        if (rc != E0M4_OK) return rc;
+        return launch_gemv_mfma8(static_cast<const char*>(X) + m0 * K * 2, M - m0, codes, N, K,
+                                 static_cast<char*>(Y) + m0 * N * 2, (hipStream_t)stream);
+    }
     if (e0m8_use_gemm(M, N, K)) {
         if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
         return launch_gemm_pipe8(X, M, codes, N, K, Y, workspace, workspace_bytes, (hipStream_t)stream);
@@ -431,6 +448,7 @@ int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t 
 static int fused_path8(const Fusion& f, int64_t M, int64_t N, int64_t K)
 {
     if (knob("gemv_mfma") != 1 && gemv_mfma8_fused_supported(f, M, N, K)) return 2;
+    if (small_batch8_in_chunks(f, M, N, K)) return 3;
     if (small_m_on_vector(M, N, K) && gemv_fused_supported(f, M, N, 2 * K)) return 0;
     return gemm_pipe_supported(K) && N <= (int64_t)1 << 24 ? 1 : -1;
 }
@@ -469,6 +487,15 @@ int e0m8_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
     const int path = fused_path8(f, M, N, K);
     if (path == 2) return launch_gemv_mfma8_fused(f, X, M, codes, N, K, Y, st);
     if (path == 0) return launch_gemv8_fused(f, X, M, codes, N, K, Y, st);
+    if (path == 3) {
+        const int64_t m0 = first_chunk_rows(M), n_out = f.swiglu ? N / 2 : N;
+        rc = launch_gemv_mfma8_fused(f, X, m0, codes, N, K, Y, st);
+        if (rc != E0M4_OK) return rc;
+        Fusion rest = f;
+        if (f.residual) rest.residual = static_cast<const char*>(f.residual) + m0 * n_out * 2;
+        return launch_gemv_mfma8_fused(rest, static_cast<const char*>(X) + m0 * K * 2, M - m0, codes, N, K,
+                                       static_cast<char*>(Y) + m0 * n_out * 2, st);
+    }
     if (path != 1) return E0M4_ERR_SHAPE;               // larger M needs K % 128 == 0 (GEMM kernels)
     const size_t nb = rms_gamma ? norm_bytes(M, K) : 0;
     const size_t need = nb + gemm_pipe_workspace_bytes(M, N, K, f.swiglu);

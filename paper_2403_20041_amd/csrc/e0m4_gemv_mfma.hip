@@ -755,6 +755,12 @@ bool gemv_mfma8_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K
     return make_mfma_plan(M, N, 2 * K, p, f.swiglu ? 2 : 1, true);
 }
 
+bool gemv_mfma8_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K)
+{
+    MfmaPlan p;
+    return gemv_mfma8_fused_supported(f, M, N, K) && make_mfma_plan(M, N, 2 * K, p, f.swiglu ? 2 : 1, true) && p.kb_phase == 0;
+}
+
 int launch_gemv_mfma8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                             hipStream_t stream)
 {

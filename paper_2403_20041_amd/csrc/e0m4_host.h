@@ -67,6 +67,7 @@ int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, in
 bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K, int group);
 // ... and all M rows of X fit the LDS at once (no phases along K)
 bool gemv_mfma_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K, int group);
+bool gemv_mfma8_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K);
 int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                            hipStream_t stream);
 // INT4 twin of the M = 1 kernel: same layout and work decomposition, codes turned into numbers with

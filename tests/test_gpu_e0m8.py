@@ -180,8 +180,17 @@ def test_gemm_default_choice(e0m4, oracle, M):
 
 def test_decode_long_rows_and_row_chunks(e0m4, oracle):
     run_matmul_case(e0m4, oracle, 8, 40, 16384, 128, seed=720)      # activations staged in several segments
-    run_matmul_case(e0m4, oracle, 21, 136, 1088, 64, seed=721)      # K = 8.5 x 128: three launches of 8 + 8 + 5 rows
+    run_matmul_case(e0m4, oracle, 37, 136, 1088, 64, seed=721)      # K = 8.5 x 128: launches of 8 + 8 + 8 + 8 + 5 rows
     run_matmul_case(e0m4, oracle, 16, 64, 256, 128, seed=722)
+
+
+@pytest.mark.parametrize("M", [17, 21, 32])
+def test_small_batch_two_chunks_of_rows(e0m4, oracle, M):
+    # 17 <= M <= 32 on small weights: the small-batch kernel on 16 (M = 17: 8) rows, then on the rest; no workspace
+    for N, K, G, seed in ((333, 1152, 128, 770), (1000, 2048, 64, 771), (68, 192, 64, 772)):
+        assert e0m4.e0m8_workspace_bytes(M, N, K, G) == 0
+        run_matmul_case(e0m4, oracle, M, N, K, G, seed=seed + M, outliers=True)
+    run_matmul_case(e0m4, oracle, 33, 336, 1152, 128, seed=773)         # beyond 32 rows: the GEMM
 
 
 @pytest.mark.parametrize("M", [1, 20])

@@ -199,7 +199,7 @@ def test_e0m8_validation_and_sizes(L):
     assert L.e0m8_quantize(odd, 64, 128, 64, p, p, p, null) == ERR_ALIGN
     assert L.e0m8_dequant(p, 64, 128, 64, null, null) == ERR_NULL
     assert L.e0m8_matmul(p, 1, p, 64, 128, 64, odd, null, 0, null) == ERR_ALIGN
-    assert L.e0m8_matmul(p, 20, p, 68, 192, 64, p, null, 0, null) == ERR_SHAPE          # row chunks of Y need N % 8 == 0
+    assert L.e0m8_matmul(p, 40, p, 68, 192, 64, p, null, 0, null) == ERR_SHAPE          # row chunks of Y need N % 8 == 0
     assert L.e0m8_matmul(null, 0, null, 64, 128, 64, null, null, 0, null) == 0
     assert L.e0m8_matmul(p, 1024, p, 4096, 13696, 128, p, null, 0, null) == -5          # split K: workspace needed
     assert L.e0m8_workspace_bytes(8, 4096, 4096, 128) == 0
