@@ -74,7 +74,8 @@ size_t e0m4_params_elems(int64_t N, int64_t K, int group);
 /* Scratch bytes e0m4_matmul needs for this shape: 0 for the small-M paths
  * (partial sums stay on chip) and for GEMM shapes with enough output tiles to fill the GPU;
  * otherwise splits * M * N * 4 bytes of fp32 partial sums for the GEMM's split
- * along K.  Depends on the tuning knobs in force; query after setting them. */
+ * along K.  A pure function of the shape (0 for empty or invalid problems), unless the calling
+ * thread has set a diagnostic knob (e0m4_set_knob), which then applies to its queries and calls alike. */
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
 
 /*
@@ -263,9 +264,12 @@ int e0m4_int4_dequant(const void* codes, int64_t N, int64_t K, int group, void* 
 int e0m4_int4_gemv(const void* X_f16, const void* codes, int64_t N, int64_t K, int group, void* Y_f16, void* stream);
 
 /*
- * Diagnostics for tuning sweeps; not needed for normal use.  Sets an integer
- * knob by name (e.g. "gemv_waves"); unknown names return E0M4_ERR_SHAPE.
- * A value of 0 restores the built-in heuristic.
+ * Diagnostics for tuning sweeps and for tests that force every kernel variant;
+ * not needed for normal use.  Sets an integer knob by name (e.g. "gemv_waves");
+ * unknown names return E0M4_ERR_SHAPE.  A value of 0 restores the built-in
+ * heuristic.  Knobs belong to the CALLING THREAD: they change that thread's later
+ * size queries and launches only, so a query and the call it sizes always agree
+ * and other threads keep the built-in choices.
  */
 int e0m4_set_knob(const char* name, int value);
 

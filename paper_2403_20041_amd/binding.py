@@ -103,6 +103,22 @@ def _stream(stream) -> int:
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
+def _empty(shape, dtype, device, stream, what: str):
+    """torch.empty for a buffer that the kernels enqueued on `stream` will use.  The caching allocator ties a
+    block to the stream that was current when it was allocated, so the buffer is allocated with `stream`
+    current; a raw stream handle that is not the current stream cannot be made current here, and the caller
+    must then own the buffer."""
+    if stream is None:
+        return torch.empty(shape, dtype=dtype, device=device)
+    if hasattr(stream, "cuda_stream"):
+        with torch.cuda.stream(stream):
+            return torch.empty(shape, dtype=dtype, device=device)
+    if int(stream) == torch.cuda.current_stream(device).cuda_stream:
+        return torch.empty(shape, dtype=dtype, device=device)
+    raise ValueError("%s: pass a caller-owned tensor when `stream` is a raw handle other than torch's current stream"
+                     % what)
+
+
 def _ptr(t) -> int:
     return 0 if t is None else t.data_ptr()
 
@@ -186,11 +202,11 @@ def e0m4_matmul(X, codes, scales, bias, N: int, K: int, group: int, out=None, wo
     M = X.shape[0]
     _need(X, torch.float16, (M, K), "X")
     if out is None:
-        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+        out = _empty((M, N), torch.float16, X.device, stream, "out")
     _need(out, torch.float16, (M, N), "out")
     need = e0m4_workspace_bytes(M, N, K, group)
     if workspace is None and need > 0:
-        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+        workspace = _empty(need, torch.uint8, X.device, stream, "workspace")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().e0m4_matmul(_ptr(X), M, _ptr(codes), _ptr(scales), _ptr(bias), N, K, group, _ptr(out),
                              _ptr(workspace), ws_bytes, _stream(stream)), "e0m4_matmul")
@@ -217,11 +233,11 @@ def e0m4_matmul_fused(X, codes, N: int, K: int, group: int, rms_gamma=None, rms_
     if residual is not None:
         _need(residual, torch.float16, (M, n_out), "residual")
     if out is None:
-        out = torch.empty((M, n_out), dtype=torch.float16, device=X.device)
+        out = _empty((M, n_out), torch.float16, X.device, stream, "out")
     _need(out, torch.float16, (M, n_out), "out")
     need = e0m4_fused_workspace_bytes(M, N, K, group, rms_gamma is not None, epilogue)
     if workspace is None and need > 0:
-        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+        workspace = _empty(need, torch.uint8, X.device, stream, "workspace")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().e0m4_matmul_fused(_ptr(X), M, _ptr(rms_gamma), float(rms_eps), _ptr(codes), N, K, group, epilogue,
                                    _ptr(residual), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream)),
@@ -288,11 +304,11 @@ def e0m8_matmul(X, codes, N: int, K: int, group: int, out=None, workspace=None, 
     M = X.shape[0]
     _need(X, torch.float16, (M, K), "X")
     if out is None:
-        out = torch.empty((M, N), dtype=torch.float16, device=X.device)
+        out = _empty((M, N), torch.float16, X.device, stream, "out")
     _need(out, torch.float16, (M, N), "out")
     need = e0m8_workspace_bytes(M, N, K, group)
     if workspace is None and need > 0:
-        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+        workspace = _empty(need, torch.uint8, X.device, stream, "workspace")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().e0m8_matmul(_ptr(X), M, _ptr(codes), N, K, group, _ptr(out), _ptr(workspace), ws_bytes,
                              _stream(stream)), "e0m8_matmul")
@@ -310,11 +326,11 @@ def e0m8_matmul_fused(X, codes, N: int, K: int, group: int, rms_gamma=None, rms_
     if residual is not None:
         _need(residual, torch.float16, (M, n_out), "residual")
     if out is None:
-        out = torch.empty((M, n_out), dtype=torch.float16, device=X.device)
+        out = _empty((M, n_out), torch.float16, X.device, stream, "out")
     _need(out, torch.float16, (M, n_out), "out")
     need = lib().e0m8_fused_workspace_bytes(M, N, K, group, 1 if rms_gamma is not None else 0, epilogue)
     if workspace is None and need > 0:
-        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+        workspace = _empty(need, torch.uint8, X.device, stream, "workspace")
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().e0m8_matmul_fused(_ptr(X), M, _ptr(rms_gamma), float(rms_eps), _ptr(codes), N, K, group, epilogue,
                                    _ptr(residual), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream)),

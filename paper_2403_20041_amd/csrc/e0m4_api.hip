@@ -13,17 +13,19 @@ namespace {
 
 thread_local char g_hip_error[256] = "";
 
+// Diagnostic knobs belong to the calling thread: a size query and the call it sizes, made from one thread,
+// always see the same values, and a thread that never sets a knob always gets the built-in heuristics.
 struct Knob {
     const char* name;
-    std::atomic<int> value;
+    int value;
 };
-Knob g_knobs[] = {
-    {"gemv_waves", {0}},               // wavefronts per workgroup of the small-M kernel (4, 8 or 16)
-    {"gemv_workgroups", {0}},          // target number of workgroups of the small-M kernel
-    {"gemv_mfma", {0}},                // 1: never use the matrix-core small-batch kernel (2 <= M <= 16); 2: use it, activations always from LDS; 3: use it, wavefront sums reduced per row block
-    {"gemv_xreg", {0}},                // M = 1 kernel, a wavefront's activations in registers: 2 never
-    {"gemm_variant", {0}},             // 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
-    {"gemm_splits", {0}},              // force the number of K splits of the pipelined GEMM kernel
+thread_local Knob g_knobs[] = {
+    {"gemv_waves", 0},                 // wavefronts per workgroup of the small-M kernel (4, 8 or 16)
+    {"gemv_workgroups", 0},            // target number of workgroups of the small-M kernel
+    {"gemv_mfma", 0},                  // 1: never use the matrix-core small-batch kernel (2 <= M <= 16); 2: use it, activations always from LDS; 3: use it, wavefront sums reduced per row block
+    {"gemv_xreg", 0},                  // M = 1 kernel, a wavefront's activations in registers: 2 never
+    {"gemm_variant", 0},               // 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
+    {"gemm_splits", 0},                // force the number of K splits of the pipelined GEMM kernel
 };
 
 __global__ void zero_fill_kernel(half_t* y, int64_t count)
@@ -84,7 +86,7 @@ int check_launch() { return record_hip_error(hipGetLastError()); }
 int knob(const char* name)
 {
     for (auto& k : g_knobs)
-        if (strcmp(k.name, name) == 0) return k.value.load(std::memory_order_relaxed);
+        if (strcmp(k.name, name) == 0) return k.value;
     return 0;
 }
 
@@ -126,7 +128,8 @@ size_t e0m4_params_elems(int64_t N, int64_t K, int group)
 
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 {
-    if (check_shape(N, K, group) != E0M4_OK || small_m_on_vector(M, N, K) || K == 0) return 0;   // the small-M kernels need none
+    if (check_shape(N, K, group) != E0M4_OK || M <= 0 || N == 0 || K == 0) return 0;             // invalid or empty: nothing runs
+    if (small_m_on_vector(M, N, K)) return 0;           // the small-M kernels need none
     if (use_gemv_mfma(M, N, K, group) || small_batch_in_chunks(Fusion{}, M, N, K, group)) return 0;
     return gemm_workspace_bytes(M, N, K);       // partial tiles of the split-K GEMM, if it splits
 }
@@ -160,7 +163,7 @@ int e0m4_set_knob(const char* name, int value)
     if (!name) return E0M4_ERR_NULL;
     for (auto& k : g_knobs)
         if (strcmp(k.name, name) == 0) {
-            k.value.store(value, std::memory_order_relaxed);
+            k.value = value;
             return E0M4_OK;
         }
     return E0M4_ERR_SHAPE;

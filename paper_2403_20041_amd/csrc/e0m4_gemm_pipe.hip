@@ -474,7 +474,8 @@ PipeTile pipe_tile(int64_t M, int64_t N, int64_t K)
     if (v == 3) return mid;
     if (v == 2) return big;
     if (M <= kFlatMaxM) return flat;
-    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256), pairs = K / (2 * BK);
+    // (at least one tile: callers ask for the tile of empty problems too, whose work item count is then zero)
+    const int64_t big_tiles = std::max<int64_t>(1, ((M + 255) / 256) * ((N + 255) / 256)), pairs = K / (2 * BK);
     const int64_t big_splits = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kComputeUnits / big_tiles, pairs / kMinPairsPerSplit), kMaxSplits));
     if (big_tiles < kFewBigTiles && M <= kFlatAlsoMaxM) return flat;
     if (big_tiles < kFewBigTilesShortK && pairs / big_splits <= kShortSplitPairs) return flat;

@@ -13,22 +13,24 @@ from test_gpu_parity import DEV, assert_quantize_exact, bits, check_matmul, e0m4
 pytestmark = pytest.mark.gpu
 
 CASES = [
-    # (name, N, K, G, prefill M or None)
-    ("cfg1_square", 4096, 4096, 128, None),
-    ("chatglm2_qkv", 4608, 4096, 128, 1024),
-    ("chatglm2_attn_out", 4096, 4096, 128, 1024),
-    ("chatglm2_gate_up", 27392, 4096, 128, 1024),
-    ("chatglm2_down", 4096, 13696, 128, 1024),
-    ("gemma_qkv", 2560, 2048, 128, 512),
-    ("gemma_attn_out", 2048, 2048, 128, 512),
-    ("gemma_gate_up", 32768, 2048, 128, 512),
-    ("gemma_down", 2048, 16384, 128, 512),
-    ("gemma_lm_head", 256000, 2048, 128, None),
-    ("d14b_qkv_g64", 15360, 5120, 64, 2048),
-    ("d14b_attn_out_g128", 5120, 5120, 128, 2048),
-    ("d14b_gate_up_g128", 27392, 5120, 128, None),
-    ("d14b_down_g64", 5120, 13696, 64, 2048),
+    # (name, N, K, G, prefill M or None, seed or None)
+    ("cfg1_square_seed0", 4096, 4096, 128, None, 0),        # the single decode GEMV of the first workload, its own seed
+    ("cfg1_square", 4096, 4096, 128, None, None),
+    ("chatglm2_qkv", 4608, 4096, 128, 1024, None),
+    ("chatglm2_attn_out", 4096, 4096, 128, 1024, None),
+    ("chatglm2_gate_up", 27392, 4096, 128, 1024, None),
+    ("chatglm2_down", 4096, 13696, 128, 1024, None),
+    ("gemma_qkv", 2560, 2048, 128, 512, None),
+    ("gemma_attn_out", 2048, 2048, 128, 512, None),
+    ("gemma_gate_up", 32768, 2048, 128, 512, None),
+    ("gemma_down", 2048, 16384, 128, 512, None),
+    ("gemma_lm_head", 256000, 2048, 128, None, None),
 ]
+# the 14B-shaped layer: every projection with groups of 64 and of 128, decode in full and prefill at M = 2048
+CASES += [("d14b_%s_g%d" % (name, G), N, K, G, 2048, None)
+          for name, N, K in (("qkv", 15360, 5120), ("attn_out", 5120, 5120), ("gate_up", 27392, 5120),
+                             ("down", 5120, 13696))
+          for G in (64, 128)]
 
 
 def sample_indices(count, total, tile, rng):
@@ -38,9 +40,10 @@ def sample_indices(count, total, tile, rng):
     return np.array(sorted(fixed | extra), dtype=np.int64)
 
 
-@pytest.mark.parametrize("name,N,K,G,Mp", CASES, ids=[c[0] for c in CASES])
-def test_full_size_layer(e0m4, oracle, name, N, K, G, Mp):
-    seed = abs(hash((N, K, G))) % 10007
+@pytest.mark.parametrize("name,N,K,G,Mp,seed", CASES, ids=[c[0] for c in CASES])
+def test_full_size_layer(e0m4, oracle, name, N, K, G, Mp, seed):
+    if seed is None:
+        seed = abs(hash((N, K, G))) % 10007
     prefill = Mp is not None
     W = synth_inputs.weights(N, K, seed=seed, row_std_range=(0.5, 2.0) if prefill else None)
     (codes, scales, bias), What = assert_quantize_exact(e0m4, oracle, W, G)

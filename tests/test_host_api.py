@@ -59,6 +59,53 @@ def test_size_functions(L):
     assert L.e0m4_workspace_bytes(1024, 4096, 4160, 64) == 0            # K not a multiple of 128: other kernel
 
 
+def test_size_queries_of_empty_and_invalid_problems(L):
+    """Every size query answers 0 for an empty or invalid problem and never faults (a query with N = 0 once
+    divided by a tile count of zero)."""
+    L.e0m4_fused_workspace_bytes.restype = ctypes.c_size_t
+    L.e0m4_fused_workspace_bytes.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 3
+    L.e0m8_fused_workspace_bytes.restype = ctypes.c_size_t
+    L.e0m8_fused_workspace_bytes.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 3
+    L.e0m8_workspace_bytes.restype = ctypes.c_size_t
+    L.e0m8_workspace_bytes.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int]
+    for M in (0, 1, 8, 16, 24, 64, 1000, 1024, 4096, -3):
+        for N, K in ((0, 4096), (4096, 0), (0, 0), (-1, 128), (128, -128), (128, 100)):
+            assert L.e0m4_workspace_bytes(M, N, K, 128) == 0, (M, N, K)
+            assert L.e0m8_workspace_bytes(M, N, K, 128) == 0, (M, N, K)
+            for norm in (0, 1):
+                for epi in (0, 1):
+                    assert L.e0m4_fused_workspace_bytes(M, N, K, 128, norm, epi) == 0, (M, N, K)
+                    assert L.e0m8_fused_workspace_bytes(M, N, K, 128, norm, epi) == 0, (M, N, K)
+    for M in (0, -1):
+        assert L.e0m4_workspace_bytes(M, 4096, 4096, 128) == 0
+        assert L.e0m8_workspace_bytes(M, 4096, 4096, 128) == 0
+        assert L.e0m4_fused_workspace_bytes(M, 4096, 4096, 128, 1, 1) == 0
+    assert L.e0m4_workspace_bytes(1024, 4096, 4096, 48) == 0            # bad group
+    assert L.e0m4_codes_bytes(0, 0, 128) == 0 and L.e0m4_params_elems(0, 128, 128) == 0
+    assert L.e0m8_codes_bytes(0, 128, 128) == 0
+
+
+def test_knobs_belong_to_the_calling_thread(L):
+    """A diagnostic knob set by one thread changes neither the size queries nor the dispatch of another."""
+    import threading
+
+    shape = (1024, 4096, 13696, 128)
+    base = L.e0m4_workspace_bytes(*shape)
+    assert base == 4 * 1024 * 4096 * 4
+    seen = {}
+
+    def other():
+        assert L.e0m4_set_knob(b"gemm_splits", 2) == 0
+        seen["other"] = L.e0m4_workspace_bytes(*shape)
+        # left set on purpose: it must die with the thread
+
+    th = threading.Thread(target=other)
+    th.start()
+    th.join()
+    assert seen["other"] == 2 * 1024 * 4096 * 4
+    assert L.e0m4_workspace_bytes(*shape) == base
+
+
 def test_error_codes_before_any_launch(L):
     p = ctypes.c_void_p(0x1000)         # aligned, never dereferenced: every call below fails validation first
     odd = ctypes.c_void_p(0x1008)

@@ -442,6 +442,61 @@ def test_int4_invariants(oracle):
             assert (np.diff(codes[n, :G][order].astype(int)) >= 0).all()
 
 
+def test_int4_fit_scale_and_zero_point_against_exact_rationals(oracle):
+    """The INT4 fit, group by group, against the stated definition in exact rationals: scale is the fp16
+    rounding of (max - min)/15 over the range extended to 0; zero is round-half-to-even of -min/scale with the
+    STORED fp16 scale, clamped to 0..15.  A fit that rounded half up, used the unrounded scale, forgot the
+    extension to 0 or the clamp fails here."""
+    def fit(w0):
+        w0 = np.asarray(w0, dtype=np.float16)
+        _, sc, ze = oracle.int4_quantize(w0.reshape(1, -1), w0.size)
+        return Fraction(float(sc[0, 0])), int(ze[0, 0]), float(ze[0, 0])
+
+    def rne(x: Fraction) -> int:
+        f = x.numerator // x.denominator
+        r = x - f
+        if r > Fraction(1, 2) or (r == Fraction(1, 2) and f % 2 == 1):
+            f += 1
+        return f
+
+    # hand-made groups whose scale is exactly 1: zero = rne(-min)
+    for w0, z_want in (([-2.5, 12.5, 0.0, 1.0], 2),           # tie: half to even, not half up
+                       ([-3.5, 11.5, 0.0, 1.0], 4),           # tie the other way
+                       ([-15.0, -1.0, -2.0, -3.0], 15),       # all negative: range extended to 0, zero at the top
+                       ([15.0, 1.0, 2.0, 3.0], 0),            # all positive: zero at the bottom
+                       ([-7.25, 7.75, 0.0, 1.0], 7), ([-7.75, 7.25, 0.5, 1.0], 8)):
+        s, z, zf = fit(w0)
+        assert s == 1 and z == z_want and zf == z_want, (w0, s, zf)
+    rng = np.random.default_rng(17)
+    exact_checked = 0
+    for trial in range(600):
+        G = int(rng.choice([2, 4, 8, 64, 128]))
+        std = float(rng.choice([1e-3, 0.02, 1.0, 50.0]))
+        w0 = (rng.standard_normal(G) * std).astype(np.float16)
+        if trial % 7 == 0:
+            w0 = np.abs(w0)
+        if trial % 11 == 0:
+            w0 = -np.abs(w0)
+        s, z, zf = fit(w0)
+        vals = [Fraction(float(v)) for v in w0]
+        mn, mx = min([Fraction(0)] + vals), max([Fraction(0)] + vals)
+        s_exact = (mx - mn) / 15
+        if s_exact >= Fraction(1, 2 ** 14):         # fp32 divide, then fp16 rounding: half an fp16 ulp (and a bit)
+            assert abs(s - s_exact) <= s_exact * Fraction(1, 2 ** 11) * Fraction(1001, 1000)
+        else:
+            assert s == Fraction(1, 2 ** 14)
+        assert zf == z and 0 <= z <= 15
+        z_exact = -mn / s                           # with the stored scale
+        want = min(max(rne(z_exact), 0), 15)
+        frac = z_exact - (z_exact.numerator // z_exact.denominator)
+        if abs(frac - Fraction(1, 2)) > Fraction(1, 2 ** 18):    # away from a tie the fp32 quotient cannot change the result
+            assert z == want, (trial, float(z_exact), z)
+            exact_checked += 1
+        else:
+            assert abs(z - z_exact) <= Fraction(1, 2) + Fraction(1, 2 ** 18)
+    assert exact_checked > 550
+
+
 def test_int4_agrees_with_the_plain_float64_definition_in_distribution(oracle):
     W = synth_inputs.weights(2000, 512, seed=13)
     codes, scales, zeros = oracle.int4_quantize(W, 128)
