@@ -142,6 +142,29 @@ int e0m4_matmul(const void* X_f16, int64_t M,
                 void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * e0m4_matmul for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  Same result, bit for bit, and same argument and
+ * error rules as e0m4_matmul(X, M, codes, NULL, NULL, N, K, group, Y, ...),
+ * but the scratch memory of the split along K is a fixed array inside the
+ * library, E0M4_STATIC_SCRATCH_BYTES = 64 MiB of device memory that every GPU
+ * the library runs on holds from the first use until the process ends.  The
+ * call allocates and frees nothing (no hipMalloc, no allocating runtime or
+ * library routine); its first call on a device looks up the array's address on
+ * that device (make that call outside a graph capture).
+ *   - E0M4_ERR_WORKSPACE if e0m4_workspace_bytes(M, N, K, group) exceeds the
+ *     array; nothing is enqueued then.  (With the built-in choices no shape needs
+ *     more than 64 MiB; only a forced number of K splits can.)
+ *   - All calls on one GPU share the one array: calls whose work may overlap
+ *     on that GPU (different streams, different threads) race on it; issue them on
+ *     one stream or order them with events.  The array is never read before the
+ *     same call has written it, so nothing has to be cleared between calls.
+ */
+#define E0M4_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int e0m4_matmul_static(const void* X_f16, int64_t M, const void* codes, int64_t N, int64_t K, int group,
+                       void* Y_f16, void* stream);
+
+/*
  * The matmul with its neighbouring operators folded in (paper: section
  * "Operator and lagging optimizations": the small operators of rms-norm are
  * fused into one, element-wise operators are fused into the operator next to

@@ -6,6 +6,7 @@ The package holds the HIP sources (``csrc/``), the in-tree build
 from .binding import (  # noqa: F401
     E0M4_EPILOGUE_NONE,
     E0M4_EPILOGUE_SWIGLU,
+    E0M4_STATIC_SCRATCH_BYTES,
     E0M4Error,
     alloc_packed,
     e0m4_codes_bytes,
@@ -17,6 +18,7 @@ from .binding import (  # noqa: F401
     e0m4_int4_quantize,
     e0m4_kv_append,
     e0m4_matmul,
+    e0m4_matmul_static,
     e0m4_matmul_fused,
     e0m4_params_elems,
     e0m4_quantize,

@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
     L.e0m4_unpack_codes.argtypes = [vp, i64, i64, ci, vp, vp]
     L.e0m4_matmul.restype = ci
     L.e0m4_matmul.argtypes = [vp, i64, vp, vp, vp, i64, i64, ci, vp, vp, sz, vp]
+    L.e0m4_matmul_static.restype = ci
+    L.e0m4_matmul_static.argtypes = [vp, i64, vp, i64, i64, ci, vp, vp]
     L.e0m4_fused_workspace_bytes.restype = sz
     L.e0m4_fused_workspace_bytes.argtypes = [i64, i64, i64, ci, ci, ci]
     L.e0m4_matmul_fused.restype = ci
@@ -210,6 +212,20 @@ def e0m4_matmul(X, codes, scales, bias, N: int, K: int, group: int, out=None, wo
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().e0m4_matmul(_ptr(X), M, _ptr(codes), _ptr(scales), _ptr(bias), N, K, group, _ptr(out),
                              _ptr(workspace), ws_bytes, _stream(stream)), "e0m4_matmul")
+    return out
+
+
+E0M4_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def e0m4_matmul_static(X, codes, N: int, K: int, group: int, out, stream=None):
+    """e0m4_matmul without a workspace argument: the library's own fixed scratch array serves the split along
+    K.  `out` is required, so that the call itself allocates nothing."""
+    M = X.shape[0]
+    _need(X, torch.float16, (M, K), "X")
+    _need(out, torch.float16, (M, N), "out")
+    _check(lib().e0m4_matmul_static(_ptr(X), M, _ptr(codes), N, K, group, _ptr(out), _stream(stream)),
+           "e0m4_matmul_static")
     return out
 
 

@@ -28,6 +28,37 @@ thread_local Knob g_knobs[] = {
     {"gemm_splits", 0},                // force the number of K splits of the pipelined GEMM kernel
 };
 
+// Scratch of e0m4_matmul_static: the split-K partial sums that e0m4_matmul keeps in the caller's workspace.
+// Every GPU the library runs on holds its own copy of the array, at its own address, until the process ends.
+constexpr size_t kStaticScratchBytes = E0M4_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device, looked up once per device (in host code the array's
+// name is only a handle for this lookup, never an address a kernel may use).
+constexpr int kMaxTrackedDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxTrackedDevices];
+
+int static_scratch(void** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return record_hip_error(e);
+    if (dev >= 0 && dev < kMaxTrackedDevices) {
+        void* known = g_scratch_ptr[dev].load(std::memory_order_acquire);
+        if (known) {
+            *out = known;
+            return E0M4_OK;
+        }
+    }
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return record_hip_error(e);
+    if (!ptr) return record_hip_error(hipErrorInvalidSymbol);
+    if (dev >= 0 && dev < kMaxTrackedDevices) g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    *out = ptr;
+    return E0M4_OK;
+}
+
 __global__ void zero_fill_kernel(half_t* y, int64_t count)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -280,6 +311,19 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // the GEMM epilogue forms 32-bit offsets of up to 256 rows of Y
     if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
     return launch_gemm(X, M, codes, N, K, group, Y, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int e0m4_matmul_static(const void* X, int64_t M, const void* codes, int64_t N, int64_t K, int group, void* Y, void* stream)
+{
+    // the shape decides the scratch size before anything else is looked at; nothing is allocated anywhere below
+    const size_t need = e0m4_workspace_bytes(M, N, K, group);
+    if (need > kStaticScratchBytes) return E0M4_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (need > 0) {
+        const int rc = static_scratch(&ws);
+        if (rc != E0M4_OK) return rc;
+    }
+    return e0m4_matmul(X, M, codes, nullptr, nullptr, N, K, group, Y, ws, need, stream);
 }
 
 int e0m4_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms_eps, const void* codes, int64_t N,
