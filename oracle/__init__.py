@@ -88,6 +88,8 @@ def _load():
     L.oracle_e0m4_matmul.restype = None
     L.oracle_e0m4_matmul.argtypes = [u16p, i64, u16p, i64, i64, u16p, f64p]
     L.oracle_num_threads.restype = ctypes.c_int
+    L.oracle_set_num_threads.restype = ctypes.c_int
+    L.oracle_set_num_threads.argtypes = [ctypes.c_int]
     _lib = L
     return L
 
@@ -229,6 +231,11 @@ def matmul(X: np.ndarray, What: np.ndarray, want_absdot: bool = True):
 
 def num_threads() -> int:
     return _load().oracle_num_threads()
+
+
+def set_num_threads(n: int) -> bool:
+    """Threads used by the parallel loops from now on (for timing on one thread); False without OpenMP."""
+    return bool(_load().oracle_set_num_threads(int(n)))
 
 
 # --------------------------------------------------------------------------------------------------

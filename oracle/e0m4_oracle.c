@@ -442,3 +442,17 @@ int oracle_num_threads(void)
     return 1;
 #endif
 }
+
+/* Number of threads the parallel loops use from now on (timing the oracle on one thread); 0 if built
+ * without OpenMP.  Changes no arithmetic. */
+int oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n < 1) n = 1;
+    omp_set_num_threads(n);
+    return 1;
+#else
+    (void)n;
+    return 0;
+#endif
+}
