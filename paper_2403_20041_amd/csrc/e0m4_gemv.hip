@@ -138,10 +138,13 @@ enum { kDeqE0M4 = 0, kDeqInt4Convert = 1, kDeqE0M8 = 2 };
 // lane queue up ahead of the weights.)
 template <int G, int M, int W, int DEQ = kDeqE0M4, bool FUSED = false, bool XREG = false>
 __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__ X, const uint4* __restrict__ packed,
-                                                      int64_t N, int64_t K, half_t* __restrict__ Y, int seg_items,
+                                                      half_t* __restrict__ Y, uint32_t N32, uint32_t K32, int seg_items,
                                                       int step_slots, int step_item, int rb_base, int rb_rem, int own_items,
                                                       GemvFusion fu)
 {
+    // (The arguments up to own_items fill the 14 scalar registers that the launch itself can preload, see the
+    // build flags: the plain kernel starts without waiting for a load of its arguments.  N <= 2^31, K <= 2^20.)
+    const int64_t N = N32, K = K32;
     constexpr int kThreads = W * 64;
     constexpr int PW = block_param_words(G);            // parameter words per k block: 16, 32 or 64
     constexpr int NPL = kSuper * PW / 64;               // dword loads per lane that fetch a work item's parameters
@@ -567,8 +570,8 @@ int launch_one(const GemvPlan& p, const void* X, const void* packed, int64_t N, 
                                           kLdsLimitBytes, lds_allowed);
         if (arc != E0M4_OK) return arc;
     }
-    hipLaunchKernelGGL((gemv_kernel<G, M, W, DEQ, FUSED, XREG>), grid, block, lds_bytes, stream, x, c, N, K, y, p.seg_items,
-                       p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.own_items, fu);
+    hipLaunchKernelGGL((gemv_kernel<G, M, W, DEQ, FUSED, XREG>), grid, block, lds_bytes, stream, x, c, y, (uint32_t)N,
+                       (uint32_t)K, p.seg_items, p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.own_items, fu);
     return check_launch();
 }
 

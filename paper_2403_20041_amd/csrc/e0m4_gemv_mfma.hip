@@ -92,12 +92,15 @@ __device__ inline int x_unit_off(int q, int w, int hl) { return ((q * 4 + (w >> 
 // part of X, visits all row blocks of the workgroup and adds to the wavefront sums, which stay in LDS
 // (`late`) until the last phase.  The weights are still read exactly once.
 template <int W, bool FUSED, bool XREG, bool E8 = false, bool PHASED = false>
-__global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restrict__ X, int M,
-                                                           const uint4* __restrict__ packed, int64_t N, int64_t K,
-                                                           half_t* __restrict__ Y, int step_slots_arg, int step_item_arg,
-                                                           int rb_base, int rb_rem, int late, uint32_t pieces_magic_arg,
-                                                           int kb_phase, uint32_t pieces_magic_last, GemvFusion fu)
+__global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restrict__ X,
+                                                           const uint4* __restrict__ packed, half_t* __restrict__ Y,
+                                                           int M, uint32_t N32, uint32_t K32, int step_slots_arg,
+                                                           int step_item_arg, int rb_base, int rb_rem, int late,
+                                                           uint32_t pieces_magic_arg, int kb_phase,
+                                                           uint32_t pieces_magic_last, GemvFusion fu)
 {
+    // (the arguments up to `late` fill the 14 scalar registers the launch can preload; N <= 2^31, K <= 2^20)
+    const int64_t N = N32, K = K32;
     static_assert(!(PHASED && XREG), "a wavefront meets other k blocks in every phase");
     constexpr int kThreads = W * 64;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -659,9 +662,9 @@ int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packe
                                       kLdsLimitBytes, lds_allowed);
     if (arc != E0M4_OK) return arc;
     hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8, PHASED>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes,
-                       stream, static_cast<const half_t*>(X), (int)M, static_cast<const uint4*>(packed), N, K,
-                       static_cast<half_t*>(Y), p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.late, p.pieces_magic,
-                       p.kb_phase, p.pieces_magic_last, fu);
+                       stream, static_cast<const half_t*>(X), static_cast<const uint4*>(packed), static_cast<half_t*>(Y),
+                       (int)M, (uint32_t)N, (uint32_t)K, p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.late,
+                       p.pieces_magic, p.kb_phase, p.pieces_magic_last, fu);
     return check_launch();
 }
 
