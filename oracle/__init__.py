@@ -87,6 +87,29 @@ def _load():
     L.oracle_e0mk_dequant.argtypes = [u8p, u16p, u16p, i64, i64, i64, ci, u16p]
     L.oracle_e0m4_matmul.restype = None
     L.oracle_e0m4_matmul.argtypes = [u16p, i64, u16p, i64, i64, u16p, f64p]
+    L.oracle_bf16_bits_to_double.restype = ctypes.c_double
+    L.oracle_bf16_bits_to_double.argtypes = [ctypes.c_uint16]
+    L.oracle_double_to_bf16_bits.restype = ctypes.c_uint16
+    L.oracle_double_to_bf16_bits.argtypes = [ctypes.c_double]
+    L.oracle_bf16_w1_bits.restype = ctypes.c_uint16
+    L.oracle_bf16_w1_bits.argtypes = [ctypes.c_int]
+    for name in ("oracle_bf16_decode_one",):
+        getattr(L, name).restype = ctypes.c_uint16
+        getattr(L, name).argtypes = [ctypes.c_int, ctypes.c_uint16, ctypes.c_uint16]
+    L.oracle_bf16_encode_one.restype = ctypes.c_int
+    L.oracle_bf16_encode_one.argtypes = [ctypes.c_uint16, ctypes.c_uint16, ctypes.c_uint16]
+    L.oracle_bf16_forward_bits.restype = ctypes.c_uint16
+    L.oracle_bf16_forward_bits.argtypes = [ctypes.c_uint16, ctypes.c_uint16, ctypes.c_uint16]
+    L.oracle_bf16_fit_group.restype = None
+    L.oracle_bf16_fit_group.argtypes = [u16p, i64, u16p, u16p]
+    L.oracle_bf16_quantize.restype = None
+    L.oracle_bf16_quantize.argtypes = [u16p, i64, i64, i64, u8p, u16p, u16p]
+    L.oracle_bf16_encode.restype = None
+    L.oracle_bf16_encode.argtypes = [u16p, i64, i64, i64, u16p, u16p, u8p]
+    L.oracle_bf16_dequant.restype = None
+    L.oracle_bf16_dequant.argtypes = [u8p, u16p, u16p, i64, i64, i64, u16p]
+    L.oracle_bf16_matmul.restype = None
+    L.oracle_bf16_matmul.argtypes = [u16p, i64, u16p, i64, i64, u16p, f64p]
     L.oracle_num_threads.restype = ctypes.c_int
     L.oracle_set_num_threads.restype = ctypes.c_int
     L.oracle_set_num_threads.argtypes = [ctypes.c_int]
@@ -366,3 +389,94 @@ def dequant_k(codes: np.ndarray, scales: np.ndarray, bias: np.ndarray, group: in
     _load().oracle_e0mk_dequant(_p(codes, ctypes.c_uint8), _p(sb, ctypes.c_uint16), _p(bb, ctypes.c_uint16),
                                 N, K, group, int(bits), _p(out, ctypes.c_uint16))
     return out.view(np.float16)
+
+
+# --------------------------------------------------------------------------------------------------
+# The same construction on bfloat16 (see the C source for the reading).  numpy has no bfloat16 type:
+# every bfloat16 array here is a uint16 array of bit patterns.
+# --------------------------------------------------------------------------------------------------
+
+def bf16_bits_to_double(h: int) -> float:
+    return _load().oracle_bf16_bits_to_double(h)
+
+
+def double_to_bf16_bits(d: float) -> int:
+    return _load().oracle_double_to_bf16_bits(d)
+
+
+def bf16_w1_bits(c: int) -> int:
+    return _load().oracle_bf16_w1_bits(c)
+
+
+def bf16_decode_one(c: int, scale_bits: int, bias_bits: int) -> int:
+    return _load().oracle_bf16_decode_one(c, scale_bits, bias_bits)
+
+
+def bf16_encode_one(w0_bits: int, scale_bits: int, bias_bits: int) -> int:
+    return _load().oracle_bf16_encode_one(w0_bits, scale_bits, bias_bits)
+
+
+def bf16_forward_bits(w0_bits: int, scale_bits: int, bias_bits: int) -> int:
+    return _load().oracle_bf16_forward_bits(w0_bits, scale_bits, bias_bits)
+
+
+def bf16_fit_group(w0_bits: np.ndarray):
+    w = np.ascontiguousarray(w0_bits, dtype=np.uint16)
+    sb, bb = ctypes.c_uint16(0), ctypes.c_uint16(0)
+    _load().oracle_bf16_fit_group(_p(w, ctypes.c_uint16), w.size, ctypes.byref(sb), ctypes.byref(bb))
+    return sb.value, bb.value
+
+
+def bf16_quantize(W_bits: np.ndarray, group: int):
+    """W_bits [N,K] bfloat16 bit patterns -> (codes u8 [N,K], scale bits u16 [N,K/G], bias bits u16 [N,K/G])."""
+    Wb = np.ascontiguousarray(W_bits, dtype=np.uint16)
+    N, K = Wb.shape
+    assert K % group == 0
+    codes = np.empty((N, K), np.uint8)
+    scales = np.empty((N, K // group), np.uint16)
+    bias = np.empty((N, K // group), np.uint16)
+    _load().oracle_bf16_quantize(_p(Wb, ctypes.c_uint16), N, K, group, _p(codes, ctypes.c_uint8),
+                                 _p(scales, ctypes.c_uint16), _p(bias, ctypes.c_uint16))
+    return codes, scales, bias
+
+
+def bf16_encode(W_bits: np.ndarray, scales: np.ndarray, bias: np.ndarray, group: int) -> np.ndarray:
+    """Codes of W under given per-group parameters (bit patterns), no fitting."""
+    Wb = np.ascontiguousarray(W_bits, dtype=np.uint16)
+    sb = np.ascontiguousarray(scales, dtype=np.uint16)
+    bb = np.ascontiguousarray(bias, dtype=np.uint16)
+    N, K = Wb.shape
+    codes = np.empty((N, K), np.uint8)
+    _load().oracle_bf16_encode(_p(Wb, ctypes.c_uint16), N, K, group, _p(sb, ctypes.c_uint16), _p(bb, ctypes.c_uint16),
+                               _p(codes, ctypes.c_uint8))
+    return codes
+
+
+def bf16_dequant(codes: np.ndarray, scales: np.ndarray, bias: np.ndarray, group: int) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    sb = np.ascontiguousarray(scales, dtype=np.uint16)
+    bb = np.ascontiguousarray(bias, dtype=np.uint16)
+    N, K = codes.shape
+    out = np.empty((N, K), np.uint16)
+    _load().oracle_bf16_dequant(_p(codes, ctypes.c_uint8), _p(sb, ctypes.c_uint16), _p(bb, ctypes.c_uint16), N, K, group,
+                                _p(out, ctypes.c_uint16))
+    return out
+
+
+def bf16_matmul(X_bits: np.ndarray, What_bits: np.ndarray):
+    """Y bits [M,N] = bf16(sum_k X[m,k] What[n,k]) in fp64, and sum_k |x w| per output."""
+    Xb = np.ascontiguousarray(X_bits, dtype=np.uint16)
+    Wb = np.ascontiguousarray(What_bits, dtype=np.uint16)
+    M, K = Xb.shape
+    N, K2 = Wb.shape
+    assert K == K2
+    Y = np.empty((M, N), np.uint16)
+    absdot = np.empty((M, N), np.float64)
+    _load().oracle_bf16_matmul(_p(Xb, ctypes.c_uint16), M, _p(Wb, ctypes.c_uint16), N, K, _p(Y, ctypes.c_uint16),
+                               _p(absdot, ctypes.c_double))
+    return Y, absdot
+
+
+def bf16_to_float64(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of an array of bfloat16 bit patterns (a bfloat16 is the upper half of a binary32)."""
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)

@@ -434,6 +434,198 @@ void oracle_e0m4_matmul(const uint16_t* X, int64_t M, const uint16_t* What, int6
     free(xd);
 }
 
+/* ------------------------------------------------------------------ */
+/* The same construction on bfloat16 (paper: closing remark of the     */
+/* section "E0M4 FP4 quantization": the approach carries over to other  */
+/* formats and bit widths).                                            */
+/* ------------------------------------------------------------------ */
+/* bfloat16 has 1 sign, 8 exponent and 7 fraction bits (the upper half of a
+ * binary32).  The paper works the method out for FP16 only; the reading taken
+ * for bfloat16 is the E0M4 definition with the format's own numbers:
+ *   - binade [2,4): CONST_EXP_BIN_PART = 0x4000 (bfloat16 2.0),
+ *     CONST_BIT_SHIFT_NUM = 7 - 4 = 3, so w1(c) = as_bf16(0x4000 | c << 3)
+ *     = 2 + c/8, the same sixteen values as for FP16;
+ *   - eps = one unit in the last place of the binade, 2^-6: the top of the range
+ *     is 4 - 2^-6 = 3.984375 (bits 0x407F);
+ *   - code = min(y1 + y2, 15) with y1 = fraction bits 6..3 and y2 = bit 2 of the
+ *     mapped bfloat16 value; the bias keeps fraction bits 6..3 (& 0xFFF8);
+ *   - scale is floored at the smallest normal bfloat16 (2^-126) and capped at the
+ *     largest finite one; weights, scale, bias, activations and outputs are
+ *     bfloat16, the arithmetic fp32 single operations as for FP16;
+ *   - w = bf16((w1 - bias) * scale): difference exact, product exact in fp32
+ *     (5-bit by 8-bit significands), one rounding. */
+
+/* Exact widening of a bfloat16 bit pattern. */
+double oracle_bf16_bits_to_double(uint16_t h)
+{
+    const int sign = (h >> 15) & 1;
+    const int e = (h >> 7) & 0xFF;
+    const int f = h & 0x7F;
+    double v;
+    if (e == 0) {
+        v = ldexp((double)f, -133);                 /* subnormal or zero: f/128 * 2^-126 */
+    } else if (e == 255) {
+        v = f ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(128 + f), e - 134);      /* (1 + f/128) * 2^(e-127) */
+    }
+    return sign ? -v : v;
+}
+
+/* Round-to-nearest-even narrowing of a double to a bfloat16 bit pattern. */
+uint16_t oracle_double_to_bf16_bits(double d)
+{
+    uint16_t sign = (uint16_t)(signbit(d) ? 0x8000u : 0u);
+    double a = fabs(d);
+    if (isnan(d)) return (uint16_t)(sign | 0x7FC0u);
+    if (isinf(d)) return (uint16_t)(sign | 0x7F80u);
+    if (a == 0.0) return sign;
+    if (a < ldexp(1.0, -126)) {
+        double q = nearbyint(ldexp(a, 133));        /* subnormal spacing 2^-133; 128 is the smallest normal */
+        return (uint16_t)(sign | (uint16_t)q);
+    }
+    int ex;
+    (void)frexp(a, &ex);
+    int e = ex - 1;                                 /* a in [2^e, 2^(e+1)) */
+    double q = nearbyint(ldexp(a, 7 - e));          /* in [128, 256] */
+    if (q >= 256.0) { q = 128.0; e += 1; }
+    if (e > 127) return (uint16_t)(sign | 0x7F80u); /* overflow to infinity */
+    return (uint16_t)(sign | (uint16_t)((e + 127) << 7) | (uint16_t)((int)q - 128));
+}
+
+static inline float b2f(uint16_t h) { return (float)oracle_bf16_bits_to_double(h); }   /* exact */
+static inline uint16_t f2b(float f) { return oracle_double_to_bf16_bits((double)f); } /* one rounding */
+
+#define BF16_EXP_BITS 0x4000u
+#define BF16_SHIFT    3
+static const float BF_LO = 2.0f;
+static const float BF_HI = 3.984375f;         /* 4 - 2^-6, bits 0x407F */
+
+uint16_t oracle_bf16_w1_bits(int c)
+{
+    return (uint16_t)(BF16_EXP_BITS | ((unsigned)(c & 15) << BF16_SHIFT));
+}
+
+uint16_t oracle_bf16_decode_one(int c, uint16_t scale_bits, uint16_t bias_bits)
+{
+    double w1 = oracle_bf16_bits_to_double(oracle_bf16_w1_bits(c));
+    double b = oracle_bf16_bits_to_double(bias_bits);
+    double s = oracle_bf16_bits_to_double(scale_bits);
+    return oracle_double_to_bf16_bits((w1 - b) * s);
+}
+
+void oracle_bf16_fit_group(const uint16_t* w0, int64_t G, uint16_t* scale_bits, uint16_t* bias_bits)
+{
+    float mn = 0.0f, mx = 0.0f;
+    for (int64_t k = 0; k < G; ++k) {
+        float v = b2f(w0[k]);
+        if (v < mn) mn = v;
+        if (v > mx) mx = v;
+    }
+    const float span = BF_HI - BF_LO;         /* 1.984375, exact */
+    float range = mx - mn;
+    float s = range / span;
+    if (s < 1.17549435e-38f) s = 1.17549435e-38f;       /* 2^-126, smallest normal */
+    if (s > 3.3895313892515355e38f) s = 3.3895313892515355e38f;   /* largest finite bfloat16, bits 0x7F7F */
+    uint16_t sb = f2b(s);
+    float sf = b2f(sb);
+    float q = mn / sf;
+    float b = BF_LO - q;
+    if (b < BF_LO) b = BF_LO;
+    if (b > BF_HI) b = BF_HI;
+    uint16_t bb = (uint16_t)(f2b(b) & 0xFFF8u);
+    *scale_bits = sb;
+    *bias_bits = bb;
+}
+
+/* bfloat16 bit pattern of the mapped value before the code is cut out of it. */
+uint16_t oracle_bf16_forward_bits(uint16_t w0_bits, uint16_t scale_bits, uint16_t bias_bits)
+{
+    float q = b2f(w0_bits) / b2f(scale_bits);
+    float t = q + b2f(bias_bits);
+    if (t < BF_LO) t = BF_LO;
+    if (t > BF_HI) t = BF_HI;
+    return f2b(t);
+}
+
+int oracle_bf16_encode_one(uint16_t w0_bits, uint16_t scale_bits, uint16_t bias_bits)
+{
+    uint16_t bits = oracle_bf16_forward_bits(w0_bits, scale_bits, bias_bits);
+    int y1 = (bits >> 3) & 15;                /* four highest fraction bits */
+    int y2 = (bits >> 2) & 1;                 /* the next bit, used for rounding */
+    int c = y1 + y2;
+    return c > 15 ? 15 : c;
+}
+
+void oracle_bf16_quantize(const uint16_t* W, int64_t N, int64_t K, int64_t G,
+                          uint8_t* codes, uint16_t* scales, uint16_t* bias)
+{
+    const int64_t ng = K / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t g = 0; g < ng; ++g) {
+            const uint16_t* w0 = W + n * K + g * G;
+            uint16_t sb, bb;
+            oracle_bf16_fit_group(w0, G, &sb, &bb);
+            scales[n * ng + g] = sb;
+            bias[n * ng + g] = bb;
+            for (int64_t k = 0; k < G; ++k)
+                codes[n * K + g * G + k] = (uint8_t)oracle_bf16_encode_one(w0[k], sb, bb);
+        }
+    }
+}
+
+/* Encode with caller-supplied parameters (no fitting). */
+void oracle_bf16_encode(const uint16_t* W, int64_t N, int64_t K, int64_t G,
+                        const uint16_t* scales, const uint16_t* bias, uint8_t* codes)
+{
+    const int64_t ng = K / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k)
+            codes[n * K + k] = (uint8_t)oracle_bf16_encode_one(W[n * K + k], scales[n * ng + k / G],
+                                                               bias[n * ng + k / G]);
+}
+
+void oracle_bf16_dequant(const uint8_t* codes, const uint16_t* scales, const uint16_t* bias,
+                         int64_t N, int64_t K, int64_t G, uint16_t* W_out)
+{
+    const int64_t ng = K / G;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k)
+            W_out[n * K + k] = oracle_bf16_decode_one(codes[n * K + k], scales[n * ng + k / G],
+                                                      bias[n * ng + k / G]);
+}
+
+/* Y[m,n] = bf16( sum_k X[m,k] * What[n,k] ), all bfloat16 bit patterns, fp64 accumulation in k order. */
+void oracle_bf16_matmul(const uint16_t* X, int64_t M, const uint16_t* What, int64_t N, int64_t K,
+                        uint16_t* Y, double* absdot)
+{
+    double* xd = (double*)malloc(sizeof(double) * (size_t)(M * K > 0 ? M * K : 1));
+    for (int64_t i = 0; i < M * K; ++i) xd[i] = oracle_bf16_bits_to_double(X[i]);
+#pragma omp parallel
+    {
+        double* wd = (double*)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));
+#pragma omp for schedule(static)
+        for (int64_t n = 0; n < N; ++n) {
+            for (int64_t k = 0; k < K; ++k) wd[k] = oracle_bf16_bits_to_double(What[n * K + k]);
+            for (int64_t m = 0; m < M; ++m) {
+                double acc = 0.0, aacc = 0.0;
+                for (int64_t k = 0; k < K; ++k) {
+                    double p = xd[m * K + k] * wd[k];
+                    acc += p;
+                    aacc += fabs(p);
+                }
+                Y[m * N + n] = oracle_double_to_bf16_bits(acc);
+                if (absdot) absdot[m * N + n] = aacc;
+            }
+        }
+        free(wd);
+    }
+    free(xd);
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

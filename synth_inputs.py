@@ -56,6 +56,22 @@ def activations(M: int, K: int, seed: int, outlier_frac: float = 0.0, outlier_sc
     return X.astype(np.float16)
 
 
+def to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """fp32 array -> bfloat16 bit patterns (uint16), round to nearest even; a change of storage type only."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def weights_bf16(N: int, K: int, seed: int, std: float = W_STD) -> np.ndarray:
+    """W [N,K] ~ N(0, std) as bfloat16 bit patterns (uint16)."""
+    return to_bf16_bits(_rng(seed, 1).standard_normal((N, K), dtype=np.float32) * np.float32(std))
+
+
+def activations_bf16(M: int, K: int, seed: int) -> np.ndarray:
+    """X [M,K] ~ N(0,1) as bfloat16 bit patterns (uint16)."""
+    return to_bf16_bits(_rng(seed, 3).standard_normal((M, K), dtype=np.float32))
+
+
 def norm_weight(K: int, seed: int) -> np.ndarray:
     """rms-norm weight gamma [K] fp16 ~ 1 + 0.1 N(0,1) (trained norm weights sit around one)."""
     return (1.0 + 0.1 * _rng(seed, 5).standard_normal(K, dtype=np.float32)).astype(np.float16)
