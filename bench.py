@@ -17,7 +17,7 @@ sections (small batches, E0M4 against INT4, 8-bit codes, operator fusion,
 KV append); and the CPU oracle timed on bounded samples of the same work.
 
 Sections can be selected with --only / --skip (names: decode, shapes, cfg1,
-prefill, gemma, d14b, small_batch, table1, e0m8, fusion, kv, cpu); the profiler
+prefill, gemma, d14b, small_batch, table1, e0m8, bf16, fusion, kv, cpu); the profiler
 commands under profiles/ use that to keep their runs short.
 
 `python bench.py --summarize DIR [--last N]` prints a summary of a rocprofv3
@@ -40,8 +40,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 matrix peak
 GROUP = 128
-SECTIONS = ("decode", "shapes", "cfg1", "prefill", "gemma", "d14b", "small_batch", "table1", "e0m8", "fusion", "kv",
-            "cpu")
+SECTIONS = ("decode", "shapes", "cfg1", "prefill", "gemma", "d14b", "small_batch", "table1", "e0m8", "bf16", "fusion",
+            "kv", "cpu")
 
 
 def algorithmic_bytes(M, N, K, G):
@@ -497,6 +497,37 @@ def main():
         out["e0m8_decode"] = {"workload": "E0M8 (8-bit codes, group %d), M=1, ChatGLM2-6B shapes; latency per launch, "
                                           "cold weights; algorithmic bytes N*K*(1 + 4/64) + 2K + 2N" % GROUP,
                               "per_shape": e8}
+
+    if "bf16" in want:
+        # E0M4 on bfloat16 (same packed codes, bfloat16 activations, parameters and outputs): M = 1 and M = 1024
+        bf = {}
+        for name, N, K in shapes:
+            W = synth_inputs.weights_device(N, K, 8800 + N + K, dev).to(torch.bfloat16)
+            cb = e0m4.e0m4_bf16_quantize(W, GROUP, stream=stream)[0]
+            del W
+            copies = max(2, min(32, int(7e8 // cb.numel())))
+            bufs = [cb] + [cb.clone() for _ in range(copies - 1)]
+            x = synth_inputs.activations_device(1, K, 8900 + K, dev).to(torch.bfloat16)
+            y = torch.empty((1, N), dtype=torch.bfloat16, device=dev)
+
+            def one_pass():
+                for c in bufs:
+                    e0m4.e0m4_bf16_matmul(x, c, N, K, GROUP, out=y, stream=stream)
+
+            us = time_us(capture(one_pass), 4, rounds=5) / copies
+            b = algorithmic_bytes(1, N, K, GROUP)
+            bf[name] = {"N": N, "K": K, "us": round(us, 3), "GBps": round(b / us / 1e3, 1),
+                        "frac_hbm": round(b / us / 1e3 / HBM_PEAK_GBPS, 4)}
+            if "prefill" in want:
+                X = synth_inputs.activations_device(1024, K, 8950 + K, dev, outlier_frac=0.01).to(torch.bfloat16)
+                Y = torch.empty((1024, N), dtype=torch.bfloat16, device=dev)
+                pus = time_us(lambda: e0m4.e0m4_bf16_matmul(X, cb, N, K, GROUP, out=Y, stream=stream), 20, rounds=2, warm=3)
+                bf[name]["prefill_M1024_us"] = round(pus, 2)
+                bf[name]["prefill_TFLOPs"] = round(2.0 * 1024 * N * K / pus / 1e6, 1)
+                del X, Y
+            del bufs, cb, x, y
+        out["e0m4_bf16"] = {"workload": "E0M4 on bfloat16 (group %d), ChatGLM2-6B shapes: M=1 latency per launch over cold "
+                                        "weights, M=1024 on the 128 x 128-tile MFMA kernel" % GROUP, "per_shape": bf}
 
     if "fusion" in want:
         import torch.nn.functional as F

@@ -51,7 +51,7 @@
 extern "C" {
 #endif
 
-#define E0M4_ABI_VERSION 3
+#define E0M4_ABI_VERSION 4
 
 #define E0M4_OK              0
 #define E0M4_ERR_NULL      (-1)   /* a required pointer is NULL */
@@ -257,6 +257,43 @@ int e0m8_matmul_fused(const void* X_f16, int64_t M, const void* rms_gamma_f16, f
                       void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
 int e0m8_matmul(const void* X_f16, int64_t M, const void* codes, int64_t N, int64_t K, int group,
                 void* Y_f16, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * E0M3, the 3-bit member of the format family (paper: same closing remark).  The
+ * E0M4 definition with three code bits: code = min(fraction bits 9..7 of the
+ * mapped fp16 value + bit 6, 7), w1 = as_half(0x4000 | code << 7) = 2 + code/4,
+ * the bias keeps its three highest fraction bits.  Codes are stored in 4-bit
+ * slots of the E0M4 packed buffer (e0m4_codes_bytes), a code c as 2c -- the E0M4
+ * code with the same value -- so e0m4_dequant, e0m4_matmul, e0m4_matmul_fused and
+ * e0m4_matmul_static serve the buffer unchanged; the storage saving of a true
+ * 3-bit packing is not realised.  e0m3_unpack_codes writes the codes 0..7.
+ */
+int e0m3_quantize(const void* W_f16, int64_t N, int64_t K, int group,
+                  void* codes, void* scales_f16, void* bias_f16, void* stream);
+int e0m3_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* codes_u8_out, void* stream);
+
+/*
+ * E0M4 on bfloat16 (paper: same closing remark; the paper works the method out
+ * for FP16 only).  bfloat16 has 7 fraction bits, so the code sits in fraction
+ * bits 6..3: w1 = as_bfloat16(0x4000 | code << 3) = 2 + code/8, the same sixteen
+ * values; the top of the binade is 4 - 2^-6 (one unit in the last place below
+ * 4), rounding takes bit 2, the bias keeps bits 6..3, the scale lies between the
+ * smallest normal and the largest finite bfloat16.  W, scales, bias, X and Y
+ * are bfloat16 (16-bit patterns, round to nearest even); accumulation is fp32.
+ * `codes` has the E0M4 layout and size (e0m4_codes_bytes; e0m4_unpack_codes
+ * reads it), its embedded parameter words hold bfloat16 pairs.
+ *   e0m4_bf16_matmul: M <= 8 the decode kernel with bfloat16 dot products
+ *   (a shift and a mask-or per pair of codes), larger M an MFMA kernel with
+ *   128 x 128 tiles that dequantises into LDS; no workspace.
+ * Shape, pointer, stream and error rules as for the E0M4 entry points.
+ */
+int e0m4_bf16_quantize(const void* W_bf16, int64_t N, int64_t K, int group,
+                       void* codes, void* scales_bf16, void* bias_bf16, void* stream);
+int e0m4_bf16_encode(const void* W_bf16, int64_t N, int64_t K, int group,
+                     const void* scales_bf16, const void* bias_bf16, void* codes, void* stream);
+int e0m4_bf16_dequant(const void* codes, int64_t N, int64_t K, int group, void* W_bf16_out, void* stream);
+int e0m4_bf16_matmul(const void* X_bf16, int64_t M, const void* codes, int64_t N, int64_t K, int group,
+                     void* Y_bf16, void* stream);
 
 /*
  * INT4 twin (paper: section "Evaluation of FP4 quantization", Table 1 and

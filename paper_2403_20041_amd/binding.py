@@ -91,9 +91,18 @@ def lib() -> ctypes.CDLL:
     L.e0m4_int4_dequant.argtypes = [vp, i64, i64, ci, vp, vp]
     L.e0m4_int4_gemv.restype = ci
     L.e0m4_int4_gemv.argtypes = [vp, vp, i64, i64, ci, vp, vp]
+    for name in ("e0m3_quantize", "e0m4_bf16_quantize", "e0m4_bf16_encode"):
+        getattr(L, name).restype = ci
+        getattr(L, name).argtypes = [vp, i64, i64, ci, vp, vp, vp, vp]
+    L.e0m3_unpack_codes.restype = ci
+    L.e0m3_unpack_codes.argtypes = [vp, i64, i64, ci, vp, vp]
+    L.e0m4_bf16_dequant.restype = ci
+    L.e0m4_bf16_dequant.argtypes = [vp, i64, i64, ci, vp, vp]
+    L.e0m4_bf16_matmul.restype = ci
+    L.e0m4_bf16_matmul.argtypes = [vp, i64, vp, i64, i64, ci, vp, vp]
     L.e0m4_set_knob.restype = ci
     L.e0m4_set_knob.argtypes = [ctypes.c_char_p, ci]
-    if L.e0m4_abi_version() != 3:
+    if L.e0m4_abi_version() != 4:
         raise RuntimeError("libe0m4 ABI version mismatch")
     _lib = L
     return L
@@ -381,4 +390,64 @@ def e0m4_int4_gemv(X, codes, N: int, K: int, group: int, out=None, stream=None) 
         out = torch.empty((1, N), dtype=torch.float16, device=X.device)
     _need(out, torch.float16, (1, N), "out")
     _check(lib().e0m4_int4_gemv(_ptr(X), _ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m4_int4_gemv")
+    return out
+
+
+# ---- E0M3 (3-bit codes in 4-bit slots) and E0M4 on bfloat16 (see include/e0m4.h) -----------------
+
+def e0m3_quantize(W: torch.Tensor, group: int, stream=None):
+    """W [N,K] fp16 -> (codes, scales, bias); the buffer is read by e0m4_dequant / e0m4_matmul unchanged."""
+    N, K = W.shape
+    _need(W, torch.float16, (N, K), "W")
+    codes, scales, bias = alloc_packed(N, K, group, W.device)
+    _check(lib().e0m3_quantize(_ptr(W), N, K, group, _ptr(codes), _ptr(scales), _ptr(bias), _stream(stream)),
+           "e0m3_quantize")
+    return codes, scales, bias
+
+
+def e0m3_unpack_codes(codes, N: int, K: int, group: int, stream=None) -> torch.Tensor:
+    out = torch.empty((N, K), dtype=torch.uint8, device=codes.device)
+    _check(lib().e0m3_unpack_codes(_ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m3_unpack_codes")
+    return out
+
+
+def e0m4_bf16_quantize(W: torch.Tensor, group: int, stream=None):
+    """W [N,K] bfloat16 -> (codes, scales bf16 [N,K/G], bias bf16 [N,K/G])."""
+    N, K = W.shape
+    _need(W, torch.bfloat16, (N, K), "W")
+    codes = torch.empty(max(e0m4_codes_bytes(N, K, group), 16), dtype=torch.uint8, device=W.device)
+    scales = torch.empty((N, K // group), dtype=torch.bfloat16, device=W.device)
+    bias = torch.empty((N, K // group), dtype=torch.bfloat16, device=W.device)
+    _check(lib().e0m4_bf16_quantize(_ptr(W), N, K, group, _ptr(codes), _ptr(scales), _ptr(bias), _stream(stream)),
+           "e0m4_bf16_quantize")
+    return codes, scales, bias
+
+
+def e0m4_bf16_encode(W: torch.Tensor, scales: torch.Tensor, bias: torch.Tensor, group: int, stream=None):
+    N, K = W.shape
+    _need(W, torch.bfloat16, (N, K), "W")
+    _need(scales, torch.bfloat16, (N, K // group), "scales")
+    _need(bias, torch.bfloat16, (N, K // group), "bias")
+    codes = torch.empty(max(e0m4_codes_bytes(N, K, group), 16), dtype=torch.uint8, device=W.device)
+    _check(lib().e0m4_bf16_encode(_ptr(W), N, K, group, _ptr(scales), _ptr(bias), _ptr(codes), _stream(stream)),
+           "e0m4_bf16_encode")
+    return codes
+
+
+def e0m4_bf16_dequant(codes, N: int, K: int, group: int, out=None, stream=None) -> torch.Tensor:
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.bfloat16, device=codes.device)
+    _need(out, torch.bfloat16, (N, K), "out")
+    _check(lib().e0m4_bf16_dequant(_ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m4_bf16_dequant")
+    return out
+
+
+def e0m4_bf16_matmul(X, codes, N: int, K: int, group: int, out=None, stream=None) -> torch.Tensor:
+    """Y [M,N] bfloat16 = X [M,K] bfloat16 times the dequantised weights, transposed."""
+    M = X.shape[0]
+    _need(X, torch.bfloat16, (M, K), "X")
+    if out is None:
+        out = _empty((M, N), torch.bfloat16, X.device, stream, "out")
+    _need(out, torch.bfloat16, (M, N), "out")
+    _check(lib().e0m4_bf16_matmul(_ptr(X), M, _ptr(codes), N, K, group, _ptr(out), _stream(stream)), "e0m4_bf16_matmul")
     return out

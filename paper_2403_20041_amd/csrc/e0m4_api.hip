@@ -207,7 +207,7 @@ int e0m4_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, v
     if (N == 0 || K == 0) return E0M4_OK;
     if (!W || !codes || !scales || !bias) return E0M4_ERR_NULL;
     if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
-    return launch_quantize(W, N, K, group, codes, scales, bias, nullptr, nullptr, true, false, (hipStream_t)stream);
+    return launch_quantize(W, N, K, group, codes, scales, bias, nullptr, nullptr, true, kFormatE0M4, (hipStream_t)stream);
 }
 
 int e0m4_encode(const void* W, int64_t N, int64_t K, int group, const void* scales, const void* bias, void* codes,
@@ -218,7 +218,7 @@ int e0m4_encode(const void* W, int64_t N, int64_t K, int group, const void* scal
     if (N == 0 || K == 0) return E0M4_OK;
     if (!W || !codes || !scales || !bias) return E0M4_ERR_NULL;
     if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
-    return launch_quantize(W, N, K, group, codes, nullptr, nullptr, scales, bias, false, false, (hipStream_t)stream);
+    return launch_quantize(W, N, K, group, codes, nullptr, nullptr, scales, bias, false, kFormatE0M4, (hipStream_t)stream);
 }
 
 int e0m4_dequant(const void* codes, const void* scales, const void* bias, int64_t N, int64_t K, int group, void* W_out,
@@ -230,7 +230,7 @@ int e0m4_dequant(const void* codes, const void* scales, const void* bias, int64_
     if (N == 0 || K == 0) return E0M4_OK;
     if (!W_out || !codes) return E0M4_ERR_NULL;
     if (!aligned16(W_out) || !aligned16(codes)) return E0M4_ERR_ALIGN;
-    return launch_dequant(codes, N, K, group, W_out, false, (hipStream_t)stream);
+    return launch_dequant(codes, N, K, group, W_out, kFormatE0M4, (hipStream_t)stream);
 }
 
 int e0m4_int4_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, void* scales, void* zeros,
@@ -241,7 +241,7 @@ int e0m4_int4_quantize(const void* W, int64_t N, int64_t K, int group, void* cod
     if (N == 0 || K == 0) return E0M4_OK;
     if (!W || !codes || !scales || !zeros) return E0M4_ERR_NULL;
     if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(zeros)) return E0M4_ERR_ALIGN;
-    return launch_quantize(W, N, K, group, codes, scales, zeros, nullptr, nullptr, true, true, (hipStream_t)stream);
+    return launch_quantize(W, N, K, group, codes, scales, zeros, nullptr, nullptr, true, kFormatInt4, (hipStream_t)stream);
 }
 
 int e0m4_int4_dequant(const void* codes, int64_t N, int64_t K, int group, void* W_out, void* stream)
@@ -251,7 +251,7 @@ int e0m4_int4_dequant(const void* codes, int64_t N, int64_t K, int group, void* 
     if (N == 0 || K == 0) return E0M4_OK;
     if (!W_out || !codes) return E0M4_ERR_NULL;
     if (!aligned16(W_out) || !aligned16(codes)) return E0M4_ERR_ALIGN;
-    return launch_dequant(codes, N, K, group, W_out, true, (hipStream_t)stream);
+    return launch_dequant(codes, N, K, group, W_out, kFormatInt4, (hipStream_t)stream);
 }
 
 int e0m4_int4_gemv(const void* X, const void* codes, int64_t N, int64_t K, int group, void* Y, void* stream)
@@ -377,6 +377,81 @@ int e0m4_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
     }
     return launch_gemm_fused(f, x, M, codes, N, K, group, Y, static_cast<char*>(workspace) + nb,
                              workspace_bytes - nb, st);
+}
+
+// ---- E0M3: the 3-bit member of the family, stored in 4-bit slots ---------------------------------------
+int e0m3_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, void* scales, void* bias, void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!W || !codes || !scales || !bias) return E0M4_ERR_NULL;
+    if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
+    return launch_quantize(W, N, K, group, codes, scales, bias, nullptr, nullptr, true, kFormatE0M3, (hipStream_t)stream);
+}
+
+int e0m3_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* out, void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!codes || !out) return E0M4_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(out)) return E0M4_ERR_ALIGN;
+    return launch_unpack(codes, N, K, group, out, (hipStream_t)stream, 1);
+}
+
+// ---- E0M4 on bfloat16 ----------------------------------------------------------------------------------
+int e0m4_bf16_quantize(const void* W, int64_t N, int64_t K, int group, void* codes, void* scales, void* bias,
+                       void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!W || !codes || !scales || !bias) return E0M4_ERR_NULL;
+    if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
+    return launch_quantize(W, N, K, group, codes, scales, bias, nullptr, nullptr, true, kFormatBf16, (hipStream_t)stream);
+}
+
+int e0m4_bf16_encode(const void* W, int64_t N, int64_t K, int group, const void* scales, const void* bias, void* codes,
+                     void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!W || !codes || !scales || !bias) return E0M4_ERR_NULL;
+    if (!aligned16(W) || !aligned16(codes) || !aligned16(scales) || !aligned16(bias)) return E0M4_ERR_ALIGN;
+    return launch_quantize(W, N, K, group, codes, nullptr, nullptr, scales, bias, false, kFormatBf16, (hipStream_t)stream);
+}
+
+int e0m4_bf16_dequant(const void* codes, int64_t N, int64_t K, int group, void* W_out, void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (N == 0 || K == 0) return E0M4_OK;
+    if (!W_out || !codes) return E0M4_ERR_NULL;
+    if (!aligned16(W_out) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    return launch_dequant(codes, N, K, group, W_out, kFormatBf16, (hipStream_t)stream);
+}
+
+int e0m4_bf16_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t K, int group, void* Y, void* stream)
+{
+    int rc = check_shape(N, K, group);
+    if (rc != E0M4_OK) return rc;
+    if (M < 0 || M > (int64_t)1 << 31) return E0M4_ERR_SHAPE;
+    if (M == 0 || N == 0) return E0M4_OK;
+    if (!Y) return E0M4_ERR_NULL;
+    if (!aligned16(Y)) return E0M4_ERR_ALIGN;
+    if (K == 0) {                                   // empty contraction: Y = +0 (the same bits in both formats)
+        const int64_t total = M * N;
+        hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                           static_cast<half_t*>(Y), total);
+        return check_launch();
+    }
+    if (!X || !codes) return E0M4_ERR_NULL;
+    if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    if (M <= kGemvMaxM) return launch_gemv_bf16(X, M, codes, N, K, group, Y, (hipStream_t)stream);
+    if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // 32-bit offsets in the GEMM epilogue
+    return launch_gemm_bf16(X, M, codes, N, K, group, Y, (hipStream_t)stream);
 }
 
 // ---- E0M8: the 8-bit member of the format family ------------------------------------------------------

@@ -52,7 +52,17 @@ struct TileFusion {
     int64_t n_half;                                     // N / 2 (gated epilogue)
 };
 
-template <int G, int BM, int BN, bool FUSED>
+// BF: E0M4 on bfloat16 (X, the embedded parameters and Y are bfloat16; the same packed codes).  A code's value
+// 2 + c/8 is taken from the fp16 pattern, the affine map runs in fp32 (difference and product exact) and is
+// rounded once to bfloat16, the bits e0m4_bf16_dequant produces; the MFMA is the bfloat16 one.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+__device__ inline uint32_t bf16_pair_bits(float lo, float hi)     // two fp32 -> two bfloat16, round to nearest even
+{
+    const uint32_t a = __builtin_bit_cast(uint32_t, lo), b = __builtin_bit_cast(uint32_t, hi);
+    return ((a + 0x7FFFu + ((a >> 16) & 1u)) >> 16) | ((b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u);
+}
+
+template <int G, int BM, int BN, bool FUSED, bool BF = false>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict__ X, int64_t M,
                                                         const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                         half_t* __restrict__ Y, int m_tiles, int n_tiles, TileFusion fu)
@@ -143,6 +153,22 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
             const half2_t s2 = {sc, sc}, b2 = {bi, bi};
             const uint32_t words[4] = {b_reg[p].x, b_reg[p].y, b_reg[p].z, b_reg[p].w};
             const int row = (b_hb + 8 * p) * kBlockRows + b_r;
+            if (BF) {
+                const float sf = __builtin_bit_cast(float, pw_reg[p] << 16);
+                const float bf = __builtin_bit_cast(float, pw_reg[p] & 0xFFFF0000u);
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const half2_t q[4] = {w1_pair<0>(words[w], fmask), w1_pair<1>(words[w], fmask),
+                                          w1_pair<2>(words[w], fmask), w1_pair<3>(words[w], fmask)};
+                    uint4 o;
+                    o.x = bf16_pair_bits(((float)q[0][0] - bf) * sf, ((float)q[0][1] - bf) * sf);
+                    o.y = bf16_pair_bits(((float)q[1][0] - bf) * sf, ((float)q[1][1] - bf) * sf);
+                    o.z = bf16_pair_bits(((float)q[2][0] - bf) * sf, ((float)q[2][1] - bf) * sf);
+                    o.w = bf16_pair_bits(((float)q[3][0] - bf) * sf, ((float)q[3][1] - bf) * sf);
+                    *reinterpret_cast<uint4*>(stage + A_BYTES + tile_off(row, b_q * 4 + w)) = o;
+                }
+                continue;
+            }
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 half2_t o[4];
@@ -180,8 +206,13 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TN; ++j) {
+                    if (BF)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a[i]),
+                                                                            __builtin_bit_cast(bf16x8_t, b[j]), acc[i][j], 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+                }
         }
     };
 
@@ -254,13 +285,17 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const half_t* __restrict
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int dr = 32 * i + 8 * (r >> 2) + (r & 3);       // compile-time row step
-                    if (row0 + dr < rows_left) Yt[off0 + (uint32_t)dr * n32 + 32 * j] = (half_t)acc[i][j][r];
+                    if (row0 + dr < rows_left) {
+                        const float v = acc[i][j][r];
+                        Yt[off0 + (uint32_t)dr * n32 + 32 * j] =
+                            BF ? __builtin_bit_cast(half_t, (uint16_t)bf16_pair_bits(v, 0.f)) : (half_t)v;
+                    }
                 }
         }
     }
 }
 
-template <int G, int BM, int BN, bool FUSED>
+template <int G, int BM, int BN, bool FUSED, bool BF = false>
 int launch_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream,
                 const Fusion& f = Fusion{})
 {
@@ -275,9 +310,9 @@ int launch_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
     constexpr size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
     static std::atomic<uint64_t> lds_allowed{0};        // LDS above the default 64 KiB limit must be requested
-    const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_kernel<G, BM, BN, FUSED>), (int)lds, lds_allowed);
+    const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_kernel<G, BM, BN, FUSED, BF>), (int)lds, lds_allowed);
     if (arc != E0M4_OK) return arc;
-    hipLaunchKernelGGL((gemm_kernel<G, BM, BN, FUSED>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(kThreads), lds, stream,
+    hipLaunchKernelGGL((gemm_kernel<G, BM, BN, FUSED, BF>), dim3((unsigned)(per_xcd * kNumXcd)), dim3(kThreads), lds, stream,
                        x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, fu);
     return check_launch();
 }
@@ -309,6 +344,21 @@ int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t
         case 32: return launch_tile<32, 128, 128, false>(x, M, c, N, K, y, stream);
         case 64: return launch_tile<64, 128, 128, false>(x, M, c, N, K, y, stream);
         case 128: return launch_tile<128, 128, 128, false>(x, M, c, N, K, y, stream);
+        default: return E0M4_ERR_GROUP;
+    }
+}
+
+// E0M4 on bfloat16, any M: the small-tile kernel with the bfloat16 operand path (no K split, no workspace).
+int launch_gemm_bf16(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                     hipStream_t stream)
+{
+    const half_t* x = static_cast<const half_t*>(X);
+    const uint4* c = static_cast<const uint4*>(packed);
+    half_t* y = static_cast<half_t*>(Y);
+    switch (group) {
+        case 32: return launch_tile<32, 128, 128, false, true>(x, M, c, N, K, y, stream);
+        case 64: return launch_tile<64, 128, 128, false, true>(x, M, c, N, K, y, stream);
+        case 128: return launch_tile<128, 128, 128, false, true>(x, M, c, N, K, y, stream);
         default: return E0M4_ERR_GROUP;
     }
 }

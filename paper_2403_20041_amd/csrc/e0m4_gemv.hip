@@ -128,7 +128,29 @@ GemvPlan make_plan(int64_t M, int64_t N, int64_t K, int unit = 1, bool* single_s
 // kDeqE0M8 is the 8-bit member of the format family (e0m8_pack.hip): a block holds 64 weights, a lane's
 // chunk 16, a 32-bit word four codes that one mask-or (and one more after a rotation) turns into two pairs
 // of binade values, so the dot product needs no folding of pair kinds.
-enum { kDeqE0M4 = 0, kDeqInt4Convert = 1, kDeqE0M8 = 2 };
+// kDeqBf16 is E0M4 on bfloat16: the same packed codes; activations, parameters and the output are bfloat16, a
+// code becomes the bfloat16 value 2 + c/8 with one shift and one mask-or (code bits 6..3 of each half), and the
+// dot products are v_dot2_f32_bf16.
+enum { kDeqE0M4 = 0, kDeqInt4Convert = 1, kDeqE0M8 = 2, kDeqBf16 = 3 };
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+constexpr uint32_t kBf16CodeMask2 = 0x00780078u;       // fraction bits 6..3 of both bfloat16 halves
+constexpr uint32_t kBf16Ones2 = 0x3F803F80u;           // (1.0, 1.0)
+__device__ inline bf16x2_t as_bf16x2(uint32_t v) { return __builtin_bit_cast(bf16x2_t, v); }
+__device__ inline float bf16_lo(uint32_t word) { return __builtin_bit_cast(float, word << 16); }
+__device__ inline float bf16_hi(uint32_t word) { return __builtin_bit_cast(float, word & 0xFFFF0000u); }
+// fp32 -> bfloat16 bits, round to nearest even (finite values)
+__device__ inline uint16_t bf16_bits(float f)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, f);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+template <int DEQ>
+__device__ inline half_t out_value(float s)
+{
+    if (DEQ == kDeqBf16) return __builtin_bit_cast(half_t, bf16_bits(s));
+    return (half_t)s;
+}
 
 // FUSED adds the operators of GemvFusion (e0m4_device.h) to the kernel.
 // XREG (M = 1, one segment, wavefront count a multiple of the work items per row block): a wavefront meets
@@ -216,6 +238,14 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
     // the two sums of one piece (a piece is the k range of one code word: elements 2..5 meet the code
     // pairs that are read at 1/128 scale)
     auto piece_sums = [&](const half8_t& v, float& s, float& sl) {
+        if (DEQ == kDeqBf16) {                          // one plain sum of the eight bfloat16 values
+            const uint4 u = __builtin_bit_cast(uint4, v);
+            s = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(u.x), as_bf16x2(kBf16Ones2), s, false);
+            s = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(u.y), as_bf16x2(kBf16Ones2), s, false);
+            s = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(u.z), as_bf16x2(kBf16Ones2), s, false);
+            s = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(u.w), as_bf16x2(kBf16Ones2), s, false);
+            return;
+        }
         const half2_t ones = {(half_t)1.f, (half_t)1.f};
         const half2_t x0 = {v[0], v[1]}, x1 = {v[2], v[3]}, x2 = {v[4], v[5]}, x3 = {v[6], v[7]};
         sl = __builtin_amdgcn_fdot2(x1, ones, sl, false);
@@ -446,8 +476,8 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
             fetch_params(nslot, nitem);
 #pragma unroll
             for (int j = 0; j < kSuper; ++j) {
-                const float sc = (float)param_scale(pwj[j]);
-                const float bi = (float)param_bias(pwj[j]);
+                const float sc = DEQ == kDeqBf16 ? bf16_lo(pwj[j]) : (float)param_scale(pwj[j]);
+                const float bi = DEQ == kDeqBf16 ? bf16_hi(pwj[j]) : (float)param_bias(pwj[j]);
                 const uint32_t words[4] = {c[j].x, c[j].y, c[j].z, c[j].w};
                 const int xoff = ((si - seg0) * kSuper + j) * BLK_K + q * CHUNK;
                 float a[M][2];      // per row of X: sum x*(2 + c/8) over code pairs 0 and 3, sum x*(2 + c/128) over 1 and 2
@@ -474,6 +504,23 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
                         }
                         continue;
                     }
+                    if (DEQ == kDeqBf16) {              // four shifts, four mask-or, four dot instructions per word
+                        const uint32_t wd = words[w];
+                        const uint32_t b0 = ((wd >> 3) & kBf16CodeMask2) | kExpBits2;
+                        const uint32_t b1 = ((wd << 1) & kBf16CodeMask2) | kExpBits2;
+                        const uint32_t b2 = ((wd >> 7) & kBf16CodeMask2) | kExpBits2;
+                        const uint32_t b3 = (__builtin_amdgcn_alignbit(wd, wd, 11) & kBf16CodeMask2) | kExpBits2;
+#pragma unroll
+                        for (int m = 0; m < M; ++m) {
+                            const half8_t xv = XREG ? xr[XREG ? j : 0][w] : *reinterpret_cast<const half8_t*>(&xs[m * seg_k + xoff + 8 * w]);
+                            const uint4 xu = __builtin_bit_cast(uint4, xv);
+                            a[m][0] = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(b0), as_bf16x2(xu.x), a[m][0], false);
+                            a[m][0] = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(b1), as_bf16x2(xu.y), a[m][0], false);
+                            a[m][0] = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(b2), as_bf16x2(xu.z), a[m][0], false);
+                            a[m][0] = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(b3), as_bf16x2(xu.w), a[m][0], false);
+                        }
+                        continue;
+                    }
                     half2_t p[4];
                     if (DEQ == kDeqInt4Convert) {
 #pragma unroll
@@ -497,7 +544,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
                     const float2 sx = XREG ? sxr[XREG ? j : 0] : sxs[m * (seg_k / CHUNK) + xoff / CHUNK];
-                    if (DEQ == kDeqE0M8)                // y += scale * (sum x*w1 - bias * sum x)
+                    if (DEQ == kDeqE0M8 || DEQ == kDeqBf16)     // y += scale * (sum x*w1 - bias * sum x)
                         acc[m] += sc * (a[m][0] - bi * sx.x);
                     else if (DEQ == kDeqInt4Convert)    // y += scale * (sum x*q - zero * sum x)
                         acc[m] += sc * ((a[m][0] + a[m][1]) - bi * sx.x);
@@ -543,7 +590,7 @@ __global__ __launch_bounds__(W * 64) void gemv_kernel(const half_t* __restrict__
 #pragma unroll
         for (int w = 0; w < W; ++w) s += red[((sl * W + w) * M + m) * kBlockRows + rr];
         const int64_t n = (rb0 + sl) * kBlockRows + rr;
-        if (n < N) Y[(int64_t)m * N + n] = (half_t)s;
+        if (n < N) Y[(int64_t)m * N + n] = out_value<DEQ>(s);
     }
 }
 
@@ -721,6 +768,48 @@ int launch_gemv8_fused(const Fusion& f, const void* X, int64_t M, const void* pa
     if (f.swiglu && gated_half_bytes(N, 2 * K, 128) > kMaxHalfBytes) return E0M4_ERR_SHAPE;
     return launch_gemv8_m<true>(make_plan(M, N, 2 * K, f.swiglu ? 2 : 1), make_gemv_fusion(f, N, 2 * K, 128), X, M, packed,
                                 N, K, Y, stream);
+}
+
+// E0M4 on bfloat16, M <= 8: X, the embedded parameters and Y are bfloat16.
+namespace {
+template <int G>
+int launch_bf16_m(const GemvPlan& p, int64_t M, const void* X, const void* packed, int64_t N, int64_t K, void* Y,
+                  hipStream_t stream)
+{
+    auto go = [&](auto m_tag) -> int {
+        constexpr int MM = decltype(m_tag)::value;
+        switch (p.waves) {
+            case 4: return launch_one<G, MM, 4, kDeqBf16>(p, X, packed, N, K, Y, stream);
+            case 8: return launch_one<G, MM, 8, kDeqBf16>(p, X, packed, N, K, Y, stream);
+            default:
+                if constexpr (MM <= 4) return launch_one<G, MM, 16, kDeqBf16>(p, X, packed, N, K, Y, stream);
+                else return E0M4_ERR_SHAPE;
+        }
+    };
+    switch (M) {
+        case 1: return go(std::integral_constant<int, 1>{});
+        case 2: return go(std::integral_constant<int, 2>{});
+        case 3: return go(std::integral_constant<int, 3>{});
+        case 4: return go(std::integral_constant<int, 4>{});
+        case 5: return go(std::integral_constant<int, 5>{});
+        case 6: return go(std::integral_constant<int, 6>{});
+        case 7: return go(std::integral_constant<int, 7>{});
+        case 8: return go(std::integral_constant<int, 8>{});
+        default: return E0M4_ERR_SHAPE;
+    }
+}
+}  // namespace
+
+int launch_gemv_bf16(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                     hipStream_t stream)
+{
+    const GemvPlan p = make_plan(M, N, K);
+    switch (group) {
+        case 32: return launch_bf16_m<32>(p, M, X, packed, N, K, Y, stream);
+        case 64: return launch_bf16_m<64>(p, M, X, packed, N, K, Y, stream);
+        case 128: return launch_bf16_m<128>(p, M, X, packed, N, K, Y, stream);
+        default: return E0M4_ERR_GROUP;
+    }
 }
 
 int launch_gemv_int4(const void* X, const void* packed, int64_t N, int64_t K, int group, void* Y, hipStream_t stream)

@@ -47,10 +47,14 @@ struct GemvFusion;
 // Device view of `f` for the decode kernels (defined in e0m4_gemv.hip).
 GemvFusion make_gemv_fusion(const Fusion& f, int64_t N, int64_t K, int group);
 
+// `format`: 0 E0M4, 1 the INT4 comparison format, 2 E0M3 (codes stored as the E0M4 codes of the same values),
+// 3 E0M4 on bfloat16 (W, scales and bias are bfloat16 bit patterns).
+enum { kFormatE0M4 = 0, kFormatInt4 = 1, kFormatE0M3 = 2, kFormatBf16 = 3 };
 int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed, void* scales, void* bias,
-                    const void* scales_in, const void* bias_in, bool fit, bool int4, hipStream_t stream);
-int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, bool int4, hipStream_t stream);
-int launch_unpack(const void* packed, int64_t N, int64_t K, int group, void* out, hipStream_t stream);
+                    const void* scales_in, const void* bias_in, bool fit, int format, hipStream_t stream);
+int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, int format, hipStream_t stream);
+// codes_u8[n,k] = stored 4-bit code >> shift (shift 1 for 3-bit codes, which are stored doubled)
+int launch_unpack(const void* packed, int64_t N, int64_t K, int group, void* out, hipStream_t stream, int shift = 0);
 
 // Small-M path (M <= kGemvMaxM).
 constexpr int kGemvMaxM = 8;
@@ -73,6 +77,12 @@ int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void
 // INT4 twin of the M = 1 kernel: same layout and work decomposition, codes turned into numbers with
 // integer-to-float conversion instructions.
 int launch_gemv_int4(const void* X, const void* packed, int64_t N, int64_t K, int group, void* Y, hipStream_t stream);
+
+// E0M4 on bfloat16: decode kernel (M <= 8) and small-tile MFMA kernel (any M); no workspace.
+int launch_gemv_bf16(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                     hipStream_t stream);
+int launch_gemm_bf16(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                     hipStream_t stream);
 
 // MFMA path.
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,

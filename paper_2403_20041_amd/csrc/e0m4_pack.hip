@@ -50,7 +50,44 @@ __device__ inline uint32_t encode_value_int4(float w0, float sf, float zf)
     return (uint32_t)t;
 }
 
-enum Format { kE0M4 = 0, kInt4 = 1 };
+// kE0M3: the 3-bit member of the family (the E0M4 definition with three code bits: code = min(fraction bits
+// 9..7 + bit 6, 7), bias truncated to three fraction bits); a code c is stored in a 4-bit slot as 2c, which
+// is the E0M4 code with the same value 2 + c/4, so every kernel that reads E0M4 codes reads these unchanged.
+// kBf16: the same construction on bfloat16 (7 fraction bits: code = min(bits 6..3 + bit 2, 15), top of the
+// binade 4 - 2^-6, bias truncated to bits 6..3; weights, scale and bias are bfloat16 bit patterns).
+enum Format { kE0M4 = 0, kInt4 = 1, kE0M3 = 2, kBf16 = 3 };
+
+constexpr float kHiBf16 = 3.984375f;            // 4 - 2^-6, bits 0x407F
+constexpr float kSpanBf16 = 1.984375f;
+constexpr float kMinScaleBf16 = 1.17549435e-38f;            // 2^-126, smallest normal bfloat16
+constexpr float kMaxScaleBf16 = 3.3895313892515355e38f;     // largest finite bfloat16, bits 0x7F7F
+
+__device__ inline float bf16_bits_to_float(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
+// round to nearest even; the argument is finite here
+__device__ inline uint16_t float_to_bf16_bits(float f)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, f);
+    return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+// The general form of encode_value: CODE_SHIFT = fraction bits below the code, TOP = largest code.
+template <int FMT>
+__device__ inline uint32_t encode_value_fmt(float w0, float sf, float bf)
+{
+    constexpr bool BF = FMT == kBf16;
+    constexpr int SHIFT = BF ? 3 : (FMT == kE0M3 ? 7 : 6);
+    constexpr uint32_t TOP = FMT == kE0M3 ? 7u : 15u;
+    const float hi = BF ? kHiBf16 : kHi;
+    float q = w0 / sf;
+    float t = q + bf;
+    t = t < kLo ? kLo : t;
+    t = t > hi ? hi : t;
+    const uint32_t bits = BF ? (uint32_t)float_to_bf16_bits(t) : (uint32_t)half_bits((half_t)t);
+    const uint32_t y1 = (bits >> SHIFT) & TOP;
+    const uint32_t y2 = (bits >> (SHIFT - 1)) & 1u;
+    const uint32_t c = y1 + y2;
+    return c > TOP ? TOP : c;
+}
 
 // Thread t owns the 8-weight piece t%16 of row (t/16) of row block i, i = 0..3,
 // so 16 consecutive lanes read 256 contiguous bytes of one row and a group of G
@@ -83,12 +120,13 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __rest
         const bool ok = k_ok && n < N;
         half8_t v8 = {0, 0, 0, 0, 0, 0, 0, 0};
         if (ok) v8 = *reinterpret_cast<const half8_t*>(W + n * K + k);
+        constexpr bool BF = FMT == kBf16;               // bfloat16 bit patterns in W, scales and bias
         float v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = (float)v8[j];
+        for (int j = 0; j < 8; ++j) v[j] = BF ? bf16_bits_to_float(half_bits(v8[j])) : (float)v8[j];
 
         float sf, bf;
-        half_t sh, bh;
+        half_t sh, bh;                                  // 16-bit patterns of the group's parameters (fp16, or bfloat16)
         if (FIT) {
             float mn = 0.0f, mx = 0.0f;                 // the range always contains 0
 #pragma unroll
@@ -102,13 +140,18 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __rest
                 mx = fmaxf(mx, __shfl_xor(mx, d));
             }
             float range = mx - mn;
-            float s = range / (FMT == kInt4 ? 15.0f : kSpan);
-            s = s < kMinScale ? kMinScale : s;
-            s = s > kMaxScale ? kMaxScale : s;
-            sh = (half_t)s;
-            sf = (float)sh;                             // encode with the stored scale
+            float s = range / (FMT == kInt4 ? 15.0f : (BF ? kSpanBf16 : kSpan));
+            s = s < (BF ? kMinScaleBf16 : kMinScale) ? (BF ? kMinScaleBf16 : kMinScale) : s;
+            s = s > (BF ? kMaxScaleBf16 : kMaxScale) ? (BF ? kMaxScaleBf16 : kMaxScale) : s;
+            sh = BF ? bits_half(float_to_bf16_bits(s)) : (half_t)s;
+            sf = BF ? bf16_bits_to_float(half_bits(sh)) : (float)sh;     // encode with the stored scale
             float q = mn / sf;
-            if (FMT == kInt4) {
+            if (BF) {
+                float b = kLo - q;
+                b = b < kLo ? kLo : b;
+                b = b > kHiBf16 ? kHiBf16 : b;
+                bh = bits_half(float_to_bf16_bits(b) & 0xFFF8u);          // keep fraction bits 6..3
+            } else if (FMT == kInt4) {
                 float z = rintf(-q);                    // integer zero point, round half to even
                 z = z < 0.0f ? 0.0f : z;
                 z = z > 15.0f ? 15.0f : z;
@@ -117,29 +160,36 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const half_t* __rest
                 float b = kLo - q;                      // image of zero in the binade
                 b = b < kLo ? kLo : b;
                 b = b > kHi ? kHi : b;
-                bh = bits_half(half_bits((half_t)b) & 0xFFC0u);   // keep the four highest fraction bits
+                // keep the four (three) highest fraction bits
+                bh = bits_half(half_bits((half_t)b) & (FMT == kE0M3 ? 0xFF80u : 0xFFC0u));
             }
-            bf = (float)bh;
+            bf = BF ? bf16_bits_to_float(half_bits(bh)) : (float)bh;
             if (ok && (piece % (G / 8)) == 0) {
                 scales_out[n * ng + g] = sh;
                 bias_out[n * ng + g] = bh;
             }
         } else {
-            sh = (half_t)1.0f;
-            bh = (half_t)kLo;
+            sh = BF ? bits_half(0x3F80u) : (half_t)1.0f;
+            bh = bits_half(0x4000u);                    // 2.0 in both formats
             if (ok) {
                 sh = scales_in[n * ng + g];
                 bh = bias_in[n * ng + g];
             }
-            sf = (float)sh;
-            bf = (float)bh;
+            sf = BF ? bf16_bits_to_float(half_bits(sh)) : (float)sh;
+            bf = BF ? bf16_bits_to_float(half_bits(bh)) : (float)bh;
         }
 
         uint32_t word = 0;
         if (ok) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                word |= place_code(FMT == kInt4 ? encode_value_int4(v[j], sf, bf) : encode_value(v[j], sf, bf), j);
+            for (int j = 0; j < 8; ++j) {
+                uint32_t c;
+                if (FMT == kInt4) c = encode_value_int4(v[j], sf, bf);
+                else if (FMT == kE0M4) c = encode_value(v[j], sf, bf);
+                else if (FMT == kE0M3) c = encode_value_fmt<kE0M3>(v[j], sf, bf) << 1;      // the E0M4 code of the same value
+                else c = encode_value_fmt<kBf16>(v[j], sf, bf);
+                word |= place_code(c, j);
+            }
         }
         stage[i * BW + ((piece >> 2) * kBlockRows + r) * 4 + (piece & 3)] = word;
         if ((piece % (G / 8)) == 0) {
@@ -182,8 +232,8 @@ __global__ __launch_bounds__(kThreads) void dequant_kernel(const uint4* __restri
         if (rb < nrb) {
             const uint4 c = packed[lay.code_index(rb, kb) + lane];
             const uint32_t pw = reinterpret_cast<const uint32_t*>(packed)[lay.param_index(rb, kb) + lay.param_slot(q, r)];
-            const float sf = (float)param_scale(pw);
-            const float bf = (float)param_bias(pw);
+            const float sf = FMT == kBf16 ? bf16_bits_to_float((uint16_t)(pw & 0xFFFFu)) : (float)param_scale(pw);
+            const float bf = FMT == kBf16 ? bf16_bits_to_float((uint16_t)(pw >> 16)) : (float)param_bias(pw);
             const uint32_t words[4] = {c.x, c.y, c.z, c.w};
             const uint32_t fmask = frac_mask_vgpr();
 #pragma unroll
@@ -197,6 +247,10 @@ __global__ __launch_bounds__(kThreads) void dequant_kernel(const uint4* __restri
                         // (q - zero) is an exact small integer, its product with the scale exact in fp32
                         o[2 * j] = (half_t)(((float)extract_code(words[w], 2 * j) - bf) * sf);
                         o[2 * j + 1] = (half_t)(((float)extract_code(words[w], 2 * j + 1) - bf) * sf);
+                    } else if (FMT == kBf16) {
+                        // w1 = 2 + code/8 whatever the format; difference and product exact in fp32, one rounding
+                        o[2 * j] = bits_half(float_to_bf16_bits(((float)p[j][0] - bf) * sf));
+                        o[2 * j + 1] = bits_half(float_to_bf16_bits(((float)p[j][1] - bf) * sf));
                     } else {
                         // (w1 - bias) is exact and its product with the scale is exact in fp32: one rounding
                         o[2 * j] = (half_t)(((float)p[j][0] - bf) * sf);
@@ -221,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void dequant_kernel(const uint4* __restri
 
 template <int G>
 __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint4* __restrict__ packed, int64_t N, int64_t K,
-                                                          uint8_t* __restrict__ out)
+                                                          uint8_t* __restrict__ out, int shift)
 {
     constexpr int kStride = kBlockK + 16;               // bytes per row in LDS
     __shared__ __attribute__((aligned(16))) uint8_t tile[kTileRows * kStride];
@@ -242,8 +296,8 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint4* __restric
                 uint32_t lo = 0, hi = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    lo |= extract_code(words[w], j) << (8 * j);
-                    hi |= extract_code(words[w], j + 4) << (8 * j);
+                    lo |= (extract_code(words[w], j) >> shift) << (8 * j);       // shift 1: 3-bit codes stored doubled
+                    hi |= (extract_code(words[w], j + 4) >> shift) << (8 * j);
                 }
                 *reinterpret_cast<uint2*>(&tile[(16 * i + r) * kStride + q * 32 + w * 8]) = make_uint2(lo, hi);
             }
@@ -269,8 +323,9 @@ dim3 tile_grid(int64_t N, int64_t K)
 }  // namespace
 
 int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed, void* scales, void* bias,
-                    const void* scales_in, const void* bias_in, bool fit, bool int4, hipStream_t stream)
+                    const void* scales_in, const void* bias_in, bool fit, int format, hipStream_t stream)
 {
+    const bool int4 = format == kInt4;
     const dim3 grid = tile_grid(N, K), block(kThreads);
     const half_t* w = static_cast<const half_t*>(W);
     uint4* c = static_cast<uint4*>(packed);
@@ -281,6 +336,9 @@ int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed
 #define E0M4_LAUNCH_Q(G)                                                                              \
     do {                                                                                              \
         if (int4) hipLaunchKernelGGL((quantize_kernel<G, true, kInt4>), grid, block, 0, stream, w, N, K, c, so, bo, si, bi); \
+        else if (format == kE0M3) hipLaunchKernelGGL((quantize_kernel<G, true, kE0M3>), grid, block, 0, stream, w, N, K, c, so, bo, si, bi); \
+        else if (format == kBf16 && fit) hipLaunchKernelGGL((quantize_kernel<G, true, kBf16>), grid, block, 0, stream, w, N, K, c, so, bo, si, bi); \
+        else if (format == kBf16) hipLaunchKernelGGL((quantize_kernel<G, false, kBf16>), grid, block, 0, stream, w, N, K, c, so, bo, si, bi); \
         else if (fit) hipLaunchKernelGGL((quantize_kernel<G, true>), grid, block, 0, stream, w, N, K, c, so, bo, si, bi); \
         else hipLaunchKernelGGL((quantize_kernel<G, false>), grid, block, 0, stream, w, N, K, c, so, bo, si, bi);    \
     } while (0)
@@ -294,11 +352,21 @@ int launch_quantize(const void* W, int64_t N, int64_t K, int group, void* packed
     return check_launch();
 }
 
-int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, bool int4, hipStream_t stream)
+int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_out, int format, hipStream_t stream)
 {
     const dim3 grid = tile_grid(N, K), block(kThreads);
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* o = static_cast<half_t*>(W_out);
+    const bool int4 = format == kInt4;
+    if (format == kBf16) {
+        switch (group) {
+            case 32: hipLaunchKernelGGL((dequant_kernel<32, kBf16>), grid, block, 0, stream, c, N, K, o); break;
+            case 64: hipLaunchKernelGGL((dequant_kernel<64, kBf16>), grid, block, 0, stream, c, N, K, o); break;
+            case 128: hipLaunchKernelGGL((dequant_kernel<128, kBf16>), grid, block, 0, stream, c, N, K, o); break;
+            default: return E0M4_ERR_GROUP;
+        }
+        return check_launch();
+    }
     if (int4) {
         switch (group) {
             case 32: hipLaunchKernelGGL((dequant_kernel<32, kInt4>), grid, block, 0, stream, c, N, K, o); break;
@@ -317,15 +385,15 @@ int launch_dequant(const void* packed, int64_t N, int64_t K, int group, void* W_
     return check_launch();
 }
 
-int launch_unpack(const void* packed, int64_t N, int64_t K, int group, void* out, hipStream_t stream)
+int launch_unpack(const void* packed, int64_t N, int64_t K, int group, void* out, hipStream_t stream, int shift)
 {
     const dim3 grid = tile_grid(N, K), block(kThreads);
     const uint4* c = static_cast<const uint4*>(packed);
     uint8_t* o = static_cast<uint8_t*>(out);
     switch (group) {
-        case 32: hipLaunchKernelGGL(unpack_kernel<32>, grid, block, 0, stream, c, N, K, o); break;
-        case 64: hipLaunchKernelGGL(unpack_kernel<64>, grid, block, 0, stream, c, N, K, o); break;
-        case 128: hipLaunchKernelGGL(unpack_kernel<128>, grid, block, 0, stream, c, N, K, o); break;
+        case 32: hipLaunchKernelGGL(unpack_kernel<32>, grid, block, 0, stream, c, N, K, o, shift); break;
+        case 64: hipLaunchKernelGGL(unpack_kernel<64>, grid, block, 0, stream, c, N, K, o, shift); break;
+        case 128: hipLaunchKernelGGL(unpack_kernel<128>, grid, block, 0, stream, c, N, K, o, shift); break;
         default: return E0M4_ERR_GROUP;
     }
     return check_launch();
