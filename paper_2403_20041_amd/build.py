@@ -13,7 +13,7 @@ INCLUDE = os.path.join(ROOT, "include")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libe0m4.so")
 
-SOURCES = ["e0m4_api.hip", "e0m4_pack.hip", "e0m4_gemv.hip", "e0m4_gemv_mfma.hip", "e0m4_gemm.hip", "e0m4_gemm_pipe.hip",
+SOURCES = ["e0m4_api.hip", "e0m4_pack.hip", "e0m4_gemv.hip", "e0m4_gemv_mfma.hip", "e0m4_gemv_dq.hip", "e0m4_gemm.hip", "e0m4_gemm_pipe.hip",
            "e0m4_norm.hip", "e0m4_kv.hip", "e0m8_pack.hip"]
 # the quantiser's fp32 steps must stay single IEEE operations
 EXTRA_FLAGS = {"e0m4_pack.hip": ["-ffp-contract=off"], "e0m8_pack.hip": ["-ffp-contract=off"]}

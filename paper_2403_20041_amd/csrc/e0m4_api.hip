@@ -70,6 +70,23 @@ bool use_gemv_mfma(int64_t M, int64_t N, int64_t K, int group)
 {
     return knob("gemv_mfma") != 1 && gemv_mfma_supported(M, N, K, group);
 }
+// The small-batch kernel with dequantised weight operands serves groups of 32 and 64 at 3 <= M <= 16 (the
+// group-128 kernel above cannot): measured against the vector kernel and the GEMM on layer shapes of 6B and 14B
+// models it is 20 - 45 % faster for 4 <= M <= 8 whatever K is, and for 9 <= M <= 16 when all of X fits the LDS
+// (4608 x 4096 at M = 16: 8.9 against 13.2 us); with K in phases at those M it equals or loses to the GEMM
+// (15360 x 5120 at M = 16: 22.9 against 20.2 us), and at M = 2 the vector kernel is faster.  It runs up to 64
+// rows (two to four row tiles per weight operand), but from 17 rows on every workgroup stages more of X than it
+// reads weights and it measured 1.3 - 5 x slower than the GEMM, so those M are not sent to it by default.
+// gemv_mfma 4 forces it wherever it can run (2 <= M <= 64), 5 switches it off.
+bool use_gemv_dq(int64_t M, int64_t N, int64_t K, int group)
+{
+    const int k = knob("gemv_mfma");
+    if (k == 1 || k == 5 || M < 2) return false;
+    if (k == 4) return gemv_dq_supported(M, N, K, group);
+    if (group == 128 || M < 3 || M > 16) return false;
+    bool whole = false;
+    return gemv_dq_supported(M, N, K, group, &whole) && (whole || M <= 8);
+}
 // M <= kGemvMaxM rows take the vector decode kernel, whose time grows with M, unless the matrix-core GEMM
 // (64 x 256 tile, time nearly independent of M) is faster: measured crossover at about M * N * K = 3.8e8
 // (27392 x 4096 from M = 4 on, 4096 x 13696 from M = 7 on, never for 4096 x 4096).
@@ -161,6 +178,7 @@ size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 {
     if (check_shape(N, K, group) != E0M4_OK || M <= 0 || N == 0 || K == 0) return 0;             // invalid or empty: nothing runs
     if (small_m_on_vector(M, N, K)) return 0;           // the small-M kernels need none
+    if (use_gemv_dq(M, N, K, group)) return 0;
     if (use_gemv_mfma(M, N, K, group) || small_batch_in_chunks(Fusion{}, M, N, K, group)) return 0;
     return gemm_workspace_bytes(M, N, K);       // partial tiles of the split-K GEMM, if it splits
 }
@@ -299,7 +317,10 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
     }
     if (!X || !codes) return E0M4_ERR_NULL;
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
+    if (knob("gemv_mfma") == 4 && use_gemv_dq(M, N, K, group))
+        return launch_gemv_dq(X, M, codes, N, K, group, Y, (hipStream_t)stream);
     if (use_gemv_mfma(M, N, K, group)) return launch_gemv_mfma(X, M, codes, N, K, Y, (hipStream_t)stream);
+    if (use_gemv_dq(M, N, K, group)) return launch_gemv_dq(X, M, codes, N, K, group, Y, (hipStream_t)stream);
     if (small_m_on_vector(M, N, K)) return launch_gemv(X, M, codes, N, K, group, Y, (hipStream_t)stream);
     if (small_batch_in_chunks(Fusion{}, M, N, K, group)) {
         const int64_t m0 = first_chunk_rows(M);

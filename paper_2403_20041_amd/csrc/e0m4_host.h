@@ -74,6 +74,11 @@ bool gemv_mfma_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K, int 
 bool gemv_mfma8_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K);
 int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                            hipStream_t stream);
+// Small-batch path with the weight operand dequantised in registers: 2 <= M <= 64, any group (e0m4_gemv_dq.hip).
+// (`whole_rows`: all M rows of X fit the LDS at once, no phases along K)
+bool gemv_dq_supported(int64_t M, int64_t N, int64_t K, int group, bool* whole_rows = nullptr);
+int launch_gemv_dq(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                   hipStream_t stream);
 // INT4 twin of the M = 1 kernel: same layout and work decomposition, codes turned into numbers with
 // integer-to-float conversion instructions.
 int launch_gemv_int4(const void* X, const void* packed, int64_t N, int64_t K, int group, void* Y, hipStream_t stream);

@@ -180,6 +180,12 @@ def run_matmul_case(e0m4, oracle, M, N, K, G, seed, outliers=False, row_std=None
 @pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_gemv_small(e0m4, oracle, M, G):
     run_matmul_case(e0m4, oracle, M, 200, 1152, G, seed=30 + M)
+    if M >= 2:                                          # and on the vector kernel where a matrix-core kernel is the default
+        e0m4.e0m4_set_knob("gemv_mfma", 1)
+        try:
+            run_matmul_case(e0m4, oracle, M, 200, 1152, G, seed=30 + M)
+        finally:
+            e0m4.e0m4_set_knob("gemv_mfma", 0)
 
 
 @pytest.mark.parametrize("N,K,G", [(64, 128, 128), (1, 32, 32), (4096, 4096, 128), (1000, 13696, 128),
@@ -482,3 +488,67 @@ def test_empty_problems(e0m4):
     W0 = torch.zeros((0, 128), dtype=torch.float16, device=DEV)
     e0m4.e0m4_quantize(W0, 128)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ small batches with dequantised weight operands
+# (2 <= M <= 64, any group; by default it serves groups of 32 and 64 at 3 <= M <= 16; knob gemv_mfma = 4 forces the
+# kernel wherever it can run)
+
+DQ_SHAPES = [(203, 1664, 32), (203, 1664, 64), (203, 1664, 128), (1040, 4096, 64), (64, 128, 128), (17, 32, 32),
+             (530, 13696, 64), (300, 8192, 128), (4608, 416, 32)]
+
+
+@pytest.mark.parametrize("N,K,G", DQ_SHAPES)
+@pytest.mark.parametrize("M", [2, 3, 8, 15, 16, 17, 24, 32, 33, 47, 64])
+def test_small_batch_dequantised_operands_forced(e0m4, oracle, M, N, K, G):
+    W = synth_inputs.weights(N, K, seed=900 + N + K + G)
+    (codes, scales, bias), What = assert_quantize_exact(e0m4, oracle, W, G)
+    X = synth_inputs.activations(M, K, seed=950 + M)
+    ws = torch.empty(max(16, e0m4.e0m4_workspace_bytes(M, N, K, G)), dtype=torch.uint8, device=DEV)
+    e0m4.e0m4_set_knob("gemv_mfma", 4)
+    try:
+        Y = e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G, workspace=ws)
+        Y2 = e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G, workspace=ws)
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+    Yref, absdot = oracle.matmul(X, What)
+    check_matmul(Y, Yref, absdot, "dq M=%d N=%d K=%d G=%d" % (M, N, K, G))
+    assert torch.equal(Y, Y2)
+
+
+@pytest.mark.parametrize("G", [32, 64, 128])
+@pytest.mark.parametrize("M", [3, 5, 16])
+def test_small_batch_default_dispatch_and_one_hot(e0m4, oracle, M, G):
+    N, K = 1040, 2048
+    W = synth_inputs.weights(N, K, seed=970 + G)
+    (codes, scales, bias), What = assert_quantize_exact(e0m4, oracle, W, G)
+    assert e0m4.e0m4_workspace_bytes(M, N, K, G) == 0               # one of the small-batch kernels serves it
+    X = synth_inputs.activations(M, K, seed=980 + M)
+    Y = e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G)
+    Yref, absdot = oracle.matmul(X, What)
+    check_matmul(Y, Yref, absdot, "small batch M=%d G=%d" % (M, G))
+    X1 = np.zeros((M, K), dtype=np.float16)
+    ks = [(131 * m + 7) % K for m in range(M)]
+    for m, k in enumerate(ks):
+        X1[m, k] = 1.0
+    Y1 = bits(e0m4.e0m4_matmul(to_dev(X1), codes, scales, bias, N, K, G))
+    for m, k in enumerate(ks):
+        assert np.array_equal(Y1[m] & 0x7FFF, What.view(np.uint16)[:, k] & 0x7FFF)
+
+
+def test_small_batch_dequantised_operands_few_workgroups(e0m4, oracle):
+    """Many row blocks per workgroup, K in several phases (the sums wait in LDS between phases)."""
+    N, K, G, M = 2000, 6144, 64, 40
+    W = synth_inputs.weights(N, K, seed=990)
+    (codes, scales, bias), What = assert_quantize_exact(e0m4, oracle, W, G)
+    X = synth_inputs.activations(M, K, seed=991)
+    Yref, absdot = oracle.matmul(X, What)
+    for target in (0, 7, 40):
+        e0m4.e0m4_set_knob("gemv_mfma", 4)
+        e0m4.e0m4_set_knob("gemv_workgroups", target)
+        try:
+            Y = e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G)
+        finally:
+            e0m4.e0m4_set_knob("gemv_mfma", 0)
+            e0m4.e0m4_set_knob("gemv_workgroups", 0)
+        check_matmul(Y, Yref, absdot, "dq target=%d" % target)
