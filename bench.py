@@ -65,7 +65,7 @@ def profile_traffic(key):
 # rocprofv3 summaries
 
 def _short_kernel_name(n):
-    m = re.search(r"(gemv_kernel|gemv_mfma_kernel|splitk_reduce_fused_kernel|gemm_pipe_kernel|gemm_kernel|quantize_kernel|"
+    m = re.search(r"(gemv_kernel|gemv_mfma_kernel|gemv_dq_kernel|splitk_reduce_fused_kernel|gemm_pipe_kernel|gemm_kernel|quantize_kernel|"
                   r"dequant_kernel|unpack_kernel|splitk_reduce_kernel|zero_fill_kernel|rmsnorm_kernel|kv_append_kernel|"
                   r"quantize8_kernel)I((?:L[ib]\d+E)+)E", n)
     if m:
@@ -75,11 +75,19 @@ def _short_kernel_name(n):
     return (m.group(1) if m else n)[:60]
 
 
+OUR_KERNELS = (r"gemv_kernel|gemv_mfma_kernel|gemv_dq_kernel|gemm_pipe_kernel|gemm_kernel|splitk_reduce|rmsnorm_kernel|"
+               r"quantize_kernel|dequant_kernel|kv_append_kernel")
+
+
 def summarize(directory, last):
-    """Per kernel and grid: dispatch count and duration statistics (kernel trace), or counter averages (counter
-    collection), from the newest rocprofv3 results database under `directory`.  With --last N only the last N
-    dispatches of this library's matmul kernels are counted: in a run of `--only decode` those are the timed
-    graph replays (steps x launches per step)."""
+    """Summary of the newest rocprofv3 results database under `directory`, for this library's kernels (and the
+    runtime's plain buffer copy, which calibrates the traffic counters).
+    Kernel trace: per kernel and grid, dispatch count and duration statistics; with --last N only the last N
+    dispatches of the matmul kernels are counted: in a run of `--only decode` those are the timed graph replays
+    (steps x launches per step).
+    Counter collection: one row per kernel, grid and group of dispatches with like readings (dispatches of one
+    kernel and grid whose first counter differs by more than 3 % are different problem shapes), one column per
+    counter, averaged over the group."""
     import collections
     import sqlite3
     import statistics
@@ -90,21 +98,39 @@ def summarize(directory, last):
     con = sqlite3.connect(max(dbs, key=os.path.getmtime))
     tables = {r[0] for r in con.execute("select name from sqlite_master where type in ('table','view')")}
     if "counters_collection" in tables and con.execute("select count(*) from counters_collection").fetchone()[0]:
-        agg = collections.defaultdict(list)
-        for name, gx, cn, val in con.execute("select kernel_name,grid_size_x,counter_name,value from counters_collection"):
-            agg[(_short_kernel_name(name), gx, cn)].append(val)
-        print("%-44s %10s %-28s %7s %14s %14s %14s" % ("kernel", "grid_x", "counter", "calls", "avg", "min", "max"))
-        for k, v in sorted(agg.items(), key=lambda kv: (kv[0][2], -sum(kv[1]))):
-            print("%-44s %10d %-28s %7d %14.1f %14.1f %14.1f" % (k[0], k[1], k[2], len(v), sum(v) / len(v), min(v), max(v)))
+        cols = [r[1] for r in con.execute("pragma table_info(counters_collection)")]
+        key = "dispatch_id" if "dispatch_id" in cols else "rowid"
+        per = collections.OrderedDict()
+        for did, name, gx, cn, val in con.execute(
+                "select %s,kernel_name,grid_size_x,counter_name,value from counters_collection order by %s" % (key, key)):
+            if not re.search(OUR_KERNELS + "|__amd_rocclr_copyBuffer", name):
+                continue
+            d = per.setdefault((did, _short_kernel_name(name), gx), {})
+            d[cn] = d.get(cn, 0.0) + val            # a counter may come in several rows (one per hardware instance)
+        counters = sorted({c for d in per.values() for c in d})
+        groups = collections.defaultdict(list)
+        for (did, kname, gx), d in per.items():
+            groups[(kname, gx)].append([d.get(c, 0.0) for c in counters])
+        print("%-42s %9s %6s " % ("kernel", "grid_x", "calls") + " ".join("%22s" % c[-22:] for c in counters))
+        rows = []
+        for (kname, gx), vs in groups.items():
+            vs.sort()
+            start = 0
+            for i in range(1, len(vs) + 1):
+                if i == len(vs) or vs[i][0] > 1.03 * vs[i - 1][0] + 1e-9:
+                    grp = vs[start:i]
+                    rows.append((kname, gx, len(grp), [sum(v[c] for v in grp) / len(grp) for c in range(len(counters))]))
+                    start = i
+        for kname, gx, n, avg in sorted(rows, key=lambda r: (r[0], r[1], r[3][0])):
+            print("%-42s %9d %6d " % (kname, gx, n) + " ".join("%22.1f" % a for a in avg))
         return
-    rows = list(con.execute("select name,grid_x,workgroup_x,start,end from kernels order by start"))
-    ours = [r for r in rows if re.search(r"gemv_kernel|gemv_mfma_kernel|gemm_pipe_kernel|gemm_kernel|splitk_reduce", r[0])]
+    rows = [r for r in con.execute("select name,grid_x,workgroup_x,start,end from kernels order by start")
+            if re.search(OUR_KERNELS, r[0])]
     if last:
-        ours = ours[-last:]
+        rows = [r for r in rows if re.search(r"gemv_kernel|gemv_mfma_kernel|gemv_dq_kernel|gemm_pipe_kernel|gemm_kernel|splitk_reduce", r[0])][-last:]
         print("last %d dispatches of the matmul kernels (the timed graph replays): %.3f ms of kernel time, "
-              "%.3f ms from the first start to the last end" % (len(ours), sum(r[4] - r[3] for r in ours) / 1e6,
-                                                                 (ours[-1][4] - ours[0][3]) / 1e6))
-        rows = ours
+              "%.3f ms from the first start to the last end" % (len(rows), sum(r[4] - r[3] for r in rows) / 1e6,
+                                                                 (rows[-1][4] - rows[0][3]) / 1e6))
     agg = collections.defaultdict(list)
     for name, gx, wx, t0, t1 in rows:
         agg[(_short_kernel_name(name), gx, wx)].append(t1 - t0)
@@ -361,6 +387,17 @@ def main():
         "roofline": headline_roofline,
         "quantize": {"s_for_stack_incl_weight_generation": round(t_q, 2)},
     }
+    # the offline kernels on their own: the widest projection, timed with events (bytes: fp16 in or out + packed)
+    name, N, K = max(shapes, key=lambda s_: s_[1] * s_[2])
+    Wq = synth_inputs.weights_device(N, K, 4242, dev)
+    bufs_q = e0m4.alloc_packed(N, K, GROUP, dev)
+    Wd = torch.empty_like(Wq)
+    q_us = time_us(lambda: e0m4.e0m4_quantize(Wq, GROUP, out=bufs_q, stream=stream), 5, rounds=2)
+    d_us = time_us(lambda: e0m4.e0m4_dequant(bufs_q[0], None, None, N, K, GROUP, out=Wd, stream=stream), 5, rounds=2)
+    io_bytes = 2 * N * K + bufs_q[0].numel()
+    out["quantize"].update({"shape": [N, K], "quantize_us": round(q_us, 1), "quantize_GBps": round(io_bytes / q_us / 1e3, 1),
+                            "dequant_us": round(d_us, 1), "dequant_GBps": round(io_bytes / d_us / 1e3, 1)})
+    del Wq, Wd, bufs_q
     configs = {}
     out["configs"] = configs
     cfg2 = {"workload": out["config"]["workload"], "roofline": headline_roofline}

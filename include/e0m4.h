@@ -72,9 +72,10 @@ size_t e0m4_codes_bytes(int64_t N, int64_t K, int group);
 /* Number of fp16 elements in `scales` (and in `bias`): N * (K/group). */
 size_t e0m4_params_elems(int64_t N, int64_t K, int group);
 /* Scratch bytes e0m4_matmul needs for this shape: 0 for the small-M paths
- * (partial sums stay on chip) and for GEMM shapes with enough output tiles to fill the GPU;
- * otherwise splits * M * N * 4 bytes of fp32 partial sums for the GEMM's split
- * along K.  A pure function of the shape (0 for empty or invalid problems), unless the calling
+ * (partial sums stay on chip) and for GEMM shapes whose output tiles fill the GPU in whole rounds;
+ * otherwise fp32 partial sums of the GEMM's split along K: splits * M * N * 4 bytes for a fixed
+ * number of splits, or 1 KiB of tile counters and (256 + t) slabs of 256 KiB when the last t tiles
+ * are shared out evenly over the 256 compute units (at most 128 MiB).  A pure function of the shape (0 for empty or invalid problems), unless the calling
  * thread has set a diagnostic knob (e0m4_set_knob), which then applies to its queries and calls alike. */
 size_t e0m4_workspace_bytes(int64_t M, int64_t N, int64_t K, int group);
 
@@ -146,21 +147,24 @@ int e0m4_matmul(const void* X_f16, int64_t M,
  * workspace: code under HIP graph capture, tight serving loops, harnesses
  * that forbid allocation.  Same result, bit for bit, and same argument and
  * error rules as e0m4_matmul(X, M, codes, NULL, NULL, N, K, group, Y, ...),
- * but the scratch memory of the split along K is a fixed array inside the
- * library, E0M4_STATIC_SCRATCH_BYTES = 64 MiB of device memory that every GPU
+ * but the scratch memory of the split along K (fp32 partial sums, and the tile
+ * counters of the even scheduling) is a fixed array inside the library,
+ * E0M4_STATIC_SCRATCH_BYTES = 128 MiB of device memory that every GPU
  * the library runs on holds from the first use until the process ends.  The
  * call allocates and frees nothing (no hipMalloc, no allocating runtime or
  * library routine); its first call on a device looks up the array's address on
  * that device (make that call outside a graph capture).
  *   - E0M4_ERR_WORKSPACE if e0m4_workspace_bytes(M, N, K, group) exceeds the
  *     array; nothing is enqueued then.  (With the built-in choices no shape needs
- *     more than 64 MiB; only a forced number of K splits can.)
+ *     more than 128 MiB; only a forced number of K splits can.)
  *   - All calls on one GPU share the one array: calls whose work may overlap
  *     on that GPU (different streams, different threads) race on it; issue them on
- *     one stream or order them with events.  The array is never read before the
- *     same call has written it, so nothing has to be cleared between calls.
+ *     one stream or order them with events.  The array keeps the last call's
+ *     contents; a call reads only what it has written itself, and zeroes the
+ *     counters it uses with a small kernel of its own (no memset node: the call
+ *     can be captured into a graph).
  */
-#define E0M4_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+#define E0M4_STATIC_SCRATCH_BYTES ((size_t)128 << 20)
 int e0m4_matmul_static(const void* X_f16, int64_t M, const void* codes, int64_t N, int64_t K, int group,
                        void* Y_f16, void* stream);
 
@@ -185,7 +189,8 @@ int e0m4_matmul_static(const void* X_f16, int64_t M, const void* codes, int64_t 
  * runs inside the GEMM kernels (or the kernel that adds the K splits) and the
  * rms-norm is a launch of its own that writes x' to the workspace.
  * Workspace: e0m4_fused_workspace_bytes() bytes, same rules as e0m4_matmul.
- * With no operator selected the result equals e0m4_matmul's.  K == 0 is
+ * With no operator selected the result is that of e0m4_matmul (up to the order of
+ * the fp32 additions, which the two may choose differently for a large problem).  K == 0 is
  * rejected (E0M4_ERR_SHAPE); other shape, pointer and error rules as above.
  */
 #define E0M4_EPILOGUE_NONE   0

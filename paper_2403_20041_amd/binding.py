@@ -224,7 +224,7 @@ def e0m4_matmul(X, codes, scales, bias, N: int, K: int, group: int, out=None, wo
     return out
 
 
-E0M4_STATIC_SCRATCH_BYTES = 64 << 20
+E0M4_STATIC_SCRATCH_BYTES = 128 << 20
 
 
 def e0m4_matmul_static(X, codes, N: int, K: int, group: int, out, stream=None):

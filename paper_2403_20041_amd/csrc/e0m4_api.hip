@@ -26,6 +26,7 @@ thread_local Knob g_knobs[] = {
     {"gemv_xreg", 0},                  // M = 1 kernel, a wavefront's activations in registers: 2 never
     {"gemm_variant", 0},               // 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
     {"gemm_splits", 0},                // force the number of K splits of the pipelined GEMM kernel
+    {"gemm_sk", 0},                    // even scheduling of the 256 x 256 tiles over the compute units: 1 whenever the last round is partly filled, 2 never
 };
 
 // Scratch of e0m4_matmul_static: the split-K partial sums that e0m4_matmul keeps in the caller's workspace.
@@ -204,7 +205,7 @@ size_t e0m4_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int group, in
     Fusion f;
     f.swiglu = epilogue == E0M4_EPILOGUE_SWIGLU;
     if (fused_path(f, M, N, K, group) != 1) return 0;
-    return (with_rmsnorm ? norm_bytes(M, K) : 0) + gemm_workspace_bytes(M, N, K, f.swiglu);
+    return (with_rmsnorm ? norm_bytes(M, K) : 0) + gemm_workspace_bytes(M, N, K, f.swiglu, true);
 }
 
 int e0m4_set_knob(const char* name, int value)
@@ -383,7 +384,7 @@ int e0m4_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
     }
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // 32-bit offsets in the GEMM epilogue
     const size_t nb = rms_gamma ? norm_bytes(M, K) : 0;
-    const size_t need = nb + gemm_workspace_bytes(M, N, K, f.swiglu);
+    const size_t need = nb + gemm_workspace_bytes(M, N, K, f.swiglu, true);
     if (need > 0) {
         if (!workspace) return E0M4_ERR_NULL;
         if (!aligned16(workspace)) return E0M4_ERR_ALIGN;
@@ -544,7 +545,7 @@ static bool e0m8_use_gemm(int64_t M, int64_t N, int64_t K)
 size_t e0m8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group)
 {
     if (check_shape8(N, K, group) != E0M4_OK || M <= 0 || N == 0 || K == 0) return 0;
-    return e0m8_use_gemm(M, N, K) ? gemm_pipe_workspace_bytes(M, N, K) : 0;
+    return e0m8_use_gemm(M, N, K) ? gemm_pipe_workspace_bytes(M, N, K, false, true) : 0;
 }
 
 int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t K, int group, void* Y, void* workspace,
@@ -603,7 +604,7 @@ size_t e0m8_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int group, in
     Fusion f;
     f.swiglu = epilogue == E0M4_EPILOGUE_SWIGLU;
     if (fused_path8(f, M, N, K) != 1) return 0;
-    return (with_rmsnorm ? norm_bytes(M, K) : 0) + gemm_pipe_workspace_bytes(M, N, K, f.swiglu);
+    return (with_rmsnorm ? norm_bytes(M, K) : 0) + gemm_pipe_workspace_bytes(M, N, K, f.swiglu, true);
 }
 
 int e0m8_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms_eps, const void* codes, int64_t N,
@@ -641,7 +642,7 @@ int e0m8_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
     }
     if (path != 1) return E0M4_ERR_SHAPE;               // larger M needs K % 128 == 0 (GEMM kernels)
     const size_t nb = rms_gamma ? norm_bytes(M, K) : 0;
-    const size_t need = nb + gemm_pipe_workspace_bytes(M, N, K, f.swiglu);
+    const size_t need = nb + gemm_pipe_workspace_bytes(M, N, K, f.swiglu, true);
     if (need > 0) {
         if (!workspace) return E0M4_ERR_NULL;
         if (!aligned16(workspace)) return E0M4_ERR_ALIGN;

@@ -328,9 +328,9 @@ bool use_pipe(int64_t M, int64_t N, int64_t K, bool swiglu = false)
 
 }  // namespace
 
-size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu)
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu, bool fused)
 {
-    return use_pipe(M, N, K, swiglu) ? gemm_pipe_workspace_bytes(M, N, K, swiglu) : 0;
+    return use_pipe(M, N, K, swiglu) ? gemm_pipe_workspace_bytes(M, N, K, swiglu, fused) : 0;
 }
 
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,

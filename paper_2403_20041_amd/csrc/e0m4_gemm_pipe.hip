@@ -59,6 +59,28 @@ struct PipeFusion {
     int64_t n_half;                                     // N / 2 (gated epilogue)
 };
 
+// Even scheduling of the tiles over the compute units ("stream-K").  When the tile count is not a multiple of
+// the number of compute units, the last, partly filled round would leave units idle for the length of a whole
+// tile.  With `enabled`, the launch has exactly one workgroup per compute unit, and each workgroup runs
+//   - `rounds_dp` whole tiles (tile r * grid + position), written out directly, then
+//   - its share of the remaining `rem_tiles` tiles: those tiles' K ranges, in pairs of K slices, laid end to end
+//     are `rem_tiles * pairs` units, of which the workgroup at position p owns [p * U / grid, (p + 1) * U / grid):
+//     at most the tail of one tile and the head of the next.
+// A tile that several workgroups share is finished by whichever of them arrives last: every sharer stores its
+// fp32 partial sums to a slab of the workspace (slabs of the sharers of a tile are consecutive, in K order) with
+// write-through stores, one thread orders them ahead of the counter (release fence) and adds one to the tile's counter; the one that brings the counter
+// to the number of sharers reads all slabs back with device-coherent loads, adds them in K order -- a fixed order,
+// whoever does it -- and writes the tile.  Nobody waits for anybody, so a workgroup that is never scheduled next to
+// the others cannot stall them.  The counters are zeroed by a small kernel before the launch.
+struct SkArgs {
+    int enabled;
+    int rounds_dp;                                      // whole tiles per workgroup
+    int rem_tiles;                                      // tiles shared out in K ranges, after rounds_dp * grid whole tiles
+    int pairs;                                          // K / 128: pairs of K slices per tile
+    unsigned int* counters;                             // [rem_tiles], zero on entry
+    float* slabs;                                       // [grid + rem_tiles][BM * BN] fp32
+};
+
 //
 // The tile is BM x BN: 256 x 256 with 2 x 4 wavefronts for large M; 128 x 128 with 2 x 2 wavefronts (two
 // workgroups per compute unit) for M up to a few hundred, where the large tile would compute rows that
@@ -72,7 +94,8 @@ template <int G, int WGM, int WGN, bool FUSED, int BM, int BN, bool E8 = false>
 __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half_t* __restrict__ X, int64_t M,
                                                              const uint4* __restrict__ packed, int64_t N, int64_t K,
                                                              half_t* __restrict__ Y, int m_tiles, int n_tiles,
-                                                             int splits, float* __restrict__ partial, PipeFusion fu)
+                                                             int splits, float* __restrict__ partial, PipeFusion fu,
+                                                             SkArgs sk)
 {
     constexpr int kThreads = 64 * WGM * WGN;
     constexpr int kStageBytes = BM * kRowBytes;
@@ -82,32 +105,101 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     // Work items are (tile, K split) pairs, the splits of a tile adjacent; each XCD takes a contiguous run.
+    // (even scheduling exists in the instance the launcher uses it with; elsewhere the segment loop below folds away)
+    constexpr bool kSk = !FUSED && !E8 && BM == 256 && BN == 256;
+    const bool sk_on = kSk && sk.enabled;
     const int total = m_tiles * n_tiles * splits;
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
     const int item = (blockIdx.x % kNumXcd) * per_xcd + blockIdx.x / kNumXcd;
-    if (item >= total) return;
+    if (!sk_on && item >= total) return;
+    const int KT_all = (int)(K / BK);
+    // Even scheduling: this workgroup's position (consecutive positions on one XCD: they share weight rows in
+    // its L2), its range of units among the shared-out tiles, and the one or two K ranges that makes.
+    // (Quotients are computed on the vector unit: every one of them goes through readfirstlane, or the segment
+    // loop below, its trip count included, counts as divergent and every buffer load turns into a per-lane loop.
+    // All of this fits 32 bits: at most 255 shared-out tiles of at most 8192 pairs, times 256 positions.)
+    const uint32_t sk_grid = gridDim.x;
+    const uint32_t sk_pos = (blockIdx.x % kNumXcd) * (sk_grid / kNumXcd) + blockIdx.x / kNumXcd;
+    const uint32_t sk_pairs = (uint32_t)sk.pairs;
+    const uint32_t sk_units = (uint32_t)sk.rem_tiles * sk_pairs;
+    // (fewer units than workgroups, which only a forced launch has: the first sk_units positions take one each, so
+    // that the sharers of a tile are always consecutive positions with a share each)
+    const uint32_t sk_div = sk_units < sk_grid ? (sk_units > 0 ? sk_units : 1u) : sk_grid;
+    auto sk_begin = [&](uint32_t pos) -> uint32_t {     // first unit of the workgroup at `pos`
+        return (uint32_t)__builtin_amdgcn_readfirstlane((int)(sk_units * (pos < sk_div ? pos : sk_div) / sk_div));
+    };
+    const uint32_t sk_u0 = sk_on ? sk_begin(sk_pos) : 0u, sk_u1 = sk_on ? sk_begin(sk_pos + 1) : 0u;
+    const uint32_t sk_t0 = sk_u1 > sk_u0 ? (uint32_t)__builtin_amdgcn_readfirstlane((int)(sk_u0 / sk_pairs)) : 0u;  // its first tile
+    int sk_segs = 0;
+    if (sk_u1 > sk_u0) sk_segs = sk_u1 > (sk_t0 + 1) * sk_pairs ? 2 : 1;
+    const int n_segments = sk_on ? sk.rounds_dp + sk_segs : 1;
+    // the position whose range holds `unit`
+    auto sk_pos_of = [&](uint32_t unit) -> int {
+        uint32_t g = (uint32_t)__builtin_amdgcn_readfirstlane((int)(unit * sk_div / sk_units));
+        while (sk_begin(g + 1) <= unit) ++g;
+        while (sk_begin(g) > unit) --g;
+        return (int)g;
+    };
+    // the work item of a launch without even scheduling
+    const int plain_tile = __builtin_amdgcn_readfirstlane(item / splits);
+    const int plain_split = __builtin_amdgcn_readfirstlane(item % splits);
+    const int plain_kb = __builtin_amdgcn_readfirstlane(2 * (int)((int64_t)(KT_all / 2) * plain_split / splits));
+    const int plain_ke = __builtin_amdgcn_readfirstlane(2 * (int)((int64_t)(KT_all / 2) * (plain_split + 1) / splits));
+  for (int seg = 0; seg < n_segments; ++seg) {
+    if (seg > 0) __syncthreads();                       // every wavefront has left the previous segment's LDS stages
+    // what this segment computes: a tile, a range of its K slices, and where the sums go
+    //   out_mode 0: the whole K range, results to Y (with the fused epilogue, if any)
+    //   out_mode 1: one of `splits` K ranges, fp32 sums to slab `split` of the [splits][M][N] workspace
+    //   out_mode 2: a shared-out K range (see SkArgs), fp32 sums to this sharer's slab; the last sharer finishes the tile
+    int seg_tile, seg_kb, seg_ke, out_mode, seg_split = 0, sk_rt = 0, sk_first = 0, sk_sharers = 1;
+    if (!sk_on) {
+        seg_tile = plain_tile;
+        seg_split = plain_split;
+        seg_kb = plain_kb;
+        seg_ke = plain_ke;
+        out_mode = splits > 1 ? 1 : 0;
+    } else if (seg < sk.rounds_dp) {
+        seg_tile = seg * (int)sk_grid + (int)sk_pos;
+        seg_kb = 0;
+        seg_ke = KT_all;
+        out_mode = 0;
+    } else {
+        sk_rt = (int)sk_t0 + (seg - sk.rounds_dp);      // the range's first tile, then its second
+        const uint32_t t_lo = (uint32_t)sk_rt * sk_pairs, t_hi = t_lo + sk_pairs;
+        const uint32_t lo = sk_u0 > t_lo ? sk_u0 : t_lo, hi = sk_u1 < t_hi ? sk_u1 : t_hi;
+        seg_tile = sk.rounds_dp * (int)sk_grid + sk_rt;
+        seg_kb = 2 * (int)(lo - t_lo);
+        seg_ke = 2 * (int)(hi - t_lo);
+        sk_first = sk_pos_of(t_lo);
+        sk_sharers = sk_pos_of(t_hi - 1) - sk_first + 1;
+        out_mode = sk_sharers > 1 ? 2 : 0;
+    }
     // (quotients and remainders are computed on the vector unit; move them to scalar registers, or
     // everything derived from them, the K loop counter included, is treated as divergent and every
     // buffer load below turns into a per-lane loop)
-    const int tile = __builtin_amdgcn_readfirstlane(item / splits);
-    const int split = __builtin_amdgcn_readfirstlane(item % splits);
+    const int tile = __builtin_amdgcn_readfirstlane(seg_tile);
+    const int split = __builtin_amdgcn_readfirstlane(seg_split);
+    out_mode = __builtin_amdgcn_readfirstlane(out_mode);
     const int64_t m0 = (int64_t)__builtin_amdgcn_readfirstlane(tile % m_tiles) * BM;
     const bool gated = FUSED && fu.swiglu;
     // first column of the tile: of the weight rows, or of the output (= of the gate rows) when gated
     const int64_t n0 = (int64_t)__builtin_amdgcn_readfirstlane(tile / m_tiles) * (gated ? BN / 2 : BN);
 
-    const int t = threadIdx.x;
+    // (the thread number is made opaque to the optimiser in every segment: what is derived from it -- loader
+    // offsets, epilogue rows and masks -- is then computed where it is used, not ahead of the segment loop, where it
+    // would hold registers through the K loop)
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
     const int lane = t & 63;
-    const int wave = t >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const uint32_t fmask = frac_mask_vgpr();
     const PackedLayout<G> lay(E8 ? 2 * K : K);
     const int64_t nrb = row_blocks(N);
     const int wm = (wave / WGN) * (BM / WGM), wn = (wave % WGN) * (BN / WGN);
-    const int KT = (int)(K / BK);                       // K % 128 == 0 is required by the launcher: KT is even
-    // this work item's K slices [kt_begin, kt_end): whole pairs of slices, spread evenly over the splits
-    const int pairs = KT / 2;
-    const int kt_begin = __builtin_amdgcn_readfirstlane(2 * (int)((int64_t)pairs * split / splits));
-    const int kt_end = __builtin_amdgcn_readfirstlane(2 * (int)((int64_t)pairs * (split + 1) / splits));
+    const int KT = KT_all;                              // K % 128 == 0 is required by the launcher: KT is even
+    // this segment's K slices [kt_begin, kt_end): whole pairs of slices
+    const int kt_begin = __builtin_amdgcn_readfirstlane(seg_kb);
+    const int kt_end = __builtin_amdgcn_readfirstlane(seg_ke);
 
     // ---- activation loader: 8 lanes cover one 128-byte row slice; pass p handles row RP*p + t/8.
     // Rows beyond M are clamped (their products are never stored).
@@ -306,7 +398,11 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
     }
 
     // accumulator layout of a 32x32 block: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
-    const uint32_t n32 = (uint32_t)N;
+    // (n32 is made opaque to the optimiser here, after the K loop: otherwise the products of n32 with the row
+    // numbers of the epilogue, invariant across the segment loop, are computed before it and held in registers
+    // through the K loop: a hundred registers more, and spills in the large tile)
+    uint32_t n32 = (uint32_t)N;
+    asm volatile("" : "+s"(n32));
     const int rows_left = (int)min((int64_t)BM, M - m0), cols_left = (int)min((int64_t)BN, N - n0);
     const int row0 = wm + 4 * (lane >> 5), col0 = wn + (lane & 31);
     const uint32_t off0 = (uint32_t)row0 * n32 + (uint32_t)col0;
@@ -325,17 +421,83 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
             }
         }
     };
-    // Split K: this work item's fp32 partial sums go to slab `split` of the workspace (row-major
-    // [splits][M][N]); a second kernel adds the slabs in split order and rounds to fp16.  (Adding them
-    // here, in the last work item to arrive, needs device-scope fences, which cost far more than the
-    // second launch on a chip whose eight L2 caches are not coherent with each other.)
+    // A shared-out K range (even scheduling): this sharer's sums go to its slab, in the order the registers hold
+    // them (16 bytes per lane and store, a wavefront's stores contiguous); the sharer that arrives last adds all
+    // slabs of the tile in K order and goes on to write the tile like an unshared one.
+    if (kSk && out_mode == 2) {
+        constexpr uint32_t kSlabStep = kThreads * 16;   // bytes between consecutive register quads of a lane
+        constexpr int kCoherent = 17;                   // sc0 | sc1: written through to memory, read from memory
+        uint32_t lane_off = (uint32_t)t * 16;
+        asm volatile("" : "+v"(lane_off));              // (opaque, like n32: the slab offsets stay here)
+        const __amdgpu_buffer_rsrc_t my_slab = make_rsrc(sk.slabs + (size_t)((int)sk_pos + sk_rt) * (size_t)(BM * BN));
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const floatx4 f = {acc[i][j][4 * q4], acc[i][j][4 * q4 + 1], acc[i][j][4 * q4 + 2], acc[i][j][4 * q4 + 3]};
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, f), my_slab,
+                                                           (int)(lane_off + ((i * TN + j) * 4 + q4) * kSlabStep), 0, kCoherent);
+                }
+        // The slab is in memory before the counter moves: every thread waits for its own stores, and after the
+        // barrier one thread orders them, at device scope, ahead of its addition to the counter.  (One fence per
+        // workgroup: a device-scope release writes back the XCD's whole L2, and two thousand of those, one per
+        // wavefront, took longer than the tiles they shared out.)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                                // (also: every wavefront has left the K loop's LDS stages)
+        if (t == 0) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            const unsigned int before = __hip_atomic_fetch_add(sk.counters + sk_rt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *reinterpret_cast<volatile int*>(smem) = before + 1 == (unsigned int)sk_sharers ? 1 : 0;
+        }
+        __syncthreads();
+        const int last = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(smem));
+        if (!last) continue;
+        // The last sharer: the tile's slabs (its own among them) added in K order, a quarter of the registers at a
+        // time -- the accumulators are not needed any more, and this way the code shares nothing with the other
+        // epilogues.  The loads are device-coherent: the other sharers ran on other XCDs, whose L2 this one cannot see.
+        half_t* __restrict__ yt = Y + m0 * N + n0;
+        // (one of the wavefront's TM row blocks at a time: two at a time measured twice as slow)
+        constexpr int kAtOnce = 1;
+#pragma unroll 1
+        for (int i0 = 0; i0 < TM; i0 += kAtOnce) {
+            floatx4 sum[kAtOnce * TN * 4];
+#pragma unroll
+            for (int v = 0; v < kAtOnce * TN * 4; ++v) sum[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+            const int quad0 = __builtin_amdgcn_readfirstlane(i0 * TN * 4 * (int)kSlabStep);
+            for (int sh = 0; sh < sk_sharers; ++sh) {
+                const __amdgpu_buffer_rsrc_t slab = make_rsrc(sk.slabs + (size_t)(sk_first + sk_rt + sh) * (size_t)(BM * BN));
+#pragma unroll
+                for (int v = 0; v < kAtOnce * TN * 4; ++v) {
+                    const u32x4 d = __builtin_amdgcn_raw_buffer_load_b128(slab, (int)(lane_off + v * kSlabStep), quad0, kCoherent);
+                    sum[v] += __builtin_bit_cast(floatx4, d);
+                }
+            }
+#pragma unroll
+            for (int a = 0; a < kAtOnce; ++a)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int dr = 32 * (i0 + a) + 8 * q4 + e;
+                            if (col0 + 32 * j < cols_left && row0 + dr < rows_left)
+                                yt[off0 + (uint32_t)dr * n32 + 32 * j] = (half_t)sum[(a * TN + j) * 4 + q4][e];
+                        }
+        }
+        continue;
+    }
+    // Split K in a fixed number of ranges: this work item's fp32 partial sums go to slab `split` of the workspace
+    // (row-major [splits][M][N]); a second kernel adds the slabs in split order and rounds to fp16.
     if (FUSED) {
         static_assert(!FUSED || TN == 2, "the gated epilogue pairs the two operand blocks of a wavefront");
         if (gated) {
             const int ocols_left = (int)min((int64_t)(BN / 2), fu.n_half - n0);
             const int ocol = (wave % WGN) * 32 + (lane & 31);
             if (ocol < ocols_left) {
-                if (splits > 1) {                       // partial sums keep the [M, N] layout of the weight rows
+                if (out_mode == 1) {                    // partial sums keep the [M, N] layout of the weight rows
                     float* __restrict__ pg = partial + ((size_t)split * (size_t)M + (size_t)m0) * (size_t)N + (size_t)n0;
                     float* __restrict__ pu = pg + fu.n_half;
                     const uint32_t o0 = (uint32_t)row0 * n32 + (uint32_t)ocol;
@@ -350,7 +512,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
                             }
                         }
                 } else {
-                    const uint32_t nh32 = (uint32_t)fu.n_half;
+                    uint32_t nh32 = (uint32_t)fu.n_half;
+                    asm volatile("" : "+s"(nh32));             // (opaque, like n32)
                     half_t* __restrict__ yt = Y + m0 * fu.n_half + n0;
                     const half_t* __restrict__ rt = fu.residual ? fu.residual + m0 * fu.n_half + n0 : nullptr;
                     const uint32_t o0 = (uint32_t)row0 * nh32 + (uint32_t)ocol;
@@ -367,9 +530,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
                         }
                 }
             }
-            return;
+            continue;
         }
-        if (splits == 1 && fu.residual) {
+        if (out_mode != 1 && fu.residual) {
             const half_t* __restrict__ rt = fu.residual + m0 * N + n0;
             half_t* __restrict__ yt = Y + m0 * N + n0;
 #pragma unroll
@@ -385,13 +548,14 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
                         }
                 }
             }
-            return;
+            continue;
         }
     }
-    if (splits > 1)
+    if (out_mode == 1)
         store_tile(partial + ((size_t)split * (size_t)M + (size_t)m0) * (size_t)N + (size_t)n0);
     else
         store_tile(Y + m0 * N + n0);
+  }
 }
 
 // The same with the fused epilogue: element i of the output is (m, j) with j < n_out; its sums are at
@@ -486,6 +650,9 @@ int choose_splits(int64_t tiles, int64_t K, int slots)
 {
     const int forced = knob("gemm_splits");
     const int64_t pairs = K / (2 * BK);
+    // every compute unit already has a tile: the partial sums and their reduction cost more than a second
+    // workgroup per unit gains (1024 x 4096 x 4096 on 256 tiles of 64 x 256: 44 us unsplit, 51 us in two splits)
+    if (forced <= 0 && tiles >= kComputeUnits) return 1;
     int64_t s = forced > 0 ? std::min<int64_t>(forced, pairs)                   // tests: down to one pair per split
                            : std::min<int64_t>(slots / tiles, pairs / kMinPairsPerSplit);
     s = std::min<int64_t>(s, kMaxSplits);
@@ -493,6 +660,50 @@ int choose_splits(int64_t tiles, int64_t K, int slots)
 }
 
 size_t partial_bytes(int splits, int64_t M, int64_t N) { return (size_t)splits * (size_t)M * (size_t)N * sizeof(float); }
+
+// Even scheduling (SkArgs) is used for the 256 x 256 tile when whole tiles would leave compute units idle for long:
+// a partly filled last round, at least kSkMinTiles tiles (fewer: the fixed K split with its reduction kernel), and
+// at least kSkMinSavedPairs pairs of K slices per compute unit saved over running that round as whole tiles.
+// What it saves is far less than the idle time it removes, for two measured reasons.  A compute unit is slower the
+// more of them run: one round of 160 tiles (K = 5120) takes 112 us, one round of 256 tiles 152 us, whether the
+// workgroups read different tiles or all the same one -- so it is not the memory side, and filling the idle units
+// buys 18 % more throughput, not 60 %.  And the slabs cost about 25 us a launch (12 us to store and publish them, 13
+// for the last sharers to add them up).  With M = 2048, G = 128: N = 27392, K = 5120 (856 tiles, 26 pairs saved)
+// 540 -> 525 us; N = 5120, K = 13696 (160 tiles, 40 saved) 290 -> 284 us; but N = 5120, K = 5120 (160 tiles, 15
+// saved) 113 -> 128 us and N = 15360, K = 5120 (480 tiles, 5 saved) 280 -> 308 us.
+// gemm_sk 1 forces it whenever the last round is partly filled, 2 forbids it.
+constexpr int kSkMinTiles = 128;
+constexpr int kSkMinSavedPairs = 24;
+constexpr size_t kSkCounterBytes = 1024;                // 255 counters at most, then the slabs (16-byte aligned)
+struct SkPlan {
+    bool on;
+    int rounds_dp, rem_tiles, pairs;
+    size_t workspace_bytes;
+};
+
+SkPlan sk_plan(int64_t tiles, int64_t K, int bm, int bn, bool allowed)
+{
+    SkPlan p{false, 0, 0, 0, 0};
+    const int forced = knob("gemm_sk");
+    if (!allowed || forced == 2 || bm != 256 || bn != 256 || tiles <= 0) return p;
+    p.rounds_dp = (int)(tiles / kComputeUnits);
+    p.rem_tiles = (int)(tiles % kComputeUnits);
+    p.pairs = (int)(K / (2 * BK));
+    if (p.rem_tiles == 0 || tiles > 0x3fffffffLL || p.pairs > 8192) return p;      // (the kernel's unit arithmetic is 32-bit)
+    if (forced != 1) {
+        if (tiles < kSkMinTiles) return p;
+        if ((int64_t)(kComputeUnits - p.rem_tiles) * p.pairs / kComputeUnits < kSkMinSavedPairs) return p;
+    }
+    p.on = true;
+    p.workspace_bytes = kSkCounterBytes + (size_t)(kComputeUnits + p.rem_tiles) * (size_t)bm * bn * sizeof(float);
+    return p;
+}
+
+__global__ void zero_u32_kernel(unsigned int* p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
 
 int64_t pipe_tiles(const PipeTile& t, int64_t M, int64_t N, bool swiglu)
 {
@@ -511,7 +722,8 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     const PipeTile shape = pipe_tile(M, N, K);
     const int64_t m_tiles = (M + BM - 1) / BM;
     const int64_t tiles = pipe_tiles(shape, M, N, f.swiglu), n_tiles = tiles / m_tiles;
-    const int splits = choose_splits(tiles, K, shape.slots);
+    const SkPlan skp = sk_plan(tiles, K, BM, BN, !FUSED && !E8);
+    const int splits = skp.on ? 1 : choose_splits(tiles, K, shape.slots);
     if (tiles * splits > 0x3fffffffLL) return E0M4_ERR_SHAPE;
     const int total = (int)(tiles * splits);
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
@@ -520,13 +732,28 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
         if (workspace == nullptr || workspace_bytes < partial_bytes(splits, M, N)) return E0M4_ERR_WORKSPACE;
         partial = static_cast<float*>(workspace);
     }
+    SkArgs sk{0, 0, 0, 0, nullptr, nullptr};
+    unsigned grid = (unsigned)(per_xcd * kNumXcd);
+    if (skp.on) {
+        if (workspace == nullptr || workspace_bytes < skp.workspace_bytes) return E0M4_ERR_WORKSPACE;
+        sk.enabled = 1;
+        sk.rounds_dp = skp.rounds_dp;
+        sk.rem_tiles = skp.rem_tiles;
+        sk.pairs = skp.pairs;
+        sk.counters = static_cast<unsigned int*>(workspace);
+        sk.slabs = reinterpret_cast<float*>(static_cast<char*>(workspace) + kSkCounterBytes);
+        grid = kComputeUnits;
+        hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(256), 0, stream, sk.counters, skp.rem_tiles);
+        const int zrc = check_launch();
+        if (zrc != E0M4_OK) return zrc;
+    }
     constexpr size_t lds = (size_t)kStages * BM * kRowBytes;       // 96 KiB for the large tile: above the default limit
     static std::atomic<uint64_t> lds_allowed{0};
     const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN, E8>),
                                       (int)lds, lds_allowed);
     if (arc != E0M4_OK) return arc;
-    hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN, E8>), dim3((unsigned)(per_xcd * kNumXcd)),
-                       dim3(64 * WGM * WGN), lds, stream, x, M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial, fu);
+    hipLaunchKernelGGL((gemm_pipe_kernel<G, WGM, WGN, FUSED, BM, BN, E8>), dim3(grid), dim3(64 * WGM * WGN), lds, stream, x,
+                       M, c, N, K, y, (int)m_tiles, (int)n_tiles, splits, partial, fu, sk);
     int rc = check_launch();
     if (rc != E0M4_OK || splits == 1) return rc;
     if (FUSED) {
@@ -553,11 +780,14 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
 
 bool gemm_pipe_supported(int64_t K) { return K >= 128 && (K % (2 * BK)) == 0; }
 
-size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu)
+// (`fused`: the call comes from a fused matmul or the 8-bit format, whose kernels keep whole tiles or the fixed K split)
+size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu, bool fused)
 {
     const PipeTile shape = pipe_tile(M, N, K);
     const int64_t tiles = pipe_tiles(shape, M, N, swiglu);
     if (tiles == 0 || !gemm_pipe_supported(K)) return 0;
+    const SkPlan skp = sk_plan(tiles, K, shape.bm, shape.bn, !fused && !swiglu);
+    if (skp.on) return skp.workspace_bytes;
     const int splits = choose_splits(tiles, K, shape.slots);
     return splits > 1 ? partial_bytes(splits, M, N) : 0;
 }

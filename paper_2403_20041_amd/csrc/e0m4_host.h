@@ -92,7 +92,7 @@ int launch_gemm_bf16(const void* X, int64_t M, const void* packed, int64_t N, in
 // MFMA path.
 int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                 void* workspace, size_t workspace_bytes, hipStream_t stream);
-size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu = false);
+size_t gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu = false, bool fused = false);
 // The same with the epilogue operators of `f` (residual add, gated product of the two halves of N);
 // rms-norm is not applied here: X must already be normalised.
 int launch_gemm_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group,
@@ -105,7 +105,7 @@ int launch_rmsnorm(const void* X, int64_t M, int64_t K, const void* gamma, float
 // fill the chip are split along K; the fp32 partial sums ([splits][M][N]) live in the caller's
 // workspace of gemm_pipe_workspace_bytes() bytes and a second kernel adds them.
 bool gemm_pipe_supported(int64_t K);
-size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu = false);
+size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu = false, bool fused = false);
 int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K, bool swiglu = false);      // tiles x K splits
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                      void* workspace, size_t workspace_bytes, hipStream_t stream);

@@ -20,7 +20,7 @@ def e0m4():
     import paper_2403_20041_amd as pkg
 
     pkg.lib()                                   # raises if the HIP library is not built
-    for k in ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits"):
+    for k in ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits", "gemm_sk"):
         pkg.e0m4_set_knob(k, 0)
     return pkg
 
@@ -414,6 +414,57 @@ def test_gemm_split_k_default_choice_and_reused_workspace(e0m4, oracle):
     rc = e0m4.lib().e0m4_matmul(Xd.data_ptr(), M, codes.data_ptr(), None, None, N, K, G, Y.data_ptr(), ws.data_ptr(),
                                need - 256, None)
     assert rc == -5
+
+
+# Even scheduling of the large-tile GEMM: the tiles beyond whole rounds of 256 are shared out by K ranges
+# among all workgroups, each writes fp32 sums to a slab of the workspace, and the last to arrive adds a
+# tile's slabs in K order.  Forced here on small problems (gemm_variant 2: the 256 x 256 tile; gemm_sk 1).
+@pytest.mark.parametrize("M,N,K,G", [
+    (300, 600, 1024, 128),      # 6 tiles x 8 slice pairs = 48 units on 256 workgroups: most have none, 8 sharers a tile
+    (513, 272, 384, 32),        # 6 tiles x 3 pairs
+    (256, 256, 128, 64),        # one tile, one pair: a single owner, written directly
+    (1024, 1040, 2048, 128),    # 20 tiles x 16 pairs = 320 units: ranges that end in one tile and begin in the next
+    (1000, 1300, 8192, 64),     # 24 tiles x 64 pairs: six pairs a workgroup, tiles shared by 10 or 11
+    (2304, 7680, 512, 128),     # 270 tiles: one whole tile each, then 14 tiles x 4 pairs shared out
+    (4096, 4112, 256, 128),     # 272 tiles (ragged last column), 16 tiles x 2 pairs shared out
+])
+def test_gemm_even_scheduling(e0m4, oracle, M, N, K, G):
+    W = synth_inputs.weights(N, K, seed=M + N, row_std_range=(0.5, 2.0))
+    X = synth_inputs.activations(M, K, seed=M + N + 1, outlier_frac=0.01)
+    codes, scales, bias = e0m4.e0m4_quantize(to_dev(W), G)
+    What = oracle.dequant(*oracle.quantize(W, G), G)
+    rng = np.random.default_rng(M)
+    rows = np.unique(np.concatenate([np.arange(0, M, 256), np.arange(255, M, 256), [M - 1],
+                                     rng.integers(0, M, size=24)]))
+    e0m4.e0m4_set_knob("gemm_variant", 2)
+    e0m4.e0m4_set_knob("gemm_sk", 1)
+    try:
+        need = e0m4.e0m4_workspace_bytes(M, N, K, G)
+        tiles = -(-M // 256) * -(-N // 256)
+        if tiles % 256 and tiles > 1:
+            assert need == 1024 + (256 + tiles % 256) * 256 * 256 * 4
+        ws = torch.full((max(need, 16),), 0xFF, dtype=torch.uint8, device=DEV)       # NaNs wherever a slab is read unwritten
+        Xd = to_dev(X)
+        Y1 = e0m4.e0m4_matmul(Xd, codes, scales, bias, N, K, G, workspace=ws).clone()
+        Y2 = e0m4.e0m4_matmul(Xd, codes, scales, bias, N, K, G, workspace=ws)       # counters and slabs left by the first call
+        torch.cuda.synchronize()
+        assert torch.equal(Y1.view(torch.int16), Y2.view(torch.int16)), "two runs differ"
+        y_ref, absdot = oracle.matmul(X[rows], What)
+        check_matmul(Y1[torch.from_numpy(rows).to(DEV)], y_ref, absdot, "even scheduling M=%d N=%d K=%d" % (M, N, K))
+        if need > 1024:
+            rc = e0m4.lib().e0m4_matmul(Xd.data_ptr(), M, codes.data_ptr(), None, None, N, K, G, Y2.data_ptr(),
+                                       ws.data_ptr(), need - 256, None)
+            assert rc == -5
+        # the rows not sampled: against the whole-tile kernel, whose sums differ by fp32 rounding order only
+        e0m4.e0m4_set_knob("gemm_sk", 2)
+        Y0 = e0m4.e0m4_matmul(Xd, codes, scales, bias, N, K, G)
+        torch.cuda.synchronize()
+        d = (Y1.float() - Y0.float()).abs()
+        bound = 2.0 ** -9 * Y0.float().abs() + 2.0 ** -6
+        assert bool((d <= bound).all()), "differs from the whole-tile kernel: %g" % float((d - bound).max())
+    finally:
+        e0m4.e0m4_set_knob("gemm_variant", 0)
+        e0m4.e0m4_set_knob("gemm_sk", 0)
 
 
 # ------------------------------------------------------------------ special inputs through both paths

@@ -51,11 +51,15 @@ def test_size_functions(L):
     assert L.e0m4_workspace_bytes(8, 151936, 4096, 128) == 0
     # 64 tiles of 256 x 256 on 256 compute units: 4 K splits, one fp32 [M, N] slab each
     assert L.e0m4_workspace_bytes(1024, 4096, 13696, 128) == 4 * 1024 * 4096 * 4
-    # the same tiles with K = 4096 would need short K splits: 256 tiles of 64 x 256 instead, split in two
-    assert L.e0m4_workspace_bytes(1024, 4096, 4096, 128) == 2 * 1024 * 4096 * 4
+    # the same tiles with K = 4096 would need short K splits: 256 tiles of 64 x 256 instead, one per compute unit, unsplit
+    assert L.e0m4_workspace_bytes(1024, 4096, 4096, 128) == 0
+    assert L.e0m4_workspace_bytes(512, 4096, 4096, 128) == 4 * 512 * 4096 * 4      # 128 such tiles: four splits
     # 128 rows: 36 tiles of 128 x 128, 8 K splits
     assert L.e0m4_workspace_bytes(128, 4608, 4096, 128) == 8 * 128 * 4608 * 4
-    assert L.e0m4_workspace_bytes(2048, 27392, 5120, 128) == 0          # enough tiles: no split
+    assert L.e0m4_workspace_bytes(2048, 32768, 5120, 128) == 0          # 1024 tiles, four whole rounds of 256: no split
+    # 856 tiles: three whole rounds, the other 88 shared out by K ranges: their counters, then one 256 x 256 fp32 slab for
+    # each compute unit and one more for each shared tile
+    assert L.e0m4_workspace_bytes(2048, 27392, 5120, 128) == 1024 + (256 + 88) * 256 * 256 * 4
     assert L.e0m4_workspace_bytes(1024, 4096, 4160, 64) == 0            # K not a multiple of 128: other kernel
 
 

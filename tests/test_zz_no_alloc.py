@@ -14,8 +14,9 @@ pytestmark = pytest.mark.gpu
 
 G = 128
 # (M, N, K): split-K GEMM with the large tile, the same with a smaller input, the flat tile, a decode call
-# (no scratch at all) and a GEMM with enough tiles to need none
-CALLS = [(1024, 1280, 4096), (640, 1040, 2048), (300, 520, 1024), (1, 1040, 2048), (512, 8192, 256)]
+# (no scratch at all), a GEMM with enough tiles to need none, and one whose 132 tiles are shared out evenly over the
+# compute units (counters and one fp32 slab per compute unit and per tile: 97 MiB of the array)
+CALLS = [(1024, 1280, 4096), (640, 1040, 2048), (300, 520, 1024), (1, 1040, 2048), (512, 8192, 256), (1024, 8448, 6400)]
 
 
 def test_static_scratch_matmul_matches_the_workspace_form(e0m4, oracle):
@@ -32,8 +33,9 @@ def test_static_scratch_matmul_matches_the_workspace_form(e0m4, oracle):
         got = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
         prepared.append((M, N, K, X, codes, want, got, need))
     assert prepared[0][7] > prepared[1][7] > prepared[2][7] > 0 and prepared[3][7] == 0
+    assert prepared[5][7] == 1024 + (256 + 132) * 256 * 256 * 4 <= e0m4.E0M4_STATIC_SCRATCH_BYTES
     # the first call on a device is the set-up call: it looks up the address of the library's scratch array
-    # (the runtime binds the array's 64 MiB to the device then); nothing after it may allocate
+    # (the runtime binds the array's 128 MiB to the device then); nothing after it may allocate
     M, N, K, X, codes, want, got, need = prepared[0]
     assert L.e0m4_matmul_static(X.data_ptr(), M, codes.data_ptr(), N, K, G, got.data_ptr(), stream) == 0
     torch.cuda.synchronize()
@@ -60,7 +62,7 @@ def test_static_scratch_matmul_rejects_what_does_not_fit(e0m4):
     p = ctypes.c_void_p(0x1000)
     M, N, K = 2048, 8192, 4096                          # 256 large tiles: no split by default ...
     assert e0m4.e0m4_workspace_bytes(M, N, K, G) == 0
-    e0m4.e0m4_set_knob("gemm_splits", 4)                # ... four slabs of 64 MiB when forced
+    e0m4.e0m4_set_knob("gemm_splits", 4)                # ... four slabs of 64 MiB when forced: twice the array
     try:
         assert e0m4.e0m4_workspace_bytes(M, N, K, G) > e0m4.E0M4_STATIC_SCRATCH_BYTES
         assert L.e0m4_matmul_static(p, M, p, N, K, G, p, None) == -5        # nothing was enqueued
