@@ -41,7 +41,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 matrix peak
 GROUP = 128
 SECTIONS = ("decode", "shapes", "cfg1", "prefill", "gemma", "d14b", "small_batch", "table1", "e0m8", "bf16", "fusion",
-            "kv", "cpu")
+            "kv", "cpu", "gemma_prefill", "d14b_prefill")
 
 
 def algorithmic_bytes(M, N, K, G):
@@ -76,7 +76,7 @@ def _short_kernel_name(n):
 
 
 OUR_KERNELS = (r"gemv_kernel|gemv_mfma_kernel|gemv_dq_kernel|gemm_pipe_kernel|gemm_kernel|splitk_reduce|rmsnorm_kernel|"
-               r"quantize_kernel|dequant_kernel|kv_append_kernel")
+               r"quantize_kernel|dequant_kernel|kv_append_kernel|zero_u32_kernel")
 
 
 def summarize(directory, last):
@@ -171,6 +171,11 @@ def main():
     if unknown:
         sys.exit("unknown section(s): %s" % ", ".join(sorted(unknown)))
     want.add("decode")                          # the headline value always runs
+    for model in ("gemma", "d14b"):             # "<model>_prefill": that model with its prefill GEMMs, whatever "prefill" says
+        if model + "_prefill" in want:
+            want.add(model)
+        elif "prefill" in want and model in want:
+            want.add(model + "_prefill")
 
     import torch
 
@@ -677,7 +682,7 @@ def main():
         cfg4["lm_head"] = hbm_roofline("gemv_kernel<G=128,M=1>", algorithmic_bytes(1, N, K, GROUP), hus,
                                        traffic_key="gemma_lm_head", N=N, K=K)
         del heads, c0, x, y
-        if "prefill" in want:
+        if "gemma_prefill" in want:
             pre, layer = prefill_shapes(gshapes, 512, GROUP, 21000, not args.no_library)
             cfg4["prefill_M512"] = {"per_shape": pre, "layer": layer}
         configs["cfg4_gemma2b"] = cfg4
@@ -696,7 +701,7 @@ def main():
                      "decode_per_shape": decode_per_shape(dshapes, both[G], G)}
             del both[G]
             torch.cuda.empty_cache()
-            if "prefill" in want:
+            if "d14b_prefill" in want:
                 pre, layer = prefill_shapes(dshapes, 2048, G, 31000 + G, not args.no_library and G == 128,
                                             "d14b_prefill_g%d" % G)
                 entry["prefill_M2048"] = {"per_shape": pre, "layer": layer}
