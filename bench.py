@@ -473,6 +473,31 @@ def main():
             sb["M=%d" % M] = row
         out["small_batch"] = {"workload": "ChatGLM2-6B shapes, 2 <= M <= 64, group %d; latency per launch, cold weights"
                                           % GROUP, "per_M": sb}
+        # groups of 64 on the 14B shapes (config 5's other group): each projection over six distinct weight copies
+        sb64 = {}
+        for p, (name, N, K) in enumerate(synth_inputs.DENSE_14B):
+            copies = []
+            for c in range(6):
+                W = synth_inputs.weights_device(N, K, 7300 + 10 * p + c, dev)
+                copies.append(e0m4.e0m4_quantize(W, 64, stream=stream)[0])
+                del W
+            for M in (1, 4, 16, 32):
+                xm = synth_inputs.activations_device(M, K, 7400 + M + K, dev)
+                ym = torch.empty((M, N), dtype=torch.float16, device=dev)
+                wsm = torch.empty(max(e0m4.e0m4_workspace_bytes(M, N, K, 64), 16), dtype=torch.uint8, device=dev)
+
+                def pass64():
+                    for cc in copies:
+                        e0m4.e0m4_matmul(xm, cc, None, None, N, K, 64, out=ym, workspace=wsm, stream=stream)
+
+                us = time_us(capture(pass64), 20) / len(copies)
+                sb64.setdefault("M=%d" % M, {})[name] = {"us": round(us, 3),
+                                                         "GBps": round(algorithmic_bytes(M, N, K, 64) / us / 1e3, 1)}
+                del xm, ym, wsm
+            del copies
+            torch.cuda.empty_cache()
+        out["small_batch_g64"] = {"workload": "14B shapes, group 64, M = 1, 4, 16, 32; latency per launch over six weight "
+                                              "copies in turn (185-470 MB)", "per_M": sb64}
 
     if "table1" in want:
         # the paper's Table 1: E0M4 against the INT4 twin, M = 1, weight [K, N] (same layout, launch shape and

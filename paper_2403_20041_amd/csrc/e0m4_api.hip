@@ -97,18 +97,26 @@ bool small_m_on_vector(int64_t M, int64_t N, int64_t K)
     if (M < 2 || !gemm_pipe_supported(K) || N > (int64_t)1 << 24) return true;
     return (double)M * (double)N * (double)K < 3.8e8;
 }
-// 17 <= M <= 32 on small weights: two launches of the small-batch matrix-core kernel (16 rows, then the rest)
-// instead of the GEMM, whose 64 x 256 tile with its split along K costs 13 - 20 us whatever M is.  Measured
-// 5 - 23 % faster up to 11008 x 4096 and 32768 x 2048, equal at 27392 x 4096, slower beyond and when the 16 rows
-// need phases along K; slower from M = 33 on (three launches).
-constexpr int64_t kChunkRows = 16, kChunkedMaxM = 32;
+// 17 <= M <= kChunkedMaxM on small weights: the small-batch matrix-core kernel on equal chunks of at most 16 rows,
+// dealt to the y dimension of one launch (the chunks of a workgroup's row blocks follow each other on a compute unit
+// or run side by side on the same XCD: the weights come from HBM once), instead of the GEMM, whose 64 x 256 tile with
+// its split along K costs 12 - 20 us whatever M is.  The launch takes about as long as one chunk times the rounds its
+// workgroups make on the 256 compute units (staging a chunk of X costs a workgroup more than its weights do):
+// 4608 x 4096 (144 workgroups) 7.3 us at M = 16, 11.9 at M = 32 and 12.1 at M = 48 (two rounds; GEMM 15.2 and 16.4),
+// 17.0 at M = 64 (three; GEMM 17.6); 4096 x 4096 (256 workgroups) 10.8 at M = 32 (GEMM 14.8), 15.0 at M = 48 (16.1),
+// 19.1 at M = 64 (four rounds; GEMM 17.1).  So: two rounds at most, or three on small weights.  Not when a chunk of X
+// needs phases along K.
+constexpr int64_t kChunkRows = 16, kChunkedMaxM = 64, kChunked8MaxM = 32;
+int row_chunks(int64_t M) { return (int)((M + kChunkRows - 1) / kChunkRows); }
+int64_t rows_per_chunk(int64_t M) { return (M + row_chunks(M) - 1) / row_chunks(M); }
 bool small_batch_in_chunks(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)
 {
-    return M > kChunkRows && M <= kChunkedMaxM && knob("gemv_mfma") != 1 && (double)N * (double)K <= 7e7 &&
-           gemv_mfma_whole_rows(f, kChunkRows, N, K, group);
+    if (M <= kChunkRows || M > kChunkedMaxM || knob("gemv_mfma") == 1 || (double)N * (double)K > 7e7) return false;
+    int64_t wgs = 0;
+    if (!gemv_mfma_whole_rows(f, rows_per_chunk(M), N, K, group, &wgs)) return false;
+    const int64_t rounds = (row_chunks(M) * wgs + 255) / 256;
+    return rounds <= 2 || (rounds == 3 && (double)N * (double)K <= 2e7);
 }
-// rows of the first launch: both launches get 2 to 16 rows, the second starts at a multiple of 8 rows
-int64_t first_chunk_rows(int64_t M) { return M - kChunkRows >= 2 ? kChunkRows : kChunkRows / 2; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Shape rules shared by all entry points.
@@ -323,13 +331,8 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
     if (use_gemv_mfma(M, N, K, group)) return launch_gemv_mfma(X, M, codes, N, K, Y, (hipStream_t)stream);
     if (use_gemv_dq(M, N, K, group)) return launch_gemv_dq(X, M, codes, N, K, group, Y, (hipStream_t)stream);
     if (small_m_on_vector(M, N, K)) return launch_gemv(X, M, codes, N, K, group, Y, (hipStream_t)stream);
-    if (small_batch_in_chunks(Fusion{}, M, N, K, group)) {
-        const int64_t m0 = first_chunk_rows(M);
-        rc = launch_gemv_mfma(X, m0, codes, N, K, Y, (hipStream_t)stream);
-        if (rc != E0M4_OK) return rc;
-        return launch_gemv_mfma(static_cast<const char*>(X) + m0 * K * 2, M - m0, codes, N, K,
-                                static_cast<char*>(Y) + m0 * N * 2, (hipStream_t)stream);
-    }
+    if (small_batch_in_chunks(Fusion{}, M, N, K, group))
+        return launch_gemv_mfma(X, M, codes, N, K, Y, (hipStream_t)stream, row_chunks(M));
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // the GEMM epilogue forms 32-bit offsets of up to 256 rows of Y
     if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
     return launch_gemm(X, M, codes, N, K, group, Y, workspace, workspace_bytes, (hipStream_t)stream);
@@ -373,15 +376,7 @@ int e0m4_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
     const int path = fused_path(f, M, N, K, group);
     if (path == 2) return launch_gemv_mfma_fused(f, X, M, codes, N, K, Y, st);
     if (path == 0) return launch_gemv_fused(f, X, M, codes, N, K, group, Y, st);
-    if (path == 3) {                                    // rows are independent, the rms-norm included
-        const int64_t m0 = first_chunk_rows(M), n_out = f.swiglu ? N / 2 : N;
-        rc = launch_gemv_mfma_fused(f, X, m0, codes, N, K, Y, st);
-        if (rc != E0M4_OK) return rc;
-        Fusion rest = f;
-        if (f.residual) rest.residual = static_cast<const char*>(f.residual) + m0 * n_out * 2;
-        return launch_gemv_mfma_fused(rest, static_cast<const char*>(X) + m0 * K * 2, M - m0, codes, N, K,
-                                      static_cast<char*>(Y) + m0 * n_out * 2, st);
-    }
+    if (path == 3) return launch_gemv_mfma_fused(f, X, M, codes, N, K, Y, st, row_chunks(M));      // rows are independent
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // 32-bit offsets in the GEMM epilogue
     const size_t nb = rms_gamma ? norm_bytes(M, K) : 0;
     const size_t need = nb + gemm_workspace_bytes(M, N, K, f.swiglu, true);
@@ -532,8 +527,8 @@ static bool e0m8_use_mfma_decode(int64_t M, int64_t N, int64_t K)
 // 512 x 4096 and larger weights 5 - 20 % slower).
 static bool small_batch8_in_chunks(const Fusion& f, int64_t M, int64_t N, int64_t K)
 {
-    return M > kChunkRows && M <= kChunkedMaxM && knob("gemv_mfma") != 1 && K <= 2048 && (double)N * (double)K <= 1e7 &&
-           gemv_mfma8_whole_rows(f, kChunkRows, N, K);
+    return M > kChunkRows && M <= kChunked8MaxM && knob("gemv_mfma") != 1 && K <= 2048 && (double)N * (double)K <= 1e7 &&
+           gemv_mfma8_whole_rows(f, rows_per_chunk(M), N, K);
 }
 
 static bool e0m8_use_gemm(int64_t M, int64_t N, int64_t K)
@@ -566,13 +561,8 @@ int e0m8_matmul(const void* X, int64_t M, const void* codes, int64_t N, int64_t 
     if (!X || !codes) return E0M4_ERR_NULL;
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
     if (e0m8_use_mfma_decode(M, N, K)) return launch_gemv_mfma8(X, M, codes, N, K, Y, (hipStream_t)stream);
-    if (small_batch8_in_chunks(Fusion{}, M, N, K)) {
-        const int64_t m0 = first_chunk_rows(M);
-        rc = launch_gemv_mfma8(X, m0, codes, N, K, Y, (hipStream_t)stream);
-        if (rc != E0M4_OK) return rc;
-        return launch_gemv_mfma8(static_cast<const char*>(X) + m0 * K * 2, M - m0, codes, N, K,
-                                 static_cast<char*>(Y) + m0 * N * 2, (hipStream_t)stream);
-    }
+    if (small_batch8_in_chunks(Fusion{}, M, N, K))
+        return launch_gemv_mfma8(X, M, codes, N, K, Y, (hipStream_t)stream, row_chunks(M));
     if (e0m8_use_gemm(M, N, K)) {
         if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
         return launch_gemm_pipe8(X, M, codes, N, K, Y, workspace, workspace_bytes, (hipStream_t)stream);
@@ -631,15 +621,7 @@ int e0m8_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
     const int path = fused_path8(f, M, N, K);
     if (path == 2) return launch_gemv_mfma8_fused(f, X, M, codes, N, K, Y, st);
     if (path == 0) return launch_gemv8_fused(f, X, M, codes, N, K, Y, st);
-    if (path == 3) {
-        const int64_t m0 = first_chunk_rows(M), n_out = f.swiglu ? N / 2 : N;
-        rc = launch_gemv_mfma8_fused(f, X, m0, codes, N, K, Y, st);
-        if (rc != E0M4_OK) return rc;
-        Fusion rest = f;
-        if (f.residual) rest.residual = static_cast<const char*>(f.residual) + m0 * n_out * 2;
-        return launch_gemv_mfma8_fused(rest, static_cast<const char*>(X) + m0 * K * 2, M - m0, codes, N, K,
-                                       static_cast<char*>(Y) + m0 * n_out * 2, st);
-    }
+    if (path == 3) return launch_gemv_mfma8_fused(f, X, M, codes, N, K, Y, st, row_chunks(M));
     if (path != 1) return E0M4_ERR_SHAPE;               // larger M needs K % 128 == 0 (GEMM kernels)
     const size_t nb = rms_gamma ? norm_bytes(M, K) : 0;
     const size_t need = nb + gemm_pipe_workspace_bytes(M, N, K, f.swiglu, true);

@@ -166,6 +166,9 @@ struct GemvFusion {
     int swiglu;
     uint32_t half_bytes;
     int64_t n_out;                                      // row length of Y and of the residual
+    // Small-batch matrix-core kernel only: more rows than one launch's 16 are dealt to the y dimension of the grid in
+    // chunks of the kernel's M argument; m_total is then the number of rows of X (0: a single chunk).
+    int m_total;
 };
 
 // Bytes between a gate row block and its up row block; the kernels add it to offsets inside a 2 GiB

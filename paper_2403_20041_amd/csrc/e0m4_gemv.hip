@@ -686,7 +686,7 @@ int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t
 
 GemvFusion make_gemv_fusion(const Fusion& f, int64_t N, int64_t K, int group)
 {
-    GemvFusion fu;
+    GemvFusion fu{};
     fu.gamma = static_cast<const half_t*>(f.gamma);
     fu.residual = static_cast<const half_t*>(f.residual);
     fu.eps = f.eps;

@@ -101,6 +101,17 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 {
     // (the arguments up to `late` fill the 14 scalar registers the launch can preload; N <= 2^31, K <= 2^20)
     const int64_t N = N32, K = K32;
+    // Row chunks: workgroups with blockIdx.y = c do rows c * M ... of X (rows are independent, the rms-norm and the
+    // epilogues included).  The chunks of one set of row blocks run one after the other on a compute unit, or side by
+    // side on two of the same XCD, so the second reads the weights from L2.
+    if (gridDim.y > 1) {
+        const int row0 = (int)blockIdx.y * M;
+        const int64_t ylen = (FUSED && fu.swiglu) ? fu.n_out : N;
+        X += (int64_t)row0 * K;
+        Y += (int64_t)row0 * ylen;
+        if (FUSED && fu.residual) fu.residual += (int64_t)row0 * ylen;
+        M = min(M, fu.m_total - row0);
+    }
     static_assert(!(PHASED && XREG), "a wavefront meets other k blocks in every phase");
     constexpr int kThreads = W * 64;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -661,10 +672,12 @@ int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packe
     const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED, XREG, E8, PHASED>),
                                       kLdsLimitBytes, lds_allowed);
     if (arc != E0M4_OK) return arc;
-    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8, PHASED>), dim3((unsigned)p.grid), dim3(W * 64), p.lds_bytes,
-                       stream, static_cast<const half_t*>(X), static_cast<const uint4*>(packed), static_cast<half_t*>(Y),
-                       (int)M, (uint32_t)N, (uint32_t)K, p.step_slots, p.step_item, p.rb_base, p.rb_rem, p.late,
-                       p.pieces_magic, p.kb_phase, p.pieces_magic_last, fu);
+    // (M: rows per chunk; fu.m_total: all rows, when there are several chunks)
+    const unsigned chunks = fu.m_total > 0 ? (unsigned)((fu.m_total + M - 1) / M) : 1u;
+    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8, PHASED>), dim3((unsigned)p.grid, chunks), dim3(W * 64),
+                       p.lds_bytes, stream, static_cast<const half_t*>(X), static_cast<const uint4*>(packed),
+                       static_cast<half_t*>(Y), (int)M, (uint32_t)N, (uint32_t)K, p.step_slots, p.step_item, p.rb_base,
+                       p.rb_rem, p.late, p.pieces_magic, p.kb_phase, p.pieces_magic_last, fu);
     return check_launch();
 }
 
@@ -701,14 +714,22 @@ bool gemv_mfma_supported(int64_t M, int64_t N, int64_t K, int group)
     return make_mfma_plan(M, N, K, p);
 }
 
-int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+// Rows per chunk when M rows go out in `chunks` equal chunks (the last may be shorter; never fewer than two rows for
+// the M and chunk counts the callers use: 17 ... 64 rows in ceil(M / 16) chunks).
+int64_t chunk_rows(int64_t M, int chunks) { return (M + chunks - 1) / chunks; }
+
+int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
+                     int chunks)
 {
     MfmaPlan p;
-    if (!make_mfma_plan(M, N, K, p)) return E0M4_ERR_SHAPE;
+    const int64_t mc = chunk_rows(M, chunks);
+    if (chunks < 1 || M - (chunks - 1) * mc < kMinM || !make_mfma_plan(mc, N, K, p)) return E0M4_ERR_SHAPE;
+    GemvFusion fu{};
+    fu.m_total = chunks > 1 ? (int)M : 0;
     switch (p.waves) {
-        case 4: return launch_mfma<4, false>(p, X, M, packed, N, K, Y, stream);
-        case 8: return launch_mfma<8, false>(p, X, M, packed, N, K, Y, stream);
-        default: return launch_mfma<16, false>(p, X, M, packed, N, K, Y, stream);
+        case 4: return launch_mfma<4, false>(p, X, mc, packed, N, K, Y, stream, fu);
+        case 8: return launch_mfma<8, false>(p, X, mc, packed, N, K, Y, stream, fu);
+        default: return launch_mfma<16, false>(p, X, mc, packed, N, K, Y, stream, fu);
     }
 }
 
@@ -743,11 +764,15 @@ int launch_mfma8(const MfmaPlan& p, const GemvFusion& fu, const void* X, int64_t
 }
 }  // namespace
 
-int launch_gemv_mfma8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream)
+int launch_gemv_mfma8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
+                      int chunks)
 {
     MfmaPlan p;
-    if (!make_mfma_plan(M, N, 2 * K, p, 1, true)) return E0M4_ERR_SHAPE;
-    return launch_mfma8<false>(p, GemvFusion{}, X, M, packed, N, K, Y, stream);
+    const int64_t mc = chunk_rows(M, chunks);
+    if (chunks < 1 || M - (chunks - 1) * mc < kMinM || !make_mfma_plan(mc, N, 2 * K, p, 1, true)) return E0M4_ERR_SHAPE;
+    GemvFusion fu{};
+    fu.m_total = chunks > 1 ? (int)M : 0;
+    return launch_mfma8<false>(p, fu, X, mc, packed, N, K, Y, stream);
 }
 
 bool gemv_mfma8_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K)
@@ -765,12 +790,16 @@ bool gemv_mfma8_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K)
 }
 
 int launch_gemv_mfma8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
-                            hipStream_t stream)
+                            hipStream_t stream, int chunks)
 {
     MfmaPlan p;
-    if (!gemv_mfma8_fused_supported(f, M, N, K) || !make_mfma_plan(M, N, 2 * K, p, f.swiglu ? 2 : 1, true))
+    const int64_t mc = chunk_rows(M, chunks);
+    if (chunks < 1 || M - (chunks - 1) * mc < kMinM || !gemv_mfma8_fused_supported(f, mc, N, K) ||
+        !make_mfma_plan(mc, N, 2 * K, p, f.swiglu ? 2 : 1, true))
         return E0M4_ERR_SHAPE;
-    return launch_mfma8<true>(p, make_gemv_fusion(f, N, 2 * K, kG), X, M, packed, N, K, Y, stream);
+    GemvFusion fu = make_gemv_fusion(f, N, 2 * K, kG);
+    fu.m_total = chunks > 1 ? (int)M : 0;
+    return launch_mfma8<true>(p, fu, X, mc, packed, N, K, Y, stream);
 }
 
 bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)
@@ -782,22 +811,29 @@ bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K,
     return make_mfma_plan(M, N, K, p, 2);
 }
 
-bool gemv_mfma_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)
+bool gemv_mfma_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K, int group, int64_t* workgroups)
 {
     MfmaPlan p;
-    return gemv_mfma_fused_supported(f, M, N, K, group) && make_mfma_plan(M, N, K, p, f.swiglu ? 2 : 1) && p.kb_phase == 0;
+    if (!gemv_mfma_fused_supported(f, M, N, K, group) || !make_mfma_plan(M, N, K, p, f.swiglu ? 2 : 1) || p.kb_phase != 0)
+        return false;
+    if (workgroups) *workgroups = p.grid;
+    return true;
 }
 
 int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
-                           hipStream_t stream)
+                           hipStream_t stream, int chunks)
 {
     MfmaPlan p;
-    if (!gemv_mfma_fused_supported(f, M, N, K, kG) || !make_mfma_plan(M, N, K, p, f.swiglu ? 2 : 1)) return E0M4_ERR_SHAPE;
-    const GemvFusion fu = make_gemv_fusion(f, N, K, kG);
+    const int64_t mc = chunk_rows(M, chunks);
+    if (chunks < 1 || M - (chunks - 1) * mc < kMinM || !gemv_mfma_fused_supported(f, mc, N, K, kG) ||
+        !make_mfma_plan(mc, N, K, p, f.swiglu ? 2 : 1))
+        return E0M4_ERR_SHAPE;
+    GemvFusion fu = make_gemv_fusion(f, N, K, kG);
+    fu.m_total = chunks > 1 ? (int)M : 0;
     switch (p.waves) {
-        case 4: return launch_mfma<4, true>(p, X, M, packed, N, K, Y, stream, fu);
-        case 8: return launch_mfma<8, true>(p, X, M, packed, N, K, Y, stream, fu);
-        default: return launch_mfma<16, true>(p, X, M, packed, N, K, Y, stream, fu);
+        case 4: return launch_mfma<4, true>(p, X, mc, packed, N, K, Y, stream, fu);
+        case 8: return launch_mfma<8, true>(p, X, mc, packed, N, K, Y, stream, fu);
+        default: return launch_mfma<16, true>(p, X, mc, packed, N, K, Y, stream, fu);
     }
 }
 

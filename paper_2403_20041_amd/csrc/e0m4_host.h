@@ -67,13 +67,16 @@ int launch_gemv_fused(const Fusion& f, const void* X, int64_t M, const void* pac
                       void* Y, hipStream_t stream);
 // Small-batch path on the matrix cores: 2 <= M <= 16, group 128, X must fit the LDS of one compute unit.
 bool gemv_mfma_supported(int64_t M, int64_t N, int64_t K, int group);
-int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream);
+// `chunks` > 1: M (17 ... 64) rows in that many equal chunks of at most 16 rows, dealt to the y dimension of one launch
+int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
+                     int chunks = 1);
 bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K, int group);
 // ... and all M rows of X fit the LDS at once (no phases along K)
-bool gemv_mfma_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K, int group);
+// (`workgroups`: the launch's grid, when it is)
+bool gemv_mfma_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K, int group, int64_t* workgroups = nullptr);
 bool gemv_mfma8_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K);
 int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
-                           hipStream_t stream);
+                           hipStream_t stream, int chunks = 1);
 // Small-batch path with the weight operand dequantised in registers: 2 <= M <= 64, any group (e0m4_gemv_dq.hip).
 // (`whole_rows`: all M rows of X fit the LDS at once, no phases along K)
 bool gemv_dq_supported(int64_t M, int64_t N, int64_t K, int group, bool* whole_rows = nullptr);
@@ -117,12 +120,13 @@ int launch_dequant8(const void* packed, int64_t N, int64_t K, void* W_out, void*
 int launch_gemm_pipe8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, void* workspace,
                       size_t workspace_bytes, hipStream_t stream);
 bool gemv_mfma8_supported(int64_t M, int64_t N, int64_t K);
-int launch_gemv_mfma8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream);
+int launch_gemv_mfma8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
+                      int chunks = 1);
 int launch_gemv8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                        hipStream_t stream);
 bool gemv_mfma8_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K);
 int launch_gemv_mfma8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
-                            hipStream_t stream);
+                            hipStream_t stream, int chunks = 1);
 int launch_gemm_pipe8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                             void* workspace, size_t workspace_bytes, hipStream_t stream);
 int launch_gemv8(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream);

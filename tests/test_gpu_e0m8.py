@@ -185,8 +185,8 @@ def test_decode_long_rows_and_row_chunks(e0m4, oracle):
 
 
 @pytest.mark.parametrize("M", [17, 21, 32])
-def test_small_batch_two_chunks_of_rows(e0m4, oracle, M):
-    # 17 <= M <= 32 on small weights: the small-batch kernel on 16 (M = 17: 8) rows, then on the rest; no workspace
+def test_small_batch_chunks_of_rows(e0m4, oracle, M):
+    # 17 <= M <= 32 on small weights: the small-batch kernel on two equal chunks of rows in one launch; no workspace
     for N, K, G, seed in ((333, 1152, 128, 770), (1000, 2048, 64, 771), (68, 192, 64, 772)):
         assert e0m4.e0m8_workspace_bytes(M, N, K, G) == 0
         run_matmul_case(e0m4, oracle, M, N, K, G, seed=seed + M, outliers=True)

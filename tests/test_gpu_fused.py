@@ -132,11 +132,11 @@ def test_small_batch_rows_longer_than_the_lds(e0m4, oracle, bits, norm, swiglu, 
 
 
 @pytest.mark.parametrize("norm,swiglu,res", COMBOS)
-@pytest.mark.parametrize("M", [17, 24, 32])
+@pytest.mark.parametrize("M", [17, 24, 32, 41, 64])
 @pytest.mark.parametrize("bits", [4, 8])
-def test_small_batch_two_chunks_of_rows(e0m4, oracle, bits, M, norm, swiglu, res):
-    # 17 <= M <= 32 on small weights: the small-batch kernel on 16 (or 8) rows, then on the rest; the second
-    # launch gets its rows of X, of the residual and of Y
+def test_small_batch_chunks_of_rows(e0m4, oracle, bits, M, norm, swiglu, res):
+    # 17 <= M <= 64 (8-bit: 32) on small weights: the small-batch kernel on equal chunks of at most 16 rows in one
+    # launch; every chunk gets its rows of X, of the residual and of Y
     run_fused(e0m4, oracle, M, 448, 1664, 128, seed=545 + M, norm=norm, swiglu=swiglu, res=res, bits=bits)
     run_fused(e0m4, oracle, M, 1088 if swiglu else 1000, 4096 if bits == 4 else 2048, 128, seed=546 + M, norm=norm,
               swiglu=swiglu, res=res, outliers=True, bits=bits)

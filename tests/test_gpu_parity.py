@@ -328,15 +328,15 @@ def test_small_batch_rows_longer_than_the_lds_forced_shapes(e0m4, oracle, waves,
         e0m4.e0m4_set_knob("gemv_workgroups", 0)
 
 
-@pytest.mark.parametrize("M", [17, 18, 25, 32])
-def test_small_batch_two_chunks_of_rows(e0m4, oracle, M):
-    # 17 <= M <= 32, group 128, small weights: two launches of the small-batch kernel (16 or 8 rows, then the
-    # rest) instead of the GEMM; no workspace
+@pytest.mark.parametrize("M", [17, 18, 25, 32, 33, 47, 48, 49, 64])
+def test_small_batch_chunks_of_rows(e0m4, oracle, M):
+    # 17 <= M <= 64, group 128, small weights: equal chunks of at most 16 rows of X, one per y index of a single
+    # launch of the small-batch kernel (M = 17: 9 + 8 rows, M = 49: 13 + 13 + 13 + 10), instead of the GEMM; no workspace
     for N, K, seed in ((333, 1152, 220), (1000, 4096, 221), (40, 128, 222)):
         assert e0m4.e0m4_workspace_bytes(M, N, K, 128) == 0
         run_matmul_case(e0m4, oracle, M, N, K, 128, seed=seed + M, outliers=True)
-    # not beyond 32 rows, not when 16 rows of X need phases along K
-    run_matmul_case(e0m4, oracle, 33, 333, 1152, 128, seed=223)
+    # not beyond 64 rows, not when a chunk of X needs phases along K
+    run_matmul_case(e0m4, oracle, 65, 333, 1152, 128, seed=223)
     run_matmul_case(e0m4, oracle, M, 130, 8192, 128, seed=224 + M)
 
 

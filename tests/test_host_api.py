@@ -196,7 +196,9 @@ def test_fused_matmul_validation_and_workspace(L):
     assert w(16, 4096, 16384, 128, 1, SWIGLU) == 0              # X longer than the LDS: still one kernel (K in phases)
     assert w(17, 4096, 16384, 128, 1, SWIGLU) > 0               # GEMM path: normalised copy of X
     assert w(24, 4096, 4096, 128, 1, NONE) == 0                 # two chunks of rows on the small-batch kernel
-    assert w(33, 4096, 4096, 128, 1, NONE) > 0
+    assert w(48, 4096, 4096, 128, 1, NONE) == 0                 # three chunks: three rounds of its 256 workgroups, small weights
+    assert w(64, 4096, 4096, 128, 1, NONE) > 0                  # four rounds: the GEMM, with its normalised copy of X
+    assert w(64, 4608, 4096, 128, 1, NONE) == 0                 # 144 workgroups: four chunks make three rounds
     assert L.e0m4_workspace_bytes(24, 4096, 4096, 128) == 0
     assert L.e0m4_workspace_bytes(24, 27392, 4096, 128) > 0     # large weights: the GEMM, split along K
     assert w(1024, 27392, 4096, 128, 1, SWIGLU) == 1024 * 4096 * 2         # normalised X; enough tiles, no K split
