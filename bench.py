@@ -594,7 +594,7 @@ def main():
                 del X, Y
             del bufs, cb, x, y
         out["e0m4_bf16"] = {"workload": "E0M4 on bfloat16 (group %d), ChatGLM2-6B shapes: M=1 latency per launch over cold "
-                                        "weights, M=1024 on the 128 x 128-tile MFMA kernel" % GROUP, "per_shape": bf}
+                                        "weights, M=1024 on the pipelined MFMA kernel in whole tiles (no workspace)" % GROUP, "per_shape": bf}
 
     if "fusion" in want:
         import torch.nn.functional as F

@@ -348,10 +348,14 @@ int launch_gemm(const void* X, int64_t M, const void* packed, int64_t N, int64_t
     }
 }
 
-// E0M4 on bfloat16, any M: the small-tile kernel with the bfloat16 operand path (no K split, no workspace).
+// E0M4 on bfloat16, any M: the pipelined kernel in whole tiles when K is a multiple of 128, else the small-tile kernel
+// with the bfloat16 operand path; no K split, no workspace.  (gemm_variant 1 forces the small-tile kernel, 2 to 4 the
+// pipelined kernel with that tile.)
 int launch_gemm_bf16(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                      hipStream_t stream)
 {
+    if (knob("gemm_variant") != 1 && gemm_pipe_bf16_pays(M, N, K))
+        return launch_gemm_pipe_bf16(X, M, packed, N, K, group, Y, stream);
     const half_t* x = static_cast<const half_t*>(X);
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);

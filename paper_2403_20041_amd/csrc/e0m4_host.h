@@ -112,6 +112,10 @@ size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu = 
 int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K, bool swiglu = false);      // tiles x K splits
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                      void* workspace, size_t workspace_bytes, hipStream_t stream);
+// The bfloat16 member on the same kernel, whole tiles only (no workspace); `pays`: enough tiles to fill the chip that way.
+bool gemm_pipe_bf16_pays(int64_t M, int64_t N, int64_t K);
+int launch_gemm_pipe_bf16(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
+                          hipStream_t stream);
 
 // 8-bit format (E0M8): offline side and decode kernel.
 int launch_quantize8(const void* W, int64_t N, int64_t K, int group, void* packed, void* scales, void* bias,

@@ -114,6 +114,45 @@ def test_bf16_gemm(e0m4, oracle, M, N, K, G):
     check_bf16_matmul(oracle, Y, Yref, absdot, "bf16 gemm M=%d N=%d K=%d" % (M, N, K))
 
 
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("M,N,K,G", [(300, 600, 1024, 128), (513, 272, 384, 32), (70, 1040, 2048, 64), (256, 256, 128, 64)])
+def test_bf16_gemm_every_kernel_and_tile(e0m4, oracle, variant, M, N, K, G):
+    # gemm_variant 1: the 128 x 128-tile kernel with both operands through LDS; 2, 3, 4: the pipelined kernel (weights
+    # dequantised in registers, in whole tiles) with its 256 x 256, 128 x 128 and 64 x 256 tile
+    codes, What, _ = assert_bf16_quantize_exact(e0m4, oracle, synth_inputs.weights_bf16(N, K, seed=3650 + N + K), G)
+    X = synth_inputs.activations_bf16(M, K, seed=3750 + M)
+    e0m4.e0m4_set_knob("gemm_variant", variant)
+    try:
+        Y = e0m4.e0m4_bf16_matmul(bf_dev(X), codes, N, K, G)
+        Y2 = e0m4.e0m4_bf16_matmul(bf_dev(X), codes, N, K, G)
+    finally:
+        e0m4.e0m4_set_knob("gemm_variant", 0)
+    Yref, absdot = oracle.bf16_matmul(X, What)
+    check_bf16_matmul(oracle, Y, Yref, absdot, "bf16 gemm variant %d M=%d N=%d K=%d" % (variant, M, N, K))
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16))
+
+
+def test_bf16_gemm_default_choice_with_many_tiles(e0m4, oracle):
+    # 5 x 26 tiles of 64 x 256: enough to fill the chip in whole tiles, so the pipelined kernel is the default;
+    # all of N on sampled rows, and one-hot rows that must reproduce the weights through the MFMA path
+    M, N, K, G = 300, 6656, 512, 128
+    codes, What, _ = assert_bf16_quantize_exact(e0m4, oracle, synth_inputs.weights_bf16(N, K, seed=3660), G)
+    X = synth_inputs.activations_bf16(M, K, seed=3760)
+    hot = {5: 17, 64: 300, 299: 511}
+    for m, k in hot.items():
+        X[m] = 0
+        X[m, k] = 0x3F80
+    Y = e0m4.e0m4_bf16_matmul(bf_dev(X), codes, N, K, G)
+    rows = np.array([0, 5, 63, 64, 65, 127, 128, 200, 255, 256, 299])
+    Yref, absdot = oracle.bf16_matmul(X[rows], What)
+    check_bf16_matmul(oracle, Y[torch.from_numpy(rows).to(DEV)], Yref, absdot, "bf16 gemm, pipelined by default")
+    Yb = bf_bits(Y)
+    for m, k in hot.items():
+        nz = (What[:, k] & 0x7FFF) != 0
+        assert np.array_equal(Yb[m][nz], What[:, k][nz])
+        assert not (Yb[m][~nz] & 0x7FFF).any()
+
+
 @pytest.mark.parametrize("M", [1, 4, 40])
 def test_bf16_one_hot_activations_reproduce_the_weights(e0m4, oracle, M):
     N, K, G = 96, 256, 64
