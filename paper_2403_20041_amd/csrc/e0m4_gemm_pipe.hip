@@ -484,6 +484,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
         __syncthreads();
         const int last = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(smem));
         if (!last) continue;
+        // (acquire at device scope: nothing this XCD's caches may still hold of these slabs from an earlier launch is
+        // used; the loads below are device-coherent besides)
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         // The last sharer: the tile's slabs (its own among them) added in K order, a quarter of the registers at a
         // time -- the accumulators are not needed any more, and this way the code shares nothing with the other
         // epilogues.  The loads are device-coherent: the other sharers ran on other XCDs, whose L2 this one cannot see.

@@ -449,6 +449,11 @@ def test_gemm_even_scheduling(e0m4, oracle, M, N, K, G):
         Y2 = e0m4.e0m4_matmul(Xd, codes, scales, bias, N, K, G, workspace=ws)       # counters and slabs left by the first call
         torch.cuda.synchronize()
         assert torch.equal(Y1.view(torch.int16), Y2.view(torch.int16)), "two runs differ"
+        # other activations through the same workspace: no slab of the calls before may be read in place of a new one
+        X3 = synth_inputs.activations(M, K, seed=M + N + 2, outlier_frac=0.01)
+        Y3 = e0m4.e0m4_matmul(to_dev(X3), codes, scales, bias, N, K, G, workspace=ws)
+        y3_ref, absdot3 = oracle.matmul(X3[rows], What)
+        check_matmul(Y3[torch.from_numpy(rows).to(DEV)], y3_ref, absdot3, "even scheduling, reused workspace")
         y_ref, absdot = oracle.matmul(X[rows], What)
         check_matmul(Y1[torch.from_numpy(rows).to(DEV)], y_ref, absdot, "even scheduling M=%d N=%d K=%d" % (M, N, K))
         if need > 1024:
