@@ -829,14 +829,6 @@ size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu, b
     return splits > 1 ? partial_bytes(splits, M, N) : 0;
 }
 
-int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K, bool swiglu)
-{
-    const PipeTile shape = pipe_tile(M, N, K);
-    const int64_t tiles = pipe_tiles(shape, M, N, swiglu);
-    if (tiles == 0 || !gemm_pipe_supported(K)) return 0;
-    return tiles * choose_splits(tiles, K, shape.slots);
-}
-
 namespace {
 
 template <int G, bool FUSED>

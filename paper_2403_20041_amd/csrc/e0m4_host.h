@@ -109,7 +109,6 @@ int launch_rmsnorm(const void* X, int64_t M, int64_t K, const void* gamma, float
 // workspace of gemm_pipe_workspace_bytes() bytes and a second kernel adds them.
 bool gemm_pipe_supported(int64_t K);
 size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu = false, bool fused = false);
-int64_t gemm_pipe_work_items(int64_t M, int64_t N, int64_t K, bool swiglu = false);      // tiles x K splits
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
                      void* workspace, size_t workspace_bytes, hipStream_t stream);
 // The bfloat16 member on the same kernel, whole tiles only (no workspace); `pays`: enough tiles to fill the chip that way.
