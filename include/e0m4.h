@@ -123,12 +123,17 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  *            every such M.  X is staged in the LDS of the compute unit, all
  *            of it (about M * K * 2 <= 140 KiB) or one part of K after the
  *            other; the weights are read once either way.
- *   17 <= M <= 32, group 128, N * K <= 7e7, 16 rows of X within the LDS:
- *            that kernel twice, on 16 (M = 17: 8) rows and on the rest.
+ *   3 <= M <= 16, group 32 or 64: the same on a kernel that dequantises the
+ *            weight operand in registers (when all of X fits the LDS, or M <= 8).
+ *   17 <= M <= 64, group 128, N * K <= 7e7, a chunk of X within the LDS:
+ *            that kernel on equal chunks of at most 16 rows in one launch,
+ *            when its workgroups make at most two rounds on the compute
+ *            units (three on small weights).
  *   M >= 9 otherwise, and 2 <= M <= 8 when M * N * K is about 3.8e8 or
  *            more (the vector kernel's time grows with M): MFMA GEMM path
  *            (tiles of 64 x 256 outputs up to M = 384 and for few large
- *            tiles, else 256 x 256; split along K when tiles are few).
+ *            tiles, else 256 x 256; split along K when tiles are few, a
+ *            partly filled last round of many tiles shared out evenly).
  *            e0m4_workspace_bytes() tells when a workspace is needed.
  * `scales_f16`/`bias_f16` may be NULL (see `codes` above); `workspace` may be
  * NULL when e0m4_workspace_bytes() is 0, else it is device memory of at least
@@ -243,7 +248,7 @@ int e0m4_kv_append(void* cache_f16, int64_t max_seq, int64_t row_elems,
  *     (and N <= 2^24): the MFMA GEMM kernels, workspace of
  *     e0m8_workspace_bytes() bytes under the rules of e0m4_matmul (17 <= M <=
  *     32 with K <= 2048 and N * K <= 1e7: the matrix-core variant on two
- *     chunks of rows instead).  Other M > 16:
+ *     chunks of rows in one launch instead).  Other M > 16:
  *     the decode kernel on 8 rows of X at a time (needs N % 8 == 0).
  * Pointer, alignment, stream and error rules as for the E0M4 entry points.
  */
@@ -288,8 +293,11 @@ int e0m3_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  * `codes` has the E0M4 layout and size (e0m4_codes_bytes; e0m4_unpack_codes
  * reads it), its embedded parameter words hold bfloat16 pairs.
  *   e0m4_bf16_matmul: M <= 8 the decode kernel with bfloat16 dot products
- *   (a shift and a mask-or per pair of codes), larger M an MFMA kernel with
- *   128 x 128 tiles that dequantises into LDS; no workspace.
+ *   (a shift and a mask-or per pair of codes), larger M the pipelined MFMA
+ *   kernel of e0m4_matmul with the weights dequantised in registers (fp32 fused
+ *   multiply-add, one rounding to bfloat16), in whole tiles (no workspace, so
+ *   no split along K); when K is not a multiple of 128 an MFMA kernel with
+ *   128 x 128 tiles that dequantises into LDS.
  * Shape, pointer, stream and error rules as for the E0M4 entry points.
  */
 int e0m4_bf16_quantize(const void* W_bf16, int64_t N, int64_t K, int group,
