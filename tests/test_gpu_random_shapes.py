@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 DEV = "cuda:0"
-KNOBS = ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits")
+KNOBS = ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits", "gemm_sk")
 
 
 @pytest.fixture(scope="module")
@@ -125,3 +125,52 @@ def test_random_shape_8bit(e0m4, oracle, case):
     Yref, info = oracle.matmul_fused(X, What, gamma=gamma, eps=1e-5, swiglu=swiglu, residual=R)
     torch.cuda.synchronize()
     check_fused(Y, Yref, info, swiglu, norm, "8-bit case %s" % (case,))
+
+
+def wide_cases(count, seed):
+    """Shapes of the paths the list above does not reach: 17 to 64 rows (row chunks in one launch) and GEMMs of many
+    tiles (whole rounds, the even scheduling of a partly filled last round, also forced on arbitrary shapes)."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        G = int(rng.choice([32, 64, 128]))
+        mode = i % 3
+        if mode == 0:
+            M, K = int(rng.choice([18, 24, 31, 40, 47, 48, 49, 63])), 128 * int(rng.integers(1, 40))
+            N = int(rng.choice([int(rng.integers(16, 400)), 64 * int(rng.integers(1, 80)), int(rng.integers(400, 12000))]))
+        elif mode == 1:
+            M, K = int(rng.choice([1024, 1100, 1536, 2048, 2304])), 128 * int(rng.integers(1, 12))
+            N = 256 * int(rng.integers(20, 60)) + int(rng.integers(0, 256))
+        else:
+            M, K, N = int(rng.integers(257, 1500)), 128 * int(rng.integers(1, 24)), int(rng.integers(100, 5000))
+        cases.append((i, M, N, K, G, mode == 2))
+    return cases
+
+
+WIDE = wide_cases(24, seed=20240329)
+
+
+@pytest.mark.parametrize("case", WIDE, ids=["%d-M%d-N%d-K%d-G%d%s" % (c[0], c[1], c[2], c[3], c[4], "-even" if c[5] else "")
+                                            for c in WIDE])
+def test_random_shape_wide(e0m4, oracle, case):
+    i, M, N, K, G, forced = case
+    rng = np.random.default_rng(i)
+    W = synth_inputs.weights(N, K, seed=9900 + i, row_std_range=(0.5, 2.0) if i % 2 else None)
+    X = synth_inputs.activations(M, K, seed=9950 + i, outlier_frac=0.01)
+    codes, scales, bias = e0m4.e0m4_quantize(to_dev(W), G)
+    What = oracle.dequant(*oracle.quantize(W, G), G)
+    rows = np.arange(M) if M * N * K <= 4e8 else np.unique(np.concatenate(
+        [np.arange(0, M, 256), np.arange(255, M, 256), [M - 1], rng.integers(0, M, size=10)]))
+    if forced:
+        e0m4.e0m4_set_knob("gemm_variant", 2)
+        e0m4.e0m4_set_knob("gemm_sk", 1)
+    try:
+        Y = e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G)
+    finally:
+        e0m4.e0m4_set_knob("gemm_variant", 0)
+        e0m4.e0m4_set_knob("gemm_sk", 0)
+    got = Y[torch.from_numpy(rows).to(DEV)].cpu().numpy().astype(np.float64)
+    Yref, absdot = oracle.matmul(X[rows], What)
+    err = np.abs(got - Yref.astype(np.float64))
+    assert (err <= 1e-2 * np.maximum(1.0, absdot)).all(), "case %s" % (case,)
+    assert (err <= 2.0 ** -9 * absdot + 2.0 ** -10 * np.abs(Yref.astype(np.float64)) + 1e-6).all(), "quality, case %s" % (case,)
