@@ -178,7 +178,25 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
         sk_rt = (int)sk_t0 + (seg - sk.rounds_dp);      // the range's first tile, then its second
         const uint32_t t_lo = (uint32_t)sk_rt * sk_pairs, t_hi = t_lo + sk_pairs;
         const uint32_t lo = sk_u0 > t_lo ? sk_u0 : t_lo, hi = sk_u1 < t_hi ? sk_u1 : t_hi;
-        seg_tile = sk.rounds_dp * (int)sk_grid + sk_rt;
+        // Which tile is shared-out tile number sk_rt: the shared tiles are the last rem_tiles of the column-by-column
+        // numbering (the tail of column c0 from row tile m_start on, then whole columns); they are taken row by row
+        // instead, so that the workgroups of one XCD, whose ranges are consecutive, are on tiles of the same rows of
+        // X at nearly the same K (consecutive tiles start 'units per workgroup' apart): the activations, four
+        // times the bytes of the weights, are then shared through that XCD's L2.
+        const uint32_t first_shared = (uint32_t)sk.rounds_dp * sk_grid, mt = (uint32_t)m_tiles;
+        const uint32_t c0 = first_shared / mt, m_start = first_shared - c0 * mt;
+        const uint32_t w_full = (uint32_t)n_tiles - 1 - c0;         // columns after c0: shared in every row tile
+        const uint32_t head = m_start * w_full;                     // shared tiles of the row tiles above m_start
+        uint32_t tm, tn;
+        if ((uint32_t)sk_rt < head) {
+            tm = (uint32_t)sk_rt / w_full;
+            tn = c0 + 1 + ((uint32_t)sk_rt - tm * w_full);
+        } else {
+            const uint32_t r = (uint32_t)sk_rt - head, q = r / (w_full + 1);
+            tm = m_start + q;
+            tn = c0 + (r - q * (w_full + 1));
+        }
+        seg_tile = (int)(tn * mt + tm);
         seg_kb = 2 * (int)(lo - t_lo);
         seg_ke = 2 * (int)(hi - t_lo);
         sk_first = sk_pos_of(t_lo);
@@ -703,8 +721,9 @@ size_t partial_bytes(int splits, int64_t M, int64_t N) { return (size_t)splits *
 // workgroups read different tiles or all the same one -- so it is not the memory side, and filling the idle units
 // buys 18 % more throughput, not 60 %.  And the slabs cost about 25 us a launch (12 us to store and publish them, 13
 // for the last sharers to add them up).  With M = 2048, G = 128: N = 27392, K = 5120 (856 tiles, 26 pairs saved)
-// 540 -> 525 us; N = 5120, K = 13696 (160 tiles, 40 saved) 290 -> 284 us; but N = 5120, K = 5120 (160 tiles, 15
-// saved) 113 -> 128 us and N = 15360, K = 5120 (480 tiles, 5 saved) 280 -> 308 us.
+// 547 -> 525 us; N = 5120, K = 13696 (160 tiles, 40 saved) 293 -> 275 us; but N = 5120, K = 5120 (160 tiles, 15
+// saved) 113 -> 133 us and N = 15360, K = 5120 (480 tiles, 5 saved) 286 -> 316 us.  (Shared tiles taken row by row,
+// see the kernel; column by column the first two were 525 and 284.)
 // gemm_sk 1 forces it whenever the last round is partly filled, 2 forbids it.
 constexpr int kSkMinTiles = 128;
 constexpr int kSkMinSavedPairs = 24;
