@@ -123,8 +123,11 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  *            every such M.  X is staged in the LDS of the compute unit, all
  *            of it (about M * K * 2 <= 140 KiB) or one part of K after the
  *            other; the weights are read once either way.
- *   3 <= M <= 16, group 32 or 64: the same on a kernel that dequantises the
- *            weight operand in registers (when all of X fits the LDS, or M <= 8).
+ *   3 <= M <= 16, group 32 or 64: the same kernel with every row of X staged
+ *            once per group of a block (M <= 8 at group 64, M <= 4 at group 32,
+ *            where a workgroup has several row blocks or the staged rows fit
+ *            the LDS), else a kernel that dequantises the weight operand in
+ *            registers (when all of X fits the LDS, or M <= 8).
  *   17 <= M <= 64, group 128, N * K <= 7e7, a chunk of X within the LDS:
  *            that kernel on equal chunks of at most 16 rows in one launch,
  *            when its workgroups make at most two rounds on the compute

@@ -67,9 +67,12 @@ __global__ void zero_fill_kernel(half_t* y, int64_t count)
 }
 
 bool group_ok(int group) { return group == 32 || group == 64 || group == 128; }
+// (gemv_mfma 1: off; 6: also for groups of 64 and 32 wherever it can run, which by default it does where it pays)
 bool use_gemv_mfma(int64_t M, int64_t N, int64_t K, int group)
 {
-    return knob("gemv_mfma") != 1 && gemv_mfma_supported(M, N, K, group);
+    const int k = knob("gemv_mfma");
+    if (k == 1 || !gemv_mfma_supported(M, N, K, group)) return false;
+    return group == 128 || k == 6 || gemv_mfma_groups_pay(M, N, K, group);
 }
 // The small-batch kernel with dequantised weight operands serves groups of 32 and 64 at 3 <= M <= 16 (the
 // group-128 kernel above cannot): measured against the vector kernel and the GEMM on layer shapes of 6B and 14B
@@ -201,7 +204,11 @@ static size_t norm_bytes(int64_t M, int64_t K) { return ((size_t)M * (size_t)K *
 // if any, as a launch of its own before them).
 static int fused_path(const Fusion& f, int64_t M, int64_t N, int64_t K, int group)
 {
-    if (knob("gemv_mfma") != 1 && gemv_mfma_fused_supported(f, M, N, K, group)) return 2;
+    // (groups of 64 and 32 from three rows on: 1.1 - 2 x the vector kernel and the GEMM there, 10 - 25 % slower than the
+    // vector kernel at two rows)
+    if (knob("gemv_mfma") != 1 && gemv_mfma_fused_supported(f, M, N, K, group) &&
+        (group == 128 || M >= 3 || knob("gemv_mfma") == 6))
+        return 2;
     if (small_batch_in_chunks(f, M, N, K, group)) return 3;
     return (small_m_on_vector(M, N, K) && gemv_fused_supported(f, M, N, K)) ? 0 : 1;
 }
@@ -328,11 +335,11 @@ int e0m4_matmul(const void* X, int64_t M, const void* codes, const void* scales,
     if (!aligned16(X) || !aligned16(codes)) return E0M4_ERR_ALIGN;
     if (knob("gemv_mfma") == 4 && use_gemv_dq(M, N, K, group))
         return launch_gemv_dq(X, M, codes, N, K, group, Y, (hipStream_t)stream);
-    if (use_gemv_mfma(M, N, K, group)) return launch_gemv_mfma(X, M, codes, N, K, Y, (hipStream_t)stream);
+    if (use_gemv_mfma(M, N, K, group)) return launch_gemv_mfma(X, M, codes, N, K, Y, (hipStream_t)stream, 1, group);
     if (use_gemv_dq(M, N, K, group)) return launch_gemv_dq(X, M, codes, N, K, group, Y, (hipStream_t)stream);
     if (small_m_on_vector(M, N, K)) return launch_gemv(X, M, codes, N, K, group, Y, (hipStream_t)stream);
     if (small_batch_in_chunks(Fusion{}, M, N, K, group))
-        return launch_gemv_mfma(X, M, codes, N, K, Y, (hipStream_t)stream, row_chunks(M));
+        return launch_gemv_mfma(X, M, codes, N, K, Y, (hipStream_t)stream, row_chunks(M), group);
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // the GEMM epilogue forms 32-bit offsets of up to 256 rows of Y
     if (workspace_bytes > 0 && (!workspace || !aligned16(workspace))) return workspace ? E0M4_ERR_ALIGN : E0M4_ERR_NULL;
     return launch_gemm(X, M, codes, N, K, group, Y, workspace, workspace_bytes, (hipStream_t)stream);
@@ -374,9 +381,9 @@ int e0m4_matmul_fused(const void* X, int64_t M, const void* rms_gamma, float rms
         return E0M4_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     const int path = fused_path(f, M, N, K, group);
-    if (path == 2) return launch_gemv_mfma_fused(f, X, M, codes, N, K, Y, st);
+    if (path == 2) return launch_gemv_mfma_fused(f, X, M, codes, N, K, Y, st, 1, group);
     if (path == 0) return launch_gemv_fused(f, X, M, codes, N, K, group, Y, st);
-    if (path == 3) return launch_gemv_mfma_fused(f, X, M, codes, N, K, Y, st, row_chunks(M));      // rows are independent
+    if (path == 3) return launch_gemv_mfma_fused(f, X, M, codes, N, K, Y, st, row_chunks(M), group);      // rows are independent
     if (N > (int64_t)1 << 24) return E0M4_ERR_SHAPE;    // 32-bit offsets in the GEMM epilogue
     const size_t nb = rms_gamma ? norm_bytes(M, K) : 0;
     const size_t need = nb + gemm_workspace_bytes(M, N, K, f.swiglu, true);

@@ -20,7 +20,15 @@
 // MFMAs consume it (one 16-byte unit per MFMA and lane); the two sums per (row of X, block) that the
 // factored form needs are MFMAs of the same operands with an all-ones weight operand.
 // One group of 128 k is one block, so the group's affine map  y += scale * (a - bias * sum x)  is
-// applied once per block on the MFMA result; that is why this kernel needs group size 128.
+// applied once per block on the MFMA result.
+//
+// Groups of 64 and 32 (GS = 2 or 4 groups per block; at most 8 or 4 rows of X).  A lane's 32 codes lie inside one
+// group (k-groups 2g and 2g + 1 of the block belong to group g of two, k-group g to group g of four), but an MFMA
+// adds all four k-groups.  So every row m of X is staged GS times, as row m + (16 / GS) * g with everything but the
+// k-groups of group g set to zero: the sixteen rows of the MFMA then hold, per group, the sums over that group
+// alone (the all-ones MFMAs likewise), the four output rows of a lane belong to one group, whose parameters the
+// lane picks, and the GS rows of a row of X are added when the wavefront sums are.  The loop over the weights is
+// the same as for one group per block.
 //
 // Long rows.  When M rows of X exceed the LDS, K is walked in phases: a phase stages its part of X,
 // visits that part of every row block of the workgroup and adds to the wavefront sums, which stay in
@@ -91,7 +99,7 @@ __device__ inline int x_unit_off(int q, int w, int hl) { return ((q * 4 + (w >> 
 // PHASED: M rows of X do not fit the LDS.  K is walked in phases of kb_phase blocks: every phase stages its
 // part of X, visits all row blocks of the workgroup and adds to the wavefront sums, which stay in LDS
 // (`late`) until the last phase.  The weights are still read exactly once.
-template <int W, bool FUSED, bool XREG, bool E8 = false, bool PHASED = false>
+template <int W, bool FUSED, bool XREG, bool E8 = false, bool PHASED = false, int GS = 1>
 __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restrict__ X,
                                                            const uint4* __restrict__ packed, half_t* __restrict__ Y,
                                                            int M, uint32_t N32, uint32_t K32, int step_slots_arg,
@@ -113,17 +121,22 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
         M = min(M, fu.m_total - row0);
     }
     static_assert(!(PHASED && XREG), "a wavefront meets other k blocks in every phase");
+    static_assert(GS == 1 || ((GS == 2 || GS == 4) && !E8 && !XREG), "several groups per block: 4-bit codes, X from LDS");
     constexpr int kThreads = W * 64;
+    constexpr int G = kG / GS;                          // group size
+    constexpr int PW = kPW * GS;                        // parameter words per block
+    constexpr int SLOT = kMaxM / GS;                    // MFMA rows per group (GS > 1): row m of X is rows m + SLOT * g
+    const int Ms = GS == 1 ? M : (GS - 1) * SLOT + M;   // staged rows of X
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int XBB = E8 ? kXBlockBytes / 2 : kXBlockBytes;   // bytes of X per row and block
     constexpr int UB = E8 ? 16 : 32;                            // bytes per (k-group, MFMA pair) unit of a block
-    const PackedLayout<kG> lay(E8 ? 2 * K : K);
+    const PackedLayout<G> lay(E8 ? 2 * K : K);
     const int nkb = (int)lay.nkb;
     const int nkb_lds = PHASED ? kb_phase : nkb;        // k blocks of X that the LDS holds at a time
     const int n_ph = PHASED ? (nkb + kb_phase - 1) / kb_phase : 1;
     const int row_stride = nkb_lds * XBB + kRowPadBytes;
     unsigned char* xs = smem;                                                   // [M] rows of X in MFMA order
-    float* norm_part = reinterpret_cast<float*>(smem + (size_t)M * row_stride); // [W][16] sums of squares, then [16] row scales
+    float* norm_part = reinterpret_cast<float*>(smem + (size_t)Ms * row_stride); // [W][16] sums of squares, then [16] row scales
     // wavefront sums: [2][W][16 m][16 n], reduced row block by row block; or, when `late` (LDS permitting),
     // [row blocks][W][M][16 n], reduced once at the end without a barrier per row block
     float* red = norm_part + kNormBytes / 4;
@@ -140,9 +153,9 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
     const int n_rb = (rb_base + ((int)blockIdx.x < rb_rem ? 1 : 0)) * (gated ? 2 : 1);
     const __amdgpu_buffer_rsrc_t wg_codes = make_rsrc(packed + lay.code_index(rb0, 0));
     const __amdgpu_buffer_rsrc_t wg_params = make_rsrc(reinterpret_cast<const char*>(packed) + 4 * lay.param_index(rb0, 0));
-    const uint32_t rb_stride = (uint32_t)nkb * block_bytes(kG);
+    const uint32_t rb_stride = (uint32_t)nkb * block_bytes(G);
     const uint32_t lane_code_off = lane * 16;
-    const int param_words_rb = nkb * kPW;
+    const int param_words_rb = nkb * PW;
     auto slot_off = [&](uint32_t s_) -> uint32_t {      // byte offset of row block slot s from the first row block
         if (FUSED && fu.swiglu) return (s_ >> 1) * rb_stride + (s_ & 1) * fu.half_bytes;
         return s_ * rb_stride;
@@ -164,14 +177,16 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 
     // ---- the work item in flight: four code blocks and their 64 parameter words (one per lane)
     uint4 c[kSuper];
-    uint32_t pwraw;
+    uint32_t pwraw[GS];                                 // the item's 64 * GS parameter words: word 64 n + lane in pwraw[n]
     auto fetch_params = [&](int fs, int fi) {           // past the end the last item is read again
         const bool in = fs < n_rb;
         const uint32_t s_ = in ? fs : n_rb - 1, i_ = in ? fi : nsi - 1;
-        const uint32_t first = (uint32_t)kb_lo * kPW + i_ * (kSuper * kPW);     // the item's first parameter word
+        const uint32_t first = (uint32_t)kb_lo * PW + i_ * (kSuper * PW);       // the item's first parameter word
         const uint32_t soff = __builtin_amdgcn_readfirstlane(slot_off(s_) + first * 4);
         const int last = param_words_rb - 1 - (int)first;
-        pwraw = __builtin_amdgcn_raw_buffer_load_b32(wg_params, min(lane, last) * 4, (int)soff, 0);
+#pragma unroll
+        for (int n = 0; n < GS; ++n)
+            pwraw[n] = __builtin_amdgcn_raw_buffer_load_b32(wg_params, min(n * 64 + lane, last) * 4, (int)soff, 0);
     };
     auto fetch_code = [&](int j, int fs, int fi) {      // k blocks beyond K: the last block again (left out of the sums)
         const bool in = fs < n_rb;
@@ -314,10 +329,15 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
             *reinterpret_cast<half8_t*>(xs + (size_t)m * row_stride + kb * XBB + q * 2 * UB + wp * UB) = v;
         } else {
             const int kb = pc >> 4, q = (pc >> 2) & 3, w = pc & 3;
-            unsigned char* blk = xs + (size_t)m * row_stride + kb * XBB;
             const half4_t hpart = {v[0], v[1], v[6], v[7]}, lpart = {v[2], v[3], v[4], v[5]};
-            *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 0)) = hpart;
-            *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 1)) = lpart;
+            const half4_t none = {0, 0, 0, 0};
+#pragma unroll
+            for (int g = 0; g < GS; ++g) {              // (GS > 1: the piece in the row of its own group, zeros in the others)
+                const bool own = GS == 1 || g == q * GS / 4;
+                unsigned char* blk = xs + (size_t)(m + SLOT * g) * row_stride + kb * XBB;
+                *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 0)) = own ? hpart : none;
+                *reinterpret_cast<half4_t*>(blk + x_unit_off(q, w, 1)) = own ? lpart : none;
+            }
         }
     };
     for (int ph = 0; ph < n_ph; ++ph) {
@@ -394,7 +414,8 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
 
         // X operand address of this lane: row min(l%16, M-1) (rows beyond M repeat the last one; their
         // results are never stored), k-group l/16
-        const unsigned char* x_lane = xs + (size_t)min(n_l, M - 1) * row_stride + g_l * 2 * UB;
+        const int x_row = GS == 1 ? min(n_l, M - 1) : (n_l / SLOT) * SLOT + min(n_l % SLOT, M - 1);
+        const unsigned char* x_lane = xs + (size_t)x_row * row_stride + g_l * 2 * UB;
 
         half8_t xreg_h[XREG ? kSuper : 1][2], xreg_l[XREG ? kSuper : 1][2];
         if (XREG) {
@@ -435,7 +456,10 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
                 // parameter word of (block j, weight row n_l): lane 16 j + n_l of the item's 64 words
                 uint32_t pwj[kSuper];
 #pragma unroll
-                for (int j = 0; j < kSuper; ++j) pwj[j] = (uint32_t)__builtin_amdgcn_ds_bpermute((j * kPW + n_l) * 4, (int)pwraw);
+                for (int j = 0; j < kSuper; ++j) {       // (GS > 1: of the group that this lane's four output rows belong to)
+                    const int word = j * PW + (g_l * GS / 4) * kBlockRows + n_l;
+                    pwj[j] = (uint32_t)__builtin_amdgcn_ds_bpermute((word & 63) * 4, (int)pwraw[GS == 1 ? 0 : (j * PW) / 64]);
+                }
                 fetch_params(nslot, nitem);
 #pragma unroll
                 for (int j = 0; j < kSuper; ++j) {
@@ -500,8 +524,8 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
             if (late) {                                 // (a cell belongs to one wavefront, which adds later phases to it)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float* cell = red + ((s_rb * W + wave) * M + 4 * g_l + r) * kBlockRows + n_l;
-                    if (4 * g_l + r < M) *cell = PHASED && ph > 0 ? *cell + ysum[r] : ysum[r];
+                    float* cell = red + ((s_rb * W + wave) * Ms + 4 * g_l + r) * kBlockRows + n_l;
+                    if ((GS == 1 ? 4 * g_l + r : (4 * g_l + r) % SLOT) < M) *cell = PHASED && ph > 0 ? *cell + ysum[r] : ysum[r];
                 }
                 continue;
             }
@@ -517,10 +541,13 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
                     const int m = t >> 4, n = t & 15;
                     float g = 0.f, u = 0.f;
 #pragma unroll
-                    for (int w = 0; w < W; ++w) {
-                        g += red[((0 * W + w) * kMaxM + m) * kBlockRows + n];
-                        u += red[((1 * W + w) * kMaxM + m) * kBlockRows + n];
-                    }
+                    for (int w = 0; w < W; ++w)
+#pragma unroll
+                        for (int gg = 0; gg < GS; ++gg) {   // (the GS rows of a row of X; rows beyond M are not used)
+                            const int mr = min(m + SLOT * gg, kMaxM - 1);
+                            g += red[((0 * W + w) * kMaxM + mr) * kBlockRows + n];
+                            u += red[((1 * W + w) * kMaxM + mr) * kBlockRows + n];
+                        }
                     const int64_t col = (rb0 + (s_rb >> 1)) * kBlockRows + n;
                     if (m < M && col < fu.n_out) {
                         float y = silu_f32(g) * u;
@@ -540,7 +567,10 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
                 const int m = t >> 4, n = t & 15;
                 float s = 0.f;
 #pragma unroll
-                for (int w = 0; w < W; ++w) s += red[(((s_rb & 1) * W + w) * kMaxM + m) * kBlockRows + n];
+                for (int w = 0; w < W; ++w)
+#pragma unroll
+                    for (int gg = 0; gg < GS; ++gg)
+                        s += red[(((s_rb & 1) * W + w) * kMaxM + min(m + SLOT * gg, kMaxM - 1)) * kBlockRows + n];
                 const int64_t row = (rb0 + s_rb) * kBlockRows + n;
                 if (FUSED && fu.residual && m < M && row < N) s += (float)fu.residual[(int64_t)m * N + row];
                 if (m < M && row < N) Y[(int64_t)m * N + row] = (half_t)s;
@@ -557,11 +587,15 @@ __global__ __launch_bounds__(W * 64) void gemv_mfma_kernel(const half_t* __restr
             const int sl = gated ? 2 * u : u;
             float v = 0.f;
 #pragma unroll
-            for (int w = 0; w < W; ++w) v += red[((sl * W + w) * M + m) * kBlockRows + n];
+            for (int w = 0; w < W; ++w)
+#pragma unroll
+                for (int gg = 0; gg < GS; ++gg) v += red[((sl * W + w) * Ms + m + SLOT * gg) * kBlockRows + n];
             if (gated) {
                 float up = 0.f;
 #pragma unroll
-                for (int w = 0; w < W; ++w) up += red[(((sl + 1) * W + w) * M + m) * kBlockRows + n];
+                for (int w = 0; w < W; ++w)
+#pragma unroll
+                    for (int gg = 0; gg < GS; ++gg) up += red[(((sl + 1) * W + w) * Ms + m + SLOT * gg) * kBlockRows + n];
                 v = silu_f32(v) * up;
             }
             const int64_t n_out = gated ? fu.n_out : N;
@@ -622,8 +656,14 @@ bool make_phased_plan(int64_t M, int64_t nrb, int64_t nkb, MfmaPlan& p, int unit
 
 // `unit`: 2 when row blocks are dealt in (gate, up) pairs; rb_base and rb_rem then count pairs
 // (e8: K counts 4-bit slots, two per weight, and a block of X is half as long)
-bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, bool e8 = false)
+// Groups per block of a group size, and the rows of X the kernel stages for M rows (see the kernel's header).
+int groups_per_block(int group) { return kG / group; }
+int64_t staged_rows(int64_t M, int gs) { return gs == 1 ? M : (gs - 1) * (kMaxM / gs) + M; }
+
+// (`gs`: groups per block; every LDS size below is for the staged rows)
+bool make_mfma_plan(int64_t M_rows, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, bool e8 = false, int gs = 1)
 {
+    const int64_t M = staged_rows(M_rows, gs);
     const int64_t nrb = row_blocks(N) / unit, nkb = k_blocks(K);
     const int64_t nsi = (nkb + kSuper - 1) / kSuper;
     int w = knob("gemv_waves");
@@ -663,18 +703,18 @@ bool make_mfma_plan(int64_t M, int64_t N, int64_t K, MfmaPlan& p, int unit = 1, 
     return true;
 }
 
-template <int W, bool FUSED, bool XREG, bool E8 = false, bool PHASED = false>
+template <int W, bool FUSED, bool XREG, bool E8 = false, bool PHASED = false, int GS = 1>
 int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                   hipStream_t stream, const GemvFusion& fu)
 {
     if (PHASED != (p.kb_phase > 0) || (PHASED && !p.late) || p.lds_bytes > (size_t)kLdsLimitBytes) return E0M4_ERR_SHAPE;
     static std::atomic<uint64_t> lds_allowed{0};
-    const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED, XREG, E8, PHASED>),
+    const int arc = allow_dynamic_lds(reinterpret_cast<const void*>(&gemv_mfma_kernel<W, FUSED, XREG, E8, PHASED, GS>),
                                       kLdsLimitBytes, lds_allowed);
     if (arc != E0M4_OK) return arc;
     // (M: rows per chunk; fu.m_total: all rows, when there are several chunks)
     const unsigned chunks = fu.m_total > 0 ? (unsigned)((fu.m_total + M - 1) / M) : 1u;
-    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8, PHASED>), dim3((unsigned)p.grid, chunks), dim3(W * 64),
+    hipLaunchKernelGGL((gemv_mfma_kernel<W, FUSED, XREG, E8, PHASED, GS>), dim3((unsigned)p.grid, chunks), dim3(W * 64),
                        p.lds_bytes, stream, static_cast<const half_t*>(X), static_cast<const uint4*>(packed),
                        static_cast<half_t*>(Y), (int)M, (uint32_t)N, (uint32_t)K, p.step_slots, p.step_item, p.rb_base,
                        p.rb_rem, p.late, p.pieces_magic, p.kb_phase, p.pieces_magic_last, fu);
@@ -682,12 +722,12 @@ int launch_mfma_x(const MfmaPlan& p, const void* X, int64_t M, const void* packe
 }
 
 // K in phases (plans with kb_phase > 0; they have eight or sixteen wavefronts)
-template <int W, bool FUSED, bool E8>
+template <int W, bool FUSED, bool E8, int GS = 1>
 int launch_mfma_phased(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
                        hipStream_t stream, const GemvFusion& fu)
 {
     if constexpr (W >= 8)
-        return launch_mfma_x<W, FUSED, false, E8, true>(p, X, M, packed, N, K, Y, stream, fu);
+        return launch_mfma_x<W, FUSED, false, E8, true, GS>(p, X, M, packed, N, K, Y, stream, fu);
     else
         return E0M4_ERR_SHAPE;
 }
@@ -695,10 +735,20 @@ int launch_mfma_phased(const MfmaPlan& p, const void* X, int64_t M, const void* 
 // Activations in registers when a wavefront always meets the same k blocks (step_item == 0); the kernel
 // then needs about 125 registers per lane -- more than sixteen wavefronts have without spilling (that form measured
 // twice as slow as reading X from LDS), so it is used with up to eight.
+template <int W, bool FUSED, int GS>
+int launch_mfma_groups(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
+                       hipStream_t stream, const GemvFusion& fu)
+{
+    if (p.kb_phase > 0) return launch_mfma_phased<W, FUSED, false, GS>(p, X, M, packed, N, K, Y, stream, fu);
+    return launch_mfma_x<W, FUSED, false, false, false, GS>(p, X, M, packed, N, K, Y, stream, fu);
+}
+
 template <int W, bool FUSED>
 int launch_mfma(const MfmaPlan& p, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
-                hipStream_t stream, const GemvFusion& fu = GemvFusion{})
+                hipStream_t stream, const GemvFusion& fu = GemvFusion{}, int gs = 1)
 {
+    if (gs == 2) return launch_mfma_groups<W, FUSED, 2>(p, X, M, packed, N, K, Y, stream, fu);
+    if (gs == 4) return launch_mfma_groups<W, FUSED, 4>(p, X, M, packed, N, K, Y, stream, fu);
     if (p.kb_phase > 0) return launch_mfma_phased<W, FUSED, false>(p, X, M, packed, N, K, Y, stream, fu);
     if (p.step_item == 0 && W <= 8 && knob("gemv_mfma") != 2)
         return launch_mfma_x<W, FUSED, true>(p, X, M, packed, N, K, Y, stream, fu);
@@ -709,27 +759,45 @@ int launch_mfma(const MfmaPlan& p, const void* X, int64_t M, const void* packed,
 
 bool gemv_mfma_supported(int64_t M, int64_t N, int64_t K, int group)
 {
-    if (group != kG || M < kMinM || M > kMaxM || N <= 0 || K <= 0) return false;
+    if ((group != 128 && group != 64 && group != 32) || M < kMinM || M > kMaxM / groups_per_block(group) || N <= 0 || K <= 0)
+        return false;
     MfmaPlan p;
-    return make_mfma_plan(M, N, K, p);
+    return make_mfma_plan(M, N, K, p, 1, false, groups_per_block(group));
 }
 
 // Rows per chunk when M rows go out in `chunks` equal chunks (the last may be shorter; never fewer than two rows for
 // the M and chunk counts the callers use: 17 ... 64 rows in ceil(M / 16) chunks).
 int64_t chunk_rows(int64_t M, int chunks) { return (M + chunks - 1) / chunks; }
 
+// Groups of 64 and 32 stage every row of X two or four times (16 rows of LDS traffic whatever M is), which the
+// kernel with dequantised operands (e0m4_gemv_dq.hip) does not: this one pays when a workgroup has several row
+// blocks to spend its staging on, or (group 64) when the staged rows fit the LDS at once.  15360 x 5120 at M = 4:
+// 12.4 us against 16.2; 27392 x 5120 at M = 8: 22.6 against 26.5; 5120 x 5120 at M = 4 7.5 against 8.8 but at
+// M = 8, in phases, 11.1 against 9.5; 5120 x 13696 at M = 4, in phases, 18.9 against 16.8; at M = 2 the vector
+// kernel is as fast or faster.
+bool gemv_mfma_groups_pay(int64_t M, int64_t N, int64_t K, int group)
+{
+    const int gs = groups_per_block(group);
+    MfmaPlan p;
+    if (gs == 1 || M < 3 || !gemv_mfma_supported(M, N, K, group) || !make_mfma_plan(M, N, K, p, 1, false, gs)) return false;
+    return p.rb_base >= 3 || (gs == 2 && p.kb_phase == 0);
+}
+
 int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
-                     int chunks)
+                     int chunks, int group)
 {
     MfmaPlan p;
     const int64_t mc = chunk_rows(M, chunks);
-    if (chunks < 1 || M - (chunks - 1) * mc < kMinM || !make_mfma_plan(mc, N, K, p)) return E0M4_ERR_SHAPE;
+    const int gs = groups_per_block(group);
+    if (chunks < 1 || M - (chunks - 1) * mc < kMinM || !gemv_mfma_supported(mc, N, K, group) ||
+        !make_mfma_plan(mc, N, K, p, 1, false, gs))
+        return E0M4_ERR_SHAPE;
     GemvFusion fu{};
     fu.m_total = chunks > 1 ? (int)M : 0;
     switch (p.waves) {
-        case 4: return launch_mfma<4, false>(p, X, mc, packed, N, K, Y, stream, fu);
-        case 8: return launch_mfma<8, false>(p, X, mc, packed, N, K, Y, stream, fu);
-        default: return launch_mfma<16, false>(p, X, mc, packed, N, K, Y, stream, fu);
+        case 4: return launch_mfma<4, false>(p, X, mc, packed, N, K, Y, stream, fu, gs);
+        case 8: return launch_mfma<8, false>(p, X, mc, packed, N, K, Y, stream, fu, gs);
+        default: return launch_mfma<16, false>(p, X, mc, packed, N, K, Y, stream, fu, gs);
     }
 }
 
@@ -808,32 +876,34 @@ bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K,
     if (!f.swiglu) return true;
     if (N % (2 * kBlockRows) != 0 || gated_half_bytes(N, K, group) > kMaxHalfBytes) return false;
     MfmaPlan p;
-    return make_mfma_plan(M, N, K, p, 2);
+    return make_mfma_plan(M, N, K, p, 2, false, groups_per_block(group));
 }
 
 bool gemv_mfma_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K, int group, int64_t* workgroups)
 {
     MfmaPlan p;
-    if (!gemv_mfma_fused_supported(f, M, N, K, group) || !make_mfma_plan(M, N, K, p, f.swiglu ? 2 : 1) || p.kb_phase != 0)
+    if (!gemv_mfma_fused_supported(f, M, N, K, group) ||
+        !make_mfma_plan(M, N, K, p, f.swiglu ? 2 : 1, false, groups_per_block(group)) || p.kb_phase != 0)
         return false;
     if (workgroups) *workgroups = p.grid;
     return true;
 }
 
 int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
-                           hipStream_t stream, int chunks)
+                           hipStream_t stream, int chunks, int group)
 {
     MfmaPlan p;
     const int64_t mc = chunk_rows(M, chunks);
-    if (chunks < 1 || M - (chunks - 1) * mc < kMinM || !gemv_mfma_fused_supported(f, mc, N, K, kG) ||
-        !make_mfma_plan(mc, N, K, p, f.swiglu ? 2 : 1))
+    const int gs = groups_per_block(group);
+    if (chunks < 1 || M - (chunks - 1) * mc < kMinM || !gemv_mfma_fused_supported(f, mc, N, K, group) ||
+        !make_mfma_plan(mc, N, K, p, f.swiglu ? 2 : 1, false, gs))
         return E0M4_ERR_SHAPE;
-    GemvFusion fu = make_gemv_fusion(f, N, K, kG);
+    GemvFusion fu = make_gemv_fusion(f, N, K, group);
     fu.m_total = chunks > 1 ? (int)M : 0;
     switch (p.waves) {
-        case 4: return launch_mfma<4, true>(p, X, mc, packed, N, K, Y, stream, fu);
-        case 8: return launch_mfma<8, true>(p, X, mc, packed, N, K, Y, stream, fu);
-        default: return launch_mfma<16, true>(p, X, mc, packed, N, K, Y, stream, fu);
+        case 4: return launch_mfma<4, true>(p, X, mc, packed, N, K, Y, stream, fu, gs);
+        case 8: return launch_mfma<8, true>(p, X, mc, packed, N, K, Y, stream, fu, gs);
+        default: return launch_mfma<16, true>(p, X, mc, packed, N, K, Y, stream, fu, gs);
     }
 }
 

@@ -65,18 +65,20 @@ int launch_gemv(const void* X, int64_t M, const void* packed, int64_t N, int64_t
 bool gemv_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K);
 int launch_gemv_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group,
                       void* Y, hipStream_t stream);
-// Small-batch path on the matrix cores: 2 <= M <= 16, group 128, X must fit the LDS of one compute unit.
+// Small-batch path on the matrix cores: 2 <= M <= 16 at group 128, 8 at group 64, 4 at group 32.
 bool gemv_mfma_supported(int64_t M, int64_t N, int64_t K, int group);
+// ... and, for groups of 64 and 32, whether it is expected to beat the kernel with dequantised operands
+bool gemv_mfma_groups_pay(int64_t M, int64_t N, int64_t K, int group);
 // `chunks` > 1: M (17 ... 64) rows in that many equal chunks of at most 16 rows, dealt to the y dimension of one launch
 int launch_gemv_mfma(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y, hipStream_t stream,
-                     int chunks = 1);
+                     int chunks = 1, int group = 128);
 bool gemv_mfma_fused_supported(const Fusion& f, int64_t M, int64_t N, int64_t K, int group);
 // ... and all M rows of X fit the LDS at once (no phases along K)
 // (`workgroups`: the launch's grid, when it is)
 bool gemv_mfma_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K, int group, int64_t* workgroups = nullptr);
 bool gemv_mfma8_whole_rows(const Fusion& f, int64_t M, int64_t N, int64_t K);
 int launch_gemv_mfma_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
-                           hipStream_t stream, int chunks = 1);
+                           hipStream_t stream, int chunks = 1, int group = 128);
 // Small-batch path with the weight operand dequantised in registers: 2 <= M <= 64, any group (e0m4_gemv_dq.hip).
 // (`whole_rows`: all M rows of X fit the LDS at once, no phases along K)
 bool gemv_dq_supported(int64_t M, int64_t N, int64_t K, int group, bool* whole_rows = nullptr);

@@ -132,6 +132,22 @@ def test_small_batch_rows_longer_than_the_lds(e0m4, oracle, bits, norm, swiglu, 
 
 
 @pytest.mark.parametrize("norm,swiglu,res", COMBOS)
+@pytest.mark.parametrize("G,M", [(64, 2), (64, 5), (64, 8), (32, 3), (32, 4)])
+def test_small_batch_groups_of_64_and_32_fused(e0m4, oracle, G, M, norm, swiglu, res):
+    # groups of 64 and 32 on the matrix-core small-batch kernel (rows of X staged once per group of a block): the
+    # default for the fused matmul at 3 <= M <= 8 (group 64) and 3 <= M <= 4 (group 32), forced at M = 2; whole rows,
+    # and K in phases
+    e0m4.e0m4_set_knob("gemv_mfma", 6)
+    try:
+        run_fused(e0m4, oracle, M, 320, 1152, G, seed=569 + M + G, norm=norm, swiglu=swiglu, res=res)
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+    run_fused(e0m4, oracle, M, 448, 1664, G, seed=570 + M + G, norm=norm, swiglu=swiglu, res=res, outliers=True)
+    run_fused(e0m4, oracle, M, 1088, 2048, G, seed=571 + M + G, norm=norm, swiglu=swiglu, res=res, row_std=(0.5, 2.0))
+    run_fused(e0m4, oracle, M, 192, 8192, G, seed=572 + M + G, norm=norm, swiglu=swiglu, res=res)
+
+
+@pytest.mark.parametrize("norm,swiglu,res", COMBOS)
 @pytest.mark.parametrize("M", [17, 24, 32, 41, 64])
 @pytest.mark.parametrize("bits", [4, 8])
 def test_small_batch_chunks_of_rows(e0m4, oracle, bits, M, norm, swiglu, res):

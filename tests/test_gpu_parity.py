@@ -416,6 +416,63 @@ def test_gemm_split_k_default_choice_and_reused_workspace(e0m4, oracle):
     assert rc == -5
 
 
+# Groups of 64 and 32 on the group-128 small-batch kernel: every row of X staged once per group of a block, masked to
+# that group's k (gemv_mfma 6 sends every shape it can run to it: M <= 8 at group 64, M <= 4 at group 32).
+@pytest.mark.parametrize("M,N,K,G", [
+    (2, 200, 1152, 64), (5, 200, 1152, 64), (8, 200, 1152, 64), (8, 333, 4096, 64), (3, 1000, 2048, 64),
+    (8, 130, 8192, 64), (6, 64, 16384, 64),             # 16 staged rows longer than the LDS: K in phases
+    (2, 200, 1152, 32), (4, 200, 1152, 32), (3, 333, 4096, 32), (4, 130, 8192, 32), (4, 48, 16384, 32),
+    (7, 5000, 640, 64), (4, 5000, 640, 32),             # many row blocks per workgroup, ragged last k block
+])
+def test_small_batch_groups_of_64_and_32_on_the_group_128_kernel(e0m4, oracle, M, N, K, G):
+    e0m4.e0m4_set_knob("gemv_mfma", 6)
+    try:
+        assert e0m4.e0m4_workspace_bytes(M, N, K, G) == 0
+        run_matmul_case(e0m4, oracle, M, N, K, G, seed=600 + M + N // 7 + K // 128 + G, outliers=True, row_std=(0.5, 2.0))
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+
+
+@pytest.mark.parametrize("waves,target", [(4, 0), (8, 3), (16, 0), (16, 3)])
+@pytest.mark.parametrize("G,M", [(64, 7), (32, 4)])
+def test_small_batch_groups_forced_shapes(e0m4, oracle, G, M, waves, target):
+    e0m4.e0m4_set_knob("gemv_mfma", 6)
+    e0m4.e0m4_set_knob("gemv_waves", waves)
+    e0m4.e0m4_set_knob("gemv_workgroups", target)
+    try:
+        run_matmul_case(e0m4, oracle, M, 1000, 2432, G, seed=620 + waves + target + G)
+        run_matmul_case(e0m4, oracle, M, 160, 8192, G, seed=630 + waves + target + G)      # phases
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+        e0m4.e0m4_set_knob("gemv_waves", 0)
+        e0m4.e0m4_set_knob("gemv_workgroups", 0)
+
+
+@pytest.mark.parametrize("G,M", [(64, 8), (64, 3), (32, 4)])
+def test_small_batch_groups_one_hot_rows_reproduce_the_weights(e0m4, oracle, G, M):
+    # one-hot rows of X at k in different groups of one block: each must return that column of the dequantised
+    # weights bit for bit -- a row staged under the wrong group's mask, or folded with the wrong group's
+    # parameters, cannot
+    N, K = 300, 1024
+    W = synth_inputs.weights(N, K, seed=640 + G, row_std_range=(0.5, 2.0))
+    codes, scales, bias = e0m4.e0m4_quantize(to_dev(W), G)
+    What = oracle.dequant(*oracle.quantize(W, G), G)
+    ks = [(m * 37 + 5 + 128 * m + (G // 2) * (m % (128 // G))) % K for m in range(M)]
+    X = np.zeros((M, K), dtype=np.float16)
+    for m, k in enumerate(ks):
+        X[m, k] = 1.0
+    e0m4.e0m4_set_knob("gemv_mfma", 6)
+    try:
+        Y = bits(e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G))
+    finally:
+        e0m4.e0m4_set_knob("gemv_mfma", 0)
+    for m, k in enumerate(ks):
+        want = What[:, k].view(np.uint16)
+        nz = (want & 0x7FFF) != 0
+        assert np.array_equal(Y[m][nz], want[nz]), "row %d, k %d" % (m, k)
+        assert not (Y[m][~nz] & 0x7FFF).any()
+
+
 # Even scheduling of the large-tile GEMM: the tiles beyond whole rounds of 256 are shared out by K ranges
 # among all workgroups, each writes fp32 sums to a slab of the workspace, and the last to arrive adds a
 # tile's slabs in K order.  Forced here on small problems (gemm_variant 2: the 256 x 256 tile; gemm_sk 1).
