@@ -78,10 +78,11 @@ struct PipeFusion {
 //     at most the tail of one tile and the head of the next.
 // A tile that several workgroups share is finished by whichever of them arrives last: every sharer stores its
 // fp32 partial sums to a slab of the workspace (slabs of the sharers of a tile are consecutive, in K order) with
-// write-through stores, one thread orders them ahead of the counter (release fence) and adds one to the tile's counter; the one that brings the counter
-// to the number of sharers reads all slabs back with device-coherent loads, adds them in K order -- a fixed order,
-// whoever does it -- and writes the tile.  Nobody waits for anybody, so a workgroup that is never scheduled next to
-// the others cannot stall them.  The counters are zeroed by a small kernel before the launch.
+// write-through stores, one thread orders them ahead of the counter (release fence) and adds one to the tile's
+// counter; the one that brings the counter to the number of sharers reads all slabs back (acquire, device-coherent
+// loads), adds them in K order -- a fixed order, whoever does it -- and writes the tile.  Nobody waits for anybody,
+// so a workgroup that is never scheduled next to the others cannot stall them.  The counters are zeroed by a small
+// kernel before the launch.  The shared-out tiles are numbered row by row (see the kernel).
 struct SkArgs {
     int enabled;
     int rounds_dp;                                      // whole tiles per workgroup
