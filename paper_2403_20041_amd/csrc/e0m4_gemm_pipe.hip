@@ -457,6 +457,18 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
     const uint32_t off0 = (uint32_t)row0 * n32 + (uint32_t)col0;
     auto store_tile = [&](auto* __restrict__ dst) {     // dst: element (m0, n0) of a row-major [M, N] array
         using out_t = std::remove_reference_t<decltype(*dst)>;
+        if (rows_left >= BM && cols_left >= BN) {       // a whole tile (uniform): stores without per-element masks
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int dr = 32 * i + 8 * (r >> 2) + (r & 3);
+                        dst[off0 + (uint32_t)dr * n32 + 32 * j] = out_value<out_t>(acc[i][j][r]);
+                    }
+            return;
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             if (col0 + 32 * j < cols_left) {
