@@ -74,8 +74,8 @@ bool use_gemv_mfma(int64_t M, int64_t N, int64_t K, int group)
     if (k == 1 || !gemv_mfma_supported(M, N, K, group)) return false;
     return group == 128 || k == 6 || gemv_mfma_groups_pay(M, N, K, group);
 }
-// The small-batch kernel with dequantised weight operands serves groups of 32 and 64 at 3 <= M <= 16 (the
-// group-128 kernel above cannot): measured against the vector kernel and the GEMM on layer shapes of 6B and 14B
+// The small-batch kernel with dequantised weight operands serves groups of 32 and 64 at 3 <= M <= 16 where the
+// kernel above does not run (more than 8 or 4 rows) or does not pay: measured against the vector kernel and the GEMM on layer shapes of 6B and 14B
 // models it is 20 - 45 % faster for 4 <= M <= 8 whatever K is, and for 9 <= M <= 16 when all of X fits the LDS
 // (4608 x 4096 at M = 16: 8.9 against 13.2 us); with K in phases at those M it equals or loses to the GEMM
 // (15360 x 5120 at M = 16: 22.9 against 20.2 us), and at M = 2 the vector kernel is faster.  It runs up to 64
