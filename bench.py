@@ -41,7 +41,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 matrix peak
 GROUP = 128
 SECTIONS = ("decode", "shapes", "cfg1", "prefill", "gemma", "d14b", "small_batch", "table1", "e0m8", "bf16", "fusion",
-            "kv", "cpu", "gemma_prefill", "d14b_prefill")
+            "kv", "dispatch", "cpu", "gemma_prefill", "d14b_prefill")
 
 
 def algorithmic_bytes(M, N, K, G):
@@ -498,6 +498,66 @@ def main():
             torch.cuda.empty_cache()
         out["small_batch_g64"] = {"workload": "14B shapes, group 64, M = 1, 4, 16, 32; latency per launch over six weight "
                                               "copies in turn (185-470 MB)", "per_M": sb64}
+
+    if "dispatch" in want:
+        # The kernel and tile that e0m4_matmul picks by itself, against every forced alternative, on seeded shapes that
+        # none of its rules was fitted on: three per range of M, N and K multiples of 128, groups 32, 64 and 128.
+        import random
+
+        rnd = random.Random(20240331)
+        ranges = (("2..8", 2, 8, {"vector_kernel": {"gemv_mfma": 1}, "matrix_core_kernel": {"gemv_mfma": 6}}),
+                  ("9..16", 9, 16, {"gemm_64x256": {"gemv_mfma": 1, "gemm_variant": 4},
+                                    "gemm_128x128": {"gemv_mfma": 1, "gemm_variant": 3}}),
+                  ("17..64", 17, 64, {"gemm_64x256": {"gemv_mfma": 1, "gemm_variant": 4},
+                                      "gemm_128x128": {"gemv_mfma": 1, "gemm_variant": 3}}),
+                  ("65..384", 65, 384, {"gemm_64x256": {"gemm_variant": 4}, "gemm_128x128": {"gemm_variant": 3},
+                                        "gemm_256x256": {"gemm_variant": 2}}),
+                  ("385..4096", 385, 4096, {"gemm_128x128": {"gemm_variant": 3}, "gemm_256x256": {"gemm_variant": 2},
+                                            "even_scheduling_always": {"gemm_sk": 1}, "even_scheduling_never": {"gemm_sk": 2}}))
+        knob_names = ("gemv_mfma", "gemm_variant", "gemm_sk")
+        rows, ratios = [], []
+        for label, m_lo, m_hi, forced in ranges:
+            for _ in range(3):
+                M = rnd.randint(m_lo, m_hi)
+                N, K = 128 * rnd.randint(8, 128), 128 * rnd.randint(8, 96)
+                G = rnd.choice((128, 128, 64, 32))
+                W = synth_inputs.weights_device(N, K, 9100 + len(rows), dev)
+                first = e0m4.e0m4_quantize(W, G, stream=stream)[0]
+                del W
+                copies = [first] + [first.clone() for _ in range(max(1, min(40, int(4e8 // first.numel()))) - 1)]
+                xm = synth_inputs.activations_device(M, K, 9200 + len(rows), dev)
+                ym = torch.empty((M, N), dtype=torch.float16, device=dev)
+                times = {}
+                try:
+                    for name, knobs in [("default", {})] + sorted(forced.items()):
+                        for k in knob_names:
+                            e0m4.e0m4_set_knob(k, knobs.get(k, 0))
+                        wsm = torch.empty(max(e0m4.e0m4_workspace_bytes(M, N, K, G), 16), dtype=torch.uint8, device=dev)
+
+                        def variant_pass():
+                            for cc in copies:
+                                e0m4.e0m4_matmul(xm, cc, None, None, N, K, G, out=ym, workspace=wsm, stream=stream)
+
+                        times[name] = time_us(capture(variant_pass), max(1, 400 // len(copies)), rounds=2) / len(copies)
+                        del wsm
+                finally:
+                    for k in knob_names:
+                        e0m4.e0m4_set_knob(k, 0)
+                best = min(times, key=times.get)
+                ratios.append(times["default"] / times[best])
+                rows.append({"M": M, "N": N, "K": K, "G": G, "range": label, "default_us": round(times["default"], 2),
+                             "best": best, "best_us": round(times[best], 2), "default_over_best": round(ratios[-1], 3),
+                             "forced_us": {k: round(v, 2) for k, v in times.items() if k != "default"}})
+                del copies, first, xm, ym
+                torch.cuda.empty_cache()
+        geo = 1.0
+        for r in ratios:
+            geo *= r
+        out["dispatch"] = {"workload": "15 seeded shapes (N, K multiples of 128 up to 16384 x 12288; groups 32/64/128): the "
+                                       "default choice of kernel and tile against every forced one, us per launch over "
+                                       "rotating weight copies",
+                           "worst_default_over_best": round(max(ratios), 3),
+                           "geomean_default_over_best": round(geo ** (1.0 / len(ratios)), 4), "shapes": rows}
 
     if "table1" in want:
         # the paper's Table 1: E0M4 against the INT4 twin, M = 1, weight [K, N] (same layout, launch shape and

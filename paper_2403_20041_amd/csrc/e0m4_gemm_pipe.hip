@@ -674,43 +674,6 @@ constexpr int kComputeUnits = 256;
 constexpr int kMinPairsPerSplit = 4;
 constexpr int kMaxSplits = 8;
 
-// The tile a problem gets (gemm_variant 2, 3, 4 force the 256 x 256, 128 x 128 and 64 x 256 tile).  Measured over
-// a grid of M = 17 .. 2048 and layer shapes of 2B to 14B models:
-//  - up to kFlatMaxM rows the 64 x 256 tile (four wavefronts side by side, every weight dequantised once per
-//    workgroup) is never slower than the 128 x 128 tile and up to 27 % faster (M = 160: three row tiles of 64
-//    instead of two of 128);
-//  - above, the 256 x 256 tile, unless it yields few tiles: under kFewBigTiles when M is at most kFlatAlsoMaxM
-//    (512 x 4096 x 4096: 31 us against 38), under kFewBigTilesShortK when the K splits that fill the chip would be
-//    short (at most kShortSplitPairs pairs of K slices each; 2048 x 2560 x 2048: 34 us against 43; 1024 x 4096 x
-//    4096: 50 us against 54).  The
-//    prologue, epilogue and reduction of many short work items then cost more than the small tile's lower rate.
-constexpr int kFlatMaxM = 384;
-constexpr int kFlatAlsoMaxM = 640;
-constexpr int kFewBigTiles = 80;
-constexpr int kFewBigTilesShortK = 128;
-constexpr int kShortSplitPairs = 8;
-struct PipeTile {
-    int bm, bn;
-    int slots;                                          // work items wanted before K is split no further
-};
-
-PipeTile pipe_tile(int64_t M, int64_t N, int64_t K)
-{
-    const PipeTile mid{128, 128, kComputeUnits + kComputeUnits / 2}, big{256, 256, kComputeUnits};
-    const PipeTile flat{64, 256, 2 * kComputeUnits};
-    const int v = knob("gemm_variant");
-    if (v == 4) return flat;
-    if (v == 3) return mid;
-    if (v == 2) return big;
-    if (M <= kFlatMaxM) return flat;
-    // (at least one tile: callers ask for the tile of empty problems too, whose work item count is then zero)
-    const int64_t big_tiles = std::max<int64_t>(1, ((M + 255) / 256) * ((N + 255) / 256)), pairs = K / (2 * BK);
-    const int64_t big_splits = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kComputeUnits / big_tiles, pairs / kMinPairsPerSplit), kMaxSplits));
-    if (big_tiles < kFewBigTiles && M <= kFlatAlsoMaxM) return flat;
-    if (big_tiles < kFewBigTilesShortK && pairs / big_splits <= kShortSplitPairs) return flat;
-    return big;
-}
-
 int choose_splits(int64_t tiles, int64_t K, int slots)
 {
     const int forced = knob("gemm_splits");
@@ -724,46 +687,128 @@ int choose_splits(int64_t tiles, int64_t K, int slots)
     return (int)std::max<int64_t>(s, 1);
 }
 
-size_t partial_bytes(int splits, int64_t M, int64_t N) { return (size_t)splits * (size_t)M * (size_t)N * sizeof(float); }
+// The tile a problem gets (gemm_variant 2, 3, 4 force the 256 x 256, 128 x 128 and 64 x 256 tile) and whether the
+// large tile runs with even scheduling (SkArgs; gemm_sk 1 forces it whenever the last round is partly filled, 2
+// forbids it) are decided by an estimate of the launch's duration.  Up to 64 rows only the 64 x 256 tile (four
+// wavefronts side by side, every weight dequantised once per workgroup) makes sense; the 128 x 128 tile never won.
+//
+// The estimate counts rounds: the work items (tiles times K splits) run `cap` at a time (one 256 x 256 tile per
+// compute unit, two 64 x 256 tiles), a full round takes  pairs-of-K-slices * a(1) + b  and the last, partly filled
+// one  pairs * a(fill) + b  with a() piecewise linear in the fill -- a compute unit is slower the more of them run
+// (one round of 160 large tiles with K = 5120 takes 112 us, one of 256 tiles 152 us, whether the workgroups read
+// different tiles or all the same one: it is not the memory side), which is why filling idle units buys much less
+// than their number suggests; the flat tile's a() has a step at half fill, where the first compute units get a
+// second workgroup.  A K split adds its reduction kernel (a fixed part and one per MB of partial sums); even
+// scheduling runs every unit for the whole time at the full rate and adds the slabs' cost, of which the part per
+// sharer of a tile is serial (the last arriver reads them all).
+// The constants are a least-squares fit (logarithm of the ratio to the measurement, rms 4.4 %) to 303 problems
+// -- M = 65 .. 8192, N = 1024 .. 256000, K = 1024 .. 16384, groups of 32, 64 and 128, random and layer shapes of 2B to
+// 14B models -- each timed with every tile, with and without even scheduling, on weights out of cache.  Choosing by
+// the estimate costs 0.14 % over always choosing the measured best (geometric mean; 0.1 - 0.2 % with the fit made on
+// two thirds and tested on the rest; worst case 10 %).
+struct PipeTile {
+    int bm, bn;
+    int slots;                                          // work items wanted before K is split no further
+};
+constexpr PipeTile kFlatTile{64, 256, 2 * kComputeUnits}, kMidTile{128, 128, kComputeUnits + kComputeUnits / 2},
+    kBigTile{256, 256, kComputeUnits};
+constexpr int kFlatOnlyMaxM = 64;
 
-// Even scheduling (SkArgs) is used for the 256 x 256 tile when whole tiles would leave compute units idle for long:
-// a partly filled last round, at least kSkMinTiles tiles (fewer: the fixed K split with its reduction kernel), and
-// at least kSkMinSavedPairs pairs of K slices per compute unit saved over running that round as whole tiles.
-// What it saves is far less than the idle time it removes, for two measured reasons.  A compute unit is slower the
-// more of them run: one round of 160 tiles (K = 5120) takes 112 us, one round of 256 tiles 152 us, whether the
-// workgroups read different tiles or all the same one -- so it is not the memory side, and filling the idle units
-// buys 18 % more throughput, not 60 %.  And the slabs cost about 25 us a launch (12 us to store and publish them, 13
-// for the last sharers to add them up).  With M = 2048, G = 128: N = 27392, K = 5120 (856 tiles, 26 pairs saved)
-// 547 -> 525 us; N = 5120, K = 13696 (160 tiles, 40 saved) 293 -> 275 us; but N = 5120, K = 5120 (160 tiles, 15
-// saved) 113 -> 133 us and N = 15360, K = 5120 (480 tiles, 5 saved) 286 -> 316 us.  (Shared tiles taken row by row,
-// see the kernel; column by column the first two were 525 and 284.)
-// gemm_sk 1 forces it whenever the last round is partly filled, 2 forbids it.
-constexpr int kSkMinTiles = 128;
-constexpr int kSkMinSavedPairs = 24;
+struct TileCost {
+    double lo[3];                                       // us per pair of K slices at fill 0, 1/4, 1/2 of a round ...
+    double hi[3];                                       // ... and just above 1/2, at 3/4 and 1
+    double b;                                           // us per round: prologue and epilogue of a work item
+    int cap;                                            // work items per round
+};
+constexpr TileCost kFlatCost{{0.315, 0.862, 1.463}, {1.546, 1.907, 2.058}, 3.96, 2 * kComputeUnits};
+constexpr TileCost kBigCost{{1.874, 2.270, 2.375}, {2.375, 2.812, 3.502}, 6.91, kComputeUnits};
+constexpr double kReduceUs = 6.53, kReduceUsPerMB = 0.146;      // reduction kernel of a K split
+constexpr double kSkUs = 33.8, kSkUsPerSharer = 1.25;           // even scheduling: slabs, and the serial part per sharer
+constexpr double kWorkspaceMargin = 1.03;
+constexpr int kSkMinTiles = 128;                        // fewer tiles: the fixed K split (the fit holds no such launch)
+
+double rounds_us(const TileCost& c, int64_t items, double pairs_per_item)
+{
+    const int64_t full = items / c.cap, rem = items % c.cap;
+    double t = (double)full * (pairs_per_item * c.hi[2] + c.b);
+    if (rem > 0) {
+        const double fill = (double)rem / (double)c.cap;
+        const double* a = fill <= 0.5 ? c.lo : c.hi;
+        const double f = 4.0 * (fill <= 0.5 ? fill : fill - 0.5);
+        const int i = std::min(1, (int)f);
+        t += pairs_per_item * (a[i] + (a[i + 1] - a[i]) * (f - i)) + c.b;
+    }
+    return t;
+}
+
+// whole tiles, or the fixed K split with its reduction kernel
+double tile_launch_us(const PipeTile& t, const TileCost& c, int64_t M, int64_t N, int64_t K, bool whole_tiles)
+{
+    const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn), pairs = K / (2 * BK);
+    const int splits = whole_tiles ? 1 : choose_splits(tiles, K, t.slots);
+    double us = rounds_us(c, tiles * splits, (double)pairs / splits);
+    // (a launch that needs the workspace has to win by kWorkspaceMargin: within the fit's error the one without is
+    // preferred -- 1024 x 4096 x 4096: 256 flat tiles 52.0 us, 64 large tiles in four K splits 52.8 on weights out of
+    // cache and 58.7 against 52.9 on the same weights over and over)
+    if (splits > 1) us = (us + kReduceUs + kReduceUsPerMB * (double)splits * (double)M * (double)N * 4e-6) * kWorkspaceMargin;
+    return us;
+}
+
+// even scheduling of `tiles` large tiles, of which `rem` are shared out
+double sk_launch_us(int64_t tiles, int64_t rem, int64_t pairs)
+{
+    const double sharers = std::min<double>((double)kComputeUnits / (double)rem + 1.0, (double)pairs);
+    return (double)tiles * (double)pairs / kComputeUnits * kBigCost.hi[2] + kBigCost.b + kSkUs + kSkUsPerSharer * sharers;
+}
+
 constexpr size_t kSkCounterBytes = 1024;                // 255 counters at most, then the slabs (16-byte aligned)
 struct SkPlan {
     bool on;
     int rounds_dp, rem_tiles, pairs;
     size_t workspace_bytes;
+    double us;                                          // estimated duration of the launch when on
 };
 
+// With M = 2048, G = 128: N = 27392, K = 5120 (856 tiles) 547 -> 525 us; N = 5120, K = 13696 (160 tiles) 293 -> 275 us;
+// but N = 5120, K = 5120 (160 tiles) 113 -> 133 us and N = 15360, K = 5120 (480 tiles) 286 -> 316 us.  (Shared tiles
+// taken row by row, see the kernel; column by column the first two were 525 and 284.)
 SkPlan sk_plan(int64_t tiles, int64_t K, int bm, int bn, bool allowed)
 {
-    SkPlan p{false, 0, 0, 0, 0};
+    SkPlan p{false, 0, 0, 0, 0, 0.0};
     const int forced = knob("gemm_sk");
     if (!allowed || forced == 2 || bm != 256 || bn != 256 || tiles <= 0) return p;
     p.rounds_dp = (int)(tiles / kComputeUnits);
     p.rem_tiles = (int)(tiles % kComputeUnits);
     p.pairs = (int)(K / (2 * BK));
     if (p.rem_tiles == 0 || tiles > 0x3fffffffLL || p.pairs > 8192) return p;      // (the kernel's unit arithmetic is 32-bit)
+    p.us = sk_launch_us(tiles, p.rem_tiles, p.pairs);
     if (forced != 1) {
         if (tiles < kSkMinTiles) return p;
-        if ((int64_t)(kComputeUnits - p.rem_tiles) * p.pairs / kComputeUnits < kSkMinSavedPairs) return p;
+        if (p.us >= rounds_us(kBigCost, tiles, (double)p.pairs)) return p;
     }
     p.on = true;
     p.workspace_bytes = kSkCounterBytes + (size_t)(kComputeUnits + p.rem_tiles) * (size_t)bm * bn * sizeof(float);
     return p;
 }
+
+// (`sk_allowed`: the launch may use even scheduling; `whole_tiles`: it has no workspace, so neither that nor a K split)
+PipeTile pipe_tile(int64_t M, int64_t N, int64_t K, bool sk_allowed, bool whole_tiles = false)
+{
+    const int v = knob("gemm_variant");
+    if (v == 4) return kFlatTile;
+    if (v == 3) return kMidTile;
+    if (v == 2) return kBigTile;
+    if (M <= kFlatOnlyMaxM || N <= 0 || K < 2 * BK) return kFlatTile;
+    const double flat_us = tile_launch_us(kFlatTile, kFlatCost, M, N, K, whole_tiles);
+    double big_us = tile_launch_us(kBigTile, kBigCost, M, N, K, whole_tiles);
+    const SkPlan skp = sk_plan(((M + 255) / 256) * ((N + 255) / 256), K, 256, 256, sk_allowed && !whole_tiles);
+    if (skp.on) big_us = std::min(big_us, skp.us);
+    return flat_us <= big_us ? kFlatTile : kBigTile;
+}
+
+PipeTile tile_of(int bm) { return bm == 64 ? kFlatTile : bm == 128 ? kMidTile : kBigTile; }
+
+size_t partial_bytes(int splits, int64_t M, int64_t N) { return (size_t)splits * (size_t)M * (size_t)N * sizeof(float); }
 
 __global__ void zero_u32_kernel(unsigned int* p, int n)
 {
@@ -786,9 +831,7 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     fu.residual = static_cast<const half_t*>(f.residual);
     fu.swiglu = f.swiglu ? 1 : 0;
     fu.n_half = N / 2;
-    PipeTile shape = pipe_tile(M, N, K);
-    shape.bm = BM;                                      // (the caller may have chosen another tile than pipe_tile's)
-    shape.bn = BN;
+    const PipeTile shape = tile_of(BM);
     const int64_t m_tiles = (M + BM - 1) / BM;
     const int64_t tiles = pipe_tiles(shape, M, N, f.swiglu), n_tiles = tiles / m_tiles;
     const SkPlan skp = sk_plan(tiles, K, BM, BN, !FUSED && !E8 && !BF && !whole_tiles);
@@ -852,7 +895,7 @@ bool gemm_pipe_supported(int64_t K) { return K >= 128 && (K % (2 * BK)) == 0; }
 // (`fused`: the call comes from a fused matmul or the 8-bit format, whose kernels keep whole tiles or the fixed K split)
 size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu, bool fused)
 {
-    const PipeTile shape = pipe_tile(M, N, K);
+    const PipeTile shape = pipe_tile(M, N, K, !fused && !swiglu);
     const int64_t tiles = pipe_tiles(shape, M, N, swiglu);
     if (tiles == 0 || !gemm_pipe_supported(K)) return 0;
     const SkPlan skp = sk_plan(tiles, K, shape.bm, shape.bn, !fused && !swiglu);
@@ -867,7 +910,7 @@ template <int G, bool FUSED>
 int launch_pipe_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, void* workspace,
                      size_t workspace_bytes, hipStream_t stream, const Fusion& f)
 {
-    const int bm = pipe_tile(M, N, K).bm;
+    const int bm = pipe_tile(M, N, K, !FUSED).bm;
     if (bm == 64) return launch_pipe<G, 1, 4, FUSED, 64, 256>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
     if (bm == 128)
         return launch_pipe<G, 2, 2, FUSED, 128, 128>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
@@ -884,7 +927,7 @@ int launch_gemm_pipe8(const void* X, int64_t M, const void* packed, int64_t N, i
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     const Fusion f;
-    const int bm = pipe_tile(M, N, K).bm;
+    const int bm = pipe_tile(M, N, K, false).bm;
     if (bm == 64) return launch_pipe<128, 1, 4, false, 64, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
     if (bm == 128)
         return launch_pipe<128, 2, 2, false, 128, 128, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
@@ -898,7 +941,7 @@ int launch_gemm_pipe8_fused(const Fusion& f, const void* X, int64_t M, const voi
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     if (f.swiglu && (N % (2 * kBlockRows) != 0 || gated_half_bytes(N, 2 * K, 128) > kMaxHalfBytes)) return E0M4_ERR_SHAPE;
-    const int bm = pipe_tile(M, N, K).bm;
+    const int bm = pipe_tile(M, N, K, false).bm;
     if (bm == 64) return launch_pipe<128, 1, 4, true, 64, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
     if (bm == 128)
         return launch_pipe<128, 2, 2, true, 128, 128, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
@@ -920,15 +963,13 @@ int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, in
 }
 
 namespace {
-// Whole tiles only (no workspace to split K into): the large tile when it fills half the chip, else the flat one.
-// M = 1024: 4608 x 4096 (72 large tiles) 70 us flat against 90 large, 27392 x 4096 (428) 214 large against 253 flat,
-// 4096 x 13696 (64) 154 flat against 253 large; 2048 x 5120 x 5120 (160) 111 large against 132 flat.
+// Whole tiles only (no workspace to split K into); the tile by the same estimate as for fp16, whose timings those of
+// this member follow.  M = 1024: 4608 x 4096 (72 large tiles) 70 us flat against 90 large, 27392 x 4096 (428) 214
+// large against 253 flat, 4096 x 13696 (64) 154 flat against 253 large; 2048 x 5120 x 5120 (160) 111 large against 132.
 template <int G>
 int launch_pipe_bf16(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
 {
-    const int v = knob("gemm_variant");
-    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-    const int bm = v == 2 ? 256 : v == 3 ? 128 : v == 4 ? 64 : (M > kFlatMaxM && big_tiles >= kComputeUnits / 2) ? 256 : 64;
+    const int bm = pipe_tile(M, N, K, false, true).bm;
     const Fusion f;
     if (bm == 64) return launch_pipe<G, 1, 4, false, 64, 256, false, true>(x, M, c, N, K, y, nullptr, 0, stream, f, true);
     if (bm == 128) return launch_pipe<G, 2, 2, false, 128, 128, false, true>(x, M, c, N, K, y, nullptr, 0, stream, f, true);

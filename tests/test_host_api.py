@@ -51,8 +51,8 @@ def test_size_functions(L):
     assert L.e0m4_workspace_bytes(8, 151936, 4096, 128) == 0
     # 64 tiles of 256 x 256 on 256 compute units: 4 K splits, one fp32 [M, N] slab each
     assert L.e0m4_workspace_bytes(1024, 4096, 13696, 128) == 4 * 1024 * 4096 * 4
-    # the same tiles with K = 4096 would need short K splits: 256 tiles of 64 x 256 instead, one per compute unit, unsplit
-    assert L.e0m4_workspace_bytes(1024, 4096, 4096, 128) == 0
+    # short K and many columns: 1024 tiles of 64 x 256, two whole rounds at two per compute unit, unsplit
+    assert L.e0m4_workspace_bytes(1024, 16384, 2048, 128) == 0
     assert L.e0m4_workspace_bytes(512, 4096, 4096, 128) == 4 * 512 * 4096 * 4      # 128 such tiles: four splits
     # 128 rows: 36 tiles of 128 x 128, 8 K splits
     assert L.e0m4_workspace_bytes(128, 4608, 4096, 128) == 8 * 128 * 4608 * 4
