@@ -511,8 +511,9 @@ def main():
                   ("17..64", 17, 64, {"gemm_64x256": {"gemv_mfma": 1, "gemm_variant": 4},
                                       "gemm_128x128": {"gemv_mfma": 1, "gemm_variant": 3}}),
                   ("65..384", 65, 384, {"gemm_64x256": {"gemm_variant": 4}, "gemm_128x128": {"gemm_variant": 3},
-                                        "gemm_256x256": {"gemm_variant": 2}}),
-                  ("385..4096", 385, 4096, {"gemm_128x128": {"gemm_variant": 3}, "gemm_256x256": {"gemm_variant": 2},
+                                        "gemm_128x256": {"gemm_variant": 5}, "gemm_256x256": {"gemm_variant": 2}}),
+                  ("385..4096", 385, 4096, {"gemm_64x256": {"gemm_variant": 4}, "gemm_128x256": {"gemm_variant": 5},
+                                            "gemm_256x256": {"gemm_variant": 2},
                                             "even_scheduling_always": {"gemm_sk": 1}, "even_scheduling_never": {"gemm_sk": 2}}))
         knob_names = ("gemv_mfma", "gemm_variant", "gemm_sk")
         rows, ratios = [], []

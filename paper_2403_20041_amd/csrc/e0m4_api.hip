@@ -24,7 +24,7 @@ thread_local Knob g_knobs[] = {
     {"gemv_workgroups", 0},            // target number of workgroups of the small-M kernel
     {"gemv_mfma", 0},                  // 1: never use the matrix-core small-batch kernel (2 <= M <= 16); 2: use it, activations always from LDS; 3: use it, wavefront sums reduced per row block
     {"gemv_xreg", 0},                  // M = 1 kernel, a wavefront's activations in registers: 2 never
-    {"gemm_variant", 0},               // 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
+    {"gemm_variant", 0},               // 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256, 5: 128 x 256
     {"gemm_splits", 0},                // force the number of K splits of the pipelined GEMM kernel
     {"gemm_sk", 0},                    // even scheduling of the 256 x 256 tiles over the compute units: 1 whenever the last round is partly filled, 2 never
 };

@@ -1,7 +1,8 @@
 // Software-pipelined tile of the prefill GEMM (paper: section "Operator and lagging optimizations",
 // matrix-matrix product; dequantisation of section "E0M4 FP4 quantization" fused in registers), built
-// for 256 x 256 outputs (M above 384) and for 128 x 128 outputs (M up to 384, four wavefronts 2 x 2 of
-// 64 x 64 each, two or three workgroups per compute unit).  The description is that of the large tile.
+// for 256 x 256 outputs, for 64 x 256 outputs (four wavefronts side by side, two workgroups per compute
+// unit) and for 128 x 128 outputs (four wavefronts 2 x 2); pipe_tile() below chooses.  The description
+// is that of the large tile.
 //
 // Eight wavefronts (2 x 4, two per SIMD) share the tile, 128 x 64 outputs and 128 fp32 accumulator
 // registers per lane each, which leaves two wavefronts per SIMD at most: little but a wavefront's own
@@ -93,9 +94,9 @@ struct SkArgs {
 };
 
 //
-// The tile is BM x BN: 256 x 256 with 2 x 4 wavefronts for large M; 128 x 128 with 2 x 2 wavefronts (two
-// workgroups per compute unit) for M up to a few hundred, where the large tile would compute rows that
-// do not exist and leave most compute units without a tile; 64 x 256 with 1 x 4 wavefronts for M up to 64.
+// The tile is BM x BN: 256 x 256 with 2 x 4 wavefronts; 64 x 256 with 1 x 4 wavefronts, where the large tile would
+// compute many rows that do not exist or leave compute units without a tile; 128 x 128 with 2 x 2 wavefronts (forced
+// launches only).
 //
 // E8 selects the 8-bit format E0M8 (e0m8_pack.hip; G is then 128, the group of its 4-bit slots): a K slice
 // of 64 is one block, a lane reads two 16-byte chunks of 16 weights per slice, and MFMA number s takes
@@ -711,7 +712,7 @@ struct PipeTile {
     int slots;                                          // work items wanted before K is split no further
 };
 constexpr PipeTile kFlatTile{64, 256, 2 * kComputeUnits}, kMidTile{128, 128, kComputeUnits + kComputeUnits / 2},
-    kBigTile{256, 256, kComputeUnits};
+    kBigTile{256, 256, kComputeUnits}, kHalfTile{128, 256, 2 * kComputeUnits};
 constexpr int kFlatOnlyMaxM = 64;
 
 struct TileCost {
@@ -720,10 +721,11 @@ struct TileCost {
     double b;                                           // us per round: prologue and epilogue of a work item
     int cap;                                            // work items per round
 };
-constexpr TileCost kFlatCost{{0.315, 0.862, 1.463}, {1.546, 1.907, 2.058}, 3.96, 2 * kComputeUnits};
-constexpr TileCost kBigCost{{1.874, 2.270, 2.375}, {2.375, 2.812, 3.502}, 6.91, kComputeUnits};
-constexpr double kReduceUs = 6.53, kReduceUsPerMB = 0.146;      // reduction kernel of a K split
-constexpr double kSkUs = 33.8, kSkUsPerSharer = 1.25;           // even scheduling: slabs, and the serial part per sharer
+constexpr TileCost kFlatCost{{0.350, 0.937, 1.481}, {1.557, 1.891, 2.057}, 3.69, 2 * kComputeUnits};
+constexpr TileCost kHalfCost{{0.928, 1.426, 1.820}, {2.527, 3.002, 3.515}, 5.92, 2 * kComputeUnits};
+constexpr TileCost kBigCost{{1.979, 2.347, 2.416}, {2.368, 2.779, 3.536}, 6.76, kComputeUnits};
+constexpr double kReduceUs = 6.00, kReduceUsPerMB = 0.155;      // reduction kernel of a K split
+constexpr double kSkUs = 33.2, kSkUsPerSharer = 1.41;           // even scheduling: slabs, and the serial part per sharer
 constexpr double kWorkspaceMargin = 1.03;
 constexpr int kSkMinTiles = 128;                        // fewer tiles: the fixed K split (the fit holds no such launch)
 
@@ -747,7 +749,7 @@ double tile_launch_us(const PipeTile& t, const TileCost& c, int64_t M, int64_t N
     const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn), pairs = K / (2 * BK);
     const int splits = whole_tiles ? 1 : choose_splits(tiles, K, t.slots);
     double us = rounds_us(c, tiles * splits, (double)pairs / splits);
-    // (a launch that needs the workspace has to win by kWorkspaceMargin: within the fit's error the one without is
+    // (a launch with a K split has to win by kWorkspaceMargin: within the fit's error the one without is
     // preferred -- 1024 x 4096 x 4096: 256 flat tiles 52.0 us, 64 large tiles in four K splits 52.8 on weights out of
     // cache and 58.7 against 52.9 on the same weights over and over)
     if (splits > 1) us = (us + kReduceUs + kReduceUsPerMB * (double)splits * (double)M * (double)N * 4e-6) * kWorkspaceMargin;
@@ -791,6 +793,7 @@ SkPlan sk_plan(int64_t tiles, int64_t K, int bm, int bn, bool allowed)
     return p;
 }
 
+// Up to 64 rows the flat tile; above, the tile with the shortest estimate (the flat one on a tie).
 // (`sk_allowed`: the launch may use even scheduling; `whole_tiles`: it has no workspace, so neither that nor a K split)
 PipeTile pipe_tile(int64_t M, int64_t N, int64_t K, bool sk_allowed, bool whole_tiles = false)
 {
@@ -798,15 +801,18 @@ PipeTile pipe_tile(int64_t M, int64_t N, int64_t K, bool sk_allowed, bool whole_
     if (v == 4) return kFlatTile;
     if (v == 3) return kMidTile;
     if (v == 2) return kBigTile;
+    if (v == 5) return kHalfTile;
     if (M <= kFlatOnlyMaxM || N <= 0 || K < 2 * BK) return kFlatTile;
     const double flat_us = tile_launch_us(kFlatTile, kFlatCost, M, N, K, whole_tiles);
+    const double half_us = tile_launch_us(kHalfTile, kHalfCost, M, N, K, whole_tiles);
     double big_us = tile_launch_us(kBigTile, kBigCost, M, N, K, whole_tiles);
     const SkPlan skp = sk_plan(((M + 255) / 256) * ((N + 255) / 256), K, 256, 256, sk_allowed && !whole_tiles);
     if (skp.on) big_us = std::min(big_us, skp.us);
+    if (half_us < flat_us && half_us <= big_us) return kHalfTile;
     return flat_us <= big_us ? kFlatTile : kBigTile;
 }
 
-PipeTile tile_of(int bm) { return bm == 64 ? kFlatTile : bm == 128 ? kMidTile : kBigTile; }
+PipeTile tile_of(int bm, int bn) { return bm == 64 ? kFlatTile : bm == 256 ? kBigTile : bn == 256 ? kHalfTile : kMidTile; }
 
 size_t partial_bytes(int splits, int64_t M, int64_t N) { return (size_t)splits * (size_t)M * (size_t)N * sizeof(float); }
 
@@ -831,7 +837,7 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     fu.residual = static_cast<const half_t*>(f.residual);
     fu.swiglu = f.swiglu ? 1 : 0;
     fu.n_half = N / 2;
-    const PipeTile shape = tile_of(BM);
+    const PipeTile shape = tile_of(BM, BN);
     const int64_t m_tiles = (M + BM - 1) / BM;
     const int64_t tiles = pipe_tiles(shape, M, N, f.swiglu), n_tiles = tiles / m_tiles;
     const SkPlan skp = sk_plan(tiles, K, BM, BN, !FUSED && !E8 && !BF && !whole_tiles);
@@ -906,15 +912,25 @@ size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu, b
 
 namespace {
 
+// the kernel instance of a tile
+template <int G, bool FUSED, bool E8 = false, bool BF = false>
+int launch_pipe_as(const PipeTile& t, const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y,
+                   void* workspace, size_t workspace_bytes, hipStream_t stream, const Fusion& f, bool whole_tiles = false)
+{
+    if (t.bm == 64)
+        return launch_pipe<G, 1, 4, FUSED, 64, 256, E8, BF>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f, whole_tiles);
+    if (t.bm == 128 && t.bn == 256)
+        return launch_pipe<G, 1, 4, FUSED, 128, 256, E8, BF>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f, whole_tiles);
+    if (t.bm == 128)
+        return launch_pipe<G, 2, 2, FUSED, 128, 128, E8, BF>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f, whole_tiles);
+    return launch_pipe<G, 2, 4, FUSED, 256, 256, E8, BF>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f, whole_tiles);
+}
+
 template <int G, bool FUSED>
 int launch_pipe_tile(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, void* workspace,
                      size_t workspace_bytes, hipStream_t stream, const Fusion& f)
 {
-    const int bm = pipe_tile(M, N, K, !FUSED).bm;
-    if (bm == 64) return launch_pipe<G, 1, 4, FUSED, 64, 256>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
-    if (bm == 128)
-        return launch_pipe<G, 2, 2, FUSED, 128, 128>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
-    return launch_pipe<G, 2, 4, FUSED, 256, 256>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+    return launch_pipe_as<G, FUSED>(pipe_tile(M, N, K, !FUSED), x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
 }
 
 }  // namespace
@@ -926,12 +942,8 @@ int launch_gemm_pipe8(const void* X, int64_t M, const void* packed, int64_t N, i
     const half_t* x = static_cast<const half_t*>(X);
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
-    const Fusion f;
-    const int bm = pipe_tile(M, N, K, false).bm;
-    if (bm == 64) return launch_pipe<128, 1, 4, false, 64, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
-    if (bm == 128)
-        return launch_pipe<128, 2, 2, false, 128, 128, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
-    return launch_pipe<128, 2, 4, false, 256, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+    return launch_pipe_as<128, false, true>(pipe_tile(M, N, K, false), x, M, c, N, K, y, workspace, workspace_bytes, stream,
+                                            Fusion{});
 }
 
 int launch_gemm_pipe8_fused(const Fusion& f, const void* X, int64_t M, const void* packed, int64_t N, int64_t K, void* Y,
@@ -941,11 +953,7 @@ int launch_gemm_pipe8_fused(const Fusion& f, const void* X, int64_t M, const voi
     const uint4* c = static_cast<const uint4*>(packed);
     half_t* y = static_cast<half_t*>(Y);
     if (f.swiglu && (N % (2 * kBlockRows) != 0 || gated_half_bytes(N, 2 * K, 128) > kMaxHalfBytes)) return E0M4_ERR_SHAPE;
-    const int bm = pipe_tile(M, N, K, false).bm;
-    if (bm == 64) return launch_pipe<128, 1, 4, true, 64, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
-    if (bm == 128)
-        return launch_pipe<128, 2, 2, true, 128, 128, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
-    return launch_pipe<128, 2, 4, true, 256, 256, true>(x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
+    return launch_pipe_as<128, true, true>(pipe_tile(M, N, K, false), x, M, c, N, K, y, workspace, workspace_bytes, stream, f);
 }
 
 int launch_gemm_pipe(const void* X, int64_t M, const void* packed, int64_t N, int64_t K, int group, void* Y,
@@ -969,11 +977,8 @@ namespace {
 template <int G>
 int launch_pipe_bf16(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K, half_t* y, hipStream_t stream)
 {
-    const int bm = pipe_tile(M, N, K, false, true).bm;
-    const Fusion f;
-    if (bm == 64) return launch_pipe<G, 1, 4, false, 64, 256, false, true>(x, M, c, N, K, y, nullptr, 0, stream, f, true);
-    if (bm == 128) return launch_pipe<G, 2, 2, false, 128, 128, false, true>(x, M, c, N, K, y, nullptr, 0, stream, f, true);
-    return launch_pipe<G, 2, 4, false, 256, 256, false, true>(x, M, c, N, K, y, nullptr, 0, stream, f, true);
+    return launch_pipe_as<G, false, false, true>(pipe_tile(M, N, K, false, true), x, M, c, N, K, y, nullptr, 0, stream,
+                                                 Fusion{}, true);
 }
 }  // namespace
 

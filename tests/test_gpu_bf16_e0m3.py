@@ -114,11 +114,11 @@ def test_bf16_gemm(e0m4, oracle, M, N, K, G):
     check_bf16_matmul(oracle, Y, Yref, absdot, "bf16 gemm M=%d N=%d K=%d" % (M, N, K))
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5])
 @pytest.mark.parametrize("M,N,K,G", [(300, 600, 1024, 128), (513, 272, 384, 32), (70, 1040, 2048, 64), (256, 256, 128, 64)])
 def test_bf16_gemm_every_kernel_and_tile(e0m4, oracle, variant, M, N, K, G):
     # gemm_variant 1: the 128 x 128-tile kernel with both operands through LDS; 2, 3, 4: the pipelined kernel (weights
-    # dequantised in registers, in whole tiles) with its 256 x 256, 128 x 128 and 64 x 256 tile
+    # dequantised in registers, in whole tiles) with its 256 x 256, 128 x 128 and 64 x 256 tile; 5: its 128 x 256 tile
     codes, What, _ = assert_bf16_quantize_exact(e0m4, oracle, synth_inputs.weights_bf16(N, K, seed=3650 + N + K), G)
     X = synth_inputs.activations_bf16(M, K, seed=3750 + M)
     e0m4.e0m4_set_knob("gemm_variant", variant)

@@ -159,7 +159,7 @@ def test_small_batch_other_kernels_when_the_matrix_core_kernel_is_off(e0m4, orac
         e0m4.e0m4_set_knob("gemv_mfma", 0)
 
 
-@pytest.mark.parametrize("variant", [2, 3, 4])        # pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
+@pytest.mark.parametrize("variant", [2, 3, 4, 5])     # pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256, 5: 128 x 256
 @pytest.mark.parametrize("splits", [0, 2, 3])
 def test_gemm_kernels(e0m4, oracle, variant, splits):
     e0m4.e0m4_set_knob("gemm_variant", variant)

@@ -241,7 +241,7 @@ def test_nothing_selected_equals_the_plain_matmul(e0m4, oracle):
 
 
 # 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5])
 @pytest.mark.parametrize("norm,swiglu,res", COMBOS)
 def test_gemm_kernels(e0m4, oracle, variant, norm, swiglu, res):
     e0m4.e0m4_set_knob("gemm_variant", variant)
@@ -254,7 +254,7 @@ def test_gemm_kernels(e0m4, oracle, variant, norm, swiglu, res):
         e0m4.e0m4_set_knob("gemm_variant", 0)
 
 
-@pytest.mark.parametrize("variant", [2, 3, 4])
+@pytest.mark.parametrize("variant", [2, 3, 4, 5])
 @pytest.mark.parametrize("splits", [2, 3, 8])
 @pytest.mark.parametrize("norm,swiglu,res", COMBOS)
 def test_gemm_split_along_k(e0m4, oracle, variant, splits, norm, swiglu, res):
@@ -319,7 +319,7 @@ def test_8bit_small_batch_matrix_core_kernel_forced_shapes(e0m4, oracle, waves, 
         e0m4.e0m4_set_knob("gemv_mfma", 0)
 
 
-@pytest.mark.parametrize("variant,splits", [(2, 0), (3, 0), (4, 0), (2, 3), (3, 2), (4, 8)])
+@pytest.mark.parametrize("variant,splits", [(2, 0), (3, 0), (4, 0), (5, 0), (2, 3), (3, 2), (4, 8), (5, 4)])
 @pytest.mark.parametrize("norm,swiglu,res", COMBOS)
 def test_8bit_gemm_kernels(e0m4, oracle, variant, splits, norm, swiglu, res):
     e0m4.e0m4_set_knob("gemm_variant", variant)

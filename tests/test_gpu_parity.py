@@ -359,8 +359,8 @@ def test_gemm_small(e0m4, oracle, M, N, K, G):
     run_matmul_case(e0m4, oracle, M, N, K, G, seed=M + N + K, outliers=True, row_std=(0.5, 2.0))
 
 
-# 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+# 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256, 5: 128 x 256
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 5])
 @pytest.mark.parametrize("M,N,K,G", [
     (300, 600, 1024, 128),      # ragged in M and N against every tile size, several tiles each way
     (513, 272, 416, 32),        # ragged K slice (416 = 6.5 x 64), N ends inside a 16-row block run
@@ -375,7 +375,7 @@ def test_gemm_both_kernels(e0m4, oracle, variant, M, N, K, G):
         e0m4.e0m4_set_knob("gemm_variant", 0)
 
 
-@pytest.mark.parametrize("variant", [2, 3, 4])
+@pytest.mark.parametrize("variant", [2, 3, 4, 5])
 @pytest.mark.parametrize("splits", [2, 3, 8])
 @pytest.mark.parametrize("M,N,K,G", [
     (300, 600, 1024, 128),      # 6 tiles, 8 slice pairs: 3 splits get 2, 3 and 3 pairs; 8 splits one each

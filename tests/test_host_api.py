@@ -57,9 +57,9 @@ def test_size_functions(L):
     # 128 rows: 36 tiles of 128 x 128, 8 K splits
     assert L.e0m4_workspace_bytes(128, 4608, 4096, 128) == 8 * 128 * 4608 * 4
     assert L.e0m4_workspace_bytes(2048, 32768, 5120, 128) == 0          # 1024 tiles, four whole rounds of 256: no split
-    # 856 tiles: three whole rounds, the other 88 shared out by K ranges: their counters, then one 256 x 256 fp32 slab for
-    # each compute unit and one more for each shared tile
-    assert L.e0m4_workspace_bytes(2048, 27392, 5120, 128) == 1024 + (256 + 88) * 256 * 256 * 4
+    # 132 large tiles with a long K, shared out by K ranges over the 256 compute units: their counters, then one
+    # 256 x 256 fp32 slab for each compute unit and one more for each shared tile
+    assert L.e0m4_workspace_bytes(1024, 8448, 13696, 128) == 1024 + (256 + 132) * 256 * 256 * 4
     assert L.e0m4_workspace_bytes(1024, 4096, 4160, 64) == 0            # K not a multiple of 128: other kernel
 
 
