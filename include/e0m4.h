@@ -134,10 +134,10 @@ int e0m4_unpack_codes(const void* codes, int64_t N, int64_t K, int group, void* 
  *            units (three on small weights).
  *   M >= 9 otherwise, and 2 <= M <= 8 when M * N * K is about 3.8e8 or
  *            more (the vector kernel's time grows with M): MFMA GEMM path
- *            (tiles of 64 x 256 or 256 x 256 outputs, whichever an estimate
- *            of the launch's duration puts ahead; split along K when tiles
- *            are few, a partly filled last round of many large tiles shared
- *            out evenly when the estimate favours that).
+ *            (tiles of 64 x 256, 128 x 256 or 256 x 256 outputs, whichever
+ *            an estimate of the launch's duration puts ahead; split along
+ *            K when tiles are few, a partly filled last round of many large
+ *            tiles shared out evenly when the estimate favours that).
  *            e0m4_workspace_bytes() tells when a workspace is needed.
  * `scales_f16`/`bias_f16` may be NULL (see `codes` above); `workspace` may be
  * NULL when e0m4_workspace_bytes() is 0, else it is device memory of at least

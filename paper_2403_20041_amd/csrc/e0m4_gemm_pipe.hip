@@ -1,8 +1,8 @@
 // Software-pipelined tile of the prefill GEMM (paper: section "Operator and lagging optimizations",
 // matrix-matrix product; dequantisation of section "E0M4 FP4 quantization" fused in registers), built
-// for 256 x 256 outputs, for 64 x 256 outputs (four wavefronts side by side, two workgroups per compute
-// unit) and for 128 x 128 outputs (four wavefronts 2 x 2); pipe_tile() below chooses.  The description
-// is that of the large tile.
+// for 256 x 256 outputs, for 128 x 256 and 64 x 256 outputs (four wavefronts side by side, two workgroups
+// per compute unit) and for 128 x 128 outputs (four wavefronts 2 x 2); pipe_tile() below chooses.  The
+// description is that of the large tile.
 //
 // Eight wavefronts (2 x 4, two per SIMD) share the tile, 128 x 64 outputs and 128 fp32 accumulator
 // registers per lane each, which leaves two wavefronts per SIMD at most: little but a wavefront's own
@@ -94,9 +94,10 @@ struct SkArgs {
 };
 
 //
-// The tile is BM x BN: 256 x 256 with 2 x 4 wavefronts; 64 x 256 with 1 x 4 wavefronts, where the large tile would
-// compute many rows that do not exist or leave compute units without a tile; 128 x 128 with 2 x 2 wavefronts (forced
-// launches only).
+// The tile is BM x BN: 256 x 256 with 2 x 4 wavefronts; 128 x 256 with 1 x 4 wavefronts (the same 128 x 64 per
+// wavefront, two independent workgroups per compute unit); 64 x 256 with 1 x 4 wavefronts, where the taller tiles
+// would compute many rows that do not exist or leave compute units without a tile; 128 x 128 with 2 x 2 wavefronts
+// (forced launches only).
 //
 // E8 selects the 8-bit format E0M8 (e0m8_pack.hip; G is then 128, the group of its 4-bit slots): a K slice
 // of 64 is one block, a lane reads two 16-byte chunks of 16 weights per slice, and MFMA number s takes
@@ -688,25 +689,29 @@ int choose_splits(int64_t tiles, int64_t K, int slots)
     return (int)std::max<int64_t>(s, 1);
 }
 
-// The tile a problem gets (gemm_variant 2, 3, 4 force the 256 x 256, 128 x 128 and 64 x 256 tile) and whether the
-// large tile runs with even scheduling (SkArgs; gemm_sk 1 forces it whenever the last round is partly filled, 2
-// forbids it) are decided by an estimate of the launch's duration.  Up to 64 rows only the 64 x 256 tile (four
-// wavefronts side by side, every weight dequantised once per workgroup) makes sense; the 128 x 128 tile never won.
+// The tile a problem gets (gemm_variant 2, 3, 4, 5 force the 256 x 256, 128 x 128, 64 x 256 and 128 x 256 tile) and
+// whether the large tile runs with even scheduling (SkArgs; gemm_sk 1 forces it whenever the last round is partly
+// filled, 2 forbids it) are decided by an estimate of the launch's duration.  Up to 64 rows only the 64 x 256 tile
+// (four wavefronts side by side, every weight dequantised once per workgroup) makes sense; the 128 x 128 tile never
+// won.  The 128 x 256 tile has the large tile's wavefront (128 x 64, 3.75 vector instructions per MFMA) in workgroups
+// of four, two to a compute unit, that start and finish independently: it pads fewer rows than the large tile,
+// dequantises half as often as the flat one and leaves a shorter tail (354 x 13056 x 10368: 111 us against 138 and
+// 146; 2048 x 27392 x 4096: 397 against 421 with even scheduling).
 //
 // The estimate counts rounds: the work items (tiles times K splits) run `cap` at a time (one 256 x 256 tile per
-// compute unit, two 64 x 256 tiles), a full round takes  pairs-of-K-slices * a(1) + b  and the last, partly filled
+// compute unit, two of the others), a full round takes  pairs-of-K-slices * a(1) + b  and the last, partly filled
 // one  pairs * a(fill) + b  with a() piecewise linear in the fill -- a compute unit is slower the more of them run
 // (one round of 160 large tiles with K = 5120 takes 112 us, one of 256 tiles 152 us, whether the workgroups read
 // different tiles or all the same one: it is not the memory side), which is why filling idle units buys much less
-// than their number suggests; the flat tile's a() has a step at half fill, where the first compute units get a
-// second workgroup.  A K split adds its reduction kernel (a fixed part and one per MB of partial sums); even
-// scheduling runs every unit for the whole time at the full rate and adds the slabs' cost, of which the part per
-// sharer of a tile is serial (the last arriver reads them all).
-// The constants are a least-squares fit (logarithm of the ratio to the measurement, rms 4.4 %) to 303 problems
+// than their number suggests; a() has a step at half fill, where the first compute units get a second workgroup.
+// A K split adds its reduction kernel (a fixed part and one per MB of partial sums); even scheduling runs every unit
+// for the whole time at the full rate and adds the slabs' cost, of which the part per sharer of a tile is serial
+// (the last arriver reads them all).
+// The constants are a least-squares fit (logarithm of the ratio to the measurement, rms 4.5 %) to 303 problems
 // -- M = 65 .. 8192, N = 1024 .. 256000, K = 1024 .. 16384, groups of 32, 64 and 128, random and layer shapes of 2B to
-// 14B models -- each timed with every tile, with and without even scheduling, on weights out of cache.  Choosing by
-// the estimate costs 0.14 % over always choosing the measured best (geometric mean; 0.1 - 0.2 % with the fit made on
-// two thirds and tested on the rest; worst case 10 %).
+// 14B models -- each timed with the three tiles and with even scheduling, on weights out of cache.  Choosing by the
+// estimate costs 0.33 % over always choosing the measured best (geometric mean; 0.30 - 0.39 % with the fit made on
+// two thirds and tested on the rest; worst case 6 %).
 struct PipeTile {
     int bm, bn;
     int slots;                                          // work items wanted before K is split no further
@@ -793,7 +798,7 @@ SkPlan sk_plan(int64_t tiles, int64_t K, int bm, int bn, bool allowed)
     return p;
 }
 
-// Up to 64 rows the flat tile; above, the tile with the shortest estimate (the flat one on a tie).
+// Up to 64 rows the flat tile; above, the tile with the shortest estimate.
 // (`sk_allowed`: the launch may use even scheduling; `whole_tiles`: it has no workspace, so neither that nor a K split)
 PipeTile pipe_tile(int64_t M, int64_t N, int64_t K, bool sk_allowed, bool whole_tiles = false)
 {
