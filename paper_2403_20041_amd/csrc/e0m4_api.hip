@@ -27,6 +27,7 @@ thread_local Knob g_knobs[] = {
     {"gemm_variant", 0},               // 1: small-tile kernel; pipelined kernel with tiles of 2: 256 x 256, 3: 128 x 128, 4: 64 x 256, 5: 128 x 256
     {"gemm_splits", 0},                // force the number of K splits of the pipelined GEMM kernel
     {"gemm_sk", 0},                    // even scheduling of the 256 x 256 tiles over the compute units: 1 whenever the last round is partly filled, 2 never
+    {"gemm_panel", 0},                 // row tiles per panel of the pipelined GEMM's tile numbering (0: the default, -1: whole columns)
 };
 
 // Scratch of e0m4_matmul_static: the split-K partial sums that e0m4_matmul keeps in the caller's workspace.

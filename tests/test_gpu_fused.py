@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 DEV = "cuda:0"
-KNOBS = ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits", "gemm_sk")
+KNOBS = ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits", "gemm_sk", "gemm_panel")
 
 
 @pytest.fixture(scope="module")
@@ -265,6 +265,19 @@ def test_gemm_split_along_k(e0m4, oracle, variant, splits, norm, swiglu, res):
     finally:
         e0m4.e0m4_set_knob("gemm_variant", 0)
         e0m4.e0m4_set_knob("gemm_splits", 0)
+
+
+# the panelled tile numbering with the gated epilogue (a tile covers half as many output columns) and 11 row tiles of 64
+@pytest.mark.parametrize("variant,panel", [(4, 0), (4, 3), (5, 1), (2, 2), (4, -1)])
+def test_gemm_panelled_tile_numbering_with_epilogues(e0m4, oracle, variant, panel):
+    e0m4.e0m4_set_knob("gemm_variant", variant)
+    e0m4.e0m4_set_knob("gemm_panel", panel)
+    try:
+        run_fused(e0m4, oracle, 700, 640, 256, 128, seed=380 + variant, norm=True, swiglu=True, res=True)
+        run_fused(e0m4, oracle, 700, 608, 256, 64, seed=381 + variant, norm=False, swiglu=False, res=True)
+    finally:
+        e0m4.e0m4_set_knob("gemm_variant", 0)
+        e0m4.e0m4_set_knob("gemm_panel", 0)
 
 
 def test_gemm_small_kernel_ragged_k(e0m4, oracle):

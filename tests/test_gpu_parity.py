@@ -20,7 +20,7 @@ def e0m4():
     import paper_2403_20041_amd as pkg
 
     pkg.lib()                                   # raises if the HIP library is not built
-    for k in ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits", "gemm_sk"):
+    for k in ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits", "gemm_sk", "gemm_panel"):
         pkg.e0m4_set_knob(k, 0)
     return pkg
 
@@ -391,6 +391,33 @@ def test_gemm_split_k(e0m4, oracle, variant, splits, M, N, K, G):
     finally:
         e0m4.e0m4_set_knob("gemm_variant", 0)
         e0m4.e0m4_set_knob("gemm_splits", 0)
+
+
+# Tile numbering in panels of row tiles (gemm_panel: height in tiles, -1 whole columns, 0 the default of 4 tiles, 2 for
+# the 256 x 256 tile).  700 rows are 11, 6 or 3 row tiles of 64, 128 or 256: panels of unequal height at the end, a
+# height of one, a height above the number of row tiles; 600 columns are 3 tiles with a ragged last one.  Every
+# numbering must visit every tile exactly once: Y starts as NaN.
+@pytest.mark.parametrize("panel", [0, 1, 3, 5, 16, -1])
+@pytest.mark.parametrize("variant", [2, 3, 4, 5])
+def test_gemm_panelled_tile_numbering(e0m4, oracle, variant, panel):
+    M, N, K, G = 700, 600, 256, 128
+    W = synth_inputs.weights(N, K, seed=910)
+    X = synth_inputs.activations(M, K, seed=911)
+    (codes, scales, bias), What = assert_quantize_exact(e0m4, oracle, W, G)
+    Yref, absdot = oracle.matmul(X, What)
+    e0m4.e0m4_set_knob("gemm_variant", variant)
+    e0m4.e0m4_set_knob("gemm_panel", panel)
+    try:
+        for splits in (1, 2):
+            e0m4.e0m4_set_knob("gemm_splits", splits)
+            ws = torch.empty(max(16, e0m4.e0m4_workspace_bytes(M, N, K, G)), dtype=torch.uint8, device=DEV)
+            Y = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
+            e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G, out=Y, workspace=ws)
+            torch.cuda.synchronize()
+            check_matmul(Y, Yref, absdot, "variant %d panel %d splits %d" % (variant, panel, splits))
+    finally:
+        for k in ("gemm_variant", "gemm_panel", "gemm_splits"):
+            e0m4.e0m4_set_knob(k, 0)
 
 
 def test_gemm_split_k_default_choice_and_reused_workspace(e0m4, oracle):
