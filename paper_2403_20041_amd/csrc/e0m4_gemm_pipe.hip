@@ -213,6 +213,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
     const int tile = __builtin_amdgcn_readfirstlane(seg_tile);
     const int split = __builtin_amdgcn_readfirstlane(seg_split);
     out_mode = __builtin_amdgcn_readfirstlane(out_mode);
+    // (Not with even scheduling, whose shared-out tiles have a numbering of their own: measured, panels under it gain
+    // or lose 2 %, 4 % lost on 2048 x 5120 x 13696.)
     // Tiles are numbered down the rows of a panel of `panel` row tiles, column after column, panel after panel: the
     // workgroups that run together on an XCD (consecutive numbers) then cover a block of panel x (their number / panel)
     // tiles and share both operands through its L2, instead of one or two whole columns of tiles.
@@ -721,8 +723,8 @@ int choose_splits(int64_t tiles, int64_t K, int slots)
 // The constants are a least-squares fit (logarithm of the ratio to the measurement, rms 4.5 %) to 303 problems
 // -- M = 65 .. 8192, N = 1024 .. 256000, K = 1024 .. 16384, groups of 32, 64 and 128, random and layer shapes of 2B to
 // 14B models -- each timed with the three tiles and with even scheduling, on weights out of cache.  Choosing by the
-// estimate costs 0.33 % over always choosing the measured best (geometric mean; 0.30 - 0.39 % with the fit made on
-// two thirds and tested on the rest; worst case 6 %).
+// estimate costs 0.5 % over always choosing the measured best (geometric mean; 0.4 - 0.5 % with the fit made on
+// two thirds and tested on the rest; worst case 10 %, on a 20 us launch).
 struct PipeTile {
     int bm, bn;
     int slots;                                          // work items wanted before K is split no further
@@ -737,12 +739,11 @@ struct TileCost {
     double b;                                           // us per round: prologue and epilogue of a work item
     int cap;                                            // work items per round
 };
-constexpr TileCost kFlatCost{{0.350, 0.937, 1.481}, {1.557, 1.891, 2.057}, 3.69, 2 * kComputeUnits};
-constexpr TileCost kHalfCost{{0.928, 1.426, 1.820}, {2.527, 3.002, 3.515}, 5.92, 2 * kComputeUnits};
-constexpr TileCost kBigCost{{1.979, 2.347, 2.416}, {2.368, 2.779, 3.536}, 6.76, kComputeUnits};
-constexpr double kReduceUs = 6.00, kReduceUsPerMB = 0.155;      // reduction kernel of a K split
-constexpr double kSkUs = 33.2, kSkUsPerSharer = 1.41;           // even scheduling: slabs, and the serial part per sharer
-constexpr double kWorkspaceMargin = 1.03;
+constexpr TileCost kFlatCost{{0.468, 0.933, 1.446}, {1.631, 2.020, 2.130}, 4.30, 2 * kComputeUnits};
+constexpr TileCost kHalfCost{{1.034, 1.356, 1.935}, {2.663, 3.174, 3.617}, 6.32, 2 * kComputeUnits};
+constexpr TileCost kBigCost{{2.099, 2.463, 2.539}, {2.516, 3.012, 3.659}, 8.43, kComputeUnits};
+constexpr double kReduceUs = 5.82, kReduceUsPerMB = 0.193;      // reduction kernel of a K split
+constexpr double kSkUs = 34.3, kSkUsPerSharer = 1.58;           // even scheduling: slabs, and the serial part per sharer
 constexpr int kSkMinTiles = 128;                        // fewer tiles: the fixed K split (the fit holds no such launch)
 
 double rounds_us(const TileCost& c, int64_t items, double pairs_per_item)
@@ -765,10 +766,7 @@ double tile_launch_us(const PipeTile& t, const TileCost& c, int64_t M, int64_t N
     const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn), pairs = K / (2 * BK);
     const int splits = whole_tiles ? 1 : choose_splits(tiles, K, t.slots);
     double us = rounds_us(c, tiles * splits, (double)pairs / splits);
-    // (a launch with a K split has to win by kWorkspaceMargin: within the fit's error the one without is
-    // preferred -- 1024 x 4096 x 4096: 256 flat tiles 52.0 us, 64 large tiles in four K splits 52.8 on weights out of
-    // cache and 58.7 against 52.9 on the same weights over and over)
-    if (splits > 1) us = (us + kReduceUs + kReduceUsPerMB * (double)splits * (double)M * (double)N * 4e-6) * kWorkspaceMargin;
+    if (splits > 1) us += kReduceUs + kReduceUsPerMB * (double)splits * (double)M * (double)N * 4e-6;
     return us;
 }
 
