@@ -28,6 +28,7 @@ thread_local Knob g_knobs[] = {
     {"gemm_splits", 0},                // force the number of K splits of the pipelined GEMM kernel
     {"gemm_sk", 0},                    // even scheduling of the 256 x 256 tiles over the compute units: 1 whenever the last round is partly filled, 2 never
     {"gemm_panel", 0},                 // row tiles per panel of the pipelined GEMM's tile numbering (0: the default, -1: whole columns)
+    {"gemm_split_order", 0},           // work items of a K-split launch: 1 by tile, 2 by split (0: by the length of a split)
 };
 
 // Scratch of e0m4_matmul_static: the split-K partial sums that e0m4_matmul keeps in the caller's workspace.

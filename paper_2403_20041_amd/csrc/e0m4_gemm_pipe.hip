@@ -68,6 +68,7 @@ struct PipeFusion {
     const half_t* residual;
     int swiglu;
     int panel;                                          // row tiles per panel of the tile numbering (0: one panel)
+    int split_major;                                    // work items ordered by K split first, then by tile
     int64_t n_half;                                     // N / 2 (gated epilogue)
 };
 
@@ -118,7 +119,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
     constexpr int PA = BM / RP;                         // activation loader passes
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-    // Work items are (tile, K split) pairs, the splits of a tile adjacent; each XCD takes a contiguous run.
+    // Work items are (tile, K split) pairs, the splits of a tile adjacent -- or, with split_major, all tiles of one
+    // split before those of the next, so that the workgroups running together on an XCD are on the same K range of
+    // neighbouring tiles and share operands in its L2; each XCD takes a contiguous run.
     // (even scheduling exists in the instance the launcher uses it with; elsewhere the segment loop below folds away)
     static_assert(!BF || (!FUSED && !E8), "the bfloat16 member has the plain 4-bit kernel only");
     constexpr bool kSk = !FUSED && !E8 && !BF && BM == 256 && BN == 256;
@@ -156,8 +159,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, 2) void gemm_pipe_kernel(const half
         return (int)g;
     };
     // the work item of a launch without even scheduling
-    const int plain_tile = __builtin_amdgcn_readfirstlane(item / splits);
-    const int plain_split = __builtin_amdgcn_readfirstlane(item % splits);
+    const int all_tiles = m_tiles * n_tiles;
+    const int plain_tile = __builtin_amdgcn_readfirstlane(fu.split_major ? item % all_tiles : item / splits);
+    const int plain_split = __builtin_amdgcn_readfirstlane(fu.split_major ? item / all_tiles : item % splits);
     const int plain_kb = __builtin_amdgcn_readfirstlane(2 * (int)((int64_t)(KT_all / 2) * plain_split / splits));
     const int plain_ke = __builtin_amdgcn_readfirstlane(2 * (int)((int64_t)(KT_all / 2) * (plain_split + 1) / splits));
   for (int seg = 0; seg < n_segments; ++seg) {
@@ -744,6 +748,7 @@ constexpr TileCost kHalfCost{{1.034, 1.356, 1.935}, {2.663, 3.174, 3.617}, 6.32,
 constexpr TileCost kBigCost{{2.099, 2.463, 2.539}, {2.516, 3.012, 3.659}, 8.43, kComputeUnits};
 constexpr double kReduceUs = 5.82, kReduceUsPerMB = 0.193;      // reduction kernel of a K split
 constexpr double kSkUs = 34.3, kSkUsPerSharer = 1.58;           // even scheduling: slabs, and the serial part per sharer
+constexpr int kSplitMajorMinPairs = 16;
 constexpr int kSkMinTiles = 128;                        // fewer tiles: the fixed K split (the fit holds no such launch)
 
 double rounds_us(const TileCost& c, int64_t items, double pairs_per_item)
@@ -856,6 +861,7 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     // gemm_panel forces a height, -1 whole columns.
     const int panel_knob = knob("gemm_panel");
     fu.panel = panel_knob > 0 ? panel_knob : panel_knob < 0 ? 0 : BM == 256 ? 2 : 4;
+    fu.split_major = 0;
     fu.n_half = N / 2;
     const PipeTile shape = tile_of(BM, BN);
     const int64_t m_tiles = (M + BM - 1) / BM;
@@ -863,6 +869,11 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     const SkPlan skp = sk_plan(tiles, K, BM, BN, !FUSED && !E8 && !BF && !whole_tiles);
     const int splits = skp.on || whole_tiles ? 1 : choose_splits(tiles, K, shape.slots);
     if (tiles * splits > 0x3fffffffLL) return E0M4_ERR_SHAPE;
+    // Long K ranges gain from the order by split (1024 x 4096 x 13696 in four splits 122 -> 116 us, 512 x 2048 x 16384
+    // in eight 46.9 -> 44.6), short ones lose (128 x 4608 x 4096 in eight splits of four pairs 19.6 -> 21.6, 1024 x 4608
+    // x 4096 in three of ten or eleven 56.9 -> 58.5); gemm_split_order 1 forces the order by tile, 2 the order by split.
+    const int order_knob = knob("gemm_split_order");
+    fu.split_major = splits > 1 && (order_knob == 2 || (order_knob == 0 && K / (2 * BK) / splits >= kSplitMajorMinPairs)) ? 1 : 0;
     const int total = (int)(tiles * splits);
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
     float* partial = nullptr;

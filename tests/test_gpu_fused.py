@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 DEV = "cuda:0"
-KNOBS = ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits", "gemm_sk", "gemm_panel")
+KNOBS = ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits", "gemm_sk", "gemm_panel", "gemm_split_order")
 
 
 @pytest.fixture(scope="module")
@@ -260,11 +260,13 @@ def test_gemm_kernels(e0m4, oracle, variant, norm, swiglu, res):
 def test_gemm_split_along_k(e0m4, oracle, variant, splits, norm, swiglu, res):
     e0m4.e0m4_set_knob("gemm_variant", variant)
     e0m4.e0m4_set_knob("gemm_splits", splits)
+    e0m4.e0m4_set_knob("gemm_split_order", 1 + splits % 2)      # work items by tile first, or by split first
     try:
         run_fused(e0m4, oracle, 257, 704, 1024, 128, seed=370 + splits, norm=norm, swiglu=swiglu, res=res)
     finally:
         e0m4.e0m4_set_knob("gemm_variant", 0)
         e0m4.e0m4_set_knob("gemm_splits", 0)
+        e0m4.e0m4_set_knob("gemm_split_order", 0)
 
 
 # the panelled tile numbering with the gated epilogue (a tile covers half as many output columns) and 11 row tiles of 64

@@ -20,7 +20,7 @@ def e0m4():
     import paper_2403_20041_amd as pkg
 
     pkg.lib()                                   # raises if the HIP library is not built
-    for k in ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits", "gemm_sk", "gemm_panel"):
+    for k in ("gemv_waves", "gemv_workgroups", "gemv_mfma", "gemv_xreg", "gemm_variant", "gemm_splits", "gemm_sk", "gemm_panel", "gemm_split_order"):
         pkg.e0m4_set_knob(k, 0)
     return pkg
 
@@ -408,15 +408,17 @@ def test_gemm_panelled_tile_numbering(e0m4, oracle, variant, panel):
     e0m4.e0m4_set_knob("gemm_variant", variant)
     e0m4.e0m4_set_knob("gemm_panel", panel)
     try:
-        for splits in (1, 2):
+        # (gemm_split_order: the work items of a K split by tile first, 1, or by split first, 2)
+        for splits, order in ((1, 0), (2, 1), (2, 2)):
             e0m4.e0m4_set_knob("gemm_splits", splits)
+            e0m4.e0m4_set_knob("gemm_split_order", order)
             ws = torch.empty(max(16, e0m4.e0m4_workspace_bytes(M, N, K, G)), dtype=torch.uint8, device=DEV)
             Y = torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)
             e0m4.e0m4_matmul(to_dev(X), codes, scales, bias, N, K, G, out=Y, workspace=ws)
             torch.cuda.synchronize()
-            check_matmul(Y, Yref, absdot, "variant %d panel %d splits %d" % (variant, panel, splits))
+            check_matmul(Y, Yref, absdot, "variant %d panel %d splits %d order %d" % (variant, panel, splits, order))
     finally:
-        for k in ("gemm_variant", "gemm_panel", "gemm_splits"):
+        for k in ("gemm_variant", "gemm_panel", "gemm_splits", "gemm_split_order"):
             e0m4.e0m4_set_knob(k, 0)
 
 
