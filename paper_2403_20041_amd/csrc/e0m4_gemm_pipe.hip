@@ -855,7 +855,7 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     PipeFusion fu;
     fu.residual = static_cast<const half_t*>(f.residual);
     fu.swiglu = f.swiglu ? 1 : 0;
-    // Panels of about 512 rows: 2 to 7 % faster than whole columns of tiles from M = 2048 on (2048 x 27392 x 5120 on
+    // Panels of four row tiles (two of the large tile): 2 to 7 % faster than whole columns of tiles from M = 2048 on (2048 x 27392 x 5120 on
     // 128 x 256 tiles: 504 -> 488 us, 2048 x 32768 x 2048: 269 -> 251; on 64 x 256 tiles 601 -> 569 and 318 -> 285; on
     // the large tile 550 -> 541 and 270 -> 254); heights of 2 to 6 tiles of 128 rows measured alike.
     // gemm_panel forces a height, -1 whole columns.
