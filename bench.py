@@ -449,6 +449,20 @@ def main():
                                                   "per_shape": pre, "layer": layer}
         big = max(pre.values(), key=lambda r: r["achieved"] * r["avg_launch_us"])
         out["roofline_prefill"] = big
+        # context, not a result: the same launch (gate+up, same kernel, grid and instruction stream) on all-zero
+        # activations and all-zero codes.  The chip holds a higher clock when the operands toggle no bits, so the
+        # gap between this figure and the one above is the clock under load, not the kernel's structure.
+        Ng, Kg = [(N, K) for name, N, K in shapes if name == "ffn_gate_up"][0]
+        zc = torch.zeros(e0m4.e0m4_codes_bytes(Ng, Kg, GROUP), dtype=torch.uint8, device=dev)
+        zx = torch.zeros((1024, Kg), dtype=torch.float16, device=dev)
+        zy = torch.empty((1024, Ng), dtype=torch.float16, device=dev)
+        zws = torch.empty(max(e0m4.e0m4_workspace_bytes(1024, Ng, Kg, GROUP), 16), dtype=torch.uint8, device=dev)
+        zus = time_us(lambda: e0m4.e0m4_matmul(zx, zc, None, None, Ng, Kg, GROUP, out=zy, workspace=zws, stream=stream),
+                      20, rounds=2, warm=3)
+        out["roofline_prefill"]["same_launch_on_zero_operands"] = {
+            "us": round(zus, 2), "TFLOPs": round(2.0 * 1024 * Ng * Kg / zus / 1e6, 1),
+            "frac": round(2.0 * 1024 * Ng * Kg / zus / 1e6 / MFMA_F16_PEAK_TFLOPS, 4)}
+        del zc, zx, zy, zws
         out["prefill"] = {"workload": "ChatGLM2-6B-shaped prefill layer, M=1024, 4 GEMMs", "value": layer["achieved"],
                           "unit": "TFLOP/s", "pct_of_mfma_peak": round(100 * layer["frac"], 2),
                           "ms_per_layer": round(layer["avg_launch_us"] / 1e3, 4)}
