@@ -687,24 +687,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     *reinterpret_cast<hvec*>(Y + i) = __builtin_convertvector(sum, hvec);
 }
 
-// Number of K splits for a problem: 1 when the tiles alone give every compute unit work, else as
-// many as fit the chip, each split keeping at least kMinPairsPerSplit pairs of K slices.
+// K splits: none when the tiles alone give every compute unit work, else the number the estimate below puts ahead,
+// up to kMaxSplits, each split keeping at least kMinPairsPerSplit pairs of K slices.
 constexpr int kComputeUnits = 256;
 constexpr int kMinPairsPerSplit = 4;
 constexpr int kMaxSplits = 8;
-
-int choose_splits(int64_t tiles, int64_t K, int slots)
-{
-    const int forced = knob("gemm_splits");
-    const int64_t pairs = K / (2 * BK);
-    // every compute unit already has a tile: the partial sums and their reduction cost more than a second
-    // workgroup per unit gains (1024 x 4096 x 4096 on 256 tiles of 64 x 256: 44 us unsplit, 51 us in two splits)
-    if (forced <= 0 && tiles >= kComputeUnits) return 1;
-    int64_t s = forced > 0 ? std::min<int64_t>(forced, pairs)                   // tests: down to one pair per split
-                           : std::min<int64_t>(slots / tiles, pairs / kMinPairsPerSplit);
-    s = std::min<int64_t>(s, kMaxSplits);
-    return (int)std::max<int64_t>(s, 1);
-}
 
 // The tile a problem gets (gemm_variant 2, 3, 4, 5 force the 256 x 256, 128 x 128, 64 x 256 and 128 x 256 tile) and
 // whether the large tile runs with even scheduling (SkArgs; gemm_sk 1 forces it whenever the last round is partly
@@ -731,23 +718,23 @@ int choose_splits(int64_t tiles, int64_t K, int slots)
 // two thirds and tested on the rest; worst case 10 %, on a 20 us launch).
 struct PipeTile {
     int bm, bn;
-    int slots;                                          // work items wanted before K is split no further
+    int slots;                                          // (128 x 128 tile) work items wanted before K is split no further
 };
 constexpr PipeTile kFlatTile{64, 256, 2 * kComputeUnits}, kMidTile{128, 128, kComputeUnits + kComputeUnits / 2},
     kBigTile{256, 256, kComputeUnits}, kHalfTile{128, 256, 2 * kComputeUnits};
 constexpr int kFlatOnlyMaxM = 64;
 
 struct TileCost {
-    double lo[3];                                       // us per pair of K slices at fill 0, 1/4, 1/2 of a round ...
+    double lo[4];                                       // us per pair of K slices at fill 0, 1/8, 1/4, 1/2 of a round ...
     double hi[3];                                       // ... and just above 1/2, at 3/4 and 1
     double b;                                           // us per round: prologue and epilogue of a work item
     int cap;                                            // work items per round
 };
-constexpr TileCost kFlatCost{{0.468, 0.933, 1.446}, {1.631, 2.020, 2.130}, 4.30, 2 * kComputeUnits};
-constexpr TileCost kHalfCost{{1.034, 1.356, 1.935}, {2.663, 3.174, 3.617}, 6.32, 2 * kComputeUnits};
-constexpr TileCost kBigCost{{2.099, 2.463, 2.539}, {2.516, 3.012, 3.659}, 8.43, kComputeUnits};
-constexpr double kReduceUs = 5.82, kReduceUsPerMB = 0.193;      // reduction kernel of a K split
-constexpr double kSkUs = 34.3, kSkUsPerSharer = 1.58;           // even scheduling: slabs, and the serial part per sharer
+constexpr TileCost kFlatCost{{0.860, 1.198, 1.294, 1.468}, {1.653, 2.084, 2.090}, 3.03, 2 * kComputeUnits};
+constexpr TileCost kHalfCost{{1.478, 1.515, 1.509, 1.903}, {2.661, 3.218, 3.649}, 4.90, 2 * kComputeUnits};
+constexpr TileCost kBigCost{{2.060, 2.342, 2.428, 2.491}, {2.520, 3.010, 3.671}, 7.73, kComputeUnits};
+constexpr double kReduceUs = 6.07, kReduceUsPerMB = 0.188;      // reduction kernel of a K split
+constexpr double kSkUs = 34.7, kSkUsPerSharer = 1.57;           // even scheduling: slabs, and the serial part per sharer
 constexpr int kSplitMajorMinPairs = 16;
 constexpr int kSkMinTiles = 128;                        // fewer tiles: the fixed K split (the fit holds no such launch)
 
@@ -757,22 +744,63 @@ double rounds_us(const TileCost& c, int64_t items, double pairs_per_item)
     double t = (double)full * (pairs_per_item * c.hi[2] + c.b);
     if (rem > 0) {
         const double fill = (double)rem / (double)c.cap;
-        const double* a = fill <= 0.5 ? c.lo : c.hi;
-        const double f = 4.0 * (fill <= 0.5 ? fill : fill - 0.5);
-        const int i = std::min(1, (int)f);
-        t += pairs_per_item * (a[i] + (a[i + 1] - a[i]) * (f - i)) + c.b;
+        double a;
+        if (fill <= 0.125) a = c.lo[0] + (c.lo[1] - c.lo[0]) * fill * 8.0;
+        else if (fill <= 0.25) a = c.lo[1] + (c.lo[2] - c.lo[1]) * (fill - 0.125) * 8.0;
+        else if (fill <= 0.5) a = c.lo[2] + (c.lo[3] - c.lo[2]) * (fill - 0.25) * 4.0;
+        else if (fill <= 0.75) a = c.hi[0] + (c.hi[1] - c.hi[0]) * (fill - 0.5) * 4.0;
+        else a = c.hi[1] + (c.hi[2] - c.hi[1]) * (fill - 0.75) * 4.0;
+        t += pairs_per_item * a + c.b;
     }
     return t;
 }
 
-// whole tiles, or the fixed K split with its reduction kernel
-double tile_launch_us(const PipeTile& t, const TileCost& c, int64_t M, int64_t N, int64_t K, bool whole_tiles)
+// `tiles` whole tiles (splits = 1), or each in `splits` K ranges followed by the reduction kernel
+double split_launch_us(const TileCost& c, int64_t tiles, int splits, int64_t M, int64_t N, int64_t K)
 {
-    const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn), pairs = K / (2 * BK);
-    const int splits = whole_tiles ? 1 : choose_splits(tiles, K, t.slots);
-    double us = rounds_us(c, tiles * splits, (double)pairs / splits);
+    double us = rounds_us(c, tiles * splits, (double)(K / (2 * BK)) / splits);
     if (splits > 1) us += kReduceUs + kReduceUsPerMB * (double)splits * (double)M * (double)N * 4e-6;
     return us;
+}
+
+const TileCost* cost_of(const PipeTile& t)
+{
+    return t.bm == 64 ? &kFlatCost : t.bm == 256 ? &kBigCost : t.bn == 256 ? &kHalfCost : nullptr;
+}
+
+// The number of K splits of a launch with the tile `t` (gemm_splits forces one).  Which number pays depends on the
+// tile count as much as on K: 1024 x 4096 x 4096 on 128 tiles of 128 x 256 takes 56 us unsplit, 44.6 in two splits
+// (one work item per compute unit) and 53 in four; 256 x 4096 x 13696 on 32 such tiles 177, 95, 55 and 41 us in one,
+// two, four and eight.
+int choose_splits(const PipeTile& t, int64_t tiles, int64_t M, int64_t N, int64_t K)
+{
+    const int forced = knob("gemm_splits");
+    const int64_t pairs = K / (2 * BK);
+    if (forced > 0) return (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(forced, pairs), kMaxSplits));   // tests: down to one pair per split
+    // every compute unit already has a tile: the partial sums and their reduction cost more than a second
+    // workgroup per unit gains
+    if (tiles >= kComputeUnits || tiles <= 0) return 1;
+    const int max_splits = (int)std::max<int64_t>(1, std::min<int64_t>(pairs / kMinPairsPerSplit, kMaxSplits));
+    const TileCost* c = cost_of(t);
+    if (c == nullptr)                                   // (the 128 x 128 tile, forced launches only: as many as fill its slots)
+        return (int)std::max<int64_t>(1, std::min<int64_t>(t.slots / tiles, max_splits));
+    int best = 1;
+    double best_us = split_launch_us(*c, tiles, 1, M, N, K);
+    for (int sp = 2; sp <= max_splits; ++sp) {
+        const double us = split_launch_us(*c, tiles, sp, M, N, K);
+        if (us < best_us) {
+            best_us = us;
+            best = sp;
+        }
+    }
+    return best;
+}
+
+// whole tiles, or the K split that the estimate puts ahead, with its reduction kernel
+double tile_launch_us(const PipeTile& t, const TileCost& c, int64_t M, int64_t N, int64_t K, bool whole_tiles)
+{
+    const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+    return split_launch_us(c, tiles, whole_tiles ? 1 : choose_splits(t, tiles, M, N, K), M, N, K);
 }
 
 // even scheduling of `tiles` large tiles, of which `rem` are shared out
@@ -867,7 +895,7 @@ int launch_pipe(const half_t* x, int64_t M, const uint4* c, int64_t N, int64_t K
     const int64_t m_tiles = (M + BM - 1) / BM;
     const int64_t tiles = pipe_tiles(shape, M, N, f.swiglu), n_tiles = tiles / m_tiles;
     const SkPlan skp = sk_plan(tiles, K, BM, BN, !FUSED && !E8 && !BF && !whole_tiles);
-    const int splits = skp.on || whole_tiles ? 1 : choose_splits(tiles, K, shape.slots);
+    const int splits = skp.on || whole_tiles ? 1 : choose_splits(shape, tiles, M, N, K);
     if (tiles * splits > 0x3fffffffLL) return E0M4_ERR_SHAPE;
     // Long K ranges gain from the order by split (1024 x 4096 x 13696 in four splits 122 -> 116 us, 512 x 2048 x 16384
     // in eight 46.9 -> 44.6), short ones lose (128 x 4608 x 4096 in eight splits of four pairs 19.6 -> 21.6, 1024 x 4608
@@ -937,7 +965,7 @@ size_t gemm_pipe_workspace_bytes(int64_t M, int64_t N, int64_t K, bool swiglu, b
     if (tiles == 0 || !gemm_pipe_supported(K)) return 0;
     const SkPlan skp = sk_plan(tiles, K, shape.bm, shape.bn, !fused && !swiglu);
     if (skp.on) return skp.workspace_bytes;
-    const int splits = choose_splits(tiles, K, shape.slots);
+    const int splits = choose_splits(shape, tiles, M, N, K);
     return splits > 1 ? partial_bytes(splits, M, N) : 0;
 }
 

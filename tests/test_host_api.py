@@ -49,13 +49,12 @@ def test_size_functions(L):
     assert L.e0m4_params_elems(100, 256, 48) == 0
     assert L.e0m4_workspace_bytes(1, 4096, 4096, 128) == 0  # small M: partial sums never leave the chip
     assert L.e0m4_workspace_bytes(8, 151936, 4096, 128) == 0
-    # 64 tiles of 256 x 256 on 256 compute units: 4 K splits, one fp32 [M, N] slab each
-    assert L.e0m4_workspace_bytes(1024, 4096, 13696, 128) == 4 * 1024 * 4096 * 4
-    # short K and many columns: 1024 tiles of 64 x 256, two whole rounds at two per compute unit, unsplit
+    # few tiles and a long K: a K split (the number by the library's estimate of the launch), one fp32 [M, N] slab each
+    for M, N, K in ((1024, 4096, 13696), (512, 4096, 4096), (128, 4608, 4096), (256, 4096, 13696)):
+        need = L.e0m4_workspace_bytes(M, N, K, 128)
+        assert need % (M * N * 4) == 0 and 2 <= need // (M * N * 4) <= 8, (M, N, K, need)
+    # short K and many columns: enough whole tiles for every compute unit, unsplit
     assert L.e0m4_workspace_bytes(1024, 16384, 2048, 128) == 0
-    assert L.e0m4_workspace_bytes(512, 4096, 4096, 128) == 4 * 512 * 4096 * 4      # 128 such tiles: four splits
-    # 128 rows: 36 tiles of 128 x 128, 8 K splits
-    assert L.e0m4_workspace_bytes(128, 4608, 4096, 128) == 8 * 128 * 4608 * 4
     assert L.e0m4_workspace_bytes(2048, 32768, 5120, 128) == 0          # 1024 tiles, four whole rounds of 256: no split
     # 132 large tiles with a long K, shared out by K ranges over the 256 compute units: their counters, then one
     # 256 x 256 fp32 slab for each compute unit and one more for each shared tile
@@ -95,18 +94,18 @@ def test_knobs_belong_to_the_calling_thread(L):
 
     shape = (1024, 4096, 13696, 128)
     base = L.e0m4_workspace_bytes(*shape)
-    assert base == 4 * 1024 * 4096 * 4
+    assert base > 0 and base % (1024 * 4096 * 4) == 0
     seen = {}
 
     def other():
-        assert L.e0m4_set_knob(b"gemm_splits", 2) == 0
+        assert L.e0m4_set_knob(b"gemm_splits", 3) == 0
         seen["other"] = L.e0m4_workspace_bytes(*shape)
         # left set on purpose: it must die with the thread
 
     th = threading.Thread(target=other)
     th.start()
     th.join()
-    assert seen["other"] == 2 * 1024 * 4096 * 4
+    assert seen["other"] == 3 * 1024 * 4096 * 4 != base
     assert L.e0m4_workspace_bytes(*shape) == base
 
 

@@ -16,7 +16,7 @@ G = 128
 # (M, N, K): split-K GEMM with the large tile, the same with a smaller input, the flat tile, a decode call
 # (no scratch at all), a GEMM with enough tiles to need none, and one whose 132 tiles are shared out evenly over the
 # compute units (counters and one fp32 slab per compute unit and per tile: 97 MiB of the array)
-CALLS = [(1024, 1280, 4096), (640, 1040, 2048), (300, 520, 1024), (1, 1040, 2048), (512, 8192, 256), (1024, 8448, 13696)]
+CALLS = [(1024, 1280, 4096), (640, 1040, 2048), (300, 520, 2048), (1, 1040, 2048), (512, 8192, 256), (1024, 8448, 13696)]
 
 
 def test_static_scratch_matmul_matches_the_workspace_form(e0m4, oracle):
