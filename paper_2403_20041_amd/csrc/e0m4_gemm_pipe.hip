@@ -708,14 +708,16 @@ constexpr int kMaxSplits = 8;
 // (one round of 160 large tiles with K = 5120 takes 112 us, one of 256 tiles 152 us, whether the workgroups read
 // different tiles or all the same one: it is not the memory side), which is why filling idle units buys much less
 // than their number suggests; a() has a step at half fill, where the first compute units get a second workgroup.
-// A K split adds its reduction kernel (a fixed part and one per MB of partial sums); even scheduling runs every unit
-// for the whole time at the full rate and adds the slabs' cost, of which the part per sharer of a tile is serial
-// (the last arriver reads them all).
-// The constants are a least-squares fit (logarithm of the ratio to the measurement, rms 4.5 %) to 303 problems
-// -- M = 65 .. 8192, N = 1024 .. 256000, K = 1024 .. 16384, groups of 32, 64 and 128, random and layer shapes of 2B to
-// 14B models -- each timed with the three tiles and with even scheduling, on weights out of cache.  Choosing by the
-// estimate costs 0.5 % over always choosing the measured best (geometric mean; 0.4 - 0.5 % with the fit made on
-// two thirds and tested on the rest; worst case 10 %, on a 20 us launch).
+// A K split adds its reduction kernel (a fixed part and one per MB of partial sums), and the number of splits is the
+// one with the shortest estimate; even scheduling runs its whole rounds like whole tiles and the shared-out rest on
+// every unit at the full rate, and adds the slabs' cost, of which the part per sharer of a tile is serial (the last
+// arriver reads them all).
+// The constants are a least-squares fit (logarithm of the ratio to the measurement, rms 5.8 %) to 1301 timings of 321
+// problems -- M = 65 .. 8192, N = 1024 .. 256000, K = 1024 .. 16384, groups of 32, 64 and 128, random and layer shapes
+// of 2B to 14B models -- each timed with the three tiles and with even scheduling, 18 of them also with one to eight K
+// splits per tile, on weights out of cache.  Choosing by the estimate costs 0.8 % over always choosing the measured
+// best (geometric mean; 0.6 - 0.9 % with the fit made on two thirds and tested on the rest; 3.6 % on the 18 problems
+// with their 15 candidates each; the timings themselves repeat within about 3 %).
 struct PipeTile {
     int bm, bn;
     int slots;                                          // (128 x 128 tile) work items wanted before K is split no further
@@ -730,11 +732,11 @@ struct TileCost {
     double b;                                           // us per round: prologue and epilogue of a work item
     int cap;                                            // work items per round
 };
-constexpr TileCost kFlatCost{{0.860, 1.198, 1.294, 1.468}, {1.653, 2.084, 2.090}, 3.03, 2 * kComputeUnits};
-constexpr TileCost kHalfCost{{1.478, 1.515, 1.509, 1.903}, {2.661, 3.218, 3.649}, 4.90, 2 * kComputeUnits};
-constexpr TileCost kBigCost{{2.060, 2.342, 2.428, 2.491}, {2.520, 3.010, 3.671}, 7.73, kComputeUnits};
-constexpr double kReduceUs = 6.07, kReduceUsPerMB = 0.188;      // reduction kernel of a K split
-constexpr double kSkUs = 34.7, kSkUsPerSharer = 1.57;           // even scheduling: slabs, and the serial part per sharer
+constexpr TileCost kFlatCost{{0.809, 1.173, 1.302, 1.456}, {1.601, 2.034, 1.971}, 4.39, 2 * kComputeUnits};
+constexpr TileCost kHalfCost{{1.427, 1.531, 1.573, 1.894}, {2.592, 3.118, 3.411}, 5.92, 2 * kComputeUnits};
+constexpr TileCost kBigCost{{2.052, 2.302, 2.454, 2.523}, {2.445, 2.908, 3.461}, 9.34, kComputeUnits};
+constexpr double kReduceUs = 4.87, kReduceUsPerMB = 0.176;      // reduction kernel of a K split
+constexpr double kSkUs = 34.7, kSkUsPerSharer = 0.68;           // even scheduling: slabs, and the serial part per sharer
 constexpr int kSplitMajorMinPairs = 16;
 constexpr int kSkMinTiles = 128;                        // fewer tiles: the fixed K split (the fit holds no such launch)
 
@@ -807,7 +809,9 @@ double tile_launch_us(const PipeTile& t, const TileCost& c, int64_t M, int64_t N
 double sk_launch_us(int64_t tiles, int64_t rem, int64_t pairs)
 {
     const double sharers = std::min<double>((double)kComputeUnits / (double)rem + 1.0, (double)pairs);
-    return (double)tiles * (double)pairs / kComputeUnits * kBigCost.hi[2] + kBigCost.b + kSkUs + kSkUsPerSharer * sharers;
+    const double whole_rounds = (double)(tiles / kComputeUnits) * ((double)pairs * kBigCost.hi[2] + kBigCost.b);
+    return whole_rounds + (double)rem * (double)pairs / kComputeUnits * kBigCost.hi[2] + kBigCost.b + kSkUs +
+           kSkUsPerSharer * sharers;
 }
 
 constexpr size_t kSkCounterBytes = 1024;                // 255 counters at most, then the slabs (16-byte aligned)
