@@ -717,7 +717,8 @@ constexpr int kMaxSplits = 8;
 // of 2B to 14B models -- each timed with the three tiles and with even scheduling, 18 of them also with one to eight K
 // splits per tile, on weights out of cache.  Choosing by the estimate costs 0.8 % over always choosing the measured
 // best (geometric mean; 0.6 - 0.9 % with the fit made on two thirds and tested on the rest; 3.6 % on the 18 problems
-// with their 15 candidates each; the timings themselves repeat within about 3 %).
+// with their 15 candidates each; the timings themselves repeat within about 3 %).  tune_gemm_estimate.py of the Python
+// package times and fits in this way.
 struct PipeTile {
     int bm, bn;
     int slots;                                          // (128 x 128 tile) work items wanted before K is split no further
